@@ -1,0 +1,220 @@
+"""Seeded synthetic inputs shaped like the paper's workloads, and their work counts.
+
+This module holds NO arithmetic of the method: only shapes, random tensors and MAC
+counting.  It imports neither the GPU binding nor the CPU oracle, so both can be fed
+the same bytes.  The tensors stand in for MNIST (1x28x28, Section IV), CIFAR-10
+(3x32x32, Section V) and ImageNet resized to 256x256 (Section VI): only the shapes
+and rough value ranges of those data sets are used.
+
+Every tensor comes from numpy's PCG64 seeded with [18040451, config, tensor_id].
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field, replace
+from typing import Dict, List, Optional, Tuple
+
+import numpy as np
+
+SEED = 18040451
+
+
+def rng(cfg: int, tensor_id: int) -> np.random.Generator:
+    return np.random.default_rng([SEED, cfg, tensor_id])
+
+
+@dataclass(frozen=True)
+class ConvSpec:
+    """One stride-1 convolution layer on an NCHW minibatch (Section II-A: N images, K kernels)."""
+    N: int
+    C: int
+    H: int
+    W: int
+    K: int
+    R: int
+    S: int
+    pad: int = 0
+    act: str = "identity"  # identity | sigmoid | relu
+    pool: int = 1          # 1 = none, 2 = 2x2 stride-2 max pool
+
+    @property
+    def Ho(self) -> int:
+        return self.H + 2 * self.pad - self.R + 1
+
+    @property
+    def Wo(self) -> int:
+        return self.W + 2 * self.pad - self.S + 1
+
+    @property
+    def x_shape(self):
+        return (self.N, self.C, self.H, self.W)
+
+    @property
+    def w_shape(self):
+        return (self.K, self.C, self.R, self.S)
+
+    @property
+    def y_shape(self):
+        return (self.N, self.K, self.Ho // self.pool, self.Wo // self.pool)
+
+    def macs_nominal(self) -> int:
+        return self.N * self.K * self.C * self.R * self.S * self.Ho * self.Wo
+
+    def macs_exact(self) -> int:
+        """Multiply-adds of one pass, not counting products with padding zeros."""
+        def taps(L, Lo, F):
+            # sum over output positions and filter taps of [input index in range]
+            return sum(1 for i in range(Lo) for r in range(F) if 0 <= i + r - self.pad < L)
+        return self.N * self.K * self.C * taps(self.H, self.Ho, self.R) * taps(self.W, self.Wo, self.S)
+
+
+@dataclass(frozen=True)
+class DenseSpec:
+    in_: int
+    out: int
+    act: str = "identity"
+
+
+@dataclass
+class ConvWorkload:
+    cfg: int
+    name: str
+    conv: ConvSpec
+    x: np.ndarray
+    w: np.ndarray
+    bias: np.ndarray
+    dy: np.ndarray
+
+    def flop(self) -> int:
+        return 2 * 3 * self.conv.macs_exact()
+
+
+@dataclass
+class CrbmWorkload:
+    cfg: int
+    name: str
+    conv: ConvSpec
+    v0: np.ndarray
+    W: np.ndarray
+    b: np.ndarray
+    c: np.ndarray
+    u: np.ndarray
+    lr: float
+
+    def flop(self) -> int:
+        return 2 * 5 * self.conv.macs_exact()
+
+
+@dataclass
+class CnnWorkload:
+    cfg: int
+    name: str
+    conv: List[ConvSpec]
+    dense: List[DenseSpec]
+    classes: int
+    lr: float
+    x: np.ndarray
+    labels: np.ndarray
+    params: List[np.ndarray] = field(default_factory=list)  # conv w0,b0,...; dense W0,b0,...
+
+    @property
+    def batch(self) -> int:
+        return self.conv[0].N
+
+    def conv_flop(self) -> int:
+        """fwd + wgrad for every conv layer, + full bwd for all but the first (no consumer)."""
+        return 2 * sum(c.macs_exact() * (2 if i == 0 else 3) for i, c in enumerate(self.conv))
+
+    def dense_flop(self) -> int:
+        return 2 * 3 * sum(self.batch * d.in_ * d.out for d in self.dense)
+
+    def flop(self) -> int:
+        return self.conv_flop() + self.dense_flop()
+
+    def clone_params(self) -> List[np.ndarray]:
+        return [p.copy() for p in self.params]
+
+
+def _f32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def config1(batch: int = 8) -> ConvWorkload:
+    """Single conv layer fwd+bwd: 1x28x28 U[0,1), 8 filters 5x5 N(0, 0.01), sigmoid, no pool."""
+    cs = ConvSpec(batch, 1, 28, 28, 8, 5, 5, 0, "sigmoid", 1)
+    return ConvWorkload(
+        1, "c1_single_conv", cs,
+        x=_f32(rng(1, 0).random(cs.x_shape)),
+        w=_f32(rng(1, 1).normal(0.0, 0.01, cs.w_shape)),
+        bias=_f32(rng(1, 2).normal(0.0, 0.01, (cs.K,))),
+        dy=_f32(rng(1, 3).normal(0.0, 1.0, cs.y_shape)))
+
+
+def config3(batch: int = 64) -> CrbmWorkload:
+    """Conv RBM CD-1 step: binary visibles Bernoulli(0.2), 40 filters 9x9 N(0, 0.01)."""
+    cs = ConvSpec(batch, 1, 28, 28, 40, 9, 9, 0, "sigmoid", 1)
+    return CrbmWorkload(
+        3, "c3_crbm_cd1", cs,
+        v0=_f32(rng(3, 0).random(cs.x_shape) < 0.2),
+        W=_f32(rng(3, 1).normal(0.0, 0.01, cs.w_shape)),
+        b=np.zeros((cs.K,), np.float32),
+        c=np.zeros((cs.C,), np.float32),
+        u=_f32(rng(3, 2).random(cs.y_shape, dtype=np.float32)),
+        lr=0.01)
+
+
+def _cnn(cfg: int, name: str, conv: List[ConvSpec], dense: List[DenseSpec], classes: int, lr: float,
+         x_kind: str, conv_sigma: Optional[float]) -> CnnWorkload:
+    """Weights: conv filters N(0, conv_sigma) when given, else N(0, sqrt(2/fan_in)); dense
+    weights N(0, sqrt(2/fan_in)); biases N(0, 0.01) so that the bias path carries signal."""
+    c0 = conv[0]
+    g = rng(cfg, 0)
+    x = g.random(c0.x_shape, dtype=np.float32) if x_kind == "uniform" else g.standard_normal(c0.x_shape, dtype=np.float32)
+    labels = rng(cfg, 1).integers(0, classes, size=(c0.N,)).astype(np.int32)
+    params: List[np.ndarray] = []
+    tid = 2
+    for c in conv:
+        sigma = conv_sigma if conv_sigma is not None else float(np.sqrt(2.0 / (c.C * c.R * c.S)))
+        params.append(_f32(rng(cfg, tid).normal(0.0, sigma, c.w_shape)))
+        params.append(_f32(rng(cfg, tid + 1).normal(0.0, 0.01, (c.K,))))
+        tid += 2
+    for d in dense:
+        sigma = float(np.sqrt(2.0 / d.in_))
+        params.append(_f32(rng(cfg, tid).standard_normal((d.out, d.in_), dtype=np.float32) * np.float32(sigma)))
+        params.append(_f32(rng(cfg, tid + 1).normal(0.0, 0.01, (d.out,))))
+        tid += 2
+    return CnnWorkload(cfg, name, conv, dense, classes, lr, _f32(x), labels, params)
+
+
+def config2(batch: int = 100) -> CnnWorkload:
+    """Small CNN on 1x28x28: conv 8@5x5 ReLU, pool 2, conv 8@5x5 ReLU, pool 2, dense 150, dense 10."""
+    conv = [ConvSpec(batch, 1, 28, 28, 8, 5, 5, 0, "relu", 2), ConvSpec(batch, 8, 12, 12, 8, 5, 5, 0, "relu", 2)]
+    dense = [DenseSpec(128, 150, "relu"), DenseSpec(150, 10, "identity")]
+    return _cnn(2, "c2_small_cnn", conv, dense, 10, 0.1, "uniform", 0.01)
+
+
+def config4(batch: int = 100) -> CnnWorkload:
+    """Color CNN on 3x32x32: conv 12@5x5 pad 2, pool 2, conv 24@3x3 pad 1, pool 2, dense 64, dense 10."""
+    conv = [ConvSpec(batch, 3, 32, 32, 12, 5, 5, 2, "relu", 2), ConvSpec(batch, 12, 16, 16, 24, 3, 3, 1, "relu", 2)]
+    dense = [DenseSpec(1536, 64, "relu"), DenseSpec(64, 10, "identity")]
+    return _cnn(4, "c4_color_cnn", conv, dense, 10, 0.001, "normal", None)
+
+
+def config5(batch: int = 128, image: int = 256, hidden: int = 2048, classes: int = 1000) -> CnnWorkload:
+    """Large-image CNN on 3x256x256: 4 x [conv 3x3 pad 1 (16,16,32,32) ReLU + pool 2], dense 2048, dense 1000.
+
+    `image`, `hidden`, `classes` shrink the same architecture for oracle-sized parity cases."""
+    assert image % 16 == 0
+    chans = [3, 16, 16, 32, 32]
+    conv, side = [], image
+    for i in range(4):
+        conv.append(ConvSpec(batch, chans[i], side, side, chans[i + 1], 3, 3, 1, "relu", 2))
+        side //= 2
+    dense = [DenseSpec(32 * side * side, hidden, "relu"), DenseSpec(hidden, classes, "identity")]
+    return _cnn(5, "c5_large_image_cnn", conv, dense, classes, 0.001, "normal", None)
+
+
+def with_batch(cs: ConvSpec, n: int) -> ConvSpec:
+    return replace(cs, N=n)
+
+
+ALL = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}
