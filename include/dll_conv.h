@@ -1,0 +1,147 @@
+/*
+ * dll_conv.h — C ABI of the MI355X (gfx950) implementation of the batched
+ * 2D-convolution hot path of DLL (arxiv 1804.04512).
+ *
+ * What the paper defines (Section II-A): every minibatch of N images is convolved with
+ * K kernels; the forward pass uses a "valid" convolution (the map shrinks), the backward
+ * pass a "full" convolution (the map expands back), a third convolution of the layer
+ * input with the output gradient yields the filter gradient; dense layers are matrix
+ * products; activations and gradient operations are fused around them; all arithmetic
+ * is single precision and works on whole minibatches; kernels are launched
+ * asynchronously and data stays on the device.
+ *
+ * Conventions shared by every entry point
+ *   - Every data pointer is a DEVICE pointer to a contiguous, row-major tensor.  fp32
+ *     unless stated; labels are int32; pooling indices are one byte each.
+ *   - The CALLER owns all memory.  The library never allocates, frees or keeps a pointer
+ *     after the call returns.  Scratch comes from `ws` (`ws_bytes` >= the matching
+ *     *_workspace_bytes query, 256-byte aligned); its contents are undefined afterwards.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     enqueue work and return without synchronising.
+ *   - Layouts: x [N][C][H][W]; w [K][C][R][S]; bias [K]; stride 1;
+ *     Ho = H + 2*pad - R + 1, Wo = W + 2*pad - S + 1;
+ *     y and pool_idx [N][K][Ho/pool][Wo/pool].
+ *   - `dy` always means the gradient w.r.t. the layer OUTPUT y (after activation and
+ *     pooling); the library applies the pooling/activation derivative itself.
+ *   - Errors are reported as dll_status before anything is launched: a missing required
+ *     pointer -> DLL_ERR_NULL; non-positive sizes, a filter larger than the padded input,
+ *     pad > R-1 or S-1, pooling on an odd map, an input aliasing an output (exact pointer
+ *     equality only; partial overlap is undetected and undefined) -> DLL_ERR_SHAPE; an
+ *     activation or pooling mode outside the enums, or a tensor of 2^31 or more elements
+ *     -> DLL_ERR_UNSUPPORTED; a workspace that is too small or misaligned ->
+ *     DLL_ERR_WORKSPACE; a failed launch -> DLL_ERR_DEVICE.  No exception crosses the ABI.
+ */
+#ifndef DLL_CONV_H
+#define DLL_CONV_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  DLL_OK = 0,
+  DLL_ERR_NULL = 1,
+  DLL_ERR_SHAPE = 2,
+  DLL_ERR_UNSUPPORTED = 3,
+  DLL_ERR_WORKSPACE = 4,
+  DLL_ERR_DEVICE = 5
+} dll_status;
+
+/* Activation functions the paper's networks use (Sections II-B, IV-B, V, VI). */
+typedef enum { DLL_ACT_IDENTITY = 0, DLL_ACT_SIGMOID = 1, DLL_ACT_RELU = 2 } dll_act;
+
+/* One stride-1 convolution layer (Section II-A: N images, K kernels). */
+typedef struct {
+  int N, C, H, W; /* input minibatch, NCHW                                        */
+  int K, R, S;    /* K filters of C x R x S                                       */
+  int pad;        /* zeros added on every side; 0 = the paper's "valid"           */
+  int act;        /* dll_act applied to conv + bias                               */
+  int pool;       /* 1 = none, 2 = 2x2 stride-2 max pooling (Ho and Wo even)      */
+} dll_conv_desc;
+
+/* One fully-connected layer, weights [out][in] (Section II-A). */
+typedef struct {
+  int in, out, act;
+} dll_dense_desc;
+
+/* A CNN: n_conv convolution layers (all with the same N, each consuming the previous
+ * one's output), flattened NCHW row-major into n_dense dense layers; the last dense layer
+ * is linear (its `act` is ignored) and feeds a softmax cross-entropy over `classes`. */
+typedef struct {
+  int n_conv;
+  const dll_conv_desc *conv; /* host pointer */
+  int n_dense;
+  const dll_dense_desc *dense; /* host pointer */
+  int classes;
+} dll_net_desc;
+
+const char *dll_status_string(dll_status s);
+
+/* Bytes of scratch the three single-layer calls below need at most (host computation). */
+size_t dll_conv_workspace_bytes(const dll_conv_desc *d);
+
+/* Forward layer (Section II-A, "valid convolution for the forward pass"):
+ *   z[n,k,i,j] = bias[k] + sum_{c,r,s} xpad[n,c,i+r,j+s] * w[k,c,r,s]
+ *   y = maxpool2x2(act(z)) when pool == 2, else act(z)
+ * pool_idx (required iff pool == 2) receives 2*a+b of the window's maximum (first one in
+ * the order (0,0),(0,1),(1,0),(1,1) on ties of the pre-activation).  bias may be NULL. */
+dll_status dll_conv_valid_fwd(const dll_conv_desc *d, const float *x, const float *w,
+                              const float *bias, float *y, unsigned char *pool_idx, void *ws,
+                              size_t ws_bytes, void *stream);
+
+/* Backward-data layer (Section II-A, "full convolution for the backward pass"):
+ *   dz = unpool(dy, pool_idx) * act'(y)          (never stored)
+ *   dx[n,c,i,j] = sum_{k,r,s} dz[n,k,i+pad-r,j+pad-s] * w[k,c,r,s]
+ * y may be NULL when act is the identity; pool_idx is required iff pool == 2. */
+dll_status dll_conv_full_bwd(const dll_conv_desc *d, const float *dy, const float *y,
+                             const unsigned char *pool_idx, const float *w, float *dx, void *ws,
+                             size_t ws_bytes, void *stream);
+
+/* Filter-gradient layer (Section II-A, gradient computations):
+ *   dw[k,c,r,s] = sum_{n,i,j} dz[n,k,i,j] * xpad[n,c,i+r,j+s];  dbias[k] = sum_{n,i,j} dz[n,k,i,j]
+ * with dz as above.  dbias may be NULL.  The batch reduction is a fixed-order tree:
+ * results are bit-identical from run to run. */
+dll_status dll_conv_valid_wgrad(const dll_conv_desc *d, const float *x, const float *dy,
+                                const float *y, const unsigned char *pool_idx, float *dw,
+                                float *dbias, void *ws, size_t ws_bytes, void *stream);
+
+/* One CD-1 step of a convolutional RBM with binary visible and hidden units (Section II:
+ * RBM/CRBM trained with Contrastive Divergence).  d->act and d->pool are ignored.
+ *   h0p = sigmoid(b_hid[k] + valid(v0, W));   h0s = 1[uniform < h0p]   (or h0_sample_in)
+ *   v1  = sigmoid(c_vis[ch] + full(h0s, W));  h1p = sigmoid(b_hid[k] + valid(v1, W))
+ *   dW = (grad(v0,h0p) - grad(v1,h1p)) / N;   db[k] = sum(h0p - h1p) / N;
+ *   dc[ch] = sum(v0 - v1) / N;                recon_mse = mean((v0 - v1)^2)
+ *   lr != 0:  W += lr*dW, b_hid += lr*db, c_vis += lr*dc   (after all gradients are formed)
+ * uniform [N][K][Ho][Wo] in [0,1) is required unless h0_sample_in is given.  dW, db, dc are
+ * required; h0_prob, h0_sample, v1, h1_prob and recon_mse (device scalar) may be NULL. */
+size_t dll_crbm_workspace_bytes(const dll_conv_desc *d);
+dll_status dll_crbm_cd1_step(const dll_conv_desc *d, const float *v0, float *W, float *b_hid,
+                             float *c_vis, const float *uniform, const float *h0_sample_in,
+                             float lr, float *dW, float *db, float *dc, float *h0_prob,
+                             float *h0_sample, float *v1, float *h1_prob, float *recon_mse,
+                             void *ws, size_t ws_bytes, void *stream);
+
+/* One mini-batch gradient-descent step of a CNN (Sections II, IV-B, V, VI): forward
+ * through every layer, softmax cross-entropy averaged over the batch, backward (full
+ * convolutions for the data gradients except into the network input, filter gradients,
+ * dense products with the transposed weights), then theta <- theta - lr * grad.
+ *   params  host array of 2*(n_conv+n_dense) device pointers: conv w0,b0,w1,b1,... then
+ *           dense W0,b0,...; updated in place when lr != 0
+ *   grads   NULL, or a host array in the same order; each non-NULL entry receives that
+ *           gradient (taken at the parameters as they were on entry)
+ *   labels  [N] int32 in [0, classes)
+ *   loss    device scalar, required;  logits [N][classes], may be NULL
+ *   pool_idx  NULL, or a host array of n_conv device pointers (entries may be NULL): each
+ *           non-NULL entry of a pooled layer receives that layer's pooling indices */
+size_t dll_cnn_workspace_bytes(const dll_net_desc *net);
+dll_status dll_cnn_train_step(const dll_net_desc *net, float *const *params, float *const *grads,
+                              const float *x, const int *labels, float lr, float *loss,
+                              float *logits, unsigned char *const *pool_idx, void *ws,
+                              size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

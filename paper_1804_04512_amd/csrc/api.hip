@@ -1,0 +1,447 @@
+// C ABI of the library: argument validation, workspace carving and the launch sequences of
+// the single-layer calls, the CRBM CD-1 step and the CNN training step.  No kernel lives
+// here and nothing is allocated: all scratch comes from the caller's workspace.
+#include "../../include/dll_conv.h"
+#include "dll_internal.h"
+
+#include <stdint.h>
+
+using namespace dllk;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Carver {
+  char *base;
+  size_t size, used;
+  Carver(void *ws, size_t bytes) : base(static_cast<char *>(ws)), size(bytes), used(0) {}
+  void *take(size_t bytes) {
+    void *p = base ? base + used : nullptr;
+    used += align_up(bytes);
+    return p;
+  }
+  float *floats(size_t n) { return static_cast<float *>(take(n * sizeof(float))); }
+};
+
+inline int out_h(const dll_conv_desc *d) { return d->H + 2 * d->pad - d->R + 1; }
+inline int out_w(const dll_conv_desc *d) { return d->W + 2 * d->pad - d->S + 1; }
+inline size_t y_count(const dll_conv_desc *d) {
+  return (size_t)d->N * d->K * (out_h(d) / d->pool) * (out_w(d) / d->pool);
+}
+inline size_t x_count(const dll_conv_desc *d) { return (size_t)d->N * d->C * d->H * d->W; }
+
+dll_status check_desc(const dll_conv_desc *d, bool check_act_pool = true) {
+  if (!d) return DLL_ERR_NULL;
+  if (d->N <= 0 || d->C <= 0 || d->H <= 0 || d->W <= 0 || d->K <= 0 || d->R <= 0 || d->S <= 0) return DLL_ERR_SHAPE;
+  if (d->pad < 0 || d->pad > d->R - 1 || d->pad > d->S - 1) return DLL_ERR_SHAPE;
+  const int Ho = out_h(d), Wo = out_w(d);
+  if (Ho <= 0 || Wo <= 0) return DLL_ERR_SHAPE;
+  if (check_act_pool) {
+    if (d->act < DLL_ACT_IDENTITY || d->act > DLL_ACT_RELU) return DLL_ERR_UNSUPPORTED;
+    if (d->pool != 1 && d->pool != 2) return DLL_ERR_UNSUPPORTED;
+    if (d->pool == 2 && ((Ho & 1) || (Wo & 1))) return DLL_ERR_SHAPE;
+  }
+  const size_t lim = (size_t)1 << 31;
+  if ((size_t)d->N * d->C * d->H * d->W >= lim || (size_t)d->N * d->K * Ho * Wo >= lim ||
+      (size_t)d->K * d->C * d->R * d->S >= lim)
+    return DLL_ERR_UNSUPPORTED;
+  if (d->R * d->S > 144) return DLL_ERR_UNSUPPORTED;  // filter-gradient kernel: at most 9 tap tiles per channel
+  return DLL_OK;
+}
+
+inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+dll_status check_ws(const void *ws, size_t have, size_t need) {
+  if (need == 0) return DLL_OK;
+  if (!ws) return DLL_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(ws) & (kAlign - 1)) return DLL_ERR_WORKSPACE;
+  return have >= need ? DLL_OK : DLL_ERR_WORKSPACE;
+}
+
+inline dll_status dev(hipError_t e) { return e == hipSuccess ? DLL_OK : DLL_ERR_DEVICE; }
+
+ConvEngineArgs fwd_args(const dll_conv_desc *d, const float *x, const float *w, const float *bias, float *y,
+                        unsigned char *idx) {
+  ConvEngineArgs a;
+  a.src = x;
+  a.N = d->N; a.Cin = d->C; a.Hin = d->H; a.Win = d->W;
+  a.w = w; a.w_flip = 0;
+  a.Kout = d->K; a.R = d->R; a.S = d->S; a.pad_h = d->pad; a.pad_w = d->pad;
+  a.Hout = out_h(d); a.Wout = out_w(d);
+  a.bias = bias; a.act = d->act; a.pool = d->pool;
+  a.out = y; a.out_idx = idx;
+  return a;
+}
+
+// Backward-data as a forward-form convolution of dz (K channels at Ho x Wo) with the
+// rotated, transposed filters on an input padded by R-1-pad (Section II-A's identity).
+ConvEngineArgs bwd_args(const dll_conv_desc *d, const float *dy, const float *y, const unsigned char *idx,
+                        const float *w, float *dx) {
+  ConvEngineArgs a;
+  a.src = dy; a.src_y = y; a.src_idx = idx;
+  a.src_dz = 1; a.src_act = d->act; a.src_pool = d->pool;
+  a.N = d->N; a.Cin = d->K; a.Hin = out_h(d); a.Win = out_w(d);
+  a.w = w; a.w_flip = 1;
+  a.Kout = d->C; a.R = d->R; a.S = d->S; a.pad_h = d->R - 1 - d->pad; a.pad_w = d->S - 1 - d->pad;
+  a.Hout = d->H; a.Wout = d->W;
+  a.act = ACT_IDENTITY; a.pool = 1;
+  a.out = dx;
+  return a;
+}
+
+WgradArgs wgrad_args(const dll_conv_desc *d, const float *x, const float *dy, const float *y,
+                     const unsigned char *idx, float *partial) {
+  WgradArgs a;
+  a.x = x; a.dy = dy; a.y = y; a.idx = idx;
+  a.act = d->act; a.pool = d->pool;
+  a.N = d->N; a.C = d->C; a.H = d->H; a.W = d->W; a.K = d->K; a.R = d->R; a.S = d->S; a.pad = d->pad;
+  a.partial = partial;
+  return a;
+}
+
+bool plan_for(const dll_conv_desc *d, WgradPlan *plan) {
+  return plan_wgrad(d->N, d->C, d->H, d->W, d->K, d->R, d->S, d->pad, plan);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *dll_status_string(dll_status s) {
+  switch (s) {
+  case DLL_OK: return "ok";
+  case DLL_ERR_NULL: return "required pointer is NULL";
+  case DLL_ERR_SHAPE: return "invalid shape or aliasing";
+  case DLL_ERR_UNSUPPORTED: return "unsupported configuration";
+  case DLL_ERR_WORKSPACE: return "workspace too small or misaligned";
+  case DLL_ERR_DEVICE: return "device launch failed";
+  }
+  return "unknown status";
+}
+
+size_t dll_conv_workspace_bytes(const dll_conv_desc *d) {
+  if (check_desc(d) != DLL_OK) return 0;
+  WgradPlan plan;
+  if (!plan_for(d, &plan)) return 0;
+  return align_up(plan.partial_floats * sizeof(float));
+}
+
+dll_status dll_conv_valid_fwd(const dll_conv_desc *d, const float *x, const float *w, const float *bias, float *y,
+                              unsigned char *pool_idx, void *ws, size_t ws_bytes, void *stream) {
+  (void)ws; (void)ws_bytes;
+  dll_status st = check_desc(d);
+  if (st != DLL_OK) return st;
+  if (!x || !w || !y || (d->pool == 2 && !pool_idx)) return DLL_ERR_NULL;
+  if ((const float *)y == x || (const float *)y == w) return DLL_ERR_SHAPE;
+  if (misaligned(x) || misaligned(w) || misaligned(y) || misaligned(pool_idx)) return DLL_ERR_SHAPE;
+  return dev(launch_conv_engine(fwd_args(d, x, w, bias, y, pool_idx), static_cast<hipStream_t>(stream)));
+}
+
+dll_status dll_conv_full_bwd(const dll_conv_desc *d, const float *dy, const float *y, const unsigned char *pool_idx,
+                             const float *w, float *dx, void *ws, size_t ws_bytes, void *stream) {
+  (void)ws; (void)ws_bytes;
+  dll_status st = check_desc(d);
+  if (st != DLL_OK) return st;
+  if (!dy || !w || !dx || (d->act != DLL_ACT_IDENTITY && !y) || (d->pool == 2 && !pool_idx)) return DLL_ERR_NULL;
+  if ((const float *)dx == dy || (const float *)dx == y || (const float *)dx == w) return DLL_ERR_SHAPE;
+  if (misaligned(dy) || misaligned(y) || misaligned(w) || misaligned(dx) || misaligned(pool_idx)) return DLL_ERR_SHAPE;
+  return dev(launch_conv_engine(bwd_args(d, dy, y, pool_idx, w, dx), static_cast<hipStream_t>(stream)));
+}
+
+dll_status dll_conv_valid_wgrad(const dll_conv_desc *d, const float *x, const float *dy, const float *y,
+                                const unsigned char *pool_idx, float *dw, float *dbias, void *ws, size_t ws_bytes,
+                                void *stream) {
+  dll_status st = check_desc(d);
+  if (st != DLL_OK) return st;
+  if (!x || !dy || !dw || (d->act != DLL_ACT_IDENTITY && !y) || (d->pool == 2 && !pool_idx)) return DLL_ERR_NULL;
+  if ((const float *)dw == x || (const float *)dw == dy || (const float *)dw == y) return DLL_ERR_SHAPE;
+  if (misaligned(x) || misaligned(dy) || misaligned(y) || misaligned(dw)) return DLL_ERR_SHAPE;
+  WgradPlan plan;
+  if (!plan_for(d, &plan)) return DLL_ERR_UNSUPPORTED;
+  st = check_ws(ws, ws_bytes, align_up(plan.partial_floats * sizeof(float)));
+  if (st != DLL_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  float *partial = static_cast<float *>(ws);
+  st = dev(launch_wgrad(wgrad_args(d, x, dy, y, pool_idx, partial), plan, s));
+  if (st != DLL_OK) return st;
+  WgradReduceArgs r;
+  r.pos = partial; r.scale = 1.0f; r.dw = dw; r.db = dbias;
+  r.C = d->C; r.K = d->K; r.R = d->R; r.S = d->S;
+  return dev(launch_wgrad_reduce(r, plan, s));
+}
+
+size_t dll_crbm_workspace_bytes(const dll_conv_desc *d) {
+  if (check_desc(d, false) != DLL_OK) return 0;
+  WgradPlan plan;
+  if (!plan_for(d, &plan)) return 0;
+  dll_conv_desc t = *d;
+  t.pool = 1;
+  Carver c(nullptr, 0);
+  c.floats(y_count(&t)); c.floats(y_count(&t)); c.floats(y_count(&t));  // h0p, h0s, h1p
+  c.floats(x_count(&t));                                                // v1
+  c.floats(plan.partial_floats); c.floats(plan.partial_floats);
+  c.floats(visible_stats_scratch_floats(d->N, d->C, d->H * d->W));
+  return c.used;
+}
+
+dll_status dll_crbm_cd1_step(const dll_conv_desc *din, const float *v0, float *W, float *b_hid, float *c_vis,
+                             const float *uniform, const float *h0_sample_in, float lr, float *dW, float *db, float *dc,
+                             float *h0_prob, float *h0_sample, float *v1, float *h1_prob, float *recon_mse, void *ws,
+                             size_t ws_bytes, void *stream) {
+  dll_status st = check_desc(din, false);
+  if (st != DLL_OK) return st;
+  if (!v0 || !W || !b_hid || !c_vis || !dW || !db || !dc || (!uniform && !h0_sample_in)) return DLL_ERR_NULL;
+  if (dW == W || db == b_hid || dc == c_vis || (const float *)v1 == v0) return DLL_ERR_SHAPE;
+  dll_conv_desc d = *din;
+  d.act = DLL_ACT_SIGMOID;
+  d.pool = 1;
+  if (misaligned(v0) || misaligned(W) || misaligned(uniform) || misaligned(h0_sample_in) || misaligned(dW) ||
+      misaligned(h0_prob) || misaligned(h0_sample) || misaligned(v1) || misaligned(h1_prob))
+    return DLL_ERR_SHAPE;
+  WgradPlan plan;
+  if (!plan_for(&d, &plan)) return DLL_ERR_UNSUPPORTED;
+  st = check_ws(ws, ws_bytes, dll_crbm_workspace_bytes(din));
+  if (st != DLL_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  Carver c(ws, ws_bytes);
+  const size_t nh = y_count(&d), nv = x_count(&d);
+  float *h0p_ws = c.floats(nh), *h0s_ws = c.floats(nh), *h1p_ws = c.floats(nh), *v1_ws = c.floats(nv);
+  float *part_pos = c.floats(plan.partial_floats), *part_neg = c.floats(plan.partial_floats);
+  float *stats = c.floats(visible_stats_scratch_floats(d.N, d.C, d.H * d.W));
+  float *h0p = h0_prob ? h0_prob : h0p_ws;
+  float *h0s = h0_sample ? h0_sample : h0s_ws;
+  float *h1p = h1_prob ? h1_prob : h1p_ws;
+  float *v1p = v1 ? v1 : v1_ws;
+
+  // positive phase: hidden probabilities (+ Bernoulli sample in the same epilogue)
+  ConvEngineArgs f0 = fwd_args(&d, v0, W, b_hid, h0p, nullptr);
+  if (!h0_sample_in) { f0.uniform = uniform; f0.sample = h0s; }
+  if ((st = dev(launch_conv_engine(f0, s))) != DLL_OK) return st;
+  const float *hs = h0s;
+  if (h0_sample_in) {
+    hs = h0_sample_in;
+    if (h0_sample && (st = dev(launch_copy(h0_sample_in, h0_sample, nh, s))) != DLL_OK) return st;
+  }
+  // reconstruction: full convolution of the sample, + c, sigmoid
+  ConvEngineArgs rec = bwd_args(&d, hs, nullptr, nullptr, W, v1p);
+  rec.src_dz = 0;
+  rec.bias = c_vis;
+  rec.act = ACT_SIGMOID;
+  if ((st = dev(launch_conv_engine(rec, s))) != DLL_OK) return st;
+  // negative phase hidden probabilities
+  if ((st = dev(launch_conv_engine(fwd_args(&d, v1p, W, b_hid, h1p, nullptr), s))) != DLL_OK) return st;
+  // statistics: filter gradients with dz := hidden probabilities
+  dll_conv_desc di = d;
+  di.act = DLL_ACT_IDENTITY;
+  if ((st = dev(launch_wgrad(wgrad_args(&di, v0, h0p, nullptr, nullptr, part_pos), plan, s))) != DLL_OK) return st;
+  if ((st = dev(launch_wgrad(wgrad_args(&di, v1p, h1p, nullptr, nullptr, part_neg), plan, s))) != DLL_OK) return st;
+  const float invB = 1.0f / (float)d.N;
+  WgradReduceArgs r;
+  r.pos = part_pos; r.neg = part_neg; r.scale = invB; r.dw = dW; r.db = db;
+  r.C = d.C; r.K = d.K; r.R = d.R; r.S = d.S;
+  if (lr != 0.0f) { r.w_update = W; r.b_update = b_hid; r.step = lr; }
+  if ((st = dev(launch_wgrad_reduce(r, plan, s))) != DLL_OK) return st;
+  return dev(launch_visible_stats(v0, v1p, d.N, d.C, d.H * d.W, invB, dc, recon_mse, lr != 0.0f ? c_vis : nullptr, lr,
+                                  stats, s));
+}
+
+}  // extern "C"
+
+// ---------------------------------------------------------------------------------------
+// CNN training step
+// ---------------------------------------------------------------------------------------
+namespace {
+
+struct NetLayout {
+  size_t total = 0;
+  size_t gmax = 0;       // floats of the largest gradient tensor passed between layers
+  size_t partial = 0;    // floats of the largest partial-sum area
+  int B = 0;
+};
+
+dll_status check_net(const dll_net_desc *net, NetLayout *lay) {
+  if (!net || !net->conv || !net->dense) return DLL_ERR_NULL;
+  if (net->n_conv < 1 || net->n_dense < 1 || net->classes < 1) return DLL_ERR_SHAPE;
+  const int B = net->conv[0].N;
+  size_t feat = 0, gmax = 0, partial = 0;
+  for (int l = 0; l < net->n_conv; ++l) {
+    const dll_conv_desc *d = &net->conv[l];
+    dll_status st = check_desc(d);
+    if (st != DLL_OK) return st;
+    if (d->N != B) return DLL_ERR_SHAPE;
+    if (l > 0) {
+      const dll_conv_desc *q = &net->conv[l - 1];
+      if (d->C != q->K || d->H != out_h(q) / q->pool || d->W != out_w(q) / q->pool) return DLL_ERR_SHAPE;
+          if (x_count(d) > gmax) gmax = x_count(d);
+    }
+    if (y_count(d) > gmax) gmax = y_count(d);
+    WgradPlan plan;
+    if (!plan_for(d, &plan)) return DLL_ERR_UNSUPPORTED;
+    if (plan.partial_floats > partial) partial = plan.partial_floats;
+    feat = y_count(d) / B;
+  }
+  for (int q = 0; q < net->n_dense; ++q) {
+    const dll_dense_desc *dd = &net->dense[q];
+    if (dd->in <= 0 || dd->out <= 0) return DLL_ERR_SHAPE;
+    if ((size_t)dd->in != feat) return DLL_ERR_SHAPE;
+    if (q < net->n_dense - 1 && (dd->act < DLL_ACT_IDENTITY || dd->act > DLL_ACT_RELU)) return DLL_ERR_UNSUPPORTED;
+    if ((size_t)dd->in * dd->out >= ((size_t)1 << 31)) return DLL_ERR_UNSUPPORTED;
+    const size_t gi = (size_t)B * dd->in, go = (size_t)B * dd->out;
+    if (gi > gmax) gmax = gi;
+    if (go > gmax) gmax = go;
+    size_t p;
+    p = (size_t)gemm_pick_split_k(B, dd->out, dd->in) * B * dd->out;      // forward
+    if (p > partial) partial = p;
+    p = (size_t)gemm_pick_split_k(B, dd->in, dd->out) * B * dd->in;       // backward data
+    if (p > partial) partial = p;
+    feat = dd->out;
+  }
+  if ((int)feat != net->classes) return DLL_ERR_SHAPE;
+  lay->gmax = gmax;
+  lay->partial = partial;
+  lay->B = B;
+  return DLL_OK;
+}
+
+struct NetBuffers {
+  float *act[64];
+  unsigned char *idx[32];
+  float *gbuf[2];
+  float *rowloss;
+  float *partial;
+};
+
+size_t carve_net(const dll_net_desc *net, const NetLayout &lay, void *ws, NetBuffers *nb) {
+  Carver c(ws, 0);
+  const int L = net->n_conv, D = net->n_dense;
+  for (int l = 0; l < L; ++l) {
+    nb->act[l + 1] = c.floats(y_count(&net->conv[l]));
+    nb->idx[l] = static_cast<unsigned char *>(c.take(y_count(&net->conv[l])));
+  }
+  for (int q = 0; q < D; ++q) nb->act[L + q + 1] = c.floats((size_t)lay.B * net->dense[q].out);
+  nb->gbuf[0] = c.floats(lay.gmax);
+  nb->gbuf[1] = c.floats(lay.gmax);
+  nb->rowloss = c.floats(lay.B);
+  nb->partial = c.floats(lay.partial);
+  return c.used;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t dll_cnn_workspace_bytes(const dll_net_desc *net) {
+  NetLayout lay;
+  if (check_net(net, &lay) != DLL_OK) return 0;
+  if (net->n_conv > 31 || net->n_conv + net->n_dense > 62) return 0;
+  NetBuffers nb;
+  return carve_net(net, lay, nullptr, &nb);
+}
+
+dll_status dll_cnn_train_step(const dll_net_desc *net, float *const *params, float *const *grads, const float *x,
+                              const int *labels, float lr, float *loss, float *logits, unsigned char *const *pool_idx,
+                              void *ws, size_t ws_bytes, void *stream) {
+  NetLayout lay;
+  dll_status st = check_net(net, &lay);
+  if (st != DLL_OK) return st;
+  const int L = net->n_conv, D = net->n_dense, B = lay.B;
+  if (L > 31 || L + D > 62) return DLL_ERR_UNSUPPORTED;
+  if (!params || !x || !labels || !loss) return DLL_ERR_NULL;
+  for (int p = 0; p < 2 * (L + D); ++p) {
+    if (!params[p]) return DLL_ERR_NULL;
+    if (misaligned(params[p]) || (grads && misaligned(grads[p]))) return DLL_ERR_SHAPE;
+    if (grads && grads[p] == params[p]) return DLL_ERR_SHAPE;
+  }
+  if (misaligned(x) || misaligned(logits)) return DLL_ERR_SHAPE;
+  NetBuffers nb;
+  const size_t need = carve_net(net, lay, ws, &nb);
+  st = check_ws(ws, ws_bytes, need);
+  if (st != DLL_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const float step = -lr;
+  const bool upd = lr != 0.0f;
+
+  for (int l = 0; l < L; ++l)
+    if (pool_idx && pool_idx[l] && net->conv[l].pool == 2) {
+      if (misaligned(pool_idx[l])) return DLL_ERR_SHAPE;
+      nb.idx[l] = pool_idx[l];
+    }
+
+  // ---- forward
+  nb.act[0] = const_cast<float *>(x);
+  for (int l = 0; l < L; ++l) {
+    const dll_conv_desc *d = &net->conv[l];
+    st = dev(launch_conv_engine(fwd_args(d, nb.act[l], params[2 * l], params[2 * l + 1], nb.act[l + 1], nb.idx[l]), s));
+    if (st != DLL_OK) return st;
+  }
+  if (logits) nb.act[L + D] = logits;
+  for (int q = 0; q < D; ++q) {
+    const dll_dense_desc *dd = &net->dense[q];
+    GemmArgs g;
+    g.M = B; g.N = dd->out; g.Kdim = dd->in;
+    g.A = nb.act[L + q]; g.a_m = dd->in; g.a_k = 1;
+    g.B = params[2 * (L + q)]; g.b_k = 1; g.b_n = dd->in;
+    g.bias = params[2 * (L + q) + 1];
+    g.act = (q == D - 1) ? ACT_IDENTITY : dd->act;
+    g.Cout = nb.act[L + q + 1]; g.c_m = dd->out; g.c_n = 1;
+    g.split_k = gemm_pick_split_k(g.M, g.N, g.Kdim);
+    g.partial = nb.partial;
+    if ((st = dev(launch_gemm(g, s))) != DLL_OK) return st;
+  }
+  // ---- loss
+  float *gcur = nb.gbuf[0], *gnext = nb.gbuf[1];
+  if ((st = dev(launch_softmax_ce(nb.act[L + D], labels, B, net->classes, loss, gcur, nb.rowloss, s))) != DLL_OK) return st;
+  // ---- dense backward: data gradient first (old weights), then weight gradient + update
+  for (int q = D - 1; q >= 0; --q) {
+    const dll_dense_desc *dd = &net->dense[q];
+    const int act = (q == D - 1) ? ACT_IDENTITY : dd->act;
+    const float *hout = (act == ACT_IDENTITY) ? nullptr : nb.act[L + q + 1];
+    float *Wq = params[2 * (L + q)], *bq = params[2 * (L + q) + 1];
+    GemmArgs g;
+    g.M = B; g.N = dd->in; g.Kdim = dd->out;
+    g.A = gcur; g.a_m = dd->out; g.a_k = 1; g.A_out = hout; g.a_act = act;
+    g.B = Wq; g.b_k = dd->in; g.b_n = 1;
+    g.Cout = gnext; g.c_m = dd->in; g.c_n = 1;
+    g.split_k = gemm_pick_split_k(g.M, g.N, g.Kdim);
+    g.partial = nb.partial;
+    if ((st = dev(launch_gemm(g, s))) != DLL_OK) return st;
+    GemmArgs h;
+    h.M = dd->out; h.N = dd->in; h.Kdim = B;
+    h.A = gcur; h.a_m = 1; h.a_k = dd->out; h.A_out = hout; h.a_act = act;
+    h.B = nb.act[L + q]; h.b_k = dd->in; h.b_n = 1;
+    h.Cout = grads ? grads[2 * (L + q)] : nullptr; h.c_m = dd->in; h.c_n = 1;
+    if (upd) { h.update = Wq; h.step = step; }
+    h.split_k = 1;
+    if (h.Cout || h.update)
+      if ((st = dev(launch_gemm(h, s))) != DLL_OK) return st;
+    float *gb = grads ? grads[2 * (L + q) + 1] : nullptr;
+    if (gb || upd)
+      if ((st = dev(launch_colsum(gcur, hout, act, B, dd->out, gb, upd ? bq : nullptr, step, s))) != DLL_OK) return st;
+    float *t = gcur; gcur = gnext; gnext = t;
+  }
+  // ---- convolution backward: data gradient with the old filters, then filter gradient + update
+  for (int l = L - 1; l >= 0; --l) {
+    const dll_conv_desc *d = &net->conv[l];
+    if (l > 0) {
+      st = dev(launch_conv_engine(bwd_args(d, gcur, nb.act[l + 1], nb.idx[l], params[2 * l], gnext), s));
+      if (st != DLL_OK) return st;
+    }
+    WgradPlan plan;
+    if (!plan_for(d, &plan)) return DLL_ERR_UNSUPPORTED;
+    st = dev(launch_wgrad(wgrad_args(d, nb.act[l], gcur, nb.act[l + 1], nb.idx[l], nb.partial), plan, s));
+    if (st != DLL_OK) return st;
+    WgradReduceArgs r;
+    r.pos = nb.partial; r.scale = 1.0f;
+    r.dw = grads ? grads[2 * l] : nullptr;
+    r.db = grads ? grads[2 * l + 1] : nullptr;
+    if (upd) { r.w_update = params[2 * l]; r.b_update = params[2 * l + 1]; r.step = step; }
+    r.C = d->C; r.K = d->K; r.R = d->R; r.S = d->S;
+    if ((st = dev(launch_wgrad_reduce(r, plan, s))) != DLL_OK) return st;
+    float *t = gcur; gcur = gnext; gnext = t;
+  }
+  return DLL_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,300 @@
+// Forward-form implicit-GEMM convolution on fp32 MFMA (v_mfma_f32_16x16x4_f32), gfx950.
+//
+// One workgroup (4 wavefronts of 64) produces a 32-wide x (8*RP)-tall tile of pre-pool
+// outputs of one image for NT*16 output channels.  Pixels sit on the MFMA M axis, output
+// channels on N, the (channel, tap) contraction on K:
+//   * an M-tile is 16 pixels = 4 pooling windows x 4 window positions, arranged so that the
+//     4 accumulator registers of a lane are exactly the 2x2 window of one pooled pixel:
+//     max-pooling, its arg-max, bias and activation need no cross-lane traffic;
+//   * the 4 M-tiles a lane owns in a row pair are 4 neighbouring pooled columns, so the
+//     pooled result leaves as one 16-byte store per lane;
+//   * the input halo tile and the filter slice of the current channel chunk live in LDS;
+//     the A operand is gathered from the halo tile with a per-step tap offset, the B
+//     operand is a contiguous 64-float row of the filter slice.
+// The source can be a plain tensor (forward layer, CRBM reconstruction) or the virtual
+// tensor dz = unpool(dy) * act'(y) (backward-data layer), which is formed while staging and
+// never reaches HBM.  With w_flip the filters are read rotated by 180 degrees and with the
+// channel roles swapped, which turns the paper's "full convolution" (Section II-A) into this
+// same valid-convolution engine run on an input padded by R-1-pad.
+#include "dll_internal.h"
+
+namespace dllk {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kTileW = 32;
+
+struct EngineGeom {
+  int CC, nchunks;   // channels per chunk, number of chunks
+  int rows, cols;    // staged halo tile extent
+  int RS, PS;        // LDS row / plane stride (floats)
+  int KC, KS;        // padded taps per chunk (multiple of 4), MFMA steps per chunk
+  int tiles_x, tiles_y;
+  int kgroups;       // groups of NT*16 output channels (gridDim.y)
+};
+
+struct EngineParams {
+  ConvEngineArgs a;
+  EngineGeom g;
+};
+
+__device__ __forceinline__ float act_apply(int act, float z) {
+  if (act == ACT_SIGMOID) return 1.0f / (1.0f + expf(-z));
+  if (act == ACT_RELU) return z > 0.0f ? z : 0.0f;
+  return z;
+}
+
+// dz at pre-pool position (i,j) of plane (n,k): dy routed to the recorded arg-max, times act'(y).
+__device__ __forceinline__ float dz_value(const ConvEngineArgs &a, int n, int k, int i, int j) {
+  int o;
+  if (a.src_pool == 2) {
+    const int Hp = a.Hin >> 1, Wp = a.Win >> 1;
+    o = ((n * a.Cin + k) * Hp + (i >> 1)) * Wp + (j >> 1);
+    if (a.src_idx[o] != (unsigned char)(((i & 1) << 1) | (j & 1))) return 0.0f;
+  } else {
+    o = ((n * a.Cin + k) * a.Hin + i) * a.Win + j;
+  }
+  float g = a.src[o];
+  if (a.src_act == ACT_SIGMOID) {
+    const float v = a.src_y[o];
+    g *= v * (1.0f - v);
+  } else if (a.src_act == ACT_RELU) {
+    if (!(a.src_y[o] > 0.0f)) g = 0.0f;
+  }
+  return g;
+}
+
+template <int NT, int RP>
+__global__ __launch_bounds__(kThreads) void conv_engine_kernel(const EngineParams p) {
+  extern __shared__ float lds[];
+  const ConvEngineArgs &a = p.a;
+  const EngineGeom &g = p.g;
+  float *xs = lds;                                  // [CC][PS]
+  float *wl = xs + g.CC * g.PS;                     // [NT][KC][16]
+  int *koff = reinterpret_cast<int *>(wl + NT * g.KC * 16);  // [KC]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i16 = lane & 15, kq = lane >> 4;
+  const int bid = blockIdx.x;
+  const int tx = bid % g.tiles_x;
+  const int ty = (bid / g.tiles_x) % g.tiles_y;
+  const int n = bid / (g.tiles_x * g.tiles_y);
+  const int ko0 = blockIdx.y * (NT * 16);
+  constexpr int TH = 8 * RP;
+  const int oy0 = ty * TH, ox0 = tx * kTileW;       // pre-pool output origin of the tile
+  const int RSf = a.R * a.S;
+
+  // tap offsets inside the halo tile: kk = (r*S + s)*CC + cl  ->  cl*PS + r*RS + s
+  for (int kk = tid; kk < g.KC; kk += kThreads) {
+    const int cl = kk % g.CC, rs = kk / g.CC;
+    const int r = rs / a.S, s = rs - r * a.S;
+    koff[kk] = rs < RSf ? cl * g.PS + r * g.RS + s : 0;
+  }
+
+  floatx4 acc[RP][4][NT];
+#pragma unroll
+  for (int rp = 0; rp < RP; ++rp)
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) acc[rp][mt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  // lane's pixel inside an M-tile: window gq, position (wa, wb)
+  const int gq = i16 >> 2, wa = (i16 >> 1) & 1, wb = i16 & 1;
+  const int a_base = (wave * 2 * RP + wa) * g.RS + 8 * gq + wb;
+
+  for (int chunk = 0; chunk < g.nchunks; ++chunk) {
+    const int c0 = chunk * g.CC;
+    __syncthreads();  // previous chunk's readers are done
+    // ---- filter slice: wl[nt][kk][j] = wgt(ko0 + 16nt + j, c0 + cl, r, s)
+    for (int e = tid; e < NT * g.KC * 16; e += kThreads) {
+      const int j = e & 15;
+      const int q = e >> 4;
+      const int kk = q % g.KC, nt = q / g.KC;
+      const int cl = kk % g.CC, rs = kk / g.CC;
+      const int r = rs / a.S, s = rs - r * a.S;
+      const int ko = ko0 + nt * 16 + j, ci = c0 + cl;
+      float v = 0.0f;
+      if (rs < RSf && ko < a.Kout && ci < a.Cin) {
+        v = a.w_flip ? a.w[((ci * a.Kout + ko) * a.R + (a.R - 1 - r)) * a.S + (a.S - 1 - s)]
+                     : a.w[((ko * a.Cin + ci) * a.R + r) * a.S + s];
+      }
+      wl[e] = v;
+    }
+    // ---- halo tile of the source, zero outside the image (padding) and past Cin
+    {
+      const int total = g.CC * g.rows * g.cols;
+      int col = tid % g.cols;
+      int q = tid / g.cols;
+      int row = q % g.rows, cl = q / g.rows;
+      const int dcol = kThreads % g.cols, dq = kThreads / g.cols;
+      for (int e = tid; e < total; e += kThreads) {
+        const int gi = oy0 - a.pad_h + row, gj = ox0 - a.pad_w + col, ci = c0 + cl;
+        float v = 0.0f;
+        if (ci < a.Cin && gi >= 0 && gi < a.Hin && gj >= 0 && gj < a.Win) {
+          v = a.src_dz ? dz_value(a, n, ci, gi, gj) : a.src[((n * a.Cin + ci) * a.Hin + gi) * a.Win + gj];
+        }
+        xs[cl * g.PS + row * g.RS + col] = v;
+        col += dcol;
+        row += dq;
+        if (col >= g.cols) { col -= g.cols; ++row; }
+        while (row >= g.rows) { row -= g.rows; ++cl; }
+      }
+    }
+    __syncthreads();
+    // ---- MFMA over the chunk's taps
+    for (int t = 0; t < g.KS; ++t) {
+      const int o = koff[4 * t + kq];
+      float bf[NT];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) bf[nt] = wl[(nt * g.KC + 4 * t + kq) * 16 + i16];
+#pragma unroll
+      for (int rp = 0; rp < RP; ++rp) {
+        const float *xr = xs + a_base + rp * 2 * g.RS + o;
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+          const float af = xr[2 * mt];
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+            acc[rp][mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(af, bf[nt], acc[rp][mt][nt], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  // ---- epilogue.  Lane owns output channel ko0+16nt+i16, window column 4*kq+mt of the tile,
+  // window row wave*RP+rp; acc[..][v] is window position v = 2a+b.
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const int ko = ko0 + nt * 16 + i16;
+    if (ko >= a.Kout) continue;
+    const float bv = a.bias ? a.bias[ko] : 0.0f;
+#pragma unroll
+    for (int rp = 0; rp < RP; ++rp) {
+      const int py = (oy0 >> 1) + wave * RP + rp;   // window row (pre-pool rows 2py, 2py+1)
+      const int px0 = (ox0 >> 1) + 4 * kq;          // first of the lane's 4 window columns
+      if (2 * py >= a.Hout) continue;
+      if (a.pool == 2) {
+        const int Hp = a.Hout >> 1, Wp = a.Wout >> 1;
+        float yv[4];
+        unsigned char iv[4];
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+          const floatx4 z = acc[rp][mt][nt];
+          float m = z[0];
+          int arg = 0;
+          if (z[1] > m) { m = z[1]; arg = 1; }
+          if (z[2] > m) { m = z[2]; arg = 2; }
+          if (z[3] > m) { m = z[3]; arg = 3; }
+          yv[mt] = act_apply(a.act, m + bv);   // bias and a monotone activation commute with max
+          iv[mt] = (unsigned char)arg;
+        }
+        const int o = ((n * a.Kout + ko) * Hp + py) * Wp + px0;
+        if (px0 + 3 < Wp && (Wp & 3) == 0) {
+          *reinterpret_cast<float4 *>(a.out + o) = make_float4(yv[0], yv[1], yv[2], yv[3]);
+          *reinterpret_cast<uchar4 *>(a.out_idx + o) = make_uchar4(iv[0], iv[1], iv[2], iv[3]);
+        } else {
+#pragma unroll
+          for (int mt = 0; mt < 4; ++mt)
+            if (px0 + mt < Wp) { a.out[o + mt] = yv[mt]; a.out_idx[o + mt] = iv[mt]; }
+        }
+      } else {
+#pragma unroll
+        for (int wa2 = 0; wa2 < 2; ++wa2) {
+          const int oy = 2 * py + wa2;
+          if (oy >= a.Hout) continue;
+          const int ox = 2 * px0;
+          const int o = ((n * a.Kout + ko) * a.Hout + oy) * a.Wout + ox;
+          float yv[8];
+#pragma unroll
+          for (int mt = 0; mt < 4; ++mt) {
+            yv[2 * mt] = act_apply(a.act, acc[rp][mt][nt][2 * wa2] + bv);
+            yv[2 * mt + 1] = act_apply(a.act, acc[rp][mt][nt][2 * wa2 + 1] + bv);
+          }
+          if (ox + 7 < a.Wout && (a.Wout & 3) == 0) {
+            *reinterpret_cast<float4 *>(a.out + o) = make_float4(yv[0], yv[1], yv[2], yv[3]);
+            *reinterpret_cast<float4 *>(a.out + o + 4) = make_float4(yv[4], yv[5], yv[6], yv[7]);
+            if (a.sample) {
+              const float4 u0 = *reinterpret_cast<const float4 *>(a.uniform + o);
+              const float4 u1 = *reinterpret_cast<const float4 *>(a.uniform + o + 4);
+              *reinterpret_cast<float4 *>(a.sample + o) =
+                  make_float4(u0.x < yv[0] ? 1.f : 0.f, u0.y < yv[1] ? 1.f : 0.f, u0.z < yv[2] ? 1.f : 0.f, u0.w < yv[3] ? 1.f : 0.f);
+              *reinterpret_cast<float4 *>(a.sample + o + 4) =
+                  make_float4(u1.x < yv[4] ? 1.f : 0.f, u1.y < yv[5] ? 1.f : 0.f, u1.z < yv[6] ? 1.f : 0.f, u1.w < yv[7] ? 1.f : 0.f);
+            }
+          } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              if (ox + e < a.Wout) {
+                a.out[o + e] = yv[e];
+                if (a.sample) a.sample[o + e] = a.uniform[o + e] < yv[e] ? 1.f : 0.f;
+              }
+          }
+        }
+      }
+    }
+  }
+}
+
+inline int round_up_mod(int v, int m, int r) {  // smallest value >= v congruent to r mod m
+  int x = v - (v % m) + r;
+  if (x < v) x += m;
+  return x;
+}
+
+bool plan_engine(const ConvEngineArgs &a, int NT, int RP, EngineGeom *g, size_t *lds_bytes) {
+  const int TH = 8 * RP;
+  g->rows = TH + a.R - 1;
+  g->cols = kTileW + a.S - 1;
+  g->RS = round_up_mod(g->cols, 8, 2);
+  g->PS = round_up_mod(g->RS * g->rows, 8, 4);
+  int CC = a.Cin < 16 ? a.Cin : 16;
+  for (;;) {
+    g->CC = CC;
+    g->KC = (CC * a.R * a.S + 3) / 4 * 4;
+    g->KS = g->KC / 4;
+    *lds_bytes = sizeof(float) * ((size_t)CC * g->PS + (size_t)NT * g->KC * 16 + g->KC);
+    if (*lds_bytes <= 64 * 1024 || CC == 1) break;
+    CC = (CC + 1) / 2;
+  }
+  if (*lds_bytes > 64 * 1024) return false;
+  g->nchunks = (a.Cin + g->CC - 1) / g->CC;
+  g->tiles_x = (a.Wout + kTileW - 1) / kTileW;
+  g->tiles_y = (a.Hout + TH - 1) / TH;
+  g->kgroups = (a.Kout + NT * 16 - 1) / (NT * 16);
+  return true;
+}
+
+template <int NT, int RP>
+hipError_t launch_t(const ConvEngineArgs &a, hipStream_t stream) {
+  EngineParams p;
+  p.a = a;
+  size_t lds = 0;
+  if (!plan_engine(a, NT, RP, &p.g, &lds)) return hipErrorInvalidValue;
+  const long blocks = (long)a.N * p.g.tiles_x * p.g.tiles_y;
+  if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  dim3 grid((unsigned)blocks, (unsigned)p.g.kgroups, 1);
+  hipLaunchKernelGGL((conv_engine_kernel<NT, RP>), grid, dim3(kThreads), lds, stream, p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_conv_engine(const ConvEngineArgs &a, hipStream_t stream) {
+  // shallow maps (<= 8 pre-pool rows) use the 8-row tile; 16 output channels per N-tile
+  const bool small = a.Hout <= 8;
+  const int nt = a.Kout <= 16 ? 1 : (a.Kout <= 32 ? 2 : 3);
+  if (small) {
+    if (nt == 1) return launch_t<1, 1>(a, stream);
+    if (nt == 2) return launch_t<2, 1>(a, stream);
+    return launch_t<3, 1>(a, stream);
+  }
+  if (nt == 1) return launch_t<1, 2>(a, stream);
+  if (nt == 2) return launch_t<2, 2>(a, stream);
+  return launch_t<3, 2>(a, stream);
+}
+
+}  // namespace dllk

@@ -1,0 +1,123 @@
+// Internal launch interfaces between the C-ABI layer and the gfx950 kernels.
+// Host-side plain structs only; every pointer is a device pointer.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace dllk {
+
+enum { ACT_IDENTITY = 0, ACT_SIGMOID = 1, ACT_RELU = 2 };
+
+// ---------------------------------------------------------------------------------------
+// Forward-form implicit-GEMM convolution engine (fp32 MFMA 16x16x4).
+//   out[n,ko,i,j] = epilogue( sum_{ci,r,s} srcpad[n,ci,i+r,j+s] * wgt(ko,ci,r,s) )
+// It serves the forward layer (src = x), the backward-data layer (src = dz derived on the
+// fly from dy/y/pool_idx, filters flipped and transposed, pad' = R-1-pad: the paper's
+// "full convolution = valid convolution with padding", Section II-A) and the CRBM
+// reconstruction.
+// ---------------------------------------------------------------------------------------
+struct ConvEngineArgs {
+  // logical source, extent [N][Cin][Hin][Win]
+  const float *src = nullptr;             // plain: the tensor itself; dz mode: dy at output resolution
+  const float *src_y = nullptr;           // dz mode: layer output (needed unless src_act is identity)
+  const unsigned char *src_idx = nullptr; // dz mode with src_pool == 2
+  int src_dz = 0;                         // 0 plain, 1 derive dz = unpool(dy) * act'(y)
+  int src_act = ACT_IDENTITY, src_pool = 1;
+  int N = 0, Cin = 0, Hin = 0, Win = 0;
+  // filters
+  const float *w = nullptr;
+  int w_flip = 0;                         // 0: w[Kout][Cin][R][S];  1: w[Cin][Kout][R][S] rotated by 180 degrees
+  int Kout = 0, R = 0, S = 0;
+  int pad_h = 0, pad_w = 0;              // implicit zero border of the logical source
+  // output, pre-pool extent Hout x Wout
+  int Hout = 0, Wout = 0;
+  const float *bias = nullptr;
+  int act = ACT_IDENTITY, pool = 1;
+  float *out = nullptr;
+  unsigned char *out_idx = nullptr;
+  const float *uniform = nullptr;         // optional Bernoulli epilogue (pool == 1): sample = 1[uniform < out]
+  float *sample = nullptr;
+};
+
+hipError_t launch_conv_engine(const ConvEngineArgs &a, hipStream_t stream);
+
+// ---------------------------------------------------------------------------------------
+// Filter gradient: stage 1 leaves per-wave partial sums in `partial`, stage 2
+// (launch_wgrad_reduce) adds them in a fixed order.
+// ---------------------------------------------------------------------------------------
+struct WgradArgs {
+  const float *x = nullptr;               // [N][C][H][W]
+  const float *dy = nullptr;              // gradient at output resolution [N][K][Ho/pool][Wo/pool]
+  const float *y = nullptr;
+  const unsigned char *idx = nullptr;
+  int act = ACT_IDENTITY, pool = 1;
+  int N = 0, C = 0, H = 0, W = 0, K = 0, R = 0, S = 0, pad = 0;
+  float *partial = nullptr;               // wgrad_partial_floats(...) floats
+};
+
+struct WgradPlan {
+  int MTF, NTT;        // 16-filter tiles, 16-tap tiles per channel chunk
+  int CC, nchunks;     // channels per chunk
+  int G;               // workgroups per chunk
+  int TH;              // tile height (8 or 16); width is 32
+  size_t lds_bytes;
+  size_t partial_floats; // dw partials followed by db partials
+  size_t db_offset;      // float offset of the db partials
+  int n_partials;        // per chunk: 4 * G
+};
+
+bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, WgradPlan *plan);
+hipError_t launch_wgrad(const WgradArgs &a, const WgradPlan &plan, hipStream_t stream);
+
+// dw = scale * (sum(pos partials) - sum(neg partials)); optional in-place theta += step * dw.
+struct WgradReduceArgs {
+  const float *pos = nullptr;  // partial buffer of the positive phase
+  const float *neg = nullptr;  // nullable: partial buffer of the negative phase (same plan)
+  float scale = 1.0f;
+  float *dw = nullptr;         // nullable
+  float *db = nullptr;         // nullable
+  float *w_update = nullptr;   // nullable: w_update += step * dw
+  float *b_update = nullptr;   // nullable
+  float step = 0.0f;
+  int C = 0, K = 0, R = 0, S = 0;
+};
+hipError_t launch_wgrad_reduce(const WgradReduceArgs &a, const WgradPlan &plan, hipStream_t stream);
+
+// ---------------------------------------------------------------------------------------
+// Dense layers: C[M][N] (+)= A * B with arbitrary element strides, fp32 MFMA.
+// ---------------------------------------------------------------------------------------
+struct GemmArgs {
+  int M = 0, N = 0, Kdim = 0;
+  const float *A = nullptr; long a_m = 0, a_k = 0;   // A(m,k) = A[m*a_m + k*a_k]
+  const float *B = nullptr; long b_k = 0, b_n = 0;   // B(k,n) = B[k*b_k + n*b_n]
+  // optional elementwise factor on A: A(m,k) *= act'(Aout[m*a_m+k*a_k]) (dense backward: dzh = dh * act'(h))
+  const float *A_out = nullptr; int a_act = ACT_IDENTITY;
+  float *Cout = nullptr; long c_m = 0, c_n = 0;      // nullable when only the update is wanted
+  const float *bias = nullptr;                       // [N], added before act
+  int act = ACT_IDENTITY;
+  float *update = nullptr; float step = 0.0f;        // nullable: update(m,n) += step * C(m,n), same strides as Cout
+  int split_k = 1;
+  float *partial = nullptr;                          // split_k * M * N floats when split_k > 1
+};
+int gemm_pick_split_k(int M, int N, int Kdim);
+hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream);
+
+// Column sums with the same optional act' factor: out[n] = sum_m A(m,n)*act'(Aout(m,n)); optional update.
+hipError_t launch_colsum(const float *A, const float *A_out, int a_act, int M, int N, float *out,
+                         float *update, float step, hipStream_t stream);
+
+// Softmax cross-entropy over rows; loss = mean; dlogits = (p - onehot)/B.  rowloss: B floats scratch.
+hipError_t launch_softmax_ce(const float *logits, const int *labels, int B, int classes, float *loss,
+                             float *dlogits, float *rowloss, hipStream_t stream);
+
+// CRBM visible statistics: dc[ch] = scale * sum(v0 - v1), mse = mean((v0-v1)^2); scratch: 2 * nblocks floats.
+size_t visible_stats_scratch_floats(int N, int C, int HW);
+hipError_t launch_visible_stats(const float *v0, const float *v1, int N, int C, int HW, float scale,
+                                float *dc, float *mse, float *c_update, float step, float *scratch,
+                                hipStream_t stream);
+
+hipError_t launch_copy(const float *src, float *dst, size_t count, hipStream_t stream);
+
+}  // namespace dllk

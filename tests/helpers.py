@@ -1,0 +1,50 @@
+"""Shared helpers of the parity tests: error metric and descriptor conversion."""
+import numpy as np
+
+from oracle import oracle as orc
+from paper_1804_04512_amd import workloads as wl
+
+ACT = {"identity": orc.ACT_IDENTITY, "sigmoid": orc.ACT_SIGMOID, "relu": orc.ACT_RELU}
+TOL_FWD = 1e-4    # forward outputs, loss, logits, probabilities
+TOL_GRAD = 5e-4   # gradients and parameter deltas
+
+
+def max_rel_err(got, ref) -> float:
+    """Per-tensor error: max |got - ref| / max(max |ref|, 1e-30)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    if ref.size == 0:
+        return 0.0
+    assert np.all(np.isfinite(got)), "non-finite values in the GPU result"
+    return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+def odesc(cs: wl.ConvSpec, pool=None, act=None):
+    return orc.conv_desc(cs.N, cs.C, cs.H, cs.W, cs.K, cs.R, cs.S, cs.pad,
+                         ACT[cs.act] if act is None else act, cs.pool if pool is None else pool)
+
+
+def onet(w: wl.CnnWorkload) -> orc.Net:
+    return orc.Net([odesc(c) for c in w.conv], [(d.in_, d.out, ACT[d.act]) for d in w.dense], w.classes)
+
+
+def check_pool_idx(gpu_idx, ora_idx, prepool_act, y, tol=2e-5):
+    """GPU and oracle may pick different window positions only where the two candidates are
+    (nearly) tied or where the pooled output is 0 (ReLU: no gradient flows either way).
+    prepool_act: oracle activations before pooling [N,K,Ho,Wo]; y: pooled oracle output."""
+    diff = gpu_idx != ora_idx
+    ndiff = int(diff.sum())
+    if ndiff == 0:
+        return 0
+    N, K, Ho, Wo = prepool_act.shape
+    win = prepool_act.reshape(N, K, Ho // 2, 2, Wo // 2, 2).transpose(0, 1, 2, 4, 3, 5).reshape(N, K, Ho // 2, Wo // 2, 4)
+    picked = np.take_along_axis(win, gpu_idx[..., None].astype(np.int64), axis=-1)[..., 0]
+    scale = max(float(np.abs(prepool_act).max()), 1e-30)
+    gap = np.abs(picked.astype(np.float64) - y.astype(np.float64))
+    bad = diff & (gap > tol * scale)
+    assert not bad.any(), f"{int(bad.sum())} pooling indices differ at non-ties (max gap {gap[diff].max():.3e}, scale {scale:.3e})"
+    # exact ties (e.g. a window of ReLU zeros) may go either way; near-ties must stay rare
+    near = int((diff & (gap > 0)).sum())
+    assert near <= max(4, int(1e-4 * diff.size)), f"too many near-tie pooling differences: {near} of {diff.size}"
+    return ndiff

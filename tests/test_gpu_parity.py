@@ -1,0 +1,244 @@
+"""GPU-vs-oracle parity of the conv trio, the CRBM CD-1 step and the CNN training step.
+
+Every test calls the HIP path through the C ABI on seeded inputs and compares it element by
+element with the CPU oracle.  Tolerances: 1e-4 (forward) and 5e-4 (gradients) on the
+per-tensor metric max|got-ref| / max|ref|; pooling indices and Bernoulli samples are
+integer decisions taken from fp32 values, so differences are allowed only at (near) ties and
+downstream tensors are compared with the oracle re-run on the GPU's decisions.
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import oracle as orc
+from paper_1804_04512_amd import binding as B
+from paper_1804_04512_amd import workloads as wl
+from paper_1804_04512_amd.workloads import ConvSpec
+
+from helpers import ACT, TOL_FWD, TOL_GRAD, check_pool_idx, max_rel_err, odesc, onet
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def rand_layer(cs: ConvSpec, seed: int):
+    r = np.random.default_rng(seed)
+    x = r.standard_normal(cs.x_shape).astype(np.float32)
+    w = (r.standard_normal(cs.w_shape) * np.sqrt(2.0 / (cs.C * cs.R * cs.S))).astype(np.float32)
+    b = (r.standard_normal((cs.K,)) * 0.1).astype(np.float32)
+    dy = r.standard_normal(cs.y_shape).astype(np.float32)
+    return x, w, b, dy
+
+
+def gpu_trio(cs: ConvSpec, x, w, b, dy, y_in=None, idx_in=None):
+    """Runs fwd, then bwd and wgrad on (y_in, idx_in) when given, else on the GPU's own."""
+    xd, wd, bd, dyd = dev(x), dev(w), dev(b), dev(dy)
+    y = torch.full(cs.y_shape, float("nan"), device="cuda")
+    idx = torch.full(cs.y_shape, 255, dtype=torch.uint8, device="cuda") if cs.pool == 2 else None
+    B.dll_conv_valid_fwd(cs, xd, wd, bd, y, idx)
+    yb = y if y_in is None else dev(y_in)
+    ib = idx if idx_in is None else dev(idx_in)
+    dx = torch.full(cs.x_shape, float("nan"), device="cuda")
+    B.dll_conv_full_bwd(cs, dyd, yb, ib, wd, dx)
+    ws = B.workspace(B.dll_conv_workspace_bytes(cs))
+    dw = torch.full(cs.w_shape, float("nan"), device="cuda")
+    db = torch.full((cs.K,), float("nan"), device="cuda")
+    B.dll_conv_valid_wgrad(cs, xd, dyd, yb, ib, dw, db, ws)
+    return host(y), (host(idx) if idx is not None else None), host(dx), host(dw), host(db)
+
+
+def check_trio(cs: ConvSpec, x, w, b, dy):
+    d = odesc(cs)
+    y_o, idx_o = orc.conv_valid_fwd(d, x, w, b)
+    y_g, idx_g, _, _, _ = gpu_trio(cs, x, w, b, dy)
+    assert max_rel_err(y_g, y_o) <= TOL_FWD
+    if cs.pool == 2:
+        pre, _ = orc.conv_valid_fwd(odesc(cs, pool=1), x, w, b)
+        check_pool_idx(idx_g, idx_o, pre, y_o)
+    # backward ops on identical inputs (the oracle's y and the GPU's own index decisions)
+    use_idx = idx_g if cs.pool == 2 else None
+    _, _, dx_g, dw_g, db_g = gpu_trio(cs, x, w, b, dy, y_in=y_o, idx_in=use_idx)
+    dx_o = orc.conv_full_bwd(d, dy, y_o, use_idx, w)
+    dw_o, db_o = orc.conv_valid_wgrad(d, x, dy, y_o, use_idx)
+    assert max_rel_err(dx_g, dx_o) <= TOL_GRAD
+    assert max_rel_err(dw_g, dw_o) <= TOL_GRAD
+    assert max_rel_err(db_g, db_o) <= TOL_GRAD
+
+
+CASES = [
+    # N, C, H, W, K, R, S, pad, act, pool
+    ConvSpec(1, 1, 3, 3, 1, 2, 2, 0, "identity", 1),          # smallest meaningful layer
+    ConvSpec(2, 3, 12, 10, 5, 3, 3, 1, "relu", 2),            # ragged: everything below one tile
+    ConvSpec(2, 1, 28, 28, 8, 5, 5, 0, "sigmoid", 1),         # MNIST-like, width 24 overhangs the 32-wide tile
+    ConvSpec(3, 8, 12, 12, 8, 5, 5, 0, "relu", 2),            # 8x8 pre-pool map: shallow-tile instance
+    ConvSpec(2, 3, 70, 75, 12, 5, 5, 2, "relu", 1),           # several tiles + ragged tail both ways, odd width
+    ConvSpec(2, 12, 36, 68, 24, 3, 3, 1, "relu", 2),          # two N-tiles, 3 tiles wide with a tail
+    ConvSpec(2, 1, 28, 28, 40, 9, 9, 0, "sigmoid", 1),        # CRBM shape: three N-tiles, single channel
+    ConvSpec(1, 20, 20, 34, 50, 3, 3, 1, "sigmoid", 2),       # channel chunks 16+4, filter groups 48+2
+    ConvSpec(2, 16, 40, 40, 16, 3, 3, 1, "relu", 2),          # config-5 style block
+    ConvSpec(1, 32, 32, 32, 32, 3, 3, 1, "relu", 2),          # config-5 conv4 shape
+    ConvSpec(2, 2, 9, 14, 3, 2, 4, 0, "identity", 1),         # non-square filter
+    ConvSpec(2, 4, 11, 9, 6, 1, 1, 0, "relu", 1),             # 1x1 filter, odd map
+    ConvSpec(1, 40, 20, 20, 1, 9, 9, 0, "identity", 1),       # single filter, deep contraction
+]
+
+
+@pytest.mark.parametrize("cs", CASES, ids=lambda c: f"N{c.N}C{c.C}_{c.H}x{c.W}_K{c.K}_{c.R}x{c.S}p{c.pad}_{c.act}_pool{c.pool}")
+def test_trio_matches_oracle(cs):
+    x, w, b, dy = rand_layer(cs, 1000 + cs.C * 7 + cs.K)
+    check_trio(cs, x, w, b, dy)
+
+
+def test_config1_single_conv_layer():
+    w1 = wl.config1()
+    check_trio(w1.conv, w1.x, w1.w, w1.bias, w1.dy)
+
+
+def test_fwd_without_bias_and_shift_identity():
+    """A delta filter turns the backward-data pass into a zero-filled shift (exact in fp32)."""
+    cs = ConvSpec(1, 1, 12, 37, 1, 3, 3, 0, "identity", 1)
+    r = np.random.default_rng(5)
+    dz = r.standard_normal(cs.y_shape).astype(np.float32)
+    w = np.zeros(cs.w_shape, np.float32)
+    w[0, 0, 1, 2] = 1.0
+    dx = torch.empty(cs.x_shape, device="cuda")
+    B.dll_conv_full_bwd(cs, dev(dz), None, None, dev(w), dx)
+    ref = np.zeros(cs.x_shape, np.float32)
+    ref[0, 0, 1:11, 2:37] = dz[0, 0]
+    np.testing.assert_array_equal(host(dx), ref)
+    x = r.standard_normal(cs.x_shape).astype(np.float32)
+    y = torch.empty(cs.y_shape, device="cuda")
+    B.dll_conv_valid_fwd(cs, dev(x), dev(w), None, y)
+    np.testing.assert_array_equal(host(y)[0, 0], x[0, 0, 1:11, 2:37])
+
+
+def test_wgrad_is_bit_reproducible():
+    cs = ConvSpec(4, 16, 40, 40, 16, 3, 3, 1, "relu", 2)
+    x, w, b, dy = rand_layer(cs, 77)
+    a = gpu_trio(cs, x, w, b, dy)
+    c = gpu_trio(cs, x, w, b, dy)
+    np.testing.assert_array_equal(a[3], c[3])
+    np.testing.assert_array_equal(a[4], c[4])
+
+
+# ---------------------------------------------------------------- CRBM CD-1
+
+def run_crbm_gpu(w3, lr, h0_sample_in=None):
+    cs = w3.conv
+    W, b, c = dev(w3.W), dev(w3.b), dev(w3.c)
+    hs = (cs.N, cs.K, cs.Ho, cs.Wo)
+    out = dict(dW=torch.empty(cs.w_shape, device="cuda"), db=torch.empty(cs.K, device="cuda"),
+               dc=torch.empty(cs.C, device="cuda"), h0_prob=torch.empty(hs, device="cuda"),
+               h0_sample=torch.empty(hs, device="cuda"), v1=torch.empty(cs.x_shape, device="cuda"),
+               h1_prob=torch.empty(hs, device="cuda"), recon_mse=torch.empty(1, device="cuda"))
+    ws = B.workspace(B.dll_crbm_workspace_bytes(cs))
+    B.dll_crbm_cd1_step(cs, dev(w3.v0), W, b, c, dev(w3.u), None if h0_sample_in is None else dev(h0_sample_in),
+                        lr, ws=ws, **out)
+    res = {k: host(v) for k, v in out.items()}
+    res.update(W=host(W), b=host(b), c=host(c))
+    return res
+
+
+@pytest.mark.parametrize("batch", [5, 64])
+def test_config3_crbm_cd1(batch):
+    w3 = wl.config3(batch)
+    cs = w3.conv
+    g = run_crbm_gpu(w3, w3.lr)
+    d = odesc(cs)
+    # (i) hidden probabilities; (ii) sample flips only where u is within rounding of p
+    free = orc.crbm_cd1_step(d, w3.v0, w3.W.copy(), w3.b.copy(), w3.c.copy(), w3.u)
+    assert max_rel_err(g["h0_prob"], free.h0_prob) <= TOL_FWD
+    flips = g["h0_sample"] != free.h0_sample
+    assert flips.sum() <= max(2, 1e-5 * flips.size)
+    assert np.all(np.abs(w3.u[flips] - free.h0_prob[flips]) <= 1e-6)
+    assert set(np.unique(g["h0_sample"])) <= {0.0, 1.0}
+    # (iii) everything downstream against the oracle driven by the GPU's samples
+    Wn, bn, cn = w3.W.copy(), w3.b.copy(), w3.c.copy()
+    o = orc.crbm_cd1_step(d, w3.v0, Wn, bn, cn, None, h0_sample_in=g["h0_sample"], lr=w3.lr)
+    assert max_rel_err(g["v1"], o.v1) <= TOL_FWD
+    assert max_rel_err(g["h1_prob"], o.h1_prob) <= TOL_FWD
+    assert max_rel_err(g["recon_mse"], np.array([o.recon_mse], np.float32)) <= TOL_FWD
+    assert max_rel_err(g["dW"], o.dW) <= TOL_GRAD
+    assert max_rel_err(g["db"], o.db) <= TOL_GRAD
+    assert max_rel_err(g["dc"], o.dc) <= TOL_GRAD
+    assert max_rel_err(g["W"] - w3.W, Wn - w3.W) <= TOL_GRAD
+    assert max_rel_err(g["b"] - w3.b, bn - w3.b) <= TOL_GRAD
+    assert max_rel_err(g["c"] - w3.c, cn - w3.c) <= TOL_GRAD
+
+
+def test_crbm_sample_override_and_lr_zero():
+    w3 = wl.config3(3)
+    r = np.random.default_rng(9)
+    forced = (r.random((3, 40, 20, 20)) < 0.5).astype(np.float32)
+    g = run_crbm_gpu(w3, 0.0, h0_sample_in=forced)
+    np.testing.assert_array_equal(g["h0_sample"], forced)
+    np.testing.assert_array_equal(g["W"], w3.W)       # lr = 0: parameters untouched
+    o = orc.crbm_cd1_step(odesc(w3.conv), w3.v0, w3.W.copy(), w3.b.copy(), w3.c.copy(), None, h0_sample_in=forced)
+    assert max_rel_err(g["v1"], o.v1) <= TOL_FWD
+    assert max_rel_err(g["dW"], o.dW) <= TOL_GRAD
+
+
+# ---------------------------------------------------------------- CNN training step
+
+def run_cnn_gpu(w: wl.CnnWorkload, lr, want_grads=True):
+    net = B.net_desc(w.conv, w.dense, w.classes)
+    params = [dev(p) for p in w.params]
+    grads = [torch.full_like(p, float("nan")) for p in params] if want_grads else None
+    idx = [torch.full(c.y_shape, 255, dtype=torch.uint8, device="cuda") for c in w.conv]
+    loss = torch.full((1,), float("nan"), device="cuda")
+    logits = torch.full((w.batch, w.classes), float("nan"), device="cuda")
+    ws = B.workspace(B.dll_cnn_workspace_bytes(net))
+    B.dll_cnn_train_step(net, params, grads, dev(w.x), dev(w.labels), lr, loss, logits, idx, ws)
+    return dict(loss=host(loss)[0], logits=host(logits), grads=[host(g) for g in grads] if grads else None,
+                idx=[host(i) for i in idx], params=[host(p) for p in params])
+
+
+def check_cnn(w: wl.CnnWorkload):
+    g = run_cnn_gpu(w, w.lr)
+    net = onet(w)
+    # the oracle's own forward, layer by layer, to judge the pooling decisions
+    a = w.x
+    for l, c in enumerate(w.conv):
+        pre, _ = orc.conv_valid_fwd(odesc(c, pool=1), a, w.params[2 * l], w.params[2 * l + 1])
+        a, idx_o = orc.conv_valid_fwd(odesc(c), a, w.params[2 * l], w.params[2 * l + 1])
+        check_pool_idx(g["idx"][l], idx_o, pre, a)
+    new = w.clone_params()
+    o = orc.cnn_train_step(net, new, w.x, w.labels, w.lr, pool_idx_in=g["idx"])
+    assert max_rel_err(np.array([g["loss"]]), np.array([o.loss])) <= TOL_FWD
+    assert max_rel_err(g["logits"], o.logits) <= TOL_FWD
+    for p, (gg, og) in enumerate(zip(g["grads"], o.grads)):
+        assert max_rel_err(gg, og) <= TOL_GRAD, f"gradient of parameter {p}"
+    for p, (gp, op, old) in enumerate(zip(g["params"], new, w.params)):
+        assert max_rel_err(gp - old, op - old) <= TOL_GRAD, f"update of parameter {p}"
+    return g, o
+
+
+def test_config2_small_cnn_step():
+    check_cnn(wl.config2())
+
+
+def test_config4_color_cnn_step():
+    check_cnn(wl.config4())
+
+
+def test_config5_architecture_reduced_size():
+    """Config 5's architecture at a size the oracle finishes in seconds (64x64 images)."""
+    check_cnn(wl.config5(batch=6, image=64, hidden=256, classes=100))
+
+
+def test_cnn_lr_zero_and_no_grads():
+    w = wl.config2(batch=10)
+    g = run_cnn_gpu(w, 0.0, want_grads=False)
+    for a, b in zip(g["params"], w.params):
+        np.testing.assert_array_equal(a, b)
+    o = orc.cnn_train_step(onet(w), w.clone_params(), w.x, w.labels, 0.0)
+    assert max_rel_err(np.array([g["loss"]]), np.array([o.loss])) <= TOL_FWD
