@@ -1,0 +1,216 @@
+#!/usr/bin/env python3
+"""Benchmark of the conv hot path on one MI355X.
+
+A step is one call of dll_cnn_train_step (forward, loss, backward, SGD update) on the
+large-image CNN workload (config 5: batch 128 of 3x256x256, four conv+ReLU+pool blocks,
+dense 2048, dense 1000), inputs and parameters resident in HBM.  Prints ONE JSON line.
+
+  value      GFLOP/s of the whole step (exact multiply-adds x 2: padding zeros, wasted
+             MFMA lanes and split-K re-reads are not counted)
+  roofline   the conv kernel with the largest share of the step, timed launch by launch
+             with HIP events on the launch stream, against the fp32 MFMA peak
+  cpu_baseline  the CPU oracle timed on this machine's host cores on a bounded sample
+
+Other workloads (--config 1..4) exist for inspection; the default line is config 5.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3   # MI355X published dense fp32 matrix peak
+METRIC = "conv GFLOP/s + images/s per fwd+bwd step; % of fp32 MFMA peak"
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--batch", type=int, default=None, help="override the batch size (inspection only)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--cpu-batch", type=int, default=32)
+    return ap.parse_args()
+
+
+def event_time_ms(fn, iters, warm=2):
+    """Average duration of fn() in ms from HIP events on torch's current stream (the launch stream)."""
+    import torch
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    t = []
+    for _ in range(iters):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        b.synchronize()
+        t.append(a.elapsed_time(b))
+    return float(np.mean(t)), float(np.min(t))
+
+
+def engine_kernel_name(kout: int, hout: int) -> str:
+    nt = 1 if kout <= 16 else (2 if kout <= 32 else 3)
+    return f"conv_engine_kernel<{nt},{1 if hout <= 8 else 2}>"
+
+
+def conv_pass_table(B, wl_cnn, dev_params, x_dev, iters):
+    """Times every convolution pass of the step as its own launch: one API call = one kernel
+    (forward, backward-data) or the filter-gradient kernel + its small reduction."""
+    import torch
+    acts, idxs = [x_dev], []
+    for l, cs in enumerate(wl_cnn.conv):
+        y = torch.empty(cs.y_shape, device="cuda")
+        idx = torch.empty(cs.y_shape, dtype=torch.uint8, device="cuda")
+        B.dll_conv_valid_fwd(cs, acts[l], dev_params[2 * l], dev_params[2 * l + 1], y, idx)
+        acts.append(y)
+        idxs.append(idx)
+    table = []
+    for l, cs in enumerate(wl_cnn.conv):
+        xin, y, idx = acts[l], acts[l + 1], idxs[l]
+        w, b = dev_params[2 * l], dev_params[2 * l + 1]
+        dy = torch.randn(cs.y_shape, device="cuda")
+        flop = 2 * cs.macs_exact()
+        y2, idx2 = torch.empty_like(y), torch.empty_like(idx)
+        ms, _ = event_time_ms(lambda: B.dll_conv_valid_fwd(cs, xin, w, b, y2, idx2), iters)
+        table.append(dict(layer=l + 1, op="fwd", kernel=engine_kernel_name(cs.K, cs.Ho), ms=ms, flop=flop))
+        if l > 0:
+            dx = torch.empty(cs.x_shape, device="cuda")
+            ms, _ = event_time_ms(lambda: B.dll_conv_full_bwd(cs, dy, y, idx, w, dx), iters)
+            table.append(dict(layer=l + 1, op="bwd_data", kernel=engine_kernel_name(cs.C, cs.H), ms=ms, flop=flop))
+        ws = B.workspace(B.dll_conv_workspace_bytes(cs))
+        dw, db = torch.empty_like(w), torch.empty_like(b)
+        ms, _ = event_time_ms(lambda: B.dll_conv_valid_wgrad(cs, xin, dy, y, idx, dw, db, ws), iters)
+        table.append(dict(layer=l + 1, op="wgrad", kernel="wgrad_kernel(+reduce)", ms=ms, flop=flop))
+        del dy
+    return table
+
+
+def cpu_baseline(cfg: int, cpu_batch: int):
+    from oracle import oracle as orc
+    from paper_1804_04512_amd import workloads as wl
+    act = {"identity": 0, "sigmoid": 1, "relu": 2}
+    w = wl.ALL[cfg](cpu_batch)
+    t0 = time.perf_counter()
+    if isinstance(w, wl.CnnWorkload):
+        net = orc.Net([orc.conv_desc(c.N, c.C, c.H, c.W, c.K, c.R, c.S, c.pad, act[c.act], c.pool) for c in w.conv],
+                      [(d.in_, d.out, act[d.act]) for d in w.dense], w.classes)
+        orc.cnn_train_step(net, w.clone_params(), w.x, w.labels, w.lr)
+        n = w.batch
+    elif isinstance(w, wl.CrbmWorkload):
+        c = w.conv
+        orc.crbm_cd1_step(orc.conv_desc(c.N, c.C, c.H, c.W, c.K, c.R, c.S), w.v0, w.W.copy(), w.b.copy(), w.c.copy(), w.u, lr=w.lr)
+        n = c.N
+    else:
+        c = w.conv
+        d = orc.conv_desc(c.N, c.C, c.H, c.W, c.K, c.R, c.S, c.pad, act[c.act], c.pool)
+        y, idx = orc.conv_valid_fwd(d, w.x, w.w, w.bias)
+        orc.conv_full_bwd(d, w.dy, y, idx, w.w)
+        orc.conv_valid_wgrad(d, w.x, w.dy, y, idx)
+        n = c.N
+    dt = time.perf_counter() - t0
+    return dict(value=w.flop() / dt / 1e9, unit="GFLOP/s", images_per_s=n / dt, seconds=dt, cores=orc.max_threads(),
+                kind="oracle", sample=f"one step of config {cfg} at batch {n} (same layer shapes), fp64 accumulation, plain loops")
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        return 2
+    import torch
+    from paper_1804_04512_amd import binding as B
+    from paper_1804_04512_amd import workloads as wl
+
+    B.lib()  # fail loudly when the HIP library is missing
+    torch.cuda.set_device(0)
+    cfg = args.config
+    w = wl.ALL[cfg](args.batch) if args.batch else wl.ALL[cfg]()
+    dev = lambda a: torch.from_numpy(a).cuda()
+
+    if isinstance(w, wl.CnnWorkload):
+        net = B.net_desc(w.conv, w.dense, w.classes)
+        params = [dev(p) for p in w.params]
+        x, labels = dev(w.x), dev(w.labels)
+        loss = torch.zeros(1, device="cuda")
+        ws = B.workspace(B.dll_cnn_workspace_bytes(net))
+        step = lambda: B.dll_cnn_train_step(net, params, None, x, labels, w.lr, loss, None, None, ws)
+        batch = w.batch
+    elif isinstance(w, wl.CrbmWorkload):
+        cs = w.conv
+        W, b, c = dev(w.W), dev(w.b), dev(w.c)
+        v0, u = dev(w.v0), dev(w.u)
+        dW, db, dc = torch.empty_like(W), torch.empty_like(b), torch.empty_like(c)
+        ws = B.workspace(B.dll_crbm_workspace_bytes(cs))
+        step = lambda: B.dll_crbm_cd1_step(cs, v0, W, b, c, u, None, w.lr, dW, db, dc, ws=ws)
+        batch = cs.N
+    else:
+        cs = w.conv
+        x, wt, bias, dy = dev(w.x), dev(w.w), dev(w.bias), dev(w.dy)
+        y, dx = torch.empty(cs.y_shape, device="cuda"), torch.empty(cs.x_shape, device="cuda")
+        dw, db = torch.empty_like(wt), torch.empty_like(bias)
+        ws = B.workspace(B.dll_conv_workspace_bytes(cs))
+
+        def step():
+            B.dll_conv_valid_fwd(cs, x, wt, bias, y, None)
+            B.dll_conv_full_bwd(cs, dy, y, None, wt, dx)
+            B.dll_conv_valid_wgrad(cs, x, dy, y, None, dw, db, ws)
+        batch = cs.N
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    flop = w.flop()
+    gflops = flop / (ms_per_step * 1e-3) / 1e9
+
+    out = {
+        "metric": METRIC, "value": gflops, "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "batch": batch, "flop_per_step": flop},
+        "images_per_s": batch / (ms_per_step * 1e-3),
+        "pct_fp32_mfma_peak": 100.0 * gflops / (PEAK_FP32_MFMA_TFLOPS * 1e3),
+    }
+    if isinstance(w, wl.CnnWorkload):
+        out["config"]["conv_flop_per_step"] = w.conv_flop()
+        table = conv_pass_table(B, w, params, x, max(5, min(args.steps, 20)))
+        conv_ms = sum(r["ms"] for r in table)
+        out["conv_passes"] = [dict(layer=r["layer"], op=r["op"], ms=round(r["ms"], 4),
+                                   tflops=round(r["flop"] / r["ms"] / 1e9, 2)) for r in table]
+        out["conv_gflops"] = sum(r["flop"] for r in table) / conv_ms / 1e6
+        # dominant kernel: group single-kernel launches by kernel name, take the largest total time
+        groups = {}
+        for r in table:
+            gname = r["kernel"] if r["op"] != "wgrad" else f"wgrad layer {r['layer']}"
+            gr = groups.setdefault(gname, dict(ms=0.0, flop=0, n=0))
+            gr["ms"] += r["ms"]; gr["flop"] += r["flop"]; gr["n"] += 1
+        name, gr = max(groups.items(), key=lambda kv: kv[1]["ms"])
+        achieved = gr["flop"] / gr["ms"] / 1e9   # TFLOP/s
+        out["roofline"] = {"bound": "mfma", "kernel": name, "launches_per_step": gr["n"],
+                           "avg_launch_ms": gr["ms"] / gr["n"], "flop_per_launch": gr["flop"] / gr["n"],
+                           "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                           "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None}
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_batch if cfg == 5 else batch)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
