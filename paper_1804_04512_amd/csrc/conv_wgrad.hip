@@ -4,12 +4,15 @@
 //
 // The contraction runs over pixels, so pixels sit on the MFMA K axis (4 neighbouring
 // columns per instruction), filters on M and the (channel, tap) pairs of a channel chunk on
-// N.  A workgroup walks over image tiles of 32 x TH output pixels: it stages the halo tile of
-// x and the tile of dz = unpool(dy) * act'(y) (formed on the fly, never stored in HBM) in LDS
-// and keeps its K x taps partial sums in accumulator registers across all its tiles.  Every
-// wavefront finally writes its partial block; a second kernel adds the blocks in a fixed
-// order (no float atomics: the result is bit-identical from run to run) and can apply the
-// parameter update in the same pass.
+// N.  A persistent workgroup walks over image tiles of 32 x 8 output pixels: it stages the
+// halo tile of x and the tile of dz = unpool(dy) * act'(y) (formed on the fly from the
+// pooled-resolution tensors, never stored in HBM) in LDS and keeps its K x taps partial sums
+// in accumulator registers across all its tiles.  In the fast path the next tile's global
+// loads (16-byte vectors) are issued into registers before the MFMA loop of the current
+// tile, so HBM latency hides behind the matrix pipe.  The four wavefronts add their
+// accumulators through LDS in a fixed order and write one partial block per workgroup; a
+// second kernel adds the blocks in a fixed order (no float atomics: results are
+// bit-identical from run to run) and can apply the parameter update in the same pass.
 #include "dll_internal.h"
 
 namespace dllk {
@@ -20,18 +23,29 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kTileW = 32;
+constexpr int TH = 8;
+constexpr int PSZ = TH * kTileW + 2;   // dz plane stride in LDS: conflict-free A-operand reads
+constexpr int NXI = 5;                 // prefetch registers: float4 of tile interior per thread
+constexpr int NXH = 2;                 // prefetch registers: halo scalars per thread
 
 struct WgradParams {
   WgradArgs a;
   int Ho, Wo;
   int CC, nchunks, G;
   int rows, cols, RS, PS;  // x halo tile in LDS
-  int PSZ;                 // dz plane stride in LDS (row stride is 32)
+  int shift;               // LDS column of the tile's first column (keeps the interior 8-byte aligned)
+  int inv_rows;            // ceil(65536 / rows): exact division of small line numbers
   int tiles_x, tiles_y, items;
   int kgroups;
   long db_offset;
   long group_stride;       // floats between filter groups in the dw partial area
 };
+
+__device__ __forceinline__ float act_deriv(int act, float out) {
+  if (act == ACT_SIGMOID) return out * (1.0f - out);
+  if (act == ACT_RELU) return out > 0.0f ? 1.0f : 0.0f;
+  return 1.0f;
+}
 
 __device__ __forceinline__ float dz_value(const WgradArgs &a, int Ho, int Wo, int n, int k, int i, int j) {
   int o;
@@ -42,28 +56,27 @@ __device__ __forceinline__ float dz_value(const WgradArgs &a, int Ho, int Wo, in
     o = ((n * a.K + k) * Ho + i) * Wo + j;
   }
   float g = a.dy[o];
-  if (a.act == ACT_SIGMOID) {
-    const float v = a.y[o];
-    g *= v * (1.0f - v);
-  } else if (a.act == ACT_RELU) {
-    if (!(a.y[o] > 0.0f)) g = 0.0f;
-  }
+  if (a.act != ACT_IDENTITY) g *= act_deriv(a.act, a.y[o]);
   return g;
 }
 
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-  return v;
-}
+// Registers that carry one tile from global memory to LDS (fast path).
+template <int MTF, int POOL>
+struct TileRegs {
+  static constexpr int DZR = POOL == 2 ? MTF : 4 * MTF;   // staging rounds over the filter planes
+  float4 xi[NXI];
+  float xh[NXH];
+  float4 dyv[DZR], yv[DZR];
+  uchar4 iv[DZR];
+};
 
 // grid: x = G * nchunks, y = filter groups of MTF*16
-template <int MTF, int NTT, int TH>
+template <int MTF, int NTT, int POOL, bool FAST>
 __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
   extern __shared__ float lds[];
   const WgradArgs &a = p.a;
   float *xs = lds;                 // [CC][PS]
-  float *dzs = xs + p.CC * p.PS;   // [MTF*16 (clipped to K)][PSZ]
+  float *dzs = xs + p.CC * p.PS;   // [filters of the group][PSZ]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i16 = lane & 15, kq = lane >> 4;
@@ -72,18 +85,18 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
   const int kcount = min(MTF * 16, a.K - k0);   // filters this group really has
   const int c0 = chunk * p.CC;
   const int RSf = a.R * a.S;
-  constexpr int PLANE = TH * kTileW;
-  constexpr int ITS_PER_K = PLANE / kThreads;   // staging iterations per filter plane
+  const int lines = p.CC * p.rows;
   constexpr int RW = TH / 4;                    // rows per wave
+  constexpr int DZR = TileRegs<MTF, POOL>::DZR;
 
   floatx4 acc[MTF][NTT];
 #pragma unroll
   for (int mf = 0; mf < MTF; ++mf)
 #pragma unroll
     for (int nt = 0; nt < NTT; ++nt) acc[mf][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
-  float dbacc[MTF * 16];
+  float dbacc[FAST ? DZR : MTF * 16];
 #pragma unroll
-  for (int k = 0; k < MTF * 16; ++k) dbacc[k] = 0.0f;
+  for (int k = 0; k < (FAST ? DZR : MTF * 16); ++k) dbacc[k] = 0.0f;
 
   // B operand: lane's tap of N-tile nt -> offset inside the halo tile
   int tapoff[NTT];
@@ -92,53 +105,174 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
     const int tap = nt * 16 + i16;
     const int cl = tap / RSf, rs = tap - cl * RSf;
     const int r = rs / a.S, s = rs - r * a.S;
-    tapoff[nt] = (cl < p.CC) ? cl * p.PS + r * p.RS + s : 0;
+    tapoff[nt] = (cl < p.CC) ? cl * p.PS + r * p.RS + s + p.shift : 0;
   }
   // A operand: lane's filter plane of M-tile mf (clipped: surplus rows are never stored)
   int fplane[MTF];
 #pragma unroll
-  for (int mf = 0; mf < MTF; ++mf) fplane[mf] = min(mf * 16 + i16, kcount - 1) * p.PSZ;
+  for (int mf = 0; mf < MTF; ++mf) fplane[mf] = min(mf * 16 + i16, kcount - 1) * PSZ;
 
-  for (int item = gidx; item < p.items; item += p.G) {
+  TileRegs<MTF, POOL> tr;
+
+  // ---- fast path, step 1: global -> registers for one tile
+  auto load_tile = [&](int item) {
     const int tx = item % p.tiles_x;
     const int ty = (item / p.tiles_x) % p.tiles_y;
     const int n = item / (p.tiles_x * p.tiles_y);
     const int oy0 = ty * TH, ox0 = tx * kTileW;
-    __syncthreads();
-    // ---- dz tile [kcount][TH][32]
 #pragma unroll
-    for (int it = 0; it < MTF * 16 * ITS_PER_K; ++it) {
-      const int k = it / ITS_PER_K;   // compile-time
+    for (int it = 0; it < NXI; ++it) {
+      const int e = tid + it * kThreads;
+      const int j = e & 7, line = e >> 3;
+      const int cl = (line * p.inv_rows) >> 16, row = line - cl * p.rows;
+      const int gi = oy0 - a.pad + row, gj = ox0 + 4 * j, ci = c0 + cl;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (line < lines && ci < a.C && gi >= 0 && gi < a.H && gj < a.W)
+        v = *reinterpret_cast<const float4 *>(a.x + ((long)(n * a.C + ci) * a.H + gi) * a.W + gj);
+      tr.xi[it] = v;
+    }
+    const int nh = a.S - 1;
+#pragma unroll
+    for (int it = 0; it < NXH; ++it) {
+      const int e = tid + it * kThreads;
+      float v = 0.0f;
+      if (nh > 0) {
+        const int line = e / nh, hc = e - line * nh;
+        const int cl = (line * p.inv_rows) >> 16, row = line - cl * p.rows;
+        const int gi = oy0 - a.pad + row, ci = c0 + cl;
+        const int gj = hc < a.pad ? ox0 - a.pad + hc : ox0 + kTileW + (hc - a.pad);
+        if (line < lines && ci < a.C && gi >= 0 && gi < a.H && gj >= 0 && gj < a.W)
+          v = a.x[((long)(n * a.C + ci) * a.H + gi) * a.W + gj];
+      }
+      tr.xh[it] = v;
+    }
+#pragma unroll
+    for (int rd = 0; rd < DZR; ++rd) {
+      float4 dv = make_float4(0.f, 0.f, 0.f, 0.f), yv = dv;
+      uchar4 iv = make_uchar4(255, 255, 255, 255);
+      if (POOL == 2) {
+        const int k = rd * 16 + (tid >> 4), q = tid & 15;
+        const int u = (oy0 >> 1) + (q >> 2), v0 = (ox0 >> 1) + (q & 3) * 4;
+        const int Hp = p.Ho >> 1, Wp = p.Wo >> 1;
+        if (k < kcount && u < Hp && v0 < Wp) {
+          const long o = ((long)(n * a.K + k0 + k) * Hp + u) * Wp + v0;
+          dv = *reinterpret_cast<const float4 *>(a.dy + o);
+          if (a.act != ACT_IDENTITY) yv = *reinterpret_cast<const float4 *>(a.y + o);
+          iv = *reinterpret_cast<const uchar4 *>(a.idx + o);
+        }
+      } else {
+        const int k = rd * 4 + (tid >> 6), q = tid & 63;
+        const int gi = oy0 + (q >> 3), gj = ox0 + (q & 7) * 4;
+        if (k < kcount && gi < p.Ho && gj < p.Wo) {
+          const long o = ((long)(n * a.K + k0 + k) * p.Ho + gi) * p.Wo + gj;
+          dv = *reinterpret_cast<const float4 *>(a.dy + o);
+          if (a.act != ACT_IDENTITY) yv = *reinterpret_cast<const float4 *>(a.y + o);
+        }
+      }
+      tr.dyv[rd] = dv; tr.yv[rd] = yv; tr.iv[rd] = iv;
+    }
+  };
+
+  // ---- fast path, step 2: registers -> LDS (dz is formed here)
+  auto store_tile = [&]() {
+#pragma unroll
+    for (int it = 0; it < NXI; ++it) {
+      const int e = tid + it * kThreads;
+      const int j = e & 7, line = e >> 3;
+      if (line < lines) {
+        const int cl = (line * p.inv_rows) >> 16, row = line - cl * p.rows;
+        float2 *d = reinterpret_cast<float2 *>(xs + cl * p.PS + row * p.RS + a.pad + p.shift + 4 * j);
+        d[0] = make_float2(tr.xi[it].x, tr.xi[it].y);
+        d[1] = make_float2(tr.xi[it].z, tr.xi[it].w);
+      }
+    }
+    const int nh = a.S - 1;
+    if (nh > 0) {
+#pragma unroll
+      for (int it = 0; it < NXH; ++it) {
+        const int e = tid + it * kThreads;
+        const int line = e / nh, hc = e - line * nh;
+        if (line < lines) {
+          const int cl = (line * p.inv_rows) >> 16, row = line - cl * p.rows;
+          const int col = hc < a.pad ? hc : kTileW + hc;
+          xs[cl * p.PS + row * p.RS + col + p.shift] = tr.xh[it];
+        }
+      }
+    }
+#pragma unroll
+    for (int rd = 0; rd < DZR; ++rd) {
+      const float gv[4] = {tr.dyv[rd].x, tr.dyv[rd].y, tr.dyv[rd].z, tr.dyv[rd].w};
+      const float ov[4] = {tr.yv[rd].x, tr.yv[rd].y, tr.yv[rd].z, tr.yv[rd].w};
+      float g[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) g[e] = a.act != ACT_IDENTITY ? gv[e] * act_deriv(a.act, ov[e]) : gv[e];
+      if (POOL == 2) {
+        const int k = rd * 16 + (tid >> 4), q = tid & 15;
+        if (k < kcount) {
+          const unsigned char pos[4] = {tr.iv[rd].x, tr.iv[rd].y, tr.iv[rd].z, tr.iv[rd].w};
+          float *d = dzs + k * PSZ + (2 * (q >> 2)) * kTileW + 8 * (q & 3);
+#pragma unroll
+          for (int wa = 0; wa < 2; ++wa)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              *reinterpret_cast<float2 *>(d + wa * kTileW + 2 * e) =
+                  make_float2(pos[e] == 2 * wa ? g[e] : 0.0f, pos[e] == 2 * wa + 1 ? g[e] : 0.0f);
+          dbacc[rd] += ((pos[0] < 4 ? g[0] : 0.f) + (pos[1] < 4 ? g[1] : 0.f)) +
+                       ((pos[2] < 4 ? g[2] : 0.f) + (pos[3] < 4 ? g[3] : 0.f));
+        }
+      } else {
+        const int k = rd * 4 + (tid >> 6), q = tid & 63;
+        if (k < kcount) {
+          float2 *d = reinterpret_cast<float2 *>(dzs + k * PSZ + (q >> 3) * kTileW + (q & 7) * 4);
+          d[0] = make_float2(g[0], g[1]);
+          d[1] = make_float2(g[2], g[3]);
+          dbacc[rd] += (g[0] + g[1]) + (g[2] + g[3]);
+        }
+      }
+    }
+  };
+
+  // ---- generic path: element-wise staging straight into LDS (any shape, any alignment)
+  auto stage_generic = [&](int item) {
+    const int tx = item % p.tiles_x;
+    const int ty = (item / p.tiles_x) % p.tiles_y;
+    const int n = item / (p.tiles_x * p.tiles_y);
+    const int oy0 = ty * TH, ox0 = tx * kTileW;
+#pragma unroll
+    for (int k = 0; k < MTF * 16; ++k) {
       if (k < kcount) {
-        const int e = (it % ITS_PER_K) * kThreads + tid;
-        const int col = e & 31, row = e >> 5;
+        const int col = tid & 31, row = tid >> 5;
         const int gi = oy0 + row, gj = ox0 + col;
         float v = 0.0f;
         if (gi < p.Ho && gj < p.Wo) v = dz_value(a, p.Ho, p.Wo, n, k0 + k, gi, gj);
-        dzs[k * p.PSZ + e] = v;
-        dbacc[k] += v;
+        dzs[k * PSZ + tid] = v;
+        if constexpr (!FAST) dbacc[k] += v;
       }
     }
-    // ---- x halo tile [CC][rows][cols]
-    {
-      const int total = p.CC * p.rows * p.cols;
-      int col = tid % p.cols;
-      int q = tid / p.cols;
-      int row = q % p.rows, cl = q / p.rows;
-      const int dcol = kThreads % p.cols, dq = kThreads / p.cols;
-      for (int e = tid; e < total; e += kThreads) {
-        const int gi = oy0 - a.pad + row, gj = ox0 - a.pad + col, ci = c0 + cl;
-        float v = 0.0f;
-        if (ci < a.C && gi >= 0 && gi < a.H && gj >= 0 && gj < a.W)
-          v = a.x[((n * a.C + ci) * a.H + gi) * a.W + gj];
-        xs[cl * p.PS + row * p.RS + col] = v;
-        col += dcol;
-        row += dq;
-        if (col >= p.cols) { col -= p.cols; ++row; }
-        while (row >= p.rows) { row -= p.rows; ++cl; }
-      }
+    const int total = lines * p.cols;
+    int col = tid % p.cols;
+    int q = tid / p.cols;
+    int row = q % p.rows, cl = q / p.rows;
+    const int dcol = kThreads % p.cols, dq = kThreads / p.cols;
+    for (int e = tid; e < total; e += kThreads) {
+      const int gi = oy0 - a.pad + row, gj = ox0 - a.pad + col, ci = c0 + cl;
+      float v = 0.0f;
+      if (ci < a.C && gi >= 0 && gi < a.H && gj >= 0 && gj < a.W)
+        v = a.x[((long)(n * a.C + ci) * a.H + gi) * a.W + gj];
+      xs[cl * p.PS + row * p.RS + col + p.shift] = v;
+      col += dcol;
+      row += dq;
+      if (col >= p.cols) { col -= p.cols; ++row; }
+      while (row >= p.rows) { row -= p.rows; ++cl; }
     }
+  };
+
+  if (FAST && gidx < p.items) load_tile(gidx);
+  for (int item = gidx; item < p.items; item += p.G) {
+    __syncthreads();   // the previous tile's MFMA reads are done
+    if (FAST) store_tile(); else stage_generic(item);
     __syncthreads();
+    if (FAST && item + p.G < p.items) load_tile(item + p.G);   // in flight during the MFMA loop
     // ---- MFMA: 4 neighbouring pixels per step
 #pragma unroll
     for (int rr = 0; rr < RW; ++rr) {
@@ -161,24 +295,82 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
     }
   }
 
-  // ---- per-wave partial block: [(chunk*G + g)*4 + wave][mf][nt][v][lane], per filter group
-  {
-    float *dst = a.partial + (long)blockIdx.y * p.group_stride +
-                 ((long)(chunk * p.G + gidx) * 4 + wave) * (MTF * NTT * 256);
+  // ---- add the four wavefronts' accumulators in a fixed order: (w0 + w2) + (w1 + w3)
+  constexpr int BLK = MTF * NTT * 256;   // floats per accumulator block
+  float *red = lds;                      // 2 * BLK floats (the host plans LDS for it)
+  __syncthreads();
+  if (wave >= 2) {
 #pragma unroll
     for (int mf = 0; mf < MTF; ++mf)
 #pragma unroll
       for (int nt = 0; nt < NTT; ++nt)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) dst[((mf * NTT + nt) * 4 + v) * 64 + lane] = acc[mf][nt][v];
+        for (int v = 0; v < 4; ++v) red[(wave - 2) * BLK + ((mf * NTT + nt) * 4 + v) * 64 + lane] = acc[mf][nt][v];
   }
-  // ---- db partials: [wave-partial of chunk 0][K]
-  if (chunk == 0) {
-    float *dbp = a.partial + p.db_offset + ((long)gidx * 4 + wave) * a.K + k0;
+  __syncthreads();
+  if (wave < 2) {
 #pragma unroll
-    for (int k = 0; k < MTF * 16; ++k) {
-      const float s = wave_sum(dbacc[k]);
-      if (lane == 0 && k < kcount) dbp[k] = s;
+    for (int mf = 0; mf < MTF; ++mf)
+#pragma unroll
+      for (int nt = 0; nt < NTT; ++nt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[mf][nt][v] += red[wave * BLK + ((mf * NTT + nt) * 4 + v) * 64 + lane];
+  }
+  __syncthreads();
+  if (wave == 1) {
+#pragma unroll
+    for (int mf = 0; mf < MTF; ++mf)
+#pragma unroll
+      for (int nt = 0; nt < NTT; ++nt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) red[((mf * NTT + nt) * 4 + v) * 64 + lane] = acc[mf][nt][v];
+  }
+  __syncthreads();
+  if (wave == 0) {
+    // partial block of this workgroup: [chunk*G + g][mf][nt][v][lane], per filter group
+    float *dst = a.partial + (long)blockIdx.y * p.group_stride + (long)(chunk * p.G + gidx) * BLK;
+#pragma unroll
+    for (int mf = 0; mf < MTF; ++mf)
+#pragma unroll
+      for (int nt = 0; nt < NTT; ++nt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int o = ((mf * NTT + nt) * 4 + v) * 64 + lane;
+          dst[o] = acc[mf][nt][v] + red[o];
+        }
+  }
+
+  // ---- db partials: one value per workgroup and filter, [g][K]
+  if (chunk == 0) {
+    float *dbs = lds + 2 * BLK;   // [4][MTF*16]
+    if (FAST) {
+#pragma unroll
+      for (int rd = 0; rd < DZR; ++rd) {
+        float s = dbacc[rd];
+        if (POOL == 2) {
+#pragma unroll
+          for (int off = 8; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);   // 16 lanes share a filter
+          if ((lane & 15) == 0) dbs[rd * 16 + (tid >> 4)] = s;
+        } else {
+#pragma unroll
+          for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);  // a wavefront shares a filter
+          if (lane == 0) dbs[rd * 4 + wave] = s;
+        }
+      }
+      __syncthreads();
+      if (tid < kcount) a.partial[p.db_offset + (long)gidx * a.K + k0 + tid] = dbs[tid];
+    } else {
+#pragma unroll
+      for (int k = 0; k < MTF * 16; ++k) {
+        float s = dbacc[k];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+        if (lane == 0) dbs[wave * (MTF * 16) + k] = s;
+      }
+      __syncthreads();
+      if (tid < kcount)
+        a.partial[p.db_offset + (long)gidx * a.K + k0 + tid] =
+            (dbs[tid] + dbs[2 * MTF * 16 + tid]) + (dbs[MTF * 16 + tid] + dbs[3 * MTF * 16 + tid]);
     }
   }
 }
@@ -186,7 +378,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
 // One workgroup per 16 outputs (consecutive taps of one filter); 16 slices of the partial
 // list are summed in parallel in double, then combined in a fixed order.
 __global__ __launch_bounds__(kThreads) void wgrad_reduce_kernel(const WgradReduceArgs a, const WgradPlan plan,
-                                                               int kgroups, long group_stride, int ndw) {
+                                                               long group_stride, int ndw) {
   __shared__ double red[16][17];
   const int tid = threadIdx.x, o16 = tid & 15, slice = tid >> 4;
   const int RSf = a.R * a.S;
@@ -256,6 +448,20 @@ inline int pick_ntt(int tiles) {
   return 0;
 }
 
+struct Geom {
+  int rows, cols, RS, PS, shift;
+};
+
+inline Geom x_geom(int R, int S, int pad) {
+  Geom g;
+  g.rows = TH + R - 1;
+  g.cols = kTileW + S - 1;
+  g.shift = pad & 1;
+  g.RS = round_up_mod(g.cols + g.shift, 32, 6);
+  g.PS = g.RS * g.rows;
+  return g;
+}
+
 }  // namespace
 
 bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, WgradPlan *plan) {
@@ -273,28 +479,27 @@ bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, WgradP
   plan->CC = best_cc;
   plan->NTT = best_ntt;
   plan->nchunks = (C + best_cc - 1) / best_cc;
-  plan->TH = 8;
-  const int rows = plan->TH + R - 1, cols = kTileW + S - 1;
-  const int RS = round_up_mod(cols, 32, 6);
-  const int PS = RS * rows;
-  const int PSZ = plan->TH * kTileW + 2;
+  plan->TH = TH;
+  const Geom g = x_geom(R, S, pad);
   int mtf = (K + 15) / 16;
   if (mtf > 3) mtf = 3;
   for (;; --mtf) {
     const int planes = K < mtf * 16 ? K : mtf * 16;
-    plan->lds_bytes = sizeof(float) * ((size_t)best_cc * PS + (size_t)planes * PSZ);
+    const size_t stage = (size_t)best_cc * g.PS + (size_t)planes * PSZ;
+    const size_t reduce = (size_t)2 * mtf * best_ntt * 256 + 4 * mtf * 16;
+    plan->lds_bytes = sizeof(float) * (stage > reduce ? stage : reduce);
     if (plan->lds_bytes <= 64 * 1024) break;
     if (mtf == 1) return false;
   }
   plan->MTF = mtf;
-  const int tiles_x = (Wo + kTileW - 1) / kTileW, tiles_y = (Ho + plan->TH - 1) / plan->TH;
+  const int tiles_x = (Wo + kTileW - 1) / kTileW, tiles_y = (Ho + TH - 1) / TH;
   const long items = (long)N * tiles_x * tiles_y;
   const int kgroups = (K + mtf * 16 - 1) / (mtf * 16);
-  long G = 1024 / ((long)plan->nchunks * kgroups);
+  long G = 512 / ((long)plan->nchunks * kgroups);
   if (G < 1) G = 1;
   if (G > items) G = items;
   plan->G = (int)G;
-  plan->n_partials = 4 * plan->G;
+  plan->n_partials = plan->G;
   const size_t blockf = (size_t)mtf * plan->NTT * 256;
   const size_t group_stride = (size_t)plan->nchunks * plan->n_partials * blockf;
   plan->db_offset = group_stride * kgroups;
@@ -303,22 +508,31 @@ bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, WgradP
 }
 
 namespace {
+
 template <int MTF, int NTT>
-hipError_t launch_wgrad_t(const WgradParams &p, const WgradPlan &plan, hipStream_t stream) {
+hipError_t launch_wgrad_t(const WgradParams &p, const WgradPlan &plan, bool fast, hipStream_t stream) {
   dim3 grid((unsigned)(plan.G * plan.nchunks), (unsigned)p.kgroups, 1);
-  hipLaunchKernelGGL((wgrad_kernel<MTF, NTT, 8>), grid, dim3(kThreads), plan.lds_bytes, stream, p);
+  if (fast && p.a.pool == 2)
+    hipLaunchKernelGGL((wgrad_kernel<MTF, NTT, 2, true>), grid, dim3(kThreads), plan.lds_bytes, stream, p);
+  else if (fast)
+    hipLaunchKernelGGL((wgrad_kernel<MTF, NTT, 1, true>), grid, dim3(kThreads), plan.lds_bytes, stream, p);
+  else
+    hipLaunchKernelGGL((wgrad_kernel<MTF, NTT, 1, false>), grid, dim3(kThreads), plan.lds_bytes, stream, p);
   return hipGetLastError();
 }
 template <int MTF>
-hipError_t launch_wgrad_m(const WgradParams &p, const WgradPlan &plan, hipStream_t stream) {
+hipError_t launch_wgrad_m(const WgradParams &p, const WgradPlan &plan, bool fast, hipStream_t stream) {
   switch (plan.NTT) {
-  case 2: return launch_wgrad_t<MTF, 2>(p, plan, stream);
-  case 5: return launch_wgrad_t<MTF, 5>(p, plan, stream);
-  case 7: return launch_wgrad_t<MTF, 7>(p, plan, stream);
-  case 9: return launch_wgrad_t<MTF, 9>(p, plan, stream);
+  case 2: return launch_wgrad_t<MTF, 2>(p, plan, fast, stream);
+  case 5: return launch_wgrad_t<MTF, 5>(p, plan, fast, stream);
+  case 7: return launch_wgrad_t<MTF, 7>(p, plan, fast, stream);
+  case 9: return launch_wgrad_t<MTF, 9>(p, plan, fast, stream);
   default: return hipErrorInvalidValue;
   }
 }
+
+inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
+
 }  // namespace
 
 hipError_t launch_wgrad(const WgradArgs &a, const WgradPlan &plan, hipStream_t stream) {
@@ -329,31 +543,36 @@ hipError_t launch_wgrad(const WgradArgs &a, const WgradPlan &plan, hipStream_t s
   p.CC = plan.CC;
   p.nchunks = plan.nchunks;
   p.G = plan.G;
-  p.rows = plan.TH + a.R - 1;
-  p.cols = kTileW + a.S - 1;
-  p.RS = round_up_mod(p.cols, 32, 6);
-  p.PS = p.RS * p.rows;
-  p.PSZ = plan.TH * kTileW + 2;
+  const Geom g = x_geom(a.R, a.S, a.pad);
+  p.rows = g.rows; p.cols = g.cols; p.RS = g.RS; p.PS = g.PS; p.shift = g.shift;
+  p.inv_rows = (65536 + g.rows - 1) / g.rows;
   p.tiles_x = (p.Wo + kTileW - 1) / kTileW;
-  p.tiles_y = (p.Ho + plan.TH - 1) / plan.TH;
+  p.tiles_y = (p.Ho + TH - 1) / TH;
   p.items = a.N * p.tiles_x * p.tiles_y;
   p.kgroups = (a.K + plan.MTF * 16 - 1) / (plan.MTF * 16);
   p.db_offset = (long)plan.db_offset;
   p.group_stride = (long)plan.nchunks * plan.n_partials * ((long)plan.MTF * plan.NTT * 256);
+  // Vector staging needs whole 16-byte groups: image rows and output rows that are multiples
+  // of 4 (8 pre-pool columns when pooling), aligned tensors, and a tile that fits the
+  // prefetch registers.
+  const int lines = plan.CC * g.rows;
+  bool fast = (a.W % 4 == 0) && aligned16(a.x) && aligned16(a.dy) && (a.act == ACT_IDENTITY || aligned16(a.y)) &&
+              lines * 8 <= NXI * kThreads && lines * (a.S - 1) <= NXH * kThreads;
+  if (a.pool == 2) fast = fast && (p.Wo % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.idx) & 3u) == 0);
+  else fast = fast && (p.Wo % 4 == 0);
   switch (plan.MTF) {
-  case 1: return launch_wgrad_m<1>(p, plan, stream);
-  case 2: return launch_wgrad_m<2>(p, plan, stream);
-  case 3: return launch_wgrad_m<3>(p, plan, stream);
+  case 1: return launch_wgrad_m<1>(p, plan, fast, stream);
+  case 2: return launch_wgrad_m<2>(p, plan, fast, stream);
+  case 3: return launch_wgrad_m<3>(p, plan, fast, stream);
   default: return hipErrorInvalidValue;
   }
 }
 
 hipError_t launch_wgrad_reduce(const WgradReduceArgs &a, const WgradPlan &plan, hipStream_t stream) {
   const int ndw = a.K * a.C * a.R * a.S;
-  const int kgroups = (a.K + plan.MTF * 16 - 1) / (plan.MTF * 16);
   const long group_stride = (long)plan.nchunks * plan.n_partials * ((long)plan.MTF * plan.NTT * 256);
   const int blocks = (ndw + 15) / 16 + (a.K + 15) / 16;
-  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(blocks), dim3(kThreads), 0, stream, a, plan, kgroups, group_stride, ndw);
+  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(blocks), dim3(kThreads), 0, stream, a, plan, group_stride, ndw);
   return hipGetLastError();
 }
 
