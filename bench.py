@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--batch", type=int, default=None, help="override the batch size (inspection only)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--cpu-batch", type=int, default=32)
+    ap.add_argument("--pmc-calib", action="store_true",
+                    help="also run one 256 MiB device copy, the known-size kernel that scales rocprofv3's byte counters")
     return ap.parse_args()
 
 
@@ -167,6 +169,12 @@ def main():
             B.dll_conv_valid_wgrad(cs, x, dy, y, None, dw, db, ws)
         batch = cs.N
 
+    if args.pmc_calib:
+        src = torch.ones(64 << 20, device="cuda")       # 256 MiB read + 256 MiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
