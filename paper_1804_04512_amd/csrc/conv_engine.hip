@@ -47,6 +47,12 @@ __device__ __forceinline__ float act_apply(int act, float z) {
   return z;
 }
 
+__device__ __forceinline__ float act_deriv(int act, float out) {
+  if (act == ACT_SIGMOID) return out * (1.0f - out);
+  if (act == ACT_RELU) return out > 0.0f ? 1.0f : 0.0f;
+  return 1.0f;
+}
+
 // dz at pre-pool position (i,j) of plane (n,k): dy routed to the recorded arg-max, times act'(y).
 __device__ __forceinline__ float dz_value(const ConvEngineArgs &a, int n, int k, int i, int j) {
   int o;
@@ -65,6 +71,83 @@ __device__ __forceinline__ float dz_value(const ConvEngineArgs &a, int n, int k,
     if (!(a.src_y[o] > 0.0f)) g = 0.0f;
   }
   return g;
+}
+
+// Epilogue shared by the engine kernels.  Lane owns output channel ko0+16nt+i16, window column
+// 4*kq+mt of the tile, window row wave*RP+rp; acc[..][v] is window position v = 2a+b.
+template <int NT, int RP>
+__device__ __forceinline__ void engine_epilogue(const ConvEngineArgs &a, floatx4 (&acc)[RP][4][NT], int n, int ko0,
+                                                int oy0, int ox0, int wave, int i16, int kq) {
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const int ko = ko0 + nt * 16 + i16;
+    if (ko >= a.Kout) continue;
+    const float bv = a.bias ? a.bias[ko] : 0.0f;
+#pragma unroll
+    for (int rp = 0; rp < RP; ++rp) {
+      const int py = (oy0 >> 1) + wave * RP + rp;   // window row (pre-pool rows 2py, 2py+1)
+      const int px0 = (ox0 >> 1) + 4 * kq;          // first of the lane's 4 window columns
+      if (2 * py >= a.Hout) continue;
+      if (a.pool == 2) {
+        const int Hp = a.Hout >> 1, Wp = a.Wout >> 1;
+        float yv[4];
+        unsigned char iv[4];
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+          const floatx4 z = acc[rp][mt][nt];
+          float m = z[0];
+          int arg = 0;
+          if (z[1] > m) { m = z[1]; arg = 1; }
+          if (z[2] > m) { m = z[2]; arg = 2; }
+          if (z[3] > m) { m = z[3]; arg = 3; }
+          yv[mt] = act_apply(a.act, m + bv);   // bias and a monotone activation commute with max
+          iv[mt] = (unsigned char)arg;
+        }
+        const int o = ((n * a.Kout + ko) * Hp + py) * Wp + px0;
+        if (px0 + 3 < Wp && (Wp & 3) == 0) {
+          *reinterpret_cast<float4 *>(a.out + o) = make_float4(yv[0], yv[1], yv[2], yv[3]);
+          *reinterpret_cast<uchar4 *>(a.out_idx + o) = make_uchar4(iv[0], iv[1], iv[2], iv[3]);
+        } else {
+#pragma unroll
+          for (int mt = 0; mt < 4; ++mt)
+            if (px0 + mt < Wp) { a.out[o + mt] = yv[mt]; a.out_idx[o + mt] = iv[mt]; }
+        }
+      } else {
+#pragma unroll
+        for (int wa2 = 0; wa2 < 2; ++wa2) {
+          const int oy = 2 * py + wa2;
+          if (oy >= a.Hout) continue;
+          const int ox = 2 * px0;
+          const int o = ((n * a.Kout + ko) * a.Hout + oy) * a.Wout + ox;
+          float yv[8];
+#pragma unroll
+          for (int mt = 0; mt < 4; ++mt) {
+            yv[2 * mt] = act_apply(a.act, acc[rp][mt][nt][2 * wa2] + bv);
+            yv[2 * mt + 1] = act_apply(a.act, acc[rp][mt][nt][2 * wa2 + 1] + bv);
+          }
+          if (ox + 7 < a.Wout && (a.Wout & 3) == 0) {
+            *reinterpret_cast<float4 *>(a.out + o) = make_float4(yv[0], yv[1], yv[2], yv[3]);
+            *reinterpret_cast<float4 *>(a.out + o + 4) = make_float4(yv[4], yv[5], yv[6], yv[7]);
+            if (a.sample) {
+              const float4 u0 = *reinterpret_cast<const float4 *>(a.uniform + o);
+              const float4 u1 = *reinterpret_cast<const float4 *>(a.uniform + o + 4);
+              *reinterpret_cast<float4 *>(a.sample + o) =
+                  make_float4(u0.x < yv[0] ? 1.f : 0.f, u0.y < yv[1] ? 1.f : 0.f, u0.z < yv[2] ? 1.f : 0.f, u0.w < yv[3] ? 1.f : 0.f);
+              *reinterpret_cast<float4 *>(a.sample + o + 4) =
+                  make_float4(u1.x < yv[4] ? 1.f : 0.f, u1.y < yv[5] ? 1.f : 0.f, u1.z < yv[6] ? 1.f : 0.f, u1.w < yv[7] ? 1.f : 0.f);
+            }
+          } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              if (ox + e < a.Wout) {
+                a.out[o + e] = yv[e];
+                if (a.sample) a.sample[o + e] = a.uniform[o + e] < yv[e] ? 1.f : 0.f;
+              }
+          }
+        }
+      }
+    }
+  }
 }
 
 template <int NT, int RP>
@@ -165,78 +248,7 @@ __global__ __launch_bounds__(kThreads) void conv_engine_kernel(const EngineParam
     }
   }
 
-  // ---- epilogue.  Lane owns output channel ko0+16nt+i16, window column 4*kq+mt of the tile,
-  // window row wave*RP+rp; acc[..][v] is window position v = 2a+b.
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    const int ko = ko0 + nt * 16 + i16;
-    if (ko >= a.Kout) continue;
-    const float bv = a.bias ? a.bias[ko] : 0.0f;
-#pragma unroll
-    for (int rp = 0; rp < RP; ++rp) {
-      const int py = (oy0 >> 1) + wave * RP + rp;   // window row (pre-pool rows 2py, 2py+1)
-      const int px0 = (ox0 >> 1) + 4 * kq;          // first of the lane's 4 window columns
-      if (2 * py >= a.Hout) continue;
-      if (a.pool == 2) {
-        const int Hp = a.Hout >> 1, Wp = a.Wout >> 1;
-        float yv[4];
-        unsigned char iv[4];
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-          const floatx4 z = acc[rp][mt][nt];
-          float m = z[0];
-          int arg = 0;
-          if (z[1] > m) { m = z[1]; arg = 1; }
-          if (z[2] > m) { m = z[2]; arg = 2; }
-          if (z[3] > m) { m = z[3]; arg = 3; }
-          yv[mt] = act_apply(a.act, m + bv);   // bias and a monotone activation commute with max
-          iv[mt] = (unsigned char)arg;
-        }
-        const int o = ((n * a.Kout + ko) * Hp + py) * Wp + px0;
-        if (px0 + 3 < Wp && (Wp & 3) == 0) {
-          *reinterpret_cast<float4 *>(a.out + o) = make_float4(yv[0], yv[1], yv[2], yv[3]);
-          *reinterpret_cast<uchar4 *>(a.out_idx + o) = make_uchar4(iv[0], iv[1], iv[2], iv[3]);
-        } else {
-#pragma unroll
-          for (int mt = 0; mt < 4; ++mt)
-            if (px0 + mt < Wp) { a.out[o + mt] = yv[mt]; a.out_idx[o + mt] = iv[mt]; }
-        }
-      } else {
-#pragma unroll
-        for (int wa2 = 0; wa2 < 2; ++wa2) {
-          const int oy = 2 * py + wa2;
-          if (oy >= a.Hout) continue;
-          const int ox = 2 * px0;
-          const int o = ((n * a.Kout + ko) * a.Hout + oy) * a.Wout + ox;
-          float yv[8];
-#pragma unroll
-          for (int mt = 0; mt < 4; ++mt) {
-            yv[2 * mt] = act_apply(a.act, acc[rp][mt][nt][2 * wa2] + bv);
-            yv[2 * mt + 1] = act_apply(a.act, acc[rp][mt][nt][2 * wa2 + 1] + bv);
-          }
-          if (ox + 7 < a.Wout && (a.Wout & 3) == 0) {
-            *reinterpret_cast<float4 *>(a.out + o) = make_float4(yv[0], yv[1], yv[2], yv[3]);
-            *reinterpret_cast<float4 *>(a.out + o + 4) = make_float4(yv[4], yv[5], yv[6], yv[7]);
-            if (a.sample) {
-              const float4 u0 = *reinterpret_cast<const float4 *>(a.uniform + o);
-              const float4 u1 = *reinterpret_cast<const float4 *>(a.uniform + o + 4);
-              *reinterpret_cast<float4 *>(a.sample + o) =
-                  make_float4(u0.x < yv[0] ? 1.f : 0.f, u0.y < yv[1] ? 1.f : 0.f, u0.z < yv[2] ? 1.f : 0.f, u0.w < yv[3] ? 1.f : 0.f);
-              *reinterpret_cast<float4 *>(a.sample + o + 4) =
-                  make_float4(u1.x < yv[4] ? 1.f : 0.f, u1.y < yv[5] ? 1.f : 0.f, u1.z < yv[6] ? 1.f : 0.f, u1.w < yv[7] ? 1.f : 0.f);
-            }
-          } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-              if (ox + e < a.Wout) {
-                a.out[o + e] = yv[e];
-                if (a.sample) a.sample[o + e] = a.uniform[o + e] < yv[e] ? 1.f : 0.f;
-              }
-          }
-        }
-      }
-    }
-  }
+  engine_epilogue<NT, RP>(a, acc, n, ko0, oy0, ox0, wave, i16, kq);
 }
 
 inline int round_up_mod(int v, int m, int r) {  // smallest value >= v congruent to r mod m
@@ -281,12 +293,299 @@ hipError_t launch_t(const ConvEngineArgs &a, hipStream_t stream) {
   return hipGetLastError();
 }
 
+
+// ---------------------------------------------------------------------------------------
+// 3x3, pad 1, 16-channel chunks: the instance every deeper layer of the paper's CNNs uses
+// (Sections V and VI: 3x3 convolutions), forward and backward-data alike (pad' = 3-1-1 = 1).
+// Same tiling as the generic kernel, with everything the MFMA loop needs known at compile
+// time: reduction order (tap major, channel minor) makes a step's four k-indices four
+// neighbouring channels, so the lane-dependent part of every LDS address is one base
+// register and all tap / M-tile / chunk displacements are instruction immediates.  Staging
+// uses 16-byte global loads; in backward-data mode it reads dy, y and the arg-max bytes at
+// pooled resolution and expands each element to its 2x2 window while storing to LDS.
+// LDS strides RS = 36 (4 mod 8), PS = 2 mod 8: conflict-free operand reads, 8-byte aligned
+// vector stores (tile column 0 sits at LDS column 1 so that the aligned interior starts at 2).
+// ---------------------------------------------------------------------------------------
+constexpr int round_up_mod_c(int v, int m, int r) { return (v - (v % m) + r) < v ? (v - (v % m) + r + m) : (v - (v % m) + r); }
+
+template <int NT, int RP, int SRC>   // SRC: 0 plain tensor, 1 dz without pooling, 2 dz through 2x2 pooling
+__global__ __launch_bounds__(kThreads, NT == 1 ? 3 : 2) void conv3x3c16_kernel(const EngineParams p) {
+  constexpr int CC = 16, TH = 8 * RP, ROWS = TH + 2;
+  constexpr int RS = 36, PS = round_up_mod_c(RS * ROWS, 8, 2);
+  constexpr int KC = CC * 9;
+  extern __shared__ float lds[];
+  const ConvEngineArgs &a = p.a;
+  const EngineGeom &g = p.g;
+  float *xs = lds;               // [16][PS]
+  float *wl = xs + CC * PS;      // [NT][144][16]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i16 = lane & 15, kq = lane >> 4;
+  const int bid = blockIdx.x;
+  const int tx = bid % g.tiles_x;
+  const int ty = (bid / g.tiles_x) % g.tiles_y;
+  const int n = bid / (g.tiles_x * g.tiles_y);
+  const int ko0 = blockIdx.y * (NT * 16);
+  const int oy0 = ty * TH, ox0 = tx * kTileW;
+
+  floatx4 acc[RP][4][NT];
+#pragma unroll
+  for (int rp = 0; rp < RP; ++rp)
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) acc[rp][mt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  const int gq = i16 >> 2, wa = (i16 >> 1) & 1, wb = i16 & 1;
+  const float *a_ptr = xs + kq * PS + (wave * 2 * RP + wa) * RS + 8 * gq + wb + 1;
+  const float *b_ptr = wl + kq * 16 + i16;
+
+  for (int chunk = 0; chunk < g.nchunks; ++chunk) {
+    const int c0 = chunk * CC;
+    __syncthreads();
+    // ---- filter slice wl[nt][rs*16 + cl][j]
+#pragma unroll
+    for (int it = 0; it < (NT * KC * 16 + kThreads - 1) / kThreads; ++it) {
+      const int e = tid + it * kThreads;
+      const int j = e & 15, q = e >> 4;
+      const int kk = q % KC, nt = q / KC;
+      const int cl = kk & 15, rs = kk >> 4;
+      const int r = rs / 3, s = rs - 3 * r;
+      const int ko = ko0 + nt * 16 + j, ci = c0 + cl;
+      float v = 0.0f;
+      if (ko < a.Kout)
+        v = a.w_flip ? a.w[((ci * a.Kout + ko) * 3 + (2 - r)) * 3 + (2 - s)] : a.w[((ko * a.Cin + ci) * 3 + r) * 3 + s];
+      if (e < NT * KC * 16) wl[e] = v;
+    }
+    // ---- halo tile [16][ROWS][34]: tile column t lives at LDS column t + 1
+    if (SRC != 2) {
+      constexpr int LINES = CC * ROWS;
+      constexpr int NI = (LINES * 8 + kThreads - 1) / kThreads;
+      constexpr int NH = (LINES * 2 + kThreads - 1) / kThreads;
+      float4 vi[NI], yi[NI];
+      float vh[NH], yh[NH];
+#pragma unroll
+      for (int it = 0; it < NI; ++it) {
+        const int e = tid + it * kThreads;
+        const int j = e & 7, line = e >> 3;
+        const int cl = line / ROWS, row = line - cl * ROWS;
+        const int gi = oy0 - 1 + row, gj = ox0 + 4 * j;
+        vi[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+        yi[it] = vi[it];
+        if (line < LINES && gi >= 0 && gi < a.Hin && gj < a.Win) {
+          const long o = ((long)(n * a.Cin + c0 + cl) * a.Hin + gi) * a.Win + gj;
+          vi[it] = *reinterpret_cast<const float4 *>(a.src + o);
+          if (SRC == 1 && a.src_act != ACT_IDENTITY) yi[it] = *reinterpret_cast<const float4 *>(a.src_y + o);
+        }
+      }
+#pragma unroll
+      for (int it = 0; it < NH; ++it) {
+        const int e = tid + it * kThreads;
+        const int side = e & 1, line = e >> 1;
+        const int cl = line / ROWS, row = line - cl * ROWS;
+        const int gi = oy0 - 1 + row, gj = side ? ox0 + kTileW : ox0 - 1;
+        vh[it] = 0.0f;
+        yh[it] = 0.0f;
+        if (line < LINES && gi >= 0 && gi < a.Hin && gj >= 0 && gj < a.Win) {
+          const long o = ((long)(n * a.Cin + c0 + cl) * a.Hin + gi) * a.Win + gj;
+          vh[it] = a.src[o];
+          if (SRC == 1 && a.src_act != ACT_IDENTITY) yh[it] = a.src_y[o];
+        }
+      }
+#pragma unroll
+      for (int it = 0; it < NI; ++it) {
+        const int e = tid + it * kThreads;
+        const int j = e & 7, line = e >> 3;
+        if (line < LINES) {
+          const int cl = line / ROWS, row = line - cl * ROWS;
+          float4 v = vi[it];
+          if (SRC == 1 && a.src_act != ACT_IDENTITY) {
+            v.x *= act_deriv(a.src_act, yi[it].x); v.y *= act_deriv(a.src_act, yi[it].y);
+            v.z *= act_deriv(a.src_act, yi[it].z); v.w *= act_deriv(a.src_act, yi[it].w);
+          }
+          float2 *d = reinterpret_cast<float2 *>(xs + cl * PS + row * RS + 2 + 4 * j);
+          d[0] = make_float2(v.x, v.y);
+          d[1] = make_float2(v.z, v.w);
+        }
+      }
+#pragma unroll
+      for (int it = 0; it < NH; ++it) {
+        const int e = tid + it * kThreads;
+        const int side = e & 1, line = e >> 1;
+        if (line < LINES) {
+          const int cl = line / ROWS, row = line - cl * ROWS;
+          float v = vh[it];
+          if (SRC == 1 && a.src_act != ACT_IDENTITY) v *= act_deriv(a.src_act, yh[it]);
+          xs[cl * PS + row * RS + (side ? kTileW + 2 : 1)] = v;
+        }
+      }
+    } else {
+      // pooled rows u = oy0/2 - 1 + pr (pr = 0 .. TH/2 + 1); pooled columns ox0/2 - 1 .. ox0/2 + 16
+      constexpr int PR = TH / 2 + 2, LINES = CC * PR;
+      constexpr int NI = (LINES * 4 + kThreads - 1) / kThreads;
+      constexpr int NH = (LINES * 2 + kThreads - 1) / kThreads;
+      const int Hp = a.Hin >> 1, Wp = a.Win >> 1;
+      float4 vi[NI], yi[NI];
+      uchar4 ii[NI];
+      float vh[NH], yh[NH];
+      unsigned char ih[NH];
+#pragma unroll
+      for (int it = 0; it < NI; ++it) {
+        const int e = tid + it * kThreads;
+        const int j = e & 3, line = e >> 2;
+        const int cl = line / PR, pr = line - cl * PR;
+        const int u = (oy0 >> 1) - 1 + pr, v0 = (ox0 >> 1) + 4 * j;
+        vi[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+        yi[it] = vi[it];
+        ii[it] = make_uchar4(255, 255, 255, 255);
+        if (line < LINES && u >= 0 && u < Hp && v0 < Wp) {
+          const long o = ((long)(n * a.Cin + c0 + cl) * Hp + u) * Wp + v0;
+          vi[it] = *reinterpret_cast<const float4 *>(a.src + o);
+          if (a.src_act != ACT_IDENTITY) yi[it] = *reinterpret_cast<const float4 *>(a.src_y + o);
+          ii[it] = *reinterpret_cast<const uchar4 *>(a.src_idx + o);
+        }
+      }
+#pragma unroll
+      for (int it = 0; it < NH; ++it) {
+        const int e = tid + it * kThreads;
+        const int side = e & 1, line = e >> 1;
+        const int cl = line / PR, pr = line - cl * PR;
+        const int u = (oy0 >> 1) - 1 + pr, v0 = side ? (ox0 >> 1) + 16 : (ox0 >> 1) - 1;
+        vh[it] = 0.0f; yh[it] = 0.0f; ih[it] = 255;
+        if (line < LINES && u >= 0 && u < Hp && v0 >= 0 && v0 < Wp) {
+          const long o = ((long)(n * a.Cin + c0 + cl) * Hp + u) * Wp + v0;
+          vh[it] = a.src[o];
+          if (a.src_act != ACT_IDENTITY) yh[it] = a.src_y[o];
+          ih[it] = a.src_idx[o];
+        }
+      }
+      // expand: pooled (pr, pc) -> tile rows 2pr-1, 2pr; LDS columns 2*(pc local)+ {0,1} (+2 for the interior)
+#pragma unroll
+      for (int it = 0; it < NI; ++it) {
+        const int e = tid + it * kThreads;
+        const int j = e & 3, line = e >> 2;
+        if (line < LINES) {
+          const int cl = line / PR, pr = line - cl * PR;
+          const float gv[4] = {vi[it].x, vi[it].y, vi[it].z, vi[it].w};
+          const float ov[4] = {yi[it].x, yi[it].y, yi[it].z, yi[it].w};
+          const unsigned char pos[4] = {ii[it].x, ii[it].y, ii[it].z, ii[it].w};
+          float gg[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) gg[q] = a.src_act != ACT_IDENTITY ? gv[q] * act_deriv(a.src_act, ov[q]) : gv[q];
+#pragma unroll
+          for (int wa2 = 0; wa2 < 2; ++wa2) {
+            const int row = 2 * pr - 1 + wa2;
+            if (row >= 0 && row < ROWS) {
+              float *d = xs + cl * PS + row * RS + 2 + 8 * j;
+#pragma unroll
+              for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<float2 *>(d + 2 * q) =
+                    make_float2(pos[q] == 2 * wa2 ? gg[q] : 0.0f, pos[q] == 2 * wa2 + 1 ? gg[q] : 0.0f);
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int it = 0; it < NH; ++it) {
+        const int e = tid + it * kThreads;
+        const int side = e & 1, line = e >> 1;
+        if (line < LINES) {
+          const int cl = line / PR, pr = line - cl * PR;
+          const float gg = a.src_act != ACT_IDENTITY ? vh[it] * act_deriv(a.src_act, yh[it]) : vh[it];
+#pragma unroll
+          for (int wa2 = 0; wa2 < 2; ++wa2) {
+            const int row = 2 * pr - 1 + wa2;
+            // left neighbour window: LDS columns 0 (unused slot) and 1; right one: 34 and 35 (unused slot)
+            if (row >= 0 && row < ROWS)
+              *reinterpret_cast<float2 *>(xs + cl * PS + row * RS + (side ? kTileW + 2 : 0)) =
+                  make_float2(ih[it] == 2 * wa2 ? gg : 0.0f, ih[it] == 2 * wa2 + 1 ? gg : 0.0f);
+          }
+        }
+      }
+    }
+    __syncthreads();
+    // ---- MFMA: 9 taps x 4 channel groups; inside a tap every address is base + immediate
+    const float *a_tap = a_ptr;
+    const float *b_tap = b_ptr;
+#pragma unroll 1
+    for (int rs = 0; rs < 9; ++rs) {
+#pragma unroll
+      for (int c4 = 0; c4 < 4; ++c4) {
+        float bf[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) bf[nt] = b_tap[(nt * KC + 4 * c4) * 16];
+#pragma unroll
+        for (int rp = 0; rp < RP; ++rp) {
+#pragma unroll
+          for (int mt = 0; mt < 4; ++mt) {
+            const float af = a_tap[c4 * 4 * PS + rp * 2 * RS + 2 * mt];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+              acc[rp][mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(af, bf[nt], acc[rp][mt][nt], 0, 0, 0);
+          }
+        }
+      }
+      a_tap += (rs % 3 == 2) ? RS - 2 : 1;   // next tap: s+1, or first column of the next filter row
+      b_tap += 16 * 16;                      // 16 channels x 16 output channels per tap
+    }
+  }
+  engine_epilogue<NT, RP>(a, acc, n, ko0, oy0, ox0, wave, i16, kq);
+}
+
+template <int NT, int RP>
+constexpr size_t conv3x3c16_lds() {
+  return sizeof(float) * ((size_t)16 * round_up_mod_c(36 * (8 * RP + 2), 8, 2) + (size_t)NT * 144 * 16);
+}
+
+inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
+
+// The specialised kernel applies to 3x3 filters with one row/column of padding, channel
+// counts that are multiples of 16, rows that are whole 16-byte groups and aligned tensors.
+bool conv3x3c16_applies(const ConvEngineArgs &a) {
+  if (a.R != 3 || a.S != 3 || a.pad_h != 1 || a.pad_w != 1 || a.Cin % 16 != 0) return false;
+  if (a.Hout != a.Hin || a.Wout != a.Win) return false;
+  if (!aligned16(a.src)) return false;
+  if (a.src_dz) {
+    if (a.src_act != ACT_IDENTITY && !aligned16(a.src_y)) return false;
+    if (a.src_pool == 2) return (a.Win % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.src_idx) & 3u) == 0);
+  }
+  return a.Win % 4 == 0;
+}
+
+template <int NT, int RP>
+hipError_t launch_3x3(const ConvEngineArgs &a, hipStream_t stream) {
+  EngineParams p;
+  p.a = a;
+  constexpr int TH = 8 * RP;
+  p.g = EngineGeom{};
+  p.g.CC = 16;
+  p.g.nchunks = a.Cin / 16;
+  p.g.tiles_x = (a.Wout + kTileW - 1) / kTileW;
+  p.g.tiles_y = (a.Hout + TH - 1) / TH;
+  p.g.kgroups = (a.Kout + NT * 16 - 1) / (NT * 16);
+  const long blocks = (long)a.N * p.g.tiles_x * p.g.tiles_y;
+  if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  dim3 grid((unsigned)blocks, (unsigned)p.g.kgroups, 1);
+  constexpr size_t lds = conv3x3c16_lds<NT, RP>();
+  if (!a.src_dz)
+    hipLaunchKernelGGL((conv3x3c16_kernel<NT, RP, 0>), grid, dim3(kThreads), lds, stream, p);
+  else if (a.src_pool == 2)
+    hipLaunchKernelGGL((conv3x3c16_kernel<NT, RP, 2>), grid, dim3(kThreads), lds, stream, p);
+  else
+    hipLaunchKernelGGL((conv3x3c16_kernel<NT, RP, 1>), grid, dim3(kThreads), lds, stream, p);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_conv_engine(const ConvEngineArgs &a, hipStream_t stream) {
   // shallow maps (<= 8 pre-pool rows) use the 8-row tile; 16 output channels per N-tile
   const bool small = a.Hout <= 8;
   const int nt = a.Kout <= 16 ? 1 : (a.Kout <= 32 ? 2 : 3);
+  if (!small && conv3x3c16_applies(a)) {
+    if (a.Kout <= 16) return launch_3x3<1, 2>(a, stream);
+    return launch_3x3<2, 2>(a, stream);   // wider layers run as groups of 32 output channels
+  }
   if (small) {
     if (nt == 1) return launch_t<1, 1>(a, stream);
     if (nt == 2) return launch_t<2, 1>(a, stream);
