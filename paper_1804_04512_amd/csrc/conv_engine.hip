@@ -18,6 +18,8 @@
 // same valid-convolution engine run on an input padded by R-1-pad.
 #include "dll_internal.h"
 
+#include <type_traits>
+
 namespace dllk {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -308,65 +310,61 @@ hipError_t launch_t(const ConvEngineArgs &a, hipStream_t stream) {
 // ---------------------------------------------------------------------------------------
 constexpr int round_up_mod_c(int v, int m, int r) { return (v - (v % m) + r) < v ? (v - (v % m) + r + m) : (v - (v % m) + r); }
 
-template <int NT, int RP, int SRC>   // SRC: 0 plain tensor, 1 dz without pooling, 2 dz through 2x2 pooling
-__global__ __launch_bounds__(kThreads, NT == 1 ? 3 : 2) void conv3x3c16_kernel(const EngineParams p) {
-  constexpr int CC = 16, TH = 8 * RP, ROWS = TH + 2;
+template <int NT, int WAVES, int SRC>   // SRC: 0 plain tensor, 1 dz without pooling, 2 dz through 2x2 pooling
+__global__ __launch_bounds__(WAVES * 64, (NT == 1 ? 3 : 2) * WAVES / 4) void conv3x3c16_kernel(const EngineParams p) {
+  constexpr int NTHR = WAVES * 64, RP = 8 / WAVES;   // 16-row tile: every wave owns RP row pairs
+  constexpr int CC = 16, TH = 16, ROWS = TH + 2;
   constexpr int RS = 36, PS = round_up_mod_c(RS * ROWS, 8, 2);
   constexpr int KC = CC * 9;
+  // staging registers per thread: plain rows, or pooled rows (u = oy0/2 - 1 + pr, pr = 0 .. TH/2 + 1)
+  constexpr int PR = TH / 2 + 2;
+  constexpr int LINES = CC * (SRC == 2 ? PR : ROWS);
+  constexpr int VPL = SRC == 2 ? 4 : 8;   // 16-byte groups per line
+  constexpr int NI = (LINES * VPL + NTHR - 1) / NTHR;
+  constexpr int NH = (LINES * 2 + NTHR - 1) / NTHR;
   extern __shared__ float lds[];
   const ConvEngineArgs &a = p.a;
   const EngineGeom &g = p.g;
   float *xs = lds;               // [16][PS]
-  float *wl = xs + CC * PS;      // [NT][144][16]
+  float *wl = xs + CC * PS;      // [chunk][NT][144][16]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i16 = lane & 15, kq = lane >> 4;
-  const int bid = blockIdx.x;
-  const int tx = bid % g.tiles_x;
-  const int ty = (bid / g.tiles_x) % g.tiles_y;
-  const int n = bid / (g.tiles_x * g.tiles_y);
   const int ko0 = blockIdx.y * (NT * 16);
-  const int oy0 = ty * TH, ox0 = tx * kTileW;
+  const int tiles = a.N * g.tiles_x * g.tiles_y;
+  const int work = tiles * g.nchunks;          // (tile, chunk) pairs, chunk fastest
+  const int Hp = a.Hin >> 1, Wp = a.Win >> 1;  // SRC == 2 only
 
-  floatx4 acc[RP][4][NT];
-#pragma unroll
-  for (int rp = 0; rp < RP; ++rp)
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) acc[rp][mt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+  // ---- filter slices of every chunk, once per workgroup: wl[chunk][nt][rs*16 + cl][j]
+  for (int e = tid; e < g.nchunks * NT * KC * 16; e += NTHR) {
+    const int j = e & 15, q = e >> 4;
+    const int kk = q % KC, q2 = q / KC;
+    const int nt = q2 % NT, chunk = q2 / NT;
+    const int cl = kk & 15, rs = kk >> 4;
+    const int r = rs / 3, s = rs - 3 * r;
+    const int ko = ko0 + nt * 16 + j, ci = chunk * CC + cl;
+    float v = 0.0f;
+    if (ko < a.Kout)
+      v = a.w_flip ? a.w[((ci * a.Kout + ko) * 3 + (2 - r)) * 3 + (2 - s)] : a.w[((ko * a.Cin + ci) * 3 + r) * 3 + s];
+    wl[e] = v;
+  }
 
-  const int gq = i16 >> 2, wa = (i16 >> 1) & 1, wb = i16 & 1;
-  const float *a_ptr = xs + kq * PS + (wave * 2 * RP + wa) * RS + 8 * gq + wb + 1;
-  const float *b_ptr = wl + kq * 16 + i16;
+  float4 vi[NI], yi[NI];
+  uchar4 ii[NI];
+  float vh[NH], yh[NH];
+  unsigned char ih[NH];
 
-  for (int chunk = 0; chunk < g.nchunks; ++chunk) {
-    const int c0 = chunk * CC;
-    __syncthreads();
-    // ---- filter slice wl[nt][rs*16 + cl][j]
-#pragma unroll
-    for (int it = 0; it < (NT * KC * 16 + kThreads - 1) / kThreads; ++it) {
-      const int e = tid + it * kThreads;
-      const int j = e & 15, q = e >> 4;
-      const int kk = q % KC, nt = q / KC;
-      const int cl = kk & 15, rs = kk >> 4;
-      const int r = rs / 3, s = rs - 3 * r;
-      const int ko = ko0 + nt * 16 + j, ci = c0 + cl;
-      float v = 0.0f;
-      if (ko < a.Kout)
-        v = a.w_flip ? a.w[((ci * a.Kout + ko) * 3 + (2 - r)) * 3 + (2 - s)] : a.w[((ko * a.Cin + ci) * 3 + r) * 3 + s];
-      if (e < NT * KC * 16) wl[e] = v;
-    }
-    // ---- halo tile [16][ROWS][34]: tile column t lives at LDS column t + 1
+  // global -> registers for work item q
+  auto load_regs = [&](int q) {
+    const int tile = q / g.nchunks, chunk = q - tile * g.nchunks;
+    const int tx = tile % g.tiles_x;
+    const int ty = (tile / g.tiles_x) % g.tiles_y;
+    const int n = tile / (g.tiles_x * g.tiles_y);
+    const int oy0 = ty * TH, ox0 = tx * kTileW, c0 = chunk * CC;
     if (SRC != 2) {
-      constexpr int LINES = CC * ROWS;
-      constexpr int NI = (LINES * 8 + kThreads - 1) / kThreads;
-      constexpr int NH = (LINES * 2 + kThreads - 1) / kThreads;
-      float4 vi[NI], yi[NI];
-      float vh[NH], yh[NH];
 #pragma unroll
       for (int it = 0; it < NI; ++it) {
-        const int e = tid + it * kThreads;
+        const int e = tid + it * NTHR;
         const int j = e & 7, line = e >> 3;
         const int cl = line / ROWS, row = line - cl * ROWS;
         const int gi = oy0 - 1 + row, gj = ox0 + 4 * j;
@@ -380,7 +378,7 @@ __global__ __launch_bounds__(kThreads, NT == 1 ? 3 : 2) void conv3x3c16_kernel(c
       }
 #pragma unroll
       for (int it = 0; it < NH; ++it) {
-        const int e = tid + it * kThreads;
+        const int e = tid + it * NTHR;
         const int side = e & 1, line = e >> 1;
         const int cl = line / ROWS, row = line - cl * ROWS;
         const int gi = oy0 - 1 + row, gj = side ? ox0 + kTileW : ox0 - 1;
@@ -392,46 +390,10 @@ __global__ __launch_bounds__(kThreads, NT == 1 ? 3 : 2) void conv3x3c16_kernel(c
           if (SRC == 1 && a.src_act != ACT_IDENTITY) yh[it] = a.src_y[o];
         }
       }
-#pragma unroll
-      for (int it = 0; it < NI; ++it) {
-        const int e = tid + it * kThreads;
-        const int j = e & 7, line = e >> 3;
-        if (line < LINES) {
-          const int cl = line / ROWS, row = line - cl * ROWS;
-          float4 v = vi[it];
-          if (SRC == 1 && a.src_act != ACT_IDENTITY) {
-            v.x *= act_deriv(a.src_act, yi[it].x); v.y *= act_deriv(a.src_act, yi[it].y);
-            v.z *= act_deriv(a.src_act, yi[it].z); v.w *= act_deriv(a.src_act, yi[it].w);
-          }
-          float2 *d = reinterpret_cast<float2 *>(xs + cl * PS + row * RS + 2 + 4 * j);
-          d[0] = make_float2(v.x, v.y);
-          d[1] = make_float2(v.z, v.w);
-        }
-      }
-#pragma unroll
-      for (int it = 0; it < NH; ++it) {
-        const int e = tid + it * kThreads;
-        const int side = e & 1, line = e >> 1;
-        if (line < LINES) {
-          const int cl = line / ROWS, row = line - cl * ROWS;
-          float v = vh[it];
-          if (SRC == 1 && a.src_act != ACT_IDENTITY) v *= act_deriv(a.src_act, yh[it]);
-          xs[cl * PS + row * RS + (side ? kTileW + 2 : 1)] = v;
-        }
-      }
     } else {
-      // pooled rows u = oy0/2 - 1 + pr (pr = 0 .. TH/2 + 1); pooled columns ox0/2 - 1 .. ox0/2 + 16
-      constexpr int PR = TH / 2 + 2, LINES = CC * PR;
-      constexpr int NI = (LINES * 4 + kThreads - 1) / kThreads;
-      constexpr int NH = (LINES * 2 + kThreads - 1) / kThreads;
-      const int Hp = a.Hin >> 1, Wp = a.Win >> 1;
-      float4 vi[NI], yi[NI];
-      uchar4 ii[NI];
-      float vh[NH], yh[NH];
-      unsigned char ih[NH];
 #pragma unroll
       for (int it = 0; it < NI; ++it) {
-        const int e = tid + it * kThreads;
+        const int e = tid + it * NTHR;
         const int j = e & 3, line = e >> 2;
         const int cl = line / PR, pr = line - cl * PR;
         const int u = (oy0 >> 1) - 1 + pr, v0 = (ox0 >> 1) + 4 * j;
@@ -447,7 +409,7 @@ __global__ __launch_bounds__(kThreads, NT == 1 ? 3 : 2) void conv3x3c16_kernel(c
       }
 #pragma unroll
       for (int it = 0; it < NH; ++it) {
-        const int e = tid + it * kThreads;
+        const int e = tid + it * NTHR;
         const int side = e & 1, line = e >> 1;
         const int cl = line / PR, pr = line - cl * PR;
         const int u = (oy0 >> 1) - 1 + pr, v0 = side ? (ox0 >> 1) + 16 : (ox0 >> 1) - 1;
@@ -459,10 +421,44 @@ __global__ __launch_bounds__(kThreads, NT == 1 ? 3 : 2) void conv3x3c16_kernel(c
           ih[it] = a.src_idx[o];
         }
       }
-      // expand: pooled (pr, pc) -> tile rows 2pr-1, 2pr; LDS columns 2*(pc local)+ {0,1} (+2 for the interior)
+    }
+  };
+
+  // registers -> LDS halo tile [16][ROWS][34]: tile column t lives at LDS column t + 1
+  auto store_regs = [&]() {
+    if (SRC != 2) {
 #pragma unroll
       for (int it = 0; it < NI; ++it) {
-        const int e = tid + it * kThreads;
+        const int e = tid + it * NTHR;
+        const int j = e & 7, line = e >> 3;
+        if (line < LINES) {
+          const int cl = line / ROWS, row = line - cl * ROWS;
+          float4 v = vi[it];
+          if (SRC == 1 && a.src_act != ACT_IDENTITY) {
+            v.x *= act_deriv(a.src_act, yi[it].x); v.y *= act_deriv(a.src_act, yi[it].y);
+            v.z *= act_deriv(a.src_act, yi[it].z); v.w *= act_deriv(a.src_act, yi[it].w);
+          }
+          float2 *d = reinterpret_cast<float2 *>(xs + cl * PS + row * RS + 2 + 4 * j);
+          d[0] = make_float2(v.x, v.y);
+          d[1] = make_float2(v.z, v.w);
+        }
+      }
+#pragma unroll
+      for (int it = 0; it < NH; ++it) {
+        const int e = tid + it * NTHR;
+        const int side = e & 1, line = e >> 1;
+        if (line < LINES) {
+          const int cl = line / ROWS, row = line - cl * ROWS;
+          float v = vh[it];
+          if (SRC == 1 && a.src_act != ACT_IDENTITY) v *= act_deriv(a.src_act, yh[it]);
+          xs[cl * PS + row * RS + (side ? kTileW + 2 : 1)] = v;
+        }
+      }
+    } else {
+      // expand: pooled (pr, pc) -> tile rows 2pr-1, 2pr; LDS columns 2*(pc local) + {0,1} (+2 for the interior)
+#pragma unroll
+      for (int it = 0; it < NI; ++it) {
+        const int e = tid + it * NTHR;
         const int j = e & 3, line = e >> 2;
         if (line < LINES) {
           const int cl = line / PR, pr = line - cl * PR;
@@ -487,7 +483,7 @@ __global__ __launch_bounds__(kThreads, NT == 1 ? 3 : 2) void conv3x3c16_kernel(c
       }
 #pragma unroll
       for (int it = 0; it < NH; ++it) {
-        const int e = tid + it * kThreads;
+        const int e = tid + it * NTHR;
         const int side = e & 1, line = e >> 1;
         if (line < LINES) {
           const int cl = line / PR, pr = line - cl * PR;
@@ -503,38 +499,96 @@ __global__ __launch_bounds__(kThreads, NT == 1 ? 3 : 2) void conv3x3c16_kernel(c
         }
       }
     }
+  };
+
+  floatx4 acc[RP][4][NT];
+  const int gq = i16 >> 2, wa = (i16 >> 1) & 1, wb = i16 & 1;
+  const float *a_ptr = xs + kq * PS + (wave * 2 * RP + wa) * RS + 8 * gq + wb + 1;
+  const float *b_ptr = wl + kq * 16 + i16;
+
+  // persistent loop over (tile, chunk) pairs; the next pair's global loads fly during the MFMA loop
+  const int q0 = blockIdx.x, qstep = gridDim.x * g.nchunks;   // whole tiles per workgroup
+  int q = q0 * g.nchunks;
+  if (q < work) load_regs(q);
+  while (q < work) {
+    const int tile = q / g.nchunks, chunk = q - tile * g.nchunks;
+    if (chunk == 0) {
+#pragma unroll
+      for (int rp = 0; rp < RP; ++rp)
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) acc[rp][mt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+    __syncthreads();   // previous MFMA loop no longer reads the tile (first pass: filters are staged)
+    store_regs();
     __syncthreads();
-    // ---- MFMA: 9 taps x 4 channel groups; inside a tap every address is base + immediate
+    const int qn = (chunk + 1 < g.nchunks) ? q + 1 : q - chunk + qstep;
+    if (qn < work) load_regs(qn);
+    // ---- MFMA: 9 taps x 4 channel groups; inside a tap every address is base + immediate.
+    // Operand fragments are double-buffered in registers: the LDS reads of step t+1 are issued
+    // before the MFMAs of step t, and scheduling barriers keep that order.
     const float *a_tap = a_ptr;
-    const float *b_tap = b_ptr;
+    const float *b_tap = b_ptr + chunk * (NT * KC * 16);
+    float af[2][RP * 4], bf[2][NT];
+    auto load_frags = [&](auto bufc, const float *at, const float *bt, int c4) {
+      constexpr int B_ = decltype(bufc)::value;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) bf[B_][nt] = bt[(nt * KC + 4 * c4) * 16];
+#pragma unroll
+      for (int rp = 0; rp < RP; ++rp)
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) af[B_][rp * 4 + mt] = at[c4 * 4 * PS + rp * 2 * RS + 2 * mt];
+    };
+    auto mfma_frags = [&](auto bufc) {
+      constexpr int B_ = decltype(bufc)::value;
+#pragma unroll
+      for (int rp = 0; rp < RP; ++rp)
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+            acc[rp][mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[B_][rp * 4 + mt], bf[B_][nt], acc[rp][mt][nt], 0, 0, 0);
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    load_frags(I0{}, a_tap, b_tap, 0);
 #pragma unroll 1
     for (int rs = 0; rs < 9; ++rs) {
-#pragma unroll
-      for (int c4 = 0; c4 < 4; ++c4) {
-        float bf[NT];
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) bf[nt] = b_tap[(nt * KC + 4 * c4) * 16];
-#pragma unroll
-        for (int rp = 0; rp < RP; ++rp) {
-#pragma unroll
-          for (int mt = 0; mt < 4; ++mt) {
-            const float af = a_tap[c4 * 4 * PS + rp * 2 * RS + 2 * mt];
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-              acc[rp][mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(af, bf[nt], acc[rp][mt][nt], 0, 0, 0);
-          }
-        }
-      }
-      a_tap += (rs % 3 == 2) ? RS - 2 : 1;   // next tap: s+1, or first column of the next filter row
-      b_tap += 16 * 16;                      // 16 channels x 16 output channels per tap
+      const float *a_next = a_tap + ((rs % 3 == 2) ? RS - 2 : 1);   // next tap: s+1, or first column of the next filter row
+      const float *b_next = b_tap + 16 * 16;                          // 16 channels x 16 output channels per tap
+      load_frags(I1{}, a_tap, b_tap, 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_frags(I0{});
+      __builtin_amdgcn_sched_barrier(0);
+      load_frags(I0{}, a_tap, b_tap, 2);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_frags(I1{});
+      __builtin_amdgcn_sched_barrier(0);
+      load_frags(I1{}, a_tap, b_tap, 3);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_frags(I0{});
+      __builtin_amdgcn_sched_barrier(0);
+      if (rs < 8) load_frags(I0{}, a_next, b_next, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_frags(I1{});
+      __builtin_amdgcn_sched_barrier(0);
+      a_tap = a_next;
+      b_tap = b_next;
     }
+    if (chunk + 1 == g.nchunks) {
+      const int tx = tile % g.tiles_x;
+      const int ty = (tile / g.tiles_x) % g.tiles_y;
+      const int n = tile / (g.tiles_x * g.tiles_y);
+      engine_epilogue<NT, RP>(a, acc, n, ko0, ty * TH, tx * kTileW, wave, i16, kq);
+    }
+    q = qn;
   }
-  engine_epilogue<NT, RP>(a, acc, n, ko0, oy0, ox0, wave, i16, kq);
 }
 
-template <int NT, int RP>
-constexpr size_t conv3x3c16_lds() {
-  return sizeof(float) * ((size_t)16 * round_up_mod_c(36 * (8 * RP + 2), 8, 2) + (size_t)NT * 144 * 16);
+template <int NT>
+size_t conv3x3c16_lds(int nchunks) {
+  return sizeof(float) * ((size_t)16 * round_up_mod_c(36 * 18, 8, 2) + (size_t)nchunks * NT * 144 * 16);
 }
 
 inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
@@ -552,28 +606,40 @@ bool conv3x3c16_applies(const ConvEngineArgs &a) {
   return a.Win % 4 == 0;
 }
 
-template <int NT, int RP>
+template <int NT, int WAVES>
 hipError_t launch_3x3(const ConvEngineArgs &a, hipStream_t stream) {
   EngineParams p;
   p.a = a;
-  constexpr int TH = 8 * RP;
+  constexpr int TH = 16;
   p.g = EngineGeom{};
   p.g.CC = 16;
   p.g.nchunks = a.Cin / 16;
   p.g.tiles_x = (a.Wout + kTileW - 1) / kTileW;
   p.g.tiles_y = (a.Hout + TH - 1) / TH;
   p.g.kgroups = (a.Kout + NT * 16 - 1) / (NT * 16);
-  const long blocks = (long)a.N * p.g.tiles_x * p.g.tiles_y;
-  if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  const long tiles = (long)a.N * p.g.tiles_x * p.g.tiles_y;
+  if (tiles <= 0 || tiles * p.g.nchunks > 0x7fffffffL) return hipErrorInvalidValue;
+  const size_t lds = conv3x3c16_lds<NT>(p.g.nchunks);
+  if (lds > 160 * 1024) return hipErrorInvalidValue;
+  // persistent workgroups: as many as fit on the chip at once (LDS-limited), each walks tiles
+  long resident = (long)(160 * 1024 / lds);
+  if (resident > (NT == 1 ? 3 : 2)) resident = (NT == 1 ? 3 : 2);
+  long blocks = 256 * resident / p.g.kgroups;
+  if (blocks < 1) blocks = 1;
+  const long rounds = (tiles + blocks - 1) / blocks;
+  blocks = (tiles + rounds - 1) / rounds;   // same number of rounds, evenly filled
   dim3 grid((unsigned)blocks, (unsigned)p.g.kgroups, 1);
-  constexpr size_t lds = conv3x3c16_lds<NT, RP>();
-  if (!a.src_dz)
-    hipLaunchKernelGGL((conv3x3c16_kernel<NT, RP, 0>), grid, dim3(kThreads), lds, stream, p);
-  else if (a.src_pool == 2)
-    hipLaunchKernelGGL((conv3x3c16_kernel<NT, RP, 2>), grid, dim3(kThreads), lds, stream, p);
-  else
-    hipLaunchKernelGGL((conv3x3c16_kernel<NT, RP, 1>), grid, dim3(kThreads), lds, stream, p);
-  return hipGetLastError();
+  auto launch = [&](auto kern) -> hipError_t {
+    if (lds > 64 * 1024) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(WAVES * 64), lds, stream, p);
+    return hipGetLastError();
+  };
+  if (!a.src_dz) return launch(conv3x3c16_kernel<NT, WAVES, 0>);
+  if (a.src_pool == 2) return launch(conv3x3c16_kernel<NT, WAVES, 2>);
+  return launch(conv3x3c16_kernel<NT, WAVES, 1>);
 }
 
 }  // namespace
@@ -583,8 +649,10 @@ hipError_t launch_conv_engine(const ConvEngineArgs &a, hipStream_t stream) {
   const bool small = a.Hout <= 8;
   const int nt = a.Kout <= 16 ? 1 : (a.Kout <= 32 ? 2 : 3);
   if (!small && conv3x3c16_applies(a)) {
-    if (a.Kout <= 16) return launch_3x3<1, 2>(a, stream);
-    return launch_3x3<2, 2>(a, stream);   // wider layers run as groups of 32 output channels
+    // 16 output channels: 4 waves x 2 row pairs; 32: 8 waves x 1 row pair (more waves hide the
+    // longer per-step operand traffic better than more accumulators do)
+    if (a.Kout <= 16) return launch_3x3<1, 4>(a, stream);
+    return launch_3x3<2, 8>(a, stream);   // wider layers run as groups of 32 output channels
   }
   if (small) {
     if (nt == 1) return launch_t<1, 1>(a, stream);

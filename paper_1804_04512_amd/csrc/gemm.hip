@@ -6,7 +6,7 @@
 //   C(m,n) = sum_k A(m,k) * B(k,n),   A(m,k) = A[m*a_m + k*a_k],  B(k,n) = B[k*b_k + n*b_n]
 // with an optional act'(.) factor on A (dzh = dh * act'(h)), bias + activation, split-K with
 // a fixed-order second pass, and an optional in-place parameter update C_upd += step * C.
-// Workgroup tile 64 x 64 x 32, four wavefronts of 32 x 32 each.
+// Workgroup tile 128 x 64 x 32, four wavefronts of 64 x 32 each, register-prefetched k-tiles.
 #include "dll_internal.h"
 
 namespace dllk {
@@ -16,12 +16,17 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int BM = 64, BN = 64, BK = 32;
-constexpr int LDS_TILE = 64 * 80;   // floats per operand tile, covers both layouts (64*34 and 32*80)
+constexpr int BM = 128, BN = 64, BK = 32;
+constexpr int LDK = 34;                // [x][k] layout (k-contiguous sources): row stride
+constexpr int LDXA = 144, LDXB = 80;   // [k][x] layout (x-contiguous sources): row strides for 128 / 64 wide tiles
+constexpr int A_TILE = BK * LDXA;      // 4608 floats >= BM * LDK
+constexpr int B_TILE = BK * LDXB;      // 2560 floats >= BN * LDK
 
 struct GemmParams {
   GemmArgs a;
   int k_per_split;   // multiple of BK
+  int a_vec, b_vec;  // operand may be staged with 16-byte loads
+  int c_vec;         // epilogue may use 16-byte accesses along n
 };
 
 __device__ __forceinline__ float act_apply(int act, float z) {
@@ -35,44 +40,77 @@ __device__ __forceinline__ float act_deriv(int act, float out) {
   return 1.0f;
 }
 
-// Stage a 64 (x) by 32 (k) operand tile.  k-contiguous sources go to LDS as [x][34] (lanes
-// run along k), x-contiguous ones as [k][80] (lanes run along x): both are conflict-free for
-// the staging writes and for the MFMA operand reads.
-__device__ __forceinline__ void stage_tile(float *dst, const float *src, const float *src_out, int act,
-                                           long sx, long sk, int x0, int k0, int X, int Kend, bool kcontig) {
+__device__ __forceinline__ float4 load4(const float *src, long base, long stride, int i0, int limit, bool inrange, bool vec) {
+  float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (!inrange) return r;
+  if (vec && i0 + 3 < limit) return *reinterpret_cast<const float4 *>(src + base);
+  if (i0 < limit) r.x = src[base];
+  if (i0 + 1 < limit) r.y = src[base + stride];
+  if (i0 + 2 < limit) r.z = src[base + 2 * stride];
+  if (i0 + 3 < limit) r.w = src[base + 3 * stride];
+  return r;
+}
+
+// One operand tile (XT along x, 32 along k) travels global -> registers -> LDS.  A thread
+// carries groups of four elements that are neighbours along the source's contiguous axis:
+// k-contiguous sources land in LDS as [x][34], x-contiguous ones as [k][XT+16]; both layouts
+// give conflict-free MFMA operand reads.
+template <int XT>
+struct TileRegs {
+  static constexpr int NV = XT * BK / 4 / kThreads;   // float4 per thread: 4 (XT = 128) or 2 (XT = 64)
+  float4 v[NV];
+};
+
+template <int XT>
+__device__ __forceinline__ void tile_load(TileRegs<XT> &t, const float *src, const float *src_out, int act, long sx,
+                                          long sk, int x0, int k0, int X, int Kend, bool kcontig, bool vec) {
   const int tid = threadIdx.x;
-  if (kcontig) {
-    const int k = tid & 31, xb = tid >> 5;
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const int x = xb + it * 8;
-      float v = 0.0f;
-      if (x0 + x < X && k0 + k < Kend) {
-        const long o = (long)(x0 + x) * sx + (long)(k0 + k) * sk;
-        v = src[o];
-        if (src_out) v *= act_deriv(act, src_out[o]);
-      }
-      dst[x * 34 + k] = v;
+  for (int it = 0; it < TileRegs<XT>::NV; ++it) {
+    float4 v, o;
+    if (kcontig) {   // 8 threads cover the 32 k of one row; 32 rows per pass
+      const int x = x0 + (tid >> 3) + 32 * it, k = k0 + 4 * (tid & 7);
+      const long base = (long)x * sx + (long)k * sk;
+      v = load4(src, base, sk, k, Kend, x < X, vec);
+      if (src_out) o = load4(src_out, base, sk, k, Kend, x < X, vec);
+    } else {         // XT/4 threads cover one k row
+      constexpr int TPR = XT / 4, RPP = kThreads / TPR;
+      const int x = x0 + 4 * (tid % TPR), k = k0 + (tid / TPR) + RPP * it;
+      const long base = (long)x * sx + (long)k * sk;
+      v = load4(src, base, sx, x, X, k < Kend, vec);
+      if (src_out) o = load4(src_out, base, sx, x, X, k < Kend, vec);
     }
-  } else {
-    const int x = tid & 63, kb = tid >> 6;
+    if (src_out) {
+      v.x *= act_deriv(act, o.x); v.y *= act_deriv(act, o.y);
+      v.z *= act_deriv(act, o.z); v.w *= act_deriv(act, o.w);
+    }
+    t.v[it] = v;
+  }
+}
+
+template <int XT>
+__device__ __forceinline__ void tile_store(const TileRegs<XT> &t, float *dst, bool kcontig) {
+  const int tid = threadIdx.x;
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const int k = kb + it * 4;
-      float v = 0.0f;
-      if (x0 + x < X && k0 + k < Kend) {
-        const long o = (long)(x0 + x) * sx + (long)(k0 + k) * sk;
-        v = src[o];
-        if (src_out) v *= act_deriv(act, src_out[o]);
-      }
-      dst[k * 80 + x] = v;
+  for (int it = 0; it < TileRegs<XT>::NV; ++it) {
+    if (kcontig) {
+      float2 *d = reinterpret_cast<float2 *>(dst + ((tid >> 3) + 32 * it) * LDK + 4 * (tid & 7));
+      d[0] = make_float2(t.v[it].x, t.v[it].y);
+      d[1] = make_float2(t.v[it].z, t.v[it].w);
+    } else {
+      constexpr int TPR = XT / 4, RPP = kThreads / TPR;
+      *reinterpret_cast<float4 *>(dst + ((tid / TPR) + RPP * it) * (XT + 16) + 4 * (tid % TPR)) = t.v[it];
     }
   }
 }
 
-__global__ __launch_bounds__(kThreads) void gemm_kernel(const GemmParams p) {
-  __shared__ float As[LDS_TILE];
-  __shared__ float Bs[LDS_TILE];
+// Workgroup tile 128 (m) x 64 (n) x 32 (k), four wavefronts of 64 x 32.  The n axis rides on
+// the MFMA row axis, so a lane's four accumulator registers are four neighbouring columns of
+// C and leave (or update the parameters) as one 16-byte access.  The next k-tile's global
+// loads are in flight while the current one is multiplied (double-buffered LDS).
+__global__ __launch_bounds__(kThreads, 2) void gemm_kernel(const GemmParams p) {
+  __shared__ __attribute__((aligned(16))) float As[2][A_TILE];
+  __shared__ __attribute__((aligned(16))) float Bs[2][B_TILE];
   const GemmArgs &a = p.a;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i16 = lane & 15, kq = lane >> 4;
@@ -80,59 +118,96 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const GemmParams p) {
   const int kbeg = blockIdx.z * p.k_per_split;
   const int kend = min(a.Kdim, kbeg + p.k_per_split);
   const bool a_kc = (a.a_k == 1), b_kc = (a.b_k == 1);
-  const int alx = a_kc ? 34 : 1, alk = a_kc ? 1 : 80;
-  const int blx = b_kc ? 34 : 1, blk = b_kc ? 1 : 80;
-  const int wm = (wave >> 1) * 32, wn = (wave & 1) * 32;
+  const int alx = a_kc ? LDK : 1, alk = a_kc ? 1 : LDXA;
+  const int blx = b_kc ? LDK : 1, blk = b_kc ? 1 : LDXB;
+  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 32;
 
-  floatx4 acc[2][2];
+  floatx4 acc[4][2];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
+  TileRegs<BM> ta;
+  TileRegs<BN> tb;
+  if (kbeg < kend) {
+    tile_load<BM>(ta, a.A, a.A_out, a.a_act, a.a_m, a.a_k, m0, kbeg, a.M, kend, a_kc, p.a_vec);
+    tile_load<BN>(tb, a.B, nullptr, 0, a.b_n, a.b_k, n0, kbeg, a.N, kend, b_kc, p.b_vec);
+    tile_store<BM>(ta, As[0], a_kc);
+    tile_store<BN>(tb, Bs[0], b_kc);
+  }
+  __syncthreads();
+  int buf = 0;
   for (int k0 = kbeg; k0 < kend; k0 += BK) {
-    __syncthreads();
-    stage_tile(As, a.A, a.A_out, a.a_act, a.a_m, a.a_k, m0, k0, a.M, kend, a_kc);
-    stage_tile(Bs, a.B, nullptr, 0, a.b_n, a.b_k, n0, k0, a.N, kend, b_kc);
-    __syncthreads();
+    const bool more = k0 + BK < kend;
+    if (more) {
+      tile_load<BM>(ta, a.A, a.A_out, a.a_act, a.a_m, a.a_k, m0, k0 + BK, a.M, kend, a_kc, p.a_vec);
+      tile_load<BN>(tb, a.B, nullptr, 0, a.b_n, a.b_k, n0, k0 + BK, a.N, kend, b_kc, p.b_vec);
+    }
+    const float *Ab = As[buf] + (wm + i16) * alx + kq * alk;
+    const float *Bb = Bs[buf] + (wn + i16) * blx + kq * blk;
 #pragma unroll
     for (int s = 0; s < BK / 4; ++s) {
-      float af[2], bf[2];
+      float af[4], bf[2];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) af[i] = As[(wm + i * 16 + i16) * alx + (4 * s + kq) * alk];
+      for (int i = 0; i < 4; ++i) af[i] = Ab[i * 16 * alx + 4 * s * alk];
 #pragma unroll
-      for (int j = 0; j < 2; ++j) bf[j] = Bs[(wn + j * 16 + i16) * blx + (4 * s + kq) * blk];
+      for (int j = 0; j < 2; ++j) bf[j] = Bb[j * 16 * blx + 4 * s * blk];
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i], bf[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf[j], af[i], acc[i][j], 0, 0, 0);
     }
+    if (more) {
+      tile_store<BM>(ta, As[buf ^ 1], a_kc);
+      tile_store<BN>(tb, Bs[buf ^ 1], b_kc);
+    }
+    __syncthreads();
+    buf ^= 1;
   }
 
-  // lane holds C(m = 4*kq + v, n = i16) of each 16x16 tile
+  // lane holds C(m = i16, n = 4*kq + v) of each 16x16 tile
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < 4; ++i) {
+    const int m = m0 + wm + i * 16 + i16;
+    if (m >= a.M) continue;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      const int n = n0 + wn + j * 16 + i16;
+      const int n = n0 + wn + j * 16 + 4 * kq;
       if (n >= a.N) continue;
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int m = m0 + wm + i * 16 + 4 * kq + v;
-        if (m >= a.M) continue;
-        float c = acc[i][j][v];
-        if (a.split_k > 1) {
-          a.partial[((long)blockIdx.z * a.M + m) * a.N + n] = c;
+      float c[4] = {acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]};
+      if (a.split_k > 1) {
+        float *d = a.partial + ((long)blockIdx.z * a.M + m) * a.N + n;
+        if (n + 3 < a.N && (a.N & 3) == 0) {
+          *reinterpret_cast<float4 *>(d) = make_float4(c[0], c[1], c[2], c[3]);
         } else {
-          if (a.bias) c += a.bias[n];
-          c = act_apply(a.act, c);
-          const long o = (long)m * a.c_m + (long)n * a.c_n;
-          if (a.Cout) a.Cout[o] = c;
-          if (a.update) a.update[o] += a.step * c;
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            if (n + v < a.N) d[v] = c[v];
         }
+        continue;
+      }
+#pragma unroll
+      for (int v = 0; v < 4; ++v) c[v] = act_apply(a.act, c[v] + ((a.bias && n + v < a.N) ? a.bias[n + v] : 0.0f));
+      const long o = (long)m * a.c_m + (long)n * a.c_n;
+      if (p.c_vec && n + 3 < a.N) {
+        if (a.Cout) *reinterpret_cast<float4 *>(a.Cout + o) = make_float4(c[0], c[1], c[2], c[3]);
+        if (a.update) {
+          float4 u = *reinterpret_cast<float4 *>(a.update + o);
+          u.x += a.step * c[0]; u.y += a.step * c[1]; u.z += a.step * c[2]; u.w += a.step * c[3];
+          *reinterpret_cast<float4 *>(a.update + o) = u;
+        }
+      } else {
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+          if (n + v < a.N) {
+            if (a.Cout) a.Cout[o + v * a.c_n] = c[v];
+            if (a.update) a.update[o + v * a.c_n] += a.step * c[v];
+          }
       }
     }
+  }
 }
 
 __global__ __launch_bounds__(kThreads) void gemm_splitk_reduce_kernel(const GemmArgs a) {
@@ -149,19 +224,28 @@ __global__ __launch_bounds__(kThreads) void gemm_splitk_reduce_kernel(const Gemm
   }
 }
 
-// out[n] = sum_m A[m][n] * act'(Aout[m][n]);  one thread per column, fixed order.
+// out[n] = sum_m A[m][n] * act'(Aout[m][n]): 64 columns per workgroup, four row slices added
+// in a fixed order.
 __global__ __launch_bounds__(kThreads) void colsum_kernel(const float *A, const float *A_out, int act, int M, int N,
                                                          float *out, float *update, float step) {
-  const int n = blockIdx.x * kThreads + threadIdx.x;
-  if (n >= N) return;
+  __shared__ float part[4][64];
+  const int col = threadIdx.x & 63, slice = threadIdx.x >> 6;
+  const int n = blockIdx.x * 64 + col;
   float s = 0.0f;
-  for (int m = 0; m < M; ++m) {
-    float v = A[(long)m * N + n];
-    if (A_out) v *= act_deriv(act, A_out[(long)m * N + n]);
-    s += v;
+  if (n < N) {
+    for (int m = slice; m < M; m += 4) {
+      float v = A[(long)m * N + n];
+      if (A_out) v *= act_deriv(act, A_out[(long)m * N + n]);
+      s += v;
+    }
   }
-  if (out) out[n] = s;
-  if (update) update[n] += step * s;
+  part[slice][col] = s;
+  __syncthreads();
+  if (slice == 0 && n < N) {
+    s = (part[0][col] + part[1][col]) + (part[2][col] + part[3][col]);
+    if (out) out[n] = s;
+    if (update) update[n] += step * s;
+  }
 }
 
 __device__ __forceinline__ float block_reduce(float v, float *sh, bool is_max) {
@@ -258,7 +342,7 @@ int gemm_pick_split_k(int M, int N, int Kdim) {
   const long tiles = (long)((M + BM - 1) / BM) * ((N + BN - 1) / BN);
   const int ksteps = (Kdim + BK - 1) / BK;
   int split = 1;
-  while (tiles * split < 512 && split * 2 <= ksteps && split < 64) split *= 2;
+  while (tiles * split < 512 && split * 2 <= ksteps / 4 && split < 64) split *= 2;
   return split;
 }
 
@@ -268,6 +352,11 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream) {
   if (p.a.split_k < 1) p.a.split_k = 1;
   const int ksteps = (a.Kdim + BK - 1) / BK;
   p.k_per_split = ((ksteps + p.a.split_k - 1) / p.a.split_k) * BK;
+  auto al16 = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
+  // 16-byte loads need an aligned base and a leading stride of whole vectors
+  p.a_vec = al16(a.A) && (!a.A_out || al16(a.A_out)) && ((a.a_k == 1 ? a.a_m : a.a_k) % 4 == 0) && (a.a_k == 1 || a.a_m == 1);
+  p.b_vec = al16(a.B) && ((a.b_k == 1 ? a.b_n : a.b_k) % 4 == 0) && (a.b_k == 1 || a.b_n == 1);
+  p.c_vec = a.c_n == 1 && a.c_m % 4 == 0 && (!a.Cout || al16(a.Cout)) && (!a.update || al16(a.update));
   dim3 grid((a.N + BN - 1) / BN, (a.M + BM - 1) / BM, p.a.split_k);
   hipLaunchKernelGGL(gemm_kernel, grid, dim3(kThreads), 0, stream, p);
   hipError_t e = hipGetLastError();
@@ -284,7 +373,7 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream) {
 
 hipError_t launch_colsum(const float *A, const float *A_out, int a_act, int M, int N, float *out, float *update,
                          float step, hipStream_t stream) {
-  hipLaunchKernelGGL(colsum_kernel, dim3((N + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, A, A_out, a_act, M, N,
+  hipLaunchKernelGGL(colsum_kernel, dim3((N + 63) / 64), dim3(kThreads), 0, stream, A, A_out, a_act, M, N,
                      out, update, step);
   return hipGetLastError();
 }
