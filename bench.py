@@ -61,7 +61,14 @@ def event_time_ms(fn, iters, warm=2):
     return float(np.mean(t)), float(np.min(t))
 
 
-def engine_kernel_name(kout: int, hout: int) -> str:
+def engine_kernel_name(cs, backward: bool) -> str:
+    """Name of the kernel instance the library launches for a forward or backward-data pass
+    (mirrors the dispatch in csrc/conv_engine.hip; used only to group launches for the report)."""
+    cin, kout, hout = (cs.K, cs.C, cs.H) if backward else (cs.C, cs.K, cs.Ho)
+    same = cs.R == 3 and cs.S == 3 and cs.pad == 1
+    if same and cin % 16 == 0 and hout > 8 and cs.W % (8 if backward and cs.pool == 2 else 4) == 0:
+        src = 0 if not backward else (2 if cs.pool == 2 else 1)
+        return f"conv3x3c16_kernel<{1 if kout <= 16 else 2},{4 if kout <= 16 else 8},{src}>"
     nt = 1 if kout <= 16 else (2 if kout <= 32 else 3)
     return f"conv_engine_kernel<{nt},{1 if hout <= 8 else 2}>"
 
@@ -85,11 +92,11 @@ def conv_pass_table(B, wl_cnn, dev_params, x_dev, iters):
         flop = 2 * cs.macs_exact()
         y2, idx2 = torch.empty_like(y), torch.empty_like(idx)
         ms, _ = event_time_ms(lambda: B.dll_conv_valid_fwd(cs, xin, w, b, y2, idx2), iters)
-        table.append(dict(layer=l + 1, op="fwd", kernel=engine_kernel_name(cs.K, cs.Ho), ms=ms, flop=flop))
+        table.append(dict(layer=l + 1, op="fwd", kernel=engine_kernel_name(cs, False), ms=ms, flop=flop))
         if l > 0:
             dx = torch.empty(cs.x_shape, device="cuda")
             ms, _ = event_time_ms(lambda: B.dll_conv_full_bwd(cs, dy, y, idx, w, dx), iters)
-            table.append(dict(layer=l + 1, op="bwd_data", kernel=engine_kernel_name(cs.C, cs.H), ms=ms, flop=flop))
+            table.append(dict(layer=l + 1, op="bwd_data", kernel=engine_kernel_name(cs, True), ms=ms, flop=flop))
         ws = B.workspace(B.dll_conv_workspace_bytes(cs))
         dw, db = torch.empty_like(w), torch.empty_like(b)
         ms, _ = event_time_ms(lambda: B.dll_conv_valid_wgrad(cs, xin, dy, y, idx, dw, db, ws), iters)
