@@ -66,9 +66,13 @@ def engine_kernel_name(cs, backward: bool) -> str:
     (mirrors the dispatch in csrc/conv_engine.hip; used only to group launches for the report)."""
     cin, kout, hout = (cs.K, cs.C, cs.H) if backward else (cs.C, cs.K, cs.Ho)
     same = cs.R == 3 and cs.S == 3 and cs.pad == 1
-    if same and cin % 16 == 0 and hout > 8 and cs.W % (8 if backward and cs.pool == 2 else 4) == 0:
+    chunked = cin % 16 == 0 or cin <= 12
+    if same and chunked and hout > 8 and cs.W % (8 if backward and cs.pool == 2 else 4) == 0:
         src = 0 if not backward else (2 if cs.pool == 2 else 1)
-        return f"conv3x3c16_kernel<{1 if kout <= 16 else 2},{4 if kout <= 16 else 8},{src}>"
+        cc = 16 if cin % 16 == 0 else 4
+        nt = 1 if kout <= 16 else 2
+        waves = 8 if (cc == 16 and nt == 2) else 4
+        return f"conv3x3c16_kernel<{nt},{waves},{src},{cc}>"
     nt = 1 if kout <= 16 else (2 if kout <= 32 else 3)
     return f"conv_engine_kernel<{nt},{1 if hout <= 8 else 2}>"
 

@@ -310,10 +310,16 @@ hipError_t launch_t(const ConvEngineArgs &a, hipStream_t stream) {
 // ---------------------------------------------------------------------------------------
 constexpr int round_up_mod_c(int v, int m, int r) { return (v - (v % m) + r) < v ? (v - (v % m) + r + m) : (v - (v % m) + r); }
 
-template <int NT, int WAVES, int SRC>   // SRC: 0 plain tensor, 1 dz without pooling, 2 dz through 2x2 pooling
-__global__ __launch_bounds__(WAVES * 64, (NT == 1 ? 3 : 2) * WAVES / 4) void conv3x3c16_kernel(const EngineParams p) {
+// waves per SIMD the register budget is held to: LDS lets 3 (16 filters) or 2 (32 filters)
+// workgroups of the 16-channel instance share a CU, 4 of the 4-channel one
+constexpr int conv3x3_occupancy(int NT, int WAVES, int CC) { return (CC == 4 ? 4 : (NT == 1 ? 3 : 2)) * WAVES / 4; }
+
+// SRC: 0 plain tensor, 1 dz without pooling, 2 dz through 2x2 pooling.  CC: channels per chunk,
+// 16, or 4 for shallow inputs such as RGB images (surplus channels are staged as zeros).
+template <int NT, int WAVES, int SRC, int CC>
+__global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void conv3x3c16_kernel(const EngineParams p) {
   constexpr int NTHR = WAVES * 64, RP = 8 / WAVES;   // 16-row tile: every wave owns RP row pairs
-  constexpr int CC = 16, TH = 16, ROWS = TH + 2;
+  constexpr int TH = 16, ROWS = TH + 2, C4 = CC / 4;
   constexpr int RS = 36, PS = round_up_mod_c(RS * ROWS, 8, 2);
   constexpr int KC = CC * 9;
   // staging registers per thread: plain rows, or pooled rows (u = oy0/2 - 1 + pr, pr = 0 .. TH/2 + 1)
@@ -325,8 +331,8 @@ __global__ __launch_bounds__(WAVES * 64, (NT == 1 ? 3 : 2) * WAVES / 4) void con
   extern __shared__ float lds[];
   const ConvEngineArgs &a = p.a;
   const EngineGeom &g = p.g;
-  float *xs = lds;               // [16][PS]
-  float *wl = xs + CC * PS;      // [chunk][NT][144][16]
+  float *xs = lds;               // [CC][PS]
+  float *wl = xs + CC * PS;      // [chunk][NT][9*CC][16]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i16 = lane & 15, kq = lane >> 4;
@@ -335,16 +341,16 @@ __global__ __launch_bounds__(WAVES * 64, (NT == 1 ? 3 : 2) * WAVES / 4) void con
   const int work = tiles * g.nchunks;          // (tile, chunk) pairs, chunk fastest
   const int Hp = a.Hin >> 1, Wp = a.Win >> 1;  // SRC == 2 only
 
-  // ---- filter slices of every chunk, once per workgroup: wl[chunk][nt][rs*16 + cl][j]
+  // ---- filter slices of every chunk, once per workgroup: wl[chunk][nt][rs*CC + cl][j]
   for (int e = tid; e < g.nchunks * NT * KC * 16; e += NTHR) {
     const int j = e & 15, q = e >> 4;
     const int kk = q % KC, q2 = q / KC;
     const int nt = q2 % NT, chunk = q2 / NT;
-    const int cl = kk & 15, rs = kk >> 4;
+    const int cl = kk % CC, rs = kk / CC;
     const int r = rs / 3, s = rs - 3 * r;
     const int ko = ko0 + nt * 16 + j, ci = chunk * CC + cl;
     float v = 0.0f;
-    if (ko < a.Kout)
+    if (ko < a.Kout && ci < a.Cin)
       v = a.w_flip ? a.w[((ci * a.Kout + ko) * 3 + (2 - r)) * 3 + (2 - s)] : a.w[((ko * a.Cin + ci) * 3 + r) * 3 + s];
     wl[e] = v;
   }
@@ -370,7 +376,7 @@ __global__ __launch_bounds__(WAVES * 64, (NT == 1 ? 3 : 2) * WAVES / 4) void con
         const int gi = oy0 - 1 + row, gj = ox0 + 4 * j;
         vi[it] = make_float4(0.f, 0.f, 0.f, 0.f);
         yi[it] = vi[it];
-        if (line < LINES && gi >= 0 && gi < a.Hin && gj < a.Win) {
+        if (line < LINES && c0 + cl < a.Cin && gi >= 0 && gi < a.Hin && gj < a.Win) {
           const long o = ((long)(n * a.Cin + c0 + cl) * a.Hin + gi) * a.Win + gj;
           vi[it] = *reinterpret_cast<const float4 *>(a.src + o);
           if (SRC == 1 && a.src_act != ACT_IDENTITY) yi[it] = *reinterpret_cast<const float4 *>(a.src_y + o);
@@ -384,7 +390,7 @@ __global__ __launch_bounds__(WAVES * 64, (NT == 1 ? 3 : 2) * WAVES / 4) void con
         const int gi = oy0 - 1 + row, gj = side ? ox0 + kTileW : ox0 - 1;
         vh[it] = 0.0f;
         yh[it] = 0.0f;
-        if (line < LINES && gi >= 0 && gi < a.Hin && gj >= 0 && gj < a.Win) {
+        if (line < LINES && c0 + cl < a.Cin && gi >= 0 && gi < a.Hin && gj >= 0 && gj < a.Win) {
           const long o = ((long)(n * a.Cin + c0 + cl) * a.Hin + gi) * a.Win + gj;
           vh[it] = a.src[o];
           if (SRC == 1 && a.src_act != ACT_IDENTITY) yh[it] = a.src_y[o];
@@ -400,7 +406,7 @@ __global__ __launch_bounds__(WAVES * 64, (NT == 1 ? 3 : 2) * WAVES / 4) void con
         vi[it] = make_float4(0.f, 0.f, 0.f, 0.f);
         yi[it] = vi[it];
         ii[it] = make_uchar4(255, 255, 255, 255);
-        if (line < LINES && u >= 0 && u < Hp && v0 < Wp) {
+        if (line < LINES && c0 + cl < a.Cin && u >= 0 && u < Hp && v0 < Wp) {
           const long o = ((long)(n * a.Cin + c0 + cl) * Hp + u) * Wp + v0;
           vi[it] = *reinterpret_cast<const float4 *>(a.src + o);
           if (a.src_act != ACT_IDENTITY) yi[it] = *reinterpret_cast<const float4 *>(a.src_y + o);
@@ -414,7 +420,7 @@ __global__ __launch_bounds__(WAVES * 64, (NT == 1 ? 3 : 2) * WAVES / 4) void con
         const int cl = line / PR, pr = line - cl * PR;
         const int u = (oy0 >> 1) - 1 + pr, v0 = side ? (ox0 >> 1) + 16 : (ox0 >> 1) - 1;
         vh[it] = 0.0f; yh[it] = 0.0f; ih[it] = 255;
-        if (line < LINES && u >= 0 && u < Hp && v0 >= 0 && v0 < Wp) {
+        if (line < LINES && c0 + cl < a.Cin && u >= 0 && u < Hp && v0 >= 0 && v0 < Wp) {
           const long o = ((long)(n * a.Cin + c0 + cl) * Hp + u) * Wp + v0;
           vh[it] = a.src[o];
           if (a.src_act != ACT_IDENTITY) yh[it] = a.src_y[o];
@@ -553,28 +559,46 @@ __global__ __launch_bounds__(WAVES * 64, (NT == 1 ? 3 : 2) * WAVES / 4) void con
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
     load_frags(I0{}, a_tap, b_tap, 0);
+    if constexpr (C4 == 4) {
 #pragma unroll 1
-    for (int rs = 0; rs < 9; ++rs) {
-      const float *a_next = a_tap + ((rs % 3 == 2) ? RS - 2 : 1);   // next tap: s+1, or first column of the next filter row
-      const float *b_next = b_tap + 16 * 16;                          // 16 channels x 16 output channels per tap
-      load_frags(I1{}, a_tap, b_tap, 1);
-      __builtin_amdgcn_sched_barrier(0);
-      mfma_frags(I0{});
-      __builtin_amdgcn_sched_barrier(0);
-      load_frags(I0{}, a_tap, b_tap, 2);
-      __builtin_amdgcn_sched_barrier(0);
-      mfma_frags(I1{});
-      __builtin_amdgcn_sched_barrier(0);
-      load_frags(I1{}, a_tap, b_tap, 3);
-      __builtin_amdgcn_sched_barrier(0);
-      mfma_frags(I0{});
-      __builtin_amdgcn_sched_barrier(0);
-      if (rs < 8) load_frags(I0{}, a_next, b_next, 0);
-      __builtin_amdgcn_sched_barrier(0);
-      mfma_frags(I1{});
-      __builtin_amdgcn_sched_barrier(0);
-      a_tap = a_next;
-      b_tap = b_next;
+      for (int rs = 0; rs < 9; ++rs) {
+        const float *a_next = a_tap + ((rs % 3 == 2) ? RS - 2 : 1);   // next tap: s+1, or first column of the next filter row
+        const float *b_next = b_tap + CC * 16;                          // CC channels x 16 output channels per tap
+        load_frags(I1{}, a_tap, b_tap, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_frags(I0{});
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(I0{}, a_tap, b_tap, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_frags(I1{});
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(I1{}, a_tap, b_tap, 3);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_frags(I0{});
+        __builtin_amdgcn_sched_barrier(0);
+        if (rs < 8) load_frags(I0{}, a_next, b_next, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_frags(I1{});
+        __builtin_amdgcn_sched_barrier(0);
+        a_tap = a_next;
+        b_tap = b_next;
+      }
+    } else {
+      // one step per tap: nine steps, fully unrolled, tap offsets are immediates
+      auto tap_step = [&](auto rsc) {
+        constexpr int rs = decltype(rsc)::value;
+        if constexpr (rs < 8)
+          load_frags(std::integral_constant<int, (rs + 1) & 1>{}, a_tap + ((rs + 1) / 3) * RS + (rs + 1) % 3,
+                     b_tap + (rs + 1) * CC * 16, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_frags(std::integral_constant<int, rs & 1>{});
+        __builtin_amdgcn_sched_barrier(0);
+      };
+      tap_step(std::integral_constant<int, 0>{}); tap_step(std::integral_constant<int, 1>{});
+      tap_step(std::integral_constant<int, 2>{}); tap_step(std::integral_constant<int, 3>{});
+      tap_step(std::integral_constant<int, 4>{}); tap_step(std::integral_constant<int, 5>{});
+      tap_step(std::integral_constant<int, 6>{}); tap_step(std::integral_constant<int, 7>{});
+      tap_step(std::integral_constant<int, 8>{});
     }
     if (chunk + 1 == g.nchunks) {
       const int tx = tile % g.tiles_x;
@@ -586,9 +610,9 @@ __global__ __launch_bounds__(WAVES * 64, (NT == 1 ? 3 : 2) * WAVES / 4) void con
   }
 }
 
-template <int NT>
+template <int NT, int CC>
 size_t conv3x3c16_lds(int nchunks) {
-  return sizeof(float) * ((size_t)16 * round_up_mod_c(36 * 18, 8, 2) + (size_t)nchunks * NT * 144 * 16);
+  return sizeof(float) * ((size_t)CC * round_up_mod_c(36 * 18, 8, 2) + (size_t)nchunks * NT * 9 * CC * 16);
 }
 
 inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
@@ -596,7 +620,8 @@ inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 
 // The specialised kernel applies to 3x3 filters with one row/column of padding, channel
 // counts that are multiples of 16, rows that are whole 16-byte groups and aligned tensors.
 bool conv3x3c16_applies(const ConvEngineArgs &a) {
-  if (a.R != 3 || a.S != 3 || a.pad_h != 1 || a.pad_w != 1 || a.Cin % 16 != 0) return false;
+  if (a.R != 3 || a.S != 3 || a.pad_h != 1 || a.pad_w != 1) return false;
+  if (a.Cin % 16 != 0 && a.Cin > 12) return false;   // 16-channel chunks, or up to three 4-channel chunks
   if (a.Hout != a.Hin || a.Wout != a.Win) return false;
   if (!aligned16(a.src)) return false;
   if (a.src_dz) {
@@ -606,24 +631,25 @@ bool conv3x3c16_applies(const ConvEngineArgs &a) {
   return a.Win % 4 == 0;
 }
 
-template <int NT, int WAVES>
+template <int NT, int WAVES, int CC>
 hipError_t launch_3x3(const ConvEngineArgs &a, hipStream_t stream) {
   EngineParams p;
   p.a = a;
   constexpr int TH = 16;
   p.g = EngineGeom{};
-  p.g.CC = 16;
-  p.g.nchunks = a.Cin / 16;
+  p.g.CC = CC;
+  p.g.nchunks = (a.Cin + CC - 1) / CC;
   p.g.tiles_x = (a.Wout + kTileW - 1) / kTileW;
   p.g.tiles_y = (a.Hout + TH - 1) / TH;
   p.g.kgroups = (a.Kout + NT * 16 - 1) / (NT * 16);
   const long tiles = (long)a.N * p.g.tiles_x * p.g.tiles_y;
   if (tiles <= 0 || tiles * p.g.nchunks > 0x7fffffffL) return hipErrorInvalidValue;
-  const size_t lds = conv3x3c16_lds<NT>(p.g.nchunks);
+  const size_t lds = conv3x3c16_lds<NT, CC>(p.g.nchunks);
   if (lds > 160 * 1024) return hipErrorInvalidValue;
   // persistent workgroups: as many as fit on the chip at once (LDS-limited), each walks tiles
   long resident = (long)(160 * 1024 / lds);
-  if (resident > (NT == 1 ? 3 : 2)) resident = (NT == 1 ? 3 : 2);
+  constexpr long by_regs = conv3x3_occupancy(NT, WAVES, CC) / (WAVES / 4);
+  if (resident > by_regs) resident = by_regs;
   long blocks = 256 * resident / p.g.kgroups;
   if (blocks < 1) blocks = 1;
   const long rounds = (tiles + blocks - 1) / blocks;
@@ -637,9 +663,9 @@ hipError_t launch_3x3(const ConvEngineArgs &a, hipStream_t stream) {
     hipLaunchKernelGGL(kern, grid, dim3(WAVES * 64), lds, stream, p);
     return hipGetLastError();
   };
-  if (!a.src_dz) return launch(conv3x3c16_kernel<NT, WAVES, 0>);
-  if (a.src_pool == 2) return launch(conv3x3c16_kernel<NT, WAVES, 2>);
-  return launch(conv3x3c16_kernel<NT, WAVES, 1>);
+  if (!a.src_dz) return launch(conv3x3c16_kernel<NT, WAVES, 0, CC>);
+  if (a.src_pool == 2) return launch(conv3x3c16_kernel<NT, WAVES, 2, CC>);
+  return launch(conv3x3c16_kernel<NT, WAVES, 1, CC>);
 }
 
 }  // namespace
@@ -651,8 +677,12 @@ hipError_t launch_conv_engine(const ConvEngineArgs &a, hipStream_t stream) {
   if (!small && conv3x3c16_applies(a)) {
     // 16 output channels: 4 waves x 2 row pairs; 32: 8 waves x 1 row pair (more waves hide the
     // longer per-step operand traffic better than more accumulators do)
-    if (a.Kout <= 16) return launch_3x3<1, 4>(a, stream);
-    return launch_3x3<2, 8>(a, stream);   // wider layers run as groups of 32 output channels
+    if (a.Cin % 16 != 0) {
+      if (a.Kout <= 16) return launch_3x3<1, 4, 4>(a, stream);
+      return launch_3x3<2, 4, 4>(a, stream);
+    }
+    if (a.Kout <= 16) return launch_3x3<1, 4, 16>(a, stream);
+    return launch_3x3<2, 8, 16>(a, stream);   // wider layers run as groups of 32 output channels
   }
   if (small) {
     if (nt == 1) return launch_t<1, 1>(a, stream);
