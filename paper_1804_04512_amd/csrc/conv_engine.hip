@@ -513,10 +513,25 @@ __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void 
   const float *b_ptr = wl + kq * 16 + i16;
 
   // persistent loop over (tile, chunk) pairs; the next pair's global loads fly during the MFMA loop
-  const int q0 = blockIdx.x, qstep = gridDim.x * g.nchunks;   // whole tiles per workgroup
-  int q = q0 * g.nchunks;
-  if (q < work) load_regs(q);
-  while (q < work) {
+  // Tile order is XCD-aware: workgroup ids are dealt round-robin to the 8 XCDs, each with its
+  // own L2, so every XCD gets one contiguous eighth of the tiles and its workgroups stride
+  // through it together: tiles in flight on an XCD are neighbours, and the halo columns and
+  // cache-line halves they share meet in that XCD's L2.
+  const int G = gridDim.x, nx = (G % 8 == 0) ? 8 : 1;
+  const int xcd = blockIdx.x % nx, slot = blockIdx.x / nx, slots = G / nx;
+  const int per_xcd = (tiles + nx - 1) / nx;
+  const int tile_lim = min(tiles, (xcd + 1) * per_xcd);
+  int cur_tile = xcd * per_xcd + slot;
+  int q = cur_tile * g.nchunks;
+  const auto next_q = [&](int qq) {   // next (tile, chunk) pair of this workgroup, or `work` when done
+    const int t = qq / g.nchunks, c = qq - t * g.nchunks;
+    if (c + 1 < g.nchunks) return qq + 1;
+    return t + slots < tile_lim ? (t + slots) * g.nchunks : work;
+  };
+  if (cur_tile >= tile_lim) q = work;
+  const int work_end = work;
+  if (q < work_end) load_regs(q);
+  while (q < work_end) {
     const int tile = q / g.nchunks, chunk = q - tile * g.nchunks;
     if (chunk == 0) {
 #pragma unroll
@@ -529,8 +544,8 @@ __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void 
     __syncthreads();   // previous MFMA loop no longer reads the tile (first pass: filters are staged)
     store_regs();
     __syncthreads();
-    const int qn = (chunk + 1 < g.nchunks) ? q + 1 : q - chunk + qstep;
-    if (qn < work) load_regs(qn);
+    const int qn = next_q(q);
+    if (qn < work_end) load_regs(qn);
     // ---- MFMA: 9 taps x 4 channel groups; inside a tap every address is base + immediate.
     // Operand fragments are double-buffered in registers: the LDS reads of step t+1 are issued
     // before the MFMAs of step t, and scheduling barriers keep that order.
@@ -654,6 +669,7 @@ hipError_t launch_3x3(const ConvEngineArgs &a, hipStream_t stream) {
   if (blocks < 1) blocks = 1;
   const long rounds = (tiles + blocks - 1) / blocks;
   blocks = (tiles + rounds - 1) / rounds;   // same number of rounds, evenly filled
+  if (blocks >= 8) blocks = (blocks + 7) / 8 * 8;   // whole rows of XCDs (see the tile order in the kernel)
   dim3 grid((unsigned)blocks, (unsigned)p.g.kgroups, 1);
   auto launch = [&](auto kern) -> hipError_t {
     if (lds > 64 * 1024) {

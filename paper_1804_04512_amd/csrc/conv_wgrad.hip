@@ -15,6 +15,8 @@
 // bit-identical from run to run) and can apply the parameter update in the same pass.
 #include "dll_internal.h"
 
+#include <type_traits>
+
 namespace dllk {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -114,62 +116,105 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
 
   TileRegs<MTF, POOL> tr;
 
+  // ---- fast path: everything about a thread's staging slots that does not depend on the
+  // tile (which element of the tile it moves, where it lands in LDS) is worked out once here;
+  // per tile only a scalar base and a few range checks remain.
+  constexpr int kUnused = -(1 << 20);
+  const int j4 = 4 * (tid & 7);      // interior: first column of the thread's 16-byte group
+  int xo[NXI], xl[NXI], xrow[NXI];   // interior slots: global offset from the tile origin, LDS offset, tile row
+  int ho[NXH], hl[NXH], hrow[NXH], hcol[NXH];
+  int dzo[DZR], dzl[DZR];            // dz slots: global offset from the tile's first pooled element, LDS offset
+  bool dzk[DZR];
+  int du = 0, dv = 0;
+  if (FAST) {
+#pragma unroll
+    for (int it = 0; it < NXI; ++it) {
+      const int e = tid + it * kThreads;
+      const int line = e >> 3;
+      const int cl = (line * p.inv_rows) >> 16, row = line - cl * p.rows;
+      const bool ok = line < lines && c0 + cl < a.C;
+      xo[it] = (cl * a.H + row) * a.W + j4;
+      xl[it] = cl * p.PS + row * p.RS + a.pad + p.shift + j4;
+      xrow[it] = ok ? row : kUnused;
+      if (line >= lines) xl[it] = -1;   // slot beyond the tile: nothing to store
+    }
+    const int nh = a.S - 1;
+#pragma unroll
+    for (int it = 0; it < NXH; ++it) {
+      const int e = tid + it * kThreads;
+      const int line = nh > 0 ? e / nh : lines, hc = nh > 0 ? e - line * nh : 0;
+      const int cl = (line * p.inv_rows) >> 16, row = line - cl * p.rows;
+      const bool ok = line < lines && c0 + cl < a.C;
+      hcol[it] = hc < a.pad ? hc - a.pad : kTileW + hc - a.pad;   // column relative to the tile's first output column
+      ho[it] = (cl * a.H + row) * a.W + hcol[it];
+      hl[it] = line < lines ? cl * p.PS + row * p.RS + (hc < a.pad ? hc : kTileW + hc) + p.shift : -1;
+      hrow[it] = ok ? row : kUnused;
+    }
+    if (POOL == 2) {
+      const int q = tid & 15;
+      du = q >> 2;
+      dv = (q & 3) * 4;
+#pragma unroll
+      for (int rd = 0; rd < DZR; ++rd) {
+        const int k = rd * 16 + (tid >> 4);
+        dzk[rd] = k < kcount;
+        dzo[rd] = ((k0 + k) * (p.Ho >> 1) + du) * (p.Wo >> 1) + dv;
+        dzl[rd] = k * PSZ + 2 * du * kTileW + 2 * dv;
+      }
+    } else {
+      const int q = tid & 63;
+      du = q >> 3;
+      dv = (q & 7) * 4;
+#pragma unroll
+      for (int rd = 0; rd < DZR; ++rd) {
+        const int k = rd * 4 + (tid >> 6);
+        dzk[rd] = k < kcount;
+        dzo[rd] = ((k0 + k) * p.Ho + du) * p.Wo + dv;
+        dzl[rd] = k * PSZ + du * kTileW + dv;
+      }
+    }
+  }
+
   // ---- fast path, step 1: global -> registers for one tile
   auto load_tile = [&](int item) {
     const int tx = item % p.tiles_x;
     const int ty = (item / p.tiles_x) % p.tiles_y;
     const int n = item / (p.tiles_x * p.tiles_y);
     const int oy0 = ty * TH, ox0 = tx * kTileW;
+    const float *xp = a.x + (((long)n * a.C + c0) * a.H + (oy0 - a.pad)) * a.W + ox0;
+    const bool col_ok = ox0 + j4 < a.W;
 #pragma unroll
     for (int it = 0; it < NXI; ++it) {
-      const int e = tid + it * kThreads;
-      const int j = e & 7, line = e >> 3;
-      const int cl = (line * p.inv_rows) >> 16, row = line - cl * p.rows;
-      const int gi = oy0 - a.pad + row, gj = ox0 + 4 * j, ci = c0 + cl;
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (line < lines && ci < a.C && gi >= 0 && gi < a.H && gj < a.W)
-        v = *reinterpret_cast<const float4 *>(a.x + ((long)(n * a.C + ci) * a.H + gi) * a.W + gj);
+      if ((unsigned)(oy0 - a.pad + xrow[it]) < (unsigned)a.H && col_ok) v = *reinterpret_cast<const float4 *>(xp + xo[it]);
       tr.xi[it] = v;
     }
-    const int nh = a.S - 1;
 #pragma unroll
     for (int it = 0; it < NXH; ++it) {
-      const int e = tid + it * kThreads;
       float v = 0.0f;
-      if (nh > 0) {
-        const int line = e / nh, hc = e - line * nh;
-        const int cl = (line * p.inv_rows) >> 16, row = line - cl * p.rows;
-        const int gi = oy0 - a.pad + row, ci = c0 + cl;
-        const int gj = hc < a.pad ? ox0 - a.pad + hc : ox0 + kTileW + (hc - a.pad);
-        if (line < lines && ci < a.C && gi >= 0 && gi < a.H && gj >= 0 && gj < a.W)
-          v = a.x[((long)(n * a.C + ci) * a.H + gi) * a.W + gj];
-      }
+      if ((unsigned)(oy0 - a.pad + hrow[it]) < (unsigned)a.H && (unsigned)(ox0 + hcol[it]) < (unsigned)a.W) v = xp[ho[it]];
       tr.xh[it] = v;
+    }
+    long dbase;
+    bool in;
+    if (POOL == 2) {
+      const int Hp = p.Ho >> 1, Wp = p.Wo >> 1;
+      dbase = ((long)n * a.K * Hp + (oy0 >> 1)) * Wp + (ox0 >> 1);
+      in = (oy0 >> 1) + du < Hp && (ox0 >> 1) + dv < Wp;
+    } else {
+      dbase = ((long)n * a.K * p.Ho + oy0) * p.Wo + ox0;
+      in = oy0 + du < p.Ho && ox0 + dv < p.Wo;
     }
 #pragma unroll
     for (int rd = 0; rd < DZR; ++rd) {
-      float4 dv = make_float4(0.f, 0.f, 0.f, 0.f), yv = dv;
+      float4 dv4 = make_float4(0.f, 0.f, 0.f, 0.f), yv = dv4;
       uchar4 iv = make_uchar4(255, 255, 255, 255);
-      if (POOL == 2) {
-        const int k = rd * 16 + (tid >> 4), q = tid & 15;
-        const int u = (oy0 >> 1) + (q >> 2), v0 = (ox0 >> 1) + (q & 3) * 4;
-        const int Hp = p.Ho >> 1, Wp = p.Wo >> 1;
-        if (k < kcount && u < Hp && v0 < Wp) {
-          const long o = ((long)(n * a.K + k0 + k) * Hp + u) * Wp + v0;
-          dv = *reinterpret_cast<const float4 *>(a.dy + o);
-          if (a.act != ACT_IDENTITY) yv = *reinterpret_cast<const float4 *>(a.y + o);
-          iv = *reinterpret_cast<const uchar4 *>(a.idx + o);
-        }
-      } else {
-        const int k = rd * 4 + (tid >> 6), q = tid & 63;
-        const int gi = oy0 + (q >> 3), gj = ox0 + (q & 7) * 4;
-        if (k < kcount && gi < p.Ho && gj < p.Wo) {
-          const long o = ((long)(n * a.K + k0 + k) * p.Ho + gi) * p.Wo + gj;
-          dv = *reinterpret_cast<const float4 *>(a.dy + o);
-          if (a.act != ACT_IDENTITY) yv = *reinterpret_cast<const float4 *>(a.y + o);
-        }
+      if (in && dzk[rd]) {
+        dv4 = *reinterpret_cast<const float4 *>(a.dy + dbase + dzo[rd]);
+        if (a.act != ACT_IDENTITY) yv = *reinterpret_cast<const float4 *>(a.y + dbase + dzo[rd]);
+        if (POOL == 2) iv = *reinterpret_cast<const uchar4 *>(a.idx + dbase + dzo[rd]);
       }
-      tr.dyv[rd] = dv; tr.yv[rd] = yv; tr.iv[rd] = iv;
+      tr.dyv[rd] = dv4; tr.yv[rd] = yv; tr.iv[rd] = iv;
     }
   };
 
@@ -177,57 +222,38 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
   auto store_tile = [&]() {
 #pragma unroll
     for (int it = 0; it < NXI; ++it) {
-      const int e = tid + it * kThreads;
-      const int j = e & 7, line = e >> 3;
-      if (line < lines) {
-        const int cl = (line * p.inv_rows) >> 16, row = line - cl * p.rows;
-        float2 *d = reinterpret_cast<float2 *>(xs + cl * p.PS + row * p.RS + a.pad + p.shift + 4 * j);
+      if (xl[it] >= 0) {
+        float2 *d = reinterpret_cast<float2 *>(xs + xl[it]);
         d[0] = make_float2(tr.xi[it].x, tr.xi[it].y);
         d[1] = make_float2(tr.xi[it].z, tr.xi[it].w);
       }
     }
-    const int nh = a.S - 1;
-    if (nh > 0) {
 #pragma unroll
-      for (int it = 0; it < NXH; ++it) {
-        const int e = tid + it * kThreads;
-        const int line = e / nh, hc = e - line * nh;
-        if (line < lines) {
-          const int cl = (line * p.inv_rows) >> 16, row = line - cl * p.rows;
-          const int col = hc < a.pad ? hc : kTileW + hc;
-          xs[cl * p.PS + row * p.RS + col + p.shift] = tr.xh[it];
-        }
-      }
-    }
+    for (int it = 0; it < NXH; ++it)
+      if (hl[it] >= 0) xs[hl[it]] = tr.xh[it];
 #pragma unroll
     for (int rd = 0; rd < DZR; ++rd) {
+      if (!dzk[rd]) continue;
       const float gv[4] = {tr.dyv[rd].x, tr.dyv[rd].y, tr.dyv[rd].z, tr.dyv[rd].w};
       const float ov[4] = {tr.yv[rd].x, tr.yv[rd].y, tr.yv[rd].z, tr.yv[rd].w};
       float g[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) g[e] = a.act != ACT_IDENTITY ? gv[e] * act_deriv(a.act, ov[e]) : gv[e];
+      float *d = dzs + dzl[rd];
       if (POOL == 2) {
-        const int k = rd * 16 + (tid >> 4), q = tid & 15;
-        if (k < kcount) {
-          const unsigned char pos[4] = {tr.iv[rd].x, tr.iv[rd].y, tr.iv[rd].z, tr.iv[rd].w};
-          float *d = dzs + k * PSZ + (2 * (q >> 2)) * kTileW + 8 * (q & 3);
+        const unsigned char pos[4] = {tr.iv[rd].x, tr.iv[rd].y, tr.iv[rd].z, tr.iv[rd].w};
 #pragma unroll
-          for (int wa = 0; wa < 2; ++wa)
+        for (int wa = 0; wa < 2; ++wa)
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-              *reinterpret_cast<float2 *>(d + wa * kTileW + 2 * e) =
-                  make_float2(pos[e] == 2 * wa ? g[e] : 0.0f, pos[e] == 2 * wa + 1 ? g[e] : 0.0f);
-          dbacc[rd] += ((pos[0] < 4 ? g[0] : 0.f) + (pos[1] < 4 ? g[1] : 0.f)) +
-                       ((pos[2] < 4 ? g[2] : 0.f) + (pos[3] < 4 ? g[3] : 0.f));
-        }
+          for (int e = 0; e < 4; ++e)
+            *reinterpret_cast<float2 *>(d + wa * kTileW + 2 * e) =
+                make_float2(pos[e] == 2 * wa ? g[e] : 0.0f, pos[e] == 2 * wa + 1 ? g[e] : 0.0f);
+        dbacc[rd] += ((pos[0] < 4 ? g[0] : 0.f) + (pos[1] < 4 ? g[1] : 0.f)) +
+                     ((pos[2] < 4 ? g[2] : 0.f) + (pos[3] < 4 ? g[3] : 0.f));
       } else {
-        const int k = rd * 4 + (tid >> 6), q = tid & 63;
-        if (k < kcount) {
-          float2 *d = reinterpret_cast<float2 *>(dzs + k * PSZ + (q >> 3) * kTileW + (q & 7) * 4);
-          d[0] = make_float2(g[0], g[1]);
-          d[1] = make_float2(g[2], g[3]);
-          dbacc[rd] += (g[0] + g[1]) + (g[2] + g[3]);
-        }
+        reinterpret_cast<float2 *>(d)[0] = make_float2(g[0], g[1]);
+        reinterpret_cast<float2 *>(d)[1] = make_float2(g[2], g[3]);
+        dbacc[rd] += (g[0] + g[1]) + (g[2] + g[3]);
       }
     }
   };
@@ -267,30 +293,54 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
     }
   };
 
-  if (FAST && gidx < p.items) load_tile(gidx);
-  for (int item = gidx; item < p.items; item += p.G) {
+  // Tile order is XCD-aware: workgroup ids are dealt round-robin to the 8 XCDs, each with its
+  // own L2, so every XCD gets one contiguous eighth of the tiles and its workgroups stride
+  // through it together: tiles in flight on an XCD are neighbours (shared halo rows and the
+  // two halves of shared cache lines meet in that XCD's L2).
+  const int nx = (p.G % 8 == 0) ? 8 : 1;
+  const int xcd = gidx % nx, slot = gidx / nx, slots = p.G / nx;
+  const int per_xcd = (p.items + nx - 1) / nx;
+  const int item_base = xcd * per_xcd, item_lim = min(p.items, item_base + per_xcd);
+  if (FAST && item_base + slot < item_lim) load_tile(item_base + slot);
+  for (int item = item_base + slot; item < item_lim; item += slots) {
     __syncthreads();   // the previous tile's MFMA reads are done
     if (FAST) store_tile(); else stage_generic(item);
     __syncthreads();
-    if (FAST && item + p.G < p.items) load_tile(item + p.G);   // in flight during the MFMA loop
-    // ---- MFMA: 4 neighbouring pixels per step
+    if (FAST && item + slots < item_lim) load_tile(item + slots);   // in flight during the MFMA loop
+    // ---- MFMA: 4 neighbouring pixels per step.  Operand fragments are double-buffered in
+    // registers: the LDS reads of step t+1 are issued before the MFMAs of step t.
+    {
+      float af[2][MTF], bf[2][NTT];
+      const float *za = dzs + (wave * RW) * kTileW + kq;
+      const float *xb = xs + (wave * RW) * p.RS + kq;
+      auto load_frags = [&](auto bufc, int rr, int cg) {
+        constexpr int B_ = decltype(bufc)::value;
 #pragma unroll
-    for (int rr = 0; rr < RW; ++rr) {
-      const int row = wave * RW + rr;
-      const float *za = dzs + row * kTileW + kq;
-      const float *xb = xs + row * p.RS + kq;
+        for (int mf = 0; mf < MTF; ++mf) af[B_][mf] = za[fplane[mf] + rr * kTileW + 4 * cg];
 #pragma unroll
-      for (int cg = 0; cg < 8; ++cg) {
-        float af[MTF], bf[NTT];
-#pragma unroll
-        for (int mf = 0; mf < MTF; ++mf) af[mf] = za[fplane[mf] + 4 * cg];
-#pragma unroll
-        for (int nt = 0; nt < NTT; ++nt) bf[nt] = xb[tapoff[nt] + 4 * cg];
+        for (int nt = 0; nt < NTT; ++nt) bf[B_][nt] = xb[tapoff[nt] + rr * p.RS + 4 * cg];
+      };
+      auto mfma_frags = [&](auto bufc) {
+        constexpr int B_ = decltype(bufc)::value;
 #pragma unroll
         for (int mf = 0; mf < MTF; ++mf)
 #pragma unroll
           for (int nt = 0; nt < NTT; ++nt)
-            acc[mf][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[mf], bf[nt], acc[mf][nt], 0, 0, 0);
+            acc[mf][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[B_][mf], bf[B_][nt], acc[mf][nt], 0, 0, 0);
+      };
+      using I0 = std::integral_constant<int, 0>;
+      using I1 = std::integral_constant<int, 1>;
+      load_frags(I0{}, 0, 0);
+#pragma unroll
+      for (int t = 0; t < RW * 8; t += 2) {
+        load_frags(I1{}, (t + 1) >> 3, (t + 1) & 7);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_frags(I0{});
+        __builtin_amdgcn_sched_barrier(0);
+        if (t + 2 < RW * 8) load_frags(I0{}, (t + 2) >> 3, (t + 2) & 7);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_frags(I1{});
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
   }
@@ -457,8 +507,13 @@ inline Geom x_geom(int R, int S, int pad) {
   g.rows = TH + R - 1;
   g.cols = kTileW + S - 1;
   g.shift = pad & 1;
-  g.RS = round_up_mod(g.cols + g.shift, 32, 6);
-  g.PS = g.RS * g.rows;
+  // A 16-tap operand tile touches consecutive (channel, filter row) lines of the halo tile,
+  // S + 1 neighbouring columns of each (tap s plus the two pixels of a half wave): spacing the
+  // lines S + 1 (rounded up to even) banks apart keeps those reads free of bank conflicts.
+  const int sp = (S + 2) & ~1;
+  g.RS = round_up_mod(g.cols + g.shift, 32, sp % 32);
+  g.PS = round_up_mod(g.RS * g.rows, 32, (sp * R) % 32);
+  if (g.PS & 1) ++g.PS;   // keeps 8-byte alignment of the vector stores
   return g;
 }
 
@@ -495,9 +550,16 @@ bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, WgradP
   const int tiles_x = (Wo + kTileW - 1) / kTileW, tiles_y = (Ho + TH - 1) / TH;
   const long items = (long)N * tiles_x * tiles_y;
   const int kgroups = (K + mtf * 16 - 1) / (mtf * 16);
-  long G = 512 / ((long)plan->nchunks * kgroups);
+  // persistent workgroups: as many as stay resident (LDS and register budget), at least two
+  // tiles each where the problem is large enough
+  long resident = (long)(160 * 1024 / plan->lds_bytes);
+  const long by_regs = best_ntt <= 5 ? 4 : (best_ntt <= 7 ? 3 : 2);
+  if (resident > by_regs) resident = by_regs;
+  if (resident < 1) resident = 1;
+  long G = 256 * resident / ((long)plan->nchunks * kgroups);
   if (G < 1) G = 1;
-  if (G > items) G = items;
+  if (G > (items + 1) / 2) G = (items + 1) / 2;
+  if (G < 1) G = 1;
   plan->G = (int)G;
   plan->n_partials = plan->G;
   const size_t blockf = (size_t)mtf * plan->NTT * 256;
