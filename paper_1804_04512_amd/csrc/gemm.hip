@@ -61,6 +61,43 @@ struct TileRegs {
   float4 v[NV];
 };
 
+// Vector path: every slot is one unconditional 16-byte load from a clamped address followed by
+// a select, so the compiler issues all loads of a tile back to back (no branch, no wait between
+// them).  It requires whole 16-byte groups along the contiguous axis (checked on the host).
+template <int XT, bool KC, bool HAS_OUT>
+__device__ __forceinline__ void tile_load_vec(TileRegs<XT> &t, const float *src, const float *src_out, int act, long sx,
+                                              long sk, int x0, int k0, int X, int Kend) {
+  const int tid = threadIdx.x;
+  float4 v[TileRegs<XT>::NV], o[TileRegs<XT>::NV];
+  bool ok[TileRegs<XT>::NV];
+#pragma unroll
+  for (int it = 0; it < TileRegs<XT>::NV; ++it) {
+    int x, k;
+    if (KC) {   // 8 threads cover the 32 k of one row; 32 rows per pass
+      x = x0 + (tid >> 3) + 32 * it;
+      k = k0 + 4 * (tid & 7);
+    } else {    // XT/4 threads cover one k row
+      constexpr int TPR = XT / 4, RPP = kThreads / TPR;
+      x = x0 + 4 * (tid % TPR);
+      k = k0 + (tid / TPR) + RPP * it;
+    }
+    ok[it] = x < X && k < Kend;
+    const long base = ok[it] ? (long)x * sx + (long)k * sk : 0;
+    v[it] = *reinterpret_cast<const float4 *>(src + base);
+    if (HAS_OUT) o[it] = *reinterpret_cast<const float4 *>(src_out + base);
+  }
+#pragma unroll
+  for (int it = 0; it < TileRegs<XT>::NV; ++it) {
+    float4 r = v[it];
+    if (HAS_OUT) {
+      r.x *= act_deriv(act, o[it].x); r.y *= act_deriv(act, o[it].y);
+      r.z *= act_deriv(act, o[it].z); r.w *= act_deriv(act, o[it].w);
+    }
+    t.v[it] = ok[it] ? r : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+}
+
+// Generic path: any strides, any alignment, ragged edges (element-wise with range checks).
 template <int XT>
 __device__ __forceinline__ void tile_load(TileRegs<XT> &t, const float *src, const float *src_out, int act, long sx,
                                           long sk, int x0, int k0, int X, int Kend, bool kcontig, bool vec) {
@@ -68,12 +105,12 @@ __device__ __forceinline__ void tile_load(TileRegs<XT> &t, const float *src, con
 #pragma unroll
   for (int it = 0; it < TileRegs<XT>::NV; ++it) {
     float4 v, o;
-    if (kcontig) {   // 8 threads cover the 32 k of one row; 32 rows per pass
+    if (kcontig) {
       const int x = x0 + (tid >> 3) + 32 * it, k = k0 + 4 * (tid & 7);
       const long base = (long)x * sx + (long)k * sk;
       v = load4(src, base, sk, k, Kend, x < X, vec);
       if (src_out) o = load4(src_out, base, sk, k, Kend, x < X, vec);
-    } else {         // XT/4 threads cover one k row
+    } else {
       constexpr int TPR = XT / 4, RPP = kThreads / TPR;
       const int x = x0 + 4 * (tid % TPR), k = k0 + (tid / TPR) + RPP * it;
       const long base = (long)x * sx + (long)k * sk;
@@ -108,6 +145,9 @@ __device__ __forceinline__ void tile_store(const TileRegs<XT> &t, float *dst, bo
 // the MFMA row axis, so a lane's four accumulator registers are four neighbouring columns of
 // C and leave (or update the parameters) as one 16-byte access.  The next k-tile's global
 // loads are in flight while the current one is multiplied (double-buffered LDS).
+// FAST: both operands take the vector path (A_KC / B_KC say which axis is contiguous, A_OUT
+// whether the act' factor is applied); otherwise the generic loader is used.
+template <bool FAST, bool A_KC, bool B_KC, bool A_OUT>
 __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(const GemmParams p) {
   __shared__ __attribute__((aligned(16))) float As[2][A_TILE];
   __shared__ __attribute__((aligned(16))) float Bs[2][B_TILE];
@@ -117,7 +157,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(const GemmParams p) {
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
   const int kbeg = blockIdx.z * p.k_per_split;
   const int kend = min(a.Kdim, kbeg + p.k_per_split);
-  const bool a_kc = (a.a_k == 1), b_kc = (a.b_k == 1);
+  const bool a_kc = FAST ? A_KC : (a.a_k == 1), b_kc = FAST ? B_KC : (a.b_k == 1);
   const int alx = a_kc ? LDK : 1, alk = a_kc ? 1 : LDXA;
   const int blx = b_kc ? LDK : 1, blk = b_kc ? 1 : LDXB;
   const int wm = (wave >> 1) * 64, wn = (wave & 1) * 32;
@@ -130,9 +170,17 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(const GemmParams p) {
 
   TileRegs<BM> ta;
   TileRegs<BN> tb;
+  auto load_tiles = [&](int k0) {
+    if (FAST) {
+      tile_load_vec<BM, A_KC, A_OUT>(ta, a.A, a.A_out, a.a_act, a.a_m, a.a_k, m0, k0, a.M, kend);
+      tile_load_vec<BN, B_KC, false>(tb, a.B, nullptr, 0, a.b_n, a.b_k, n0, k0, a.N, kend);
+    } else {
+      tile_load<BM>(ta, a.A, a.A_out, a.a_act, a.a_m, a.a_k, m0, k0, a.M, kend, a_kc, p.a_vec);
+      tile_load<BN>(tb, a.B, nullptr, 0, a.b_n, a.b_k, n0, k0, a.N, kend, b_kc, p.b_vec);
+    }
+  };
   if (kbeg < kend) {
-    tile_load<BM>(ta, a.A, a.A_out, a.a_act, a.a_m, a.a_k, m0, kbeg, a.M, kend, a_kc, p.a_vec);
-    tile_load<BN>(tb, a.B, nullptr, 0, a.b_n, a.b_k, n0, kbeg, a.N, kend, b_kc, p.b_vec);
+    load_tiles(kbeg);
     tile_store<BM>(ta, As[0], a_kc);
     tile_store<BN>(tb, Bs[0], b_kc);
   }
@@ -140,10 +188,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(const GemmParams p) {
   int buf = 0;
   for (int k0 = kbeg; k0 < kend; k0 += BK) {
     const bool more = k0 + BK < kend;
-    if (more) {
-      tile_load<BM>(ta, a.A, a.A_out, a.a_act, a.a_m, a.a_k, m0, k0 + BK, a.M, kend, a_kc, p.a_vec);
-      tile_load<BN>(tb, a.B, nullptr, 0, a.b_n, a.b_k, n0, k0 + BK, a.N, kend, b_kc, p.b_vec);
-    }
+    if (more) load_tiles(k0 + BK);
     const float *Ab = As[buf] + (wm + i16) * alx + kq * alk;
     const float *Bb = Bs[buf] + (wn + i16) * blx + kq * blk;
 #pragma unroll
@@ -358,7 +403,22 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream) {
   p.b_vec = al16(a.B) && ((a.b_k == 1 ? a.b_n : a.b_k) % 4 == 0) && (a.b_k == 1 || a.b_n == 1);
   p.c_vec = a.c_n == 1 && a.c_m % 4 == 0 && (!a.Cout || al16(a.Cout)) && (!a.update || al16(a.update));
   dim3 grid((a.N + BN - 1) / BN, (a.M + BM - 1) / BM, p.a.split_k);
-  hipLaunchKernelGGL(gemm_kernel, grid, dim3(kThreads), 0, stream, p);
+  // whole 16-byte groups along each operand's contiguous axis, and the k ranges of the splits
+  // start on multiples of 32: then both operands take the branch-free vector loader
+  const bool a_kc = a.a_k == 1, b_kc = a.b_k == 1;
+  const bool fast = p.a_vec && p.b_vec && (a_kc ? a.Kdim % 4 == 0 : a.M % 4 == 0) && (b_kc ? a.Kdim % 4 == 0 : a.N % 4 == 0);
+  const bool has_out = a.A_out != nullptr;
+#define DLL_GEMM_LAUNCH(F, AK, BK_, AO) hipLaunchKernelGGL((gemm_kernel<F, AK, BK_, AO>), grid, dim3(kThreads), 0, stream, p)
+  if (!fast) DLL_GEMM_LAUNCH(false, false, false, false);
+  else if (a_kc && b_kc && !has_out) DLL_GEMM_LAUNCH(true, true, true, false);
+  else if (a_kc && b_kc && has_out) DLL_GEMM_LAUNCH(true, true, true, true);
+  else if (a_kc && !b_kc && !has_out) DLL_GEMM_LAUNCH(true, true, false, false);
+  else if (a_kc && !b_kc && has_out) DLL_GEMM_LAUNCH(true, true, false, true);
+  else if (!a_kc && b_kc && !has_out) DLL_GEMM_LAUNCH(true, false, true, false);
+  else if (!a_kc && b_kc && has_out) DLL_GEMM_LAUNCH(true, false, true, true);
+  else if (!has_out) DLL_GEMM_LAUNCH(true, false, false, false);
+  else DLL_GEMM_LAUNCH(true, false, false, true);
+#undef DLL_GEMM_LAUNCH
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (p.a.split_k > 1) {
