@@ -9,6 +9,8 @@
 // Workgroup tile 128 x 64 x 32, four wavefronts of 64 x 32 each, register-prefetched k-tiles.
 #include "dll_internal.h"
 
+#include <type_traits>
+
 namespace dllk {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -168,27 +170,26 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(const GemmParams p) {
 #pragma unroll
     for (int j = 0; j < 2; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-  TileRegs<BM> ta;
-  TileRegs<BN> tb;
-  auto load_tiles = [&](int k0) {
+  // two register sets: tile t+2 is requested while tile t is multiplied and tile t+1 waits in
+  // registers for its turn in LDS, so two k-tiles of global loads are always in flight
+  TileRegs<BM> ta[2];
+  TileRegs<BN> tb[2];
+  auto load_tiles = [&](auto setc, int k0) {
+    constexpr int S_ = decltype(setc)::value;
     if (FAST) {
-      tile_load_vec<BM, A_KC, A_OUT>(ta, a.A, a.A_out, a.a_act, a.a_m, a.a_k, m0, k0, a.M, kend);
-      tile_load_vec<BN, B_KC, false>(tb, a.B, nullptr, 0, a.b_n, a.b_k, n0, k0, a.N, kend);
+      tile_load_vec<BM, A_KC, A_OUT>(ta[S_], a.A, a.A_out, a.a_act, a.a_m, a.a_k, m0, k0, a.M, kend);
+      tile_load_vec<BN, B_KC, false>(tb[S_], a.B, nullptr, 0, a.b_n, a.b_k, n0, k0, a.N, kend);
     } else {
-      tile_load<BM>(ta, a.A, a.A_out, a.a_act, a.a_m, a.a_k, m0, k0, a.M, kend, a_kc, p.a_vec);
-      tile_load<BN>(tb, a.B, nullptr, 0, a.b_n, a.b_k, n0, k0, a.N, kend, b_kc, p.b_vec);
+      tile_load<BM>(ta[S_], a.A, a.A_out, a.a_act, a.a_m, a.a_k, m0, k0, a.M, kend, a_kc, p.a_vec);
+      tile_load<BN>(tb[S_], a.B, nullptr, 0, a.b_n, a.b_k, n0, k0, a.N, kend, b_kc, p.b_vec);
     }
   };
-  if (kbeg < kend) {
-    load_tiles(kbeg);
-    tile_store<BM>(ta, As[0], a_kc);
-    tile_store<BN>(tb, Bs[0], b_kc);
-  }
-  __syncthreads();
-  int buf = 0;
-  for (int k0 = kbeg; k0 < kend; k0 += BK) {
-    const bool more = k0 + BK < kend;
-    if (more) load_tiles(k0 + BK);
+  auto store_tiles = [&](auto setc, int buf) {
+    constexpr int S_ = decltype(setc)::value;
+    tile_store<BM>(ta[S_], As[buf], a_kc);
+    tile_store<BN>(tb[S_], Bs[buf], b_kc);
+  };
+  auto multiply = [&](int buf) {
     const float *Ab = As[buf] + (wm + i16) * alx + kq * alk;
     const float *Bb = Bs[buf] + (wn + i16) * blx + kq * blk;
 #pragma unroll
@@ -204,12 +205,40 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(const GemmParams p) {
         for (int j = 0; j < 2; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf[j], af[i], acc[i][j], 0, 0, 0);
     }
-    if (more) {
-      tile_store<BM>(ta, As[buf ^ 1], a_kc);
-      tile_store<BN>(tb, Bs[buf ^ 1], b_kc);
-    }
+  };
+  using S0 = std::integral_constant<int, 0>;
+  using S1 = std::integral_constant<int, 1>;
+  if (kbeg < kend) {
+    load_tiles(S0{}, kbeg);
+    if (kbeg + BK < kend) load_tiles(S1{}, kbeg + BK);
+    store_tiles(S0{}, 0);
+  }
+  __syncthreads();
+  for (int k0 = kbeg; k0 < kend; k0 += 2 * BK) {
+    // LDS buffer 0 holds tile k0, register set 1 holds tile k0 + BK
+    if (k0 + 2 * BK < kend) load_tiles(S0{}, k0 + 2 * BK);
+    multiply(0);
+    if (k0 + BK < kend) store_tiles(S1{}, 1);
     __syncthreads();
-    buf ^= 1;
+    if (k0 + BK >= kend) break;
+    if (k0 + 3 * BK < kend) load_tiles(S1{}, k0 + 3 * BK);
+    multiply(1);
+    if (k0 + 2 * BK < kend) store_tiles(S0{}, 0);
+    __syncthreads();
+  }
+
+  // fused parameter update: fetch the lane's eight 16-byte groups of the parameters with
+  // unconditional loads from clamped addresses, so they are all in flight together
+  float4 upd[4][2];
+  if (a.update && p.c_vec && a.split_k == 1) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int m = m0 + wm + i * 16 + i16, n = n0 + wn + j * 16 + 4 * kq;
+        const bool ok = m < a.M && n + 3 < a.N;
+        upd[i][j] = *reinterpret_cast<const float4 *>(a.update + (ok ? (long)m * a.c_m + (long)n * a.c_n : 0));
+      }
   }
 
   // lane holds C(m = i16, n = 4*kq + v) of each 16x16 tile
@@ -239,7 +268,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(const GemmParams p) {
       if (p.c_vec && n + 3 < a.N) {
         if (a.Cout) *reinterpret_cast<float4 *>(a.Cout + o) = make_float4(c[0], c[1], c[2], c[3]);
         if (a.update) {
-          float4 u = *reinterpret_cast<float4 *>(a.update + o);
+          float4 u = upd[i][j];   // requested before the epilogue loop, all eight at once
           u.x += a.step * c[0]; u.y += a.step * c[1]; u.z += a.step * c[2]; u.w += a.step * c[3];
           *reinterpret_cast<float4 *>(a.update + o) = u;
         }
