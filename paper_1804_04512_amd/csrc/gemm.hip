@@ -189,21 +189,38 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(const GemmParams p) {
     tile_store<BM>(ta[S_], As[buf], a_kc);
     tile_store<BN>(tb[S_], Bs[buf], b_kc);
   };
+  // operand fragments are double-buffered in registers: the LDS reads of step s+1 are issued
+  // before the MFMAs of step s (scheduling barriers keep that order)
   auto multiply = [&](int buf) {
     const float *Ab = As[buf] + (wm + i16) * alx + kq * alk;
     const float *Bb = Bs[buf] + (wn + i16) * blx + kq * blk;
+    float af[2][4], bf[2][2];
+    auto load_frags = [&](auto bc, int s) {
+      constexpr int B_ = decltype(bc)::value;
 #pragma unroll
-    for (int s = 0; s < BK / 4; ++s) {
-      float af[4], bf[2];
+      for (int i = 0; i < 4; ++i) af[B_][i] = Ab[i * 16 * alx + 4 * s * alk];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) af[i] = Ab[i * 16 * alx + 4 * s * alk];
-#pragma unroll
-      for (int j = 0; j < 2; ++j) bf[j] = Bb[j * 16 * blx + 4 * s * blk];
+      for (int j = 0; j < 2; ++j) bf[B_][j] = Bb[j * 16 * blx + 4 * s * blk];
+    };
+    auto mfma_frags = [&](auto bc) {
+      constexpr int B_ = decltype(bc)::value;
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf[j], af[i], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf[B_][j], af[B_][i], acc[i][j], 0, 0, 0);
+    };
+    load_frags(std::integral_constant<int, 0>{}, 0);
+#pragma unroll
+    for (int s = 0; s < BK / 4; s += 2) {
+      load_frags(std::integral_constant<int, 1>{}, s + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_frags(std::integral_constant<int, 0>{});
+      __builtin_amdgcn_sched_barrier(0);
+      if (s + 2 < BK / 4) load_frags(std::integral_constant<int, 0>{}, s + 2);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_frags(std::integral_constant<int, 1>{});
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
   using S0 = std::integral_constant<int, 0>;
