@@ -26,9 +26,18 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kTileW = 32;
 constexpr int TH = 8;
-constexpr int PSZ = TH * kTileW + 2;   // dz plane stride in LDS: conflict-free A-operand reads
+constexpr int PSZ = TH * kTileW + 18;  // dz plane stride in LDS: half of it is odd, so A-operand reads are conflict-free
 constexpr int NXI = 5;                 // prefetch registers: float4 of tile interior per thread
 constexpr int NXH = 2;                 // prefetch registers: halo scalars per thread
+
+// Offset of row r inside a dz plane.  The staging stores are 8 bytes wide and LDS serves them 16
+// lanes at a time, so those 16 lanes must land in 32 different banks.  Pooled staging: 16 lanes
+// hold 4 window rows x 4 column groups of 8, so window rows are 66 floats apart (2 banks) with
+// the window's second row 32 floats after the first.  Unpooled staging: 16 lanes hold 2 rows x 8
+// column groups of 4, so rows are 34 floats apart.
+template <int POOL>
+__device__ constexpr int dz_row(int r) { return POOL == 2 ? (r >> 1) * 66 + (r & 1) * kTileW : r * 34; }
+static_assert(dz_row<2>(TH - 1) + kTileW <= PSZ && dz_row<1>(TH - 1) + kTileW <= PSZ && (PSZ / 2) % 2 == 1, "dz plane layout");
 
 struct WgradParams {
   WgradArgs a;
@@ -159,7 +168,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
         const int k = rd * 16 + (tid >> 4);
         dzk[rd] = k < kcount;
         dzo[rd] = ((k0 + k) * (p.Ho >> 1) + du) * (p.Wo >> 1) + dv;
-        dzl[rd] = k * PSZ + 2 * du * kTileW + 2 * dv;
+        dzl[rd] = k * PSZ + dz_row<POOL>(2 * du) + 2 * dv;
       }
     } else {
       const int q = tid & 63;
@@ -170,7 +179,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
         const int k = rd * 4 + (tid >> 6);
         dzk[rd] = k < kcount;
         dzo[rd] = ((k0 + k) * p.Ho + du) * p.Wo + dv;
-        dzl[rd] = k * PSZ + du * kTileW + dv;
+        dzl[rd] = k * PSZ + dz_row<POOL>(du) + dv;
       }
     }
   }
@@ -271,7 +280,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
         const int gi = oy0 + row, gj = ox0 + col;
         float v = 0.0f;
         if (gi < p.Ho && gj < p.Wo) v = dz_value(a, p.Ho, p.Wo, n, k0 + k, gi, gj);
-        dzs[k * PSZ + tid] = v;
+        dzs[k * PSZ + dz_row<POOL>(row) + col] = v;
         if constexpr (!FAST) dbacc[k] += v;
       }
     }
@@ -311,12 +320,13 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
     // registers: the LDS reads of step t+1 are issued before the MFMAs of step t.
     {
       float af[2][MTF], bf[2][NTT];
-      const float *za = dzs + (wave * RW) * kTileW + kq;
+      static_assert(RW == 2, "dz_row(wave * RW + rr) = dz_row(wave * RW) + dz_row(rr) needs an even first row");
+      const float *za = dzs + dz_row<POOL>(wave * RW) + kq;
       const float *xb = xs + (wave * RW) * p.RS + kq;
       auto load_frags = [&](auto bufc, int rr, int cg) {
         constexpr int B_ = decltype(bufc)::value;
 #pragma unroll
-        for (int mf = 0; mf < MTF; ++mf) af[B_][mf] = za[fplane[mf] + rr * kTileW + 4 * cg];
+        for (int mf = 0; mf < MTF; ++mf) af[B_][mf] = za[fplane[mf] + dz_row<POOL>(rr) + 4 * cg];
 #pragma unroll
         for (int nt = 0; nt < NTT; ++nt) bf[B_][nt] = xb[tapoff[nt] + rr * p.RS + 4 * cg];
       };
