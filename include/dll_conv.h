@@ -85,8 +85,10 @@ size_t dll_conv_workspace_bytes(const dll_conv_desc *d);
 /* Forward layer (Section II-A, "valid convolution for the forward pass"):
  *   z[n,k,i,j] = bias[k] + sum_{c,r,s} xpad[n,c,i+r,j+s] * w[k,c,r,s]
  *   y = maxpool2x2(act(z)) when pool == 2, else act(z)
- * pool_idx (required iff pool == 2) receives 2*a+b of the window's maximum (first one in
- * the order (0,0),(0,1),(1,0),(1,1) on ties of the pre-activation).  bias may be NULL. */
+ * pool_idx (required iff pool == 2) receives, in bits 0-1 of each byte, 2*a+b of the window's
+ * maximum (first one in the order (0,0),(0,1),(1,0),(1,1) on ties of the pre-activation).
+ * When act is ReLU, bit 2 (value 4) is also set where the pooled output is zero, i.e. where
+ * the unit passes no gradient; all other bits are zero.  bias may be NULL. */
 dll_status dll_conv_valid_fwd(const dll_conv_desc *d, const float *x, const float *w,
                               const float *bias, float *y, unsigned char *pool_idx, void *ws,
                               size_t ws_bytes, void *stream);
@@ -94,14 +96,17 @@ dll_status dll_conv_valid_fwd(const dll_conv_desc *d, const float *x, const floa
 /* Backward-data layer (Section II-A, "full convolution for the backward pass"):
  *   dz = unpool(dy, pool_idx) * act'(y)          (never stored)
  *   dx[n,c,i,j] = sum_{k,r,s} dz[n,k,i+pad-r,j+pad-s] * w[k,c,r,s]
- * y may be NULL when act is the identity; pool_idx is required iff pool == 2. */
+ * pool_idx is required iff pool == 2; only bits 0-1 of its bytes are read when y is given.
+ * y may be NULL when act is the identity.  y may also be NULL when act is ReLU and pool == 2:
+ * then act'(y) is taken from bit 2 of pool_idx as dll_conv_valid_fwd wrote it (zero gradient
+ * where the bit is set) and the layer output is not read at all. */
 dll_status dll_conv_full_bwd(const dll_conv_desc *d, const float *dy, const float *y,
                              const unsigned char *pool_idx, const float *w, float *dx, void *ws,
                              size_t ws_bytes, void *stream);
 
 /* Filter-gradient layer (Section II-A, gradient computations):
  *   dw[k,c,r,s] = sum_{n,i,j} dz[n,k,i,j] * xpad[n,c,i+r,j+s];  dbias[k] = sum_{n,i,j} dz[n,k,i,j]
- * with dz as above.  dbias may be NULL.  The batch reduction is a fixed-order tree:
+ * with dz as above (same rules for y and pool_idx).  dbias may be NULL.  The batch reduction is a fixed-order tree:
  * results are bit-identical from run to run. */
 dll_status dll_conv_valid_wgrad(const dll_conv_desc *d, const float *x, const float *dy,
                                 const float *y, const unsigned char *pool_idx, float *dw,
@@ -134,7 +139,8 @@ dll_status dll_crbm_cd1_step(const dll_conv_desc *d, const float *v0, float *W, 
  *   labels  [N] int32 in [0, classes)
  *   loss    device scalar, required;  logits [N][classes], may be NULL
  *   pool_idx  NULL, or a host array of n_conv device pointers (entries may be NULL): each
- *           non-NULL entry of a pooled layer receives that layer's pooling indices */
+ *           non-NULL entry of a pooled layer receives that layer's pooling indices, in the
+ *           encoding dll_conv_valid_fwd writes */
 size_t dll_cnn_workspace_bytes(const dll_net_desc *net);
 dll_status dll_cnn_train_step(const dll_net_desc *net, float *const *params, float *const *grads,
                               const float *x, const int *labels, float lr, float *loss,

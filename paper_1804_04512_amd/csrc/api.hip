@@ -75,13 +75,22 @@ ConvEngineArgs fwd_args(const dll_conv_desc *d, const float *x, const float *w, 
   return a;
 }
 
+// A pooled ReLU layer's backward passes may run without the layer output: the forward pass
+// left the unit's activity in the pooling index.
+inline bool flagged_relu(const dll_conv_desc *d, const float *y) {
+  return !y && d->act == DLL_ACT_RELU && d->pool == 2;
+}
+inline bool output_required(const dll_conv_desc *d) {
+  return d->act != DLL_ACT_IDENTITY && !(d->act == DLL_ACT_RELU && d->pool == 2);
+}
+
 // Backward-data as a forward-form convolution of dz (K channels at Ho x Wo) with the
 // rotated, transposed filters on an input padded by R-1-pad (Section II-A's identity).
 ConvEngineArgs bwd_args(const dll_conv_desc *d, const float *dy, const float *y, const unsigned char *idx,
                         const float *w, float *dx) {
   ConvEngineArgs a;
   a.src = dy; a.src_y = y; a.src_idx = idx;
-  a.src_dz = 1; a.src_act = d->act; a.src_pool = d->pool;
+  a.src_dz = 1; a.src_act = flagged_relu(d, y) ? ACT_RELU_FLAGGED : d->act; a.src_pool = d->pool;
   a.N = d->N; a.Cin = d->K; a.Hin = out_h(d); a.Win = out_w(d);
   a.w = w; a.w_flip = 1;
   a.Kout = d->C; a.R = d->R; a.S = d->S; a.pad_h = d->R - 1 - d->pad; a.pad_w = d->S - 1 - d->pad;
@@ -95,7 +104,7 @@ WgradArgs wgrad_args(const dll_conv_desc *d, const float *x, const float *dy, co
                      const unsigned char *idx, float *partial) {
   WgradArgs a;
   a.x = x; a.dy = dy; a.y = y; a.idx = idx;
-  a.act = d->act; a.pool = d->pool;
+  a.act = flagged_relu(d, y) ? ACT_RELU_FLAGGED : d->act; a.pool = d->pool;
   a.N = d->N; a.C = d->C; a.H = d->H; a.W = d->W; a.K = d->K; a.R = d->R; a.S = d->S; a.pad = d->pad;
   a.partial = partial;
   return a;
@@ -144,7 +153,7 @@ dll_status dll_conv_full_bwd(const dll_conv_desc *d, const float *dy, const floa
   (void)ws; (void)ws_bytes;
   dll_status st = check_desc(d);
   if (st != DLL_OK) return st;
-  if (!dy || !w || !dx || (d->act != DLL_ACT_IDENTITY && !y) || (d->pool == 2 && !pool_idx)) return DLL_ERR_NULL;
+  if (!dy || !w || !dx || (output_required(d) && !y) || (d->pool == 2 && !pool_idx)) return DLL_ERR_NULL;
   if ((const float *)dx == dy || (const float *)dx == y || (const float *)dx == w) return DLL_ERR_SHAPE;
   if (misaligned(dy) || misaligned(y) || misaligned(w) || misaligned(dx) || misaligned(pool_idx)) return DLL_ERR_SHAPE;
   return dev(launch_conv_engine(bwd_args(d, dy, y, pool_idx, w, dx), static_cast<hipStream_t>(stream)));
@@ -155,7 +164,7 @@ dll_status dll_conv_valid_wgrad(const dll_conv_desc *d, const float *x, const fl
                                 void *stream) {
   dll_status st = check_desc(d);
   if (st != DLL_OK) return st;
-  if (!x || !dy || !dw || (d->act != DLL_ACT_IDENTITY && !y) || (d->pool == 2 && !pool_idx)) return DLL_ERR_NULL;
+  if (!x || !dy || !dw || (output_required(d) && !y) || (d->pool == 2 && !pool_idx)) return DLL_ERR_NULL;
   if ((const float *)dw == x || (const float *)dw == dy || (const float *)dw == y) return DLL_ERR_SHAPE;
   if (misaligned(x) || misaligned(dy) || misaligned(y) || misaligned(dw)) return DLL_ERR_SHAPE;
   WgradPlan plan;
@@ -424,13 +433,16 @@ dll_status dll_cnn_train_step(const dll_net_desc *net, float *const *params, flo
   // ---- convolution backward: data gradient with the old filters, then filter gradient + update
   for (int l = L - 1; l >= 0; --l) {
     const dll_conv_desc *d = &net->conv[l];
+    // pooled ReLU layers: the forward pass above flagged the inactive units in idx, so the
+    // backward passes do not read the layer output
+    const float *yl = (d->act == DLL_ACT_RELU && d->pool == 2) ? nullptr : nb.act[l + 1];
     if (l > 0) {
-      st = dev(launch_conv_engine(bwd_args(d, gcur, nb.act[l + 1], nb.idx[l], params[2 * l], gnext), s));
+      st = dev(launch_conv_engine(bwd_args(d, gcur, yl, nb.idx[l], params[2 * l], gnext), s));
       if (st != DLL_OK) return st;
     }
     WgradPlan plan;
     if (!plan_for(d, &plan)) return DLL_ERR_UNSUPPORTED;
-    st = dev(launch_wgrad(wgrad_args(d, nb.act[l], gcur, nb.act[l + 1], nb.idx[l], nb.partial), plan, s));
+    st = dev(launch_wgrad(wgrad_args(d, nb.act[l], gcur, yl, nb.idx[l], nb.partial), plan, s));
     if (st != DLL_OK) return st;
     WgradReduceArgs r;
     r.pos = nb.partial; r.scale = 1.0f;

@@ -55,13 +55,22 @@ __device__ __forceinline__ float act_deriv(int act, float out) {
   return 1.0f;
 }
 
+// dy times act'(y) for a pooled element: from the layer output, or from the index byte's flag.
+__device__ __forceinline__ float pooled_dz(int act, float g, float out, unsigned char f) {
+  if (act == ACT_RELU_FLAGGED) return (f & kIdxInactive) ? 0.0f : g;
+  return act != ACT_IDENTITY ? g * act_deriv(act, out) : g;
+}
+__host__ __device__ __forceinline__ bool reads_output(int act) { return act == ACT_SIGMOID || act == ACT_RELU; }
+
 // dz at pre-pool position (i,j) of plane (n,k): dy routed to the recorded arg-max, times act'(y).
 __device__ __forceinline__ float dz_value(const ConvEngineArgs &a, int n, int k, int i, int j) {
   int o;
   if (a.src_pool == 2) {
     const int Hp = a.Hin >> 1, Wp = a.Win >> 1;
     o = ((n * a.Cin + k) * Hp + (i >> 1)) * Wp + (j >> 1);
-    if (a.src_idx[o] != (unsigned char)(((i & 1) << 1) | (j & 1))) return 0.0f;
+    const unsigned char f = a.src_idx[o];
+    if ((f & kIdxPosMask) != (unsigned char)(((i & 1) << 1) | (j & 1))) return 0.0f;
+    if (a.src_act == ACT_RELU_FLAGGED) return (f & kIdxInactive) ? 0.0f : a.src[o];
   } else {
     o = ((n * a.Cin + k) * a.Hin + i) * a.Win + j;
   }
@@ -103,7 +112,7 @@ __device__ __forceinline__ void engine_epilogue(const ConvEngineArgs &a, floatx4
           if (z[2] > m) { m = z[2]; arg = 2; }
           if (z[3] > m) { m = z[3]; arg = 3; }
           yv[mt] = act_apply(a.act, m + bv);   // bias and a monotone activation commute with max
-          iv[mt] = (unsigned char)arg;
+          iv[mt] = (unsigned char)(arg | ((a.act == ACT_RELU && !(yv[mt] > 0.0f)) ? kIdxInactive : 0));
         }
         const int o = ((n * a.Kout + ko) * Hp + py) * Wp + px0;
         if (px0 + 3 < Wp && (Wp & 3) == 0) {
@@ -409,7 +418,7 @@ __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void 
         if (line < LINES && c0 + cl < a.Cin && u >= 0 && u < Hp && v0 < Wp) {
           const long o = ((long)(n * a.Cin + c0 + cl) * Hp + u) * Wp + v0;
           vi[it] = *reinterpret_cast<const float4 *>(a.src + o);
-          if (a.src_act != ACT_IDENTITY) yi[it] = *reinterpret_cast<const float4 *>(a.src_y + o);
+          if (reads_output(a.src_act)) yi[it] = *reinterpret_cast<const float4 *>(a.src_y + o);
           ii[it] = *reinterpret_cast<const uchar4 *>(a.src_idx + o);
         }
       }
@@ -423,7 +432,7 @@ __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void 
         if (line < LINES && c0 + cl < a.Cin && u >= 0 && u < Hp && v0 >= 0 && v0 < Wp) {
           const long o = ((long)(n * a.Cin + c0 + cl) * Hp + u) * Wp + v0;
           vh[it] = a.src[o];
-          if (a.src_act != ACT_IDENTITY) yh[it] = a.src_y[o];
+          if (reads_output(a.src_act)) yh[it] = a.src_y[o];
           ih[it] = a.src_idx[o];
         }
       }
@@ -470,10 +479,14 @@ __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void 
           const int cl = line / PR, pr = line - cl * PR;
           const float gv[4] = {vi[it].x, vi[it].y, vi[it].z, vi[it].w};
           const float ov[4] = {yi[it].x, yi[it].y, yi[it].z, yi[it].w};
-          const unsigned char pos[4] = {ii[it].x, ii[it].y, ii[it].z, ii[it].w};
+          const unsigned char fl[4] = {ii[it].x, ii[it].y, ii[it].z, ii[it].w};
+          unsigned char pos[4];
           float gg[4];
 #pragma unroll
-          for (int q = 0; q < 4; ++q) gg[q] = a.src_act != ACT_IDENTITY ? gv[q] * act_deriv(a.src_act, ov[q]) : gv[q];
+          for (int q = 0; q < 4; ++q) {
+            gg[q] = pooled_dz(a.src_act, gv[q], ov[q], fl[q]);
+            pos[q] = fl[q] & kIdxPosMask;   // slots outside the image hold dy = 0
+          }
 #pragma unroll
           for (int wa2 = 0; wa2 < 2; ++wa2) {
             const int row = 2 * pr - 1 + wa2;
@@ -493,14 +506,15 @@ __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void 
         const int side = e & 1, line = e >> 1;
         if (line < LINES) {
           const int cl = line / PR, pr = line - cl * PR;
-          const float gg = a.src_act != ACT_IDENTITY ? vh[it] * act_deriv(a.src_act, yh[it]) : vh[it];
+          const float gg = pooled_dz(a.src_act, vh[it], yh[it], ih[it]);
+          const unsigned char hp = ih[it] & kIdxPosMask;
 #pragma unroll
           for (int wa2 = 0; wa2 < 2; ++wa2) {
             const int row = 2 * pr - 1 + wa2;
             // left neighbour window: LDS columns 0 (unused slot) and 1; right one: 34 and 35 (unused slot)
             if (row >= 0 && row < ROWS)
               *reinterpret_cast<float2 *>(xs + cl * PS + row * RS + (side ? kTileW + 2 : 0)) =
-                  make_float2(ih[it] == 2 * wa2 ? gg : 0.0f, ih[it] == 2 * wa2 + 1 ? gg : 0.0f);
+                  make_float2(hp == 2 * wa2 ? gg : 0.0f, hp == 2 * wa2 + 1 ? gg : 0.0f);
           }
         }
       }
@@ -640,7 +654,7 @@ bool conv3x3c16_applies(const ConvEngineArgs &a) {
   if (a.Hout != a.Hin || a.Wout != a.Win) return false;
   if (!aligned16(a.src)) return false;
   if (a.src_dz) {
-    if (a.src_act != ACT_IDENTITY && !aligned16(a.src_y)) return false;
+    if (reads_output(a.src_act) && !aligned16(a.src_y)) return false;
     if (a.src_pool == 2) return (a.Win % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.src_idx) & 3u) == 0);
   }
   return a.Win % 4 == 0;

@@ -62,7 +62,9 @@ __device__ __forceinline__ float dz_value(const WgradArgs &a, int Ho, int Wo, in
   int o;
   if (a.pool == 2) {
     o = ((n * a.K + k) * (Ho >> 1) + (i >> 1)) * (Wo >> 1) + (j >> 1);
-    if (a.idx[o] != (unsigned char)(((i & 1) << 1) | (j & 1))) return 0.0f;
+    const unsigned char f = a.idx[o];
+    if ((f & kIdxPosMask) != (unsigned char)(((i & 1) << 1) | (j & 1))) return 0.0f;
+    if (a.act == ACT_RELU_FLAGGED) return (f & kIdxInactive) ? 0.0f : a.dy[o];
   } else {
     o = ((n * a.K + k) * Ho + i) * Wo + j;
   }
@@ -70,6 +72,8 @@ __device__ __forceinline__ float dz_value(const WgradArgs &a, int Ho, int Wo, in
   if (a.act != ACT_IDENTITY) g *= act_deriv(a.act, a.y[o]);
   return g;
 }
+
+__host__ __device__ __forceinline__ bool reads_output(int act) { return act == ACT_SIGMOID || act == ACT_RELU; }
 
 // Registers that carry one tile from global memory to LDS (fast path).
 template <int MTF, int POOL>
@@ -220,7 +224,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
       uchar4 iv = make_uchar4(255, 255, 255, 255);
       if (in && dzk[rd]) {
         dv4 = *reinterpret_cast<const float4 *>(a.dy + dbase + dzo[rd]);
-        if (a.act != ACT_IDENTITY) yv = *reinterpret_cast<const float4 *>(a.y + dbase + dzo[rd]);
+        if (reads_output(a.act)) yv = *reinterpret_cast<const float4 *>(a.y + dbase + dzo[rd]);
         if (POOL == 2) iv = *reinterpret_cast<const uchar4 *>(a.idx + dbase + dzo[rd]);
       }
       tr.dyv[rd] = dv4; tr.yv[rd] = yv; tr.iv[rd] = iv;
@@ -247,18 +251,23 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
       const float ov[4] = {tr.yv[rd].x, tr.yv[rd].y, tr.yv[rd].z, tr.yv[rd].w};
       float g[4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) g[e] = a.act != ACT_IDENTITY ? gv[e] * act_deriv(a.act, ov[e]) : gv[e];
+      for (int e = 0; e < 4; ++e) g[e] = reads_output(a.act) ? gv[e] * act_deriv(a.act, ov[e]) : gv[e];
       float *d = dzs + dzl[rd];
       if (POOL == 2) {
-        const unsigned char pos[4] = {tr.iv[rd].x, tr.iv[rd].y, tr.iv[rd].z, tr.iv[rd].w};
+        const unsigned char fl[4] = {tr.iv[rd].x, tr.iv[rd].y, tr.iv[rd].z, tr.iv[rd].w};
+        unsigned char pos[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (a.act == ACT_RELU_FLAGGED && (fl[e] & kIdxInactive)) g[e] = 0.0f;
+          pos[e] = fl[e] & kIdxPosMask;   // slots outside the image hold dy = 0
+        }
 #pragma unroll
         for (int wa = 0; wa < 2; ++wa)
 #pragma unroll
           for (int e = 0; e < 4; ++e)
             *reinterpret_cast<float2 *>(d + wa * kTileW + 2 * e) =
                 make_float2(pos[e] == 2 * wa ? g[e] : 0.0f, pos[e] == 2 * wa + 1 ? g[e] : 0.0f);
-        dbacc[rd] += ((pos[0] < 4 ? g[0] : 0.f) + (pos[1] < 4 ? g[1] : 0.f)) +
-                     ((pos[2] < 4 ? g[2] : 0.f) + (pos[3] < 4 ? g[3] : 0.f));
+        dbacc[rd] += (g[0] + g[1]) + (g[2] + g[3]);
       } else {
         reinterpret_cast<float2 *>(d)[0] = make_float2(g[0], g[1]);
         reinterpret_cast<float2 *>(d)[1] = make_float2(g[2], g[3]);
@@ -435,19 +444,23 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
   }
 }
 
-// One workgroup per 16 outputs (consecutive taps of one filter); 16 slices of the partial
-// list are summed in parallel in double, then combined in a fixed order.
+// One workgroup per 4 outputs (consecutive taps of one filter); 64 slices of the partial
+// list are summed in parallel in double, then combined in a fixed order (the partial buffers
+// are small and L2-resident; what matters is how many independent loads are in flight).
+constexpr int kRedOut = 4, kRedSlices = kThreads / kRedOut;
 __global__ __launch_bounds__(kThreads) void wgrad_reduce_kernel(const WgradReduceArgs a, const WgradPlan plan,
                                                                long group_stride, int ndw) {
-  __shared__ double red[16][17];
-  const int tid = threadIdx.x, o16 = tid & 15, slice = tid >> 4;
+  __shared__ double red[kRedSlices][kRedOut + 1];
+  __shared__ double red2[4][kRedOut + 1];
+  const int tid = threadIdx.x, oq = tid % kRedOut, slice = tid / kRedOut;
   const int RSf = a.R * a.S;
   const int blk = blockIdx.x;
-  const int nblk_dw = (ndw + 15) / 16;
+  const int nblk_dw = (ndw + kRedOut - 1) / kRedOut;
   double sum = 0.0;
   int out_index = -1;
+  long base = 0, stride = 0;
   if (blk < nblk_dw) {
-    const int o = blk * 16 + o16;   // flat index into dw[K][C][R][S]
+    const int o = blk * kRedOut + oq;   // flat index into dw[K][C][R][S]
     if (o < ndw) {
       const int ko = o / (a.C * RSf), rem = o - ko * (a.C * RSf);
       const int ci = rem / RSf, rs = rem - ci * RSf;
@@ -457,32 +470,38 @@ __global__ __launch_bounds__(kThreads) void wgrad_reduce_kernel(const WgradReduc
       const int mf = m >> 4, lq = (m & 15) >> 2, v = m & 3;
       const int nt = tap >> 4, lane = lq * 16 + (tap & 15);
       const long within = ((long)(mf * plan.NTT + nt) * 4 + v) * 64 + lane;
-      const long blockf = (long)plan.MTF * plan.NTT * 256;
-      const long base = (long)grp * group_stride + (long)chunk * plan.n_partials * blockf + within;
-      for (int pidx = slice; pidx < plan.n_partials; pidx += 16) {
-        double t = (double)a.pos[base + pidx * blockf];
-        if (a.neg) t -= (double)a.neg[base + pidx * blockf];
-        sum += t;
-      }
+      stride = (long)plan.MTF * plan.NTT * 256;
+      base = (long)grp * group_stride + (long)chunk * plan.n_partials * stride + within;
       out_index = o;
     }
   } else {
-    const int k = (blk - nblk_dw) * 16 + o16;
+    const int k = (blk - nblk_dw) * kRedOut + oq;
     if (k < a.K) {
-      for (int pidx = slice; pidx < plan.n_partials; pidx += 16) {
-        double t = (double)a.pos[plan.db_offset + (long)pidx * a.K + k];
-        if (a.neg) t -= (double)a.neg[plan.db_offset + (long)pidx * a.K + k];
-        sum += t;
-      }
+      stride = a.K;
+      base = plan.db_offset + k;
       out_index = k;
     }
   }
-  red[slice][o16] = sum;
+  if (out_index >= 0) {
+#pragma unroll 4
+    for (int pidx = slice; pidx < plan.n_partials; pidx += kRedSlices) {
+      double t = (double)a.pos[base + pidx * stride];
+      if (a.neg) t -= (double)a.neg[base + pidx * stride];
+      sum += t;
+    }
+  }
+  red[slice][oq] = sum;
   __syncthreads();
-  if (slice == 0 && out_index >= 0) {
+  if (tid < 4 * kRedOut) {   // four threads per output, 16 slices each
+    const int part = tid / kRedOut;
     double s = 0.0;
 #pragma unroll
-    for (int q = 0; q < 16; ++q) s += red[q][o16];
+    for (int q = 0; q < kRedSlices / 4; ++q) s += red[part * (kRedSlices / 4) + q][oq];
+    red2[part][oq] = s;
+  }
+  __syncthreads();
+  if (tid < kRedOut && out_index >= 0) {
+    const double s = (red2[0][oq] + red2[1][oq]) + (red2[2][oq] + red2[3][oq]);
     const float gval = (float)(s * (double)a.scale);
     if (blk < nblk_dw) {
       if (a.dw) a.dw[out_index] = gval;
@@ -628,7 +647,7 @@ hipError_t launch_wgrad(const WgradArgs &a, const WgradPlan &plan, hipStream_t s
   // of 4 (8 pre-pool columns when pooling), aligned tensors, and a tile that fits the
   // prefetch registers.
   const int lines = plan.CC * g.rows;
-  bool fast = (a.W % 4 == 0) && aligned16(a.x) && aligned16(a.dy) && (a.act == ACT_IDENTITY || aligned16(a.y)) &&
+  bool fast = (a.W % 4 == 0) && aligned16(a.x) && aligned16(a.dy) && (!reads_output(a.act) || aligned16(a.y)) &&
               lines * 8 <= NXI * kThreads && lines * (a.S - 1) <= NXH * kThreads;
   if (a.pool == 2) fast = fast && (p.Wo % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.idx) & 3u) == 0);
   else fast = fast && (p.Wo % 4 == 0);
@@ -643,7 +662,7 @@ hipError_t launch_wgrad(const WgradArgs &a, const WgradPlan &plan, hipStream_t s
 hipError_t launch_wgrad_reduce(const WgradReduceArgs &a, const WgradPlan &plan, hipStream_t stream) {
   const int ndw = a.K * a.C * a.R * a.S;
   const long group_stride = (long)plan.nchunks * plan.n_partials * ((long)plan.MTF * plan.NTT * 256);
-  const int blocks = (ndw + 15) / 16 + (a.K + 15) / 16;
+  const int blocks = (ndw + kRedOut - 1) / kRedOut + (a.K + kRedOut - 1) / kRedOut;
   hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(blocks), dim3(kThreads), 0, stream, a, plan, group_stride, ndw);
   return hipGetLastError();
 }

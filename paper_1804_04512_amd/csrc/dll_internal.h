@@ -9,6 +9,12 @@
 namespace dllk {
 
 enum { ACT_IDENTITY = 0, ACT_SIGMOID = 1, ACT_RELU = 2 };
+// Backward passes only: ReLU whose derivative comes from the flag bit in the pooling index
+// (kIdxInactive) instead of from the layer output, which then is not read at all.
+enum { ACT_RELU_FLAGGED = 3 };
+// Pooling index byte: bits 0-1 hold the arg-max position 2a+b inside the 2x2 window; the
+// forward pass of a ReLU layer also sets kIdxInactive where the pooled output is zero.
+constexpr unsigned char kIdxPosMask = 3, kIdxInactive = 4;
 
 // ---------------------------------------------------------------------------------------
 // Forward-form implicit-GEMM convolution engine (fp32 MFMA 16x16x4).

@@ -315,16 +315,18 @@ __global__ __launch_bounds__(kThreads) void gemm_splitk_reduce_kernel(const Gemm
   }
 }
 
-// out[n] = sum_m A[m][n] * act'(Aout[m][n]): 64 columns per workgroup, four row slices added
-// in a fixed order.
+// out[n] = sum_m A[m][n] * act'(Aout[m][n]): 16 columns per workgroup, 16 row slices added
+// in a fixed order (small inputs: many short independent load chains beat few long ones).
+constexpr int kColsumCols = 16, kColsumSlices = kThreads / kColsumCols;
 __global__ __launch_bounds__(kThreads) void colsum_kernel(const float *A, const float *A_out, int act, int M, int N,
                                                          float *out, float *update, float step) {
-  __shared__ float part[4][64];
-  const int col = threadIdx.x & 63, slice = threadIdx.x >> 6;
-  const int n = blockIdx.x * 64 + col;
+  __shared__ float part[kColsumSlices][kColsumCols + 1];
+  const int col = threadIdx.x % kColsumCols, slice = threadIdx.x / kColsumCols;
+  const int n = blockIdx.x * kColsumCols + col;
   float s = 0.0f;
   if (n < N) {
-    for (int m = slice; m < M; m += 4) {
+#pragma unroll 4
+    for (int m = slice; m < M; m += kColsumSlices) {
       float v = A[(long)m * N + n];
       if (A_out) v *= act_deriv(act, A_out[(long)m * N + n]);
       s += v;
@@ -333,7 +335,14 @@ __global__ __launch_bounds__(kThreads) void colsum_kernel(const float *A, const 
   part[slice][col] = s;
   __syncthreads();
   if (slice == 0 && n < N) {
-    s = (part[0][col] + part[1][col]) + (part[2][col] + part[3][col]);
+    float q[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      q[g] = 0.0f;
+#pragma unroll
+      for (int i = 0; i < kColsumSlices / 4; ++i) q[g] += part[g * (kColsumSlices / 4) + i][col];
+    }
+    s = (q[0] + q[1]) + (q[2] + q[3]);
     if (out) out[n] = s;
     if (update) update[n] += step * s;
   }
@@ -479,7 +488,7 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream) {
 
 hipError_t launch_colsum(const float *A, const float *A_out, int a_act, int M, int N, float *out, float *update,
                          float step, hipStream_t stream) {
-  hipLaunchKernelGGL(colsum_kernel, dim3((N + 63) / 64), dim3(kThreads), 0, stream, A, A_out, a_act, M, N,
+  hipLaunchKernelGGL(colsum_kernel, dim3((N + kColsumCols - 1) / kColsumCols), dim3(kThreads), 0, stream, A, A_out, a_act, M, N,
                      out, update, step);
   return hipGetLastError();
 }

@@ -29,6 +29,33 @@ def onet(w: wl.CnnWorkload) -> orc.Net:
     return orc.Net([odesc(c) for c in w.conv], [(d.in_, d.out, ACT[d.act]) for d in w.dense], w.classes)
 
 
+def check_idx_bytes(raw, relu, y_gpu):
+    """Splits the library's pooling-index bytes: bits 0-1 are the window position; bit 2 is set
+    exactly where a ReLU layer's pooled output (the library's own y) is zero; nothing else is set.
+    Returns the positions."""
+    flags = raw & ~np.uint8(3)
+    if relu:
+        assert np.array_equal(flags, np.where(y_gpu > 0, 0, 4).astype(np.uint8))
+    else:
+        assert not flags.any()
+    return raw & np.uint8(3)
+
+
+def check_idx_flags_against(raw, relu, y_ref, tol=2e-5):
+    """Flag bits against a reference output: clear where y_ref is clearly positive; where y_ref
+    is zero they may only be clear if the GPU's y rounded to a tiny positive value, which must
+    stay rare."""
+    flags = raw & ~np.uint8(3)
+    if not relu:
+        assert not flags.any()
+        return
+    assert not (flags & ~np.uint8(4)).any()
+    scale = max(float(np.abs(y_ref).max()), 1e-30)
+    assert not (flags[y_ref > tol * scale] != 0).any(), "inactive flag on a clearly active unit"
+    stray = int((flags[y_ref == 0] == 0).sum())
+    assert stray <= max(4, int(1e-4 * raw.size)), f"{stray} units flagged active where the reference output is zero"
+
+
 def check_pool_idx(gpu_idx, ora_idx, prepool_act, y, tol=2e-5):
     """GPU and oracle may pick different window positions only where the two candidates are
     (nearly) tied or where the pooled output is 0 (ReLU: no gradient flows either way).

@@ -16,7 +16,7 @@ from paper_1804_04512_amd import binding as B
 from paper_1804_04512_amd import workloads as wl
 from paper_1804_04512_amd.workloads import ConvSpec
 
-from helpers import ACT, TOL_FWD, TOL_GRAD, check_pool_idx, max_rel_err, odesc, onet
+from helpers import ACT, TOL_FWD, TOL_GRAD, check_idx_bytes, check_idx_flags_against, check_pool_idx, max_rel_err, odesc, onet
 
 pytestmark = pytest.mark.gpu
 
@@ -39,13 +39,15 @@ def rand_layer(cs: ConvSpec, seed: int):
     return x, w, b, dy
 
 
-def gpu_trio(cs: ConvSpec, x, w, b, dy, y_in=None, idx_in=None):
-    """Runs fwd, then bwd and wgrad on (y_in, idx_in) when given, else on the GPU's own."""
+def gpu_trio(cs: ConvSpec, x, w, b, dy, y_in=None, idx_in=None, flagged=False):
+    """Runs fwd, then bwd and wgrad on (y_in, idx_in) when given, else on the GPU's own.
+    flagged: the backward passes get no layer output (pooled ReLU: activity flags in idx).
+    The returned idx is the raw byte the library wrote: position in bits 0-1, ReLU flag in bit 2."""
     xd, wd, bd, dyd = dev(x), dev(w), dev(b), dev(dy)
     y = torch.full(cs.y_shape, float("nan"), device="cuda")
     idx = torch.full(cs.y_shape, 255, dtype=torch.uint8, device="cuda") if cs.pool == 2 else None
     B.dll_conv_valid_fwd(cs, xd, wd, bd, y, idx)
-    yb = y if y_in is None else dev(y_in)
+    yb = None if flagged else (y if y_in is None else dev(y_in))
     ib = idx if idx_in is None else dev(idx_in)
     dx = torch.full(cs.x_shape, float("nan"), device="cuda")
     B.dll_conv_full_bwd(cs, dyd, yb, ib, wd, dx)
@@ -59,11 +61,18 @@ def gpu_trio(cs: ConvSpec, x, w, b, dy, y_in=None, idx_in=None):
 def check_trio(cs: ConvSpec, x, w, b, dy):
     d = odesc(cs)
     y_o, idx_o = orc.conv_valid_fwd(d, x, w, b)
-    y_g, idx_g, _, _, _ = gpu_trio(cs, x, w, b, dy)
+    y_g, raw_g, dx_own, dw_own, db_own = gpu_trio(cs, x, w, b, dy)
     assert max_rel_err(y_g, y_o) <= TOL_FWD
+    idx_g = None
     if cs.pool == 2:
         pre, _ = orc.conv_valid_fwd(odesc(cs, pool=1), x, w, b)
+        idx_g = check_idx_bytes(raw_g, cs.act == "relu", y_g)
         check_pool_idx(idx_g, idx_o, pre, y_o)
+        if cs.act == "relu":
+            # without the layer output the backward passes take act' from the flags: the very
+            # same decisions as y > 0 on the GPU's own y, hence bit-identical results
+            _, _, dx_f, dw_f, db_f = gpu_trio(cs, x, w, b, dy, flagged=True)
+            assert np.array_equal(dx_f, dx_own) and np.array_equal(dw_f, dw_own) and np.array_equal(db_f, db_own)
     # backward ops on identical inputs (the oracle's y and the GPU's own index decisions)
     use_idx = idx_g if cs.pool == 2 else None
     _, _, dx_g, dw_g, db_g = gpu_trio(cs, x, w, b, dy, y_in=y_o, idx_in=use_idx)
@@ -198,8 +207,9 @@ def run_cnn_gpu(w: wl.CnnWorkload, lr, want_grads=True):
     logits = torch.full((w.batch, w.classes), float("nan"), device="cuda")
     ws = B.workspace(B.dll_cnn_workspace_bytes(net))
     B.dll_cnn_train_step(net, params, grads, dev(w.x), dev(w.labels), lr, loss, logits, idx, ws)
+    # idx: window positions (bits 0-1 of the bytes); raw_idx: the bytes as written
     return dict(loss=host(loss)[0], logits=host(logits), grads=[host(g) for g in grads] if grads else None,
-                idx=[host(i) for i in idx], params=[host(p) for p in params])
+                idx=[host(i) & 3 for i in idx], raw_idx=[host(i) for i in idx], params=[host(p) for p in params])
 
 
 def check_cnn(w: wl.CnnWorkload):
@@ -211,6 +221,7 @@ def check_cnn(w: wl.CnnWorkload):
         pre, _ = orc.conv_valid_fwd(odesc(c, pool=1), a, w.params[2 * l], w.params[2 * l + 1])
         a, idx_o = orc.conv_valid_fwd(odesc(c), a, w.params[2 * l], w.params[2 * l + 1])
         check_pool_idx(g["idx"][l], idx_o, pre, a)
+        check_idx_flags_against(g["raw_idx"][l], c.act == "relu", a)
     new = w.clone_params()
     o = orc.cnn_train_step(net, new, w.x, w.labels, w.lr, pool_idx_in=g["idx"])
     assert max_rel_err(np.array([g["loss"]]), np.array([o.loss])) <= TOL_FWD
@@ -246,7 +257,7 @@ def test_config5_full_size_step():
     new = w.clone_params()
     o = orc.cnn_train_step(onet(w), new, w.x, w.labels, w.lr, pool_idx_in=g["idx"])
     for l, (gi, oi) in enumerate(zip(g["idx"], o.pool_idx)):
-        assert gi.max() <= 3
+        assert g["raw_idx"][l].max() <= 7
         differ = int((gi != oi).sum())
         assert differ <= 0.3 * gi.size, f"layer {l}: pooling decisions differ on {differ} of {gi.size} windows"
     assert max_rel_err(np.array([g["loss"]]), np.array([o.loss])) <= TOL_FWD
