@@ -405,20 +405,21 @@ dll_status dll_cnn_train_step(const dll_net_desc *net, float *const *params, flo
   // ---- dense backward: data gradient first (old weights), then weight gradient + update
   for (int q = D - 1; q >= 0; --q) {
     const dll_dense_desc *dd = &net->dense[q];
-    const int act = (q == D - 1) ? ACT_IDENTITY : dd->act;
-    const float *hout = (act == ACT_IDENTITY) ? nullptr : nb.act[L + q + 1];
+    // gcur is dz of layer q: the loss kernel wrote it for the top layer, and each data-gradient
+    // product below multiplies by the next lower layer's act' on its way out
     float *Wq = params[2 * (L + q)], *bq = params[2 * (L + q) + 1];
     GemmArgs g;
     g.M = B; g.N = dd->in; g.Kdim = dd->out;
-    g.A = gcur; g.a_m = dd->out; g.a_k = 1; g.A_out = hout; g.a_act = act;
+    g.A = gcur; g.a_m = dd->out; g.a_k = 1;
     g.B = Wq; g.b_k = dd->in; g.b_n = 1;
     g.Cout = gnext; g.c_m = dd->in; g.c_n = 1;
+    if (q > 0 && net->dense[q - 1].act != DLL_ACT_IDENTITY) { g.C_ref = nb.act[L + q]; g.c_ref_act = net->dense[q - 1].act; }
     g.split_k = gemm_pick_split_k(g.M, g.N, g.Kdim);
     g.partial = nb.partial;
     if ((st = dev(launch_gemm(g, s))) != DLL_OK) return st;
     GemmArgs h;
     h.M = dd->out; h.N = dd->in; h.Kdim = B;
-    h.A = gcur; h.a_m = 1; h.a_k = dd->out; h.A_out = hout; h.a_act = act;
+    h.A = gcur; h.a_m = 1; h.a_k = dd->out;
     h.B = nb.act[L + q]; h.b_k = dd->in; h.b_n = 1;
     h.Cout = grads ? grads[2 * (L + q)] : nullptr; h.c_m = dd->in; h.c_n = 1;
     if (upd) { h.update = Wq; h.step = step; }
@@ -427,7 +428,7 @@ dll_status dll_cnn_train_step(const dll_net_desc *net, float *const *params, flo
       if ((st = dev(launch_gemm(h, s))) != DLL_OK) return st;
     float *gb = grads ? grads[2 * (L + q) + 1] : nullptr;
     if (gb || upd)
-      if ((st = dev(launch_colsum(gcur, hout, act, B, dd->out, gb, upd ? bq : nullptr, step, s))) != DLL_OK) return st;
+      if ((st = dev(launch_colsum(gcur, B, dd->out, gb, upd ? bq : nullptr, step, s))) != DLL_OK) return st;
     float *t = gcur; gcur = gnext; gnext = t;
   }
   // ---- convolution backward: data gradient with the old filters, then filter gradient + update

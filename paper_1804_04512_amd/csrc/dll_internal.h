@@ -98,11 +98,12 @@ struct GemmArgs {
   int M = 0, N = 0, Kdim = 0;
   const float *A = nullptr; long a_m = 0, a_k = 0;   // A(m,k) = A[m*a_m + k*a_k]
   const float *B = nullptr; long b_k = 0, b_n = 0;   // B(k,n) = B[k*b_k + n*b_n]
-  // optional elementwise factor on A: A(m,k) *= act'(Aout[m*a_m+k*a_k]) (dense backward: dzh = dh * act'(h))
-  const float *A_out = nullptr; int a_act = ACT_IDENTITY;
   float *Cout = nullptr; long c_m = 0, c_n = 0;      // nullable when only the update is wanted
   const float *bias = nullptr;                       // [N], added before act
   int act = ACT_IDENTITY;
+  // optional factor applied last: C(m,n) *= act'(C_ref(m,n)), C_ref with the strides of Cout (dense
+  // backward: the data gradient leaves as dz of the layer below, dz = dh * act'(h))
+  const float *C_ref = nullptr; int c_ref_act = ACT_IDENTITY;
   float *update = nullptr; float step = 0.0f;        // nullable: update(m,n) += step * C(m,n), same strides as Cout
   int split_k = 1;
   float *partial = nullptr;                          // split_k * M * N floats when split_k > 1
@@ -110,8 +111,8 @@ struct GemmArgs {
 int gemm_pick_split_k(int M, int N, int Kdim);
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream);
 
-// Column sums with the same optional act' factor: out[n] = sum_m A(m,n)*act'(Aout(m,n)); optional update.
-hipError_t launch_colsum(const float *A, const float *A_out, int a_act, int M, int N, float *out,
+// Column sums out[n] = sum_m A(m,n) of a row-major [M][N] array; optional update.
+hipError_t launch_colsum(const float *A, int M, int N, float *out,
                          float *update, float step, hipStream_t stream);
 
 // Softmax cross-entropy over rows; loss = mean; dlogits = (p - onehot)/B.  rowloss: B floats scratch.

@@ -4,8 +4,9 @@
 // one matrix product, the backward pass one with the transposed weights, the gradient one
 // more.  A single kernel serves all three through element strides:
 //   C(m,n) = sum_k A(m,k) * B(k,n),   A(m,k) = A[m*a_m + k*a_k],  B(k,n) = B[k*b_k + n*b_n]
-// with an optional act'(.) factor on A (dzh = dh * act'(h)), bias + activation, split-K with
-// a fixed-order second pass, and an optional in-place parameter update C_upd += step * C.
+// with bias + activation, an optional act'(.) factor on the result (the data gradient leaves as
+// dz of the layer below), split-K with a fixed-order second pass, and an optional in-place
+// parameter update C_upd += step * C.
 // Workgroup tile 128 x 64 x 32, four wavefronts of 64 x 32 each, register-prefetched k-tiles.
 #include "dll_internal.h"
 
@@ -63,65 +64,23 @@ struct TileRegs {
   float4 v[NV];
 };
 
-// Vector path: every slot is one unconditional 16-byte load from a clamped address followed by
-// a select, so the compiler issues all loads of a tile back to back (no branch, no wait between
-// them).  It requires whole 16-byte groups along the contiguous axis (checked on the host).
-template <int XT, bool KC, bool HAS_OUT>
-__device__ __forceinline__ void tile_load_vec(TileRegs<XT> &t, const float *src, const float *src_out, int act, long sx,
-                                              long sk, int x0, int k0, int X, int Kend) {
-  const int tid = threadIdx.x;
-  float4 v[TileRegs<XT>::NV], o[TileRegs<XT>::NV];
-  bool ok[TileRegs<XT>::NV];
-#pragma unroll
-  for (int it = 0; it < TileRegs<XT>::NV; ++it) {
-    int x, k;
-    if (KC) {   // 8 threads cover the 32 k of one row; 32 rows per pass
-      x = x0 + (tid >> 3) + 32 * it;
-      k = k0 + 4 * (tid & 7);
-    } else {    // XT/4 threads cover one k row
-      constexpr int TPR = XT / 4, RPP = kThreads / TPR;
-      x = x0 + 4 * (tid % TPR);
-      k = k0 + (tid / TPR) + RPP * it;
-    }
-    ok[it] = x < X && k < Kend;
-    const long base = ok[it] ? (long)x * sx + (long)k * sk : 0;
-    v[it] = *reinterpret_cast<const float4 *>(src + base);
-    if (HAS_OUT) o[it] = *reinterpret_cast<const float4 *>(src_out + base);
-  }
-#pragma unroll
-  for (int it = 0; it < TileRegs<XT>::NV; ++it) {
-    float4 r = v[it];
-    if (HAS_OUT) {
-      r.x *= act_deriv(act, o[it].x); r.y *= act_deriv(act, o[it].y);
-      r.z *= act_deriv(act, o[it].z); r.w *= act_deriv(act, o[it].w);
-    }
-    t.v[it] = ok[it] ? r : make_float4(0.f, 0.f, 0.f, 0.f);
-  }
-}
-
 // Generic path: any strides, any alignment, ragged edges (element-wise with range checks).
 template <int XT>
-__device__ __forceinline__ void tile_load(TileRegs<XT> &t, const float *src, const float *src_out, int act, long sx,
-                                          long sk, int x0, int k0, int X, int Kend, bool kcontig, bool vec) {
+__device__ __forceinline__ void tile_load(TileRegs<XT> &t, const float *src, long sx, long sk, int x0, int k0, int X,
+                                          int Kend, bool kcontig, bool vec) {
   const int tid = threadIdx.x;
 #pragma unroll
   for (int it = 0; it < TileRegs<XT>::NV; ++it) {
-    float4 v, o;
+    float4 v;
     if (kcontig) {
       const int x = x0 + (tid >> 3) + 32 * it, k = k0 + 4 * (tid & 7);
       const long base = (long)x * sx + (long)k * sk;
       v = load4(src, base, sk, k, Kend, x < X, vec);
-      if (src_out) o = load4(src_out, base, sk, k, Kend, x < X, vec);
     } else {
       constexpr int TPR = XT / 4, RPP = kThreads / TPR;
       const int x = x0 + 4 * (tid % TPR), k = k0 + (tid / TPR) + RPP * it;
       const long base = (long)x * sx + (long)k * sk;
       v = load4(src, base, sx, x, X, k < Kend, vec);
-      if (src_out) o = load4(src_out, base, sx, x, X, k < Kend, vec);
-    }
-    if (src_out) {
-      v.x *= act_deriv(act, o.x); v.y *= act_deriv(act, o.y);
-      v.z *= act_deriv(act, o.z); v.w *= act_deriv(act, o.w);
     }
     t.v[it] = v;
   }
@@ -149,7 +108,6 @@ __device__ __forceinline__ void tile_store(const TileRegs<XT> &t, float *dst, bo
 // loads are in flight while the current one is multiplied (double-buffered LDS).
 // FAST: both operands take the vector path (A_KC / B_KC say which axis is contiguous, A_OUT
 // whether the act' factor is applied); otherwise the generic loader is used.
-template <bool FAST, bool A_KC, bool B_KC, bool A_OUT>
 __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(const GemmParams p) {
   __shared__ __attribute__((aligned(16))) float As[2][A_TILE];
   __shared__ __attribute__((aligned(16))) float Bs[2][B_TILE];
@@ -159,7 +117,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(const GemmParams p) {
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
   const int kbeg = blockIdx.z * p.k_per_split;
   const int kend = min(a.Kdim, kbeg + p.k_per_split);
-  const bool a_kc = FAST ? A_KC : (a.a_k == 1), b_kc = FAST ? B_KC : (a.b_k == 1);
+  const bool a_kc = a.a_k == 1, b_kc = a.b_k == 1;
   const int alx = a_kc ? LDK : 1, alk = a_kc ? 1 : LDXA;
   const int blx = b_kc ? LDK : 1, blk = b_kc ? 1 : LDXB;
   const int wm = (wave >> 1) * 64, wn = (wave & 1) * 32;
@@ -176,13 +134,8 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(const GemmParams p) {
   TileRegs<BN> tb[2];
   auto load_tiles = [&](auto setc, int k0) {
     constexpr int S_ = decltype(setc)::value;
-    if (FAST) {
-      tile_load_vec<BM, A_KC, A_OUT>(ta[S_], a.A, a.A_out, a.a_act, a.a_m, a.a_k, m0, k0, a.M, kend);
-      tile_load_vec<BN, B_KC, false>(tb[S_], a.B, nullptr, 0, a.b_n, a.b_k, n0, k0, a.N, kend);
-    } else {
-      tile_load<BM>(ta[S_], a.A, a.A_out, a.a_act, a.a_m, a.a_k, m0, k0, a.M, kend, a_kc, p.a_vec);
-      tile_load<BN>(tb[S_], a.B, nullptr, 0, a.b_n, a.b_k, n0, k0, a.N, kend, b_kc, p.b_vec);
-    }
+    tile_load<BM>(ta[S_], a.A, a.a_m, a.a_k, m0, k0, a.M, kend, a_kc, p.a_vec);
+    tile_load<BN>(tb[S_], a.B, a.b_n, a.b_k, n0, k0, a.N, kend, b_kc, p.b_vec);
   };
   auto store_tiles = [&](auto setc, int buf) {
     constexpr int S_ = decltype(setc)::value;
@@ -282,6 +235,11 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(const GemmParams p) {
 #pragma unroll
       for (int v = 0; v < 4; ++v) c[v] = act_apply(a.act, c[v] + ((a.bias && n + v < a.N) ? a.bias[n + v] : 0.0f));
       const long o = (long)m * a.c_m + (long)n * a.c_n;
+      if (a.C_ref) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+          if (n + v < a.N) c[v] *= act_deriv(a.c_ref_act, a.C_ref[o + v * a.c_n]);
+      }
       if (p.c_vec && n + 3 < a.N) {
         if (a.Cout) *reinterpret_cast<float4 *>(a.Cout + o) = make_float4(c[0], c[1], c[2], c[3]);
         if (a.update) {
@@ -301,6 +259,284 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(const GemmParams p) {
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Persistent kernel for the vector-loadable case.  A unit of work is one (m-tile, n-tile,
+// k-split); a workgroup walks units w, w+G, w+2G, ... and treats their k-tiles as ONE stream:
+// the k-tile two places ahead is always in flight from global memory, also across unit
+// boundaries, so neither the first loads of a unit nor (update mode) the parameter tile that
+// the epilogue needs are waited for with the MFMA pipe idle.  Offsets are 32-bit byte
+// offsets from the operand bases (the host checks the extents), one add per load.
+// LDS holds k-contiguous sources as [x][34] and x-contiguous ones as [k][XT] with the x index
+// XOR-ed by 16 on odd k: both give conflict-free operand reads, and two buffers of both
+// operands stay under a third of the CU's LDS (three workgroups per CU).
+constexpr int FA_TILE = BM * LDK;   // 4352 floats >= BK * BM
+constexpr int FB_TILE = BN * LDK;   // 2176 floats >= BK * BN
+
+template <int XT, bool KC>
+struct SlotGeom {
+  static constexpr int NV = XT * BK / 4 / kThreads;
+  static constexpr int TPR = XT / 4, RPP = kThreads / TPR;
+  __device__ static int xl(int tid, int it) { return KC ? (tid >> 3) + 32 * it : 4 * (tid % TPR); }
+  __device__ static int kl(int tid, int it) { return KC ? 4 * (tid & 7) : (tid / TPR) + RPP * it; }
+};
+
+template <int XT, bool KC>
+__device__ __forceinline__ void fast_tile_load(TileRegs<XT> &t, const float *src,
+                                               const unsigned (&slot)[SlotGeom<XT, KC>::NV], unsigned sx, unsigned sk,
+                                               int x0, int k0, int X, int Kend) {
+  using G = SlotGeom<XT, KC>;
+  const int tid = threadIdx.x;
+  const unsigned base = 4u * ((unsigned)x0 * sx + (unsigned)k0 * sk);   // uniform
+  const char *sb = reinterpret_cast<const char *>(src);
+  float4 v[G::NV];
+  if (x0 + XT <= X && k0 + BK <= Kend) {   // whole tile inside: plain loads
+#pragma unroll
+    for (int it = 0; it < G::NV; ++it) {
+      const unsigned off = base + slot[it];
+      v[it] = *reinterpret_cast<const float4 *>(sb + off);
+    }
+  } else {                                  // edge tile: clamped address, then select
+    bool ok[G::NV];
+#pragma unroll
+    for (int it = 0; it < G::NV; ++it) {
+      ok[it] = x0 + G::xl(tid, it) < X && k0 + G::kl(tid, it) < Kend;
+      const unsigned off = ok[it] ? base + slot[it] : 0u;
+      v[it] = *reinterpret_cast<const float4 *>(sb + off);
+    }
+#pragma unroll
+    for (int it = 0; it < G::NV; ++it)
+      if (!ok[it]) v[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+#pragma unroll
+  for (int it = 0; it < G::NV; ++it) t.v[it] = v[it];
+}
+
+template <int XT, bool KC>
+__device__ __forceinline__ void fast_tile_store(const TileRegs<XT> &t, float *dst) {
+  using G = SlotGeom<XT, KC>;
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int it = 0; it < G::NV; ++it) {
+    const int x = G::xl(tid, it), k = G::kl(tid, it);
+    if (KC) {
+      float2 *d = reinterpret_cast<float2 *>(dst + x * LDK + k);
+      d[0] = make_float2(t.v[it].x, t.v[it].y);
+      d[1] = make_float2(t.v[it].z, t.v[it].w);
+    } else {
+      *reinterpret_cast<float4 *>(dst + k * XT + (x ^ ((k & 1) << 4))) = t.v[it];
+    }
+  }
+}
+
+struct UnitPos {
+  int unit;        // index of the (m-tile, n-tile, split) unit, or >= units when the stream has ended
+  int kt, nkt;     // k-tile inside the unit, number of k-tiles of the unit
+  int m0, n0, kbeg, kend, z;
+};
+
+template <bool A_KC, bool B_KC>
+__global__ __launch_bounds__(kThreads, 3) void gemm_fast_kernel(const GemmParams p) {
+  __shared__ __attribute__((aligned(16))) float As[2][FA_TILE];
+  __shared__ __attribute__((aligned(16))) float Bs[2][FB_TILE];
+  const GemmArgs &a = p.a;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i16 = lane & 15, kq = lane >> 4;
+  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 32;
+  const int tiles_n = (a.N + BN - 1) / BN, tiles_m = (a.M + BM - 1) / BM;
+  const int units = tiles_m * tiles_n * a.split_k;
+  const unsigned a_sx = (unsigned)a.a_m, a_sk = (unsigned)a.a_k, b_sx = (unsigned)a.b_n, b_sk = (unsigned)a.b_k;
+
+  auto locate = [&](UnitPos &u) __attribute__((always_inline)) {   // fills the fields that follow from u.unit
+    if (u.unit >= units) return;
+    const int tile = u.unit / a.split_k;
+    u.z = u.unit - tile * a.split_k;
+    u.m0 = (tile / tiles_n) * BM;
+    u.n0 = (tile % tiles_n) * BN;
+    u.kbeg = u.z * p.k_per_split;
+    u.kend = min(a.Kdim, u.kbeg + p.k_per_split);
+    u.nkt = max(1, (u.kend - u.kbeg + BK - 1) / BK);   // an empty split still writes its zero partial
+    u.kt = 0;
+  };
+  auto advance = [&](UnitPos &u) __attribute__((always_inline)) {
+    if (++u.kt < u.nkt) return;
+    u.unit += gridDim.x;
+    locate(u);
+  };
+
+  // per-slot byte offsets inside a tile (constant for the whole kernel)
+  unsigned sa[SlotGeom<BM, A_KC>::NV], sb[SlotGeom<BN, B_KC>::NV];
+#pragma unroll
+  for (int it = 0; it < SlotGeom<BM, A_KC>::NV; ++it)
+    sa[it] = 4u * ((unsigned)SlotGeom<BM, A_KC>::xl(tid, it) * a_sx + (unsigned)SlotGeom<BM, A_KC>::kl(tid, it) * a_sk);
+#pragma unroll
+  for (int it = 0; it < SlotGeom<BN, B_KC>::NV; ++it)
+    sb[it] = 4u * ((unsigned)SlotGeom<BN, B_KC>::xl(tid, it) * b_sx + (unsigned)SlotGeom<BN, B_KC>::kl(tid, it) * b_sk);
+
+  TileRegs<BM> ta[2];
+  TileRegs<BN> tb[2];
+  auto load_tiles = [&](auto setc, const UnitPos &u) __attribute__((always_inline)) {
+    constexpr int S_ = decltype(setc)::value;
+    const int k0 = u.kbeg + u.kt * BK;
+    fast_tile_load<BM, A_KC>(ta[S_], a.A, sa, a_sx, a_sk, u.m0, k0, a.M, u.kend);
+    fast_tile_load<BN, B_KC>(tb[S_], a.B, sb, b_sx, b_sk, u.n0, k0, a.N, u.kend);
+  };
+  auto store_tiles = [&](auto setc, int buf) __attribute__((always_inline)) {
+    constexpr int S_ = decltype(setc)::value;
+    fast_tile_store<BM, A_KC>(ta[S_], As[buf]);
+    fast_tile_store<BN, B_KC>(tb[S_], Bs[buf]);
+  };
+
+  // operand read pointers: fragment i of A sits 16*i rows (or columns) after the base; in the
+  // swizzled layout lanes with odd k read even fragments 16 higher and odd ones 16 lower
+  const int dsw = (kq & 1) << 4;
+  const float *Ae = A_KC ? As[0] + (wm + i16) * LDK + kq : As[0] + kq * BM + wm + i16 + dsw;
+  const float *Ao = A_KC ? Ae : As[0] + kq * BM + wm + i16 - dsw;
+  const float *Be = B_KC ? Bs[0] + (wn + i16) * LDK + kq : Bs[0] + kq * BN + wn + i16 + dsw;
+  const float *Bo = B_KC ? Be : Bs[0] + kq * BN + wn + i16 - dsw;
+  constexpr int a_fx = A_KC ? 16 * LDK : 16, a_fk = A_KC ? 4 : 4 * BM;   // fragment and k-step strides
+  constexpr int b_fx = B_KC ? 16 * LDK : 16, b_fk = B_KC ? 4 : 4 * BN;
+
+  floatx4 acc[4][2];
+  auto clear_acc = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+  };
+  clear_acc();
+
+  auto multiply = [&](int buf) __attribute__((always_inline)) {
+    const int ao = buf * FA_TILE, bo = buf * FB_TILE;
+    float af[2][4], bf[2][2];
+    auto load_frags = [&](auto bc, int s) __attribute__((always_inline)) {
+      constexpr int B_ = decltype(bc)::value;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) af[B_][i] = ((i & 1) ? Ao : Ae)[ao + i * a_fx + s * a_fk];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) bf[B_][j] = ((j & 1) ? Bo : Be)[bo + j * b_fx + s * b_fk];
+    };
+    auto mfma_frags = [&](auto bc) __attribute__((always_inline)) {
+      constexpr int B_ = decltype(bc)::value;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf[B_][j], af[B_][i], acc[i][j], 0, 0, 0);
+    };
+    load_frags(std::integral_constant<int, 0>{}, 0);
+#pragma unroll
+    for (int s = 0; s < BK / 4; s += 2) {
+      load_frags(std::integral_constant<int, 1>{}, s + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_frags(std::integral_constant<int, 0>{});
+      __builtin_amdgcn_sched_barrier(0);
+      if (s + 2 < BK / 4) load_frags(std::integral_constant<int, 0>{}, s + 2);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_frags(std::integral_constant<int, 1>{});
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  // parameter tile of the unit whose last k-tile is about to be multiplied (update mode)
+  const bool upd_mode = a.update && p.c_vec && a.split_k == 1;
+  float4 upd[4][2];
+  auto prefetch_update = [&](const UnitPos &u) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int m = u.m0 + wm + i * 16 + i16, n = u.n0 + wn + j * 16 + 4 * kq;
+        const bool ok = m < a.M && n + 3 < a.N;
+        upd[i][j] = *reinterpret_cast<const float4 *>(a.update + (ok ? (long)m * a.c_m + (long)n * a.c_n : 0));
+      }
+  };
+
+  // lane holds C(m = i16, n = 4*kq + v) of each 16x16 tile
+  auto epilogue = [&](const UnitPos &u) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int m = u.m0 + wm + i * 16 + i16;
+      if (m >= a.M) continue;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int n = u.n0 + wn + j * 16 + 4 * kq;
+        if (n >= a.N) continue;
+        float c[4] = {acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]};
+        if (a.split_k > 1) {
+          float *d = a.partial + ((long)u.z * a.M + m) * a.N + n;
+          if (n + 3 < a.N && (a.N & 3) == 0) {
+            *reinterpret_cast<float4 *>(d) = make_float4(c[0], c[1], c[2], c[3]);
+          } else {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+              if (n + v < a.N) d[v] = c[v];
+          }
+          continue;
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) c[v] = act_apply(a.act, c[v] + ((a.bias && n + v < a.N) ? a.bias[n + v] : 0.0f));
+        const long o = (long)m * a.c_m + (long)n * a.c_n;
+        if (a.C_ref) {
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            if (n + v < a.N) c[v] *= act_deriv(a.c_ref_act, a.C_ref[o + v * a.c_n]);
+        }
+        if (p.c_vec && n + 3 < a.N) {
+          if (a.Cout) *reinterpret_cast<float4 *>(a.Cout + o) = make_float4(c[0], c[1], c[2], c[3]);
+          if (a.update) {
+            float4 w4 = upd[i][j];
+            w4.x += a.step * c[0]; w4.y += a.step * c[1]; w4.z += a.step * c[2]; w4.w += a.step * c[3];
+            *reinterpret_cast<float4 *>(a.update + o) = w4;
+          }
+        } else {
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            if (n + v < a.N) {
+              if (a.Cout) a.Cout[o + v * a.c_n] = c[v];
+              if (a.update) a.update[o + v * a.c_n] += a.step * c[v];
+            }
+        }
+      }
+    }
+  };
+
+  using S0 = std::integral_constant<int, 0>;
+  using S1 = std::integral_constant<int, 1>;
+  UnitPos cur, ld;
+  cur.unit = blockIdx.x;
+  locate(cur);
+  if (cur.unit >= units) return;
+  ld = cur;
+  load_tiles(S0{}, ld);
+  advance(ld);
+  if (ld.unit < units) { load_tiles(S1{}, ld); advance(ld); }
+  store_tiles(S0{}, 0);
+  __syncthreads();
+  // one step: LDS buffer BUF holds the stream's current k-tile, register set 1-BUF the next one
+  auto step = [&](auto bufc) __attribute__((always_inline)) -> bool {
+    constexpr int BUF = decltype(bufc)::value;
+    using SAME = std::integral_constant<int, BUF>;
+    using OTHER = std::integral_constant<int, 1 - BUF>;
+    const bool last_kt = cur.kt + 1 == cur.nkt;
+    const bool more = !(last_kt && cur.unit + (int)gridDim.x >= units);   // a k-tile follows in the stream
+    if (ld.unit < units) { load_tiles(SAME{}, ld); advance(ld); }         // two places ahead
+    if (last_kt && upd_mode) prefetch_update(cur);
+    multiply(BUF);
+    if (more) store_tiles(OTHER{}, 1 - BUF);
+    __syncthreads();
+    if (last_kt) {
+      epilogue(cur);
+      clear_acc();
+    }
+    advance(cur);
+    return more;
+  };
+  while (true) {
+    if (!step(S0{})) break;
+    if (!step(S1{})) break;
+  }
+}
+
 __global__ __launch_bounds__(kThreads) void gemm_splitk_reduce_kernel(const GemmArgs a) {
   const long total = (long)a.M * a.N;
   for (long e = (long)blockIdx.x * kThreads + threadIdx.x; e < total; e += (long)gridDim.x * kThreads) {
@@ -310,16 +546,17 @@ __global__ __launch_bounds__(kThreads) void gemm_splitk_reduce_kernel(const Gemm
     if (a.bias) c += a.bias[n];
     c = act_apply(a.act, c);
     const long o = (long)m * a.c_m + (long)n * a.c_n;
+    if (a.C_ref) c *= act_deriv(a.c_ref_act, a.C_ref[o]);
     if (a.Cout) a.Cout[o] = c;
     if (a.update) a.update[o] += a.step * c;
   }
 }
 
-// out[n] = sum_m A[m][n] * act'(Aout[m][n]): 16 columns per workgroup, 16 row slices added
+// out[n] = sum_m A[m][n]: 16 columns per workgroup, 16 row slices added
 // in a fixed order (small inputs: many short independent load chains beat few long ones).
 constexpr int kColsumCols = 16, kColsumSlices = kThreads / kColsumCols;
-__global__ __launch_bounds__(kThreads) void colsum_kernel(const float *A, const float *A_out, int act, int M, int N,
-                                                         float *out, float *update, float step) {
+__global__ __launch_bounds__(kThreads) void colsum_kernel(const float *A, int M, int N, float *out, float *update,
+                                                         float step) {
   __shared__ float part[kColsumSlices][kColsumCols + 1];
   const int col = threadIdx.x % kColsumCols, slice = threadIdx.x / kColsumCols;
   const int n = blockIdx.x * kColsumCols + col;
@@ -327,9 +564,7 @@ __global__ __launch_bounds__(kThreads) void colsum_kernel(const float *A, const 
   if (n < N) {
 #pragma unroll 4
     for (int m = slice; m < M; m += kColsumSlices) {
-      float v = A[(long)m * N + n];
-      if (A_out) v *= act_deriv(act, A_out[(long)m * N + n]);
-      s += v;
+      s += A[(long)m * N + n];
     }
   }
   part[slice][col] = s;
@@ -454,26 +689,31 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream) {
   p.k_per_split = ((ksteps + p.a.split_k - 1) / p.a.split_k) * BK;
   auto al16 = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
   // 16-byte loads need an aligned base and a leading stride of whole vectors
-  p.a_vec = al16(a.A) && (!a.A_out || al16(a.A_out)) && ((a.a_k == 1 ? a.a_m : a.a_k) % 4 == 0) && (a.a_k == 1 || a.a_m == 1);
+  p.a_vec = al16(a.A) && ((a.a_k == 1 ? a.a_m : a.a_k) % 4 == 0) && (a.a_k == 1 || a.a_m == 1);
   p.b_vec = al16(a.B) && ((a.b_k == 1 ? a.b_n : a.b_k) % 4 == 0) && (a.b_k == 1 || a.b_n == 1);
   p.c_vec = a.c_n == 1 && a.c_m % 4 == 0 && (!a.Cout || al16(a.Cout)) && (!a.update || al16(a.update));
   dim3 grid((a.N + BN - 1) / BN, (a.M + BM - 1) / BM, p.a.split_k);
-  // whole 16-byte groups along each operand's contiguous axis, and the k ranges of the splits
-  // start on multiples of 32: then both operands take the branch-free vector loader
+  // whole 16-byte groups along each operand's contiguous axis, the k ranges of the splits start
+  // on multiples of 32, and every operand element lies within 4 GiB of its base (32-bit byte
+  // offsets): then the persistent vector kernel runs, else the generic one
   const bool a_kc = a.a_k == 1, b_kc = a.b_k == 1;
-  const bool fast = p.a_vec && p.b_vec && (a_kc ? a.Kdim % 4 == 0 : a.M % 4 == 0) && (b_kc ? a.Kdim % 4 == 0 : a.N % 4 == 0);
-  const bool has_out = a.A_out != nullptr;
-#define DLL_GEMM_LAUNCH(F, AK, BK_, AO) hipLaunchKernelGGL((gemm_kernel<F, AK, BK_, AO>), grid, dim3(kThreads), 0, stream, p)
-  if (!fast) DLL_GEMM_LAUNCH(false, false, false, false);
-  else if (a_kc && b_kc && !has_out) DLL_GEMM_LAUNCH(true, true, true, false);
-  else if (a_kc && b_kc && has_out) DLL_GEMM_LAUNCH(true, true, true, true);
-  else if (a_kc && !b_kc && !has_out) DLL_GEMM_LAUNCH(true, true, false, false);
-  else if (a_kc && !b_kc && has_out) DLL_GEMM_LAUNCH(true, true, false, true);
-  else if (!a_kc && b_kc && !has_out) DLL_GEMM_LAUNCH(true, false, true, false);
-  else if (!a_kc && b_kc && has_out) DLL_GEMM_LAUNCH(true, false, true, true);
-  else if (!has_out) DLL_GEMM_LAUNCH(true, false, false, false);
-  else DLL_GEMM_LAUNCH(true, false, false, true);
+  const auto extent = [](long n0, long s0, long n1, long s1) { return 4 * ((n0 - 1) * s0 + (n1 - 1) * s1 + 4); };
+  const bool small = extent(a.M, a.a_m, a.Kdim, a.a_k) < (1L << 32) && extent(a.N, a.b_n, a.Kdim, a.b_k) < (1L << 32) &&
+                     a.a_m >= 0 && a.a_k >= 0 && a.b_n >= 0 && a.b_k >= 0;
+  const bool fast = small && p.a_vec && p.b_vec && (a_kc ? a.Kdim % 4 == 0 : a.M % 4 == 0) &&
+                    (b_kc ? a.Kdim % 4 == 0 : a.N % 4 == 0);
+  if (!fast) {
+    hipLaunchKernelGGL(gemm_kernel, grid, dim3(kThreads), 0, stream, p);
+  } else {
+    const long units = (long)grid.x * grid.y * grid.z;
+    const dim3 pgrid((unsigned)(units < 768 ? units : 768));   // three resident workgroups per CU
+#define DLL_GEMM_LAUNCH(AK, BK_) hipLaunchKernelGGL((gemm_fast_kernel<AK, BK_>), pgrid, dim3(kThreads), 0, stream, p)
+    if (a_kc && b_kc) DLL_GEMM_LAUNCH(true, true);
+    else if (a_kc && !b_kc) DLL_GEMM_LAUNCH(true, false);
+    else if (!a_kc && b_kc) DLL_GEMM_LAUNCH(false, true);
+    else DLL_GEMM_LAUNCH(false, false);
 #undef DLL_GEMM_LAUNCH
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (p.a.split_k > 1) {
@@ -486,10 +726,9 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream) {
   return e;
 }
 
-hipError_t launch_colsum(const float *A, const float *A_out, int a_act, int M, int N, float *out, float *update,
-                         float step, hipStream_t stream) {
-  hipLaunchKernelGGL(colsum_kernel, dim3((N + kColsumCols - 1) / kColsumCols), dim3(kThreads), 0, stream, A, A_out, a_act, M, N,
-                     out, update, step);
+hipError_t launch_colsum(const float *A, int M, int N, float *out, float *update, float step, hipStream_t stream) {
+  hipLaunchKernelGGL(colsum_kernel, dim3((N + kColsumCols - 1) / kColsumCols), dim3(kThreads), 0, stream, A, M, N, out, update,
+                     step);
   return hipGetLastError();
 }
 
