@@ -681,8 +681,10 @@ hipError_t launch_3x3(const ConvEngineArgs &a, hipStream_t stream) {
   if (resident > by_regs) resident = by_regs;
   long blocks = 256 * resident / p.g.kgroups;
   if (blocks < 1) blocks = 1;
-  const long rounds = (tiles + blocks - 1) / blocks;
-  blocks = (tiles + rounds - 1) / rounds;   // same number of rounds, evenly filled
+  // Every CU gets its full set of resident workgroups even when the tiles do not divide evenly:
+  // the workgroups of one CU share its MFMA pipes, so what has to balance is the tile count per
+  // CU (workgroups b, b+256, b+512, ... land on the same CU), not per workgroup.
+  if (blocks > tiles) blocks = tiles;
   if (blocks >= 8) blocks = (blocks + 7) / 8 * 8;   // whole rows of XCDs (see the tile order in the kernel)
   dim3 grid((unsigned)blocks, (unsigned)p.g.kgroups, 1);
   auto launch = [&](auto kern) -> hipError_t {

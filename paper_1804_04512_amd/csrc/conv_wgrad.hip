@@ -483,11 +483,18 @@ __global__ __launch_bounds__(kThreads) void wgrad_reduce_kernel(const WgradReduc
     }
   }
   if (out_index >= 0) {
-#pragma unroll 4
-    for (int pidx = slice; pidx < plan.n_partials; pidx += kRedSlices) {
-      double t = (double)a.pos[base + pidx * stride];
-      if (a.neg) t -= (double)a.neg[base + pidx * stride];
-      sum += t;
+    // loads first, sums after: eight independent loads are in flight per thread
+    for (int p0 = slice; p0 < plan.n_partials; p0 += 8 * kRedSlices) {
+      float pv[8], nv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int pidx = p0 + u * kRedSlices;
+        const bool in = pidx < plan.n_partials;
+        pv[u] = in ? a.pos[base + pidx * stride] : 0.0f;
+        nv[u] = (in && a.neg) ? a.neg[base + pidx * stride] : 0.0f;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) sum += (double)pv[u] - (double)nv[u];
     }
   }
   red[slice][oq] = sum;
