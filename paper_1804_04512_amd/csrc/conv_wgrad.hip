@@ -444,78 +444,98 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
   }
 }
 
-// One workgroup per 4 outputs (consecutive taps of one filter); 64 slices of the partial
-// list are summed in parallel in double, then combined in a fixed order (the partial buffers
-// are small and L2-resident; what matters is how many independent loads are in flight).
-constexpr int kRedOut = 4, kRedSlices = kThreads / kRedOut;
+// Second pass over the partial blocks.  A block is laid out [mf][nt][v][lane] and a lane's 16
+// neighbours are 16 consecutive taps of one filter, i.e. (inside a channel chunk) consecutive
+// elements of dw.  A workgroup owns 16 such floats of the block layout: four threads read them
+// as 16-byte groups, 64 slices of the partial list run in parallel, sums are kept in double
+// and combined in a fixed order.  Blocks past the dw part sum the bias partials [g][K].
+constexpr int kRedSlices = kThreads / 4;
 __global__ __launch_bounds__(kThreads) void wgrad_reduce_kernel(const WgradReduceArgs a, const WgradPlan plan,
-                                                               long group_stride, int ndw) {
-  __shared__ double red[kRedSlices][kRedOut + 1];
-  __shared__ double red2[4][kRedOut + 1];
-  const int tid = threadIdx.x, oq = tid % kRedOut, slice = tid / kRedOut;
+                                                               long group_stride, int kgroups) {
+  __shared__ double red[kRedSlices][17];
+  __shared__ double red2[4][17];
+  const int tid = threadIdx.x, t4 = tid & 3, slice = tid >> 2;
   const int RSf = a.R * a.S;
-  const int blk = blockIdx.x;
-  const int nblk_dw = (ndw + kRedOut - 1) / kRedOut;
-  double sum = 0.0;
-  int out_index = -1;
-  long base = 0, stride = 0;
-  if (blk < nblk_dw) {
-    const int o = blk * kRedOut + oq;   // flat index into dw[K][C][R][S]
-    if (o < ndw) {
-      const int ko = o / (a.C * RSf), rem = o - ko * (a.C * RSf);
-      const int ci = rem / RSf, rs = rem - ci * RSf;
-      const int chunk = ci / plan.CC, cl = ci - chunk * plan.CC;
-      const int tap = cl * RSf + rs;
-      const int grp = ko / (plan.MTF * 16), m = ko - grp * (plan.MTF * 16);
-      const int mf = m >> 4, lq = (m & 15) >> 2, v = m & 3;
-      const int nt = tap >> 4, lane = lq * 16 + (tap & 15);
-      const long within = ((long)(mf * plan.NTT + nt) * 4 + v) * 64 + lane;
-      stride = (long)plan.MTF * plan.NTT * 256;
-      base = (long)grp * group_stride + (long)chunk * plan.n_partials * stride + within;
-      out_index = o;
-    }
-  } else {
-    const int k = (blk - nblk_dw) * kRedOut + oq;
-    if (k < a.K) {
-      stride = a.K;
-      base = plan.db_offset + k;
-      out_index = k;
-    }
-  }
-  if (out_index >= 0) {
-    // loads first, sums after: eight independent loads are in flight per thread
-    for (int p0 = slice; p0 < plan.n_partials; p0 += 8 * kRedSlices) {
-      float pv[8], nv[8];
+  const int rows = plan.MTF * plan.NTT * 4;           // 64-float rows of a block
+  const int per_chunk = rows * 4;                     // workgroups per (filter group, chunk)
+  const int nblk_dw = kgroups * plan.nchunks * per_chunk;
+  const long blockf = (long)rows * 64;
+  int blk = blockIdx.x;
+  double sum[4] = {0.0, 0.0, 0.0, 0.0};
+  const bool is_dw = blk < nblk_dw;
+  int grp = 0, chunk = 0, within0 = 0;
+  if (is_dw) {
+    grp = blk / (plan.nchunks * per_chunk);
+    blk -= grp * plan.nchunks * per_chunk;
+    chunk = blk / per_chunk;
+    within0 = (blk - chunk * per_chunk) * 16;
+    const long base = (long)grp * group_stride + (long)chunk * plan.n_partials * blockf + within0 + 4 * t4;
+    // loads first, sums after: four independent 16-byte loads are in flight per thread
+    for (int p0 = slice; p0 < plan.n_partials; p0 += 4 * kRedSlices) {
+      float4 pv[4], nv[4];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
+      for (int u = 0; u < 4; ++u) {
         const int pidx = p0 + u * kRedSlices;
         const bool in = pidx < plan.n_partials;
-        pv[u] = in ? a.pos[base + pidx * stride] : 0.0f;
-        nv[u] = (in && a.neg) ? a.neg[base + pidx * stride] : 0.0f;
+        const long o = base + (in ? pidx : 0) * blockf;
+        pv[u] = *reinterpret_cast<const float4 *>(a.pos + o);
+        nv[u] = a.neg ? *reinterpret_cast<const float4 *>(a.neg + o) : make_float4(0.f, 0.f, 0.f, 0.f);
+        if (!in) { pv[u] = make_float4(0.f, 0.f, 0.f, 0.f); nv[u] = pv[u]; }
       }
 #pragma unroll
-      for (int u = 0; u < 8; ++u) sum += (double)pv[u] - (double)nv[u];
+      for (int u = 0; u < 4; ++u) {
+        sum[0] += (double)pv[u].x - (double)nv[u].x;
+        sum[1] += (double)pv[u].y - (double)nv[u].y;
+        sum[2] += (double)pv[u].z - (double)nv[u].z;
+        sum[3] += (double)pv[u].w - (double)nv[u].w;
+      }
+    }
+  } else {
+    const int k = (blk - nblk_dw) * 16 + 4 * t4;
+    for (int pidx = slice; pidx < plan.n_partials; pidx += kRedSlices) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (k + j < a.K) {
+          double t = (double)a.pos[plan.db_offset + (long)pidx * a.K + k + j];
+          if (a.neg) t -= (double)a.neg[plan.db_offset + (long)pidx * a.K + k + j];
+          sum[j] += t;
+        }
+      }
     }
   }
-  red[slice][oq] = sum;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) red[slice][4 * t4 + j] = sum[j];
   __syncthreads();
-  if (tid < 4 * kRedOut) {   // four threads per output, 16 slices each
-    const int part = tid / kRedOut;
+  if (tid < 64) {   // four threads per output, 16 slices each
+    const int part = tid >> 4, o16 = tid & 15;
     double s = 0.0;
 #pragma unroll
-    for (int q = 0; q < kRedSlices / 4; ++q) s += red[part * (kRedSlices / 4) + q][oq];
-    red2[part][oq] = s;
+    for (int q = 0; q < kRedSlices / 4; ++q) s += red[part * (kRedSlices / 4) + q][o16];
+    red2[part][o16] = s;
   }
   __syncthreads();
-  if (tid < kRedOut && out_index >= 0) {
-    const double s = (red2[0][oq] + red2[1][oq]) + (red2[2][oq] + red2[3][oq]);
+  if (tid < 16) {
+    const double s = (red2[0][tid] + red2[1][tid]) + (red2[2][tid] + red2[3][tid]);
     const float gval = (float)(s * (double)a.scale);
-    if (blk < nblk_dw) {
-      if (a.dw) a.dw[out_index] = gval;
-      if (a.w_update) a.w_update[out_index] += a.step * gval;
+    if (is_dw) {
+      // position in the block layout -> (filter, channel, tap)
+      const int within = within0 + tid;
+      const int row = within >> 6, lane = within & 63;
+      const int v = row & 3, nt = (row >> 2) % plan.NTT, mf = (row >> 2) / plan.NTT;
+      const int m = mf * 16 + (lane >> 4) * 4 + v, tap = nt * 16 + (lane & 15);
+      const int cl = tap / RSf, rs = tap - cl * RSf;
+      const int ko = grp * plan.MTF * 16 + m, ci = chunk * plan.CC + cl;
+      if (cl < plan.CC && ci < a.C && ko < a.K) {
+        const long o = ((long)ko * a.C + ci) * RSf + rs;
+        if (a.dw) a.dw[o] = gval;
+        if (a.w_update) a.w_update[o] += a.step * gval;
+      }
     } else {
-      if (a.db) a.db[out_index] = gval;
-      if (a.b_update) a.b_update[out_index] += a.step * gval;
+      const int k = (blk - nblk_dw) * 16 + tid;
+      if (k < a.K) {
+        if (a.db) a.db[k] = gval;
+        if (a.b_update) a.b_update[k] += a.step * gval;
+      }
     }
   }
 }
@@ -667,10 +687,12 @@ hipError_t launch_wgrad(const WgradArgs &a, const WgradPlan &plan, hipStream_t s
 }
 
 hipError_t launch_wgrad_reduce(const WgradReduceArgs &a, const WgradPlan &plan, hipStream_t stream) {
-  const int ndw = a.K * a.C * a.R * a.S;
-  const long group_stride = (long)plan.nchunks * plan.n_partials * ((long)plan.MTF * plan.NTT * 256);
-  const int blocks = (ndw + kRedOut - 1) / kRedOut + (a.K + kRedOut - 1) / kRedOut;
-  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(blocks), dim3(kThreads), 0, stream, a, plan, group_stride, ndw);
+  const long blockf = (long)plan.MTF * plan.NTT * 256;
+  const long group_stride = (long)plan.nchunks * plan.n_partials * blockf;
+  const int kgroups = (a.K + plan.MTF * 16 - 1) / (plan.MTF * 16);
+  const int blocks = kgroups * plan.nchunks * plan.MTF * plan.NTT * 16 + (a.K + 15) / 16;
+  if ((reinterpret_cast<uintptr_t>(a.pos) & 15u) || (a.neg && (reinterpret_cast<uintptr_t>(a.neg) & 15u))) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(blocks), dim3(kThreads), 0, stream, a, plan, group_stride, kgroups);
   return hipGetLastError();
 }
 

@@ -71,7 +71,7 @@ struct WgradPlan {
   size_t lds_bytes;
   size_t partial_floats; // dw partials followed by db partials
   size_t db_offset;      // float offset of the db partials
-  int n_partials;        // per chunk: 4 * G
+  int n_partials;        // per chunk: one block per workgroup (G)
 };
 
 bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, WgradPlan *plan);
