@@ -36,6 +36,7 @@ struct EngineGeom {
   int KC, KS;        // padded taps per chunk (multiple of 4), MFMA steps per chunk
   int tiles_x, tiles_y;
   int kgroups;       // groups of NT*16 output channels (gridDim.y)
+  unsigned src_bytes; // 3x3 instance: bytes of the source tensor (below 2 GiB)
 };
 
 struct EngineParams {
@@ -331,12 +332,6 @@ __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void 
   constexpr int TH = 16, ROWS = TH + 2, C4 = CC / 4;
   constexpr int RS = 36, PS = round_up_mod_c(RS * ROWS, 8, 2);
   constexpr int KC = CC * 9;
-  // staging registers per thread: plain rows, or pooled rows (u = oy0/2 - 1 + pr, pr = 0 .. TH/2 + 1)
-  constexpr int PR = TH / 2 + 2;
-  constexpr int LINES = CC * (SRC == 2 ? PR : ROWS);
-  constexpr int VPL = SRC == 2 ? 4 : 8;   // 16-byte groups per line
-  constexpr int NI = (LINES * VPL + NTHR - 1) / NTHR;
-  constexpr int NH = (LINES * 2 + NTHR - 1) / NTHR;
   extern __shared__ float lds[];
   const ConvEngineArgs &a = p.a;
   const EngineGeom &g = p.g;
@@ -364,10 +359,64 @@ __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void 
     wl[e] = v;
   }
 
-  float4 vi[NI], yi[NI];
-  uchar4 ii[NI];
-  float vh[NH], yh[NH];
-  unsigned char ih[NH];
+  // ---- staging: global -> registers -> LDS halo tile xs[cl][18 rows][36]: tile column t lives at
+  // LDS column t + 2, the left halo at column 1, the right one at column 34.
+  // Slots are dealt so that a thread's slot in round `it` differs from round 0 only by whole
+  // channels: its global offset and LDS address are fixed for the whole kernel, the per-round part
+  // is uniform (scalar offset of the buffer load, immediate of the LDS store).  Loads are
+  // range-checked buffer loads: a slot outside the image, beyond the last channel or beyond the
+  // slot count gets an offset past the end of the buffer and reads zeros, which is exactly the
+  // padding value; no branch, no select.
+  constexpr unsigned kOob = 0x80000000u;          // byte offset beyond any buffer (tensors are < 2 GiB)
+  const __amdgpu_buffer_rsrc_t rs_src = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.src), 0, (int)g.src_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.src_y ? a.src_y : a.src), 0, (int)g.src_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_idx = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char *>(a.src_idx ? a.src_idx : reinterpret_cast<const unsigned char *>(a.src)), 0, (int)(g.src_bytes >> 2), 0x00020000);
+  auto ld4 = [&](const __amdgpu_buffer_rsrc_t &r, unsigned voff, unsigned soff) __attribute__((always_inline)) {
+    const floatx4 v = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0));
+    return make_float4(v[0], v[1], v[2], v[3]);
+  };
+  auto ld1 = [&](const __amdgpu_buffer_rsrc_t &r, unsigned voff, unsigned soff) __attribute__((always_inline)) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0));
+  };
+  const bool need_y = SRC == 2 ? reads_output(a.src_act) : (SRC == 1 && a.src_act != ACT_IDENTITY);
+  // source plane geometry in elements (SRC == 2: the pooled planes)
+  const int SH = SRC == 2 ? Hp : a.Hin, SW = SRC == 2 ? Wp : a.Win;
+  const unsigned plane = (unsigned)SH * SW;
+
+  // slot classes (TR = tile rows of the source: 16 plain rows or 8 pooled rows; G4 = 16-byte groups per row)
+  constexpr int TR = SRC == 2 ? TH / 2 : TH, G4 = SRC == 2 ? 4 : 8;
+  constexpr int M_PER_C = TR * G4;                      // main slots per channel
+  constexpr int M_CPR = NTHR / M_PER_C;                 // channels per round
+  constexpr int NM = (CC + M_CPR - 1) / M_CPR;          // main rounds
+  constexpr int S_PER_C = TR * 2;                       // side (halo column) slots per channel
+  constexpr int S_CPR = NTHR / S_PER_C;
+  constexpr int NS = (CC + S_CPR - 1) / S_CPR;          // side rounds
+  static_assert(NTHR % M_PER_C == 0 && CC * 2 * G4 <= NTHR && CC * 4 <= NTHR, "slot classes");
+  // main: rows 0..TR-1 of the tile, 16-byte groups
+  const int m_j = tid % G4, m_r = (tid / G4) % TR, m_c = tid / M_PER_C;
+  // top/bottom halo rows, 16-byte groups: one round, threads below CC * 2 * G4
+  const int t_j = tid % G4, t_b = (tid / G4) & 1, t_c = tid / (2 * G4);
+  // side columns of rows 0..TR-1, single elements
+  const int s_side = tid & 1, s_r = (tid >> 1) % TR, s_c = tid / S_PER_C;
+  // corners, single elements: threads below CC * 4
+  const int c_side = tid & 1, c_b = (tid >> 1) & 1, c_c = tid >> 2;
+  // element offsets relative to (channel c0, row sy0, column sx0) of the tile, sy0/sx0 = tile origin in the source plane
+  const int m_off = m_c * (int)plane + m_r * SW + 4 * m_j;
+  const int t_off = t_c * (int)plane + (t_b ? TR : -1) * SW + 4 * t_j;
+  const int s_off = s_c * (int)plane + s_r * SW + (s_side ? (SRC == 2 ? 16 : kTileW) : -1);
+  const int c_off = c_c * (int)plane + (c_b ? TR : -1) * SW + (c_side ? (SRC == 2 ? 16 : kTileW) : -1);
+
+  constexpr bool M_EXACT = NM * M_CPR == CC, S_EXACT = NS * S_CPR == CC;
+  float4 vm[NM], ym[NM], vt, yt;
+  float vs[NS], ys[NS], vc, yc;
+  int im[NM], it_;                    // SRC == 2: four index bytes per group
+  unsigned char is_[NS], ic;
+  // registers of the optional operands start defined; they stay so when the loads are skipped
+  yt = make_float4(0.f, 0.f, 0.f, 0.f); yc = 0.0f; it_ = 0; ic = 0;
+#pragma unroll
+  for (int it = 0; it < NM; ++it) { ym[it] = yt; im[it] = 0; }
+#pragma unroll
+  for (int it = 0; it < NS; ++it) { ys[it] = 0.0f; is_[it] = 0; }
 
   // global -> registers for work item q
   auto load_regs = [&](int q) {
@@ -376,147 +425,140 @@ __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void 
     const int ty = (tile / g.tiles_x) % g.tiles_y;
     const int n = tile / (g.tiles_x * g.tiles_y);
     const int oy0 = ty * TH, ox0 = tx * kTileW, c0 = chunk * CC;
-    if (SRC != 2) {
+    const int sy0 = SRC == 2 ? oy0 >> 1 : oy0, sx0 = SRC == 2 ? ox0 >> 1 : ox0;
+    const int cleft = a.Cin - c0;                                        // valid channels from c0 on
+    const unsigned base = ((unsigned)(n * a.Cin + c0) * SH) * SW;      // element offset of (n, c0, 0, 0)
+    const int pos = sy0 * SW + sx0;                                      // tile origin inside the plane
+    // main
+    {
+      const bool ok = sy0 + m_r < SH && sx0 + 4 * m_j < SW;
+      const unsigned e = (unsigned)(pos + m_off);
 #pragma unroll
-      for (int it = 0; it < NI; ++it) {
-        const int e = tid + it * NTHR;
-        const int j = e & 7, line = e >> 3;
-        const int cl = line / ROWS, row = line - cl * ROWS;
-        const int gi = oy0 - 1 + row, gj = ox0 + 4 * j;
-        vi[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-        yi[it] = vi[it];
-        if (line < LINES && c0 + cl < a.Cin && gi >= 0 && gi < a.Hin && gj < a.Win) {
-          const long o = ((long)(n * a.Cin + c0 + cl) * a.Hin + gi) * a.Win + gj;
-          vi[it] = *reinterpret_cast<const float4 *>(a.src + o);
-          if (SRC == 1 && a.src_act != ACT_IDENTITY) yi[it] = *reinterpret_cast<const float4 *>(a.src_y + o);
-        }
+      for (int it = 0; it < NM; ++it) {
+        // 16-channel chunks are always whole (the launcher checks Cin % 16 == 0)
+        const bool okc = (CC == 16 && M_EXACT) ? ok : ok && it * M_CPR + m_c < (cleft < CC ? cleft : CC);
+        const unsigned so = base + (unsigned)it * M_CPR * plane;
+        vm[it] = ld4(rs_src, okc ? 4u * e : kOob, 4u * so);
+        if (need_y) ym[it] = ld4(rs_y, okc ? 4u * e : kOob, 4u * so);
+        if (SRC == 2) im[it] = __builtin_amdgcn_raw_buffer_load_b32(rs_idx, (int)(okc ? e : kOob), (int)so, 0);
       }
+    }
+    // top / bottom halo rows
+    {
+      const int row = sy0 + (t_b ? TR : -1);
+      const bool ok = tid < CC * 2 * G4 && (unsigned)row < (unsigned)SH && sx0 + 4 * t_j < SW && t_c < cleft;
+      const unsigned e = (unsigned)(pos + t_off);
+      vt = ld4(rs_src, ok ? 4u * e : kOob, 4u * base);
+      if (need_y) yt = ld4(rs_y, ok ? 4u * e : kOob, 4u * base);
+      if (SRC == 2) it_ = __builtin_amdgcn_raw_buffer_load_b32(rs_idx, (int)(ok ? e : kOob), (int)base, 0);
+    }
+    // side columns
+    {
+      const int col = sx0 + (s_side ? (SRC == 2 ? 16 : kTileW) : -1);
+      const bool ok = sy0 + s_r < SH && (unsigned)col < (unsigned)SW;
+      const unsigned e = (unsigned)(pos + s_off);
 #pragma unroll
-      for (int it = 0; it < NH; ++it) {
-        const int e = tid + it * NTHR;
-        const int side = e & 1, line = e >> 1;
-        const int cl = line / ROWS, row = line - cl * ROWS;
-        const int gi = oy0 - 1 + row, gj = side ? ox0 + kTileW : ox0 - 1;
-        vh[it] = 0.0f;
-        yh[it] = 0.0f;
-        if (line < LINES && c0 + cl < a.Cin && gi >= 0 && gi < a.Hin && gj >= 0 && gj < a.Win) {
-          const long o = ((long)(n * a.Cin + c0 + cl) * a.Hin + gi) * a.Win + gj;
-          vh[it] = a.src[o];
-          if (SRC == 1 && a.src_act != ACT_IDENTITY) yh[it] = a.src_y[o];
-        }
+      for (int it = 0; it < NS; ++it) {
+        const bool okc = (CC == 16 && S_EXACT) ? ok : ok && it * S_CPR + s_c < (cleft < CC ? cleft : CC);
+        const unsigned so = base + (unsigned)it * S_CPR * plane;
+        vs[it] = ld1(rs_src, okc ? 4u * e : kOob, 4u * so);
+        if (need_y) ys[it] = ld1(rs_y, okc ? 4u * e : kOob, 4u * so);
+        if (SRC == 2) is_[it] = __builtin_amdgcn_raw_buffer_load_b8(rs_idx, (int)(okc ? e : kOob), (int)so, 0);
       }
-    } else {
-#pragma unroll
-      for (int it = 0; it < NI; ++it) {
-        const int e = tid + it * NTHR;
-        const int j = e & 3, line = e >> 2;
-        const int cl = line / PR, pr = line - cl * PR;
-        const int u = (oy0 >> 1) - 1 + pr, v0 = (ox0 >> 1) + 4 * j;
-        vi[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-        yi[it] = vi[it];
-        ii[it] = make_uchar4(255, 255, 255, 255);
-        if (line < LINES && c0 + cl < a.Cin && u >= 0 && u < Hp && v0 < Wp) {
-          const long o = ((long)(n * a.Cin + c0 + cl) * Hp + u) * Wp + v0;
-          vi[it] = *reinterpret_cast<const float4 *>(a.src + o);
-          if (reads_output(a.src_act)) yi[it] = *reinterpret_cast<const float4 *>(a.src_y + o);
-          ii[it] = *reinterpret_cast<const uchar4 *>(a.src_idx + o);
-        }
-      }
-#pragma unroll
-      for (int it = 0; it < NH; ++it) {
-        const int e = tid + it * NTHR;
-        const int side = e & 1, line = e >> 1;
-        const int cl = line / PR, pr = line - cl * PR;
-        const int u = (oy0 >> 1) - 1 + pr, v0 = side ? (ox0 >> 1) + 16 : (ox0 >> 1) - 1;
-        vh[it] = 0.0f; yh[it] = 0.0f; ih[it] = 255;
-        if (line < LINES && c0 + cl < a.Cin && u >= 0 && u < Hp && v0 >= 0 && v0 < Wp) {
-          const long o = ((long)(n * a.Cin + c0 + cl) * Hp + u) * Wp + v0;
-          vh[it] = a.src[o];
-          if (reads_output(a.src_act)) yh[it] = a.src_y[o];
-          ih[it] = a.src_idx[o];
-        }
-      }
+    }
+    // corners
+    {
+      const int row = sy0 + (c_b ? TR : -1), col = sx0 + (c_side ? (SRC == 2 ? 16 : kTileW) : -1);
+      const bool ok = tid < CC * 4 && (unsigned)row < (unsigned)SH && (unsigned)col < (unsigned)SW && c_c < cleft;
+      const unsigned e = (unsigned)(pos + c_off);
+      vc = ld1(rs_src, ok ? 4u * e : kOob, 4u * base);
+      if (need_y) yc = ld1(rs_y, ok ? 4u * e : kOob, 4u * base);
+      if (SRC == 2) ic = __builtin_amdgcn_raw_buffer_load_b8(rs_idx, (int)(ok ? e : kOob), (int)base, 0);
     }
   };
 
-  // registers -> LDS halo tile [16][ROWS][34]: tile column t lives at LDS column t + 1
+  // registers -> LDS.  Plain sources: one 16-byte group is two 8-byte stores.  Pooled sources: a
+  // pooled element (row pr, column pc) expands to LDS rows 2pr+1, 2pr+2 and columns 2pc+2, 2pc+3
+  // (pr, pc relative to the tile; the halo row/column keep only the half that lies inside).
+  float *const m_dst = SRC == 2 ? xs + m_c * PS + (2 * m_r + 1) * RS + 2 + 8 * m_j : xs + m_c * PS + (m_r + 1) * RS + 2 + 4 * m_j;
+  float *const t_dst = SRC == 2 ? xs + t_c * PS + (t_b ? 17 : 0) * RS + 2 + 8 * t_j : xs + t_c * PS + (t_b ? 17 : 0) * RS + 2 + 4 * t_j;
+  float *const s_dst = SRC == 2 ? xs + s_c * PS + (2 * s_r + 1) * RS + (s_side ? kTileW + 2 : 0) : xs + s_c * PS + (s_r + 1) * RS + (s_side ? kTileW + 2 : 1);
+  float *const c_dst = SRC == 2 ? xs + c_c * PS + (c_b ? 17 : 0) * RS + (c_side ? kTileW + 2 : 0) : xs + c_c * PS + (c_b ? 17 : 0) * RS + (c_side ? kTileW + 2 : 1);
+  auto put4 = [&](float *d, float4 v) __attribute__((always_inline)) {
+    reinterpret_cast<float2 *>(d)[0] = make_float2(v.x, v.y);
+    reinterpret_cast<float2 *>(d)[1] = make_float2(v.z, v.w);
+  };
+  // one window row (wa2 = 0 top, 1 bottom) of four pooled elements -> 8 floats
+  auto put_pooled4 = [&](float *d, const float (&gg)[4], const unsigned char (&pos)[4], int wa2) __attribute__((always_inline)) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      *reinterpret_cast<float2 *>(d + 2 * q) = make_float2(pos[q] == 2 * wa2 ? gg[q] : 0.0f, pos[q] == 2 * wa2 + 1 ? gg[q] : 0.0f);
+  };
+  auto pooled_group = [&](float4 v, float4 y, int idx4, float (&gg)[4], unsigned char (&pos)[4]) __attribute__((always_inline)) {
+    const float gv[4] = {v.x, v.y, v.z, v.w}, ov[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const unsigned char f = (unsigned char)((unsigned)idx4 >> (8 * q));
+      gg[q] = pooled_dz(a.src_act, gv[q], ov[q], f);
+      pos[q] = f & kIdxPosMask;   // slots outside the image hold dy = 0
+    }
+  };
   auto store_regs = [&]() {
     if (SRC != 2) {
 #pragma unroll
-      for (int it = 0; it < NI; ++it) {
-        const int e = tid + it * NTHR;
-        const int j = e & 7, line = e >> 3;
-        if (line < LINES) {
-          const int cl = line / ROWS, row = line - cl * ROWS;
-          float4 v = vi[it];
-          if (SRC == 1 && a.src_act != ACT_IDENTITY) {
-            v.x *= act_deriv(a.src_act, yi[it].x); v.y *= act_deriv(a.src_act, yi[it].y);
-            v.z *= act_deriv(a.src_act, yi[it].z); v.w *= act_deriv(a.src_act, yi[it].w);
-          }
-          float2 *d = reinterpret_cast<float2 *>(xs + cl * PS + row * RS + 2 + 4 * j);
-          d[0] = make_float2(v.x, v.y);
-          d[1] = make_float2(v.z, v.w);
+      for (int it = 0; it < NM; ++it) {
+        if (!M_EXACT && it * M_CPR + m_c >= CC) continue;   // slot beyond the chunk's channels
+        float4 v = vm[it];
+        if (need_y) {
+          v.x *= act_deriv(a.src_act, ym[it].x); v.y *= act_deriv(a.src_act, ym[it].y);
+          v.z *= act_deriv(a.src_act, ym[it].z); v.w *= act_deriv(a.src_act, ym[it].w);
         }
+        put4(m_dst + it * M_CPR * PS, v);
+      }
+      if (tid < CC * 2 * G4) {
+        float4 v = vt;
+        if (need_y) {
+          v.x *= act_deriv(a.src_act, yt.x); v.y *= act_deriv(a.src_act, yt.y);
+          v.z *= act_deriv(a.src_act, yt.z); v.w *= act_deriv(a.src_act, yt.w);
+        }
+        put4(t_dst, v);
       }
 #pragma unroll
-      for (int it = 0; it < NH; ++it) {
-        const int e = tid + it * NTHR;
-        const int side = e & 1, line = e >> 1;
-        if (line < LINES) {
-          const int cl = line / ROWS, row = line - cl * ROWS;
-          float v = vh[it];
-          if (SRC == 1 && a.src_act != ACT_IDENTITY) v *= act_deriv(a.src_act, yh[it]);
-          xs[cl * PS + row * RS + (side ? kTileW + 2 : 1)] = v;
-        }
+      for (int it = 0; it < NS; ++it) {
+        if (!S_EXACT && it * S_CPR + s_c >= CC) continue;
+        s_dst[it * S_CPR * PS] = need_y ? vs[it] * act_deriv(a.src_act, ys[it]) : vs[it];
       }
+      if (tid < CC * 4) *c_dst = need_y ? vc * act_deriv(a.src_act, yc) : vc;
     } else {
-      // expand: pooled (pr, pc) -> tile rows 2pr-1, 2pr; LDS columns 2*(pc local) + {0,1} (+2 for the interior)
+      float gg[4];
+      unsigned char pos[4];
 #pragma unroll
-      for (int it = 0; it < NI; ++it) {
-        const int e = tid + it * NTHR;
-        const int j = e & 3, line = e >> 2;
-        if (line < LINES) {
-          const int cl = line / PR, pr = line - cl * PR;
-          const float gv[4] = {vi[it].x, vi[it].y, vi[it].z, vi[it].w};
-          const float ov[4] = {yi[it].x, yi[it].y, yi[it].z, yi[it].w};
-          const unsigned char fl[4] = {ii[it].x, ii[it].y, ii[it].z, ii[it].w};
-          unsigned char pos[4];
-          float gg[4];
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            gg[q] = pooled_dz(a.src_act, gv[q], ov[q], fl[q]);
-            pos[q] = fl[q] & kIdxPosMask;   // slots outside the image hold dy = 0
-          }
-#pragma unroll
-          for (int wa2 = 0; wa2 < 2; ++wa2) {
-            const int row = 2 * pr - 1 + wa2;
-            if (row >= 0 && row < ROWS) {
-              float *d = xs + cl * PS + row * RS + 2 + 8 * j;
-#pragma unroll
-              for (int q = 0; q < 4; ++q)
-                *reinterpret_cast<float2 *>(d + 2 * q) =
-                    make_float2(pos[q] == 2 * wa2 ? gg[q] : 0.0f, pos[q] == 2 * wa2 + 1 ? gg[q] : 0.0f);
-            }
-          }
-        }
+      for (int it = 0; it < NM; ++it) {
+        if (!M_EXACT && it * M_CPR + m_c >= CC) continue;
+        pooled_group(vm[it], ym[it], im[it], gg, pos);
+        put_pooled4(m_dst + it * M_CPR * PS, gg, pos, 0);
+        put_pooled4(m_dst + it * M_CPR * PS + RS, gg, pos, 1);
+      }
+      if (tid < CC * 2 * G4) {
+        // pooled row above the tile: only its bottom window row (LDS row 0); below: only its top one (row 17)
+        pooled_group(vt, yt, it_, gg, pos);
+        put_pooled4(t_dst, gg, pos, t_b ? 0 : 1);
       }
 #pragma unroll
-      for (int it = 0; it < NH; ++it) {
-        const int e = tid + it * NTHR;
-        const int side = e & 1, line = e >> 1;
-        if (line < LINES) {
-          const int cl = line / PR, pr = line - cl * PR;
-          const float gg = pooled_dz(a.src_act, vh[it], yh[it], ih[it]);
-          const unsigned char hp = ih[it] & kIdxPosMask;
-#pragma unroll
-          for (int wa2 = 0; wa2 < 2; ++wa2) {
-            const int row = 2 * pr - 1 + wa2;
-            // left neighbour window: LDS columns 0 (unused slot) and 1; right one: 34 and 35 (unused slot)
-            if (row >= 0 && row < ROWS)
-              *reinterpret_cast<float2 *>(xs + cl * PS + row * RS + (side ? kTileW + 2 : 0)) =
-                  make_float2(hp == 2 * wa2 ? gg : 0.0f, hp == 2 * wa2 + 1 ? gg : 0.0f);
-          }
-        }
+      for (int it = 0; it < NS; ++it) {
+        if (!S_EXACT && it * S_CPR + s_c >= CC) continue;
+        // left neighbour window: LDS columns 0 (unused slot) and 1; right one: 34 and 35 (unused slot)
+        const float g1 = pooled_dz(a.src_act, vs[it], ys[it], is_[it]);
+        const unsigned char hp = is_[it] & kIdxPosMask;
+        float *d = s_dst + it * S_CPR * PS;
+        *reinterpret_cast<float2 *>(d) = make_float2(hp == 0 ? g1 : 0.0f, hp == 1 ? g1 : 0.0f);
+        *reinterpret_cast<float2 *>(d + RS) = make_float2(hp == 2 ? g1 : 0.0f, hp == 3 ? g1 : 0.0f);
+      }
+      if (tid < CC * 4) {
+        const float g1 = pooled_dz(a.src_act, vc, yc, ic);
+        const unsigned char hp = ic & kIdxPosMask;
+        const int wa2 = c_b ? 0 : 1;
+        *reinterpret_cast<float2 *>(c_dst) = make_float2(hp == 2 * wa2 ? g1 : 0.0f, hp == 2 * wa2 + 1 ? g1 : 0.0f);
       }
     }
   };
@@ -653,6 +695,8 @@ bool conv3x3c16_applies(const ConvEngineArgs &a) {
   if (a.Cin % 16 != 0 && a.Cin > 12) return false;   // 16-channel chunks, or up to three 4-channel chunks
   if (a.Hout != a.Hin || a.Wout != a.Win) return false;
   if (!aligned16(a.src)) return false;
+  // the kernel addresses the source through 32-bit byte offsets that must stay below 2 GiB
+  if ((long)a.N * a.Cin * a.Hin * a.Win * 4 >= (1L << 31)) return false;
   if (a.src_dz) {
     if (reads_output(a.src_act) && !aligned16(a.src_y)) return false;
     if (a.src_pool == 2) return (a.Win % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.src_idx) & 3u) == 0);
@@ -671,6 +715,10 @@ hipError_t launch_3x3(const ConvEngineArgs &a, hipStream_t stream) {
   p.g.tiles_x = (a.Wout + kTileW - 1) / kTileW;
   p.g.tiles_y = (a.Hout + TH - 1) / TH;
   p.g.kgroups = (a.Kout + NT * 16 - 1) / (NT * 16);
+  {
+    const long src_elems = (a.src_dz && a.src_pool == 2) ? (long)a.N * a.Cin * (a.Hin / 2) * (a.Win / 2) : (long)a.N * a.Cin * a.Hin * a.Win;
+    p.g.src_bytes = (unsigned)(src_elems * 4);
+  }
   const long tiles = (long)a.N * p.g.tiles_x * p.g.tiles_y;
   if (tiles <= 0 || tiles * p.g.nchunks > 0x7fffffffL) return hipErrorInvalidValue;
   const size_t lds = conv3x3c16_lds<NT, CC>(p.g.nchunks);
