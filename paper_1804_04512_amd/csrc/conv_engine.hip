@@ -87,8 +87,8 @@ __device__ __forceinline__ float dz_value(const ConvEngineArgs &a, int n, int k,
 
 // Epilogue shared by the engine kernels.  Lane owns output channel ko0+16nt+i16, window column
 // 4*kq+mt of the tile, window row wave*RP+rp; acc[..][v] is window position v = 2a+b.
-template <int NT, int RP>
-__device__ __forceinline__ void engine_epilogue(const ConvEngineArgs &a, floatx4 (&acc)[RP][4][NT], int n, int ko0,
+template <int NT, int RP, int ACT, int POOL>
+__device__ __forceinline__ void engine_epilogue_as(const ConvEngineArgs &a, floatx4 (&acc)[RP][4][NT], int n, int ko0,
                                                 int oy0, int ox0, int wave, int i16, int kq) {
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
@@ -100,7 +100,7 @@ __device__ __forceinline__ void engine_epilogue(const ConvEngineArgs &a, floatx4
       const int py = (oy0 >> 1) + wave * RP + rp;   // window row (pre-pool rows 2py, 2py+1)
       const int px0 = (ox0 >> 1) + 4 * kq;          // first of the lane's 4 window columns
       if (2 * py >= a.Hout) continue;
-      if (a.pool == 2) {
+      if (POOL == 2) {
         const int Hp = a.Hout >> 1, Wp = a.Wout >> 1;
         float yv[4];
         unsigned char iv[4];
@@ -112,8 +112,8 @@ __device__ __forceinline__ void engine_epilogue(const ConvEngineArgs &a, floatx4
           if (z[1] > m) { m = z[1]; arg = 1; }
           if (z[2] > m) { m = z[2]; arg = 2; }
           if (z[3] > m) { m = z[3]; arg = 3; }
-          yv[mt] = act_apply(a.act, m + bv);   // bias and a monotone activation commute with max
-          iv[mt] = (unsigned char)(arg | ((a.act == ACT_RELU && !(yv[mt] > 0.0f)) ? kIdxInactive : 0));
+          yv[mt] = act_apply(ACT, m + bv);   // bias and a monotone activation commute with max
+          iv[mt] = (unsigned char)(arg | ((ACT == ACT_RELU && !(yv[mt] > 0.0f)) ? kIdxInactive : 0));
         }
         const int o = ((n * a.Kout + ko) * Hp + py) * Wp + px0;
         if (px0 + 3 < Wp && (Wp & 3) == 0) {
@@ -134,8 +134,8 @@ __device__ __forceinline__ void engine_epilogue(const ConvEngineArgs &a, floatx4
           float yv[8];
 #pragma unroll
           for (int mt = 0; mt < 4; ++mt) {
-            yv[2 * mt] = act_apply(a.act, acc[rp][mt][nt][2 * wa2] + bv);
-            yv[2 * mt + 1] = act_apply(a.act, acc[rp][mt][nt][2 * wa2 + 1] + bv);
+            yv[2 * mt] = act_apply(ACT, acc[rp][mt][nt][2 * wa2] + bv);
+            yv[2 * mt + 1] = act_apply(ACT, acc[rp][mt][nt][2 * wa2 + 1] + bv);
           }
           if (ox + 7 < a.Wout && (a.Wout & 3) == 0) {
             *reinterpret_cast<float4 *>(a.out + o) = make_float4(yv[0], yv[1], yv[2], yv[3]);
@@ -160,6 +160,24 @@ __device__ __forceinline__ void engine_epilogue(const ConvEngineArgs &a, floatx4
       }
     }
   }
+}
+
+// The activation and the pooling mode are fixed for a launch: dispatch once, so that the
+// per-element code carries no branches on them.
+template <int NT, int RP>
+__device__ __forceinline__ void engine_epilogue(const ConvEngineArgs &a, floatx4 (&acc)[RP][4][NT], int n, int ko0,
+                                                int oy0, int ox0, int wave, int i16, int kq) {
+#define DLL_EPI(ACT_, POOL_) engine_epilogue_as<NT, RP, ACT_, POOL_>(a, acc, n, ko0, oy0, ox0, wave, i16, kq)
+  if (a.pool == 2) {
+    if (a.act == ACT_RELU) DLL_EPI(ACT_RELU, 2);
+    else if (a.act == ACT_SIGMOID) DLL_EPI(ACT_SIGMOID, 2);
+    else DLL_EPI(ACT_IDENTITY, 2);
+  } else {
+    if (a.act == ACT_RELU) DLL_EPI(ACT_RELU, 1);
+    else if (a.act == ACT_SIGMOID) DLL_EPI(ACT_SIGMOID, 1);
+    else DLL_EPI(ACT_IDENTITY, 1);
+  }
+#undef DLL_EPI
 }
 
 template <int NT, int RP>
@@ -494,73 +512,83 @@ __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void 
     for (int q = 0; q < 4; ++q)
       *reinterpret_cast<float2 *>(d + 2 * q) = make_float2(pos[q] == 2 * wa2 ? gg[q] : 0.0f, pos[q] == 2 * wa2 + 1 ? gg[q] : 0.0f);
   };
-  auto pooled_group = [&](float4 v, float4 y, int idx4, float (&gg)[4], unsigned char (&pos)[4]) __attribute__((always_inline)) {
+  auto pooled_group = [&](auto actc, float4 v, float4 y, int idx4, float (&gg)[4], unsigned char (&pos)[4]) __attribute__((always_inline)) {
+    constexpr int SA = decltype(actc)::value;
     const float gv[4] = {v.x, v.y, v.z, v.w}, ov[4] = {y.x, y.y, y.z, y.w};
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const unsigned char f = (unsigned char)((unsigned)idx4 >> (8 * q));
-      gg[q] = pooled_dz(a.src_act, gv[q], ov[q], f);
+      gg[q] = pooled_dz(SA, gv[q], ov[q], f);
       pos[q] = f & kIdxPosMask;   // slots outside the image hold dy = 0
     }
   };
-  auto store_regs = [&]() {
+  auto store_regs_as = [&](auto actc) __attribute__((always_inline)) {
+    constexpr int SA = decltype(actc)::value;
+    constexpr bool need_y = SRC == 2 ? (SA == ACT_SIGMOID || SA == ACT_RELU) : (SRC == 1 && SA != ACT_IDENTITY);
     if (SRC != 2) {
 #pragma unroll
       for (int it = 0; it < NM; ++it) {
         if (!M_EXACT && it * M_CPR + m_c >= CC) continue;   // slot beyond the chunk's channels
         float4 v = vm[it];
         if (need_y) {
-          v.x *= act_deriv(a.src_act, ym[it].x); v.y *= act_deriv(a.src_act, ym[it].y);
-          v.z *= act_deriv(a.src_act, ym[it].z); v.w *= act_deriv(a.src_act, ym[it].w);
+          v.x *= act_deriv(SA, ym[it].x); v.y *= act_deriv(SA, ym[it].y);
+          v.z *= act_deriv(SA, ym[it].z); v.w *= act_deriv(SA, ym[it].w);
         }
         put4(m_dst + it * M_CPR * PS, v);
       }
       if (tid < CC * 2 * G4) {
         float4 v = vt;
         if (need_y) {
-          v.x *= act_deriv(a.src_act, yt.x); v.y *= act_deriv(a.src_act, yt.y);
-          v.z *= act_deriv(a.src_act, yt.z); v.w *= act_deriv(a.src_act, yt.w);
+          v.x *= act_deriv(SA, yt.x); v.y *= act_deriv(SA, yt.y);
+          v.z *= act_deriv(SA, yt.z); v.w *= act_deriv(SA, yt.w);
         }
         put4(t_dst, v);
       }
 #pragma unroll
       for (int it = 0; it < NS; ++it) {
         if (!S_EXACT && it * S_CPR + s_c >= CC) continue;
-        s_dst[it * S_CPR * PS] = need_y ? vs[it] * act_deriv(a.src_act, ys[it]) : vs[it];
+        s_dst[it * S_CPR * PS] = need_y ? vs[it] * act_deriv(SA, ys[it]) : vs[it];
       }
-      if (tid < CC * 4) *c_dst = need_y ? vc * act_deriv(a.src_act, yc) : vc;
+      if (tid < CC * 4) *c_dst = need_y ? vc * act_deriv(SA, yc) : vc;
     } else {
       float gg[4];
       unsigned char pos[4];
 #pragma unroll
       for (int it = 0; it < NM; ++it) {
         if (!M_EXACT && it * M_CPR + m_c >= CC) continue;
-        pooled_group(vm[it], ym[it], im[it], gg, pos);
+        pooled_group(actc, vm[it], ym[it], im[it], gg, pos);
         put_pooled4(m_dst + it * M_CPR * PS, gg, pos, 0);
         put_pooled4(m_dst + it * M_CPR * PS + RS, gg, pos, 1);
       }
       if (tid < CC * 2 * G4) {
         // pooled row above the tile: only its bottom window row (LDS row 0); below: only its top one (row 17)
-        pooled_group(vt, yt, it_, gg, pos);
+        pooled_group(actc, vt, yt, it_, gg, pos);
         put_pooled4(t_dst, gg, pos, t_b ? 0 : 1);
       }
 #pragma unroll
       for (int it = 0; it < NS; ++it) {
         if (!S_EXACT && it * S_CPR + s_c >= CC) continue;
         // left neighbour window: LDS columns 0 (unused slot) and 1; right one: 34 and 35 (unused slot)
-        const float g1 = pooled_dz(a.src_act, vs[it], ys[it], is_[it]);
+        const float g1 = pooled_dz(SA, vs[it], ys[it], is_[it]);
         const unsigned char hp = is_[it] & kIdxPosMask;
         float *d = s_dst + it * S_CPR * PS;
         *reinterpret_cast<float2 *>(d) = make_float2(hp == 0 ? g1 : 0.0f, hp == 1 ? g1 : 0.0f);
         *reinterpret_cast<float2 *>(d + RS) = make_float2(hp == 2 ? g1 : 0.0f, hp == 3 ? g1 : 0.0f);
       }
       if (tid < CC * 4) {
-        const float g1 = pooled_dz(a.src_act, vc, yc, ic);
+        const float g1 = pooled_dz(SA, vc, yc, ic);
         const unsigned char hp = ic & kIdxPosMask;
         const int wa2 = c_b ? 0 : 1;
         *reinterpret_cast<float2 *>(c_dst) = make_float2(hp == 2 * wa2 ? g1 : 0.0f, hp == 2 * wa2 + 1 ? g1 : 0.0f);
       }
     }
+  };
+  // the source activation is fixed for a launch: dispatch once, no per-element branches on it
+  auto store_regs = [&]() __attribute__((always_inline)) {
+    if (SRC == 0 || a.src_act == ACT_IDENTITY) store_regs_as(std::integral_constant<int, ACT_IDENTITY>{});
+    else if (a.src_act == ACT_RELU) store_regs_as(std::integral_constant<int, ACT_RELU>{});
+    else if (a.src_act == ACT_SIGMOID) store_regs_as(std::integral_constant<int, ACT_SIGMOID>{});
+    else store_regs_as(std::integral_constant<int, ACT_RELU_FLAGGED>{});
   };
 
   floatx4 acc[RP][4][NT];
