@@ -37,6 +37,7 @@ struct EngineGeom {
   int tiles_x, tiles_y;
   int kgroups;       // groups of NT*16 output channels (gridDim.y)
   unsigned src_bytes; // 3x3 instance: bytes of the source tensor (below 2 GiB)
+  int pack3;          // 3x3 instance, three input channels: the 27 taps run as 7 MFMA steps, not 9
 };
 
 struct EngineParams {
@@ -344,8 +345,9 @@ constexpr int conv3x3_occupancy(int NT, int WAVES, int CC) { return (CC == 4 ? 4
 
 // SRC: 0 plain tensor, 1 dz without pooling, 2 dz through 2x2 pooling.  CC: channels per chunk,
 // 16, or 4 for shallow inputs such as RGB images (surplus channels are staged as zeros).
-template <int NT, int WAVES, int SRC, int CC>
+template <int NT, int WAVES, int SRC, int CC, bool PACK3 = false>
 __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void conv3x3c16_kernel(const EngineParams p) {
+  static_assert(!PACK3 || (CC == 4 && SRC == 0), "the packed three-channel path is a forward path of the 4-channel instance");
   constexpr int NTHR = WAVES * 64, RP = 8 / WAVES;   // 16-row tile: every wave owns RP row pairs
   constexpr int TH = 16, ROWS = TH + 2, C4 = CC / 4;
   constexpr int RS = 36, PS = round_up_mod_c(RS * ROWS, 8, 2);
@@ -363,7 +365,16 @@ __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void 
   const int work = tiles * g.nchunks;          // (tile, chunk) pairs, chunk fastest
   const int Hp = a.Hin >> 1, Wp = a.Win >> 1;  // SRC == 2 only
 
-  // ---- filter slices of every chunk, once per workgroup: wl[chunk][nt][rs*CC + cl][j]
+  // ---- filter slices of every chunk, once per workgroup: wl[chunk][nt][rs*CC + cl][j];
+  // three-channel inputs: wl[nt][k][j] with k = (c*3 + r)*3 + s, the filter's own order, and a zero row 27
+  if (PACK3) {
+    for (int e = tid; e < NT * 28 * 16; e += NTHR) {
+      const int j = e & 15, q = e >> 4;
+      const int k = q % 28, nt = q / 28;
+      const int ko = ko0 + nt * 16 + j;
+      wl[e] = (k < 27 && ko < a.Kout) ? a.w[ko * 27 + k] : 0.0f;
+    }
+  } else
   for (int e = tid; e < g.nchunks * NT * KC * 16; e += NTHR) {
     const int j = e & 15, q = e >> 4;
     const int kk = q % KC, q2 = q / KC;
@@ -595,6 +606,12 @@ __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void 
   const int gq = i16 >> 2, wa = (i16 >> 1) & 1, wb = i16 & 1;
   const float *a_ptr = xs + kq * PS + (wave * 2 * RP + wa) * RS + 8 * gq + wb + 1;
   const float *b_ptr = wl + kq * 16 + i16;
+  const float *a3[7];   // three-channel inputs: lane's tile pointer of MFMA step t (k = 4t + kq)
+#pragma unroll
+  for (int t = 0; t < (PACK3 ? 7 : 0); ++t) {
+    const int k = 4 * t + kq, c = k / 9, tap = k - 9 * c;
+    a3[t] = a_ptr - kq * PS + (k < 27 ? c * PS + (tap / 3) * RS + tap % 3 : 0);
+  }
 
   // persistent loop over (tile, chunk) pairs; the next pair's global loads fly during the MFMA loop
   // Tile order is XCD-aware: workgroup ids are dealt round-robin to the 8 XCDs, each with its
@@ -657,7 +674,7 @@ __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void 
     };
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
-    load_frags(I0{}, a_tap, b_tap, 0);
+    if (!PACK3) load_frags(I0{}, a_tap, b_tap, 0);
     if constexpr (C4 == 4) {
 #pragma unroll 1
       for (int rs = 0; rs < 9; ++rs) {
@@ -682,6 +699,30 @@ __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void 
         a_tap = a_next;
         b_tap = b_next;
       }
+    } else if constexpr (PACK3) {
+      // three input channels: k = 4t + kq runs over (channel, tap) in the filter's order; the lane's
+      // seven tile offsets were worked out once (a3), the filter rows are 64 floats apart
+      auto load3 = [&](auto bufc, auto tc) {
+        constexpr int B_ = decltype(bufc)::value, t = decltype(tc)::value;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) bf[B_][nt] = b_ptr[(nt * 28 + 4 * t) * 16];
+#pragma unroll
+        for (int rp = 0; rp < RP; ++rp)
+#pragma unroll
+          for (int mt = 0; mt < 4; ++mt) af[B_][rp * 4 + mt] = a3[t][rp * 2 * RS + 2 * mt];
+      };
+      auto step3 = [&](auto tc) {
+        constexpr int t = decltype(tc)::value;
+        if constexpr (t < 6) load3(std::integral_constant<int, (t + 1) & 1>{}, std::integral_constant<int, t + 1>{});
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_frags(std::integral_constant<int, t & 1>{});
+        __builtin_amdgcn_sched_barrier(0);
+      };
+      load3(I0{}, I0{});
+      step3(std::integral_constant<int, 0>{}); step3(std::integral_constant<int, 1>{});
+      step3(std::integral_constant<int, 2>{}); step3(std::integral_constant<int, 3>{});
+      step3(std::integral_constant<int, 4>{}); step3(std::integral_constant<int, 5>{});
+      step3(std::integral_constant<int, 6>{});
     } else {
       // one step per tap: nine steps, fully unrolled, tap offsets are immediates
       auto tap_step = [&](auto rsc) {
@@ -743,6 +784,7 @@ hipError_t launch_3x3(const ConvEngineArgs &a, hipStream_t stream) {
   p.g.tiles_x = (a.Wout + kTileW - 1) / kTileW;
   p.g.tiles_y = (a.Hout + TH - 1) / TH;
   p.g.kgroups = (a.Kout + NT * 16 - 1) / (NT * 16);
+  p.g.pack3 = (CC == 4 && a.Cin == 3 && !a.src_dz && !a.w_flip) ? 1 : 0;
   {
     const long src_elems = (a.src_dz && a.src_pool == 2) ? (long)a.N * a.Cin * (a.Hin / 2) * (a.Win / 2) : (long)a.N * a.Cin * a.Hin * a.Win;
     p.g.src_bytes = (unsigned)(src_elems * 4);
@@ -771,7 +813,12 @@ hipError_t launch_3x3(const ConvEngineArgs &a, hipStream_t stream) {
     hipLaunchKernelGGL(kern, grid, dim3(WAVES * 64), lds, stream, p);
     return hipGetLastError();
   };
-  if (!a.src_dz) return launch(conv3x3c16_kernel<NT, WAVES, 0, CC>);
+  if (!a.src_dz) {
+    if constexpr (CC == 4) {
+      if (p.g.pack3) return launch(conv3x3c16_kernel<NT, WAVES, 0, CC, true>);
+    }
+    return launch(conv3x3c16_kernel<NT, WAVES, 0, CC>);
+  }
   if (a.src_pool == 2) return launch(conv3x3c16_kernel<NT, WAVES, 2, CC>);
   return launch(conv3x3c16_kernel<NT, WAVES, 1, CC>);
 }
