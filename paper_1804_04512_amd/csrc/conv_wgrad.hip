@@ -50,6 +50,8 @@ struct WgradParams {
   int kgroups;
   long db_offset;
   long group_stride;       // floats between filter groups in the dw partial area
+  int nxi, nxh;            // fast path: staging rounds the tile really needs (<= NXI, NXH)
+  unsigned x_bytes, dy_bytes;   // fast path: tensor sizes (below 2 GiB) for the range-checked loads
 };
 
 __device__ __forceinline__ float act_deriv(int act, float out) {
@@ -139,6 +141,16 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
   int dzo[DZR], dzl[DZR];            // dz slots: global offset from the tile's first pooled element, LDS offset
   bool dzk[DZR];
   int du = 0, dv = 0;
+  // The fast path reads through range-checked buffer loads: a slot that does not exist (beyond
+  // the tile, the last channel or the filter group) keeps an offset past the end of the tensor
+  // and reads zeros, as do rows and columns outside the image on the edge tiles.  Interior tiles
+  // need no per-slot arithmetic at all: fixed per-thread offset + the tile's scalar offset.
+  constexpr unsigned kOob = 0x80000000u;
+  const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.x), 0, (int)p.x_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_dy = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.dy), 0, (int)p.dy_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.y ? a.y : a.dy), 0, (int)p.dy_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_idx = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<unsigned char *>(a.idx ? a.idx : reinterpret_cast<const unsigned char *>(a.dy)), 0, (int)(p.dy_bytes >> 2), 0x00020000);
   if (FAST) {
 #pragma unroll
     for (int it = 0; it < NXI; ++it) {
@@ -146,7 +158,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
       const int line = e >> 3;
       const int cl = (line * p.inv_rows) >> 16, row = line - cl * p.rows;
       const bool ok = line < lines && c0 + cl < a.C;
-      xo[it] = (cl * a.H + row) * a.W + j4;
+      xo[it] = ok ? 4 * ((cl * a.H + row) * a.W + j4 + a.pad) : (int)kOob;   // bytes from the halo tile's first element
       xl[it] = cl * p.PS + row * p.RS + a.pad + p.shift + j4;
       xrow[it] = ok ? row : kUnused;
       if (line >= lines) xl[it] = -1;   // slot beyond the tile: nothing to store
@@ -159,7 +171,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
       const int cl = (line * p.inv_rows) >> 16, row = line - cl * p.rows;
       const bool ok = line < lines && c0 + cl < a.C;
       hcol[it] = hc < a.pad ? hc - a.pad : kTileW + hc - a.pad;   // column relative to the tile's first output column
-      ho[it] = (cl * a.H + row) * a.W + hcol[it];
+      ho[it] = ok ? 4 * ((cl * a.H + row) * a.W + hcol[it] + a.pad) : (int)kOob;   // never negative: the range check reads it as unsigned
       hl[it] = line < lines ? cl * p.PS + row * p.RS + (hc < a.pad ? hc : kTileW + hc) + p.shift : -1;
       hrow[it] = ok ? row : kUnused;
     }
@@ -171,7 +183,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
       for (int rd = 0; rd < DZR; ++rd) {
         const int k = rd * 16 + (tid >> 4);
         dzk[rd] = k < kcount;
-        dzo[rd] = ((k0 + k) * (p.Ho >> 1) + du) * (p.Wo >> 1) + dv;
+        dzo[rd] = dzk[rd] ? ((k0 + k) * (p.Ho >> 1) + du) * (p.Wo >> 1) + dv : (int)(kOob >> 2);   // element offset
         dzl[rd] = k * PSZ + dz_row<POOL>(2 * du) + 2 * dv;
       }
     } else {
@@ -182,52 +194,66 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
       for (int rd = 0; rd < DZR; ++rd) {
         const int k = rd * 4 + (tid >> 6);
         dzk[rd] = k < kcount;
-        dzo[rd] = ((k0 + k) * p.Ho + du) * p.Wo + dv;
+        dzo[rd] = dzk[rd] ? ((k0 + k) * p.Ho + du) * p.Wo + dv : (int)(kOob >> 2);
         dzl[rd] = k * PSZ + dz_row<POOL>(du) + dv;
       }
     }
   }
 
   // ---- fast path, step 1: global -> registers for one tile
+  auto ldx4 = [&](const __amdgpu_buffer_rsrc_t &r, int voff, unsigned soff) __attribute__((always_inline)) {
+    const floatx4 v = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(r, voff, (int)soff, 0));
+    return make_float4(v[0], v[1], v[2], v[3]);
+  };
   auto load_tile = [&](int item) {
     const int tx = item % p.tiles_x;
     const int ty = (item / p.tiles_x) % p.tiles_y;
     const int n = item / (p.tiles_x * p.tiles_y);
     const int oy0 = ty * TH, ox0 = tx * kTileW;
-    const float *xp = a.x + (((long)n * a.C + c0) * a.H + (oy0 - a.pad)) * a.W + ox0;
-    const bool col_ok = ox0 + j4 < a.W;
+    const int gy0 = oy0 - a.pad;                                            // image row of the halo tile's first row
+    const unsigned xbase = 4u * ((unsigned)(n * a.C + c0) * a.H * a.W);     // bytes to (n, c0, 0, 0)
+    const int torg = 4 * (gy0 * a.W + ox0 - a.pad);                         // bytes to the halo tile's first element inside a plane (negative on the top/left edge)
+    // interior tile: every row and column of the halo tile lies inside the image
+    const bool inner = gy0 >= 0 && gy0 + p.rows <= a.H && ox0 - a.pad >= 0 && ox0 - a.pad + p.cols <= a.W;
+    if (inner) {
+      const unsigned so = xbase + (unsigned)torg;
 #pragma unroll
-    for (int it = 0; it < NXI; ++it) {
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if ((unsigned)(oy0 - a.pad + xrow[it]) < (unsigned)a.H && col_ok) v = *reinterpret_cast<const float4 *>(xp + xo[it]);
-      tr.xi[it] = v;
-    }
+      for (int it = 0; it < NXI; ++it)
+        if (it < p.nxi) tr.xi[it] = ldx4(rs_x, xo[it], so);
 #pragma unroll
-    for (int it = 0; it < NXH; ++it) {
-      float v = 0.0f;
-      if ((unsigned)(oy0 - a.pad + hrow[it]) < (unsigned)a.H && (unsigned)(ox0 + hcol[it]) < (unsigned)a.W) v = xp[ho[it]];
-      tr.xh[it] = v;
+      for (int it = 0; it < NXH; ++it)
+        if (it < p.nxh) tr.xh[it] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_x, ho[it], (int)so, 0));
+    } else {
+      const bool col_ok = ox0 + j4 < a.W;
+#pragma unroll
+      for (int it = 0; it < NXI; ++it) {
+        if (it >= p.nxi) continue;
+        const bool ok = (unsigned)(gy0 + xrow[it]) < (unsigned)a.H && col_ok;
+        tr.xi[it] = ldx4(rs_x, ok ? xo[it] + torg : (int)kOob, xbase);
+      }
+#pragma unroll
+      for (int it = 0; it < NXH; ++it) {
+        if (it >= p.nxh) continue;
+        const bool ok = (unsigned)(gy0 + hrow[it]) < (unsigned)a.H && (unsigned)(ox0 + hcol[it]) < (unsigned)a.W;
+        tr.xh[it] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_x, ok ? ho[it] + torg : (int)kOob, (int)xbase, 0));
+      }
     }
-    long dbase;
+    unsigned dbase;   // element offset of the tile's first (pooled) output element of filter 0
     bool in;
     if (POOL == 2) {
       const int Hp = p.Ho >> 1, Wp = p.Wo >> 1;
-      dbase = ((long)n * a.K * Hp + (oy0 >> 1)) * Wp + (ox0 >> 1);
+      dbase = ((unsigned)n * a.K * Hp + (oy0 >> 1)) * Wp + (ox0 >> 1);
       in = (oy0 >> 1) + du < Hp && (ox0 >> 1) + dv < Wp;
     } else {
-      dbase = ((long)n * a.K * p.Ho + oy0) * p.Wo + ox0;
+      dbase = ((unsigned)n * a.K * p.Ho + oy0) * p.Wo + ox0;
       in = oy0 + du < p.Ho && ox0 + dv < p.Wo;
     }
 #pragma unroll
     for (int rd = 0; rd < DZR; ++rd) {
-      float4 dv4 = make_float4(0.f, 0.f, 0.f, 0.f), yv = dv4;
-      uchar4 iv = make_uchar4(255, 255, 255, 255);
-      if (in && dzk[rd]) {
-        dv4 = *reinterpret_cast<const float4 *>(a.dy + dbase + dzo[rd]);
-        if (reads_output(a.act)) yv = *reinterpret_cast<const float4 *>(a.y + dbase + dzo[rd]);
-        if (POOL == 2) iv = *reinterpret_cast<const uchar4 *>(a.idx + dbase + dzo[rd]);
-      }
-      tr.dyv[rd] = dv4; tr.yv[rd] = yv; tr.iv[rd] = iv;
+      const int eo = in ? dzo[rd] : (int)(kOob >> 2);
+      tr.dyv[rd] = ldx4(rs_dy, 4 * eo, 4u * dbase);
+      if (reads_output(a.act)) tr.yv[rd] = ldx4(rs_y, 4 * eo, 4u * dbase);
+      if (POOL == 2) tr.iv[rd] = __builtin_bit_cast(uchar4, __builtin_amdgcn_raw_buffer_load_b32(rs_idx, eo, (int)dbase, 0));
     }
   };
 
@@ -235,7 +261,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
   auto store_tile = [&]() {
 #pragma unroll
     for (int it = 0; it < NXI; ++it) {
-      if (xl[it] >= 0) {
+      if (it < p.nxi && xl[it] >= 0) {
         float2 *d = reinterpret_cast<float2 *>(xs + xl[it]);
         d[0] = make_float2(tr.xi[it].x, tr.xi[it].y);
         d[1] = make_float2(tr.xi[it].z, tr.xi[it].w);
@@ -243,7 +269,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
     }
 #pragma unroll
     for (int it = 0; it < NXH; ++it)
-      if (hl[it] >= 0) xs[hl[it]] = tr.xh[it];
+      if (it < p.nxh && hl[it] >= 0) xs[hl[it]] = tr.xh[it];
 #pragma unroll
     for (int rd = 0; rd < DZR; ++rd) {
       if (!dzk[rd]) continue;
@@ -678,6 +704,14 @@ hipError_t launch_wgrad(const WgradArgs &a, const WgradPlan &plan, hipStream_t s
               lines * 8 <= NXI * kThreads && lines * (a.S - 1) <= NXH * kThreads;
   if (a.pool == 2) fast = fast && (p.Wo % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.idx) & 3u) == 0);
   else fast = fast && (p.Wo % 4 == 0);
+  // 32-bit byte offsets with an out-of-range marker at 2 GiB
+  const long x_bytes = 4L * a.N * a.C * a.H * a.W, dy_bytes = 4L * a.N * a.K * (p.Ho / a.pool) * (p.Wo / a.pool);
+  const long limit = (1L << 31) - (1L << 24);
+  fast = fast && x_bytes < limit && dy_bytes < limit;
+  p.x_bytes = (unsigned)(x_bytes < limit ? x_bytes : 0);
+  p.dy_bytes = (unsigned)(dy_bytes < limit ? dy_bytes : 0);
+  p.nxi = (lines * 8 + kThreads - 1) / kThreads;
+  p.nxh = (lines * (a.S - 1) + kThreads - 1) / kThreads;
   switch (plan.MTF) {
   case 1: return launch_wgrad_m<1>(p, plan, fast, stream);
   case 2: return launch_wgrad_m<2>(p, plan, fast, stream);
