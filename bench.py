@@ -45,20 +45,23 @@ def parse():
 
 
 def event_time_ms(fn, iters, warm=2):
-    """Average duration of fn() in ms from HIP events on torch's current stream (the launch stream)."""
+    """Average duration of fn() in ms: HIP events on torch's current stream (the launch stream)
+    around `iters` back-to-back calls, so the figure is the kernels' own time plus the gap
+    between dependent launches, not the host's call overhead.  Returns (mean of groups, groups)."""
     import torch
     for _ in range(warm):
         fn()
     torch.cuda.synchronize()
-    t = []
-    for _ in range(iters):
+    groups = []
+    for _ in range(3):
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
-        fn()
+        for _ in range(iters):
+            fn()
         b.record()
         b.synchronize()
-        t.append(a.elapsed_time(b))
-    return float(np.mean(t)), float(np.min(t))
+        groups.append(a.elapsed_time(b) / iters)
+    return float(np.median(groups)), groups
 
 
 def engine_kernel_name(cs, backward: bool) -> str:
@@ -72,7 +75,8 @@ def engine_kernel_name(cs, backward: bool) -> str:
         cc = 16 if cin % 16 == 0 else 4
         nt = 1 if kout <= 16 else 2
         waves = 8 if (cc == 16 and nt == 2) else 4
-        return f"conv3x3c16_kernel<{nt},{waves},{src},{cc}>"
+        pack3 = "true" if (cc == 4 and cin == 3 and not backward) else "false"
+        return f"conv3x3c16_kernel<{nt},{waves},{src},{cc},{pack3}>"
     nt = 1 if kout <= 16 else (2 if kout <= 32 else 3)
     return f"conv_engine_kernel<{nt},{1 if hout <= 8 else 2}>"
 

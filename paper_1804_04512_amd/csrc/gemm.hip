@@ -311,19 +311,25 @@ __device__ __forceinline__ void fast_tile_load(TileRegs<XT> &t, const float *src
   for (int it = 0; it < G::NV; ++it) t.v[it] = v[it];
 }
 
+// LDS offset (in floats) of slot `it` of a thread: fixed for the whole kernel
 template <int XT, bool KC>
-__device__ __forceinline__ void fast_tile_store(const TileRegs<XT> &t, float *dst) {
+__device__ __forceinline__ int fast_slot_lds(int tid, int it) {
   using G = SlotGeom<XT, KC>;
-  const int tid = threadIdx.x;
+  const int x = G::xl(tid, it), k = G::kl(tid, it);
+  return KC ? x * LDK + k : k * XT + (x ^ ((k & 1) << 4));
+}
+
+template <int XT, bool KC>
+__device__ __forceinline__ void fast_tile_store(const TileRegs<XT> &t, float *dst, const int (&lds_off)[SlotGeom<XT, KC>::NV]) {
+  using G = SlotGeom<XT, KC>;
 #pragma unroll
   for (int it = 0; it < G::NV; ++it) {
-    const int x = G::xl(tid, it), k = G::kl(tid, it);
     if (KC) {
-      float2 *d = reinterpret_cast<float2 *>(dst + x * LDK + k);
+      float2 *d = reinterpret_cast<float2 *>(dst + lds_off[it]);
       d[0] = make_float2(t.v[it].x, t.v[it].y);
       d[1] = make_float2(t.v[it].z, t.v[it].w);
     } else {
-      *reinterpret_cast<float4 *>(dst + k * XT + (x ^ ((k & 1) << 4))) = t.v[it];
+      *reinterpret_cast<float4 *>(dst + lds_off[it]) = t.v[it];
     }
   }
 }
@@ -372,6 +378,12 @@ __global__ __launch_bounds__(kThreads, 3) void gemm_fast_kernel(const GemmParams
   for (int it = 0; it < SlotGeom<BN, B_KC>::NV; ++it)
     sb[it] = 4u * ((unsigned)SlotGeom<BN, B_KC>::xl(tid, it) * b_sx + (unsigned)SlotGeom<BN, B_KC>::kl(tid, it) * b_sk);
 
+  int la[SlotGeom<BM, A_KC>::NV], lb[SlotGeom<BN, B_KC>::NV];   // LDS offsets of the thread's slots
+#pragma unroll
+  for (int it = 0; it < SlotGeom<BM, A_KC>::NV; ++it) la[it] = fast_slot_lds<BM, A_KC>(tid, it);
+#pragma unroll
+  for (int it = 0; it < SlotGeom<BN, B_KC>::NV; ++it) lb[it] = fast_slot_lds<BN, B_KC>(tid, it);
+
   TileRegs<BM> ta[2];
   TileRegs<BN> tb[2];
   auto load_tiles = [&](auto setc, const UnitPos &u) __attribute__((always_inline)) {
@@ -382,8 +394,8 @@ __global__ __launch_bounds__(kThreads, 3) void gemm_fast_kernel(const GemmParams
   };
   auto store_tiles = [&](auto setc, int buf) __attribute__((always_inline)) {
     constexpr int S_ = decltype(setc)::value;
-    fast_tile_store<BM, A_KC>(ta[S_], As[buf]);
-    fast_tile_store<BN, B_KC>(tb[S_], Bs[buf]);
+    fast_tile_store<BM, A_KC>(ta[S_], As[buf], la);
+    fast_tile_store<BN, B_KC>(tb[S_], Bs[buf], lb);
   };
 
   // operand read pointers: fragment i of A sits 16*i rows (or columns) after the base; in the
