@@ -76,7 +76,8 @@ def engine_kernel_name(cs, backward: bool) -> str:
         nt = 1 if kout <= 16 else 2
         waves = 8 if (cc == 16 and nt == 2) else 4
         pack3 = "true" if (cc == 4 and cin == 3 and not backward) else "false"
-        return f"conv3x3c16_kernel<{nt},{waves},{src},{cc},{pack3}>"
+        epi = 2 if backward else (1 if (cs.act == "relu" and cs.pool == 2) else 0)
+        return f"conv3x3c16_kernel<{nt},{waves},{src},{cc},{pack3},{epi}>"
     nt = 1 if kout <= 16 else (2 if kout <= 32 else 3)
     return f"conv_engine_kernel<{nt},{1 if hout <= 8 else 2}>"
 

@@ -345,7 +345,11 @@ constexpr int conv3x3_occupancy(int NT, int WAVES, int CC) { return (CC == 4 ? 4
 
 // SRC: 0 plain tensor, 1 dz without pooling, 2 dz through 2x2 pooling.  CC: channels per chunk,
 // 16, or 4 for shallow inputs such as RGB images (surplus channels are staged as zeros).
-template <int NT, int WAVES, int SRC, int CC, bool PACK3 = false>
+// EPI fixes the epilogue at compile time where the launcher knows it: 1 = bias + ReLU + 2x2 pool
+// (the forward pass of the networks this path is for), 2 = plain store (backward-data), 0 = decided
+// at run time (any activation, pooling or sampling).  The fixed forms keep the other epilogues'
+// code out of the kernel.
+template <int NT, int WAVES, int SRC, int CC, bool PACK3 = false, int EPI = 0>
 __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void conv3x3c16_kernel(const EngineParams p) {
   static_assert(!PACK3 || (CC == 4 && SRC == 0), "the packed three-channel path is a forward path of the 4-channel instance");
   constexpr int NTHR = WAVES * 64, RP = 8 / WAVES;   // 16-row tile: every wave owns RP row pairs
@@ -744,7 +748,9 @@ __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void 
       const int tx = tile % g.tiles_x;
       const int ty = (tile / g.tiles_x) % g.tiles_y;
       const int n = tile / (g.tiles_x * g.tiles_y);
-      engine_epilogue<NT, RP>(a, acc, n, ko0, ty * TH, tx * kTileW, wave, i16, kq);
+      if constexpr (EPI == 1) engine_epilogue_as<NT, RP, ACT_RELU, 2>(a, acc, n, ko0, ty * TH, tx * kTileW, wave, i16, kq);
+      else if constexpr (EPI == 2) engine_epilogue_as<NT, RP, ACT_IDENTITY, 1>(a, acc, n, ko0, ty * TH, tx * kTileW, wave, i16, kq);
+      else engine_epilogue<NT, RP>(a, acc, n, ko0, ty * TH, tx * kTileW, wave, i16, kq);
     }
     q = qn;
   }
@@ -767,6 +773,8 @@ bool conv3x3c16_applies(const ConvEngineArgs &a) {
   // the kernel addresses the source through 32-bit byte offsets that must stay below 2 GiB
   if ((long)a.N * a.Cin * a.Hin * a.Win * 4 >= (1L << 31)) return false;
   if (a.src_dz) {
+    // the dz instances store plainly: anything else on top of a backward-form pass takes the generic kernel
+    if (a.act != ACT_IDENTITY || a.pool != 1) return false;
     if (reads_output(a.src_act) && !aligned16(a.src_y)) return false;
     if (a.src_pool == 2) return (a.Win % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.src_idx) & 3u) == 0);
   }
@@ -814,13 +822,15 @@ hipError_t launch_3x3(const ConvEngineArgs &a, hipStream_t stream) {
     return hipGetLastError();
   };
   if (!a.src_dz) {
+    const bool relu_pool = a.act == ACT_RELU && a.pool == 2;
     if constexpr (CC == 4) {
-      if (p.g.pack3) return launch(conv3x3c16_kernel<NT, WAVES, 0, CC, true>);
+      if (p.g.pack3) return relu_pool ? launch(conv3x3c16_kernel<NT, WAVES, 0, CC, true, 1>) : launch(conv3x3c16_kernel<NT, WAVES, 0, CC, true, 0>);
     }
-    return launch(conv3x3c16_kernel<NT, WAVES, 0, CC>);
+    return relu_pool ? launch(conv3x3c16_kernel<NT, WAVES, 0, CC, false, 1>) : launch(conv3x3c16_kernel<NT, WAVES, 0, CC, false, 0>);
   }
-  if (a.src_pool == 2) return launch(conv3x3c16_kernel<NT, WAVES, 2, CC>);
-  return launch(conv3x3c16_kernel<NT, WAVES, 1, CC>);
+  // dz sources: the launcher only comes here with a plain-store epilogue (conv3x3c16_applies)
+  if (a.src_pool == 2) return launch(conv3x3c16_kernel<NT, WAVES, 2, CC, false, 2>);
+  return launch(conv3x3c16_kernel<NT, WAVES, 1, CC, false, 2>);
 }
 
 }  // namespace
