@@ -288,7 +288,6 @@ dll_status check_net(const dll_net_desc *net, NetLayout *lay) {
     if (y_count(d) > gmax) gmax = y_count(d);
     WgradPlan plan;
     if (!plan_for(d, &plan)) return DLL_ERR_UNSUPPORTED;
-    if (plan.partial_floats > partial) partial = plan.partial_floats;
     feat = y_count(d) / B;
   }
   for (int q = 0; q < net->n_dense; ++q) {
@@ -319,7 +318,9 @@ struct NetBuffers {
   unsigned char *idx[32];
   float *gbuf[2];
   float *rowloss;
-  float *partial;
+  float *partial;        // split-K partials of the dense products
+  float *cpartial[32];   // per conv layer: filter-gradient partial blocks (reduced by the step's closing kernel)
+  float *dz[32];         // per dense layer: dz of that layer (kept until the closing kernel sums the bias gradients)
 };
 
 size_t carve_net(const dll_net_desc *net, const NetLayout &lay, void *ws, NetBuffers *nb) {
@@ -334,6 +335,11 @@ size_t carve_net(const dll_net_desc *net, const NetLayout &lay, void *ws, NetBuf
   nb->gbuf[1] = c.floats(lay.gmax);
   nb->rowloss = c.floats(lay.B);
   nb->partial = c.floats(lay.partial);
+  for (int l = 0; l < L; ++l) {
+    WgradPlan plan;
+    nb->cpartial[l] = plan_for(&net->conv[l], &plan) ? c.floats(plan.partial_floats) : nullptr;
+  }
+  for (int q = 0; q < D; ++q) nb->dz[q] = c.floats((size_t)lay.B * net->dense[q].out);
   return c.used;
 }
 
@@ -400,14 +406,24 @@ dll_status dll_cnn_train_step(const dll_net_desc *net, float *const *params, flo
     if ((st = dev(launch_gemm(g, s))) != DLL_OK) return st;
   }
   // ---- loss
-  float *gcur = nb.gbuf[0], *gnext = nb.gbuf[1];
-  if ((st = dev(launch_softmax_ce(nb.act[L + D], labels, B, net->classes, loss, gcur, nb.rowloss, s))) != DLL_OK) return st;
+  // Reductions that nothing later in the step waits for (filter-gradient reductions with the
+  // filter updates, dense bias gradients, the mean loss) are collected as jobs of one closing
+  // launch; a full job list is flushed on the spot, which keeps the order of the plain sequence.
+  StepTail tail;
+  auto flush_tail = [&]() -> dll_status {
+    const dll_status r = dev(launch_step_tail(tail, s));
+    tail = StepTail{};
+    return r;
+  };
+  tail.rowloss = nb.rowloss; tail.rows = B; tail.loss = loss;
+  if ((st = dev(launch_softmax_ce(nb.act[L + D], labels, B, net->classes, nullptr, nb.dz[D - 1], nb.rowloss, s))) != DLL_OK) return st;
   // ---- dense backward: data gradient first (old weights), then weight gradient + update
   for (int q = D - 1; q >= 0; --q) {
     const dll_dense_desc *dd = &net->dense[q];
-    // gcur is dz of layer q: the loss kernel wrote it for the top layer, and each data-gradient
+    // dz[q] is dz of layer q: the loss kernel wrote it for the top layer, and each data-gradient
     // product below multiplies by the next lower layer's act' on its way out
     float *Wq = params[2 * (L + q)], *bq = params[2 * (L + q) + 1];
+    float *gcur = nb.dz[q], *gnext = q > 0 ? nb.dz[q - 1] : nb.gbuf[0];
     GemmArgs g;
     g.M = B; g.N = dd->in; g.Kdim = dd->out;
     g.A = gcur; g.a_m = dd->out; g.a_k = 1;
@@ -427,11 +443,14 @@ dll_status dll_cnn_train_step(const dll_net_desc *net, float *const *params, flo
     if (h.Cout || h.update)
       if ((st = dev(launch_gemm(h, s))) != DLL_OK) return st;
     float *gb = grads ? grads[2 * (L + q) + 1] : nullptr;
-    if (gb || upd)
-      if ((st = dev(launch_colsum(gcur, B, dd->out, gb, upd ? bq : nullptr, step, s))) != DLL_OK) return st;
-    float *t = gcur; gcur = gnext; gnext = t;
+    if (gb || upd) {
+      if (tail.n_colsum == StepTail::kMaxColsum && (st = flush_tail()) != DLL_OK) return st;
+      tail.colsum[tail.n_colsum++] = StepTail::Colsum{gcur, B, dd->out, gb, upd ? bq : nullptr, step};
+    }
   }
-  // ---- convolution backward: data gradient with the old filters, then filter gradient + update
+  // ---- convolution backward: data gradient with the old filters, then the filter-gradient partial
+  // sums; their reduction and the filter update wait for the closing launch
+  float *gcur = nb.gbuf[0], *gnext = nb.gbuf[1];
   for (int l = L - 1; l >= 0; --l) {
     const dll_conv_desc *d = &net->conv[l];
     // pooled ReLU layers: the forward pass above flagged the inactive units in idx, so the
@@ -443,17 +462,21 @@ dll_status dll_cnn_train_step(const dll_net_desc *net, float *const *params, flo
     }
     WgradPlan plan;
     if (!plan_for(d, &plan)) return DLL_ERR_UNSUPPORTED;
-    st = dev(launch_wgrad(wgrad_args(d, nb.act[l], gcur, yl, nb.idx[l], nb.partial), plan, s));
+    st = dev(launch_wgrad(wgrad_args(d, nb.act[l], gcur, yl, nb.idx[l], nb.cpartial[l]), plan, s));
     if (st != DLL_OK) return st;
     WgradReduceArgs r;
-    r.pos = nb.partial; r.scale = 1.0f;
+    r.pos = nb.cpartial[l]; r.scale = 1.0f;
     r.dw = grads ? grads[2 * l] : nullptr;
     r.db = grads ? grads[2 * l + 1] : nullptr;
     if (upd) { r.w_update = params[2 * l]; r.b_update = params[2 * l + 1]; r.step = step; }
     r.C = d->C; r.K = d->K; r.R = d->R; r.S = d->S;
-    if ((st = dev(launch_wgrad_reduce(r, plan, s))) != DLL_OK) return st;
+    if (tail.n_reduce == StepTail::kMaxReduce && (st = flush_tail()) != DLL_OK) return st;
+    tail.reduce[tail.n_reduce].a = r;
+    tail.reduce[tail.n_reduce].plan = plan;
+    ++tail.n_reduce;
     float *t = gcur; gcur = gnext; gnext = t;
   }
+  if ((st = flush_tail()) != DLL_OK) return st;
   return DLL_OK;
 }
 

@@ -14,6 +14,7 @@
 // second kernel adds the blocks in a fixed order (no float atomics: results are
 // bit-identical from run to run) and can apply the parameter update in the same pass.
 #include "dll_internal.h"
+#include "small_bodies.h"
 
 #include <type_traits>
 
@@ -475,8 +476,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
 // as 16-byte groups, 64 slices of the partial list run in parallel, sums are kept in double
 // and combined in a fixed order.  Blocks past the dw part sum the bias partials [g][K].
 constexpr int kRedSlices = kThreads / 4;
-__global__ __launch_bounds__(kThreads) void wgrad_reduce_kernel(const WgradReduceArgs a, const WgradPlan plan,
-                                                               long group_stride, int kgroups) {
+__device__ __forceinline__ void wgrad_reduce_block(const WgradReduceArgs &a, const WgradPlan &plan, long group_stride,
+                                                   int kgroups, int block) {
   __shared__ double red[kRedSlices][17];
   __shared__ double red2[4][17];
   const int tid = threadIdx.x, t4 = tid & 3, slice = tid >> 2;
@@ -485,7 +486,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_reduce_kernel(const WgradReduc
   const int per_chunk = rows * 4;                     // workgroups per (filter group, chunk)
   const int nblk_dw = kgroups * plan.nchunks * per_chunk;
   const long blockf = (long)rows * 64;
-  int blk = blockIdx.x;
+  int blk = block;
   double sum[4] = {0.0, 0.0, 0.0, 0.0};
   const bool is_dw = blk < nblk_dw;
   int grp = 0, chunk = 0, within0 = 0;
@@ -562,6 +563,42 @@ __global__ __launch_bounds__(kThreads) void wgrad_reduce_kernel(const WgradReduc
         if (a.b_update) a.b_update[k] += a.step * gval;
       }
     }
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void wgrad_reduce_kernel(const WgradReduceArgs a, const WgradPlan plan,
+                                                               long group_stride, int kgroups) {
+  wgrad_reduce_block(a, plan, group_stride, kgroups, blockIdx.x);
+}
+
+inline long reduce_group_stride(const WgradPlan &plan) {
+  return (long)plan.nchunks * plan.n_partials * ((long)plan.MTF * plan.NTT * 256);
+}
+inline int reduce_kgroups(const WgradReduceArgs &a, const WgradPlan &plan) { return (a.K + plan.MTF * 16 - 1) / (plan.MTF * 16); }
+inline int reduce_blocks(const WgradReduceArgs &a, const WgradPlan &plan) {
+  return reduce_kgroups(a, plan) * plan.nchunks * plan.MTF * plan.NTT * 16 + (a.K + 15) / 16;
+}
+
+// The step's closing kernel: workgroup ranges [start[j], start[j+1]) belong to job j; jobs are the
+// filter-gradient reductions, then the column sums, then the mean loss.
+struct StepTailParams {
+  StepTail t;
+  int start[StepTail::kMaxReduce + StepTail::kMaxColsum + 2];
+  long group_stride[StepTail::kMaxReduce];
+  int kgroups[StepTail::kMaxReduce];
+};
+__global__ __launch_bounds__(kThreads) void step_tail_kernel(const StepTailParams p) {
+  const int b = blockIdx.x;
+  int j = 0;
+  while (b >= p.start[j + 1]) ++j;   // uniform; at most a dozen jobs
+  const int blk = b - p.start[j];
+  if (j < p.t.n_reduce) {
+    wgrad_reduce_block(p.t.reduce[j].a, p.t.reduce[j].plan, p.group_stride[j], p.kgroups[j], blk);
+  } else if (j < p.t.n_reduce + p.t.n_colsum) {
+    const StepTail::Colsum &c = p.t.colsum[j - p.t.n_reduce];
+    colsum_block(c.A, c.M, c.N, c.out, c.update, c.step, blk);
+  } else {
+    mean_block(p.t.rowloss, p.t.rows, p.t.loss);
   }
 }
 
@@ -720,12 +757,36 @@ hipError_t launch_wgrad(const WgradArgs &a, const WgradPlan &plan, hipStream_t s
 }
 
 hipError_t launch_wgrad_reduce(const WgradReduceArgs &a, const WgradPlan &plan, hipStream_t stream) {
-  const long blockf = (long)plan.MTF * plan.NTT * 256;
-  const long group_stride = (long)plan.nchunks * plan.n_partials * blockf;
-  const int kgroups = (a.K + plan.MTF * 16 - 1) / (plan.MTF * 16);
-  const int blocks = kgroups * plan.nchunks * plan.MTF * plan.NTT * 16 + (a.K + 15) / 16;
   if ((reinterpret_cast<uintptr_t>(a.pos) & 15u) || (a.neg && (reinterpret_cast<uintptr_t>(a.neg) & 15u))) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(blocks), dim3(kThreads), 0, stream, a, plan, group_stride, kgroups);
+  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(reduce_blocks(a, plan)), dim3(kThreads), 0, stream, a, plan,
+                     reduce_group_stride(plan), reduce_kgroups(a, plan));
+  return hipGetLastError();
+}
+
+hipError_t launch_step_tail(const StepTail &t, hipStream_t stream) {
+  if (t.n_reduce < 0 || t.n_reduce > StepTail::kMaxReduce || t.n_colsum < 0 || t.n_colsum > StepTail::kMaxColsum) return hipErrorInvalidValue;
+  StepTailParams p;
+  p.t = t;
+  int jobs = 0, blocks = 0;
+  for (int j = 0; j < t.n_reduce; ++j) {
+    const WgradReduceArgs &a = t.reduce[j].a;
+    if ((reinterpret_cast<uintptr_t>(a.pos) & 15u) || (a.neg && (reinterpret_cast<uintptr_t>(a.neg) & 15u))) return hipErrorInvalidValue;
+    p.group_stride[j] = reduce_group_stride(t.reduce[j].plan);
+    p.kgroups[j] = reduce_kgroups(a, t.reduce[j].plan);
+    p.start[jobs++] = blocks;
+    blocks += reduce_blocks(a, t.reduce[j].plan);
+  }
+  for (int j = 0; j < t.n_colsum; ++j) {
+    p.start[jobs++] = blocks;
+    blocks += (t.colsum[j].N + kColsumCols - 1) / kColsumCols;
+  }
+  if (t.loss) {
+    p.start[jobs++] = blocks;
+    blocks += 1;
+  }
+  if (blocks == 0) return hipSuccess;
+  for (int j = jobs; j < StepTail::kMaxReduce + StepTail::kMaxColsum + 2; ++j) p.start[j] = blocks;
+  hipLaunchKernelGGL(step_tail_kernel, dim3(blocks), dim3(kThreads), 0, stream, p);
   return hipGetLastError();
 }
 

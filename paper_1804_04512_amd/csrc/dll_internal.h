@@ -127,4 +127,18 @@ hipError_t launch_visible_stats(const float *v0, const float *v1, int N, int C, 
 
 hipError_t launch_copy(const float *src, float *dst, size_t count, hipStream_t stream);
 
+// ---------------------------------------------------------------------------------------
+// Closing kernel of a training step: the reductions that nothing later in the step waits for
+// (filter-gradient reductions with their updates, dense bias gradients, the mean loss) run as
+// jobs of ONE launch instead of one tiny dependent kernel each.
+// ---------------------------------------------------------------------------------------
+struct StepTail {
+  static constexpr int kMaxReduce = 8, kMaxColsum = 4;
+  int n_reduce = 0, n_colsum = 0;
+  struct Reduce { WgradReduceArgs a; WgradPlan plan; } reduce[kMaxReduce];
+  struct Colsum { const float *A; int M, N; float *out, *update; float step; } colsum[kMaxColsum];
+  const float *rowloss = nullptr; int rows = 0; float *loss = nullptr;   // optional: *loss = mean(rowloss)
+};
+hipError_t launch_step_tail(const StepTail &t, hipStream_t stream);
+
 }  // namespace dllk

@@ -9,6 +9,7 @@
 // parameter update C_upd += step * C.
 // Workgroup tile 128 x 64 x 32, four wavefronts of 64 x 32 each, register-prefetched k-tiles.
 #include "dll_internal.h"
+#include "small_bodies.h"
 
 #include <type_traits>
 
@@ -564,48 +565,9 @@ __global__ __launch_bounds__(kThreads) void gemm_splitk_reduce_kernel(const Gemm
   }
 }
 
-// out[n] = sum_m A[m][n]: 16 columns per workgroup, 16 row slices added
-// in a fixed order (small inputs: many short independent load chains beat few long ones).
-constexpr int kColsumCols = 16, kColsumSlices = kThreads / kColsumCols;
 __global__ __launch_bounds__(kThreads) void colsum_kernel(const float *A, int M, int N, float *out, float *update,
                                                          float step) {
-  __shared__ float part[kColsumSlices][kColsumCols + 1];
-  const int col = threadIdx.x % kColsumCols, slice = threadIdx.x / kColsumCols;
-  const int n = blockIdx.x * kColsumCols + col;
-  float s = 0.0f;
-  if (n < N) {
-#pragma unroll 4
-    for (int m = slice; m < M; m += kColsumSlices) {
-      s += A[(long)m * N + n];
-    }
-  }
-  part[slice][col] = s;
-  __syncthreads();
-  if (slice == 0 && n < N) {
-    float q[4];
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      q[g] = 0.0f;
-#pragma unroll
-      for (int i = 0; i < kColsumSlices / 4; ++i) q[g] += part[g * (kColsumSlices / 4) + i][col];
-    }
-    s = (q[0] + q[1]) + (q[2] + q[3]);
-    if (out) out[n] = s;
-    if (update) update[n] += step * s;
-  }
-}
-
-__device__ __forceinline__ float block_reduce(float v, float *sh, bool is_max) {
-  const int tid = threadIdx.x;
-  sh[tid] = v;
-  __syncthreads();
-  for (int s = kThreads / 2; s > 0; s >>= 1) {
-    if (tid < s) sh[tid] = is_max ? fmaxf(sh[tid], sh[tid + s]) : sh[tid] + sh[tid + s];
-    __syncthreads();
-  }
-  const float r = sh[0];
-  __syncthreads();
-  return r;
+  colsum_block(A, M, N, out, update, step, blockIdx.x);
 }
 
 // One workgroup per sample: p = softmax(logits) with the row maximum subtracted,
@@ -630,13 +592,7 @@ __global__ __launch_bounds__(kThreads) void softmax_ce_kernel(const float *logit
   if (tid == 0) rowloss[n] = -(row[label] - m - logf(s));
 }
 
-__global__ __launch_bounds__(kThreads) void mean_kernel(const float *v, int count, float *out) {
-  __shared__ float sh[kThreads];
-  float s = 0.0f;
-  for (int j = threadIdx.x; j < count; j += kThreads) s += v[j];
-  s = block_reduce(s, sh, false);
-  if (threadIdx.x == 0) *out = s / (float)count;
-}
+__global__ __launch_bounds__(kThreads) void mean_kernel(const float *v, int count, float *out) { mean_block(v, count, out); }
 
 constexpr int kStatBlocks = 32;
 
@@ -749,6 +705,7 @@ hipError_t launch_softmax_ce(const float *logits, const int *labels, int B, int 
   hipLaunchKernelGGL(softmax_ce_kernel, dim3(B), dim3(kThreads), 0, stream, logits, labels, B, classes, dlogits, rowloss);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (!loss) return e;   // the caller takes the mean of rowloss later (step closing kernel)
   hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(kThreads), 0, stream, rowloss, B, loss);
   return hipGetLastError();
 }

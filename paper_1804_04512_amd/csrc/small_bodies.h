@@ -1,0 +1,63 @@
+// Bodies of the small reduction kernels, shared by their stand-alone launches (gemm.hip) and by
+// the training step's closing kernel (conv_wgrad.hip), which runs all of a step's deferred
+// reductions in one launch.  One workgroup of 256 threads per call; `blk` is the workgroup's
+// index inside its job.
+#pragma once
+
+#include "dll_internal.h"
+
+namespace dllk {
+
+constexpr int kSmallThreads = 256;
+constexpr int kColsumCols = 16, kColsumSlices = kSmallThreads / kColsumCols;
+
+// out[n] = sum_m A[m][n]: 16 columns per workgroup, 16 row slices added in a fixed order
+// (small inputs: many short independent load chains beat few long ones).
+__device__ __forceinline__ void colsum_block(const float *A, int M, int N, float *out, float *update, float step, int blk) {
+  __shared__ float part[kColsumSlices][kColsumCols + 1];
+  const int col = threadIdx.x % kColsumCols, slice = threadIdx.x / kColsumCols;
+  const int n = blk * kColsumCols + col;
+  float s = 0.0f;
+  if (n < N) {
+#pragma unroll 4
+    for (int m = slice; m < M; m += kColsumSlices) s += A[(long)m * N + n];
+  }
+  part[slice][col] = s;
+  __syncthreads();
+  if (slice == 0 && n < N) {
+    float q[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      q[g] = 0.0f;
+#pragma unroll
+      for (int i = 0; i < kColsumSlices / 4; ++i) q[g] += part[g * (kColsumSlices / 4) + i][col];
+    }
+    s = (q[0] + q[1]) + (q[2] + q[3]);
+    if (out) out[n] = s;
+    if (update) update[n] += step * s;
+  }
+}
+
+__device__ __forceinline__ float block_reduce(float v, float *sh, bool is_max) {
+  const int tid = threadIdx.x;
+  sh[tid] = v;
+  __syncthreads();
+  for (int s = kSmallThreads / 2; s > 0; s >>= 1) {
+    if (tid < s) sh[tid] = is_max ? fmaxf(sh[tid], sh[tid + s]) : sh[tid] + sh[tid + s];
+    __syncthreads();
+  }
+  const float r = sh[0];
+  __syncthreads();
+  return r;
+}
+
+// *out = mean of v[0 .. count)
+__device__ __forceinline__ void mean_block(const float *v, int count, float *out) {
+  __shared__ float sh[kSmallThreads];
+  float s = 0.0f;
+  for (int j = threadIdx.x; j < count; j += kSmallThreads) s += v[j];
+  s = block_reduce(s, sh, false);
+  if (threadIdx.x == 0) *out = s / (float)count;
+}
+
+}  // namespace dllk
