@@ -283,3 +283,26 @@ def cnn_train_step(net: Net, params, x, labels, lr=0.0, pool_idx_in=None, f64=Fa
                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     _check(fn(C.byref(nd), pp, gg, _p(x), _p(labels), lr, _p(loss), _p(logits), ii, io), "cnn_train_step")
     return CnnResult(float(loss[0]), logits, grads, idx_out)
+
+
+def cnn_forward(net: Net, params, x, f64=False):
+    """Inference pass: returns (logits, probabilities), both [N, classes]."""
+    dt = _dt(f64)
+    shapes = net.param_shapes()
+    assert len(params) == len(shapes)
+    for p, s in zip(params, shapes):
+        assert p.dtype == dt and p.flags.c_contiguous and tuple(p.shape) == tuple(s), (p.shape, s)
+    L = len(net.conv)
+    convs = (ConvDesc * L)(*net.conv)
+    denses = (DenseDesc * len(net.dense))(*[DenseDesc(i, o, a) for (i, o, a) in net.dense])
+    nd = NetDesc(L, convs, len(net.dense), denses, net.classes)
+    x = _arr(x, f64)
+    B = net.conv[0].N
+    logits = np.empty((B, net.classes), dt)
+    prob = np.empty((B, net.classes), dt)
+    PP = C.c_void_p * len(shapes)
+    pp = PP(*[p.ctypes.data for p in params])
+    fn = getattr(lib(), _pfx(f64) + "cnn_forward")
+    fn.argtypes = [C.POINTER(NetDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    _check(fn(C.byref(nd), pp, _p(x), _p(logits), _p(prob)), "cnn_forward")
+    return logits, prob

@@ -213,6 +213,42 @@ def config5(batch: int = 128, image: int = 256, hidden: int = 2048, classes: int
     return _cnn(5, "c5_large_image_cnn", conv, dense, classes, 0.001, "normal", None)
 
 
+# ---- the networks as the paper describes them (inference workloads; seeds 11..13)
+
+def paper_mnist_cnn(batch: int = 100) -> CnnWorkload:
+    """Section IV-B: 1x28x28, conv 8@5x5 + pool 2, conv 8@5x5 + pool 2, dense 150, dense 10; sigmoid
+    everywhere but the softmax output."""
+    conv = [ConvSpec(batch, 1, 28, 28, 8, 5, 5, 0, "sigmoid", 2), ConvSpec(batch, 8, 12, 12, 8, 5, 5, 0, "sigmoid", 2)]
+    dense = [DenseSpec(128, 150, "sigmoid"), DenseSpec(150, 10, "identity")]
+    return _cnn(11, "paper_mnist_cnn", conv, dense, 10, 0.1, "uniform", None)
+
+
+def paper_cifar_cnn(batch: int = 100) -> CnnWorkload:
+    """Section V: 3x32x32, conv 12@5x5 + pool 2, conv 24@3x3 + pool 2 (no padding), dense 64, dense 10; ReLU."""
+    conv = [ConvSpec(batch, 3, 32, 32, 12, 5, 5, 0, "relu", 2), ConvSpec(batch, 12, 14, 14, 24, 3, 3, 0, "relu", 2)]
+    dense = [DenseSpec(24 * 6 * 6, 64, "relu"), DenseSpec(64, 10, "identity")]
+    return _cnn(12, "paper_cifar_cnn", conv, dense, 10, 0.001, "normal", None)
+
+
+def paper_imagenet_cnn(batch: int = 128, image: int = 256, hidden: int = 2048, classes: int = 1000) -> CnnWorkload:
+    """Section VI: 3 x image x image, five blocks of conv 3x3 (16, 16, 32, 32, 32 kernels, zero-padded to
+    keep the size) + ReLU + pool 2, dense `hidden` ReLU, dense `classes`.  `image`, `hidden`, `classes`
+    shrink the same architecture for oracle-sized parity cases."""
+    assert image % 32 == 0
+    chans = [3, 16, 16, 32, 32, 32]
+    conv, side = [], image
+    for i in range(5):
+        conv.append(ConvSpec(batch, chans[i], side, side, chans[i + 1], 3, 3, 1, "relu", 2))
+        side //= 2
+    dense = [DenseSpec(32 * side * side, hidden, "relu"), DenseSpec(hidden, classes, "identity")]
+    return _cnn(13, "paper_imagenet_cnn", conv, dense, classes, 0.001, "normal", None)
+
+
+def forward_flop(w: CnnWorkload) -> int:
+    """Exact multiply-adds x 2 of one inference pass."""
+    return 2 * sum(c.macs_exact() for c in w.conv) + 2 * sum(w.batch * d.in_ * d.out for d in w.dense)
+
+
 def with_batch(cs: ConvSpec, n: int) -> ConvSpec:
     return replace(cs, N=n)
 

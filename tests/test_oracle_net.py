@@ -244,3 +244,93 @@ def test_crbm_is_the_composition_of_the_trio():
     np.testing.assert_allclose(W2, W + 0.5 * res.dW, rtol=1e-14)
     np.testing.assert_allclose(b2, b + 0.5 * res.db, rtol=1e-14)
     np.testing.assert_allclose(c2, c + 0.5 * res.dc, rtol=1e-14)
+
+
+# ---------------------------------------------------------------- inference pass
+
+def _np_forward(net, params, x):
+    """Independent forward pass: scipy's 2-D cross-correlation per (filter, channel) pair, numpy
+    reshapes for the 2x2 max pool, numpy matmul for the dense layers."""
+    from scipy.signal import correlate2d
+    act = {orc.ACT_IDENTITY: lambda z: z, orc.ACT_SIGMOID: sigmoid, orc.ACT_RELU: lambda z: np.maximum(z, 0)}
+    a = np.asarray(x, np.float64)
+    L = len(net.conv)
+    for l, d in enumerate(net.conv):
+        w, b = params[2 * l].astype(np.float64), params[2 * l + 1].astype(np.float64)
+        ap = np.pad(a, ((0, 0), (0, 0), (d.pad, d.pad), (d.pad, d.pad)))
+        N, K = a.shape[0], w.shape[0]
+        Ho, Wo = ap.shape[2] - w.shape[2] + 1, ap.shape[3] - w.shape[3] + 1
+        z = np.zeros((N, K, Ho, Wo))
+        for n in range(N):
+            for k in range(K):
+                for c in range(w.shape[1]):
+                    z[n, k] += correlate2d(ap[n, c], w[k, c], mode="valid")
+                z[n, k] += b[k]
+        a = act[d.act](z)
+        if d.pool == 2:
+            a = a.reshape(N, K, Ho // 2, 2, Wo // 2, 2).max(axis=(3, 5))
+    a = a.reshape(a.shape[0], -1)
+    for q, (nin, nout, ac) in enumerate(net.dense):
+        W, b = params[2 * (L + q)].astype(np.float64), params[2 * (L + q) + 1].astype(np.float64)
+        z = a @ W.T + b
+        a = z if q == len(net.dense) - 1 else act[ac](z)
+    e = np.exp(a - a.max(1, keepdims=True))
+    return a, e / e.sum(1, keepdims=True)
+
+
+def _small_net(act, pad):
+    conv = [orc.conv_desc(3, 2, 10, 12, 4, 3, 3, pad, act, 2)]
+    h1, w1 = (10 + 2 * pad - 2) // 2, (12 + 2 * pad - 2) // 2
+    conv.append(orc.conv_desc(3, 4, h1, w1, 3, 3, 2, 0, act, 1))
+    feat = 3 * (h1 - 2) * (w1 - 1)
+    return orc.Net(conv, [(feat, 6, act), (6, 5, orc.ACT_IDENTITY)], 5)
+
+
+@pytest.mark.parametrize("act,pad", [(orc.ACT_SIGMOID, 0), (orc.ACT_RELU, 1)])
+def test_cnn_forward_vs_scipy_numpy(act, pad):
+    net = _small_net(act, pad)
+    r = np.random.default_rng(300 + act)
+    params = [r.normal(size=s) * 0.5 for s in net.param_shapes()]
+    x = r.normal(size=(3, 2, 10, 12))
+    logits, prob = orc.cnn_forward(net, params, x, f64=True)
+    ref_logits, ref_prob = _np_forward(net, params, x)
+    np.testing.assert_allclose(logits, ref_logits, atol=1e-12)
+    np.testing.assert_allclose(prob, ref_prob, atol=1e-13)
+    np.testing.assert_allclose(prob.sum(1), 1.0, rtol=1e-14)
+    # the float instance rounds once per layer: same values to fp32 accuracy
+    l32, p32 = orc.cnn_forward(net, [p.astype(np.float32) for p in params], x.astype(np.float32))
+    assert np.abs(l32 - ref_logits).max() <= 2e-5 * max(1.0, np.abs(ref_logits).max())
+    assert np.abs(p32 - ref_prob).max() <= 2e-6
+
+
+def test_cnn_forward_closed_forms():
+    net = _small_net(orc.ACT_SIGMOID, 0)
+    shapes = net.param_shapes()
+    x = np.random.default_rng(310).normal(size=(3, 2, 10, 12))
+    # all parameters zero: logits 0, every class equally likely
+    logits, prob = orc.cnn_forward(net, [np.zeros(s) for s in shapes], x, f64=True)
+    assert not logits.any()
+    np.testing.assert_allclose(prob, 0.2, rtol=1e-15)
+    # only the output bias set: logits = bias, probabilities = softmax(bias), whatever the image
+    params = [np.zeros(s) for s in shapes]
+    params[-1][:] = [0.0, np.log(2.0), np.log(3.0), 0.0, np.log(4.0)]
+    logits, prob = orc.cnn_forward(net, params, x, f64=True)
+    np.testing.assert_allclose(logits, np.tile(params[-1], (3, 1)), atol=1e-15)
+    np.testing.assert_allclose(prob, np.tile(np.array([1, 2, 3, 1, 4]) / 11.0, (3, 1)), rtol=1e-14)
+    # a constant added to the output bias leaves the probabilities alone, also when huge
+    r = np.random.default_rng(311)
+    params = [r.normal(size=s) for s in shapes]
+    _, p0 = orc.cnn_forward(net, params, x, f64=True)
+    params[-1] += 700.0
+    _, p1 = orc.cnn_forward(net, params, x, f64=True)
+    np.testing.assert_allclose(p1, p0, rtol=1e-9)
+
+
+def test_cnn_forward_matches_training_pass_logits():
+    net = _small_net(orc.ACT_RELU, 1)
+    r = np.random.default_rng(320)
+    params = [(r.normal(size=s) * 0.5).astype(np.float32) for s in net.param_shapes()]
+    x = r.normal(size=(3, 2, 10, 12)).astype(np.float32)
+    logits, _ = orc.cnn_forward(net, params, x)
+    step = orc.cnn_train_step(net, [p.copy() for p in params], x, np.array([0, 1, 2]), lr=0.0)
+    assert np.array_equal(logits, step.logits)
