@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--batch", type=int, default=None, help="override the batch size (inspection only)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--cpu-batch", type=int, default=32)
+    ap.add_argument("--mode", choices=["train", "infer"], default="train",
+                    help="infer: time dll_cnn_forward on the paper's ImageNet network (batch 128 of 3x256x256) instead of the training step")
     ap.add_argument("--pmc-calib", action="store_true",
                     help="also run one 256 MiB device copy, the known-size kernel that scales rocprofv3's byte counters")
     return ap.parse_args()
@@ -144,6 +146,46 @@ def cpu_baseline(cfg: int, cpu_batch: int):
                 kind="oracle", sample=f"one step of config {cfg} at batch {n} (same layer shapes), fp64 accumulation, plain loops")
 
 
+def infer_line(args, B, wl, torch):
+    """Inspection mode: one inference pass of the paper's five-block ImageNet network per step."""
+    w = wl.paper_imagenet_cnn(args.batch) if args.batch else wl.paper_imagenet_cnn()
+    net = B.net_desc(w.conv, w.dense, w.classes)
+    params = [torch.from_numpy(p).cuda() for p in w.params]
+    x = torch.from_numpy(w.x).cuda()
+    prob = torch.empty((w.batch, w.classes), device="cuda")
+    ws = B.workspace(B.dll_cnn_forward_workspace_bytes(net))
+    step = lambda: B.dll_cnn_forward(net, params, x, None, prob, ws)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    flop = wl.forward_flop(w)
+    gflops = flop / (ms * 1e-3) / 1e9
+    out = {"metric": "inference GFLOP/s + images/s per forward pass; % of fp32 MFMA peak", "value": gflops, "unit": "GFLOP/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": w.name, "batch": w.batch, "flop_per_step": flop},
+           "images_per_s": w.batch / (ms * 1e-3), "pct_fp32_mfma_peak": 100.0 * gflops / (PEAK_FP32_MFMA_TFLOPS * 1e3)}
+    if not args.no_cpu:
+        from oracle import oracle as orc
+        act = {"identity": 0, "sigmoid": 1, "relu": 2}
+        wc = wl.paper_imagenet_cnn(min(args.cpu_batch, w.batch))
+        onet = orc.Net([orc.conv_desc(c.N, c.C, c.H, c.W, c.K, c.R, c.S, c.pad, act[c.act], c.pool) for c in wc.conv],
+                       [(d.in_, d.out, act[d.act]) for d in wc.dense], wc.classes)
+        t0 = time.perf_counter()
+        orc.cnn_forward(onet, wc.params, wc.x)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = dict(value=wl.forward_flop(wc) / dt / 1e9, unit="GFLOP/s", images_per_s=wc.batch / dt, seconds=dt,
+                                   cores=orc.max_threads(), kind="oracle",
+                                   sample=f"one inference pass of {wc.name} at batch {wc.batch}, fp64 accumulation, plain loops")
+    print(json.dumps(out))
+    return 0
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -155,6 +197,8 @@ def main():
 
     B.lib()  # fail loudly when the HIP library is missing
     torch.cuda.set_device(0)
+    if args.mode == "infer":
+        return infer_line(args, B, wl, torch)
     cfg = args.config
     w = wl.ALL[cfg](args.batch) if args.batch else wl.ALL[cfg]()
     dev = lambda a: torch.from_numpy(a).cuda()

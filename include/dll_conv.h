@@ -147,6 +147,18 @@ dll_status dll_cnn_train_step(const dll_net_desc *net, float *const *params, flo
                               float *logits, unsigned char *const *pool_idx, void *ws,
                               size_t ws_bytes, void *stream);
 
+/* Inference pass of the same network description (Sections IV-VI: the networks the paper times
+ * end in a softmax layer): the convolution blocks, the dense layers (the last one without
+ * activation) and the softmax of its outputs.  Nothing is kept for a backward pass: activations
+ * ping-pong between two workspace buffers and no pooling index is written.
+ *   params  host array of 2*(n_conv+n_dense) device pointers, order as in dll_cnn_train_step; read only
+ *   x       [N][C][H][W] of the first layer
+ *   logits  [N][classes], may be NULL;  prob [N][classes], may be NULL (not both)
+ * Errors as for dll_cnn_train_step. */
+size_t dll_cnn_forward_workspace_bytes(const dll_net_desc *net);
+dll_status dll_cnn_forward(const dll_net_desc *net, const float *const *params, const float *x,
+                           float *logits, float *prob, void *ws, size_t ws_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,7 @@ LIB_PATH = os.path.join(_HERE, "libdll_conv.so")
 ACT = {"identity": 0, "sigmoid": 1, "relu": 2}
 SYMBOLS = ["dll_status_string", "dll_conv_workspace_bytes", "dll_conv_valid_fwd", "dll_conv_full_bwd",
            "dll_conv_valid_wgrad", "dll_crbm_workspace_bytes", "dll_crbm_cd1_step",
-           "dll_cnn_workspace_bytes", "dll_cnn_train_step"]
+           "dll_cnn_workspace_bytes", "dll_cnn_train_step", "dll_cnn_forward_workspace_bytes", "dll_cnn_forward"]
 
 
 class DllError(RuntimeError):
@@ -69,6 +69,9 @@ def lib() -> C.CDLL:
         L.dll_cnn_workspace_bytes.restype = sz
         L.dll_cnn_workspace_bytes.argtypes = [C.POINTER(dll_net_desc)]
         L.dll_cnn_train_step.argtypes = [C.POINTER(dll_net_desc), vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, sz, vp]
+        L.dll_cnn_forward_workspace_bytes.restype = sz
+        L.dll_cnn_forward_workspace_bytes.argtypes = [C.POINTER(dll_net_desc)]
+        L.dll_cnn_forward.argtypes = [C.POINTER(dll_net_desc), vp, vp, vp, vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -168,3 +171,13 @@ def dll_cnn_train_step(net: NetHandle, params: List[torch.Tensor], grads, x, lab
     _ok(lib().dll_cnn_train_step(C.byref(net.desc), pa, ga, _ptr(x), _ptr(labels), C.c_float(lr), _ptr(loss),
                                  _ptr(logits), ia, _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream)),
         "dll_cnn_train_step")
+
+
+def dll_cnn_forward_workspace_bytes(net: NetHandle) -> int:
+    return int(lib().dll_cnn_forward_workspace_bytes(C.byref(net.desc)))
+
+
+def dll_cnn_forward(net: NetHandle, params: List[torch.Tensor], x, logits=None, prob=None, ws=None, stream=None) -> None:
+    pa = _ptr_array(params)
+    _ok(lib().dll_cnn_forward(C.byref(net.desc), pa, _ptr(x), _ptr(logits), _ptr(prob), _ptr(ws),
+                              0 if ws is None else ws.numel(), _stream(stream)), "dll_cnn_forward")

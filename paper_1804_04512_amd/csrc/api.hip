@@ -480,4 +480,65 @@ dll_status dll_cnn_train_step(const dll_net_desc *net, float *const *params, flo
   return DLL_OK;
 }
 
+size_t dll_cnn_forward_workspace_bytes(const dll_net_desc *net) {
+  NetLayout lay;
+  if (check_net(net, &lay) != DLL_OK) return 0;
+  Carver c(nullptr, 0);
+  c.floats(lay.gmax); c.floats(lay.gmax);
+  c.floats(lay.partial);
+  c.floats((size_t)lay.B * net->classes);
+  return c.used;
+}
+
+dll_status dll_cnn_forward(const dll_net_desc *net, const float *const *params, const float *x, float *logits,
+                           float *prob, void *ws, size_t ws_bytes, void *stream) {
+  NetLayout lay;
+  dll_status st = check_net(net, &lay);
+  if (st != DLL_OK) return st;
+  const int L = net->n_conv, D = net->n_dense, B = lay.B;
+  if (!params || !x || (!logits && !prob)) return DLL_ERR_NULL;
+  for (int p = 0; p < 2 * (L + D); ++p) {
+    if (!params[p]) return DLL_ERR_NULL;
+    if (misaligned(params[p])) return DLL_ERR_SHAPE;
+  }
+  if (misaligned(x) || misaligned(logits) || misaligned(prob)) return DLL_ERR_SHAPE;
+  if (logits && logits == prob) return DLL_ERR_SHAPE;
+  Carver c(ws, 0);
+  float *buf[2] = {c.floats(lay.gmax), c.floats(lay.gmax)};
+  float *partial = c.floats(lay.partial);
+  float *own_logits = c.floats((size_t)B * net->classes);
+  st = check_ws(ws, ws_bytes, c.used);
+  if (st != DLL_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const float *cur = x;
+  int flip = 0;
+  for (int l = 0; l < L; ++l) {
+    const dll_conv_desc *d = &net->conv[l];
+    float *out = buf[flip];
+    st = dev(launch_conv_engine(fwd_args(d, cur, params[2 * l], params[2 * l + 1], out, nullptr), s));
+    if (st != DLL_OK) return st;
+    cur = out;
+    flip ^= 1;
+  }
+  float *lg = logits ? logits : own_logits;
+  for (int q = 0; q < D; ++q) {
+    const dll_dense_desc *dd = &net->dense[q];
+    float *out = (q == D - 1) ? lg : buf[flip];
+    GemmArgs g;
+    g.M = B; g.N = dd->out; g.Kdim = dd->in;
+    g.A = cur; g.a_m = dd->in; g.a_k = 1;
+    g.B = params[2 * (L + q)]; g.b_k = 1; g.b_n = dd->in;
+    g.bias = params[2 * (L + q) + 1];
+    g.act = (q == D - 1) ? ACT_IDENTITY : dd->act;
+    g.Cout = out; g.c_m = dd->out; g.c_n = 1;
+    g.split_k = gemm_pick_split_k(g.M, g.N, g.Kdim);
+    g.partial = partial;
+    if ((st = dev(launch_gemm(g, s))) != DLL_OK) return st;
+    cur = out;
+    flip ^= 1;
+  }
+  if (prob && (st = dev(launch_softmax_prob(lg, B, net->classes, prob, s))) != DLL_OK) return st;
+  return DLL_OK;
+}
+
 }  // extern "C"

@@ -119,11 +119,14 @@ __device__ __forceinline__ void engine_epilogue_as(const ConvEngineArgs &a, floa
         const int o = ((n * a.Kout + ko) * Hp + py) * Wp + px0;
         if (px0 + 3 < Wp && (Wp & 3) == 0) {
           *reinterpret_cast<float4 *>(a.out + o) = make_float4(yv[0], yv[1], yv[2], yv[3]);
-          *reinterpret_cast<uchar4 *>(a.out_idx + o) = make_uchar4(iv[0], iv[1], iv[2], iv[3]);
+          if (a.out_idx) *reinterpret_cast<uchar4 *>(a.out_idx + o) = make_uchar4(iv[0], iv[1], iv[2], iv[3]);
         } else {
 #pragma unroll
           for (int mt = 0; mt < 4; ++mt)
-            if (px0 + mt < Wp) { a.out[o + mt] = yv[mt]; a.out_idx[o + mt] = iv[mt]; }
+            if (px0 + mt < Wp) {
+              a.out[o + mt] = yv[mt];
+              if (a.out_idx) a.out_idx[o + mt] = iv[mt];
+            }
         }
       } else {
 #pragma unroll

@@ -42,7 +42,7 @@ struct ConvEngineArgs {
   const float *bias = nullptr;
   int act = ACT_IDENTITY, pool = 1;
   float *out = nullptr;
-  unsigned char *out_idx = nullptr;
+  unsigned char *out_idx = nullptr;           // pool == 2: optional (an inference pass does not keep the decisions)
   const float *uniform = nullptr;         // optional Bernoulli epilogue (pool == 1): sample = 1[uniform < out]
   float *sample = nullptr;
 };
@@ -118,6 +118,9 @@ hipError_t launch_colsum(const float *A, int M, int N, float *out,
 // Softmax cross-entropy over rows; loss = mean; dlogits = (p - onehot)/B.  rowloss: B floats scratch.
 hipError_t launch_softmax_ce(const float *logits, const int *labels, int B, int classes, float *loss,
                              float *dlogits, float *rowloss, hipStream_t stream);
+
+// prob[n][j] = softmax(logits[n][:])[j] with the row maximum subtracted (inference output).
+hipError_t launch_softmax_prob(const float *logits, int B, int classes, float *prob, hipStream_t stream);
 
 // CRBM visible statistics: dc[ch] = scale * sum(v0 - v1), mse = mean((v0-v1)^2); scratch: 2 * nblocks floats.
 size_t visible_stats_scratch_floats(int N, int C, int HW);

@@ -592,6 +592,21 @@ __global__ __launch_bounds__(kThreads) void softmax_ce_kernel(const float *logit
   if (tid == 0) rowloss[n] = -(row[label] - m - logf(s));
 }
 
+// One workgroup per sample: prob = softmax(logits) with the row maximum subtracted.
+__global__ __launch_bounds__(kThreads) void softmax_prob_kernel(const float *logits, int classes, float *prob) {
+  __shared__ float sh[kThreads];
+  const int n = blockIdx.x, tid = threadIdx.x;
+  const float *row = logits + (long)n * classes;
+  float m = -INFINITY;
+  for (int j = tid; j < classes; j += kThreads) m = fmaxf(m, row[j]);
+  m = block_reduce(m, sh, true);
+  float s = 0.0f;
+  for (int j = tid; j < classes; j += kThreads) s += expf(row[j] - m);
+  s = block_reduce(s, sh, false);
+  const float inv = 1.0f / s;
+  for (int j = tid; j < classes; j += kThreads) prob[(long)n * classes + j] = expf(row[j] - m) * inv;
+}
+
 __global__ __launch_bounds__(kThreads) void mean_kernel(const float *v, int count, float *out) { mean_block(v, count, out); }
 
 constexpr int kStatBlocks = 32;
@@ -707,6 +722,11 @@ hipError_t launch_softmax_ce(const float *logits, const int *labels, int B, int 
   if (e != hipSuccess) return e;
   if (!loss) return e;   // the caller takes the mean of rowloss later (step closing kernel)
   hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(kThreads), 0, stream, rowloss, B, loss);
+  return hipGetLastError();
+}
+
+hipError_t launch_softmax_prob(const float *logits, int B, int classes, float *prob, hipStream_t stream) {
+  hipLaunchKernelGGL(softmax_prob_kernel, dim3(B), dim3(kThreads), 0, stream, logits, classes, prob);
   return hipGetLastError();
 }
 

@@ -275,3 +275,50 @@ def test_cnn_lr_zero_and_no_grads():
         np.testing.assert_array_equal(a, b)
     o = orc.cnn_train_step(onet(w), w.clone_params(), w.x, w.labels, 0.0)
     assert max_rel_err(np.array([g["loss"]]), np.array([o.loss])) <= TOL_FWD
+
+
+# ---------------------------------------------------------------- inference pass
+
+def run_forward_gpu(w: wl.CnnWorkload):
+    net = B.net_desc(w.conv, w.dense, w.classes)
+    params = [dev(p) for p in w.params]
+    logits = torch.full((w.batch, w.classes), float("nan"), device="cuda")
+    prob = torch.full((w.batch, w.classes), float("nan"), device="cuda")
+    ws = B.workspace(B.dll_cnn_forward_workspace_bytes(net))
+    B.dll_cnn_forward(net, params, dev(w.x), logits, prob, ws)
+    return host(logits), host(prob)
+
+
+def check_forward(w: wl.CnnWorkload):
+    lg, pg = run_forward_gpu(w)
+    lo, po = orc.cnn_forward(onet(w), w.params, w.x)
+    assert max_rel_err(lg, lo) <= TOL_FWD
+    assert max_rel_err(pg, po) <= TOL_FWD
+    np.testing.assert_allclose(pg.sum(1), 1.0, rtol=1e-5)
+
+
+@pytest.mark.parametrize("make", [lambda: wl.paper_mnist_cnn(37), lambda: wl.paper_cifar_cnn(21),
+                                  lambda: wl.paper_imagenet_cnn(5, 64, 96, 40),
+                                  lambda: wl.config5(batch=3, image=64, hidden=128, classes=50)],
+                         ids=["paper_mnist_cnn", "paper_cifar_cnn", "paper_imagenet_cnn_64px", "config5_64px"])
+def test_forward_pass_matches_oracle(make):
+    """Inference pass of the networks as the paper describes them (full layer shapes for the MNIST
+    and CIFAR nets, the ImageNet architecture at 64x64) against the oracle's inference pass."""
+    check_forward(make())
+
+
+def test_forward_pass_logits_equal_training_pass_logits():
+    """Same kernels, same order of operations: the inference pass and the training step's forward
+    half give bit-identical logits; logits-only and probabilities-only calls work."""
+    w = wl.config5(batch=4, image=64, hidden=128, classes=50)
+    g = run_cnn_gpu(w, 0.0, want_grads=False)
+    lg, pg = run_forward_gpu(w)
+    assert np.array_equal(lg, g["logits"])
+    net = B.net_desc(w.conv, w.dense, w.classes)
+    params = [dev(p) for p in w.params]
+    ws = B.workspace(B.dll_cnn_forward_workspace_bytes(net))
+    only_p = torch.full((w.batch, w.classes), float("nan"), device="cuda")
+    B.dll_cnn_forward(net, params, dev(w.x), None, only_p, ws)
+    assert np.array_equal(host(only_p), pg)
+    with pytest.raises(B.DllError):
+        B.dll_cnn_forward(net, params, dev(w.x), None, None, ws)
