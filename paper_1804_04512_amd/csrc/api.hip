@@ -392,6 +392,7 @@ dll_status dll_cnn_train_step(const dll_net_desc *net, float *const *params, flo
     if (st != DLL_OK) return st;
   }
   if (logits) nb.act[L + D] = logits;
+  int logits_split = 1;
   for (int q = 0; q < D; ++q) {
     const dll_dense_desc *dd = &net->dense[q];
     GemmArgs g;
@@ -403,6 +404,8 @@ dll_status dll_cnn_train_step(const dll_net_desc *net, float *const *params, flo
     g.Cout = nb.act[L + q + 1]; g.c_m = dd->out; g.c_n = 1;
     g.split_k = gemm_pick_split_k(g.M, g.N, g.Kdim);
     g.partial = nb.partial;
+    // the logits' split-K partials are added by the loss kernel, which reads them anyway
+    if (q == D - 1 && g.split_k > 1) { g.defer_reduce = true; logits_split = g.split_k; }
     if ((st = dev(launch_gemm(g, s))) != DLL_OK) return st;
   }
   // ---- loss
@@ -416,7 +419,9 @@ dll_status dll_cnn_train_step(const dll_net_desc *net, float *const *params, flo
     return r;
   };
   tail.rowloss = nb.rowloss; tail.rows = B; tail.loss = loss;
-  if ((st = dev(launch_softmax_ce(nb.act[L + D], labels, B, net->classes, nullptr, nb.dz[D - 1], nb.rowloss, s))) != DLL_OK) return st;
+  st = dev(launch_softmax_ce(nb.act[L + D], labels, B, net->classes, nullptr, nb.dz[D - 1], nb.rowloss,
+                             logits_split > 1 ? nb.partial : nullptr, logits_split, params[2 * (L + D - 1) + 1], s));
+  if (st != DLL_OK) return st;
   // ---- dense backward: data gradient first (old weights), then weight gradient + update
   for (int q = D - 1; q >= 0; --q) {
     const dll_dense_desc *dd = &net->dense[q];

@@ -107,6 +107,9 @@ struct GemmArgs {
   float *update = nullptr; float step = 0.0f;        // nullable: update(m,n) += step * C(m,n), same strides as Cout
   int split_k = 1;
   float *partial = nullptr;                          // split_k * M * N floats when split_k > 1
+  // split_k > 1 only: leave the partials as they are; the consumer adds them (in split order,
+  // then the bias) itself.  Only for an identity epilogue without update.
+  bool defer_reduce = false;
 };
 int gemm_pick_split_k(int M, int N, int Kdim);
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream);
@@ -116,8 +119,11 @@ hipError_t launch_colsum(const float *A, int M, int N, float *out,
                          float *update, float step, hipStream_t stream);
 
 // Softmax cross-entropy over rows; loss = mean; dlogits = (p - onehot)/B.  rowloss: B floats scratch.
-hipError_t launch_softmax_ce(const float *logits, const int *labels, int B, int classes, float *loss,
-                             float *dlogits, float *rowloss, hipStream_t stream);
+// With partial != NULL the logits are first formed from split_k partial products [z][B][classes]
+// plus bias (what the deferred split-K reduction would have written) and stored to `logits`.
+hipError_t launch_softmax_ce(float *logits, const int *labels, int B, int classes, float *loss,
+                             float *dlogits, float *rowloss, const float *partial, int split_k, const float *bias,
+                             hipStream_t stream);
 
 // prob[n][j] = softmax(logits[n][:])[j] with the row maximum subtracted (inference output).
 hipError_t launch_softmax_prob(const float *logits, int B, int classes, float *prob, hipStream_t stream);

@@ -572,11 +572,22 @@ __global__ __launch_bounds__(kThreads) void colsum_kernel(const float *A, int M,
 
 // One workgroup per sample: p = softmax(logits) with the row maximum subtracted,
 // rowloss = -ln p[label], dlogits = (p - onehot) / B.
-__global__ __launch_bounds__(kThreads) void softmax_ce_kernel(const float *logits, const int *labels, int B, int classes,
-                                                             float *dlogits, float *rowloss) {
+__global__ __launch_bounds__(kThreads) void softmax_ce_kernel(float *logits, const int *labels, int B, int classes,
+                                                             float *dlogits, float *rowloss, const float *partial,
+                                                             int split_k, const float *bias) {
   __shared__ float sh[kThreads];
   const int n = blockIdx.x, tid = threadIdx.x;
-  const float *row = logits + (long)n * classes;
+  float *row = logits + (long)n * classes;
+  if (partial) {   // the product's split-K partials, added in split order, then the bias
+    const long total = (long)B * classes;
+    for (int j = tid; j < classes; j += kThreads) {
+      float c = 0.0f;
+      for (int z = 0; z < split_k; ++z) c += partial[(long)z * total + (long)n * classes + j];
+      if (bias) c += bias[j];
+      row[j] = c;
+    }
+    __syncthreads();   // the row is complete (and visible to the whole workgroup) before it is read back
+  }
   float m = -INFINITY;
   for (int j = tid; j < classes; j += kThreads) m = fmaxf(m, row[j]);
   m = block_reduce(m, sh, true);
@@ -699,7 +710,7 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream) {
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (p.a.split_k > 1) {
+  if (p.a.split_k > 1 && !a.defer_reduce) {
     const long total = (long)a.M * a.N;
     long blocks = (total + kThreads - 1) / kThreads;
     if (blocks > 2048) blocks = 2048;
@@ -715,9 +726,10 @@ hipError_t launch_colsum(const float *A, int M, int N, float *out, float *update
   return hipGetLastError();
 }
 
-hipError_t launch_softmax_ce(const float *logits, const int *labels, int B, int classes, float *loss, float *dlogits,
-                             float *rowloss, hipStream_t stream) {
-  hipLaunchKernelGGL(softmax_ce_kernel, dim3(B), dim3(kThreads), 0, stream, logits, labels, B, classes, dlogits, rowloss);
+hipError_t launch_softmax_ce(float *logits, const int *labels, int B, int classes, float *loss, float *dlogits,
+                             float *rowloss, const float *partial, int split_k, const float *bias, hipStream_t stream) {
+  hipLaunchKernelGGL(softmax_ce_kernel, dim3(B), dim3(kThreads), 0, stream, logits, labels, B, classes, dlogits, rowloss,
+                     partial, split_k, bias);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (!loss) return e;   // the caller takes the mean of rowloss later (step closing kernel)
