@@ -111,7 +111,7 @@ WgradArgs wgrad_args(const dll_conv_desc *d, const float *x, const float *dy, co
 }
 
 bool plan_for(const dll_conv_desc *d, WgradPlan *plan) {
-  return plan_wgrad(d->N, d->C, d->H, d->W, d->K, d->R, d->S, d->pad, plan);
+  return plan_wgrad(d->N, d->C, d->H, d->W, d->K, d->R, d->S, d->pad, d->pool, plan);
 }
 
 }  // namespace

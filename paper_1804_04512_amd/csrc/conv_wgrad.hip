@@ -637,7 +637,7 @@ inline Geom x_geom(int R, int S, int pad) {
 
 }  // namespace
 
-bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, WgradPlan *plan) {
+bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, int pool, WgradPlan *plan) {
   const int Ho = H + 2 * pad - R + 1, Wo = W + 2 * pad - S + 1;
   const int RSf = R * S;
   // channels per chunk: minimise (chunks x tap tiles) with at most 9 tap tiles
@@ -671,7 +671,15 @@ bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, WgradP
   // persistent workgroups: as many as stay resident (LDS and register budget), at least two
   // tiles each where the problem is large enough
   long resident = (long)(160 * 1024 / plan->lds_bytes);
-  const long by_regs = best_ntt <= 5 ? 4 : (best_ntt <= 7 ? 3 : 2);
+  // waves per SIMD that the kernel instance's registers (vector + accumulator, from the compiler's
+  // resource report) leave room for; a grid beyond it would queue workgroups behind resident ones
+  static const int kByRegs[2][3][4] = {
+      // NTT =  2  5  7  9     (pooled staging)
+      {{5, 4, 3, 3}, {4, 3, 2, 2}, {3, 2, 2, 2}},
+      //                      (unpooled staging: more loader registers)
+      {{4, 3, 3, 2}, {3, 2, 2, 2}, {2, 1, 1, 1}}};
+  const int ntt_slot = best_ntt <= 2 ? 0 : (best_ntt <= 5 ? 1 : (best_ntt <= 7 ? 2 : 3));
+  const long by_regs = kByRegs[pool == 2 ? 0 : 1][mtf - 1][ntt_slot];
   if (resident > by_regs) resident = by_regs;
   if (resident < 1) resident = 1;
   long G = 256 * resident / ((long)plan->nchunks * kgroups);

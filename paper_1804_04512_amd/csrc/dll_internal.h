@@ -74,7 +74,7 @@ struct WgradPlan {
   int n_partials;        // per chunk: one block per workgroup (G)
 };
 
-bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, WgradPlan *plan);
+bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, int pool, WgradPlan *plan);
 hipError_t launch_wgrad(const WgradArgs &a, const WgradPlan &plan, hipStream_t stream);
 
 // dw = scale * (sum(pos partials) - sum(neg partials)); optional in-place theta += step * dw.
