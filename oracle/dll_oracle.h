@@ -68,6 +68,8 @@ void oracle_set_threads(int n);
   int PFX##softmax_ce(int B, int classes, const REAL *logits, const int *labels, REAL *loss,     \
                       REAL *prob, REAL *dlogits);                                                \
   int PFX##sgd(long count, REAL *theta, const REAL *g, REAL lr);                                 \
+  int PFX##sgd_momentum(long count, REAL *theta, REAL *vel, const REAL *g, REAL lr, REAL mu,     \
+                        REAL decay);                                                             \
   int PFX##crbm_cd1_step(const oracle_conv_desc *d, const REAL *v0, REAL *W, REAL *b_hid,        \
                          REAL *c_vis, const REAL *uniform, const REAL *h0_sample_in, REAL lr,    \
                          REAL *dW, REAL *db, REAL *dc, REAL *h0_prob, REAL *h0_sample, REAL *v1, \

@@ -192,6 +192,17 @@ def sgd(theta, g, lr, f64=False):
     return theta
 
 
+def sgd_momentum(theta, vel, g, lr, mu, decay, f64=False):
+    """In place on contiguous arrays of the storage dtype: v <- mu v - lr (g + decay theta); theta <- theta + v."""
+    assert theta.dtype == _dt(f64) and theta.flags.c_contiguous and vel.dtype == _dt(f64) and vel.flags.c_contiguous
+    g = _arr(g, f64)
+    fn = getattr(lib(), _pfx(f64) + "sgd_momentum")
+    real = C.c_double if f64 else C.c_float
+    fn.argtypes = [C.c_long, C.c_void_p, C.c_void_p, C.c_void_p, real, real, real]
+    _check(fn(theta.size, _p(theta), _p(vel), _p(g), lr, mu, decay), "sgd_momentum")
+    return theta, vel
+
+
 @dataclass
 class CrbmResult:
     dW: np.ndarray

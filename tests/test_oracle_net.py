@@ -334,3 +334,35 @@ def test_cnn_forward_matches_training_pass_logits():
     logits, _ = orc.cnn_forward(net, params, x)
     step = orc.cnn_train_step(net, [p.copy() for p in params], x, np.array([0, 1, 2]), lr=0.0)
     assert np.array_equal(logits, step.logits)
+
+
+# ---------------------------------------------------------------- momentum and weight decay
+
+def test_sgd_momentum_closed_forms():
+    r = np.random.default_rng(400)
+    th0, g = r.normal(size=50), r.normal(size=50)
+    # no momentum, no decay: exactly the plain update
+    a, va = th0.copy(), np.zeros(50)
+    orc.sgd_momentum(a, va, g, 0.1, 0.0, 0.0, f64=True)
+    b = orc.sgd(th0.copy(), g, 0.1, f64=True)
+    assert np.array_equal(a, b) and np.array_equal(va, -0.1 * g)
+    # constant gradient, n steps: v_n = -lr g (1 - mu^n)/(1 - mu), theta_n = theta_0 + sum of the v_k
+    lr, mu, n = 0.05, 0.9, 7
+    th, v = th0.copy(), np.zeros(50)
+    for _ in range(n):
+        orc.sgd_momentum(th, v, g, lr, mu, 0.0, f64=True)
+    geo = lambda k: (1 - mu ** k) / (1 - mu)
+    np.testing.assert_allclose(v, -lr * g * geo(n), rtol=1e-13)
+    np.testing.assert_allclose(th, th0 - lr * g * sum(geo(k) for k in range(1, n + 1)), rtol=1e-12, atol=1e-14)
+    # decay only, zero gradient: theta shrinks geometrically by (1 - lr decay) per step
+    th, v = th0.copy(), np.zeros(50)
+    for _ in range(5):
+        orc.sgd_momentum(th, v, np.zeros(50), 0.1, 0.0, 0.3, f64=True)
+    np.testing.assert_allclose(th, th0 * (1 - 0.1 * 0.3) ** 5, rtol=1e-13)
+    # one general step against the formula written out with numpy
+    th, v = th0.copy(), r.normal(size=50)
+    v_ref = 0.8 * v - 0.02 * (g + 0.01 * th)
+    th_ref = th + v_ref
+    orc.sgd_momentum(th, v, g, 0.02, 0.8, 0.01, f64=True)
+    np.testing.assert_allclose(v, v_ref, rtol=1e-14)
+    np.testing.assert_allclose(th, th_ref, rtol=1e-14)
