@@ -147,6 +147,20 @@ dll_status dll_cnn_train_step(const dll_net_desc *net, float *const *params, flo
                               float *logits, unsigned char *const *pool_idx, void *ws,
                               size_t ws_bytes, void *stream);
 
+/* The same step with momentum and weight decay (Section II names both as learning options,
+ * Section IV trains with momentum 0.9).  Reading taken here, the classical form, per parameter:
+ *   v <- momentum * v - lr * (g + weight_decay * theta);   theta <- theta + v
+ * with weight_decay applied to filters and dense weights only (0 for biases).
+ *   velocity  host array of device pointers, same order and shapes as params; required, updated
+ *             in place when lr != 0 (start from zeros)
+ * Everything else as in dll_cnn_train_step, which equals momentum = weight_decay = 0. */
+dll_status dll_cnn_train_step_momentum(const dll_net_desc *net, float *const *params,
+                                       float *const *velocity, float *const *grads, const float *x,
+                                       const int *labels, float lr, float momentum,
+                                       float weight_decay, float *loss, float *logits,
+                                       unsigned char *const *pool_idx, void *ws, size_t ws_bytes,
+                                       void *stream);
+
 /* Inference pass of the same network description (Sections IV-VI: the networks the paper times
  * end in a softmax layer): the convolution blocks, the dense layers (the last one without
  * activation) and the softmax of its outputs.  Nothing is kept for a backward pass: activations

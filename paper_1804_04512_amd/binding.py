@@ -21,7 +21,8 @@ LIB_PATH = os.path.join(_HERE, "libdll_conv.so")
 ACT = {"identity": 0, "sigmoid": 1, "relu": 2}
 SYMBOLS = ["dll_status_string", "dll_conv_workspace_bytes", "dll_conv_valid_fwd", "dll_conv_full_bwd",
            "dll_conv_valid_wgrad", "dll_crbm_workspace_bytes", "dll_crbm_cd1_step",
-           "dll_cnn_workspace_bytes", "dll_cnn_train_step", "dll_cnn_forward_workspace_bytes", "dll_cnn_forward"]
+           "dll_cnn_workspace_bytes", "dll_cnn_train_step", "dll_cnn_forward_workspace_bytes", "dll_cnn_forward",
+           "dll_cnn_train_step_momentum"]
 
 
 class DllError(RuntimeError):
@@ -69,6 +70,8 @@ def lib() -> C.CDLL:
         L.dll_cnn_workspace_bytes.restype = sz
         L.dll_cnn_workspace_bytes.argtypes = [C.POINTER(dll_net_desc)]
         L.dll_cnn_train_step.argtypes = [C.POINTER(dll_net_desc), vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, sz, vp]
+        L.dll_cnn_train_step_momentum.argtypes = [C.POINTER(dll_net_desc), vp, vp, vp, vp, vp, C.c_float, C.c_float, C.c_float,
+                                                  vp, vp, vp, vp, sz, vp]
         L.dll_cnn_forward_workspace_bytes.restype = sz
         L.dll_cnn_forward_workspace_bytes.argtypes = [C.POINTER(dll_net_desc)]
         L.dll_cnn_forward.argtypes = [C.POINTER(dll_net_desc), vp, vp, vp, vp, vp, sz, vp]
@@ -181,3 +184,11 @@ def dll_cnn_forward(net: NetHandle, params: List[torch.Tensor], x, logits=None, 
     pa = _ptr_array(params)
     _ok(lib().dll_cnn_forward(C.byref(net.desc), pa, _ptr(x), _ptr(logits), _ptr(prob), _ptr(ws),
                               0 if ws is None else ws.numel(), _stream(stream)), "dll_cnn_forward")
+
+
+def dll_cnn_train_step_momentum(net: NetHandle, params: List[torch.Tensor], velocity: List[torch.Tensor], grads, x, labels, lr,
+                                momentum, weight_decay, loss, logits=None, pool_idx=None, ws=None, stream=None) -> None:
+    pa, va, ga, ia = _ptr_array(params), _ptr_array(velocity), _ptr_array(grads), _ptr_array(pool_idx)
+    _ok(lib().dll_cnn_train_step_momentum(C.byref(net.desc), pa, va, ga, _ptr(x), _ptr(labels), C.c_float(lr),
+                                          C.c_float(momentum), C.c_float(weight_decay), _ptr(loss), _ptr(logits), ia, _ptr(ws),
+                                          0 if ws is None else ws.numel(), _stream(stream)), "dll_cnn_train_step_momentum")

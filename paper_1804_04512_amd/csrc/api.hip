@@ -355,9 +355,14 @@ size_t dll_cnn_workspace_bytes(const dll_net_desc *net) {
   return carve_net(net, lay, nullptr, &nb);
 }
 
-dll_status dll_cnn_train_step(const dll_net_desc *net, float *const *params, float *const *grads, const float *x,
-                              const int *labels, float lr, float *loss, float *logits, unsigned char *const *pool_idx,
-                              void *ws, size_t ws_bytes, void *stream) {
+}  // extern "C"
+
+namespace {
+
+// One training step; `velocity` (nullable) switches the updates to momentum + weight decay.
+dll_status run_cnn_step(const dll_net_desc *net, float *const *params, float *const *velocity, float *const *grads,
+                        const float *x, const int *labels, float lr, float mu, float decay, float *loss, float *logits,
+                        unsigned char *const *pool_idx, void *ws, size_t ws_bytes, void *stream) {
   NetLayout lay;
   dll_status st = check_net(net, &lay);
   if (st != DLL_OK) return st;
@@ -368,6 +373,10 @@ dll_status dll_cnn_train_step(const dll_net_desc *net, float *const *params, flo
     if (!params[p]) return DLL_ERR_NULL;
     if (misaligned(params[p]) || (grads && misaligned(grads[p]))) return DLL_ERR_SHAPE;
     if (grads && grads[p] == params[p]) return DLL_ERR_SHAPE;
+    if (velocity) {
+      if (!velocity[p]) return DLL_ERR_NULL;
+      if (misaligned(velocity[p]) || velocity[p] == params[p] || (grads && grads[p] == velocity[p])) return DLL_ERR_SHAPE;
+    }
   }
   if (misaligned(x) || misaligned(logits)) return DLL_ERR_SHAPE;
   NetBuffers nb;
@@ -443,14 +452,18 @@ dll_status dll_cnn_train_step(const dll_net_desc *net, float *const *params, flo
     h.A = gcur; h.a_m = 1; h.a_k = dd->out;
     h.B = nb.act[L + q]; h.b_k = dd->in; h.b_n = 1;
     h.Cout = grads ? grads[2 * (L + q)] : nullptr; h.c_m = dd->in; h.c_n = 1;
-    if (upd) { h.update = Wq; h.step = step; }
+    if (upd) {
+      h.update = Wq; h.step = step;
+      if (velocity) { h.vel = velocity[2 * (L + q)]; h.mu = mu; h.decay = decay; }
+    }
     h.split_k = 1;
     if (h.Cout || h.update)
       if ((st = dev(launch_gemm(h, s))) != DLL_OK) return st;
     float *gb = grads ? grads[2 * (L + q) + 1] : nullptr;
     if (gb || upd) {
       if (tail.n_colsum == StepTail::kMaxColsum && (st = flush_tail()) != DLL_OK) return st;
-      tail.colsum[tail.n_colsum++] = StepTail::Colsum{gcur, B, dd->out, gb, upd ? bq : nullptr, step};
+      tail.colsum[tail.n_colsum++] = StepTail::Colsum{gcur, B, dd->out, gb, upd ? bq : nullptr, step,
+                                                      (upd && velocity) ? velocity[2 * (L + q) + 1] : nullptr, mu};
     }
   }
   // ---- convolution backward: data gradient with the old filters, then the filter-gradient partial
@@ -473,7 +486,10 @@ dll_status dll_cnn_train_step(const dll_net_desc *net, float *const *params, flo
     r.pos = nb.cpartial[l]; r.scale = 1.0f;
     r.dw = grads ? grads[2 * l] : nullptr;
     r.db = grads ? grads[2 * l + 1] : nullptr;
-    if (upd) { r.w_update = params[2 * l]; r.b_update = params[2 * l + 1]; r.step = step; }
+    if (upd) {
+      r.w_update = params[2 * l]; r.b_update = params[2 * l + 1]; r.step = step;
+      if (velocity) { r.w_vel = velocity[2 * l]; r.b_vel = velocity[2 * l + 1]; r.mu = mu; r.w_decay = decay; }
+    }
     r.C = d->C; r.K = d->K; r.R = d->R; r.S = d->S;
     if (tail.n_reduce == StepTail::kMaxReduce && (st = flush_tail()) != DLL_OK) return st;
     tail.reduce[tail.n_reduce].a = r;
@@ -483,6 +499,26 @@ dll_status dll_cnn_train_step(const dll_net_desc *net, float *const *params, flo
   }
   if ((st = flush_tail()) != DLL_OK) return st;
   return DLL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+dll_status dll_cnn_train_step(const dll_net_desc *net, float *const *params, float *const *grads, const float *x,
+                              const int *labels, float lr, float *loss, float *logits, unsigned char *const *pool_idx,
+                              void *ws, size_t ws_bytes, void *stream) {
+  return run_cnn_step(net, params, nullptr, grads, x, labels, lr, 0.0f, 0.0f, loss, logits, pool_idx, ws, ws_bytes, stream);
+}
+
+dll_status dll_cnn_train_step_momentum(const dll_net_desc *net, float *const *params, float *const *velocity,
+                                       float *const *grads, const float *x, const int *labels, float lr, float momentum,
+                                       float weight_decay, float *loss, float *logits, unsigned char *const *pool_idx,
+                                       void *ws, size_t ws_bytes, void *stream) {
+  if (!velocity) return DLL_ERR_NULL;
+  if (!(momentum >= 0.0f) || !(weight_decay >= 0.0f)) return DLL_ERR_SHAPE;
+  return run_cnn_step(net, params, velocity, grads, x, labels, lr, momentum, weight_decay, loss, logits, pool_idx, ws,
+                      ws_bytes, stream);
 }
 
 size_t dll_cnn_forward_workspace_bytes(const dll_net_desc *net) {

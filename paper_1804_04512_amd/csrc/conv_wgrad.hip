@@ -554,13 +554,13 @@ __device__ __forceinline__ void wgrad_reduce_block(const WgradReduceArgs &a, con
       if (cl < plan.CC && ci < a.C && ko < a.K) {
         const long o = ((long)ko * a.C + ci) * RSf + rs;
         if (a.dw) a.dw[o] = gval;
-        if (a.w_update) a.w_update[o] += a.step * gval;
+        if (a.w_update) update_param(a.w_update + o, a.w_vel ? a.w_vel + o : nullptr, gval, a.step, a.mu, a.w_decay);
       }
     } else {
       const int k = (blk - nblk_dw) * 16 + tid;
       if (k < a.K) {
         if (a.db) a.db[k] = gval;
-        if (a.b_update) a.b_update[k] += a.step * gval;
+        if (a.b_update) update_param(a.b_update + k, a.b_vel ? a.b_vel + k : nullptr, gval, a.step, a.mu, 0.0f);
       }
     }
   }
@@ -596,7 +596,7 @@ __global__ __launch_bounds__(kThreads) void step_tail_kernel(const StepTailParam
     wgrad_reduce_block(p.t.reduce[j].a, p.t.reduce[j].plan, p.group_stride[j], p.kgroups[j], blk);
   } else if (j < p.t.n_reduce + p.t.n_colsum) {
     const StepTail::Colsum &c = p.t.colsum[j - p.t.n_reduce];
-    colsum_block(c.A, c.M, c.N, c.out, c.update, c.step, blk);
+    colsum_block(c.A, c.M, c.N, c.out, c.update, c.step, c.vel, c.mu, blk);
   } else {
     mean_block(p.t.rowloss, p.t.rows, p.t.loss);
   }

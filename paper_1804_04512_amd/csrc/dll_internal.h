@@ -16,6 +16,19 @@ enum { ACT_RELU_FLAGGED = 3 };
 // forward pass of a ReLU layer also sets kIdxInactive where the pooled output is zero.
 constexpr unsigned char kIdxPosMask = 3, kIdxInactive = 4;
 
+// In-place parameter update, shared by every kernel that produces a gradient g of a parameter theta:
+//   v == NULL:  theta += step * g                                    (plain descent, step = -lr)
+//   v != NULL:  v = mu * v + step * (g + decay * theta);  theta += v  (momentum and weight decay)
+__host__ __device__ __forceinline__ void update_param(float *theta, float *v, float g, float step, float mu, float decay) {
+  if (v) {
+    const float nv = mu * (*v) + step * (g + decay * (*theta));
+    *v = nv;
+    *theta += nv;
+  } else {
+    *theta += step * g;
+  }
+}
+
 // ---------------------------------------------------------------------------------------
 // Forward-form implicit-GEMM convolution engine (fp32 MFMA 16x16x4).
 //   out[n,ko,i,j] = epilogue( sum_{ci,r,s} srcpad[n,ci,i+r,j+s] * wgt(ko,ci,r,s) )
@@ -87,6 +100,8 @@ struct WgradReduceArgs {
   float *w_update = nullptr;   // nullable: w_update += step * dw
   float *b_update = nullptr;   // nullable
   float step = 0.0f;
+  float *w_vel = nullptr, *b_vel = nullptr;   // nullable: momentum buffers of the filters and biases
+  float mu = 0.0f, w_decay = 0.0f;            // momentum; weight decay (filters only)
   int C = 0, K = 0, R = 0, S = 0;
 };
 hipError_t launch_wgrad_reduce(const WgradReduceArgs &a, const WgradPlan &plan, hipStream_t stream);
@@ -105,6 +120,7 @@ struct GemmArgs {
   // backward: the data gradient leaves as dz of the layer below, dz = dh * act'(h))
   const float *C_ref = nullptr; int c_ref_act = ACT_IDENTITY;
   float *update = nullptr; float step = 0.0f;        // nullable: update(m,n) += step * C(m,n), same strides as Cout
+  float *vel = nullptr; float mu = 0.0f, decay = 0.0f; // nullable momentum buffer of `update` (see update_param)
   int split_k = 1;
   float *partial = nullptr;                          // split_k * M * N floats when split_k > 1
   // split_k > 1 only: leave the partials as they are; the consumer adds them (in split order,
@@ -116,7 +132,7 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream);
 
 // Column sums out[n] = sum_m A(m,n) of a row-major [M][N] array; optional update.
 hipError_t launch_colsum(const float *A, int M, int N, float *out,
-                         float *update, float step, hipStream_t stream);
+                         float *update, float step, float *vel, float mu, hipStream_t stream);
 
 // Softmax cross-entropy over rows; loss = mean; dlogits = (p - onehot)/B.  rowloss: B floats scratch.
 // With partial != NULL the logits are first formed from split_k partial products [z][B][classes]
@@ -145,7 +161,7 @@ struct StepTail {
   static constexpr int kMaxReduce = 8, kMaxColsum = 4;
   int n_reduce = 0, n_colsum = 0;
   struct Reduce { WgradReduceArgs a; WgradPlan plan; } reduce[kMaxReduce];
-  struct Colsum { const float *A; int M, N; float *out, *update; float step; } colsum[kMaxColsum];
+  struct Colsum { const float *A; int M, N; float *out, *update; float step; float *vel; float mu; } colsum[kMaxColsum];
   const float *rowloss = nullptr; int rows = 0; float *loss = nullptr;   // optional: *loss = mean(rowloss)
 };
 hipError_t launch_step_tail(const StepTail &t, hipStream_t stream);

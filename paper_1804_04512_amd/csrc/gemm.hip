@@ -245,15 +245,19 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(const GemmParams p) {
         if (a.Cout) *reinterpret_cast<float4 *>(a.Cout + o) = make_float4(c[0], c[1], c[2], c[3]);
         if (a.update) {
           float4 u = upd[i][j];   // requested before the epilogue loop, all eight at once
-          u.x += a.step * c[0]; u.y += a.step * c[1]; u.z += a.step * c[2]; u.w += a.step * c[3];
+          float4 vv = a.vel ? *reinterpret_cast<const float4 *>(a.vel + o) : make_float4(0.f, 0.f, 0.f, 0.f);
+          float *vp = a.vel ? &vv.x : nullptr;
+          update_param(&u.x, vp, c[0], a.step, a.mu, a.decay); update_param(&u.y, vp ? vp + 1 : nullptr, c[1], a.step, a.mu, a.decay);
+          update_param(&u.z, vp ? vp + 2 : nullptr, c[2], a.step, a.mu, a.decay); update_param(&u.w, vp ? vp + 3 : nullptr, c[3], a.step, a.mu, a.decay);
           *reinterpret_cast<float4 *>(a.update + o) = u;
+          if (a.vel) *reinterpret_cast<float4 *>(a.vel + o) = vv;
         }
       } else {
 #pragma unroll
         for (int v = 0; v < 4; ++v)
           if (n + v < a.N) {
             if (a.Cout) a.Cout[o + v * a.c_n] = c[v];
-            if (a.update) a.update[o + v * a.c_n] += a.step * c[v];
+            if (a.update) update_param(a.update + o + v * a.c_n, a.vel ? a.vel + o + v * a.c_n : nullptr, c[v], a.step, a.mu, a.decay);
           }
       }
     }
@@ -498,7 +502,14 @@ __global__ __launch_bounds__(kThreads, 3) void gemm_fast_kernel(const GemmParams
           if (a.Cout) *reinterpret_cast<float4 *>(a.Cout + o) = make_float4(c[0], c[1], c[2], c[3]);
           if (a.update) {
             float4 w4 = upd[i][j];
-            w4.x += a.step * c[0]; w4.y += a.step * c[1]; w4.z += a.step * c[2]; w4.w += a.step * c[3];
+            if (a.vel) {   // momentum: the velocity tile is read here (the plain update stays the fast path)
+              float4 vv = *reinterpret_cast<const float4 *>(a.vel + o);
+              update_param(&w4.x, &vv.x, c[0], a.step, a.mu, a.decay); update_param(&w4.y, &vv.y, c[1], a.step, a.mu, a.decay);
+              update_param(&w4.z, &vv.z, c[2], a.step, a.mu, a.decay); update_param(&w4.w, &vv.w, c[3], a.step, a.mu, a.decay);
+              *reinterpret_cast<float4 *>(a.vel + o) = vv;
+            } else {
+              w4.x += a.step * c[0]; w4.y += a.step * c[1]; w4.z += a.step * c[2]; w4.w += a.step * c[3];
+            }
             *reinterpret_cast<float4 *>(a.update + o) = w4;
           }
         } else {
@@ -506,7 +517,7 @@ __global__ __launch_bounds__(kThreads, 3) void gemm_fast_kernel(const GemmParams
           for (int v = 0; v < 4; ++v)
             if (n + v < a.N) {
               if (a.Cout) a.Cout[o + v * a.c_n] = c[v];
-              if (a.update) a.update[o + v * a.c_n] += a.step * c[v];
+              if (a.update) update_param(a.update + o + v * a.c_n, a.vel ? a.vel + o + v * a.c_n : nullptr, c[v], a.step, a.mu, a.decay);
             }
         }
       }
@@ -561,13 +572,13 @@ __global__ __launch_bounds__(kThreads) void gemm_splitk_reduce_kernel(const Gemm
     const long o = (long)m * a.c_m + (long)n * a.c_n;
     if (a.C_ref) c *= act_deriv(a.c_ref_act, a.C_ref[o]);
     if (a.Cout) a.Cout[o] = c;
-    if (a.update) a.update[o] += a.step * c;
+    if (a.update) update_param(a.update + o, a.vel ? a.vel + o : nullptr, c, a.step, a.mu, a.decay);
   }
 }
 
 __global__ __launch_bounds__(kThreads) void colsum_kernel(const float *A, int M, int N, float *out, float *update,
-                                                         float step) {
-  colsum_block(A, M, N, out, update, step, blockIdx.x);
+                                                         float step, float *vel, float mu) {
+  colsum_block(A, M, N, out, update, step, vel, mu, blockIdx.x);
 }
 
 // One workgroup per sample: p = softmax(logits) with the row maximum subtracted,
@@ -685,7 +696,7 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream) {
   // 16-byte loads need an aligned base and a leading stride of whole vectors
   p.a_vec = al16(a.A) && ((a.a_k == 1 ? a.a_m : a.a_k) % 4 == 0) && (a.a_k == 1 || a.a_m == 1);
   p.b_vec = al16(a.B) && ((a.b_k == 1 ? a.b_n : a.b_k) % 4 == 0) && (a.b_k == 1 || a.b_n == 1);
-  p.c_vec = a.c_n == 1 && a.c_m % 4 == 0 && (!a.Cout || al16(a.Cout)) && (!a.update || al16(a.update));
+  p.c_vec = a.c_n == 1 && a.c_m % 4 == 0 && (!a.Cout || al16(a.Cout)) && (!a.update || al16(a.update)) && (!a.vel || al16(a.vel));
   dim3 grid((a.N + BN - 1) / BN, (a.M + BM - 1) / BM, p.a.split_k);
   // whole 16-byte groups along each operand's contiguous axis, the k ranges of the splits start
   // on multiples of 32, and every operand element lies within 4 GiB of its base (32-bit byte
@@ -720,9 +731,10 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream) {
   return e;
 }
 
-hipError_t launch_colsum(const float *A, int M, int N, float *out, float *update, float step, hipStream_t stream) {
+hipError_t launch_colsum(const float *A, int M, int N, float *out, float *update, float step, float *vel, float mu,
+                         hipStream_t stream) {
   hipLaunchKernelGGL(colsum_kernel, dim3((N + kColsumCols - 1) / kColsumCols), dim3(kThreads), 0, stream, A, M, N, out, update,
-                     step);
+                     step, vel, mu);
   return hipGetLastError();
 }
 

@@ -13,7 +13,8 @@ constexpr int kColsumCols = 16, kColsumSlices = kSmallThreads / kColsumCols;
 
 // out[n] = sum_m A[m][n]: 16 columns per workgroup, 16 row slices added in a fixed order
 // (small inputs: many short independent load chains beat few long ones).
-__device__ __forceinline__ void colsum_block(const float *A, int M, int N, float *out, float *update, float step, int blk) {
+__device__ __forceinline__ void colsum_block(const float *A, int M, int N, float *out, float *update, float step, float *vel,
+                                             float mu, int blk) {
   __shared__ float part[kColsumSlices][kColsumCols + 1];
   const int col = threadIdx.x % kColsumCols, slice = threadIdx.x / kColsumCols;
   const int n = blk * kColsumCols + col;
@@ -34,7 +35,7 @@ __device__ __forceinline__ void colsum_block(const float *A, int M, int N, float
     }
     s = (q[0] + q[1]) + (q[2] + q[3]);
     if (out) out[n] = s;
-    if (update) update[n] += step * s;
+    if (update) update_param(update + n, vel ? vel + n : nullptr, s, step, mu, 0.0f);
   }
 }
 

@@ -71,6 +71,7 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.dll_crbm_cd1_step(C.byref(d), a, b, c, e, None, None, 0.0, *([a] * 8), None, 0, None) == 1   # no uniforms
     assert L.dll_cnn_train_step(None, None, None, None, None, 0.0, None, None, None, None, 0, None) == 1
     assert L.dll_cnn_forward(None, None, None, None, None, None, 0, None) == 1
+    assert L.dll_cnn_train_step_momentum(None, None, None, None, None, None, 0.0, 0.0, 0.0, None, None, None, None, 0, None) == 1
     assert L.dll_cnn_forward_workspace_bytes(None) == 0
 
 

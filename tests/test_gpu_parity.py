@@ -322,3 +322,38 @@ def test_forward_pass_logits_equal_training_pass_logits():
     assert np.array_equal(host(only_p), pg)
     with pytest.raises(B.DllError):
         B.dll_cnn_forward(net, params, dev(w.x), None, None, ws)
+
+
+# ---------------------------------------------------------------- momentum and weight decay
+
+def test_momentum_step_matches_oracle():
+    """One step with momentum 0.9, weight decay 1e-3 and a non-zero velocity: gradients, new
+    velocities and parameter changes against the oracle's gradients fed through its own
+    momentum update (decay on weights only).  Zero momentum/decay/velocity equals the plain step."""
+    w = wl.config5(batch=6, image=64, hidden=256, classes=100)
+    lr, mu, decay = 0.01, 0.9, 1e-3
+    r = np.random.default_rng(77)
+    vel0 = [(r.standard_normal(p.shape) * 0.01 * max(float(np.abs(p).max()), 1e-3)).astype(np.float32) for p in w.params]
+    net = B.net_desc(w.conv, w.dense, w.classes)
+    params, vel = [dev(p) for p in w.params], [dev(v) for v in vel0]
+    grads = [torch.full_like(p, float("nan")) for p in params]
+    idx = [torch.full(c.y_shape, 255, dtype=torch.uint8, device="cuda") for c in w.conv]
+    loss = torch.full((1,), float("nan"), device="cuda")
+    ws = B.workspace(B.dll_cnn_workspace_bytes(net))
+    B.dll_cnn_train_step_momentum(net, params, vel, grads, dev(w.x), dev(w.labels), lr, mu, decay, loss, None, idx, ws)
+    o = orc.cnn_train_step(onet(w), w.clone_params(), w.x, w.labels, 0.0, pool_idx_in=[host(i) & 3 for i in idx])
+    assert max_rel_err(np.array([host(loss)[0]]), np.array([o.loss])) <= TOL_FWD
+    for p, (old, v0, og) in enumerate(zip(w.params, vel0, o.grads)):
+        th, v = old.copy(), v0.copy()
+        orc.sgd_momentum(th, v, og, lr, mu, decay if p % 2 == 0 else 0.0)
+        assert max_rel_err(host(grads[p]), og) <= TOL_GRAD, f"gradient of parameter {p}"
+        assert max_rel_err(host(vel[p]), v) <= TOL_GRAD, f"velocity of parameter {p}"
+        assert max_rel_err(host(params[p]) - old, th - old) <= TOL_GRAD, f"update of parameter {p}"
+    # momentum 0, decay 0, zero velocity: the plain step up to the rounding of one product (the plain
+    # update is a single fused multiply-add, the momentum form rounds the velocity first)
+    pa, pb = [dev(p) for p in w.params], [dev(p) for p in w.params]
+    vz = [torch.zeros_like(p) for p in pa]
+    B.dll_cnn_train_step_momentum(net, pa, vz, None, dev(w.x), dev(w.labels), lr, 0.0, 0.0, loss, None, None, ws)
+    B.dll_cnn_train_step(net, pb, None, dev(w.x), dev(w.labels), lr, loss, None, None, ws)
+    for a_, b_ in zip(pa, pb):
+        assert max_rel_err(host(a_), host(b_)) <= 2e-7   # one ulp of the parameter itself
