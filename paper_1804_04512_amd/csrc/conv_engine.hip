@@ -839,10 +839,12 @@ hipError_t launch_3x3(const ConvEngineArgs &a, hipStream_t stream) {
 }  // namespace
 
 hipError_t launch_conv_engine(const ConvEngineArgs &a, hipStream_t stream) {
-  // shallow maps (<= 8 pre-pool rows) use the 8-row tile; 16 output channels per N-tile
-  const bool small = a.Hout <= 8;
+  // 16 output channels per N-tile.  The generic kernel uses the 8-row tile for shallow maps
+  // (<= 8 pre-pool rows) and whenever 16-row tiles would leave CUs without a workgroup.
   const int nt = a.Kout <= 16 ? 1 : (a.Kout <= 32 ? 2 : 3);
-  if (!small && conv3x3c16_applies(a)) {
+  const long tiles16 = (long)a.N * ((a.Wout + kTileW - 1) / kTileW) * ((a.Hout + 15) / 16) * ((a.Kout + nt * 16 - 1) / (nt * 16));
+  const bool small = a.Hout <= 8 || tiles16 < 512;
+  if (a.Hout > 8 && conv3x3c16_applies(a)) {
     // 16 output channels: 4 waves x 2 row pairs; 32: 8 waves x 1 row pair (more waves hide the
     // longer per-step operand traffic better than more accumulators do)
     if (a.Cin % 16 != 0) {
