@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--batch", type=int, default=None, help="override the batch size (inspection only)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
-    ap.add_argument("--cpu-batch", type=int, default=32)
+    ap.add_argument("--cpu-batch", type=int, default=128, help="batch of the CPU oracle leg (config 5 and --mode infer)")
     ap.add_argument("--mode", choices=["train", "infer"], default="train",
                     help="infer: time dll_cnn_forward on the paper's ImageNet network (batch 128 of 3x256x256) instead of the training step")
     ap.add_argument("--pmc-calib", action="store_true",
@@ -119,31 +119,41 @@ def conv_pass_table(B, wl_cnn, dev_params, x_dev, iters):
     return table
 
 
-def cpu_baseline(cfg: int, cpu_batch: int):
+def cpu_baseline(cfg: int, cpu_batch: int, budget_s: float = 10.0, max_reps: int = 100):
+    """The oracle as it stands on the host cores: whole steps of the same workload, repeated until
+    about `budget_s` seconds of CPU work are done (at least one step)."""
     from oracle import oracle as orc
     from paper_1804_04512_amd import workloads as wl
     act = {"identity": 0, "sigmoid": 1, "relu": 2}
     w = wl.ALL[cfg](cpu_batch)
-    t0 = time.perf_counter()
     if isinstance(w, wl.CnnWorkload):
         net = orc.Net([orc.conv_desc(c.N, c.C, c.H, c.W, c.K, c.R, c.S, c.pad, act[c.act], c.pool) for c in w.conv],
                       [(d.in_, d.out, act[d.act]) for d in w.dense], w.classes)
-        orc.cnn_train_step(net, w.clone_params(), w.x, w.labels, w.lr)
+        step = lambda: orc.cnn_train_step(net, w.clone_params(), w.x, w.labels, w.lr)
         n = w.batch
     elif isinstance(w, wl.CrbmWorkload):
         c = w.conv
-        orc.crbm_cd1_step(orc.conv_desc(c.N, c.C, c.H, c.W, c.K, c.R, c.S), w.v0, w.W.copy(), w.b.copy(), w.c.copy(), w.u, lr=w.lr)
+        d = orc.conv_desc(c.N, c.C, c.H, c.W, c.K, c.R, c.S)
+        step = lambda: orc.crbm_cd1_step(d, w.v0, w.W.copy(), w.b.copy(), w.c.copy(), w.u, lr=w.lr)
         n = c.N
     else:
         c = w.conv
         d = orc.conv_desc(c.N, c.C, c.H, c.W, c.K, c.R, c.S, c.pad, act[c.act], c.pool)
-        y, idx = orc.conv_valid_fwd(d, w.x, w.w, w.bias)
-        orc.conv_full_bwd(d, w.dy, y, idx, w.w)
-        orc.conv_valid_wgrad(d, w.x, w.dy, y, idx)
+
+        def step():
+            y, idx = orc.conv_valid_fwd(d, w.x, w.w, w.bias)
+            orc.conv_full_bwd(d, w.dy, y, idx, w.w)
+            orc.conv_valid_wgrad(d, w.x, w.dy, y, idx)
         n = c.N
-    dt = time.perf_counter() - t0
-    return dict(value=w.flop() / dt / 1e9, unit="GFLOP/s", images_per_s=n / dt, seconds=dt, cores=orc.max_threads(),
-                kind="oracle", sample=f"one step of config {cfg} at batch {n} (same layer shapes), fp64 accumulation, plain loops")
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        step()
+        reps += 1
+        dt = time.perf_counter() - t0
+        if dt >= budget_s or reps >= max_reps:
+            break
+    return dict(value=w.flop() * reps / dt / 1e9, unit="GFLOP/s", images_per_s=n * reps / dt, seconds=dt, cores=orc.max_threads(),
+                kind="oracle", sample=f"{reps} step(s) of config {cfg} at batch {n} (same layer shapes), fp64 accumulation, plain loops")
 
 
 def infer_line(args, B, wl, torch):
