@@ -7,8 +7,9 @@
  * yields the filter gradient, the dense-layer matrix products, the activation
  * functions, 2x2 max pooling, softmax cross-entropy, mini-batch gradient descent
  * (Section II) and the CD-1 step of a convolutional RBM (Section II, CRBM with
- * Contrastive Divergence).  The paper gives no formulas; every function states the
- * textbook definition it writes out.  Sums are accumulated in double and rounded to
+ * Contrastive Divergence; binary or Gaussian visible units; independent hidden units or
+ * probabilistic max pooling) and of a fully-connected RBM.  The paper gives no formulas;
+ * every function states the textbook definition it writes out.  Sums are accumulated in double and rounded to
  * the storage type once, on store.  Nothing here is blocked, fused or reordered,
  * and nothing here is used by, or shares code with, the GPU library.
  *
@@ -49,6 +50,8 @@ typedef struct {
   int n_dense;
   const oracle_dense_desc *dense; /* last one: identity, followed by softmax-CE */
   int classes;
+  int batch; /* minibatch size of a network without convolution layers (n_conv == 0: a
+                fully-connected network, x is [batch][dense[0].in]); ignored otherwise */
 } oracle_net_desc;
 
 int oracle_max_threads(void);
@@ -74,6 +77,15 @@ void oracle_set_threads(int n);
                          REAL *c_vis, const REAL *uniform, const REAL *h0_sample_in, REAL lr,    \
                          REAL *dW, REAL *db, REAL *dc, REAL *h0_prob, REAL *h0_sample, REAL *v1, \
                          REAL *h1_prob, REAL *recon_mse);                                        \
+  int PFX##crbm_cd1_step_units(const oracle_conv_desc *d, int visible, int hidden_pool,          \
+                               const REAL *v0, REAL *W, REAL *b_hid, REAL *c_vis,                \
+                               const REAL *uniform, const REAL *h0_sample_in, REAL lr, REAL *dW, \
+                               REAL *db, REAL *dc, REAL *h0_prob, REAL *h0_sample,               \
+                               REAL *pool_prob, REAL *v1, REAL *h1_prob, REAL *recon_mse);       \
+  int PFX##rbm_cd1_step(int B, int nv, int nh, int visible, const REAL *v0, REAL *W,             \
+                        REAL *b_hid, REAL *c_vis, const REAL *uniform, const REAL *h0_sample_in, \
+                        REAL lr, REAL *dW, REAL *db, REAL *dc, REAL *h0_prob, REAL *h0_sample,   \
+                        REAL *v1, REAL *h1_prob, REAL *recon_mse);                               \
   int PFX##cnn_train_step(const oracle_net_desc *net, REAL *const *params, REAL *const *grads,   \
                           const REAL *x, const int *labels, REAL lr, REAL *loss, REAL *logits,   \
                           const unsigned char *const *pool_idx_in, unsigned char *const *pool_idx_out); \

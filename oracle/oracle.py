@@ -54,7 +54,7 @@ class DenseDesc(C.Structure):
 
 class NetDesc(C.Structure):
     _fields_ = [("n_conv", C.c_int), ("conv", C.POINTER(ConvDesc)), ("n_dense", C.c_int),
-                ("dense", C.POINTER(DenseDesc)), ("classes", C.c_int)]
+                ("dense", C.POINTER(DenseDesc)), ("classes", C.c_int), ("batch", C.c_int)]
 
 
 def conv_desc(N, C_, H, W, K, R, S, pad=0, act=ACT_IDENTITY, pool=1) -> ConvDesc:
@@ -213,6 +213,61 @@ class CrbmResult:
     v1: np.ndarray
     h1_prob: np.ndarray
     recon_mse: float
+    pool_prob: Optional[np.ndarray] = None
+
+
+VIS_BINARY, VIS_GAUSSIAN = 0, 1
+
+
+def crbm_cd1_step_units(d: ConvDesc, visible, hidden_pool, v0, W, b_hid, c_vis, uniform=None,
+                        h0_sample_in=None, lr=0.0, f64=False) -> CrbmResult:
+    """CD-1 step with a choice of visible unit (VIS_*) and of hidden layer (hidden_pool 1:
+    independent units; 2: probabilistic max pooling, uniform is then one number per 2x2 block).
+    W, b_hid, c_vis are updated IN PLACE when lr != 0 (pass arrays of the storage dtype)."""
+    dt = _dt(f64)
+    for t in (W, b_hid, c_vis):
+        assert t.dtype == dt and t.flags.c_contiguous
+    v0, uniform, h0_sample_in = _arr(v0, f64), _arr(uniform, f64), _arr(h0_sample_in, f64)
+    hs = (d.N, d.K, d.Ho, d.Wo)
+    if uniform is not None:
+        assert uniform.shape == (hs if hidden_pool == 1 else (d.N, d.K, d.Ho // 2, d.Wo // 2))
+    res = CrbmResult(np.empty(W.shape, dt), np.empty((d.K,), dt), np.empty((d.C,), dt),
+                     np.empty(hs, dt), np.empty(hs, dt), np.empty(v0.shape, dt), np.empty(hs, dt), 0.0)
+    if hidden_pool == 2:
+        res.pool_prob = np.empty((d.N, d.K, d.Ho // 2, d.Wo // 2), dt)
+    mse = np.empty((1,), dt)
+    fn = getattr(lib(), _pfx(f64) + "crbm_cd1_step_units")
+    real = C.c_double if f64 else C.c_float
+    fn.argtypes = [C.POINTER(ConvDesc), C.c_int, C.c_int] + [C.c_void_p] * 6 + [real] + [C.c_void_p] * 9
+    _check(fn(C.byref(d), visible, hidden_pool, _p(v0), _p(W), _p(b_hid), _p(c_vis), _p(uniform),
+              _p(h0_sample_in), lr, _p(res.dW), _p(res.db), _p(res.dc), _p(res.h0_prob),
+              _p(res.h0_sample), _p(res.pool_prob), _p(res.v1), _p(res.h1_prob), _p(mse)),
+           "crbm_cd1_step_units")
+    res.recon_mse = float(mse[0])
+    return res
+
+
+def rbm_cd1_step(B, nv, nh, visible, v0, W, b_hid, c_vis, uniform=None, h0_sample_in=None, lr=0.0,
+                 f64=False) -> CrbmResult:
+    """CD-1 step of a fully-connected RBM: v0 [B, nv], W [nh, nv], uniform [B, nh].
+    W, b_hid, c_vis are updated IN PLACE when lr != 0."""
+    dt = _dt(f64)
+    for t in (W, b_hid, c_vis):
+        assert t.dtype == dt and t.flags.c_contiguous
+    v0, uniform, h0_sample_in = _arr(v0, f64), _arr(uniform, f64), _arr(h0_sample_in, f64)
+    assert v0.shape == (B, nv) and W.shape == (nh, nv) and b_hid.shape == (nh,) and c_vis.shape == (nv,)
+    res = CrbmResult(np.empty((nh, nv), dt), np.empty((nh,), dt), np.empty((nv,), dt),
+                     np.empty((B, nh), dt), np.empty((B, nh), dt), np.empty((B, nv), dt),
+                     np.empty((B, nh), dt), 0.0)
+    mse = np.empty((1,), dt)
+    fn = getattr(lib(), _pfx(f64) + "rbm_cd1_step")
+    real = C.c_double if f64 else C.c_float
+    fn.argtypes = [C.c_int] * 4 + [C.c_void_p] * 6 + [real] + [C.c_void_p] * 8
+    _check(fn(B, nv, nh, visible, _p(v0), _p(W), _p(b_hid), _p(c_vis), _p(uniform), _p(h0_sample_in),
+              lr, _p(res.dW), _p(res.db), _p(res.dc), _p(res.h0_prob), _p(res.h0_sample), _p(res.v1),
+              _p(res.h1_prob), _p(mse)), "rbm_cd1_step")
+    res.recon_mse = float(mse[0])
+    return res
 
 
 def crbm_cd1_step(d: ConvDesc, v0, W, b_hid, c_vis, uniform=None, h0_sample_in=None, lr=0.0,
@@ -238,10 +293,16 @@ def crbm_cd1_step(d: ConvDesc, v0, W, b_hid, c_vis, uniform=None, h0_sample_in=N
 
 @dataclass
 class Net:
-    """A CNN: conv descriptors, then (in, out, act) dense layers, the last one feeding softmax-CE."""
+    """A CNN: conv descriptors, then (in, out, act) dense layers, the last one feeding softmax-CE.
+    With no conv descriptors it is a fully-connected network on [batch, in] inputs."""
     conv: Sequence[ConvDesc]
     dense: Sequence[tuple]
     classes: int
+    batch: int = 0
+
+    @property
+    def B(self):
+        return self.conv[0].N if len(self.conv) else self.batch
 
     def param_shapes(self):
         shapes = []
@@ -270,10 +331,10 @@ def cnn_train_step(net: Net, params, x, labels, lr=0.0, pool_idx_in=None, f64=Fa
     L = len(net.conv)
     convs = (ConvDesc * L)(*net.conv)
     denses = (DenseDesc * len(net.dense))(*[DenseDesc(i, o, a) for (i, o, a) in net.dense])
-    nd = NetDesc(L, convs, len(net.dense), denses, net.classes)
+    nd = NetDesc(L, convs, len(net.dense), denses, net.classes, net.batch)
     x = _arr(x, f64)
     labels = np.ascontiguousarray(labels, dtype=np.int32)
-    B = net.conv[0].N
+    B = net.B
     grads = [np.empty(s, dt) for s in shapes]
     idx_out = [np.zeros(d.out_shape, np.uint8) for d in net.conv]
     logits = np.empty((B, net.classes), dt)
@@ -306,9 +367,9 @@ def cnn_forward(net: Net, params, x, f64=False):
     L = len(net.conv)
     convs = (ConvDesc * L)(*net.conv)
     denses = (DenseDesc * len(net.dense))(*[DenseDesc(i, o, a) for (i, o, a) in net.dense])
-    nd = NetDesc(L, convs, len(net.dense), denses, net.classes)
+    nd = NetDesc(L, convs, len(net.dense), denses, net.classes, net.batch)
     x = _arr(x, f64)
-    B = net.conv[0].N
+    B = net.B
     logits = np.empty((B, net.classes), dt)
     prob = np.empty((B, net.classes), dt)
     PP = C.c_void_p * len(shapes)
