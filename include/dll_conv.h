@@ -68,14 +68,21 @@ typedef struct {
 
 /* A CNN: n_conv convolution layers (all with the same N, each consuming the previous
  * one's output), flattened NCHW row-major into n_dense dense layers; the last dense layer
- * is linear (its `act` is ignored) and feeds a softmax cross-entropy over `classes`. */
+ * is linear (its `act` is ignored) and feeds a softmax cross-entropy over `classes`.
+ * n_conv may be 0: then the network is fully connected (Section IV-A), its input x is
+ * [batch][dense[0].in] and `batch` gives the mini-batch size; with n_conv > 0 `batch` is
+ * ignored (the batch is conv[0].N) and `conv` must not be NULL. */
 typedef struct {
   int n_conv;
   const dll_conv_desc *conv; /* host pointer */
   int n_dense;
   const dll_dense_desc *dense; /* host pointer */
   int classes;
+  int batch;
 } dll_net_desc;
+
+/* Visible unit types of the RBM steps (Section II). */
+typedef enum { DLL_VISIBLE_BINARY = 0, DLL_VISIBLE_GAUSSIAN = 1 } dll_visible_unit;
 
 const char *dll_status_string(dll_status s);
 
@@ -127,6 +134,46 @@ dll_status dll_crbm_cd1_step(const dll_conv_desc *d, const float *v0, float *W, 
                              float lr, float *dW, float *db, float *dc, float *h0_prob,
                              float *h0_sample, float *v1, float *h1_prob, float *recon_mse,
                              void *ws, size_t ws_bytes, void *stream);
+
+/* The CD-1 step with a choice of visible unit and of hidden layer (Section II: the RBM's unit
+ * types; the CRBM's second version with probabilistic max pooling).  Everything not said here
+ * is as in dll_crbm_cd1_step, which is this call with (DLL_VISIBLE_BINARY, hidden_pool 1).
+ *   visible  DLL_VISIBLE_BINARY:   v1 = sigmoid(c_vis[ch] + full(h0s, W))
+ *            DLL_VISIBLE_GAUSSIAN: v1 = c_vis[ch] + full(h0s, W)   (unit variance; the mean)
+ *   hidden_pool 1: independent binary hidden units, uniform [N][K][Ho][Wo]
+ *   hidden_pool 2: probabilistic max pooling over 2x2 blocks (Ho and Wo even, else
+ *            DLL_ERR_SHAPE): with I = b_hid[k] + valid(v, W), P(h_i = 1) = exp(I_i) /
+ *            (1 + sum over the block of exp(I_j)); at most one unit of a block is on.
+ *            uniform [N][K][Ho/2][Wo/2] holds one number u per block: with the block's
+ *            probabilities q0..q3 (order 2a+b) and fp32 running sums s_i = s_(i-1) + q_i,
+ *            unit i is on iff s_(i-1) <= u < s_i, none when u >= s_3.
+ *            pool_prob (nullable; must be NULL when hidden_pool is 1) [N][K][Ho/2][Wo/2]
+ *            receives P(pooling unit on | v0) = q0 + q1 + q2 + q3. */
+dll_status dll_crbm_cd1_step_units(const dll_conv_desc *d, int visible, int hidden_pool,
+                                   const float *v0, float *W, float *b_hid, float *c_vis,
+                                   const float *uniform, const float *h0_sample_in, float lr,
+                                   float *dW, float *db, float *dc, float *h0_prob,
+                                   float *h0_sample, float *pool_prob, float *v1, float *h1_prob,
+                                   float *recon_mse, void *ws, size_t ws_bytes, void *stream);
+
+/* One CD-1 step of a fully-connected RBM (Section II: RBM trained with Contrastive
+ * Divergence; Section II-A: every dense product is one matrix-matrix multiplication).
+ *   v0 [batch][n_vis], W [n_hid][n_vis], b_hid [n_hid], c_vis [n_vis], uniform [batch][n_hid]
+ *   h0p = sigmoid(b_hid + v0 W^T);  h0s = 1[uniform < h0p]  (or h0_sample_in)
+ *   v1  = sigmoid(c_vis + h0s W)  (DLL_VISIBLE_BINARY)  or  c_vis + h0s W  (DLL_VISIBLE_GAUSSIAN)
+ *   h1p = sigmoid(b_hid + v1 W^T)
+ *   dW = (h0p^T v0 - h1p^T v1) / batch;  db = colsum(h0p - h1p) / batch;
+ *   dc = colsum(v0 - v1) / batch;  recon_mse = mean((v0 - v1)^2)
+ *   lr != 0:  W += lr*dW, b_hid += lr*db, c_vis += lr*dc   (after all gradients are formed)
+ * All pointers are device pointers, 16-byte aligned.  dW, db, dc are required; h0_prob,
+ * h0_sample, v1, h1_prob [same shapes as above] and recon_mse (device scalar) may be NULL.
+ * Returns DLL_ERR_WORKSPACE when ws is smaller than dll_rbm_workspace_bytes says. */
+size_t dll_rbm_workspace_bytes(int batch, int n_vis, int n_hid);
+dll_status dll_rbm_cd1_step(int batch, int n_vis, int n_hid, int visible, const float *v0,
+                            float *W, float *b_hid, float *c_vis, const float *uniform,
+                            const float *h0_sample_in, float lr, float *dW, float *db, float *dc,
+                            float *h0_prob, float *h0_sample, float *v1, float *h1_prob,
+                            float *recon_mse, void *ws, size_t ws_bytes, void *stream);
 
 /* One mini-batch gradient-descent step of a CNN (Sections II, IV-B, V, VI): forward
  * through every layer, softmax cross-entropy averaged over the batch, backward (full

@@ -22,7 +22,8 @@ ACT = {"identity": 0, "sigmoid": 1, "relu": 2}
 SYMBOLS = ["dll_status_string", "dll_conv_workspace_bytes", "dll_conv_valid_fwd", "dll_conv_full_bwd",
            "dll_conv_valid_wgrad", "dll_crbm_workspace_bytes", "dll_crbm_cd1_step",
            "dll_cnn_workspace_bytes", "dll_cnn_train_step", "dll_cnn_forward_workspace_bytes", "dll_cnn_forward",
-           "dll_cnn_train_step_momentum"]
+           "dll_cnn_train_step_momentum", "dll_crbm_cd1_step_units", "dll_rbm_workspace_bytes", "dll_rbm_cd1_step"]
+VISIBLE = {"binary": 0, "gaussian": 1}
 
 
 class DllError(RuntimeError):
@@ -42,7 +43,7 @@ class dll_dense_desc(C.Structure):
 
 class dll_net_desc(C.Structure):
     _fields_ = [("n_conv", C.c_int), ("conv", C.POINTER(dll_conv_desc)), ("n_dense", C.c_int),
-                ("dense", C.POINTER(dll_dense_desc)), ("classes", C.c_int)]
+                ("dense", C.POINTER(dll_dense_desc)), ("classes", C.c_int), ("batch", C.c_int)]
 
 
 _lib = None
@@ -67,6 +68,10 @@ def lib() -> C.CDLL:
         L.dll_crbm_workspace_bytes.restype = sz
         L.dll_crbm_workspace_bytes.argtypes = [pd]
         L.dll_crbm_cd1_step.argtypes = [pd, vp, vp, vp, vp, vp, vp, C.c_float] + [vp] * 8 + [vp, sz, vp]
+        L.dll_crbm_cd1_step_units.argtypes = [pd, C.c_int, C.c_int, vp, vp, vp, vp, vp, vp, C.c_float] + [vp] * 9 + [vp, sz, vp]
+        L.dll_rbm_workspace_bytes.restype = sz
+        L.dll_rbm_workspace_bytes.argtypes = [C.c_int] * 3
+        L.dll_rbm_cd1_step.argtypes = [C.c_int] * 4 + [vp, vp, vp, vp, vp, vp, C.c_float] + [vp] * 8 + [vp, sz, vp]
         L.dll_cnn_workspace_bytes.restype = sz
         L.dll_cnn_workspace_bytes.argtypes = [C.POINTER(dll_net_desc)]
         L.dll_cnn_train_step.argtypes = [C.POINTER(dll_net_desc), vp, vp, vp, vp, C.c_float, vp, vp, vp, vp, sz, vp]
@@ -141,6 +146,30 @@ def dll_crbm_cd1_step(cs: ConvSpec, v0, W, b_hid, c_vis, uniform, h0_sample_in, 
                                 0 if ws is None else ws.numel(), _stream(stream)), "dll_crbm_cd1_step")
 
 
+def dll_crbm_cd1_step_units(cs: ConvSpec, visible: int, hidden_pool: int, v0, W, b_hid, c_vis, uniform, h0_sample_in, lr,
+                            dW, db, dc, h0_prob=None, h0_sample=None, pool_prob=None, v1=None, h1_prob=None,
+                            recon_mse=None, ws=None, stream=None) -> None:
+    d = conv_desc(cs)
+    _ok(lib().dll_crbm_cd1_step_units(C.byref(d), int(visible), int(hidden_pool), _ptr(v0), _ptr(W), _ptr(b_hid),
+                                      _ptr(c_vis), _ptr(uniform), _ptr(h0_sample_in), C.c_float(lr), _ptr(dW), _ptr(db),
+                                      _ptr(dc), _ptr(h0_prob), _ptr(h0_sample), _ptr(pool_prob), _ptr(v1), _ptr(h1_prob),
+                                      _ptr(recon_mse), _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream)),
+        "dll_crbm_cd1_step_units")
+
+
+def dll_rbm_workspace_bytes(batch: int, n_vis: int, n_hid: int) -> int:
+    return int(lib().dll_rbm_workspace_bytes(batch, n_vis, n_hid))
+
+
+def dll_rbm_cd1_step(batch: int, n_vis: int, n_hid: int, visible: int, v0, W, b_hid, c_vis, uniform, h0_sample_in, lr, dW,
+                     db, dc, h0_prob=None, h0_sample=None, v1=None, h1_prob=None, recon_mse=None, ws=None,
+                     stream=None) -> None:
+    _ok(lib().dll_rbm_cd1_step(batch, n_vis, n_hid, int(visible), _ptr(v0), _ptr(W), _ptr(b_hid), _ptr(c_vis),
+                               _ptr(uniform), _ptr(h0_sample_in), C.c_float(lr), _ptr(dW), _ptr(db), _ptr(dc),
+                               _ptr(h0_prob), _ptr(h0_sample), _ptr(v1), _ptr(h1_prob), _ptr(recon_mse), _ptr(ws),
+                               0 if ws is None else ws.numel(), _stream(stream)), "dll_rbm_cd1_step")
+
+
 @dataclass
 class NetHandle:
     """Host-side descriptor arrays kept alive for the duration of the calls."""
@@ -149,10 +178,11 @@ class NetHandle:
     denses: object
 
 
-def net_desc(conv: Sequence[ConvSpec], dense: Sequence[DenseSpec], classes: int) -> NetHandle:
+def net_desc(conv: Sequence[ConvSpec], dense: Sequence[DenseSpec], classes: int, batch: int = 0) -> NetHandle:
+    """`batch` is needed only for a fully-connected network (no conv layers)."""
     convs = (dll_conv_desc * len(conv))(*[conv_desc(c) for c in conv])
     denses = (dll_dense_desc * len(dense))(*[dll_dense_desc(d.in_, d.out, ACT[d.act]) for d in dense])
-    return NetHandle(dll_net_desc(len(conv), convs, len(dense), denses, classes), convs, denses)
+    return NetHandle(dll_net_desc(len(conv), convs, len(dense), denses, classes, batch), convs, denses)
 
 
 def dll_cnn_workspace_bytes(net: NetHandle) -> int:

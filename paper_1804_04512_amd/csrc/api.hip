@@ -195,19 +195,24 @@ size_t dll_crbm_workspace_bytes(const dll_conv_desc *d) {
   return c.used;
 }
 
-dll_status dll_crbm_cd1_step(const dll_conv_desc *din, const float *v0, float *W, float *b_hid, float *c_vis,
-                             const float *uniform, const float *h0_sample_in, float lr, float *dW, float *db, float *dc,
-                             float *h0_prob, float *h0_sample, float *v1, float *h1_prob, float *recon_mse, void *ws,
-                             size_t ws_bytes, void *stream) {
+dll_status dll_crbm_cd1_step_units(const dll_conv_desc *din, int visible, int hidden_pool, const float *v0, float *W,
+                                   float *b_hid, float *c_vis, const float *uniform, const float *h0_sample_in, float lr,
+                                   float *dW, float *db, float *dc, float *h0_prob, float *h0_sample, float *pool_prob,
+                                   float *v1, float *h1_prob, float *recon_mse, void *ws, size_t ws_bytes, void *stream) {
   dll_status st = check_desc(din, false);
   if (st != DLL_OK) return st;
   if (!v0 || !W || !b_hid || !c_vis || !dW || !db || !dc || (!uniform && !h0_sample_in)) return DLL_ERR_NULL;
   if (dW == W || db == b_hid || dc == c_vis || (const float *)v1 == v0) return DLL_ERR_SHAPE;
+  if ((visible != DLL_VISIBLE_BINARY && visible != DLL_VISIBLE_GAUSSIAN) || (hidden_pool != 1 && hidden_pool != 2))
+    return DLL_ERR_SHAPE;
   dll_conv_desc d = *din;
   d.act = DLL_ACT_SIGMOID;
   d.pool = 1;
+  const bool pmp = hidden_pool == 2;
+  if (pmp && ((out_h(&d) & 1) || (out_w(&d) & 1))) return DLL_ERR_SHAPE;
+  if (pool_prob && !pmp) return DLL_ERR_SHAPE;
   if (misaligned(v0) || misaligned(W) || misaligned(uniform) || misaligned(h0_sample_in) || misaligned(dW) ||
-      misaligned(h0_prob) || misaligned(h0_sample) || misaligned(v1) || misaligned(h1_prob))
+      misaligned(h0_prob) || misaligned(h0_sample) || misaligned(v1) || misaligned(h1_prob) || misaligned(pool_prob))
     return DLL_ERR_SHAPE;
   WgradPlan plan;
   if (!plan_for(&d, &plan)) return DLL_ERR_UNSUPPORTED;
@@ -223,9 +228,12 @@ dll_status dll_crbm_cd1_step(const dll_conv_desc *din, const float *v0, float *W
   float *h0s = h0_sample ? h0_sample : h0s_ws;
   float *h1p = h1_prob ? h1_prob : h1p_ws;
   float *v1p = v1 ? v1 : v1_ws;
+  const int hid_act = pmp ? ACT_PMP : ACT_SIGMOID;
 
-  // positive phase: hidden probabilities (+ Bernoulli sample in the same epilogue)
+  // positive phase: hidden probabilities (+ the sampled states in the same epilogue)
   ConvEngineArgs f0 = fwd_args(&d, v0, W, b_hid, h0p, nullptr);
+  f0.act = hid_act;
+  f0.out_pool = pool_prob;
   if (!h0_sample_in) { f0.uniform = uniform; f0.sample = h0s; }
   if ((st = dev(launch_conv_engine(f0, s))) != DLL_OK) return st;
   const float *hs = h0s;
@@ -233,14 +241,16 @@ dll_status dll_crbm_cd1_step(const dll_conv_desc *din, const float *v0, float *W
     hs = h0_sample_in;
     if (h0_sample && (st = dev(launch_copy(h0_sample_in, h0_sample, nh, s))) != DLL_OK) return st;
   }
-  // reconstruction: full convolution of the sample, + c, sigmoid
+  // reconstruction: full convolution of the states, + c, then the visible unit's mean
   ConvEngineArgs rec = bwd_args(&d, hs, nullptr, nullptr, W, v1p);
   rec.src_dz = 0;
   rec.bias = c_vis;
-  rec.act = ACT_SIGMOID;
+  rec.act = visible == DLL_VISIBLE_BINARY ? ACT_SIGMOID : ACT_IDENTITY;
   if ((st = dev(launch_conv_engine(rec, s))) != DLL_OK) return st;
   // negative phase hidden probabilities
-  if ((st = dev(launch_conv_engine(fwd_args(&d, v1p, W, b_hid, h1p, nullptr), s))) != DLL_OK) return st;
+  ConvEngineArgs f1 = fwd_args(&d, v1p, W, b_hid, h1p, nullptr);
+  f1.act = hid_act;
+  if ((st = dev(launch_conv_engine(f1, s))) != DLL_OK) return st;
   // statistics: filter gradients with dz := hidden probabilities
   dll_conv_desc di = d;
   di.act = DLL_ACT_IDENTITY;
@@ -254,6 +264,117 @@ dll_status dll_crbm_cd1_step(const dll_conv_desc *din, const float *v0, float *W
   if ((st = dev(launch_wgrad_reduce(r, plan, s))) != DLL_OK) return st;
   return dev(launch_visible_stats(v0, v1p, d.N, d.C, d.H * d.W, invB, dc, recon_mse, lr != 0.0f ? c_vis : nullptr, lr,
                                   stats, s));
+}
+
+dll_status dll_crbm_cd1_step(const dll_conv_desc *d, const float *v0, float *W, float *b_hid, float *c_vis,
+                             const float *uniform, const float *h0_sample_in, float lr, float *dW, float *db, float *dc,
+                             float *h0_prob, float *h0_sample, float *v1, float *h1_prob, float *recon_mse, void *ws,
+                             size_t ws_bytes, void *stream) {
+  return dll_crbm_cd1_step_units(d, DLL_VISIBLE_BINARY, 1, v0, W, b_hid, c_vis, uniform, h0_sample_in, lr, dW, db, dc,
+                                 h0_prob, h0_sample, nullptr, v1, h1_prob, recon_mse, ws, ws_bytes, stream);
+}
+
+namespace {
+// split-K partial area the three batch-by-units products of the RBM step need at most
+size_t rbm_partial_floats(int B, int nv, int nh) {
+  const size_t a = (size_t)gemm_pick_split_k(B, nh, nv) * B * nh, b = (size_t)gemm_pick_split_k(B, nv, nh) * B * nv;
+  return a > b ? a : b;
+}
+bool rbm_sizes_ok(int B, int nv, int nh) {
+  return B > 0 && nv > 0 && nh > 0 && (size_t)nv * nh < ((size_t)1 << 31) && (size_t)2 * B * nv < ((size_t)1 << 31) &&
+         (size_t)2 * B * nh < ((size_t)1 << 31);
+}
+}  // namespace
+
+size_t dll_rbm_workspace_bytes(int batch, int n_vis, int n_hid) {
+  if (!rbm_sizes_ok(batch, n_vis, n_hid)) return 0;
+  const size_t nH = (size_t)batch * n_hid, nV = (size_t)batch * n_vis;
+  Carver c(nullptr, 0);
+  c.floats(nH); c.floats(nH); c.floats(nH);      // h0p, h0s, h1p
+  c.floats(2 * nH); c.floats(2 * nV);            // stacked hidden probabilities, stacked visibles
+  c.floats(rbm_partial_floats(batch, n_vis, n_hid));
+  c.floats(rbm_visible_scratch_floats(n_vis));
+  return c.used;
+}
+
+dll_status dll_rbm_cd1_step(int batch, int n_vis, int n_hid, int visible, const float *v0, float *W, float *b_hid,
+                            float *c_vis, const float *uniform, const float *h0_sample_in, float lr, float *dW, float *db,
+                            float *dc, float *h0_prob, float *h0_sample, float *v1, float *h1_prob, float *recon_mse,
+                            void *ws, size_t ws_bytes, void *stream) {
+  if (batch <= 0 || n_vis <= 0 || n_hid <= 0) return DLL_ERR_SHAPE;
+  if (!rbm_sizes_ok(batch, n_vis, n_hid)) return DLL_ERR_UNSUPPORTED;
+  if (visible != DLL_VISIBLE_BINARY && visible != DLL_VISIBLE_GAUSSIAN) return DLL_ERR_SHAPE;
+  if (!v0 || !W || !b_hid || !c_vis || !dW || !db || !dc || (!uniform && !h0_sample_in)) return DLL_ERR_NULL;
+  if (dW == W || db == b_hid || dc == c_vis || (const float *)v1 == v0) return DLL_ERR_SHAPE;
+  if (misaligned(v0) || misaligned(W) || misaligned(uniform) || misaligned(h0_sample_in) || misaligned(dW) ||
+      misaligned(h0_prob) || misaligned(h0_sample) || misaligned(v1) || misaligned(h1_prob))
+    return DLL_ERR_SHAPE;
+  dll_status st = check_ws(ws, ws_bytes, dll_rbm_workspace_bytes(batch, n_vis, n_hid));
+  if (st != DLL_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int B = batch, nv = n_vis, nh = n_hid;
+  const size_t nH = (size_t)B * nh, nV = (size_t)B * nv;
+  Carver c(ws, ws_bytes);
+  float *h0p_ws = c.floats(nH), *h0s_ws = c.floats(nH), *h1p_ws = c.floats(nH);
+  float *hstack = c.floats(2 * nH), *vstack = c.floats(2 * nV);
+  float *partial = c.floats(rbm_partial_floats(B, nv, nh));
+  float *stats = c.floats(rbm_visible_scratch_floats(nv));
+  float *h0p = h0_prob ? h0_prob : h0p_ws;
+  float *h0s = h0_sample ? h0_sample : h0s_ws;
+  float *h1p = h1_prob ? h1_prob : h1p_ws;
+  float *v1p = vstack + nV;   // the reconstruction is produced in place as the lower half of the stack
+
+  // hidden probabilities of a visible batch: sigmoid(b_hid + v W^T)
+  auto hidden = [&](const float *v, float *out) {
+    GemmArgs g;
+    g.M = B; g.N = nh; g.Kdim = nv;
+    g.A = v; g.a_m = nv; g.a_k = 1;
+    g.B = W; g.b_k = 1; g.b_n = nv;
+    g.bias = b_hid; g.act = ACT_SIGMOID;
+    g.Cout = out; g.c_m = nh; g.c_n = 1;
+    g.split_k = gemm_pick_split_k(g.M, g.N, g.Kdim);
+    g.partial = partial;
+    return dev(launch_gemm(g, s));
+  };
+  if ((st = hidden(v0, h0p)) != DLL_OK) return st;
+  const float *hs = h0s;
+  if (h0_sample_in) {
+    hs = h0_sample_in;
+    if (h0_sample && (st = dev(launch_copy(h0_sample_in, h0_sample, nH, s))) != DLL_OK) return st;
+  } else if ((st = dev(launch_bernoulli(h0p, uniform, h0s, nH, s))) != DLL_OK) {
+    return st;
+  }
+  {
+    // reconstruction: c_vis + h0s W, then the visible unit's mean
+    GemmArgs g;
+    g.M = B; g.N = nv; g.Kdim = nh;
+    g.A = hs; g.a_m = nh; g.a_k = 1;
+    g.B = W; g.b_k = nv; g.b_n = 1;
+    g.bias = c_vis; g.act = visible == DLL_VISIBLE_BINARY ? ACT_SIGMOID : ACT_IDENTITY;
+    g.Cout = v1p; g.c_m = nv; g.c_n = 1;
+    g.split_k = gemm_pick_split_k(g.M, g.N, g.Kdim);
+    g.partial = partial;
+    if ((st = dev(launch_gemm(g, s))) != DLL_OK) return st;
+  }
+  if ((st = hidden(v1p, h1p)) != DLL_OK) return st;
+  if (v1 && (st = dev(launch_copy(v1p, v1, nV, s))) != DLL_OK) return st;
+  // statistics: with the phases stacked along the batch axis (signs and 1/B folded into the hidden
+  // half), dW is ONE product over 2B rows and db one column sum; the updates ride in their epilogues
+  const float invB = 1.0f / (float)B;
+  if ((st = dev(launch_copy(v0, vstack, nV, s))) != DLL_OK) return st;
+  if ((st = dev(launch_rbm_stack(h0p, h1p, invB, hstack, nH, s))) != DLL_OK) return st;
+  if ((st = dev(launch_rbm_visible_stats(v0, v1p, B, nv, invB, dc, recon_mse, lr != 0.0f ? c_vis : nullptr, lr, stats, s))) !=
+      DLL_OK)
+    return st;
+  if ((st = dev(launch_colsum(hstack, 2 * B, nh, db, lr != 0.0f ? b_hid : nullptr, lr, nullptr, 0.0f, s))) != DLL_OK) return st;
+  GemmArgs g;
+  g.M = nh; g.N = nv; g.Kdim = 2 * B;
+  g.A = hstack; g.a_m = 1; g.a_k = nh;
+  g.B = vstack; g.b_k = nv; g.b_n = 1;
+  g.Cout = dW; g.c_m = nv; g.c_n = 1;
+  if (lr != 0.0f) { g.update = W; g.step = lr; }
+  g.split_k = 1;
+  return dev(launch_gemm(g, s));
 }
 
 }  // extern "C"
@@ -271,10 +392,13 @@ struct NetLayout {
 };
 
 dll_status check_net(const dll_net_desc *net, NetLayout *lay) {
-  if (!net || !net->conv || !net->dense) return DLL_ERR_NULL;
-  if (net->n_conv < 1 || net->n_dense < 1 || net->classes < 1) return DLL_ERR_SHAPE;
-  const int B = net->conv[0].N;
-  size_t feat = 0, gmax = 0, partial = 0;
+  if (!net || !net->dense || (net->n_conv > 0 && !net->conv)) return DLL_ERR_NULL;
+  if (net->n_conv < 0 || net->n_dense < 1 || net->classes < 1) return DLL_ERR_SHAPE;
+  // a network without convolution layers is fully connected: its batch size is given, and its
+  // input rows are as long as the first dense layer's input
+  const int B = net->n_conv > 0 ? net->conv[0].N : net->batch;
+  if (B < 1) return DLL_ERR_SHAPE;
+  size_t feat = net->n_conv > 0 ? 0 : (size_t)(net->dense[0].in > 0 ? net->dense[0].in : 0), gmax = 0, partial = 0;
   for (int l = 0; l < net->n_conv; ++l) {
     const dll_conv_desc *d = &net->conv[l];
     dll_status st = check_desc(d);
@@ -446,7 +570,9 @@ dll_status run_cnn_step(const dll_net_desc *net, float *const *params, float *co
     if (q > 0 && net->dense[q - 1].act != DLL_ACT_IDENTITY) { g.C_ref = nb.act[L + q]; g.c_ref_act = net->dense[q - 1].act; }
     g.split_k = gemm_pick_split_k(g.M, g.N, g.Kdim);
     g.partial = nb.partial;
-    if ((st = dev(launch_gemm(g, s))) != DLL_OK) return st;
+    // the gradient with respect to the network input has no consumer
+    if (q > 0 || L > 0)
+      if ((st = dev(launch_gemm(g, s))) != DLL_OK) return st;
     GemmArgs h;
     h.M = dd->out; h.N = dd->in; h.Kdim = B;
     h.A = gcur; h.a_m = 1; h.a_k = dd->out;

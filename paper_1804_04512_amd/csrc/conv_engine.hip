@@ -57,6 +57,17 @@ __device__ __forceinline__ float act_deriv(int act, float out) {
   return 1.0f;
 }
 
+// Probabilistic max pooling over one 2x2 block (Section II, the CRBM's pooling form): the four
+// units (inputs z[v] + bias) and the state "all off" form one multinomial with weights exp(input)
+// and 1; the largest exponent is subtracted before exponentiating.
+__device__ __forceinline__ floatx4 pmp_block(const floatx4 z, float bias) {
+  const float i0 = z[0] + bias, i1 = z[1] + bias, i2 = z[2] + bias, i3 = z[3] + bias;
+  const float m = fmaxf(fmaxf(fmaxf(i0, i1), fmaxf(i2, i3)), 0.0f);
+  const float e0 = expf(i0 - m), e1 = expf(i1 - m), e2 = expf(i2 - m), e3 = expf(i3 - m);
+  const float inv = 1.0f / (expf(-m) + ((e0 + e1) + (e2 + e3)));
+  return floatx4{e0 * inv, e1 * inv, e2 * inv, e3 * inv};
+}
+
 // dy times act'(y) for a pooled element: from the layer output, or from the index byte's flag.
 __device__ __forceinline__ float pooled_dz(int act, float g, float out, unsigned char f) {
   if (act == ACT_RELU_FLAGGED) return (f & kIdxInactive) ? 0.0f : g;
@@ -129,35 +140,75 @@ __device__ __forceinline__ void engine_epilogue_as(const ConvEngineArgs &a, floa
             }
         }
       } else {
+        // the lane's four windows: unit outputs pr[mt][2a+b] and, for the sampling epilogues, their states
+        floatx4 pr[4], sm[4] = {};
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+          if (ACT == ACT_PMP) {
+            pr[mt] = pmp_block(acc[rp][mt][nt], bv);
+          } else {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) pr[mt][v] = act_apply(ACT, acc[rp][mt][nt][v] + bv);
+          }
+        }
+        if (ACT == ACT_PMP) {
+          // one uniform number per block picks among "unit v on" (v = 0..3) and "all off"; the
+          // pooling unit's probability is the sum of its block
+          const int Hp = a.Hout >> 1, Wp = a.Wout >> 1;
+          const int ob = ((n * a.Kout + ko) * Hp + py) * Wp + px0;
+#pragma unroll
+          for (int mt = 0; mt < 4; ++mt) {
+            if (px0 + mt >= Wp) continue;
+            if (a.out_pool) a.out_pool[ob + mt] = (pr[mt][0] + pr[mt][1]) + (pr[mt][2] + pr[mt][3]);
+            if (a.sample) {
+              const float u = a.uniform[ob + mt];
+              float lo = 0.0f;
+              bool taken = false;
+#pragma unroll
+              for (int v = 0; v < 4; ++v) {
+                const float hi = lo + pr[mt][v];
+                const bool on = !taken && lo <= u && u < hi;
+                sm[mt][v] = on ? 1.0f : 0.0f;
+                taken = taken || on;
+                lo = hi;
+              }
+            }
+          }
+        }
 #pragma unroll
         for (int wa2 = 0; wa2 < 2; ++wa2) {
           const int oy = 2 * py + wa2;
           if (oy >= a.Hout) continue;
           const int ox = 2 * px0;
           const int o = ((n * a.Kout + ko) * a.Hout + oy) * a.Wout + ox;
-          float yv[8];
+          float yv[8], sv[8];
 #pragma unroll
           for (int mt = 0; mt < 4; ++mt) {
-            yv[2 * mt] = act_apply(ACT, acc[rp][mt][nt][2 * wa2] + bv);
-            yv[2 * mt + 1] = act_apply(ACT, acc[rp][mt][nt][2 * wa2 + 1] + bv);
+            yv[2 * mt] = pr[mt][2 * wa2];
+            yv[2 * mt + 1] = pr[mt][2 * wa2 + 1];
+            if (ACT == ACT_PMP) { sv[2 * mt] = sm[mt][2 * wa2]; sv[2 * mt + 1] = sm[mt][2 * wa2 + 1]; }
           }
           if (ox + 7 < a.Wout && (a.Wout & 3) == 0) {
             *reinterpret_cast<float4 *>(a.out + o) = make_float4(yv[0], yv[1], yv[2], yv[3]);
             *reinterpret_cast<float4 *>(a.out + o + 4) = make_float4(yv[4], yv[5], yv[6], yv[7]);
             if (a.sample) {
-              const float4 u0 = *reinterpret_cast<const float4 *>(a.uniform + o);
-              const float4 u1 = *reinterpret_cast<const float4 *>(a.uniform + o + 4);
-              *reinterpret_cast<float4 *>(a.sample + o) =
-                  make_float4(u0.x < yv[0] ? 1.f : 0.f, u0.y < yv[1] ? 1.f : 0.f, u0.z < yv[2] ? 1.f : 0.f, u0.w < yv[3] ? 1.f : 0.f);
-              *reinterpret_cast<float4 *>(a.sample + o + 4) =
-                  make_float4(u1.x < yv[4] ? 1.f : 0.f, u1.y < yv[5] ? 1.f : 0.f, u1.z < yv[6] ? 1.f : 0.f, u1.w < yv[7] ? 1.f : 0.f);
+              if (ACT != ACT_PMP) {
+                const float4 u0 = *reinterpret_cast<const float4 *>(a.uniform + o);
+                const float4 u1 = *reinterpret_cast<const float4 *>(a.uniform + o + 4);
+                sv[0] = u0.x < yv[0] ? 1.f : 0.f; sv[1] = u0.y < yv[1] ? 1.f : 0.f;
+                sv[2] = u0.z < yv[2] ? 1.f : 0.f; sv[3] = u0.w < yv[3] ? 1.f : 0.f;
+                sv[4] = u1.x < yv[4] ? 1.f : 0.f; sv[5] = u1.y < yv[5] ? 1.f : 0.f;
+                sv[6] = u1.z < yv[6] ? 1.f : 0.f; sv[7] = u1.w < yv[7] ? 1.f : 0.f;
+              }
+              *reinterpret_cast<float4 *>(a.sample + o) = make_float4(sv[0], sv[1], sv[2], sv[3]);
+              *reinterpret_cast<float4 *>(a.sample + o + 4) = make_float4(sv[4], sv[5], sv[6], sv[7]);
             }
           } else {
 #pragma unroll
             for (int e = 0; e < 8; ++e)
               if (ox + e < a.Wout) {
                 a.out[o + e] = yv[e];
-                if (a.sample) a.sample[o + e] = a.uniform[o + e] < yv[e] ? 1.f : 0.f;
+                if (a.sample) a.sample[o + e] = ACT == ACT_PMP ? sv[e] : (a.uniform[o + e] < yv[e] ? 1.f : 0.f);
               }
           }
         }
@@ -179,6 +230,7 @@ __device__ __forceinline__ void engine_epilogue(const ConvEngineArgs &a, floatx4
   } else {
     if (a.act == ACT_RELU) DLL_EPI(ACT_RELU, 1);
     else if (a.act == ACT_SIGMOID) DLL_EPI(ACT_SIGMOID, 1);
+    else if (a.act == ACT_PMP) DLL_EPI(ACT_PMP, 1);
     else DLL_EPI(ACT_IDENTITY, 1);
   }
 #undef DLL_EPI

@@ -12,6 +12,10 @@ enum { ACT_IDENTITY = 0, ACT_SIGMOID = 1, ACT_RELU = 2 };
 // Backward passes only: ReLU whose derivative comes from the flag bit in the pooling index
 // (kIdxInactive) instead of from the layer output, which then is not read at all.
 enum { ACT_RELU_FLAGGED = 3 };
+// Forward epilogue only (pool == 1, even output extents): probabilistic max pooling over 2x2
+// blocks, the hidden layer of the pooling CRBM (Section II).  `uniform` then holds one number per
+// block, [N][Kout][Hout/2][Wout/2], and `out_pool` may receive the pooling units' probabilities.
+enum { ACT_PMP = 4 };
 // Pooling index byte: bits 0-1 hold the arg-max position 2a+b inside the 2x2 window; the
 // forward pass of a ReLU layer also sets kIdxInactive where the pooled output is zero.
 constexpr unsigned char kIdxPosMask = 3, kIdxInactive = 4;
@@ -58,6 +62,7 @@ struct ConvEngineArgs {
   unsigned char *out_idx = nullptr;           // pool == 2: optional (an inference pass does not keep the decisions)
   const float *uniform = nullptr;         // optional Bernoulli epilogue (pool == 1): sample = 1[uniform < out]
   float *sample = nullptr;
+  float *out_pool = nullptr;              // act == ACT_PMP: optional P(pooling unit on), [N][Kout][Hout/2][Wout/2]
 };
 
 hipError_t launch_conv_engine(const ConvEngineArgs &a, hipStream_t stream);
@@ -151,6 +156,15 @@ hipError_t launch_visible_stats(const float *v0, const float *v1, int N, int C, 
                                 hipStream_t stream);
 
 hipError_t launch_copy(const float *src, float *dst, size_t count, hipStream_t stream);
+
+// Fully-connected RBM step, element-wise parts: Bernoulli states 1[u < p]; the two phases' hidden
+// probabilities stacked as [scale * h0p; -scale * h1p] (2 * count floats); visible statistics
+// dc[i] = scale * sum_n (v0 - v1)[n][i], mse = mean((v0 - v1)^2) with rbm_visible_scratch_floats(nv) floats of scratch.
+hipError_t launch_bernoulli(const float *p, const float *u, float *states, size_t count, hipStream_t stream);
+hipError_t launch_rbm_stack(const float *h0p, const float *h1p, float scale, float *stacked, size_t count, hipStream_t stream);
+size_t rbm_visible_scratch_floats(int nv);
+hipError_t launch_rbm_visible_stats(const float *v0, const float *v1, int B, int nv, float scale, float *dc, float *mse,
+                                    float *c_update, float step, float *scratch, hipStream_t stream);
 
 // ---------------------------------------------------------------------------------------
 // Closing kernel of a training step: the reductions that nothing later in the step waits for

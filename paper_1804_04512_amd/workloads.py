@@ -118,7 +118,7 @@ class CnnWorkload:
 
     @property
     def batch(self) -> int:
-        return self.conv[0].N
+        return self.conv[0].N if self.conv else int(self.x.shape[0])
 
     def conv_flop(self) -> int:
         """fwd + wgrad for every conv layer, + full bwd for all but the first (no consumer)."""
@@ -242,6 +242,64 @@ def paper_imagenet_cnn(batch: int = 128, image: int = 256, hidden: int = 2048, c
         side //= 2
     dense = [DenseSpec(32 * side * side, hidden, "relu"), DenseSpec(hidden, classes, "identity")]
     return _cnn(13, "paper_imagenet_cnn", conv, dense, classes, 0.001, "normal", None)
+
+
+def paper_mnist_dense(batch: int = 100, sizes=(784, 500, 250, 10)) -> CnnWorkload:
+    """Section IV-A: fully-connected 784-500-250-10, sigmoid hidden layers, softmax output,
+    mini-batches of 100, learning rate 0.1 (momentum 0.9 is an argument of the step).
+    Inputs uniform in [0, 1) like grey-scale pixels; weights N(0, sqrt(2/fan_in)), biases N(0, 0.01)."""
+    dense = [DenseSpec(sizes[i], sizes[i + 1], "sigmoid" if i + 2 < len(sizes) else "identity") for i in range(len(sizes) - 1)]
+    x = rng(14, 0).random((batch, sizes[0]), dtype=np.float32)
+    labels = rng(14, 1).integers(0, sizes[-1], size=(batch,)).astype(np.int32)
+    params: List[np.ndarray] = []
+    tid = 2
+    for d in dense:
+        params.append(_f32(rng(14, tid).standard_normal((d.out, d.in_), dtype=np.float32) * np.float32(np.sqrt(2.0 / d.in_))))
+        params.append(_f32(rng(14, tid + 1).normal(0.0, 0.01, (d.out,))))
+        tid += 2
+    return CnnWorkload(14, "paper_mnist_dense", [], dense, sizes[-1], 0.1, _f32(x), labels, params)
+
+
+@dataclass
+class RbmWorkload:
+    """Fully-connected RBM step: v0 [batch, n_vis], W [n_hid, n_vis], u [batch, n_hid]."""
+    name: str
+    batch: int
+    n_vis: int
+    n_hid: int
+    visible: str
+    v0: np.ndarray
+    W: np.ndarray
+    b: np.ndarray
+    c: np.ndarray
+    u: np.ndarray
+    lr: float
+
+    def flop(self) -> int:
+        return 2 * 5 * self.batch * self.n_vis * self.n_hid
+
+
+def dense_rbm(batch: int = 100, n_vis: int = 784, n_hid: int = 500, visible: str = "binary", seed: int = 15) -> RbmWorkload:
+    """The first layer of Section IV-A's network as an RBM (Section II): binary inputs with about a
+    fifth of the pixels on (or standard-normal inputs for Gaussian visible units), W ~ N(0, 0.05),
+    small random biases."""
+    g = rng(seed, 0)
+    v0 = (g.random((batch, n_vis)) < 0.2).astype(np.float32) if visible == "binary" else \
+        g.standard_normal((batch, n_vis), dtype=np.float32)
+    return RbmWorkload(f"dense_rbm_{visible}", batch, n_vis, n_hid, visible, _f32(v0),
+                       _f32(rng(seed, 1).normal(0.0, 0.05, (n_hid, n_vis))), _f32(rng(seed, 2).normal(0.0, 0.1, (n_hid,))),
+                       _f32(rng(seed, 3).normal(0.0, 0.1, (n_vis,))), _f32(rng(seed, 4).random((batch, n_hid), dtype=np.float32)), 0.05)
+
+
+def crbm_units(cs: ConvSpec, visible: str, hidden_pool: int, seed: int = 16) -> CrbmWorkload:
+    """A CRBM step on any shape: binary (30 % on) or standard-normal visibles, filters N(0, 0.05),
+    small random biases, one uniform number per hidden unit (hidden_pool 1) or per 2x2 block (2)."""
+    g = rng(seed, 0)
+    v0 = (g.random(cs.x_shape) < 0.3).astype(np.float32) if visible == "binary" else g.standard_normal(cs.x_shape, dtype=np.float32)
+    ushape = (cs.N, cs.K, cs.Ho // hidden_pool, cs.Wo // hidden_pool)
+    return CrbmWorkload(0, f"crbm_{visible}_pool{hidden_pool}", cs, _f32(v0), _f32(rng(seed, 1).normal(0.0, 0.05, cs.w_shape)),
+                        _f32(rng(seed, 2).normal(0.0, 0.1, (cs.K,))), _f32(rng(seed, 3).normal(0.0, 0.1, (cs.C,))),
+                        _f32(rng(seed, 4).random(ushape, dtype=np.float32)), 0.01)
 
 
 def forward_flop(w: CnnWorkload) -> int:

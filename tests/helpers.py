@@ -26,7 +26,8 @@ def odesc(cs: wl.ConvSpec, pool=None, act=None):
 
 
 def onet(w: wl.CnnWorkload) -> orc.Net:
-    return orc.Net([odesc(c) for c in w.conv], [(d.in_, d.out, ACT[d.act]) for d in w.dense], w.classes)
+    return orc.Net([odesc(c) for c in w.conv], [(d.in_, d.out, ACT[d.act]) for d in w.dense], w.classes,
+                   batch=0 if w.conv else w.batch)
 
 
 def check_idx_bytes(raw, relu, y_gpu):

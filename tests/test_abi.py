@@ -43,6 +43,15 @@ def test_workspace_queries_are_host_side():
     bad = binding.net_desc([ConvSpec(4, 1, 28, 28, 8, 5, 5, 0, "relu", 2)], [DenseSpec(77, 10)], 10)
     assert binding.dll_cnn_workspace_bytes(bad) == 0          # flatten size mismatch
     assert binding.dll_conv_workspace_bytes(ConvSpec(1, 1, 5, 5, 1, 3, 3, 0, "relu", 2)) == 0   # odd map + pool
+    # fully-connected networks: the batch size comes from the descriptor
+    dense = [DenseSpec(784, 500, "sigmoid"), DenseSpec(500, 250, "sigmoid"), DenseSpec(250, 10)]
+    assert binding.dll_cnn_workspace_bytes(binding.net_desc([], dense, 10, 100)) > 0
+    assert binding.dll_cnn_forward_workspace_bytes(binding.net_desc([], dense, 10, 100)) > 0
+    assert binding.dll_cnn_workspace_bytes(binding.net_desc([], dense, 10, 0)) == 0
+    assert binding.dll_cnn_workspace_bytes(binding.net_desc([], dense, 11, 100)) == 0        # classes != last layer
+    assert binding.dll_rbm_workspace_bytes(100, 784, 500) > 0
+    assert binding.dll_rbm_workspace_bytes(100, 784, 500) % 256 == 0
+    assert binding.dll_rbm_workspace_bytes(0, 784, 500) == 0
 
 
 def test_argument_errors_are_reported_before_any_launch():
@@ -69,6 +78,14 @@ def test_argument_errors_are_reported_before_any_launch():
     pooled = binding.conv_desc(ConvSpec(2, 1, 8, 8, 4, 3, 3, 0, "relu", 2))
     assert L.dll_conv_full_bwd(C.byref(pooled), a, b, None, c, e, None, 0, None) == 1           # pool needs idx
     assert L.dll_crbm_cd1_step(C.byref(d), a, b, c, e, None, None, 0.0, *([a] * 8), None, 0, None) == 1   # no uniforms
+    assert L.dll_crbm_cd1_step_units(C.byref(d), 0, 1, a, b, c, e, None, None, 0.0, *([a] * 9), None, 0, None) == 1  # no uniforms
+    assert L.dll_crbm_cd1_step_units(C.byref(d), 7, 1, a, b, c, e, a, None, 0.0, b, c, e, *([None] * 6), None, 0, None) == 2
+    odd = binding.conv_desc(ConvSpec(2, 1, 9, 8, 4, 3, 3))
+    assert L.dll_crbm_cd1_step_units(C.byref(odd), 0, 2, a, b, c, e, a, None, 0.0, b, c, e, *([None] * 6), None, 0, None) == 2
+    assert L.dll_rbm_cd1_step(4, 8, 6, 0, a, b, c, e, None, None, 0.0, *([a] * 8), None, 0, None) == 1    # no uniforms
+    assert L.dll_rbm_cd1_step(4, 0, 6, 0, a, b, c, e, a, None, 0.0, *([a] * 8), None, 0, None) == 2       # no visible units
+    assert L.dll_rbm_cd1_step(4, 8, 6, 0, a, b, c, e, a, None, 0.0, b, a, a, *([None] * 5), None, 0, None) == 2  # dW aliases W
+    assert L.dll_rbm_cd1_step(4, 8, 6, 0, a, b, c, e, a, None, 0.0, a, b, c, *([None] * 5), None, 0, None) == 4  # no workspace
     assert L.dll_cnn_train_step(None, None, None, None, None, 0.0, None, None, None, None, 0, None) == 1
     assert L.dll_cnn_forward(None, None, None, None, None, None, 0, None) == 1
     assert L.dll_cnn_train_step_momentum(None, None, None, None, None, None, 0.0, 0.0, 0.0, None, None, None, None, 0, None) == 1

@@ -199,7 +199,7 @@ def test_crbm_sample_override_and_lr_zero():
 # ---------------------------------------------------------------- CNN training step
 
 def run_cnn_gpu(w: wl.CnnWorkload, lr, want_grads=True):
-    net = B.net_desc(w.conv, w.dense, w.classes)
+    net = B.net_desc(w.conv, w.dense, w.classes, 0 if w.conv else w.batch)
     params = [dev(p) for p in w.params]
     grads = [torch.full_like(p, float("nan")) for p in params] if want_grads else None
     idx = [torch.full(c.y_shape, 255, dtype=torch.uint8, device="cuda") for c in w.conv]
@@ -280,7 +280,7 @@ def test_cnn_lr_zero_and_no_grads():
 # ---------------------------------------------------------------- inference pass
 
 def run_forward_gpu(w: wl.CnnWorkload):
-    net = B.net_desc(w.conv, w.dense, w.classes)
+    net = B.net_desc(w.conv, w.dense, w.classes, 0 if w.conv else w.batch)
     params = [dev(p) for p in w.params]
     logits = torch.full((w.batch, w.classes), float("nan"), device="cuda")
     prob = torch.full((w.batch, w.classes), float("nan"), device="cuda")
@@ -314,7 +314,7 @@ def test_forward_pass_logits_equal_training_pass_logits():
     g = run_cnn_gpu(w, 0.0, want_grads=False)
     lg, pg = run_forward_gpu(w)
     assert np.array_equal(lg, g["logits"])
-    net = B.net_desc(w.conv, w.dense, w.classes)
+    net = B.net_desc(w.conv, w.dense, w.classes, 0 if w.conv else w.batch)
     params = [dev(p) for p in w.params]
     ws = B.workspace(B.dll_cnn_forward_workspace_bytes(net))
     only_p = torch.full((w.batch, w.classes), float("nan"), device="cuda")
@@ -334,7 +334,7 @@ def test_momentum_step_matches_oracle():
     lr, mu, decay = 0.01, 0.9, 1e-3
     r = np.random.default_rng(77)
     vel0 = [(r.standard_normal(p.shape) * 0.01 * max(float(np.abs(p).max()), 1e-3)).astype(np.float32) for p in w.params]
-    net = B.net_desc(w.conv, w.dense, w.classes)
+    net = B.net_desc(w.conv, w.dense, w.classes, 0 if w.conv else w.batch)
     params, vel = [dev(p) for p in w.params], [dev(v) for v in vel0]
     grads = [torch.full_like(p, float("nan")) for p in params]
     idx = [torch.full(c.y_shape, 255, dtype=torch.uint8, device="cuda") for c in w.conv]
