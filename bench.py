@@ -39,8 +39,11 @@ def parse():
     ap.add_argument("--batch", type=int, default=None, help="override the batch size (inspection only)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--cpu-batch", type=int, default=128, help="batch of the CPU oracle leg (config 5 and --mode infer)")
-    ap.add_argument("--mode", choices=["train", "infer"], default="train",
-                    help="infer: time dll_cnn_forward on the paper's ImageNet network (batch 128 of 3x256x256) instead of the training step")
+    ap.add_argument("--mode", choices=["train", "infer", "dense", "rbm", "crbm_pmp"], default="train",
+                    help="inspection lines instead of the training step of --config: infer = dll_cnn_forward on the paper's "
+                         "ImageNet network (batch 128 of 3x256x256); dense = momentum step of the fully-connected 784-500-250-10 "
+                         "network (batch 100); rbm = CD-1 step of a 784-500 RBM (batch 100); crbm_pmp = CD-1 step of the "
+                         "config-3 CRBM with probabilistic max pooling")
     ap.add_argument("--pmc-calib", action="store_true",
                     help="also run one 256 MiB device copy, the known-size kernel that scales rocprofv3's byte counters")
     return ap.parse_args()
@@ -196,6 +199,89 @@ def infer_line(args, B, wl, torch):
     return 0
 
 
+def timed_ms(step, args, torch):
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / args.steps * 1e3
+
+
+def timed_cpu(step, budget_s=10.0, max_reps=200):
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        step()
+        reps += 1
+        dt = time.perf_counter() - t0
+        if dt >= budget_s or reps >= max_reps:
+            return reps, dt
+
+
+def extra_line(args, B, wl, torch):
+    """Inspection modes for the steps built around the same kernels: the fully-connected network,
+    the fully-connected RBM and the CRBM with probabilistic max pooling."""
+    dev = lambda a: torch.from_numpy(a).cuda()
+    if args.mode == "dense":
+        w = wl.paper_mnist_dense(args.batch) if args.batch else wl.paper_mnist_dense()
+        net = B.net_desc(w.conv, w.dense, w.classes, w.batch)
+        params = [dev(p) for p in w.params]
+        vel = [torch.zeros_like(p) for p in params]
+        x, labels, loss = dev(w.x), dev(w.labels), torch.zeros(1, device="cuda")
+        ws = B.workspace(B.dll_cnn_workspace_bytes(net))
+        step = lambda: B.dll_cnn_train_step_momentum(net, params, vel, None, x, labels, w.lr, 0.9, 0.0, loss, None, None, ws)
+        batch, flop, name = w.batch, w.flop(), w.name
+        what = "momentum step (lr 0.1, momentum 0.9) of the fully-connected network"
+    elif args.mode == "rbm":
+        w = wl.dense_rbm(args.batch) if args.batch else wl.dense_rbm()
+        W, b, c, v0, u = dev(w.W), dev(w.b), dev(w.c), dev(w.v0), dev(w.u)
+        dW, db, dc = torch.empty_like(W), torch.empty_like(b), torch.empty_like(c)
+        ws = B.workspace(B.dll_rbm_workspace_bytes(w.batch, w.n_vis, w.n_hid))
+        step = lambda: B.dll_rbm_cd1_step(w.batch, w.n_vis, w.n_hid, 0, v0, W, b, c, u, None, w.lr, dW, db, dc, ws=ws)
+        batch, flop, name = w.batch, w.flop(), w.name
+        what = "CD-1 step of the fully-connected RBM"
+    else:
+        cs = wl.config3(args.batch).conv if args.batch else wl.config3().conv
+        w = wl.crbm_units(cs, "binary", 2)
+        W, b, c, v0, u = dev(w.W), dev(w.b), dev(w.c), dev(w.v0), dev(w.u)
+        dW, db, dc = torch.empty_like(W), torch.empty_like(b), torch.empty_like(c)
+        ws = B.workspace(B.dll_crbm_workspace_bytes(cs))
+        step = lambda: B.dll_crbm_cd1_step_units(cs, 0, 2, v0, W, b, c, u, None, w.lr, dW, db, dc, ws=ws)
+        batch, flop, name = cs.N, w.flop(), "c3_crbm_probabilistic_max_pooling"
+        what = "CD-1 step of the CRBM with probabilistic max pooling"
+    ms = timed_ms(step, args, torch)
+    gflops = flop / (ms * 1e-3) / 1e9
+    out = {"metric": f"{what}: GFLOP/s + samples/s; % of fp32 MFMA peak", "value": gflops, "unit": "GFLOP/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": name, "batch": batch, "flop_per_step": flop},
+           "images_per_s": batch / (ms * 1e-3), "pct_fp32_mfma_peak": 100.0 * gflops / (PEAK_FP32_MFMA_TFLOPS * 1e3)}
+    if not args.no_cpu:
+        from oracle import oracle as orc
+        act = {"identity": 0, "sigmoid": 1, "relu": 2}
+        if args.mode == "dense":
+            onet = orc.Net([], [(d.in_, d.out, act[d.act]) for d in w.dense], w.classes, batch=w.batch)
+
+            def cpu_step():
+                ps = w.clone_params()
+                r = orc.cnn_train_step(onet, ps, w.x, w.labels, 0.0)
+                for p_, g_ in zip(ps, r.grads):
+                    orc.sgd_momentum(p_, np.zeros_like(p_), g_, w.lr, 0.9, 0.0)
+        elif args.mode == "rbm":
+            cpu_step = lambda: orc.rbm_cd1_step(w.batch, w.n_vis, w.n_hid, 0, w.v0, w.W.copy(), w.b.copy(), w.c.copy(), w.u, lr=w.lr)
+        else:
+            d = orc.conv_desc(cs.N, cs.C, cs.H, cs.W, cs.K, cs.R, cs.S)
+            cpu_step = lambda: orc.crbm_cd1_step_units(d, 0, 2, w.v0, w.W.copy(), w.b.copy(), w.c.copy(), w.u, lr=w.lr)
+        reps, dt = timed_cpu(cpu_step)
+        out["cpu_baseline"] = dict(value=flop * reps / dt / 1e9, unit="GFLOP/s", images_per_s=batch * reps / dt, seconds=dt,
+                                   cores=orc.max_threads(), kind="oracle",
+                                   sample=f"{reps} step(s) of {name} at batch {batch}, fp64 accumulation, plain loops")
+    print(json.dumps(out))
+    return 0
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -209,6 +295,8 @@ def main():
     torch.cuda.set_device(0)
     if args.mode == "infer":
         return infer_line(args, B, wl, torch)
+    if args.mode != "train":
+        return extra_line(args, B, wl, torch)
     cfg = args.config
     w = wl.ALL[cfg](args.batch) if args.batch else wl.ALL[cfg]()
     dev = lambda a: torch.from_numpy(a).cuda()

@@ -25,20 +25,31 @@ __global__ __launch_bounds__(kThreads) void rbm_stack_kernel(const float *h0p, c
   }
 }
 
-// One thread per visible unit i: dc[i] = scale * sum_n (v0 - v1)[n][i] (rows in order, so the result
-// does not depend on the launch), the optional bias update, and the block's sum of squared differences.
+// 32 visible units per workgroup, 8 row slices each: dc[i] = scale * sum_n (v0 - v1)[n][i] (slices
+// added in a fixed order, so the result does not depend on the launch), the optional bias update,
+// and the workgroup's sum of squared differences.
+constexpr int kVisCols = 32, kVisSlices = kThreads / kVisCols;
 __global__ __launch_bounds__(kThreads) void rbm_visible_kernel(const float *v0, const float *v1, int B, int nv, float scale,
                                                               float *dc, float *c_update, float step, float *sq_partial) {
   __shared__ float sh[kThreads];
-  const int i = blockIdx.x * kThreads + threadIdx.x;
+  __shared__ float part[kVisSlices][kVisCols + 1];
+  const int col = threadIdx.x % kVisCols, slice = threadIdx.x / kVisCols;
+  const int i = blockIdx.x * kVisCols + col;
   float s = 0.0f, q = 0.0f;
   if (i < nv) {
-    for (int n = 0; n < B; ++n) {
+    for (int n = slice; n < B; n += kVisSlices) {
       const float d = v0[(size_t)n * nv + i] - v1[(size_t)n * nv + i];
       s += d;
       q += d * d;
     }
-    const float g = scale * s;
+  }
+  part[slice][col] = s;
+  __syncthreads();
+  if (slice == 0 && i < nv) {
+    float t = 0.0f;
+#pragma unroll
+    for (int k = 0; k < kVisSlices; ++k) t += part[k][col];
+    const float g = scale * t;
     if (dc) dc[i] = g;
     if (c_update) c_update[i] += step * g;
   }
@@ -73,11 +84,11 @@ hipError_t launch_rbm_stack(const float *h0p, const float *h1p, float scale, flo
   return hipGetLastError();
 }
 
-size_t rbm_visible_scratch_floats(int nv) { return (size_t)(nv + kThreads - 1) / kThreads; }
+size_t rbm_visible_scratch_floats(int nv) { return (size_t)(nv + kVisCols - 1) / kVisCols; }
 
 hipError_t launch_rbm_visible_stats(const float *v0, const float *v1, int B, int nv, float scale, float *dc, float *mse,
                                     float *c_update, float step, float *scratch, hipStream_t stream) {
-  const int blocks = (nv + kThreads - 1) / kThreads;
+  const int blocks = (nv + kVisCols - 1) / kVisCols;
   hipLaunchKernelGGL(rbm_visible_kernel, dim3(blocks), dim3(kThreads), 0, stream, v0, v1, B, nv, scale, dc, c_update, step,
                      scratch);
   hipError_t e = hipGetLastError();
