@@ -97,16 +97,28 @@ __device__ __forceinline__ float dz_value(const ConvEngineArgs &a, int n, int k,
   return g;
 }
 
+// The lane's bias values, one per N-tile (output channel ko0 + 16nt + i16).  Read once per
+// workgroup, ahead of the tile loop: a load inside the epilogue would be waited for on the spot,
+// together with every prefetch load issued before it.
+template <int NT>
+__device__ __forceinline__ void lane_bias(const ConvEngineArgs &a, int ko0, int i16, float (&bias)[NT]) {
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const int ko = ko0 + nt * 16 + i16;
+    bias[nt] = (a.bias && ko < a.Kout) ? a.bias[ko] : 0.0f;
+  }
+}
+
 // Epilogue shared by the engine kernels.  Lane owns output channel ko0+16nt+i16, window column
 // 4*kq+mt of the tile, window row wave*RP+rp; acc[..][v] is window position v = 2a+b.
 template <int NT, int RP, int ACT, int POOL>
-__device__ __forceinline__ void engine_epilogue_as(const ConvEngineArgs &a, floatx4 (&acc)[RP][4][NT], int n, int ko0,
-                                                int oy0, int ox0, int wave, int i16, int kq) {
+__device__ __forceinline__ void engine_epilogue_as(const ConvEngineArgs &a, floatx4 (&acc)[RP][4][NT], const float (&bias)[NT],
+                                                int n, int ko0, int oy0, int ox0, int wave, int i16, int kq) {
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     const int ko = ko0 + nt * 16 + i16;
     if (ko >= a.Kout) continue;
-    const float bv = a.bias ? a.bias[ko] : 0.0f;
+    const float bv = bias[nt];
 #pragma unroll
     for (int rp = 0; rp < RP; ++rp) {
       const int py = (oy0 >> 1) + wave * RP + rp;   // window row (pre-pool rows 2py, 2py+1)
@@ -220,9 +232,9 @@ __device__ __forceinline__ void engine_epilogue_as(const ConvEngineArgs &a, floa
 // The activation and the pooling mode are fixed for a launch: dispatch once, so that the
 // per-element code carries no branches on them.
 template <int NT, int RP>
-__device__ __forceinline__ void engine_epilogue(const ConvEngineArgs &a, floatx4 (&acc)[RP][4][NT], int n, int ko0,
-                                                int oy0, int ox0, int wave, int i16, int kq) {
-#define DLL_EPI(ACT_, POOL_) engine_epilogue_as<NT, RP, ACT_, POOL_>(a, acc, n, ko0, oy0, ox0, wave, i16, kq)
+__device__ __forceinline__ void engine_epilogue(const ConvEngineArgs &a, floatx4 (&acc)[RP][4][NT], const float (&bias)[NT],
+                                                int n, int ko0, int oy0, int ox0, int wave, int i16, int kq) {
+#define DLL_EPI(ACT_, POOL_) engine_epilogue_as<NT, RP, ACT_, POOL_>(a, acc, bias, n, ko0, oy0, ox0, wave, i16, kq)
   if (a.pool == 2) {
     if (a.act == ACT_RELU) DLL_EPI(ACT_RELU, 2);
     else if (a.act == ACT_SIGMOID) DLL_EPI(ACT_SIGMOID, 2);
@@ -334,7 +346,9 @@ __global__ __launch_bounds__(kThreads) void conv_engine_kernel(const EngineParam
     }
   }
 
-  engine_epilogue<NT, RP>(a, acc, n, ko0, oy0, ox0, wave, i16, kq);
+  float bias_v[NT];
+  lane_bias<NT>(a, ko0, i16, bias_v);
+  engine_epilogue<NT, RP>(a, acc, bias_v, n, ko0, oy0, ox0, wave, i16, kq);
 }
 
 inline int round_up_mod(int v, int m, int r) {  // smallest value >= v congruent to r mod m
@@ -662,6 +676,8 @@ __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void 
   };
 
   floatx4 acc[RP][4][NT];
+  float bias_v[NT];
+  lane_bias<NT>(a, ko0, i16, bias_v);
   const int gq = i16 >> 2, wa = (i16 >> 1) & 1, wb = i16 & 1;
   const float *a_ptr = xs + kq * PS + (wave * 2 * RP + wa) * RS + 8 * gq + wb + 1;
   const float *b_ptr = wl + kq * 16 + i16;
@@ -803,9 +819,9 @@ __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void 
       const int tx = tile % g.tiles_x;
       const int ty = (tile / g.tiles_x) % g.tiles_y;
       const int n = tile / (g.tiles_x * g.tiles_y);
-      if constexpr (EPI == 1) engine_epilogue_as<NT, RP, ACT_RELU, 2>(a, acc, n, ko0, ty * TH, tx * kTileW, wave, i16, kq);
-      else if constexpr (EPI == 2) engine_epilogue_as<NT, RP, ACT_IDENTITY, 1>(a, acc, n, ko0, ty * TH, tx * kTileW, wave, i16, kq);
-      else engine_epilogue<NT, RP>(a, acc, n, ko0, ty * TH, tx * kTileW, wave, i16, kq);
+      if constexpr (EPI == 1) engine_epilogue_as<NT, RP, ACT_RELU, 2>(a, acc, bias_v, n, ko0, ty * TH, tx * kTileW, wave, i16, kq);
+      else if constexpr (EPI == 2) engine_epilogue_as<NT, RP, ACT_IDENTITY, 1>(a, acc, bias_v, n, ko0, ty * TH, tx * kTileW, wave, i16, kq);
+      else engine_epilogue<NT, RP>(a, acc, bias_v, n, ko0, ty * TH, tx * kTileW, wave, i16, kq);
     }
     q = qn;
   }

@@ -582,36 +582,60 @@ __global__ __launch_bounds__(kThreads) void colsum_kernel(const float *A, int M,
 }
 
 // One workgroup per sample: p = softmax(logits) with the row maximum subtracted,
-// rowloss = -ln p[label], dlogits = (p - onehot) / B.
+// rowloss = -ln p[label], dlogits = (p - onehot) / B.  Rows of up to kRowCache classes are kept
+// in LDS between the passes; longer rows are read back from `logits`.
+constexpr int kRowCache = 4096;
 __global__ __launch_bounds__(kThreads) void softmax_ce_kernel(float *logits, const int *labels, int B, int classes,
                                                              float *dlogits, float *rowloss, const float *partial,
                                                              int split_k, const float *bias) {
   __shared__ float sh[kThreads];
+  __shared__ float cache[kRowCache];
   const int n = blockIdx.x, tid = threadIdx.x;
   float *row = logits + (long)n * classes;
+  const bool cached = classes <= kRowCache;
   if (partial) {   // the product's split-K partials, added in split order, then the bias
     const long total = (long)B * classes;
-    for (int j = tid; j < classes; j += kThreads) {
-      float c = 0.0f;
-      for (int z = 0; z < split_k; ++z) c += partial[(long)z * total + (long)n * classes + j];
-      if (bias) c += bias[j];
-      row[j] = c;
+    const float *p0 = partial + (long)n * classes;
+    // four classes per thread and pass: their loads of several splits are in flight together,
+    // the additions keep the split order
+    for (int j0 = tid; j0 < classes; j0 += 4 * kThreads) {
+      float c[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll 4
+      for (int z = 0; z < split_k; ++z) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int j = j0 + q * kThreads;
+          if (j < classes) c[q] += p0[(long)z * total + j];
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int j = j0 + q * kThreads;
+        if (j < classes) {
+          const float v = bias ? c[q] + bias[j] : c[q];
+          row[j] = v;
+          if (cached) cache[j] = v;
+        }
+      }
     }
-    __syncthreads();   // the row is complete (and visible to the whole workgroup) before it is read back
+  } else if (cached) {
+    for (int j = tid; j < classes; j += kThreads) cache[j] = row[j];
   }
+  __syncthreads();   // the row is complete (and visible to the whole workgroup) before it is read back
+  const float *r = cached ? cache : row;
   float m = -INFINITY;
-  for (int j = tid; j < classes; j += kThreads) m = fmaxf(m, row[j]);
+  for (int j = tid; j < classes; j += kThreads) m = fmaxf(m, r[j]);
   m = block_reduce(m, sh, true);
   float s = 0.0f;
-  for (int j = tid; j < classes; j += kThreads) s += expf(row[j] - m);
+  for (int j = tid; j < classes; j += kThreads) s += expf(r[j] - m);
   s = block_reduce(s, sh, false);
   const int label = labels[n];
   const float inv = 1.0f / s, invB = 1.0f / (float)B;
   for (int j = tid; j < classes; j += kThreads) {
-    const float pj = expf(row[j] - m) * inv;
+    const float pj = expf(r[j] - m) * inv;
     dlogits[(long)n * classes + j] = (pj - (j == label ? 1.0f : 0.0f)) * invB;
   }
-  if (tid == 0) rowloss[n] = -(row[label] - m - logf(s));
+  if (tid == 0) rowloss[n] = -(r[label] - m - logf(s));
 }
 
 // One workgroup per sample: prob = softmax(logits) with the row maximum subtracted.
