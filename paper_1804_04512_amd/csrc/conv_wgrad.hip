@@ -518,15 +518,26 @@ __device__ __forceinline__ void wgrad_reduce_block(const WgradReduceArgs &a, con
     }
   } else {
     const int k = (blk - nblk_dw) * 16 + 4 * t4;
-    for (int pidx = slice; pidx < plan.n_partials; pidx += kRedSlices) {
+    // same scheme: the loads of four partial blocks are issued before anything is added
+    for (int p0 = slice; p0 < plan.n_partials; p0 += 4 * kRedSlices) {
+      float pv[4][4], nv[4][4];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        if (k + j < a.K) {
-          double t = (double)a.pos[plan.db_offset + (long)pidx * a.K + k + j];
-          if (a.neg) t -= (double)a.neg[plan.db_offset + (long)pidx * a.K + k + j];
-          sum[j] += t;
+      for (int u = 0; u < 4; ++u) {
+        const int pidx = p0 + u * kRedSlices;
+        const bool in = pidx < plan.n_partials;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const bool ok = in && k + j < a.K;
+          const long o = plan.db_offset + (ok ? (long)pidx * a.K + k + j : 0);
+          pv[u][j] = a.pos[o];
+          nv[u][j] = a.neg ? a.neg[o] : 0.0f;
+          if (!ok) { pv[u][j] = 0.0f; nv[u][j] = 0.0f; }
         }
       }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) sum[j] += (double)pv[u][j] - (double)nv[u][j];
     }
   }
 #pragma unroll

@@ -566,6 +566,7 @@ __global__ __launch_bounds__(kThreads) void gemm_splitk_reduce_kernel(const Gemm
   for (long e = (long)blockIdx.x * kThreads + threadIdx.x; e < total; e += (long)gridDim.x * kThreads) {
     const int m = (int)(e / a.N), n = (int)(e - (long)m * a.N);
     float c = 0.0f;
+#pragma unroll 8
     for (int z = 0; z < a.split_k; ++z) c += a.partial[(long)z * total + e];
     if (a.bias) c += a.bias[n];
     c = act_apply(a.act, c);
@@ -573,6 +574,34 @@ __global__ __launch_bounds__(kThreads) void gemm_splitk_reduce_kernel(const Gemm
     if (a.C_ref) c *= act_deriv(a.c_ref_act, a.C_ref[o]);
     if (a.Cout) a.Cout[o] = c;
     if (a.update) update_param(a.update + o, a.vel ? a.vel + o : nullptr, c, a.step, a.mu, a.decay);
+  }
+}
+
+// The same for rows of whole 16-byte groups (N, c_m multiples of 4, c_n = 1, aligned bases): four
+// neighbouring elements per thread, the loads of several splits in flight, additions in split order.
+__global__ __launch_bounds__(kThreads) void gemm_splitk_reduce4_kernel(const GemmArgs a) {
+  const long total = (long)a.M * a.N, groups = total / 4;
+  for (long g = (long)blockIdx.x * kThreads + threadIdx.x; g < groups; g += (long)gridDim.x * kThreads) {
+    const long e = 4 * g;
+    const int m = (int)(e / a.N), n = (int)(e - (long)m * a.N);
+    float c[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll 8
+    for (int z = 0; z < a.split_k; ++z) {
+      const float4 v = *reinterpret_cast<const float4 *>(a.partial + (long)z * total + e);
+      c[0] += v.x; c[1] += v.y; c[2] += v.z; c[3] += v.w;
+    }
+    const long o = (long)m * a.c_m + n;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      if (a.bias) c[v] += a.bias[n + v];
+      c[v] = act_apply(a.act, c[v]);
+      if (a.C_ref) c[v] *= act_deriv(a.c_ref_act, a.C_ref[o + v]);
+    }
+    if (a.Cout) *reinterpret_cast<float4 *>(a.Cout + o) = make_float4(c[0], c[1], c[2], c[3]);
+    if (a.update) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) update_param(a.update + o + v, a.vel ? a.vel + o + v : nullptr, c[v], a.step, a.mu, a.decay);
+    }
   }
 }
 
@@ -747,9 +776,11 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream) {
   if (e != hipSuccess) return e;
   if (p.a.split_k > 1 && !a.defer_reduce) {
     const long total = (long)a.M * a.N;
-    long blocks = (total + kThreads - 1) / kThreads;
+    const bool vec = a.N % 4 == 0 && a.c_n == 1 && a.c_m % 4 == 0 && al16(a.partial) && (!a.Cout || al16(a.Cout));
+    long blocks = ((vec ? total / 4 : total) + kThreads - 1) / kThreads;
     if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL(gemm_splitk_reduce_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, p.a);
+    if (vec) hipLaunchKernelGGL(gemm_splitk_reduce4_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, p.a);
+    else hipLaunchKernelGGL(gemm_splitk_reduce_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, p.a);
     e = hipGetLastError();
   }
   return e;
