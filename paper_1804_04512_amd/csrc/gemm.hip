@@ -44,17 +44,6 @@ __device__ __forceinline__ float act_deriv(int act, float out) {
   return 1.0f;
 }
 
-__device__ __forceinline__ float4 load4(const float *src, long base, long stride, int i0, int limit, bool inrange, bool vec) {
-  float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (!inrange) return r;
-  if (vec && i0 + 3 < limit) return *reinterpret_cast<const float4 *>(src + base);
-  if (i0 < limit) r.x = src[base];
-  if (i0 + 1 < limit) r.y = src[base + stride];
-  if (i0 + 2 < limit) r.z = src[base + 2 * stride];
-  if (i0 + 3 < limit) r.w = src[base + 3 * stride];
-  return r;
-}
-
 // One operand tile (XT along x, 32 along k) travels global -> registers -> LDS.  A thread
 // carries groups of four elements that are neighbours along the source's contiguous axis:
 // k-contiguous sources land in LDS as [x][34], x-contiguous ones as [k][XT+16]; both layouts
@@ -63,28 +52,54 @@ template <int XT>
 struct TileRegs {
   static constexpr int NV = XT * BK / 4 / kThreads;   // float4 per thread: 4 (XT = 128) or 2 (XT = 64)
   float4 v[NV];
+  unsigned valid;   // generic loader: bit 4*it + e is set when element e of group `it` lies inside the operand
 };
 
-// Generic path: any strides, any alignment, ragged edges (element-wise with range checks).
+// Generic path: any strides, any alignment, ragged edges.  Every load is issued unconditionally
+// from a clamped address (element 0 of the operand stands in for anything out of range) and the
+// out-of-range elements are zeroed only when the tile is written to LDS: a load under a per-lane
+// branch, or one whose value is touched right away, is waited for before the next one is issued,
+// and a k-tile would cost as many memory round trips as it has groups.
 template <int XT>
 __device__ __forceinline__ void tile_load(TileRegs<XT> &t, const float *src, long sx, long sk, int x0, int k0, int X,
                                           int Kend, bool kcontig, bool vec) {
+  constexpr int NV = TileRegs<XT>::NV;
+  constexpr int TPR = XT / 4, RPP = kThreads / TPR;
   const int tid = threadIdx.x;
+  const long stride = kcontig ? sk : sx;
+  const int limit = kcontig ? Kend : X;
+  long base[NV];
+  int i0[NV];
+  bool inr[NV];
 #pragma unroll
-  for (int it = 0; it < TileRegs<XT>::NV; ++it) {
-    float4 v;
-    if (kcontig) {
-      const int x = x0 + (tid >> 3) + 32 * it, k = k0 + 4 * (tid & 7);
-      const long base = (long)x * sx + (long)k * sk;
-      v = load4(src, base, sk, k, Kend, x < X, vec);
-    } else {
-      constexpr int TPR = XT / 4, RPP = kThreads / TPR;
-      const int x = x0 + 4 * (tid % TPR), k = k0 + (tid / TPR) + RPP * it;
-      const long base = (long)x * sx + (long)k * sk;
-      v = load4(src, base, sx, x, X, k < Kend, vec);
-    }
-    t.v[it] = v;
+  for (int it = 0; it < NV; ++it) {
+    const int x = kcontig ? x0 + (tid >> 3) + 32 * it : x0 + 4 * (tid % TPR);
+    const int k = kcontig ? k0 + 4 * (tid & 7) : k0 + (tid / TPR) + RPP * it;
+    base[it] = (long)x * sx + (long)k * sk;
+    i0[it] = kcontig ? k : x;
+    inr[it] = kcontig ? x < X : k < Kend;
   }
+  unsigned valid = 0;
+  if (vec && (limit & 3) == 0) {   // uniform: whole aligned 16-byte groups, each entirely in or out of range
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      const bool ok = inr[it] && i0[it] < limit;
+      t.v[it] = *reinterpret_cast<const float4 *>(src + (ok ? base[it] : 0));
+      valid |= ok ? (0xFu << (4 * it)) : 0u;
+    }
+  } else {
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      const bool e0 = inr[it] && i0[it] < limit, e1 = inr[it] && i0[it] + 1 < limit, e2 = inr[it] && i0[it] + 2 < limit,
+                 e3 = inr[it] && i0[it] + 3 < limit;
+      t.v[it].x = src[e0 ? base[it] : 0];
+      t.v[it].y = src[e1 ? base[it] + stride : 0];
+      t.v[it].z = src[e2 ? base[it] + 2 * stride : 0];
+      t.v[it].w = src[e3 ? base[it] + 3 * stride : 0];
+      valid |= ((e0 ? 1u : 0u) | (e1 ? 2u : 0u) | (e2 ? 4u : 0u) | (e3 ? 8u : 0u)) << (4 * it);
+    }
+  }
+  t.valid = valid;
 }
 
 template <int XT>
@@ -92,13 +107,16 @@ __device__ __forceinline__ void tile_store(const TileRegs<XT> &t, float *dst, bo
   const int tid = threadIdx.x;
 #pragma unroll
   for (int it = 0; it < TileRegs<XT>::NV; ++it) {
+    const unsigned m = t.valid >> (4 * it);
+    const float4 v = make_float4((m & 1u) ? t.v[it].x : 0.f, (m & 2u) ? t.v[it].y : 0.f, (m & 4u) ? t.v[it].z : 0.f,
+                                 (m & 8u) ? t.v[it].w : 0.f);
     if (kcontig) {
       float2 *d = reinterpret_cast<float2 *>(dst + ((tid >> 3) + 32 * it) * LDK + 4 * (tid & 7));
-      d[0] = make_float2(t.v[it].x, t.v[it].y);
-      d[1] = make_float2(t.v[it].z, t.v[it].w);
+      d[0] = make_float2(v.x, v.y);
+      d[1] = make_float2(v.z, v.w);
     } else {
       constexpr int TPR = XT / 4, RPP = kThreads / TPR;
-      *reinterpret_cast<float4 *>(dst + ((tid / TPR) + RPP * it) * (XT + 16) + 4 * (tid % TPR)) = t.v[it];
+      *reinterpret_cast<float4 *>(dst + ((tid / TPR) + RPP * it) * (XT + 16) + 4 * (tid % TPR)) = v;
     }
   }
 }
@@ -212,10 +230,35 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(const GemmParams p) {
       }
   }
 
-  // lane holds C(m = i16, n = 4*kq + v) of each 16x16 tile
+  // lane holds C(m = i16, n = 4*kq + v) of each 16x16 tile; bias values and (per row) reference
+  // outputs come in batches through clamped indices, never behind a per-element branch
+  float bv[2][4];
+  const bool direct = a.split_k == 1;
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) bv[j][v] = (direct && a.bias) ? a.bias[min(n0 + wn + j * 16 + 4 * kq + v, a.N - 1)] : 0.0f;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int m = m0 + wm + i * 16 + i16;
+    float rv[2][4];
+    if (direct && a.C_ref) {
+      const long om = (long)min(m, a.M - 1) * a.c_m;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) rv[j][v] = a.C_ref[om + (long)min(n0 + wn + j * 16 + 4 * kq + v, a.N - 1) * a.c_n];
+    }
+    // momentum: the row's two velocity groups, requested together from clamped addresses
+    float4 velp[2];
+    if (a.update && a.vel && p.c_vec && direct) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int n = n0 + wn + j * 16 + 4 * kq;
+        const bool ok = m < a.M && n + 3 < a.N;
+        velp[j] = *reinterpret_cast<const float4 *>(a.vel + (ok ? (long)m * a.c_m + (long)n * a.c_n : 0));
+      }
+    }
     if (m >= a.M) continue;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -234,18 +277,17 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(const GemmParams p) {
         continue;
       }
 #pragma unroll
-      for (int v = 0; v < 4; ++v) c[v] = act_apply(a.act, c[v] + ((a.bias && n + v < a.N) ? a.bias[n + v] : 0.0f));
+      for (int v = 0; v < 4; ++v) c[v] = act_apply(a.act, c[v] + bv[j][v]);
       const long o = (long)m * a.c_m + (long)n * a.c_n;
       if (a.C_ref) {
 #pragma unroll
-        for (int v = 0; v < 4; ++v)
-          if (n + v < a.N) c[v] *= act_deriv(a.c_ref_act, a.C_ref[o + v * a.c_n]);
+        for (int v = 0; v < 4; ++v) c[v] *= act_deriv(a.c_ref_act, rv[j][v]);
       }
       if (p.c_vec && n + 3 < a.N) {
         if (a.Cout) *reinterpret_cast<float4 *>(a.Cout + o) = make_float4(c[0], c[1], c[2], c[3]);
         if (a.update) {
           float4 u = upd[i][j];   // requested before the epilogue loop, all eight at once
-          float4 vv = a.vel ? *reinterpret_cast<const float4 *>(a.vel + o) : make_float4(0.f, 0.f, 0.f, 0.f);
+          float4 vv = a.vel ? velp[j] : make_float4(0.f, 0.f, 0.f, 0.f);
           float *vp = a.vel ? &vv.x : nullptr;
           update_param(&u.x, vp, c[0], a.step, a.mu, a.decay); update_param(&u.y, vp ? vp + 1 : nullptr, c[1], a.step, a.mu, a.decay);
           update_param(&u.z, vp ? vp + 2 : nullptr, c[2], a.step, a.mu, a.decay); update_param(&u.w, vp ? vp + 3 : nullptr, c[3], a.step, a.mu, a.decay);
@@ -470,15 +512,42 @@ __global__ __launch_bounds__(kThreads, 3) void gemm_fast_kernel(const GemmParams
 
   // lane holds C(m = i16, n = 4*kq + v) of each 16x16 tile
   auto epilogue = [&](const UnitPos &u) __attribute__((always_inline)) {
+    const bool direct = a.split_k == 1;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int m = u.m0 + wm + i * 16 + i16;
+      // momentum: the row's two velocity groups, requested together from clamped addresses
+      float4 velp[2];
+      if (upd_mode && a.vel) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int n = u.n0 + wn + j * 16 + 4 * kq;
+          const bool ok = m < a.M && n + 3 < a.N;
+          velp[j] = *reinterpret_cast<const float4 *>(a.vel + (ok ? (long)m * a.c_m + (long)n * a.c_n : 0));
+        }
+      }
       if (m >= a.M) continue;
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         const int n = u.n0 + wn + j * 16 + 4 * kq;
         if (n >= a.N) continue;
         float c[4] = {acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]};
+        // the group's bias values and reference outputs: eight loads issued together through clamped
+        // 32-bit offsets from uniform bases (the launcher checks that C's extent fits), none of them
+        // behind a per-element branch, which would make each wait for the one before
+        float bv[4] = {0.0f, 0.0f, 0.0f, 0.0f}, rv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (direct && a.bias) {
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            bv[v] = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(a.bias) + 4u * (unsigned)min(n + v, a.N - 1));
+        }
+        if (direct && a.C_ref) {
+          const unsigned om = (unsigned)m * (unsigned)a.c_m;
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            rv[v] = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(a.C_ref) +
+                                                     4u * (om + (unsigned)min(n + v, a.N - 1) * (unsigned)a.c_n));
+        }
         if (a.split_k > 1) {
           float *d = a.partial + ((long)u.z * a.M + m) * a.N + n;
           if (n + 3 < a.N && (a.N & 3) == 0) {
@@ -491,19 +560,18 @@ __global__ __launch_bounds__(kThreads, 3) void gemm_fast_kernel(const GemmParams
           continue;
         }
 #pragma unroll
-        for (int v = 0; v < 4; ++v) c[v] = act_apply(a.act, c[v] + ((a.bias && n + v < a.N) ? a.bias[n + v] : 0.0f));
+        for (int v = 0; v < 4; ++v) c[v] = act_apply(a.act, c[v] + bv[v]);
         const long o = (long)m * a.c_m + (long)n * a.c_n;
         if (a.C_ref) {
 #pragma unroll
-          for (int v = 0; v < 4; ++v)
-            if (n + v < a.N) c[v] *= act_deriv(a.c_ref_act, a.C_ref[o + v * a.c_n]);
+          for (int v = 0; v < 4; ++v) c[v] *= act_deriv(a.c_ref_act, rv[v]);
         }
         if (p.c_vec && n + 3 < a.N) {
           if (a.Cout) *reinterpret_cast<float4 *>(a.Cout + o) = make_float4(c[0], c[1], c[2], c[3]);
           if (a.update) {
             float4 w4 = upd[i][j];
-            if (a.vel) {   // momentum: the velocity tile is read here (the plain update stays the fast path)
-              float4 vv = *reinterpret_cast<const float4 *>(a.vel + o);
+            if (a.vel) {
+              float4 vv = upd_mode ? velp[j] : *reinterpret_cast<const float4 *>(a.vel + o);
               update_param(&w4.x, &vv.x, c[0], a.step, a.mu, a.decay); update_param(&w4.y, &vv.y, c[1], a.step, a.mu, a.decay);
               update_param(&w4.z, &vv.z, c[2], a.step, a.mu, a.decay); update_param(&w4.w, &vv.w, c[3], a.step, a.mu, a.decay);
               *reinterpret_cast<float4 *>(a.vel + o) = vv;
@@ -625,23 +693,41 @@ __global__ __launch_bounds__(kThreads) void softmax_ce_kernel(float *logits, con
   if (partial) {   // the product's split-K partials, added in split order, then the bias
     const long total = (long)B * classes;
     const float *p0 = partial + (long)n * classes;
-    // four classes per thread and pass: their loads of several splits are in flight together,
-    // the additions keep the split order
+    // four classes per thread and pass, four splits per round: sixteen loads are in flight
+    // together, none of them behind a branch (a thread past the end of the row re-reads the last
+    // class and drops the result); the additions keep the split order
     for (int j0 = tid; j0 < classes; j0 += 4 * kThreads) {
-      float c[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll 4
-      for (int z = 0; z < split_k; ++z) {
+      int jq[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int j = j0 + q * kThreads;
-          if (j < classes) c[q] += p0[(long)z * total + j];
-        }
+      for (int q = 0; q < 4; ++q) jq[q] = min(j0 + q * kThreads, classes - 1);
+      float c[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      int z = 0;
+      for (; z + 4 <= split_k; z += 4) {
+        float v[4][4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) v[u][q] = p0[(long)(z + u) * total + jq[q]];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) c[q] += v[u][q];
       }
+      for (; z < split_k; ++z) {
+        float v[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = p0[(long)z * total + jq[q]];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) c[q] += v[q];
+      }
+      float bq[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) bq[q] = bias ? bias[jq[q]] : 0.0f;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int j = j0 + q * kThreads;
         if (j < classes) {
-          const float v = bias ? c[q] + bias[j] : c[q];
+          const float v = bias ? c[q] + bq[q] : c[q];
           row[j] = v;
           if (cached) cache[j] = v;
         }
@@ -757,7 +843,8 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream) {
   const bool a_kc = a.a_k == 1, b_kc = a.b_k == 1;
   const auto extent = [](long n0, long s0, long n1, long s1) { return 4 * ((n0 - 1) * s0 + (n1 - 1) * s1 + 4); };
   const bool small = extent(a.M, a.a_m, a.Kdim, a.a_k) < (1L << 32) && extent(a.N, a.b_n, a.Kdim, a.b_k) < (1L << 32) &&
-                     a.a_m >= 0 && a.a_k >= 0 && a.b_n >= 0 && a.b_k >= 0;
+                     extent(a.M, a.c_m, a.N, a.c_n) < (1L << 32) && a.a_m >= 0 && a.a_k >= 0 && a.b_n >= 0 && a.b_k >= 0 &&
+                     a.c_m >= 0 && a.c_n >= 0;
   const bool fast = small && p.a_vec && p.b_vec && (a_kc ? a.Kdim % 4 == 0 : a.M % 4 == 0) &&
                     (b_kc ? a.Kdim % 4 == 0 : a.N % 4 == 0);
   if (!fast) {
