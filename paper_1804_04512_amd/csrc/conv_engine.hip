@@ -75,28 +75,6 @@ __device__ __forceinline__ float pooled_dz(int act, float g, float out, unsigned
 }
 __host__ __device__ __forceinline__ bool reads_output(int act) { return act == ACT_SIGMOID || act == ACT_RELU; }
 
-// dz at pre-pool position (i,j) of plane (n,k): dy routed to the recorded arg-max, times act'(y).
-__device__ __forceinline__ float dz_value(const ConvEngineArgs &a, int n, int k, int i, int j) {
-  int o;
-  if (a.src_pool == 2) {
-    const int Hp = a.Hin >> 1, Wp = a.Win >> 1;
-    o = ((n * a.Cin + k) * Hp + (i >> 1)) * Wp + (j >> 1);
-    const unsigned char f = a.src_idx[o];
-    if ((f & kIdxPosMask) != (unsigned char)(((i & 1) << 1) | (j & 1))) return 0.0f;
-    if (a.src_act == ACT_RELU_FLAGGED) return (f & kIdxInactive) ? 0.0f : a.src[o];
-  } else {
-    o = ((n * a.Cin + k) * a.Hin + i) * a.Win + j;
-  }
-  float g = a.src[o];
-  if (a.src_act == ACT_SIGMOID) {
-    const float v = a.src_y[o];
-    g *= v * (1.0f - v);
-  } else if (a.src_act == ACT_RELU) {
-    if (!(a.src_y[o] > 0.0f)) g = 0.0f;
-  }
-  return g;
-}
-
 // The lane's bias values, one per N-tile (output channel ko0 + 16nt + i16).  Read once per
 // workgroup, ahead of the tile loop: a load inside the epilogue would be waited for on the spot,
 // together with every prefetch load issued before it.
@@ -290,20 +268,34 @@ __global__ __launch_bounds__(kThreads) void conv_engine_kernel(const EngineParam
   for (int chunk = 0; chunk < g.nchunks; ++chunk) {
     const int c0 = chunk * g.CC;
     __syncthreads();  // previous chunk's readers are done
+    // Both staging loops work in batches of kStage elements per thread: all addresses first, then all
+    // loads, unconditionally and from clamped addresses (element 0 stands in for anything that is
+    // padding or out of range), then the selects and the LDS stores.  A load behind a per-lane
+    // branch would be waited for before the next one is issued.
+    constexpr int kStage = 4;
     // ---- filter slice: wl[nt][kk][j] = wgt(ko0 + 16nt + j, c0 + cl, r, s)
-    for (int e = tid; e < NT * g.KC * 16; e += kThreads) {
-      const int j = e & 15;
-      const int q = e >> 4;
-      const int kk = q % g.KC, nt = q / g.KC;
-      const int cl = kk % g.CC, rs = kk / g.CC;
-      const int r = rs / a.S, s = rs - r * a.S;
-      const int ko = ko0 + nt * 16 + j, ci = c0 + cl;
-      float v = 0.0f;
-      if (rs < RSf && ko < a.Kout && ci < a.Cin) {
-        v = a.w_flip ? a.w[((ci * a.Kout + ko) * a.R + (a.R - 1 - r)) * a.S + (a.S - 1 - s)]
-                     : a.w[((ko * a.Cin + ci) * a.R + r) * a.S + s];
+    for (int e0 = tid; e0 < NT * g.KC * 16; e0 += kStage * kThreads) {
+      float v[kStage];
+      bool ok[kStage];
+#pragma unroll
+      for (int u = 0; u < kStage; ++u) {
+        const int e = e0 + u * kThreads;
+        const int j = e & 15;
+        const int q = e >> 4;
+        const int kk = q % g.KC, nt = q / g.KC;
+        const int cl = kk % g.CC, rs = kk / g.CC;
+        const int r = rs / a.S, s = rs - r * a.S;
+        const int ko = ko0 + nt * 16 + j, ci = c0 + cl;
+        ok[u] = e < NT * g.KC * 16 && rs < RSf && ko < a.Kout && ci < a.Cin;
+        const int o = a.w_flip ? ((ci * a.Kout + ko) * a.R + (a.R - 1 - r)) * a.S + (a.S - 1 - s)
+                               : ((ko * a.Cin + ci) * a.R + r) * a.S + s;
+        v[u] = a.w[ok[u] ? o : 0];
       }
-      wl[e] = v;
+#pragma unroll
+      for (int u = 0; u < kStage; ++u) {
+        const int e = e0 + u * kThreads;
+        if (e < NT * g.KC * 16) wl[e] = ok[u] ? v[u] : 0.0f;
+      }
     }
     // ---- halo tile of the source, zero outside the image (padding) and past Cin
     {
@@ -312,40 +304,88 @@ __global__ __launch_bounds__(kThreads) void conv_engine_kernel(const EngineParam
       int q = tid / g.cols;
       int row = q % g.rows, cl = q / g.rows;
       const int dcol = kThreads % g.cols, dq = kThreads / g.cols;
-      for (int e = tid; e < total; e += kThreads) {
-        const int gi = oy0 - a.pad_h + row, gj = ox0 - a.pad_w + col, ci = c0 + cl;
-        float v = 0.0f;
-        if (ci < a.Cin && gi >= 0 && gi < a.Hin && gj >= 0 && gj < a.Win) {
-          v = a.src_dz ? dz_value(a, n, ci, gi, gj) : a.src[((n * a.Cin + ci) * a.Hin + gi) * a.Win + gj];
+      const int Hp = a.Hin >> 1, Wp = a.Win >> 1;   // pooled dz sources only
+      const bool pooled = a.src_dz && a.src_pool == 2;
+      const bool need_y = a.src_dz && reads_output(a.src_act);
+      for (int e0 = tid; e0 < total; e0 += kStage * kThreads) {
+        float gv[kStage], yv[kStage];
+        unsigned char fv[kStage];
+        bool ok[kStage];
+        int dst[kStage], want[kStage];
+#pragma unroll
+        for (int u = 0; u < kStage; ++u) {
+          const int gi = oy0 - a.pad_h + row, gj = ox0 - a.pad_w + col, ci = c0 + cl;
+          ok[u] = e0 + u * kThreads < total && ci < a.Cin && gi >= 0 && gi < a.Hin && gj >= 0 && gj < a.Win;
+          dst[u] = cl * g.PS + row * g.RS + col;
+          want[u] = ((gi & 1) << 1) | (gj & 1);
+          int o = pooled ? ((n * a.Cin + ci) * Hp + (gi >> 1)) * Wp + (gj >> 1) : ((n * a.Cin + ci) * a.Hin + gi) * a.Win + gj;
+          o = ok[u] ? o : 0;
+          gv[u] = a.src[o];
+          yv[u] = need_y ? a.src_y[o] : 0.0f;
+          fv[u] = pooled ? a.src_idx[o] : (unsigned char)0;
+          col += dcol;
+          row += dq;
+          if (col >= g.cols) { col -= g.cols; ++row; }
+          while (row >= g.rows) { row -= g.rows; ++cl; }
         }
-        xs[cl * g.PS + row * g.RS + col] = v;
-        col += dcol;
-        row += dq;
-        if (col >= g.cols) { col -= g.cols; ++row; }
-        while (row >= g.rows) { row -= g.rows; ++cl; }
+#pragma unroll
+        for (int u = 0; u < kStage; ++u) {
+          if (e0 + u * kThreads >= total) continue;
+          float v = gv[u];
+          if (a.src_dz) {
+            // dz at a pre-pool position: dy routed to the recorded arg-max, times act'(y)
+            if (pooled && (fv[u] & kIdxPosMask) != (unsigned char)want[u]) v = 0.0f;
+            if (a.src_act == ACT_RELU_FLAGGED) v = (fv[u] & kIdxInactive) ? 0.0f : v;
+            else if (a.src_act == ACT_SIGMOID) v *= yv[u] * (1.0f - yv[u]);
+            else if (a.src_act == ACT_RELU) v = yv[u] > 0.0f ? v : 0.0f;
+          }
+          xs[dst[u]] = ok[u] ? v : 0.0f;
+        }
       }
     }
     __syncthreads();
-    // ---- MFMA over the chunk's taps
-    for (int t = 0; t < g.KS; ++t) {
-      const int o = koff[4 * t + kq];
-      float bf[NT];
+    // ---- MFMA over the chunk's taps, software-pipelined over two register sets: while step t is
+    // multiplied, the operand fragments of step t+1 are on their way from LDS and the tap offset of
+    // step t+2 is being read (offset -> fragment -> MFMA is a chain of two LDS latencies that a
+    // plain loop would pay at every step).  Steps past the end re-read the last step and are not
+    // multiplied.
+    {
+      float afA[RP * 4], bfA[NT], afB[RP * 4], bfB[NT];
+      auto load_step = [&](int t, int o, float (&af)[RP * 4], float (&bf)[NT]) __attribute__((always_inline)) {
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) bf[nt] = wl[(nt * g.KC + 4 * t + kq) * 16 + i16];
+        for (int nt = 0; nt < NT; ++nt) bf[nt] = wl[(nt * g.KC + 4 * t + kq) * 16 + i16];
 #pragma unroll
-      for (int rp = 0; rp < RP; ++rp) {
-        const float *xr = xs + a_base + rp * 2 * g.RS + o;
+        for (int rp = 0; rp < RP; ++rp)
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-          const float af = xr[2 * mt];
+          for (int mt = 0; mt < 4; ++mt) af[rp * 4 + mt] = xs[a_base + rp * 2 * g.RS + o + 2 * mt];
+      };
+      auto mfma_step = [&](const float (&af)[RP * 4], const float (&bf)[NT]) __attribute__((always_inline)) {
 #pragma unroll
-          for (int nt = 0; nt < NT; ++nt)
-            acc[rp][mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(af, bf[nt], acc[rp][mt][nt], 0, 0, 0);
-        }
+        for (int rp = 0; rp < RP; ++rp)
+#pragma unroll
+          for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+              acc[rp][mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[rp * 4 + mt], bf[nt], acc[rp][mt][nt], 0, 0, 0);
+      };
+      const int last = g.KS - 1;
+      int o1 = koff[4 * min(1, last) + kq];
+      load_step(0, koff[kq], afA, bfA);
+      for (int t = 0; t < g.KS; t += 2) {
+        const int o2 = koff[4 * min(t + 2, last) + kq];
+        load_step(min(t + 1, last), o1, afB, bfB);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_step(afA, bfA);
+        __builtin_amdgcn_sched_barrier(0);
+        const int o3 = koff[4 * min(t + 3, last) + kq];
+        load_step(min(t + 2, last), o2, afA, bfA);
+        __builtin_amdgcn_sched_barrier(0);
+        if (t + 1 < g.KS) mfma_step(afB, bfB);
+        __builtin_amdgcn_sched_barrier(0);
+        o1 = o3;
       }
     }
   }
-
   float bias_v[NT];
   lane_bias<NT>(a, ko0, i16, bias_v);
   engine_epilogue<NT, RP>(a, acc, bias_v, n, ko0, oy0, ox0, wave, i16, kq);
