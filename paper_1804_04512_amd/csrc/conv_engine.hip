@@ -36,6 +36,7 @@ struct EngineGeom {
   int KC, KS;        // padded taps per chunk (multiple of 4), MFMA steps per chunk
   int tiles_x, tiles_y;
   int kgroups;       // groups of NT*16 output channels (gridDim.y)
+  int jw_log;        // generic kernel: log2 of the filter columns staged per N-tile (16, or fewer when Kout is small)
   unsigned src_bytes; // 3x3 instance: bytes of the source tensor (below 2 GiB)
   int pack3;          // 3x3 instance, three input channels: the 27 taps run as 7 MFMA steps, not 9
 };
@@ -234,6 +235,7 @@ __global__ __launch_bounds__(kThreads) void conv_engine_kernel(const EngineParam
   float *xs = lds;                                  // [CC][PS]
   float *wl = xs + g.CC * g.PS;                     // [NT][KC][16]
   int *koff = reinterpret_cast<int *>(wl + NT * g.KC * 16);  // [KC]
+  int2 *wtab = reinterpret_cast<int2 *>(koff + g.KC);        // [KC]: offset of tap kk inside a filter slice (-1: padding), channel
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i16 = lane & 15, kq = lane >> 4;
@@ -246,12 +248,20 @@ __global__ __launch_bounds__(kThreads) void conv_engine_kernel(const EngineParam
   const int oy0 = ty * TH, ox0 = tx * kTileW;       // pre-pool output origin of the tile
   const int RSf = a.R * a.S;
 
-  // tap offsets inside the halo tile: kk = (r*S + s)*CC + cl  ->  cl*PS + r*RS + s
+  // tap offsets inside the halo tile: kk = (r*S + s)*CC + cl  ->  cl*PS + r*RS + s, and inside the
+  // filter tensor relative to the chunk's first channel (rotated and transposed filters: w_flip)
   for (int kk = tid; kk < g.KC; kk += kThreads) {
     const int cl = kk % g.CC, rs = kk / g.CC;
     const int r = rs / a.S, s = rs - r * a.S;
     koff[kk] = rs < RSf ? cl * g.PS + r * g.RS + s : 0;
+    const int wo = a.w_flip ? cl * a.Kout * RSf + (a.R - 1 - r) * a.S + (a.S - 1 - s) : cl * RSf + r * a.S + s;
+    wtab[kk] = make_int2(rs < RSf ? wo : -1, cl);
   }
+  // Only the first 2^jw_log columns of a filter slice can be non-zero (Kout is small); the others
+  // are cleared once here and never written again.
+  const int jw = 1 << g.jw_log;
+  if (jw < 16)
+    for (int e = tid; e < NT * g.KC * 16; e += kThreads) wl[e] = 0.0f;
 
   floatx4 acc[RP][4][NT];
 #pragma unroll
@@ -273,29 +283,29 @@ __global__ __launch_bounds__(kThreads) void conv_engine_kernel(const EngineParam
     // padding or out of range), then the selects and the LDS stores.  A load behind a per-lane
     // branch would be waited for before the next one is issued.
     constexpr int kStage = 4;
-    // ---- filter slice: wl[nt][kk][j] = wgt(ko0 + 16nt + j, c0 + cl, r, s)
-    for (int e0 = tid; e0 < NT * g.KC * 16; e0 += kStage * kThreads) {
+    // ---- filter slice: wl[nt][kk][j] = wgt(ko0 + 16nt + j, c0 + cl, r, s) for the columns j < jw
+    const int f_total = NT * g.KC * jw;
+    const int w_base = a.w_flip ? c0 * a.Kout * RSf : c0 * RSf;   // + ko * RSf (flipped) or ko * Cin * RSf
+    const int w_ko = a.w_flip ? RSf : a.Cin * RSf;
+    for (int e0 = tid; e0 < f_total; e0 += kStage * kThreads) {
       float v[kStage];
       bool ok[kStage];
+      int dst[kStage];
 #pragma unroll
       for (int u = 0; u < kStage; ++u) {
-        const int e = e0 + u * kThreads;
-        const int j = e & 15;
-        const int q = e >> 4;
-        const int kk = q % g.KC, nt = q / g.KC;
-        const int cl = kk % g.CC, rs = kk / g.CC;
-        const int r = rs / a.S, s = rs - r * a.S;
-        const int ko = ko0 + nt * 16 + j, ci = c0 + cl;
-        ok[u] = e < NT * g.KC * 16 && rs < RSf && ko < a.Kout && ci < a.Cin;
-        const int o = a.w_flip ? ((ci * a.Kout + ko) * a.R + (a.R - 1 - r)) * a.S + (a.S - 1 - s)
-                               : ((ko * a.Cin + ci) * a.R + r) * a.S + s;
-        v[u] = a.w[ok[u] ? o : 0];
+        const int e = min(e0 + u * kThreads, f_total - 1);
+        const int j = e & (jw - 1);
+        int kk = e >> g.jw_log, nt = 0;
+        while (kk >= g.KC) { kk -= g.KC; ++nt; }   // at most NT - 1 rounds
+        const int2 t = wtab[kk];
+        const int ko = ko0 + nt * 16 + j;
+        ok[u] = t.x >= 0 && ko < a.Kout && c0 + t.y < a.Cin;
+        dst[u] = (nt * g.KC + kk) * 16 + j;
+        v[u] = a.w[ok[u] ? w_base + ko * w_ko + t.x : 0];
       }
 #pragma unroll
-      for (int u = 0; u < kStage; ++u) {
-        const int e = e0 + u * kThreads;
-        if (e < NT * g.KC * 16) wl[e] = ok[u] ? v[u] : 0.0f;
-      }
+      for (int u = 0; u < kStage; ++u)
+        if (e0 + u * kThreads < f_total) wl[dst[u]] = ok[u] ? v[u] : 0.0f;
     }
     // ---- halo tile of the source, zero outside the image (padding) and past Cin
     {
@@ -408,7 +418,7 @@ bool plan_engine(const ConvEngineArgs &a, int NT, int RP, EngineGeom *g, size_t 
     g->CC = CC;
     g->KC = (CC * a.R * a.S + 3) / 4 * 4;
     g->KS = g->KC / 4;
-    *lds_bytes = sizeof(float) * ((size_t)CC * g->PS + (size_t)NT * g->KC * 16 + g->KC);
+    *lds_bytes = sizeof(float) * ((size_t)CC * g->PS + (size_t)NT * g->KC * 16 + 3 * (size_t)g->KC);
     if (*lds_bytes <= 64 * 1024 || CC == 1) break;
     CC = (CC + 1) / 2;
   }
@@ -417,6 +427,9 @@ bool plan_engine(const ConvEngineArgs &a, int NT, int RP, EngineGeom *g, size_t 
   g->tiles_x = (a.Wout + kTileW - 1) / kTileW;
   g->tiles_y = (a.Hout + TH - 1) / TH;
   g->kgroups = (a.Kout + NT * 16 - 1) / (NT * 16);
+  g->jw_log = 4;
+  if (NT == 1 && a.Kout < 16)
+    while (g->jw_log > 0 && (1 << (g->jw_log - 1)) >= a.Kout) --g->jw_log;
   return true;
 }
 
