@@ -965,6 +965,10 @@ hipError_t launch_conv_engine(const ConvEngineArgs &a, hipStream_t stream) {
   const int nt = a.Kout <= 16 ? 1 : (a.Kout <= 32 ? 2 : 3);
   const long tiles16 = (long)a.N * ((a.Wout + kTileW - 1) / kTileW) * ((a.Hout + 15) / 16) * ((a.Kout + nt * 16 - 1) / (nt * 16));
   const bool small = a.Hout <= 8 || tiles16 < 512;
+  // very few output channels: the banded-filter kernel wins when its share of real products,
+  // S of every 4*ceil((16+S-1)/4) window columns, clearly beats Kout of 16 channel columns
+  if (a.Kout <= 3 && a.Kout * (4 * ((16 + a.S - 1 + 3) / 4)) * 3 < 16 * a.S * 2 && conv_fewout_applies(a))
+    return launch_conv_fewout(a, stream);
   if (a.Hout > 8 && conv3x3c16_applies(a)) {
     // 16 output channels: 4 waves x 2 row pairs; 32: 8 waves x 1 row pair (more waves hide the
     // longer per-step operand traffic better than more accumulators do)

@@ -67,6 +67,12 @@ struct ConvEngineArgs {
 
 hipError_t launch_conv_engine(const ConvEngineArgs &a, hipStream_t stream);
 
+// The same operation for at most three output channels (CRBM reconstruction, backward-data into a
+// grey-scale or RGB input): output columns instead of output channels ride on the MFMA N axis.
+// launch_conv_engine routes there by itself when it pays.
+bool conv_fewout_applies(const ConvEngineArgs &a);
+hipError_t launch_conv_fewout(const ConvEngineArgs &a, hipStream_t stream);
+
 // ---------------------------------------------------------------------------------------
 // Filter gradient: stage 1 leaves per-wave partial sums in `partial`, stage 2
 // (launch_wgrad_reduce) adds them in a fixed order.

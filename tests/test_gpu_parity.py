@@ -98,6 +98,10 @@ CASES = [
     ConvSpec(2, 2, 9, 14, 3, 2, 4, 0, "identity", 1),         # non-square filter
     ConvSpec(2, 4, 11, 9, 6, 1, 1, 0, "relu", 1),             # 1x1 filter, odd map
     ConvSpec(1, 40, 20, 20, 1, 9, 9, 0, "identity", 1),       # single filter, deep contraction
+    # few input channels: their backward-data pass has few OUTPUT channels and takes the banded-filter kernel
+    ConvSpec(3, 3, 20, 22, 6, 7, 7, 0, "sigmoid", 1),         # three channels, 14x16 maps back to 20x22: 2x2 tiles with tails
+    ConvSpec(2, 2, 19, 17, 5, 5, 5, 2, "relu", 1),            # two channels, padded, odd sizes
+    ConvSpec(2, 1, 16, 33, 20, 3, 5, 1, "identity", 1),       # one channel, non-square filter, 20 source channels = 3 rounds
 ]
 
 
