@@ -77,8 +77,8 @@ def engine_kernel_name(cs, backward: bool) -> str:
     chunked = cin % 16 == 0 or cin <= 12
     if same and chunked and hout > 8 and cs.W % (8 if backward and cs.pool == 2 else 4) == 0:
         src = 0 if not backward else (2 if cs.pool == 2 else 1)
-        cc = 16 if cin % 16 == 0 else 4
         nt = 1 if kout <= 16 else 2
+        cc = (8 if nt == 1 else 16) if cin % 16 == 0 else 4
         waves = 8 if (cc == 16 and nt == 2) else 4
         pack3 = "true" if (cc == 4 and cin == 3 and not backward) else "false"
         epi = 2 if backward else (1 if (cs.act == "relu" and cs.pool == 2) else 0)

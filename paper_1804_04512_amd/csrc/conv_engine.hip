@@ -462,11 +462,12 @@ hipError_t launch_t(const ConvEngineArgs &a, hipStream_t stream) {
 constexpr int round_up_mod_c(int v, int m, int r) { return (v - (v % m) + r) < v ? (v - (v % m) + r + m) : (v - (v % m) + r); }
 
 // waves per SIMD the register budget is held to: LDS lets 3 (16 filters) or 2 (32 filters)
-// workgroups of the 16-channel instance share a CU, 4 of the 4-channel one
-constexpr int conv3x3_occupancy(int NT, int WAVES, int CC) { return (CC == 4 ? 4 : (NT == 1 ? 3 : 2)) * WAVES / 4; }
+// workgroups of the 16-channel instance share a CU, 4 of the 8- and 4-channel ones
+constexpr int conv3x3_occupancy(int NT, int WAVES, int CC) { return (CC <= 8 ? 4 : (NT == 1 ? 3 : 2)) * WAVES / 4; }
 
-// SRC: 0 plain tensor, 1 dz without pooling, 2 dz through 2x2 pooling.  CC: channels per chunk,
-// 16, or 4 for shallow inputs such as RGB images (surplus channels are staged as zeros).
+// SRC: 0 plain tensor, 1 dz without pooling, 2 dz through 2x2 pooling.  CC: channels per chunk:
+// 16 (32 filters per workgroup), 8 (16 filters: the smaller tile lets a fourth workgroup share the
+// CU), or 4 for shallow inputs such as RGB images (surplus channels are staged as zeros).
 // EPI fixes the epilogue at compile time where the launcher knows it: 1 = bias + ReLU + 2x2 pool
 // (the forward pass of the networks this path is for), 2 = plain store (backward-data), 0 = decided
 // at run time (any activation, pooling or sampling).  The fixed forms keep the other epilogues'
@@ -590,8 +591,8 @@ __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void 
       const unsigned e = (unsigned)(pos + m_off);
 #pragma unroll
       for (int it = 0; it < NM; ++it) {
-        // 16-channel chunks are always whole (the launcher checks Cin % 16 == 0)
-        const bool okc = (CC == 16 && M_EXACT) ? ok : ok && it * M_CPR + m_c < (cleft < CC ? cleft : CC);
+        // 8- and 16-channel chunks are always whole (the launcher checks Cin % 16 == 0)
+        const bool okc = (CC >= 8 && M_EXACT) ? ok : ok && it * M_CPR + m_c < (cleft < CC ? cleft : CC);
         const unsigned so = base + (unsigned)it * M_CPR * plane;
         vm[it] = ld4(rs_src, okc ? 4u * e : kOob, 4u * so);
         if (need_y) ym[it] = ld4(rs_y, okc ? 4u * e : kOob, 4u * so);
@@ -614,7 +615,7 @@ __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void 
       const unsigned e = (unsigned)(pos + s_off);
 #pragma unroll
       for (int it = 0; it < NS; ++it) {
-        const bool okc = (CC == 16 && S_EXACT) ? ok : ok && it * S_CPR + s_c < (cleft < CC ? cleft : CC);
+        const bool okc = (CC >= 8 && S_EXACT) ? ok : ok && it * S_CPR + s_c < (cleft < CC ? cleft : CC);
         const unsigned so = base + (unsigned)it * S_CPR * plane;
         vs[it] = ld1(rs_src, okc ? 4u * e : kOob, 4u * so);
         if (need_y) ys[it] = ld1(rs_y, okc ? 4u * e : kOob, 4u * so);
@@ -827,6 +828,23 @@ __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void 
         a_tap = a_next;
         b_tap = b_next;
       }
+    } else if constexpr (C4 == 2) {
+      // 8-channel chunks: two steps per tap, the same two-set rotation
+#pragma unroll 1
+      for (int rs = 0; rs < 9; ++rs) {
+        const float *a_next = a_tap + ((rs % 3 == 2) ? RS - 2 : 1);
+        const float *b_next = b_tap + CC * 16;
+        load_frags(I1{}, a_tap, b_tap, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_frags(I0{});
+        __builtin_amdgcn_sched_barrier(0);
+        if (rs < 8) load_frags(I0{}, a_next, b_next, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_frags(I1{});
+        __builtin_amdgcn_sched_barrier(0);
+        a_tap = a_next;
+        b_tap = b_next;
+      }
     } else if constexpr (PACK3) {
       // three input channels: k = 4t + kq runs over (channel, tap) in the filter's order; the lane's
       // seven tile offsets were worked out once (a3), the filter rows are 64 floats apart
@@ -976,7 +994,7 @@ hipError_t launch_conv_engine(const ConvEngineArgs &a, hipStream_t stream) {
       if (a.Kout <= 16) return launch_3x3<1, 4, 4>(a, stream);
       return launch_3x3<2, 4, 4>(a, stream);
     }
-    if (a.Kout <= 16) return launch_3x3<1, 4, 16>(a, stream);
+    if (a.Kout <= 16) return launch_3x3<1, 4, 8>(a, stream);   // 8-channel chunks: four workgroups fit a CU's LDS instead of three
     return launch_3x3<2, 8, 16>(a, stream);   // wider layers run as groups of 32 output channels
   }
   if (small) {
