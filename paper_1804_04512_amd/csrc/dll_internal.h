@@ -140,6 +140,11 @@ struct GemmArgs {
 };
 int gemm_pick_split_k(int M, int N, int Kdim);
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream);
+// Small products (the dense layers of the MNIST/CIFAR-sized networks) take a kernel built for a
+// short latency chain instead: 32 x 32 tiles, the k range split between the wavefronts of a
+// workgroup, no split-K partials (gemm_pick_split_k returns 1 for them).  launch_gemm routes there.
+bool gemm_is_small(int M, int N, int Kdim);
+hipError_t launch_gemm_small(const GemmArgs &a, hipStream_t stream);
 
 // Column sums out[n] = sum_m A(m,n) of a row-major [M][N] array; optional update.
 hipError_t launch_colsum(const float *A, int M, int N, float *out,

@@ -818,6 +818,7 @@ __global__ __launch_bounds__(kThreads) void copy_kernel(const float *src, float 
 }  // namespace
 
 int gemm_pick_split_k(int M, int N, int Kdim) {
+  if (gemm_is_small(M, N, Kdim)) return 1;   // the small-product kernel splits k inside the workgroup
   const long tiles = (long)((M + BM - 1) / BM) * ((N + BN - 1) / BN);
   const int ksteps = (Kdim + BK - 1) / BK;
   int split = 1;
@@ -826,6 +827,7 @@ int gemm_pick_split_k(int M, int N, int Kdim) {
 }
 
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream) {
+  if (a.split_k <= 1 && gemm_is_small(a.M, a.N, a.Kdim)) return launch_gemm_small(a, stream);
   GemmParams p;
   p.a = a;
   if (p.a.split_k < 1) p.a.split_k = 1;

@@ -1,0 +1,191 @@
+// fp32 MFMA matrix product for SMALL problems: the dense layers of the paper's MNIST and CIFAR
+// networks and of the fully-connected RBM (Sections II-A, IV, V: a few hundred units, batch 100).
+//
+// Such a product cannot fill the chip; what it costs is a chain of latencies (launch, first
+// loads, one LDS round trip and one barrier per k-tile, a split-K reduction launch).  This kernel
+// shortens the chain instead of raising the rate:
+//   * 32 x 32 output tile per workgroup (many more workgroups than the 128 x 64 tiles of the big
+//     kernel, far fewer products with padding);
+//   * the four wavefronts split the k range BETWEEN them and each multiplies the whole tile, so
+//     there is no LDS staging and no barrier inside the k loop at all: every lane loads its
+//     MFMA fragments straight from global memory, the next k-tile's loads in flight while the
+//     current one is multiplied.  Inside a k-tile of 32, the lane with k-quarter kq owns the 8
+//     consecutive k values 8*kq .. 8*kq+7 of both operands (any assignment works as long as both
+//     operands use the same one), which makes a k-contiguous operand two 16-byte loads per row;
+//   * the four partial tiles meet in LDS once, are added in wavefront order (results do not
+//     depend on timing), and each wavefront finishes one 16 x 16 quarter: bias, activation,
+//     act' of a reference tensor, store and/or fused parameter update.  No split-K partials in
+//     global memory, no reduction launch.
+// Every global load is issued unconditionally from a clamped address and masked afterwards.
+#include "dll_internal.h"
+
+namespace dllk {
+namespace {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;
+constexpr int TS = 32;    // tile side
+constexpr int KT = 32;    // k-tile
+
+__device__ __forceinline__ float act_apply(int act, float z) {
+  if (act == ACT_SIGMOID) return 1.0f / (1.0f + expf(-z));
+  if (act == ACT_RELU) return z > 0.0f ? z : 0.0f;
+  return z;
+}
+__device__ __forceinline__ float act_deriv(int act, float out) {
+  if (act == ACT_SIGMOID) return out * (1.0f - out);
+  if (act == ACT_RELU) return out > 0.0f ? 1.0f : 0.0f;
+  return 1.0f;
+}
+
+struct SmallParams {
+  GemmArgs a;
+  int a_vec, b_vec;   // k-contiguous operand with aligned rows of whole 16-byte groups
+};
+
+// One operand's fragments of a k-tile: frag[t][s] = X(x0 + 16 t + i16, k0 + 8 kq + s), zero out of range.
+// X(x, k) = src[x * sx + k * sk].
+template <bool KC>
+__device__ __forceinline__ void load_frags(float (&frag)[2][8], const float *src, long sx, long sk, int x0, int X, int k0,
+                                           int Kdim, int i16, int kq, bool vec) {
+  const int k = k0 + 8 * kq;
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const int x = x0 + 16 * t + i16;
+    const bool xin = x < X;
+    const long base = xin ? (long)x * sx : 0;
+    if (KC && vec) {   // uniform: rows are whole aligned 16-byte groups, so a group is entirely in or out of range
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const bool ok = xin && k + 4 * h < Kdim;
+        const float4 v = *reinterpret_cast<const float4 *>(src + (ok ? base + k + 4 * h : 0));
+        frag[t][4 * h + 0] = ok ? v.x : 0.0f;
+        frag[t][4 * h + 1] = ok ? v.y : 0.0f;
+        frag[t][4 * h + 2] = ok ? v.z : 0.0f;
+        frag[t][4 * h + 3] = ok ? v.w : 0.0f;
+      }
+    } else {
+      float v[8];
+      bool ok[8];
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        ok[s] = xin && k + s < Kdim;
+        v[s] = src[ok[s] ? base + (long)(k + s) * sk : 0];
+      }
+#pragma unroll
+      for (int s = 0; s < 8; ++s) frag[t][s] = ok[s] ? v[s] : 0.0f;
+    }
+  }
+}
+
+template <bool A_KC, bool B_KC>
+__global__ __launch_bounds__(kThreads) void gemm_small_kernel(const SmallParams p) {
+  __shared__ __attribute__((aligned(16))) float red[4][4][64][4];   // [wavefront][quarter][lane][4]
+  const GemmArgs &a = p.a;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i16 = lane & 15, kq = lane >> 4;
+  const int m0 = blockIdx.y * TS, n0 = blockIdx.x * TS;
+  const int nkt = (a.Kdim + KT - 1) / KT;
+
+  floatx4 acc[2][2];   // [m quarter][n quarter]; lane holds C(m = i16, n = 4 kq + v)
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  float afA[2][8], bfA[2][8], afB[2][8], bfB[2][8];
+  auto load_tile = [&](int kt, float (&af)[2][8], float (&bf)[2][8]) __attribute__((always_inline)) {
+    // a k-tile past the end reads nothing but zeros (every k is out of range): the loads still go out, clamped
+    load_frags<A_KC>(af, a.A, a.a_m, a.a_k, m0, a.M, kt * KT, a.Kdim, i16, kq, p.a_vec != 0);
+    load_frags<B_KC>(bf, a.B, a.b_n, a.b_k, n0, a.N, kt * KT, a.Kdim, i16, kq, p.b_vec != 0);
+  };
+  auto multiply = [&](const float (&af)[2][8], const float (&bf)[2][8]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf[j][s], af[i][s], acc[i][j], 0, 0, 0);
+  };
+  // this wavefront's k-tiles: wave, wave + 4, ...; two register sets, the next tile's loads in flight
+  if (wave < nkt) {
+    load_tile(wave, afA, bfA);
+    for (int kt = wave; kt < nkt; kt += 8) {
+      load_tile(kt + 4, afB, bfB);
+      __builtin_amdgcn_sched_barrier(0);
+      multiply(afA, bfA);
+      __builtin_amdgcn_sched_barrier(0);
+      load_tile(kt + 8, afA, bfA);
+      __builtin_amdgcn_sched_barrier(0);
+      if (kt + 4 < nkt) multiply(afB, bfB);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+
+  // ---- the four partial tiles meet in LDS
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      *reinterpret_cast<float4 *>(&red[wave][2 * i + j][lane][0]) = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+  __syncthreads();
+  // ---- wavefront w finishes quarter w: rows m0 + 16 (w >> 1) .., columns n0 + 16 (w & 1) ..
+  const int m = m0 + 16 * (wave >> 1) + i16, n = n0 + 16 * (wave & 1) + 4 * kq;
+  float c[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {   // wavefront order, whatever finished first
+    const float4 t = *reinterpret_cast<const float4 *>(&red[w][wave][lane][0]);
+    c[0] += t.x; c[1] += t.y; c[2] += t.z; c[3] += t.w;
+  }
+  // everything the epilogue reads, in one batch of clamped loads
+  const bool min_ = m < a.M;
+  bool ok[4];
+  long o[4];
+  float bv[4], rv[4], uv[4], vv[4];
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    ok[v] = min_ && n + v < a.N;
+    o[v] = ok[v] ? (long)m * a.c_m + (long)(n + v) * a.c_n : 0;
+    bv[v] = a.bias ? a.bias[n + v < a.N ? n + v : 0] : 0.0f;
+    rv[v] = a.C_ref ? a.C_ref[o[v]] : 0.0f;
+    uv[v] = a.update ? a.update[o[v]] : 0.0f;
+    vv[v] = a.vel ? a.vel[o[v]] : 0.0f;
+  }
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    c[v] = act_apply(a.act, c[v] + bv[v]);
+    if (a.C_ref) c[v] *= act_deriv(a.c_ref_act, rv[v]);
+    if (!ok[v]) continue;
+    if (a.Cout) a.Cout[o[v]] = c[v];
+    if (a.update) {
+      update_param(&uv[v], a.vel ? &vv[v] : nullptr, c[v], a.step, a.mu, a.decay);
+      a.update[o[v]] = uv[v];
+      if (a.vel) a.vel[o[v]] = vv[v];
+    }
+  }
+}
+
+}  // namespace
+
+// Products below this many multiply-adds run here; above it the chip can be filled and the
+// persistent kernel's rate matters more than the latency chain.
+bool gemm_is_small(int M, int N, int Kdim) { return (long)M * N * Kdim <= (1L << 27); }
+
+hipError_t launch_gemm_small(const GemmArgs &a, hipStream_t stream) {
+  SmallParams p;
+  p.a = a;
+  p.a.split_k = 1;
+  auto al16 = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
+  const bool a_kc = a.a_k == 1, b_kc = a.b_k == 1;
+  p.a_vec = a_kc && al16(a.A) && a.a_m % 4 == 0 && a.Kdim % 4 == 0;
+  p.b_vec = b_kc && al16(a.B) && a.b_n % 4 == 0 && a.Kdim % 4 == 0;
+  const dim3 grid((a.N + TS - 1) / TS, (a.M + TS - 1) / TS);
+  if (a_kc && b_kc) hipLaunchKernelGGL((gemm_small_kernel<true, true>), grid, dim3(kThreads), 0, stream, p);
+  else if (a_kc) hipLaunchKernelGGL((gemm_small_kernel<true, false>), grid, dim3(kThreads), 0, stream, p);
+  else if (b_kc) hipLaunchKernelGGL((gemm_small_kernel<false, true>), grid, dim3(kThreads), 0, stream, p);
+  else hipLaunchKernelGGL((gemm_small_kernel<false, false>), grid, dim3(kThreads), 0, stream, p);
+  return hipGetLastError();
+}
+
+}  // namespace dllk
