@@ -12,11 +12,12 @@
 //     current one is multiplied.  Inside a k-tile of 32, the lane with k-quarter kq owns the 8
 //     consecutive k values 8*kq .. 8*kq+7 of both operands (any assignment works as long as both
 //     operands use the same one), which makes a k-contiguous operand two 16-byte loads per row;
-//   * the four partial tiles meet in LDS once, are added in wavefront order (results do not
-//     depend on timing), and each wavefront finishes one 16 x 16 quarter: bias, activation,
+//   * the partial tiles meet in LDS once, are added in wavefront order (results do not depend
+//     on timing), and four wavefronts finish one 16 x 16 quarter each: bias, activation,
 //     act' of a reference tensor, store and/or fused parameter update.  No split-K partials in
 //     global memory, no reduction launch.
-// Every global load is issued unconditionally from a clamped address and masked afterwards.
+// Every global load is issued unconditionally from a clamped address; nothing is masked before
+// the multiplication needs it.
 #include "dll_internal.h"
 
 namespace dllk {
@@ -24,7 +25,6 @@ namespace {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 256;
 constexpr int TS = 32;    // tile side
 constexpr int KT = 32;    // k-tile
 
@@ -44,44 +44,43 @@ struct SmallParams {
   int a_vec, b_vec;   // k-contiguous operand with aligned rows of whole 16-byte groups
 };
 
-// One operand's fragments of a k-tile: frag[t][s] = X(x0 + 16 t + i16, k0 + 8 kq + s), zero out of range.
-// X(x, k) = src[x * sx + k * sk].
+// One operand's fragments of a k-tile: frag[t][s] = X(x0 + 16 t + i16, k0 + 8 kq + s), X(x, k) = src[x * sx + k * sk].
+// Nothing here depends on a loaded value, so all loads of a k-tile stay in flight until the
+// multiplication needs them.  Rows past the operand's end re-read its last row: they only feed
+// output rows/columns that are never stored.  A k past the end re-reads k = 0 (a finite value);
+// `zero_tail` (uniform; set for ONE operand of the k-tile that overhangs Kdim) then clears those
+// entries, so that their products vanish.
 template <bool KC>
 __device__ __forceinline__ void load_frags(float (&frag)[2][8], const float *src, long sx, long sk, int x0, int X, int k0,
-                                           int Kdim, int i16, int kq, bool vec) {
+                                           int Kdim, int i16, int kq, bool vec, bool zero_tail) {
   const int k = k0 + 8 * kq;
 #pragma unroll
   for (int t = 0; t < 2; ++t) {
-    const int x = x0 + 16 * t + i16;
-    const bool xin = x < X;
-    const long base = xin ? (long)x * sx : 0;
+    const long base = (long)min(x0 + 16 * t + i16, X - 1) * sx;
     if (KC && vec) {   // uniform: rows are whole aligned 16-byte groups, so a group is entirely in or out of range
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
-        const bool ok = xin && k + 4 * h < Kdim;
-        const float4 v = *reinterpret_cast<const float4 *>(src + (ok ? base + k + 4 * h : 0));
-        frag[t][4 * h + 0] = ok ? v.x : 0.0f;
-        frag[t][4 * h + 1] = ok ? v.y : 0.0f;
-        frag[t][4 * h + 2] = ok ? v.z : 0.0f;
-        frag[t][4 * h + 3] = ok ? v.w : 0.0f;
+        const int kk = k + 4 * h;
+        const float4 v = *reinterpret_cast<const float4 *>(src + base + (kk < Kdim ? kk : 0));
+        frag[t][4 * h + 0] = v.x; frag[t][4 * h + 1] = v.y; frag[t][4 * h + 2] = v.z; frag[t][4 * h + 3] = v.w;
       }
     } else {
-      float v[8];
-      bool ok[8];
 #pragma unroll
-      for (int s = 0; s < 8; ++s) {
-        ok[s] = xin && k + s < Kdim;
-        v[s] = src[ok[s] ? base + (long)(k + s) * sk : 0];
-      }
-#pragma unroll
-      for (int s = 0; s < 8; ++s) frag[t][s] = ok[s] ? v[s] : 0.0f;
+      for (int s = 0; s < 8; ++s) frag[t][s] = src[base + (long)(k + s < Kdim ? k + s : 0) * sk];
     }
+  }
+  if (zero_tail) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int s = 0; s < 8; ++s)
+        if (k + s >= Kdim) frag[t][s] = 0.0f;
   }
 }
 
-template <bool A_KC, bool B_KC>
-__global__ __launch_bounds__(kThreads) void gemm_small_kernel(const SmallParams p) {
-  __shared__ __attribute__((aligned(16))) float red[4][4][64][4];   // [wavefront][quarter][lane][4]
+template <bool A_KC, bool B_KC, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void gemm_small_kernel(const SmallParams p) {
+  __shared__ __attribute__((aligned(16))) float red[WAVES][4][64][4];   // [wavefront][quarter][lane][4]
   const GemmArgs &a = p.a;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i16 = lane & 15, kq = lane >> 4;
@@ -96,9 +95,9 @@ __global__ __launch_bounds__(kThreads) void gemm_small_kernel(const SmallParams 
 
   float afA[2][8], bfA[2][8], afB[2][8], bfB[2][8];
   auto load_tile = [&](int kt, float (&af)[2][8], float (&bf)[2][8]) __attribute__((always_inline)) {
-    // a k-tile past the end reads nothing but zeros (every k is out of range): the loads still go out, clamped
-    load_frags<A_KC>(af, a.A, a.a_m, a.a_k, m0, a.M, kt * KT, a.Kdim, i16, kq, p.a_vec != 0);
-    load_frags<B_KC>(bf, a.B, a.b_n, a.b_k, n0, a.N, kt * KT, a.Kdim, i16, kq, p.b_vec != 0);
+    // a k-tile past the end is loaded (from clamped addresses) like any other and never multiplied
+    load_frags<A_KC>(af, a.A, a.a_m, a.a_k, m0, a.M, kt * KT, a.Kdim, i16, kq, p.a_vec != 0, false);
+    load_frags<B_KC>(bf, a.B, a.b_n, a.b_k, n0, a.N, kt * KT, a.Kdim, i16, kq, p.b_vec != 0, kt * KT + KT > a.Kdim);
   };
   auto multiply = [&](const float (&af)[2][8], const float (&bf)[2][8]) __attribute__((always_inline)) {
 #pragma unroll
@@ -108,33 +107,34 @@ __global__ __launch_bounds__(kThreads) void gemm_small_kernel(const SmallParams 
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf[j][s], af[i][s], acc[i][j], 0, 0, 0);
   };
-  // this wavefront's k-tiles: wave, wave + 4, ...; two register sets, the next tile's loads in flight
+  // this wavefront's k-tiles: wave, wave + WAVES, ...; two register sets, the next tile's loads in flight
   if (wave < nkt) {
     load_tile(wave, afA, bfA);
-    for (int kt = wave; kt < nkt; kt += 8) {
-      load_tile(kt + 4, afB, bfB);
+    for (int kt = wave; kt < nkt; kt += 2 * WAVES) {
+      load_tile(kt + WAVES, afB, bfB);
       __builtin_amdgcn_sched_barrier(0);
       multiply(afA, bfA);
       __builtin_amdgcn_sched_barrier(0);
-      load_tile(kt + 8, afA, bfA);
+      load_tile(kt + 2 * WAVES, afA, bfA);
       __builtin_amdgcn_sched_barrier(0);
-      if (kt + 4 < nkt) multiply(afB, bfB);
+      if (kt + WAVES < nkt) multiply(afB, bfB);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
 
-  // ---- the four partial tiles meet in LDS
+  // ---- the partial tiles meet in LDS
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
       *reinterpret_cast<float4 *>(&red[wave][2 * i + j][lane][0]) = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
   __syncthreads();
-  // ---- wavefront w finishes quarter w: rows m0 + 16 (w >> 1) .., columns n0 + 16 (w & 1) ..
+  if (wave >= 4) return;
+  // ---- wavefront w < 4 finishes quarter w: rows m0 + 16 (w >> 1) .., columns n0 + 16 (w & 1) ..
   const int m = m0 + 16 * (wave >> 1) + i16, n = n0 + 16 * (wave & 1) + 4 * kq;
   float c[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-  for (int w = 0; w < 4; ++w) {   // wavefront order, whatever finished first
+  for (int w = 0; w < WAVES; ++w) {   // wavefront order, whatever finished first
     const float4 t = *reinterpret_cast<const float4 *>(&red[w][wave][lane][0]);
     c[0] += t.x; c[1] += t.y; c[2] += t.z; c[3] += t.w;
   }
@@ -181,10 +181,13 @@ hipError_t launch_gemm_small(const GemmArgs &a, hipStream_t stream) {
   p.a_vec = a_kc && al16(a.A) && a.a_m % 4 == 0 && a.Kdim % 4 == 0;
   p.b_vec = b_kc && al16(a.B) && a.b_n % 4 == 0 && a.Kdim % 4 == 0;
   const dim3 grid((a.N + TS - 1) / TS, (a.M + TS - 1) / TS);
-  if (a_kc && b_kc) hipLaunchKernelGGL((gemm_small_kernel<true, true>), grid, dim3(kThreads), 0, stream, p);
-  else if (a_kc) hipLaunchKernelGGL((gemm_small_kernel<true, false>), grid, dim3(kThreads), 0, stream, p);
-  else if (b_kc) hipLaunchKernelGGL((gemm_small_kernel<false, true>), grid, dim3(kThreads), 0, stream, p);
-  else hipLaunchKernelGGL((gemm_small_kernel<false, false>), grid, dim3(kThreads), 0, stream, p);
+  // (eight wavefronts per workgroup, sharing the k range in eighths, measured slower at every size tried)
+#define DLL_SMALL(AK, BK_) hipLaunchKernelGGL((gemm_small_kernel<AK, BK_, 4>), grid, dim3(256), 0, stream, p)
+  if (a_kc && b_kc) DLL_SMALL(true, true);
+  else if (a_kc) DLL_SMALL(true, false);
+  else if (b_kc) DLL_SMALL(false, true);
+  else DLL_SMALL(false, false);
+#undef DLL_SMALL
   return hipGetLastError();
 }
 
