@@ -74,11 +74,11 @@ def engine_kernel_name(cs, backward: bool) -> str:
     (mirrors the dispatch in csrc/conv_engine.hip; used only to group launches for the report)."""
     cin, kout, hout = (cs.K, cs.C, cs.H) if backward else (cs.C, cs.K, cs.Ho)
     same = cs.R == 3 and cs.S == 3 and cs.pad == 1
-    chunked = cin % 16 == 0 or cin <= 12
+    chunked = cin % 16 == 0 or (cin % 8 == 0 and kout <= 16) or cin <= 12
     if same and chunked and hout > 8 and cs.W % (8 if backward and cs.pool == 2 else 4) == 0:
         src = 0 if not backward else (2 if cs.pool == 2 else 1)
         nt = 1 if kout <= 16 else 2
-        cc = (8 if nt == 1 else 16) if cin % 16 == 0 else 4
+        cc = 8 if (nt == 1 and cin % 8 == 0) else (16 if cin % 16 == 0 else 4)
         waves = 8 if (cc == 16 and nt == 2) else 4
         pack3 = "true" if (cc == 4 and cin == 3 and not backward) else "false"
         epi = 2 if backward else (1 if (cs.act == "relu" and cs.pool == 2) else 0)

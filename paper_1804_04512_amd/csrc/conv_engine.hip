@@ -591,7 +591,7 @@ __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void 
       const unsigned e = (unsigned)(pos + m_off);
 #pragma unroll
       for (int it = 0; it < NM; ++it) {
-        // 8- and 16-channel chunks are always whole (the launcher checks Cin % 16 == 0)
+        // 8- and 16-channel chunks are always whole (the launcher checks that Cin is a multiple of the chunk)
         const bool okc = (CC >= 8 && M_EXACT) ? ok : ok && it * M_CPR + m_c < (cleft < CC ? cleft : CC);
         const unsigned so = base + (unsigned)it * M_CPR * plane;
         vm[it] = ld4(rs_src, okc ? 4u * e : kOob, 4u * so);
@@ -909,7 +909,8 @@ inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 
 // counts that are multiples of 16, rows that are whole 16-byte groups and aligned tensors.
 bool conv3x3c16_applies(const ConvEngineArgs &a) {
   if (a.R != 3 || a.S != 3 || a.pad_h != 1 || a.pad_w != 1) return false;
-  if (a.Cin % 16 != 0 && a.Cin > 12) return false;   // 16-channel chunks, or up to three 4-channel chunks
+  // whole 16-channel chunks, whole 8-channel chunks for layers of at most 16 filters, or up to three 4-channel chunks
+  if (a.Cin % 16 != 0 && !(a.Cin % 8 == 0 && a.Kout <= 16) && a.Cin > 12) return false;
   if (a.Hout != a.Hin || a.Wout != a.Win) return false;
   if (!aligned16(a.src)) return false;
   // the kernel addresses the source through 32-bit byte offsets that must stay below 2 GiB
@@ -990,11 +991,11 @@ hipError_t launch_conv_engine(const ConvEngineArgs &a, hipStream_t stream) {
   if (a.Hout > 8 && conv3x3c16_applies(a)) {
     // 16 output channels: 4 waves x 2 row pairs; 32: 8 waves x 1 row pair (more waves hide the
     // longer per-step operand traffic better than more accumulators do)
+    if (a.Cin % 8 == 0 && a.Kout <= 16) return launch_3x3<1, 4, 8>(a, stream);   // 8-channel chunks: four workgroups fit a CU's LDS instead of three
     if (a.Cin % 16 != 0) {
       if (a.Kout <= 16) return launch_3x3<1, 4, 4>(a, stream);
       return launch_3x3<2, 4, 4>(a, stream);
     }
-    if (a.Kout <= 16) return launch_3x3<1, 4, 8>(a, stream);   // 8-channel chunks: four workgroups fit a CU's LDS instead of three
     return launch_3x3<2, 8, 16>(a, stream);   // wider layers run as groups of 32 output channels
   }
   if (small) {

@@ -98,6 +98,8 @@ CASES = [
     ConvSpec(2, 2, 9, 14, 3, 2, 4, 0, "identity", 1),         # non-square filter
     ConvSpec(2, 4, 11, 9, 6, 1, 1, 0, "relu", 1),             # 1x1 filter, odd map
     ConvSpec(1, 40, 20, 20, 1, 9, 9, 0, "identity", 1),       # single filter, deep contraction
+    ConvSpec(2, 24, 24, 40, 10, 3, 3, 1, "sigmoid", 1),       # 24 channels = three 8-channel chunks of the 3x3 instance
+    ConvSpec(3, 12, 16, 32, 24, 3, 3, 1, "relu", 2),          # its backward-data pass: 24 -> 12 channels through pooling
     # few input channels: their backward-data pass has few OUTPUT channels and takes the banded-filter kernel
     ConvSpec(3, 3, 20, 22, 6, 7, 7, 0, "sigmoid", 1),         # three channels, 14x16 maps back to 20x22: 2x2 tiles with tails
     ConvSpec(2, 2, 19, 17, 5, 5, 5, 2, "relu", 1),            # two channels, padded, odd sizes
