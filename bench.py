@@ -11,7 +11,8 @@ dense 2048, dense 1000), inputs and parameters resident in HBM.  Prints ONE JSON
              with HIP events on the launch stream, against the fp32 MFMA peak
   cpu_baseline  the CPU oracle timed on this machine's host cores on a bounded sample
 
-Other workloads (--config 1..4) exist for inspection; the default line is config 5.
+Other workloads (--config 1..4, --mode infer/dense/rbm/crbm_pmp) exist for inspection; the default
+line is config 5.
 """
 from __future__ import annotations
 

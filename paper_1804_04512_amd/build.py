@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdll_conv.so")
 SOURCES = ["conv_engine.hip", "conv_fewout.hip", "conv_wgrad.hip", "gemm.hip", "gemm_small.hip", "rbm.hip", "api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-# packed-fp32 VALU forms are switched off on purpose (see DESIGN notes on the build flags)
+# packed-fp32 VALU forms are switched off on purpose: the compiler then emits no v_pk_*_f32 instructions
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
