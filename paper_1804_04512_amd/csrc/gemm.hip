@@ -387,7 +387,13 @@ struct UnitPos {
   int m0, n0, kbeg, kend, z;
 };
 
-template <bool A_KC, bool B_KC>
+// MODE fixes the epilogue at compile time (the launcher knows it), which keeps the code and the
+// scalar state of the other forms out of the kernel:
+//   0  split-K: the tile goes to the partial area as it is
+//   1  fused parameter update, nothing else on the way (no bias, identity, no reference tensor);
+//      the parameter tile is prefetched during the unit's last k-tile
+//   2  everything else
+template <bool A_KC, bool B_KC, int MODE>
 __global__ __launch_bounds__(kThreads, 3) void gemm_fast_kernel(const GemmParams p) {
   __shared__ __attribute__((aligned(16))) float As[2][FA_TILE];
   __shared__ __attribute__((aligned(16))) float Bs[2][FB_TILE];
@@ -497,7 +503,7 @@ __global__ __launch_bounds__(kThreads, 3) void gemm_fast_kernel(const GemmParams
   };
 
   // parameter tile of the unit whose last k-tile is about to be multiplied (update mode)
-  const bool upd_mode = a.update && p.c_vec && a.split_k == 1;
+  constexpr bool upd_mode = MODE == 1;
   float4 upd[4][2];
   auto prefetch_update = [&](const UnitPos &u) __attribute__((always_inline)) {
 #pragma unroll
@@ -512,13 +518,12 @@ __global__ __launch_bounds__(kThreads, 3) void gemm_fast_kernel(const GemmParams
 
   // lane holds C(m = i16, n = 4*kq + v) of each 16x16 tile
   auto epilogue = [&](const UnitPos &u) __attribute__((always_inline)) {
-    const bool direct = a.split_k == 1;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int m = u.m0 + wm + i * 16 + i16;
       // momentum: the row's two velocity groups, requested together from clamped addresses
       float4 velp[2];
-      if (upd_mode && a.vel) {
+      if (MODE == 1 && a.vel) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
           const int n = u.n0 + wn + j * 16 + 4 * kq;
@@ -532,23 +537,7 @@ __global__ __launch_bounds__(kThreads, 3) void gemm_fast_kernel(const GemmParams
         const int n = u.n0 + wn + j * 16 + 4 * kq;
         if (n >= a.N) continue;
         float c[4] = {acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]};
-        // the group's bias values and reference outputs: eight loads issued together through clamped
-        // 32-bit offsets from uniform bases (the launcher checks that C's extent fits), none of them
-        // behind a per-element branch, which would make each wait for the one before
-        float bv[4] = {0.0f, 0.0f, 0.0f, 0.0f}, rv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        if (direct && a.bias) {
-#pragma unroll
-          for (int v = 0; v < 4; ++v)
-            bv[v] = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(a.bias) + 4u * (unsigned)min(n + v, a.N - 1));
-        }
-        if (direct && a.C_ref) {
-          const unsigned om = (unsigned)m * (unsigned)a.c_m;
-#pragma unroll
-          for (int v = 0; v < 4; ++v)
-            rv[v] = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(a.C_ref) +
-                                                     4u * (om + (unsigned)min(n + v, a.N - 1) * (unsigned)a.c_n));
-        }
-        if (a.split_k > 1) {
+        if constexpr (MODE == 0) {
           float *d = a.partial + ((long)u.z * a.M + m) * a.N + n;
           if (n + 3 < a.N && (a.N & 3) == 0) {
             *reinterpret_cast<float4 *>(d) = make_float4(c[0], c[1], c[2], c[3]);
@@ -557,21 +546,13 @@ __global__ __launch_bounds__(kThreads, 3) void gemm_fast_kernel(const GemmParams
             for (int v = 0; v < 4; ++v)
               if (n + v < a.N) d[v] = c[v];
           }
-          continue;
-        }
-#pragma unroll
-        for (int v = 0; v < 4; ++v) c[v] = act_apply(a.act, c[v] + bv[v]);
-        const long o = (long)m * a.c_m + (long)n * a.c_n;
-        if (a.C_ref) {
-#pragma unroll
-          for (int v = 0; v < 4; ++v) c[v] *= act_deriv(a.c_ref_act, rv[v]);
-        }
-        if (p.c_vec && n + 3 < a.N) {
-          if (a.Cout) *reinterpret_cast<float4 *>(a.Cout + o) = make_float4(c[0], c[1], c[2], c[3]);
-          if (a.update) {
+        } else if constexpr (MODE == 1) {
+          const long o = (long)m * a.c_m + (long)n * a.c_n;
+          if (n + 3 < a.N) {   // the launcher guarantees whole 16-byte groups (c_vec); a ragged last group falls through
+            if (a.Cout) *reinterpret_cast<float4 *>(a.Cout + o) = make_float4(c[0], c[1], c[2], c[3]);
             float4 w4 = upd[i][j];
             if (a.vel) {
-              float4 vv = upd_mode ? velp[j] : *reinterpret_cast<const float4 *>(a.vel + o);
+              float4 vv = velp[j];
               update_param(&w4.x, &vv.x, c[0], a.step, a.mu, a.decay); update_param(&w4.y, &vv.y, c[1], a.step, a.mu, a.decay);
               update_param(&w4.z, &vv.z, c[2], a.step, a.mu, a.decay); update_param(&w4.w, &vv.w, c[3], a.step, a.mu, a.decay);
               *reinterpret_cast<float4 *>(a.vel + o) = vv;
@@ -579,14 +560,60 @@ __global__ __launch_bounds__(kThreads, 3) void gemm_fast_kernel(const GemmParams
               w4.x += a.step * c[0]; w4.y += a.step * c[1]; w4.z += a.step * c[2]; w4.w += a.step * c[3];
             }
             *reinterpret_cast<float4 *>(a.update + o) = w4;
+          } else {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+              if (n + v < a.N) {
+                if (a.Cout) a.Cout[o + v * a.c_n] = c[v];
+                update_param(a.update + o + v * a.c_n, a.vel ? a.vel + o + v * a.c_n : nullptr, c[v], a.step, a.mu, a.decay);
+              }
           }
         } else {
+          // the group's bias values and reference outputs: eight loads issued together through clamped
+          // 32-bit offsets from uniform bases (the launcher checks that C's extent fits), none of them
+          // behind a per-element branch, which would make each wait for the one before
+          float bv[4] = {0.0f, 0.0f, 0.0f, 0.0f}, rv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+          if (a.bias) {
 #pragma unroll
-          for (int v = 0; v < 4; ++v)
-            if (n + v < a.N) {
-              if (a.Cout) a.Cout[o + v * a.c_n] = c[v];
-              if (a.update) update_param(a.update + o + v * a.c_n, a.vel ? a.vel + o + v * a.c_n : nullptr, c[v], a.step, a.mu, a.decay);
+            for (int v = 0; v < 4; ++v)
+              bv[v] = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(a.bias) + 4u * (unsigned)min(n + v, a.N - 1));
+          }
+          if (a.C_ref) {
+            const unsigned om = (unsigned)m * (unsigned)a.c_m;
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+              rv[v] = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(a.C_ref) +
+                                                       4u * (om + (unsigned)min(n + v, a.N - 1) * (unsigned)a.c_n));
+          }
+#pragma unroll
+          for (int v = 0; v < 4; ++v) c[v] = act_apply(a.act, c[v] + bv[v]);
+          const long o = (long)m * a.c_m + (long)n * a.c_n;
+          if (a.C_ref) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) c[v] *= act_deriv(a.c_ref_act, rv[v]);
+          }
+          if (p.c_vec && n + 3 < a.N) {
+            if (a.Cout) *reinterpret_cast<float4 *>(a.Cout + o) = make_float4(c[0], c[1], c[2], c[3]);
+            if (a.update) {
+              float4 w4 = *reinterpret_cast<const float4 *>(a.update + o);
+              if (a.vel) {
+                float4 vv = *reinterpret_cast<const float4 *>(a.vel + o);
+                update_param(&w4.x, &vv.x, c[0], a.step, a.mu, a.decay); update_param(&w4.y, &vv.y, c[1], a.step, a.mu, a.decay);
+                update_param(&w4.z, &vv.z, c[2], a.step, a.mu, a.decay); update_param(&w4.w, &vv.w, c[3], a.step, a.mu, a.decay);
+                *reinterpret_cast<float4 *>(a.vel + o) = vv;
+              } else {
+                w4.x += a.step * c[0]; w4.y += a.step * c[1]; w4.z += a.step * c[2]; w4.w += a.step * c[3];
+              }
+              *reinterpret_cast<float4 *>(a.update + o) = w4;
             }
+          } else {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+              if (n + v < a.N) {
+                if (a.Cout) a.Cout[o + v * a.c_n] = c[v];
+                if (a.update) update_param(a.update + o + v * a.c_n, a.vel ? a.vel + o + v * a.c_n : nullptr, c[v], a.step, a.mu, a.decay);
+              }
+          }
         }
       }
     }
@@ -612,7 +639,7 @@ __global__ __launch_bounds__(kThreads, 3) void gemm_fast_kernel(const GemmParams
     const bool last_kt = cur.kt + 1 == cur.nkt;
     const bool more = !(last_kt && cur.unit + (int)gridDim.x >= units);   // a k-tile follows in the stream
     if (ld.unit < units) { load_tiles(SAME{}, ld); advance(ld); }         // two places ahead
-    if (last_kt && upd_mode) prefetch_update(cur);
+    if constexpr (upd_mode) { if (last_kt) prefetch_update(cur); }
     multiply(BUF);
     if (more) store_tiles(OTHER{}, 1 - BUF);
     __syncthreads();
@@ -854,7 +881,13 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream) {
   } else {
     const long units = (long)grid.x * grid.y * grid.z;
     const dim3 pgrid((unsigned)(units < 768 ? units : 768));   // three resident workgroups per CU
-#define DLL_GEMM_LAUNCH(AK, BK_) hipLaunchKernelGGL((gemm_fast_kernel<AK, BK_>), pgrid, dim3(kThreads), 0, stream, p)
+    const int mode = p.a.split_k > 1 ? 0 : ((a.update && p.c_vec && !a.bias && a.act == ACT_IDENTITY && !a.C_ref) ? 1 : 2);
+#define DLL_GEMM_LAUNCH(AK, BK_)                                                                                      \
+  do {                                                                                                                 \
+    if (mode == 0) hipLaunchKernelGGL((gemm_fast_kernel<AK, BK_, 0>), pgrid, dim3(kThreads), 0, stream, p);           \
+    else if (mode == 1) hipLaunchKernelGGL((gemm_fast_kernel<AK, BK_, 1>), pgrid, dim3(kThreads), 0, stream, p);      \
+    else hipLaunchKernelGGL((gemm_fast_kernel<AK, BK_, 2>), pgrid, dim3(kThreads), 0, stream, p);                     \
+  } while (0)
     if (a_kc && b_kc) DLL_GEMM_LAUNCH(true, true);
     else if (a_kc && !b_kc) DLL_GEMM_LAUNCH(true, false);
     else if (!a_kc && b_kc) DLL_GEMM_LAUNCH(false, true);
