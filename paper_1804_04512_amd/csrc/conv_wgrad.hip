@@ -287,12 +287,15 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
           if (a.act == ACT_RELU_FLAGGED && (fl[e] & kIdxInactive)) g[e] = 0.0f;
           pos[e] = fl[e] & kIdxPosMask;   // slots outside the image hold dy = 0
         }
+        // the four 2x2 windows are cleared with plain stores, then each gradient is dropped at its
+        // arg-max position (LDS writes of one wavefront land in program order): one address
+        // computation per element instead of four compare/select pairs
 #pragma unroll
         for (int wa = 0; wa < 2; ++wa)
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-            *reinterpret_cast<float2 *>(d + wa * kTileW + 2 * e) =
-                make_float2(pos[e] == 2 * wa ? g[e] : 0.0f, pos[e] == 2 * wa + 1 ? g[e] : 0.0f);
+          for (int e = 0; e < 4; ++e) *reinterpret_cast<float2 *>(d + wa * kTileW + 2 * e) = make_float2(0.0f, 0.0f);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) d[2 * e + (pos[e] >> 1) * kTileW + (pos[e] & 1)] = g[e];
         dbacc[rd] += (g[0] + g[1]) + (g[2] + g[3]);
       } else {
         reinterpret_cast<float2 *>(d)[0] = make_float2(g[0], g[1]);
