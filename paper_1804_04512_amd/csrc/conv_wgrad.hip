@@ -79,18 +79,23 @@ __device__ __forceinline__ float dz_value(const WgradArgs &a, int Ho, int Wo, in
 __host__ __device__ __forceinline__ bool reads_output(int act) { return act == ACT_SIGMOID || act == ACT_RELU; }
 
 // Registers that carry one tile from global memory to LDS (fast path).
-template <int MTF, int POOL>
+template <int MTF, int POOL, int XI, int XH>
 struct TileRegs {
   static constexpr int DZR = POOL == 2 ? MTF : 4 * MTF;   // staging rounds over the filter planes
-  float4 xi[NXI];
-  float xh[NXH];
+  float4 xi[XI];
+  float xh[XH];
   float4 dyv[DZR], yv[DZR];
   uchar4 iv[DZR];
 };
 
 // grid: x = G * nchunks, y = filter groups of MTF*16
-template <int MTF, int NTT, int POOL, bool FAST>
+// FAST: 0 = element-wise staging; 1 = vector staging with NXI / NXH rounds; 2 = vector staging
+// of a halo tile small enough for ONE round of each (a few channels of a small filter): the
+// loader registers and per-slot indices of the other rounds are gone, which buys two more
+// resident workgroups per CU for a kernel whose rate follows its occupancy.
+template <int MTF, int NTT, int POOL, int FAST>
 __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
+  constexpr int XI = FAST == 2 ? 1 : NXI, XH = FAST == 2 ? 1 : NXH;
   extern __shared__ float lds[];
   const WgradArgs &a = p.a;
   float *xs = lds;                 // [CC][PS]
@@ -105,7 +110,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
   const int RSf = a.R * a.S;
   const int lines = p.CC * p.rows;
   constexpr int RW = TH / 4;                    // rows per wave
-  constexpr int DZR = TileRegs<MTF, POOL>::DZR;
+  constexpr int DZR = TileRegs<MTF, POOL, XI, XH>::DZR;
 
   floatx4 acc[MTF][NTT];
 #pragma unroll
@@ -130,15 +135,15 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
 #pragma unroll
   for (int mf = 0; mf < MTF; ++mf) fplane[mf] = min(mf * 16 + i16, kcount - 1) * PSZ;
 
-  TileRegs<MTF, POOL> tr;
+  TileRegs<MTF, POOL, XI, XH> tr;
 
   // ---- fast path: everything about a thread's staging slots that does not depend on the
   // tile (which element of the tile it moves, where it lands in LDS) is worked out once here;
   // per tile only a scalar base and a few range checks remain.
   constexpr int kUnused = -(1 << 20);
   const int j4 = 4 * (tid & 7);      // interior: first column of the thread's 16-byte group
-  int xo[NXI], xl[NXI], xrow[NXI];   // interior slots: global offset from the tile origin, LDS offset, tile row
-  int ho[NXH], hl[NXH], hrow[NXH], hcol[NXH];
+  int xo[XI], xl[XI], xrow[XI];   // interior slots: global offset from the tile origin, LDS offset, tile row
+  int ho[XH], hl[XH], hrow[XH], hcol[XH];
   int dzo[DZR], dzl[DZR];            // dz slots: global offset from the tile's first pooled element, LDS offset
   bool dzk[DZR];
   int du = 0, dv = 0;
@@ -154,7 +159,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
       const_cast<unsigned char *>(a.idx ? a.idx : reinterpret_cast<const unsigned char *>(a.dy)), 0, (int)(p.dy_bytes >> 2), 0x00020000);
   if (FAST) {
 #pragma unroll
-    for (int it = 0; it < NXI; ++it) {
+    for (int it = 0; it < XI; ++it) {
       const int e = tid + it * kThreads;
       const int line = e >> 3;
       const int cl = (line * p.inv_rows) >> 16, row = line - cl * p.rows;
@@ -166,7 +171,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
     }
     const int nh = a.S - 1;
 #pragma unroll
-    for (int it = 0; it < NXH; ++it) {
+    for (int it = 0; it < XH; ++it) {
       const int e = tid + it * kThreads;
       const int line = nh > 0 ? e / nh : lines, hc = nh > 0 ? e - line * nh : 0;
       const int cl = (line * p.inv_rows) >> 16, row = line - cl * p.rows;
@@ -221,19 +226,19 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
       // every round is issued: slots the tile does not have carry the out-of-range offset and cost
       // one load instruction that never reaches memory (cheaper than a branch with register copies)
 #pragma unroll
-      for (int it = 0; it < NXI; ++it) tr.xi[it] = ldx4(rs_x, xo[it], so);
+      for (int it = 0; it < XI; ++it) tr.xi[it] = ldx4(rs_x, xo[it], so);
 #pragma unroll
-      for (int it = 0; it < NXH; ++it)
+      for (int it = 0; it < XH; ++it)
         tr.xh[it] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_x, ho[it], (int)so, 0));
     } else {
       const bool col_ok = ox0 + j4 < a.W;
 #pragma unroll
-      for (int it = 0; it < NXI; ++it) {
+      for (int it = 0; it < XI; ++it) {
         const bool ok = (unsigned)(gy0 + xrow[it]) < (unsigned)a.H && col_ok;
         tr.xi[it] = ldx4(rs_x, ok ? xo[it] + torg : (int)kOob, xbase);
       }
 #pragma unroll
-      for (int it = 0; it < NXH; ++it) {
+      for (int it = 0; it < XH; ++it) {
         const bool ok = (unsigned)(gy0 + hrow[it]) < (unsigned)a.H && (unsigned)(ox0 + hcol[it]) < (unsigned)a.W;
         tr.xh[it] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_x, ok ? ho[it] + torg : (int)kOob, (int)xbase, 0));
       }
@@ -258,9 +263,12 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
   };
 
   // ---- fast path, step 2: registers -> LDS (dz is formed here)
-  auto store_tile = [&]() {
+  // `actc` carries the activation as a compile-time constant: with a run-time one the compiler
+  // evaluates every derivative form for every element and selects afterwards
+  auto store_tile_as = [&](auto actc) {
+    constexpr int ACT = decltype(actc)::value;
 #pragma unroll
-    for (int it = 0; it < NXI; ++it) {
+    for (int it = 0; it < XI; ++it) {
       if (it < p.nxi && xl[it] >= 0) {
         float2 *d = reinterpret_cast<float2 *>(xs + xl[it]);
         d[0] = make_float2(tr.xi[it].x, tr.xi[it].y);
@@ -268,7 +276,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
       }
     }
 #pragma unroll
-    for (int it = 0; it < NXH; ++it)
+    for (int it = 0; it < XH; ++it)
       if (it < p.nxh && hl[it] >= 0) xs[hl[it]] = tr.xh[it];
 #pragma unroll
     for (int rd = 0; rd < DZR; ++rd) {
@@ -277,14 +285,14 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
       const float ov[4] = {tr.yv[rd].x, tr.yv[rd].y, tr.yv[rd].z, tr.yv[rd].w};
       float g[4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) g[e] = reads_output(a.act) ? gv[e] * act_deriv(a.act, ov[e]) : gv[e];
+      for (int e = 0; e < 4; ++e) g[e] = reads_output(ACT) ? gv[e] * act_deriv(ACT, ov[e]) : gv[e];
       float *d = dzs + dzl[rd];
       if (POOL == 2) {
         const unsigned char fl[4] = {tr.iv[rd].x, tr.iv[rd].y, tr.iv[rd].z, tr.iv[rd].w};
         unsigned char pos[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          if (a.act == ACT_RELU_FLAGGED && (fl[e] & kIdxInactive)) g[e] = 0.0f;
+          if (ACT == ACT_RELU_FLAGGED && (fl[e] & kIdxInactive)) g[e] = 0.0f;
           pos[e] = fl[e] & kIdxPosMask;   // slots outside the image hold dy = 0
         }
         // the four 2x2 windows are cleared with plain stores, then each gradient is dropped at its
@@ -303,6 +311,12 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p) {
         dbacc[rd] += (g[0] + g[1]) + (g[2] + g[3]);
       }
     }
+  };
+  auto store_tile = [&]() {
+    if (a.act == ACT_SIGMOID) store_tile_as(std::integral_constant<int, ACT_SIGMOID>{});
+    else if (a.act == ACT_RELU) store_tile_as(std::integral_constant<int, ACT_RELU>{});
+    else if (a.act == ACT_RELU_FLAGGED) store_tile_as(std::integral_constant<int, ACT_RELU_FLAGGED>{});
+    else store_tile_as(std::integral_constant<int, ACT_IDENTITY>{});
   };
 
   // ---- generic path: element-wise staging straight into LDS (any shape, any alignment)
@@ -693,7 +707,11 @@ bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, int po
       //                      (unpooled staging: more loader registers)
       {{4, 3, 3, 2}, {3, 2, 2, 2}, {2, 1, 1, 1}}};
   const int ntt_slot = best_ntt <= 2 ? 0 : (best_ntt <= 5 ? 1 : (best_ntt <= 7 ? 2 : 3));
-  const long by_regs = kByRegs[pool == 2 ? 0 : 1][mtf - 1][ntt_slot];
+  long by_regs = kByRegs[pool == 2 ? 0 : 1][mtf - 1][ntt_slot];
+  // the one-round instances (two tap tiles, halo tile of at most 32 lines) carry far fewer loader registers
+  static const int kByRegsOneRound[2][3] = {{7, 5, 4}, {5, 3, 2}};
+  const int lines = best_cc * g.rows;
+  if (best_ntt == 2 && lines * 8 <= kThreads && lines * (S - 1) <= kThreads) by_regs = kByRegsOneRound[pool == 2 ? 0 : 1][mtf - 1];
   if (resident > by_regs) resident = by_regs;
   if (resident < 1) resident = 1;
   long G = 256 * resident / ((long)plan->nchunks * kgroups);
@@ -714,12 +732,19 @@ namespace {
 template <int MTF, int NTT>
 hipError_t launch_wgrad_t(const WgradParams &p, const WgradPlan &plan, bool fast, hipStream_t stream) {
   dim3 grid((unsigned)(plan.G * plan.nchunks), (unsigned)p.kgroups, 1);
+  if constexpr (NTT == 2) {
+    if (fast && p.nxi <= 1 && p.nxh <= 1) {   // one staging round: the instance with the small loader
+      if (p.a.pool == 2) hipLaunchKernelGGL((wgrad_kernel<MTF, NTT, 2, 2>), grid, dim3(kThreads), plan.lds_bytes, stream, p);
+      else hipLaunchKernelGGL((wgrad_kernel<MTF, NTT, 1, 2>), grid, dim3(kThreads), plan.lds_bytes, stream, p);
+      return hipGetLastError();
+    }
+  }
   if (fast && p.a.pool == 2)
-    hipLaunchKernelGGL((wgrad_kernel<MTF, NTT, 2, true>), grid, dim3(kThreads), plan.lds_bytes, stream, p);
+    hipLaunchKernelGGL((wgrad_kernel<MTF, NTT, 2, 1>), grid, dim3(kThreads), plan.lds_bytes, stream, p);
   else if (fast)
-    hipLaunchKernelGGL((wgrad_kernel<MTF, NTT, 1, true>), grid, dim3(kThreads), plan.lds_bytes, stream, p);
+    hipLaunchKernelGGL((wgrad_kernel<MTF, NTT, 1, 1>), grid, dim3(kThreads), plan.lds_bytes, stream, p);
   else
-    hipLaunchKernelGGL((wgrad_kernel<MTF, NTT, 1, false>), grid, dim3(kThreads), plan.lds_bytes, stream, p);
+    hipLaunchKernelGGL((wgrad_kernel<MTF, NTT, 1, 0>), grid, dim3(kThreads), plan.lds_bytes, stream, p);
   return hipGetLastError();
 }
 template <int MTF>
