@@ -39,6 +39,7 @@ def parse():
     ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--batch", type=int, default=None, help="override the batch size (inspection only)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--cpu-threads", type=int, default=0, help="threads of the CPU oracle leg (0 = all the box gives)")
     ap.add_argument("--cpu-batch", type=int, default=128, help="batch of the CPU oracle leg (config 5 and --mode infer)")
     ap.add_argument("--mode", choices=["train", "infer", "dense", "rbm", "crbm_pmp"], default="train",
                     help="inspection lines instead of the training step of --config: infer = dll_cnn_forward on the paper's "
@@ -123,12 +124,14 @@ def conv_pass_table(B, wl_cnn, dev_params, x_dev, iters):
     return table
 
 
-def cpu_baseline(cfg: int, cpu_batch: int, budget_s: float = 10.0, max_reps: int = 100):
+def cpu_baseline(cfg: int, cpu_batch: int, budget_s: float = 10.0, max_reps: int = 100, threads: int = 0):
     """The oracle as it stands on the host cores: whole steps of the same workload, repeated until
     about `budget_s` seconds of CPU work are done (at least one step)."""
     from oracle import oracle as orc
     from paper_1804_04512_amd import workloads as wl
     act = {"identity": 0, "sigmoid": 1, "relu": 2}
+    if threads > 0:
+        orc.set_threads(threads)
     w = wl.ALL[cfg](cpu_batch)
     if isinstance(w, wl.CnnWorkload):
         net = orc.Net([orc.conv_desc(c.N, c.C, c.H, c.W, c.K, c.R, c.S, c.pad, act[c.act], c.pool) for c in w.conv],
@@ -377,7 +380,7 @@ def main():
                            "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                            "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None}
     if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_batch if cfg == 5 else batch)
+        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_batch if cfg == 5 else batch, threads=args.cpu_threads)
     print(json.dumps(out))
     return 0
 

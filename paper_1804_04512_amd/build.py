@@ -13,6 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdll_conv.so")
 SOURCES = ["conv_engine.hip", "conv_fewout.hip", "conv_wgrad.hip", "gemm.hip", "gemm_small.hip", "rbm.hip", "api.hip"]
+PROBE = os.path.join(HERE, "chip_probe")   # stand-alone program: measured MFMA and HBM rates of the GPU
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 VALU forms are switched off on purpose: the compiler then emits no v_pk_*_f32 instructions
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
@@ -37,6 +38,8 @@ def build() -> str:
         objs = list(ex.map(_compile, SOURCES))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     subprocess.run(cmd, check=True)
+    obj = _compile("chip_probe.hip")
+    subprocess.run([HIPCC, "--offload-arch=gfx950", "-o", PROBE, obj], check=True)
     return LIB
 
 
