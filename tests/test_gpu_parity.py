@@ -313,6 +313,22 @@ def test_forward_pass_matches_oracle(make):
     check_forward(make())
 
 
+def test_forward_pass_full_size_sampled_images():
+    """Section VI's network at its full shape (batch 128, 3x256x256, five blocks, dense 2048, dense
+    1000), the launch configuration of `bench.py --mode infer`.  An image's logits depend on that
+    image alone, so the oracle runs the same network on a sample of the batch (first, last, two in
+    between) and those rows are compared one by one."""
+    w = wl.paper_imagenet_cnn()
+    lg, pg = run_forward_gpu(w)
+    rows = [0, 45, 86, w.batch - 1]
+    sub = wl.paper_imagenet_cnn(len(rows))
+    lo, po = orc.cnn_forward(onet(sub), w.params, np.ascontiguousarray(w.x[rows]))
+    assert max_rel_err(lg[rows], lo) <= TOL_FWD
+    assert max_rel_err(pg[rows], po) <= TOL_FWD
+    assert np.isfinite(lg).all()
+    np.testing.assert_allclose(pg.sum(1), 1.0, rtol=1e-5)
+
+
 def test_forward_pass_logits_equal_training_pass_logits():
     """Same kernels, same order of operations: the inference pass and the training step's forward
     half give bit-identical logits; logits-only and probabilities-only calls work."""
