@@ -14,7 +14,7 @@ torch = pytest.importorskip("torch")
 from oracle import oracle as orc
 from paper_1804_04512_amd import binding as B
 from paper_1804_04512_amd import workloads as wl
-from paper_1804_04512_amd.workloads import ConvSpec
+from paper_1804_04512_amd.workloads import ConvSpec, DenseSpec
 
 from helpers import ACT, TOL_FWD, TOL_GRAD, check_idx_bytes, check_idx_flags_against, check_pool_idx, max_rel_err, odesc, onet
 
@@ -226,8 +226,9 @@ def check_cnn(w: wl.CnnWorkload):
     for l, c in enumerate(w.conv):
         pre, _ = orc.conv_valid_fwd(odesc(c, pool=1), a, w.params[2 * l], w.params[2 * l + 1])
         a, idx_o = orc.conv_valid_fwd(odesc(c), a, w.params[2 * l], w.params[2 * l + 1])
-        check_pool_idx(g["idx"][l], idx_o, pre, a)
-        check_idx_flags_against(g["raw_idx"][l], c.act == "relu", a)
+        if c.pool == 2:
+            check_pool_idx(g["idx"][l], idx_o, pre, a)
+            check_idx_flags_against(g["raw_idx"][l], c.act == "relu", a)
     new = w.clone_params()
     o = orc.cnn_train_step(net, new, w.x, w.labels, w.lr, pool_idx_in=g["idx"])
     assert max_rel_err(np.array([g["loss"]]), np.array([o.loss])) <= TOL_FWD
@@ -272,6 +273,18 @@ def test_config5_full_size_step():
         assert max_rel_err(gg, og) <= TOL_GRAD, f"gradient of parameter {p}"
     for p, (gp, op, old) in enumerate(zip(g["params"], new, w.params)):
         assert max_rel_err(gp - old, op - old) <= TOL_GRAD, f"update of parameter {p}"
+
+
+def test_cnn_step_with_unpooled_and_mixed_layers():
+    """Layers without pooling inside a network (sigmoid and identity activations, a 1x1 and a 2x2
+    filter, three dense layers): the step's backward passes then read the layer outputs instead
+    of pooling bytes."""
+    conv = [ConvSpec(5, 3, 20, 24, 8, 3, 3, 1, "relu", 2), ConvSpec(5, 8, 10, 12, 12, 2, 2, 0, "sigmoid", 1),
+            ConvSpec(5, 12, 9, 11, 6, 1, 1, 0, "identity", 1), ConvSpec(5, 6, 9, 11, 16, 3, 3, 0, "relu", 1)]
+    dense = [DenseSpec(16 * 7 * 9, 64, "sigmoid"), DenseSpec(64, 33, "relu"), DenseSpec(33, 7, "identity")]
+    w = wl._cnn(21, "mixed_layers", conv, dense, 7, 0.05, "normal", None)
+    check_cnn(w)
+    check_forward(w)
 
 
 def test_cnn_lr_zero_and_no_grads():
