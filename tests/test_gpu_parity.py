@@ -287,6 +287,47 @@ def test_cnn_step_with_unpooled_and_mixed_layers():
     check_forward(w)
 
 
+def test_step_captured_in_a_hip_graph_replays_bit_identically():
+    """The library allocates nothing and synchronises nothing, so a whole training step can be
+    captured into a HIP graph (what `bench.py` times by default).  Three replays, with unrelated
+    plain launches and synchronisations between them, must leave exactly the parameters, loss and
+    logits that three plain steps leave: the kernels are deterministic."""
+    w = wl.config5(batch=4, image=64, hidden=128, classes=50)
+    net = B.net_desc(w.conv, w.dense, w.classes)
+    x, labels = dev(w.x), dev(w.labels)
+    ws = B.workspace(B.dll_cnn_workspace_bytes(net))
+
+    def fresh():
+        return ([dev(p) for p in w.params], torch.full((1,), float("nan"), device="cuda"),
+                torch.full((w.batch, w.classes), float("nan"), device="cuda"))
+
+    pe, le, ge = fresh()
+    snaps = []
+    for _ in range(3):
+        B.dll_cnn_train_step(net, pe, None, x, labels, 0.05, le, ge, None, ws)
+        snaps.append(([host(p) for p in pe], host(le).copy(), host(ge).copy()))
+    pg, lg, gg = fresh()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.dll_cnn_train_step(net, pg, None, x, labels, 0.05, lg, gg, None, ws)
+    torch.cuda.synchronize()
+    for a, b in zip(pg, w.params):                      # capturing runs nothing
+        np.testing.assert_array_equal(host(a), b)
+    other = ConvSpec(2, 3, 12, 10, 5, 3, 3, 1, "relu", 2)
+    ox, ow, ob, _ = rand_layer(other, 77)
+    for r in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        params, loss, logits = snaps[r]
+        for p, (a, b) in enumerate(zip(pg, params)):
+            assert np.array_equal(host(a), b), f"replay {r}: parameter {p}"
+        assert np.array_equal(host(lg), loss) and np.array_equal(host(gg), logits), f"replay {r}"
+        # the program's own work between replays: another layer through the plain entry point
+        oy = torch.empty(other.y_shape, device="cuda")
+        B.dll_conv_valid_fwd(other, dev(ox), dev(ow), dev(ob), oy, torch.empty(other.y_shape, dtype=torch.uint8, device="cuda"))
+        torch.cuda.synchronize()
+
+
 def test_cnn_lr_zero_and_no_grads():
     w = wl.config2(batch=10)
     g = run_cnn_gpu(w, 0.0, want_grads=False)
