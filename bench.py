@@ -34,8 +34,8 @@ METRIC = "conv GFLOP/s + images/s per fwd+bwd step; % of fp32 MFMA peak"
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--batch", type=int, default=None, help="override the batch size (inspection only)")
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
