@@ -126,7 +126,7 @@ def conv_pass_table(B, wl_cnn, dev_params, x_dev, iters):
     return table
 
 
-def cpu_baseline(cfg: int, cpu_batch: int, budget_s: float = 10.0, max_reps: int = 100, threads: int = 0):
+def cpu_baseline(cfg: int, cpu_batch: int, budget_s: float = 10.0, max_reps: int = 1000000, threads: int = 0):
     """The oracle as it stands on the host cores: whole steps of the same workload, repeated until
     about `budget_s` seconds of CPU work are done (at least one step)."""
     from oracle import oracle as orc
