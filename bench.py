@@ -126,6 +126,16 @@ def conv_pass_table(B, wl_cnn, dev_params, x_dev, iters):
     return table
 
 
+# HBM bytes per launch of the kernels that can come out as the dominant one at config 5, batch 128,
+# from the FETCH_SIZE / WRITE_SIZE counter runs summarised in profiles/c5_cnn_train_step.md
+# (fetch scaled by the copy-kernel calibration, so an upper bound; averaged over the kernel's
+# launches of a step like `achieved`).  Counters need profiler runs of their own, so the figure
+# cannot be taken live; any other kernel or workload reports null.
+MEASURED_TRAFFIC_BYTES = {
+    ("c5_large_image_cnn", 128, "conv3x3c16_kernel<1,4,2,8,false,2>"): (31019.3 + 81920.1) * 1024,
+}
+
+
 def cpu_baseline(cfg: int, cpu_batch: int, budget_s: float = 10.0, max_reps: int = 1000000, threads: int = 0):
     """The oracle as it stands on the host cores: whole steps of the same workload, repeated until
     about `budget_s` seconds of CPU work are done (at least one step)."""
@@ -398,7 +408,8 @@ def main():
         out["roofline"] = {"bound": "mfma", "kernel": name, "launches_per_step": gr["n"],
                            "avg_launch_ms": gr["ms"] / gr["n"], "flop_per_launch": gr["flop"] / gr["n"],
                            "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                           "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None}
+                           "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                           "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, batch, name))}
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_batch if cfg == 5 else batch, threads=args.cpu_threads)
     print(json.dumps(out))
