@@ -126,6 +126,8 @@ def conv_pass_table(B, wl_cnn, dev_params, x_dev, iters):
     return table
 
 
+SETTLE_S = 0.1   # untimed steady-state run-in before the timed steps (see main)
+
 # HBM bytes per launch of the kernels that can come out as the dominant one at config 5, batch 128,
 # from the FETCH_SIZE / WRITE_SIZE counter runs summarised in profiles/c5_cnn_train_step.md
 # (fetch scaled by the copy-kernel calibration, so an upper bound; averaged over the kernel's
@@ -352,6 +354,11 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    # Per-pass timing of the convolution kernels first: it is the roofline measurement, and its few
+    # thousand launches also bring the chip to its working clocks before the steps are timed.
+    table = None
+    if isinstance(w, wl.CnnWorkload):
+        table = conv_pass_table(B, w, params, x, 20)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -373,6 +380,14 @@ def main():
         except Exception as e:   # noqa: BLE001 - any capture problem means: time plain launches
             print(f"bench.py: graph capture failed ({e}); timing plain launches", file=sys.stderr)
             torch.cuda.synchronize()
+    # The chip takes some tens of milliseconds of continuous work to reach its steady clocks after
+    # an idle spell (the set-up above leaves several): steps are run, untimed, for SETTLE_S seconds
+    # so that the timed steps measure the steady state a training job runs in.
+    t_settle = time.perf_counter()
+    while time.perf_counter() - t_settle < SETTLE_S:
+        for _ in range(10):
+            run()
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         run()
@@ -386,13 +401,12 @@ def main():
         "metric": METRIC, "value": gflops, "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": w.name, "batch": batch, "flop_per_step": flop, "launch": launch},
+        "config": {"workload": w.name, "batch": batch, "flop_per_step": flop, "launch": launch, "settle_s": SETTLE_S},
         "images_per_s": batch / (ms_per_step * 1e-3),
         "pct_fp32_mfma_peak": 100.0 * gflops / (PEAK_FP32_MFMA_TFLOPS * 1e3),
     }
     if isinstance(w, wl.CnnWorkload):
         out["config"]["conv_flop_per_step"] = w.conv_flop()
-        table = conv_pass_table(B, w, params, x, max(5, min(args.steps, 20)))
         conv_ms = sum(r["ms"] for r in table)
         out["conv_passes"] = [dict(layer=r["layer"], op=r["op"], ms=round(r["ms"], 4),
                                    tflops=round(r["flop"] / r["ms"] / 1e9, 2)) for r in table]
