@@ -43,11 +43,12 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--cpu-threads", type=int, default=0, help="threads of the CPU oracle leg (0 = all the box gives)")
     ap.add_argument("--cpu-batch", type=int, default=128, help="batch of the CPU oracle leg (config 5 and --mode infer)")
-    ap.add_argument("--mode", choices=["train", "infer", "dense", "rbm", "crbm_pmp"], default="train",
+    ap.add_argument("--mode", choices=["train", "infer", "dense", "rbm", "crbm_pmp", "fft"], default="train",
                     help="inspection lines instead of the training step of --config: infer = dll_cnn_forward on the paper's "
                          "ImageNet network (batch 128 of 3x256x256); dense = momentum step of the fully-connected 784-500-250-10 "
                          "network (batch 100); rbm = CD-1 step of a 784-500 RBM (batch 100); crbm_pmp = CD-1 step of the "
-                         "config-3 CRBM with probabilistic max pooling")
+                         "config-3 CRBM with probabilistic max pooling; fft = backward-data pass of a 32-channel layer with "
+                         "12x12 filters through dll_conv_full_bwd_fft (and the direct kernel's time beside it)")
     ap.add_argument("--pmc-calib", action="store_true",
                     help="also run one 256 MiB device copy, the known-size kernel that scales rocprofv3's byte counters")
     return ap.parse_args()
@@ -260,6 +261,16 @@ def extra_line(args, B, wl, torch):
         step = lambda: B.dll_rbm_cd1_step(w.batch, w.n_vis, w.n_hid, 0, v0, W, b, c, u, None, w.lr, dW, db, dc, ws=ws)
         batch, flop, name = w.batch, w.flop(), w.name
         what = "CD-1 step of the fully-connected RBM"
+    elif args.mode == "fft":
+        w = wl.large_filter_layer(args.batch) if args.batch else wl.large_filter_layer()
+        cs = w.conv
+        dy, wt = dev(w.dy), dev(w.w)
+        dx, dx_direct = torch.empty(cs.x_shape, device="cuda"), torch.empty(cs.x_shape, device="cuda")
+        ws = B.workspace(B.dll_conv_full_fft_workspace_bytes(cs))
+        step = lambda: B.dll_conv_full_bwd_fft(cs, dy, None, None, wt, dx, ws)
+        direct = lambda: B.dll_conv_full_bwd(cs, dy, None, None, wt, dx_direct)
+        batch, flop, name = cs.N, 2 * cs.macs_exact(), w.name
+        what = "backward-data pass of a 12x12-filter layer through the Fourier transform (FLOP of the direct sum)"
     else:
         cs = wl.config3(args.batch).conv if args.batch else wl.config3().conv
         w = wl.crbm_units(cs, "binary", 2)
@@ -276,10 +287,16 @@ def extra_line(args, B, wl, torch):
            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": name, "batch": batch, "flop_per_step": flop},
            "images_per_s": batch / (ms * 1e-3), "pct_fp32_mfma_peak": 100.0 * gflops / (PEAK_FP32_MFMA_TFLOPS * 1e3)}
+    if args.mode == "fft":
+        out["direct_kernel_ms"] = timed_ms(direct, args, torch)
+        out["max_abs_diff_over_max_abs"] = float((dx - dx_direct).abs().max() / dx_direct.abs().max())
     if not args.no_cpu:
         from oracle import oracle as orc
         act = {"identity": 0, "sigmoid": 1, "relu": 2}
-        if args.mode == "dense":
+        if args.mode == "fft":
+            d = orc.conv_desc(cs.N, cs.C, cs.H, cs.W, cs.K, cs.R, cs.S)
+            cpu_step = lambda: orc.conv_full_bwd(d, w.dy, None, None, w.w)
+        elif args.mode == "dense":
             onet = orc.Net([], [(d.in_, d.out, act[d.act]) for d in w.dense], w.classes, batch=w.batch)
 
             def cpu_step():

@@ -111,6 +111,19 @@ dll_status dll_conv_full_bwd(const dll_conv_desc *d, const float *dy, const floa
                              const unsigned char *pool_idx, const float *w, float *dx, void *ws,
                              size_t ws_bytes, void *stream);
 
+/* The same backward-data layer computed through the Fourier transform (Section II-A: the full
+ * convolution "expressed in terms of" the FFT; image and filter padded to the output size,
+ * transformed, multiplied point by point, transformed back, each image transformed once for all
+ * filters).  Same arguments, same result up to rounding (fp32 throughout).  Padded sides are the
+ * next powers of two: the full-convolution size (Ho + R - 1) x (Wo + S - 1) must not exceed
+ * 64 x 64, else DLL_ERR_UNSUPPORTED (and a workspace size of 0); within that, filters may be
+ * larger than the direct kernels take (R * S > 144).  ws holds the spectra:
+ * dll_conv_full_fft_workspace_bytes(d) bytes, device memory, caller-owned, overwritten. */
+size_t dll_conv_full_fft_workspace_bytes(const dll_conv_desc *d);
+dll_status dll_conv_full_bwd_fft(const dll_conv_desc *d, const float *dy, const float *y,
+                                 const unsigned char *pool_idx, const float *w, float *dx, void *ws,
+                                 size_t ws_bytes, void *stream);
+
 /* Filter-gradient layer (Section II-A, gradient computations):
  *   dw[k,c,r,s] = sum_{n,i,j} dz[n,k,i,j] * xpad[n,c,i+r,j+s];  dbias[k] = sum_{n,i,j} dz[n,k,i,j]
  * with dz as above (same rules for y and pool_idx).  dbias may be NULL.  The batch reduction is a fixed-order tree:

@@ -22,7 +22,8 @@ ACT = {"identity": 0, "sigmoid": 1, "relu": 2}
 SYMBOLS = ["dll_status_string", "dll_conv_workspace_bytes", "dll_conv_valid_fwd", "dll_conv_full_bwd",
            "dll_conv_valid_wgrad", "dll_crbm_workspace_bytes", "dll_crbm_cd1_step",
            "dll_cnn_workspace_bytes", "dll_cnn_train_step", "dll_cnn_forward_workspace_bytes", "dll_cnn_forward",
-           "dll_cnn_train_step_momentum", "dll_crbm_cd1_step_units", "dll_rbm_workspace_bytes", "dll_rbm_cd1_step"]
+           "dll_cnn_train_step_momentum", "dll_crbm_cd1_step_units", "dll_rbm_workspace_bytes", "dll_rbm_cd1_step",
+           "dll_conv_full_fft_workspace_bytes", "dll_conv_full_bwd_fft"]
 VISIBLE = {"binary": 0, "gaussian": 1}
 
 
@@ -65,6 +66,9 @@ def lib() -> C.CDLL:
         L.dll_conv_valid_fwd.argtypes = [pd, vp, vp, vp, vp, vp, vp, sz, vp]
         L.dll_conv_full_bwd.argtypes = [pd, vp, vp, vp, vp, vp, vp, sz, vp]
         L.dll_conv_valid_wgrad.argtypes = [pd, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.dll_conv_full_fft_workspace_bytes.restype = sz
+        L.dll_conv_full_fft_workspace_bytes.argtypes = [pd]
+        L.dll_conv_full_bwd_fft.argtypes = [pd, vp, vp, vp, vp, vp, vp, sz, vp]
         L.dll_crbm_workspace_bytes.restype = sz
         L.dll_crbm_workspace_bytes.argtypes = [pd]
         L.dll_crbm_cd1_step.argtypes = [pd, vp, vp, vp, vp, vp, vp, C.c_float] + [vp] * 8 + [vp, sz, vp]
@@ -124,6 +128,17 @@ def dll_conv_full_bwd(cs: ConvSpec, dy, y, pool_idx, w, dx, ws=None, stream=None
     d = conv_desc(cs)
     _ok(lib().dll_conv_full_bwd(C.byref(d), _ptr(dy), _ptr(y), _ptr(pool_idx), _ptr(w), _ptr(dx), _ptr(ws),
                                 0 if ws is None else ws.numel(), _stream(stream)), "dll_conv_full_bwd")
+
+
+def dll_conv_full_fft_workspace_bytes(cs: ConvSpec) -> int:
+    d = conv_desc(cs)
+    return int(lib().dll_conv_full_fft_workspace_bytes(C.byref(d)))
+
+
+def dll_conv_full_bwd_fft(cs: ConvSpec, dy, y, pool_idx, w, dx, ws, stream=None) -> None:
+    d = conv_desc(cs)
+    _ok(lib().dll_conv_full_bwd_fft(C.byref(d), _ptr(dy), _ptr(y), _ptr(pool_idx), _ptr(w), _ptr(dx), _ptr(ws),
+                                    0 if ws is None else ws.numel(), _stream(stream)), "dll_conv_full_bwd_fft")
 
 
 def dll_conv_valid_wgrad(cs: ConvSpec, x, dy, y, pool_idx, dw, dbias, ws, stream=None) -> None:

@@ -32,7 +32,7 @@ inline size_t y_count(const dll_conv_desc *d) {
 }
 inline size_t x_count(const dll_conv_desc *d) { return (size_t)d->N * d->C * d->H * d->W; }
 
-dll_status check_desc(const dll_conv_desc *d, bool check_act_pool = true) {
+dll_status check_desc(const dll_conv_desc *d, bool check_act_pool = true, bool check_taps = true) {
   if (!d) return DLL_ERR_NULL;
   if (d->N <= 0 || d->C <= 0 || d->H <= 0 || d->W <= 0 || d->K <= 0 || d->R <= 0 || d->S <= 0) return DLL_ERR_SHAPE;
   if (d->pad < 0 || d->pad > d->R - 1 || d->pad > d->S - 1) return DLL_ERR_SHAPE;
@@ -47,7 +47,7 @@ dll_status check_desc(const dll_conv_desc *d, bool check_act_pool = true) {
   if ((size_t)d->N * d->C * d->H * d->W >= lim || (size_t)d->N * d->K * Ho * Wo >= lim ||
       (size_t)d->K * d->C * d->R * d->S >= lim)
     return DLL_ERR_UNSUPPORTED;
-  if (d->R * d->S > 144) return DLL_ERR_UNSUPPORTED;  // filter-gradient kernel: at most 9 tap tiles per channel
+  if (check_taps && d->R * d->S > 144) return DLL_ERR_UNSUPPORTED;  // filter-gradient kernel: at most 9 tap tiles per channel
   return DLL_OK;
 }
 
@@ -157,6 +157,40 @@ dll_status dll_conv_full_bwd(const dll_conv_desc *d, const float *dy, const floa
   if ((const float *)dx == dy || (const float *)dx == y || (const float *)dx == w) return DLL_ERR_SHAPE;
   if (misaligned(dy) || misaligned(y) || misaligned(w) || misaligned(dx) || misaligned(pool_idx)) return DLL_ERR_SHAPE;
   return dev(launch_conv_engine(bwd_args(d, dy, y, pool_idx, w, dx), static_cast<hipStream_t>(stream)));
+}
+
+size_t dll_conv_full_fft_workspace_bytes(const dll_conv_desc *d) {
+  if (check_desc(d, true, false) != DLL_OK) return 0;
+  int lph, lpw;
+  if (!conv_fft_plan(out_h(d), out_w(d), d->R, d->S, &lph, &lpw)) return 0;
+  const size_t F = (size_t)1 << (lph + lpw);
+  Carver c(nullptr, 0);
+  c.take((size_t)d->N * d->K * F * sizeof(float2));
+  c.take((size_t)d->K * d->C * F * sizeof(float2));
+  return c.used;
+}
+
+dll_status dll_conv_full_bwd_fft(const dll_conv_desc *d, const float *dy, const float *y, const unsigned char *pool_idx,
+                                 const float *w, float *dx, void *ws, size_t ws_bytes, void *stream) {
+  dll_status st = check_desc(d, true, false);   // any filter size the transform can hold
+  if (st != DLL_OK) return st;
+  if (!dy || !w || !dx || (output_required(d) && !y) || (d->pool == 2 && !pool_idx)) return DLL_ERR_NULL;
+  if ((const float *)dx == dy || (const float *)dx == y || (const float *)dx == w) return DLL_ERR_SHAPE;
+  int lph, lpw;
+  if (!conv_fft_plan(out_h(d), out_w(d), d->R, d->S, &lph, &lpw)) return DLL_ERR_UNSUPPORTED;
+  st = check_ws(ws, ws_bytes, dll_conv_full_fft_workspace_bytes(d));
+  if (st != DLL_OK) return st;
+  const size_t F = (size_t)1 << (lph + lpw);
+  Carver c(ws, ws_bytes);
+  ConvFftArgs a;
+  a.dy = dy; a.y = y; a.idx = pool_idx;
+  a.act = flagged_relu(d, y) ? ACT_RELU_FLAGGED : d->act; a.pool = d->pool;
+  a.N = d->N; a.K = d->K; a.C = d->C; a.Ho = out_h(d); a.Wo = out_w(d); a.R = d->R; a.S = d->S;
+  a.H = d->H; a.W = d->W; a.pad = d->pad;
+  a.w = w; a.dx = dx;
+  a.xf = static_cast<float2 *>(c.take((size_t)d->N * d->K * F * sizeof(float2)));
+  a.wf = static_cast<float2 *>(c.take((size_t)d->K * d->C * F * sizeof(float2)));
+  return dev(launch_conv_full_fft(a, static_cast<hipStream_t>(stream)));
 }
 
 dll_status dll_conv_valid_wgrad(const dll_conv_desc *d, const float *x, const float *dy, const float *y,

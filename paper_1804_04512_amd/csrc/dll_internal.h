@@ -73,6 +73,21 @@ hipError_t launch_conv_engine(const ConvEngineArgs &a, hipStream_t stream);
 bool conv_fewout_applies(const ConvEngineArgs &a);
 hipError_t launch_conv_fewout(const ConvEngineArgs &a, hipStream_t stream);
 
+// Backward-data through the Fourier transform (Section II-A's second route for the full
+// convolution): full-convolution sizes up to 64 x 64.  xf and wf are scratch for the spectra,
+// N*K and K*C images of F = PH*PW complex numbers (PH, PW from conv_fft_plan as powers of two).
+struct ConvFftArgs {
+  const float *dy = nullptr, *y = nullptr;
+  const unsigned char *idx = nullptr;
+  int act = ACT_IDENTITY, pool = 1;       // of the layer whose gradient comes in (ACT_RELU_FLAGGED: flags in idx)
+  int N = 0, K = 0, C = 0, Ho = 0, Wo = 0, R = 0, S = 0, H = 0, W = 0, pad = 0;
+  const float *w = nullptr;               // [K][C][R][S]
+  float *dx = nullptr;                    // [N][C][H][W]
+  float2 *xf = nullptr, *wf = nullptr;
+};
+bool conv_fft_plan(int Ho, int Wo, int R, int S, int *lph, int *lpw);
+hipError_t launch_conv_full_fft(const ConvFftArgs &a, hipStream_t stream);
+
 // ---------------------------------------------------------------------------------------
 // Filter gradient: stage 1 leaves per-wave partial sums in `partial`, stage 2
 // (launch_wgrad_reduce) adds them in a fixed order.

@@ -302,6 +302,16 @@ def crbm_units(cs: ConvSpec, visible: str, hidden_pool: int, seed: int = 16) -> 
                         _f32(rng(seed, 4).random(ushape, dtype=np.float32)), 0.01)
 
 
+def large_filter_layer(batch: int = 64) -> ConvWorkload:
+    """A layer with large filters (32 -> 32 channels, 12x12 filters, 32x32 output maps from 43x43
+    inputs): the case Section II-A sends through the Fourier transform.  Gradients N(0, 1), filters
+    N(0, sqrt(2/fan_in)); x and bias are not used by the backward-data pass and stay empty."""
+    cs = ConvSpec(batch, 32, 43, 43, 32, 12, 12, 0, "identity", 1)
+    return ConvWorkload(17, "large_filter_full_convolution", cs, x=np.zeros((0,), np.float32),
+                        w=_f32(rng(17, 1).normal(0.0, np.sqrt(2.0 / (cs.C * cs.R * cs.S)), cs.w_shape)),
+                        bias=np.zeros((0,), np.float32), dy=_f32(rng(17, 3).normal(0.0, 1.0, cs.y_shape)))
+
+
 def forward_flop(w: CnnWorkload) -> int:
     """Exact multiply-adds x 2 of one inference pass."""
     return 2 * sum(c.macs_exact() for c in w.conv) + 2 * sum(w.batch * d.in_ * d.out for d in w.dense)

@@ -113,6 +113,59 @@ def test_trio_matches_oracle(cs):
     check_trio(cs, x, w, b, dy)
 
 
+FFT_CASES = [
+    ConvSpec(2, 1, 28, 28, 40, 9, 9, 0, "sigmoid", 1),        # CRBM shape: 20x20 maps, 9x9 filters, full size 28 -> 32x32
+    ConvSpec(3, 5, 40, 36, 7, 15, 11, 0, "identity", 1),      # large non-square filters, 26x26 maps, full 40x36 -> 64x64
+    ConvSpec(2, 3, 30, 22, 6, 5, 5, 2, "relu", 2),            # padded layer (the crop starts at 2), pooled ReLU
+    ConvSpec(2, 4, 24, 24, 8, 3, 3, 1, "sigmoid", 2),         # pooled sigmoid: act' from the pooled output
+    ConvSpec(1, 2, 64, 64, 3, 17, 17, 0, "relu", 1),          # the largest supported full size, 48x48 maps
+    ConvSpec(2, 2, 3, 5, 3, 2, 4, 0, "identity", 1),          # tiny: padded sides 4 x 8, fewer butterflies than threads
+    ConvSpec(1, 1, 1, 1, 1, 1, 1, 0, "identity", 1),          # degenerate: a single product
+]
+
+
+@pytest.mark.parametrize("cs", FFT_CASES, ids=lambda c: f"N{c.N}C{c.C}_{c.H}x{c.W}_K{c.K}_{c.R}x{c.S}p{c.pad}_{c.act}_pool{c.pool}")
+def test_full_convolution_through_fft_matches_oracle(cs):
+    """Backward-data computed through the Fourier transform against the oracle's plain sum, and
+    against the direct kernel; with the ReLU flags instead of the layer output as well."""
+    x, w, b, dy = rand_layer(cs, 3000 + cs.R * 13 + cs.K)
+    d = odesc(cs)
+    y_o, idx_o = orc.conv_valid_fwd(d, x, w, b)
+    dx_o = orc.conv_full_bwd(d, dy, y_o, idx_o, w)
+    idx = dev(idx_o) if cs.pool == 2 else None
+    ws = B.workspace(B.dll_conv_full_fft_workspace_bytes(cs))
+    assert B.dll_conv_full_fft_workspace_bytes(cs) > 0
+    dx_f = torch.full(cs.x_shape, float("nan"), device="cuda")
+    B.dll_conv_full_bwd_fft(cs, dev(dy), dev(y_o), idx, dev(w), dx_f, ws)
+    assert max_rel_err(host(dx_f), dx_o) <= TOL_GRAD
+    if cs.R * cs.S <= 144:   # filters the direct kernels take
+        dx_d = torch.full(cs.x_shape, float("nan"), device="cuda")
+        B.dll_conv_full_bwd(cs, dev(dy), dev(y_o), idx, dev(w), dx_d)
+        assert max_rel_err(host(dx_f), host(dx_d)) <= 1e-5
+    if cs.act == "relu" and cs.pool == 2:
+        # the library's own forward pass writes the activity flags; without y they decide act'
+        yg = torch.empty(cs.y_shape, device="cuda")
+        ig = torch.empty(cs.y_shape, dtype=torch.uint8, device="cuda")
+        B.dll_conv_valid_fwd(cs, dev(x), dev(w), dev(b), yg, ig)
+        a, c = torch.empty(cs.x_shape, device="cuda"), torch.empty(cs.x_shape, device="cuda")
+        B.dll_conv_full_bwd_fft(cs, dev(dy), None, ig, dev(w), a, ws)
+        B.dll_conv_full_bwd_fft(cs, dev(dy), yg, ig, dev(w), c, ws)
+        assert np.array_equal(host(a), host(c))
+
+
+def test_full_convolution_through_fft_limits():
+    big = ConvSpec(1, 1, 66, 20, 2, 3, 3, 0, "identity", 1)   # full size 66 rows: beyond one LDS image
+    assert B.dll_conv_full_fft_workspace_bytes(big) == 0
+    t = lambda *s: torch.zeros(s, device="cuda")
+    with pytest.raises(B.DllError) as e:
+        B.dll_conv_full_bwd_fft(big, t(*big.y_shape), None, None, t(*big.w_shape), t(*big.x_shape), B.workspace(1 << 20))
+    assert e.value.status == 3
+    ok = ConvSpec(1, 2, 12, 12, 3, 5, 5, 0, "identity", 1)
+    with pytest.raises(B.DllError) as e:                     # workspace too small
+        B.dll_conv_full_bwd_fft(ok, t(*ok.y_shape), None, None, t(*ok.w_shape), t(*ok.x_shape), B.workspace(256))
+    assert e.value.status == 4
+
+
 def test_config1_single_conv_layer():
     w1 = wl.config1()
     check_trio(w1.conv, w1.x, w1.w, w1.bias, w1.dy)
