@@ -165,7 +165,7 @@ size_t dll_conv_full_fft_workspace_bytes(const dll_conv_desc *d) {
   if (!conv_fft_plan(out_h(d), out_w(d), d->R, d->S, &lph, &lpw)) return 0;
   const size_t F = (size_t)1 << (lph + lpw);
   Carver c(nullptr, 0);
-  c.take((size_t)d->N * d->K * F * sizeof(float2));
+  c.take((size_t)((d->N + 1) / 2) * d->K * F * sizeof(float2));   // two batch images per complex image
   c.take((size_t)d->K * d->C * F * sizeof(float2));
   return c.used;
 }
@@ -188,7 +188,7 @@ dll_status dll_conv_full_bwd_fft(const dll_conv_desc *d, const float *dy, const 
   a.N = d->N; a.K = d->K; a.C = d->C; a.Ho = out_h(d); a.Wo = out_w(d); a.R = d->R; a.S = d->S;
   a.H = d->H; a.W = d->W; a.pad = d->pad;
   a.w = w; a.dx = dx;
-  a.xf = static_cast<float2 *>(c.take((size_t)d->N * d->K * F * sizeof(float2)));
+  a.xf = static_cast<float2 *>(c.take((size_t)((d->N + 1) / 2) * d->K * F * sizeof(float2)));
   a.wf = static_cast<float2 *>(c.take((size_t)d->K * d->C * F * sizeof(float2)));
   return dev(launch_conv_full_fft(a, static_cast<hipStream_t>(stream)));
 }

@@ -16,6 +16,10 @@
 //                          products of the two spectra (both in the same bit-reversed order, so
 //                          no reordering pass exists anywhere), then columns and rows back by
 //                          decimation in time (bit-reversed in, natural out), scaled, cropped.
+// The filters are real, so convolving is linear over the complex numbers with real coefficients:
+// two images n, n+1 of the batch ride through all three stages as ONE complex signal
+// dz[n] + i dz[n+1], and the real and imaginary parts of the result are dx[n] and dx[n+1].  That
+// halves the image transforms, the products and the inverse transforms.
 // All arithmetic is fp32; the result differs from the direct sum by rounding only (a few 1e-7 of
 // the largest output).
 #include "dll_internal.h"
@@ -73,6 +77,10 @@ struct FftFwdArgs {
   const unsigned char *src_idx;
   int src_dz, src_act, src_pool;
   int count, H, W;             // real image size before padding (a dz map: pre-pool size)
+  int pair_stride;             // > 0: workgroup g packs images g' and g' + pair_stride (the same filter map of
+                               // two neighbouring batch images) as real and imaginary part; count = images given,
+                               // planes = maps per batch image
+  int planes;
   int lph, lpw;                // log2 of the padded sides
   float2 *out;                 // [count][PH * PW], bit-reversed order
 };
@@ -104,22 +112,30 @@ __global__ __launch_bounds__(kFftThreads) void fft2_forward_kernel(const FftFwdA
   extern __shared__ float2 fbuf[];   // [PH * PW] + twiddles
   const int PH = 1 << a.lph, PW = 1 << a.lpw, F = PH * PW;
   float2 *tw = fbuf + F;
-  const int img = blockIdx.x;
+  // packed: workgroup (pair p, plane k) takes images (2p, k) and (2p + 1, k) of [N][planes]
+  int img = blockIdx.x, img2 = -1;
+  if (a.pair_stride > 0) {
+    const int p = blockIdx.x / a.planes, k = blockIdx.x - p * a.planes;
+    img = 2 * p * a.planes + k;
+    img2 = img + a.pair_stride < a.count ? img + a.pair_stride : -1;
+  }
   make_twiddles(tw);
   for (int e = threadIdx.x; e < F; e += kFftThreads) {
     const int i = e >> a.lpw, j = e & (PW - 1);
-    const float v = (i < a.H && j < a.W) ? fft_src_value(a, img, i, j) : 0.0f;
-    fbuf[e] = make_float2(v, 0.0f);
+    const bool in = i < a.H && j < a.W;
+    const float v = in ? fft_src_value(a, img, i, j) : 0.0f;
+    const float v2 = (in && img2 >= 0) ? fft_src_value(a, img2, i, j) : 0.0f;
+    fbuf[e] = make_float2(v, v2);
   }
   __syncthreads();
   for (int s = 0; s < a.lpw; ++s) fft_pass<false>(fbuf, tw, a.lpw, PH, 1, PW, false, s);   // along the rows
   for (int s = 0; s < a.lph; ++s) fft_pass<false>(fbuf, tw, a.lph, PW, PW, 1, true, s);    // down the columns
-  float2 *dst = a.out + (long)img * F;
+  float2 *dst = a.out + (long)blockIdx.x * F;
   for (int e = threadIdx.x; e < F; e += kFftThreads) dst[e] = fbuf[e];
 }
 
 struct FftInvArgs {
-  const float2 *xf;   // [N][K][F]
+  const float2 *xf;   // [ceil(N/2)][K][F]: batch images 2p (real part) and 2p + 1 (imaginary part)
   const float2 *wf;   // [K][C][F]
   int N, K, C;
   int lph, lpw;
@@ -131,13 +147,13 @@ __global__ __launch_bounds__(kFftThreads) void fft2_product_inverse_kernel(const
   extern __shared__ float2 fbuf[];
   const int PH = 1 << a.lph, PW = 1 << a.lpw, F = PH * PW;
   float2 *tw = fbuf + F;
-  const int c = blockIdx.x, n = blockIdx.y;
+  const int c = blockIdx.x, pr = blockIdx.y, n = 2 * pr;
   make_twiddles(tw);
   constexpr int kSlots = (1 << (2 * kMaxLog)) / kFftThreads;   // 16 spectrum entries per thread at 64 x 64
   float2 acc[kSlots];
 #pragma unroll
   for (int q = 0; q < kSlots; ++q) acc[q] = make_float2(0.0f, 0.0f);
-  const float2 *xp = a.xf + (long)n * a.K * F;
+  const float2 *xp = a.xf + (long)pr * a.K * F;
   const float2 *wp = a.wf + (long)c * F;
   for (int k = 0; k < a.K; ++k) {
     // loads of a k first, products after: entries past F re-read entry 0 and are never stored
@@ -166,9 +182,13 @@ __global__ __launch_bounds__(kFftThreads) void fft2_product_inverse_kernel(const
   for (int s = 0; s < a.lpw; ++s) fft_pass<true>(fbuf, tw, a.lpw, PH, 1, PW, false, s);   // rows back
   const float scale = 1.0f / (float)F;
   float *dst = a.out + ((long)n * a.C + c) * a.H * a.W;
+  const long next = (long)a.C * a.H * a.W;   // the pair's second image
+  const bool two = n + 1 < a.N;
   for (int e = threadIdx.x; e < a.H * a.W; e += kFftThreads) {
     const int i = e / a.W, j = e - i * a.W;
-    dst[e] = fbuf[((i + a.off) << a.lpw) + j + a.off].x * scale;
+    const float2 v = fbuf[((i + a.off) << a.lpw) + j + a.off];
+    dst[e] = v.x * scale;
+    if (two) dst[e + next] = v.y * scale;
   }
 }
 
@@ -199,18 +219,21 @@ hipError_t launch_conv_full_fft(const ConvFftArgs &g, hipStream_t stream) {
   x.src = g.dy; x.src_y = g.y; x.src_idx = g.idx;
   x.src_dz = 1; x.src_act = g.act; x.src_pool = g.pool;
   x.count = g.N * g.K; x.H = g.Ho; x.W = g.Wo; x.lph = lph; x.lpw = lpw;
+  x.pair_stride = g.K; x.planes = g.K;
   x.out = g.xf;
-  hipLaunchKernelGGL(fft2_forward_kernel, dim3(x.count), dim3(kFftThreads), lds, stream, x);
+  const int pairs = (g.N + 1) / 2;
+  hipLaunchKernelGGL(fft2_forward_kernel, dim3(pairs * g.K), dim3(kFftThreads), lds, stream, x);
   FftFwdArgs f;
   f.src = g.w; f.src_y = nullptr; f.src_idx = nullptr;
   f.src_dz = 0; f.src_act = ACT_IDENTITY; f.src_pool = 1;
   f.count = g.K * g.C; f.H = g.R; f.W = g.S; f.lph = lph; f.lpw = lpw;
+  f.pair_stride = 0; f.planes = 1;
   f.out = g.wf;
   hipLaunchKernelGGL(fft2_forward_kernel, dim3(f.count), dim3(kFftThreads), lds, stream, f);
   FftInvArgs v;
   v.xf = g.xf; v.wf = g.wf; v.N = g.N; v.K = g.K; v.C = g.C; v.lph = lph; v.lpw = lpw;
   v.H = g.H; v.W = g.W; v.off = g.pad; v.out = g.dx;
-  hipLaunchKernelGGL(fft2_product_inverse_kernel, dim3(g.C, g.N), dim3(kFftThreads), lds, stream, v);
+  hipLaunchKernelGGL(fft2_product_inverse_kernel, dim3(g.C, pairs), dim3(kFftThreads), lds, stream, v);
   return hipGetLastError();
 }
 

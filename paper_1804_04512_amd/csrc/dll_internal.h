@@ -75,7 +75,7 @@ hipError_t launch_conv_fewout(const ConvEngineArgs &a, hipStream_t stream);
 
 // Backward-data through the Fourier transform (Section II-A's second route for the full
 // convolution): full-convolution sizes up to 64 x 64.  xf and wf are scratch for the spectra,
-// N*K and K*C images of F = PH*PW complex numbers (PH, PW from conv_fft_plan as powers of two).
+// ceil(N/2)*K and K*C images of F = PH*PW complex numbers (PH, PW from conv_fft_plan as powers of two).
 struct ConvFftArgs {
   const float *dy = nullptr, *y = nullptr;
   const unsigned char *idx = nullptr;
