@@ -111,8 +111,8 @@ dll_status dll_conv_full_bwd(const dll_conv_desc *d, const float *dy, const floa
                              const unsigned char *pool_idx, const float *w, float *dx, void *ws,
                              size_t ws_bytes, void *stream);
 
-/* The same backward-data layer computed through the Fourier transform (Section II-A: the full
- * convolution "expressed in terms of" the FFT; image and filter padded to the output size,
+/* The same backward-data layer computed through the Fourier transform (Section II-A's first
+ * implementation of the full convolution: image and filter padded to the output size,
  * transformed, multiplied point by point, transformed back, each image transformed once for all
  * filters).  Same arguments, same result up to rounding (fp32 throughout).  Padded sides are the
  * next powers of two: the full-convolution size (Ho + R - 1) x (Wo + S - 1) must not exceed
