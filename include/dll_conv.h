@@ -89,7 +89,7 @@ const char *dll_status_string(dll_status s);
 /* Bytes of scratch the three single-layer calls below need at most (host computation). */
 size_t dll_conv_workspace_bytes(const dll_conv_desc *d);
 
-/* Forward layer (Section II-A, "valid convolution for the forward pass"):
+/* Forward layer (Section II-A: the valid convolution of the forward pass):
  *   z[n,k,i,j] = bias[k] + sum_{c,r,s} xpad[n,c,i+r,j+s] * w[k,c,r,s]
  *   y = maxpool2x2(act(z)) when pool == 2, else act(z)
  * pool_idx (required iff pool == 2) receives, in bits 0-1 of each byte, 2*a+b of the window's
@@ -100,7 +100,7 @@ dll_status dll_conv_valid_fwd(const dll_conv_desc *d, const float *x, const floa
                               const float *bias, float *y, unsigned char *pool_idx, void *ws,
                               size_t ws_bytes, void *stream);
 
-/* Backward-data layer (Section II-A, "full convolution for the backward pass"):
+/* Backward-data layer (Section II-A: the full convolution of the backward pass):
  *   dz = unpool(dy, pool_idx) * act'(y)          (never stored)
  *   dx[n,c,i,j] = sum_{k,r,s} dz[n,k,i+pad-r,j+pad-s] * w[k,c,r,s]
  * pool_idx is required iff pool == 2; only bits 0-1 of its bytes are read when y is given.

@@ -14,7 +14,7 @@
  * and nothing here is used by, or shares code with, the GPU library.
  *
  * Every pointer is a HOST pointer.  Tensors are contiguous, row-major:
- *   x  [N][C][H][W]       minibatch of N images (Section II-A: "batch of N images")
+ *   x  [N][C][H][W]       minibatch of N images (Section II-A: N images per batch)
  *   w  [K][C][R][S]       K kernels
  *   y  [N][K][Ho/pool][Wo/pool]   with Ho = H + 2*pad - R + 1 (stride 1)
  *   pool_idx  same shape as y, one byte each: 2*a+b of the window's first maximum
