@@ -143,53 +143,83 @@ struct FftInvArgs {
   float *out;         // [N][C][H][W]
 };
 
+// PT pairs of batch images x CT channels per workgroup: every spectrum entry that is loaded serves
+// PT (a filter's) or CT (an image's) products, which is what the product stage is bound by.
+template <int PT, int CT>
 __global__ __launch_bounds__(kFftThreads) void fft2_product_inverse_kernel(const FftInvArgs a) {
   extern __shared__ float2 fbuf[];
   const int PH = 1 << a.lph, PW = 1 << a.lpw, F = PH * PW;
   float2 *tw = fbuf + F;
-  const int c = blockIdx.x, pr = blockIdx.y, n = 2 * pr;
+  const int c0 = blockIdx.x * CT, pr0 = blockIdx.y * PT;
+  const int pairs = (a.N + 1) / 2;
   make_twiddles(tw);
   constexpr int kSlots = (1 << (2 * kMaxLog)) / kFftThreads;   // 16 spectrum entries per thread at 64 x 64
-  float2 acc[kSlots];
+  constexpr int kBatch = PT * CT > 1 ? kSlots / 2 : kSlots;    // entries whose loads are in flight together
+  float2 acc[PT][CT][kSlots];
 #pragma unroll
-  for (int q = 0; q < kSlots; ++q) acc[q] = make_float2(0.0f, 0.0f);
-  const float2 *xp = a.xf + (long)pr * a.K * F;
-  const float2 *wp = a.wf + (long)c * F;
+  for (int i = 0; i < PT; ++i)
+#pragma unroll
+    for (int j = 0; j < CT; ++j)
+#pragma unroll
+      for (int q = 0; q < kSlots; ++q) acc[i][j][q] = make_float2(0.0f, 0.0f);
+  // surplus rows and columns of the last tiles re-read the last pair / channel and are never stored
+  const float2 *xp[PT], *wp[CT];
+#pragma unroll
+  for (int i = 0; i < PT; ++i) xp[i] = a.xf + (long)min(pr0 + i, pairs - 1) * a.K * F;
+#pragma unroll
+  for (int j = 0; j < CT; ++j) wp[j] = a.wf + (long)min(c0 + j, a.C - 1) * F;
   for (int k = 0; k < a.K; ++k) {
-    // loads of a k first, products after: entries past F re-read entry 0 and are never stored
-    float2 xv[kSlots], wv[kSlots];
 #pragma unroll
-    for (int q = 0; q < kSlots; ++q) {
-      const int e = threadIdx.x + q * kFftThreads;
-      const int ec = e < F ? e : 0;
-      xv[q] = xp[(long)k * F + ec];
-      wv[q] = wp[(long)k * a.C * F + ec];
-    }
+    for (int h = 0; h < kSlots / kBatch; ++h) {
+      // loads first, products after: entries past F re-read entry 0 and are never stored
+      float2 xv[PT][kBatch], wv[CT][kBatch];
 #pragma unroll
-    for (int q = 0; q < kSlots; ++q) {
-      const float2 p = cmul(xv[q], wv[q]);
-      acc[q].x += p.x;
-      acc[q].y += p.y;
+      for (int q = 0; q < kBatch; ++q) {
+        const int e = threadIdx.x + (h * kBatch + q) * kFftThreads;
+        const int ec = e < F ? e : 0;
+#pragma unroll
+        for (int i = 0; i < PT; ++i) xv[i][q] = xp[i][(long)k * F + ec];
+#pragma unroll
+        for (int j = 0; j < CT; ++j) wv[j][q] = wp[j][(long)k * a.C * F + ec];
+      }
+#pragma unroll
+      for (int q = 0; q < kBatch; ++q)
+#pragma unroll
+        for (int i = 0; i < PT; ++i)
+#pragma unroll
+          for (int j = 0; j < CT; ++j) {
+            const float2 p = cmul(xv[i][q], wv[j][q]);
+            acc[i][j][h * kBatch + q].x += p.x;
+            acc[i][j][h * kBatch + q].y += p.y;
+          }
     }
   }
-#pragma unroll
-  for (int q = 0; q < kSlots; ++q) {
-    const int e = threadIdx.x + q * kFftThreads;
-    if (e < F) fbuf[e] = acc[q];
-  }
-  __syncthreads();
-  for (int s = 0; s < a.lph; ++s) fft_pass<true>(fbuf, tw, a.lph, PW, PW, 1, true, s);    // columns back
-  for (int s = 0; s < a.lpw; ++s) fft_pass<true>(fbuf, tw, a.lpw, PH, 1, PW, false, s);   // rows back
   const float scale = 1.0f / (float)F;
-  float *dst = a.out + ((long)n * a.C + c) * a.H * a.W;
   const long next = (long)a.C * a.H * a.W;   // the pair's second image
-  const bool two = n + 1 < a.N;
-  for (int e = threadIdx.x; e < a.H * a.W; e += kFftThreads) {
-    const int i = e / a.W, j = e - i * a.W;
-    const float2 v = fbuf[((i + a.off) << a.lpw) + j + a.off];
-    dst[e] = v.x * scale;
-    if (two) dst[e + next] = v.y * scale;
-  }
+#pragma unroll
+  for (int i = 0; i < PT; ++i)
+#pragma unroll
+    for (int j = 0; j < CT; ++j) {
+      const int pr = pr0 + i, c = c0 + j, n = 2 * pr;
+      if (pr >= pairs || c >= a.C) continue;   // uniform over the workgroup
+#pragma unroll
+      for (int q = 0; q < kSlots; ++q) {
+        const int e = threadIdx.x + q * kFftThreads;
+        if (e < F) fbuf[e] = acc[i][j][q];
+      }
+      __syncthreads();
+      for (int s = 0; s < a.lph; ++s) fft_pass<true>(fbuf, tw, a.lph, PW, PW, 1, true, s);    // columns back
+      for (int s = 0; s < a.lpw; ++s) fft_pass<true>(fbuf, tw, a.lpw, PH, 1, PW, false, s);   // rows back
+      float *dst = a.out + ((long)n * a.C + c) * a.H * a.W;
+      const bool two = n + 1 < a.N;
+      for (int e = threadIdx.x; e < a.H * a.W; e += kFftThreads) {
+        const int r = e / a.W, col = e - r * a.W;
+        const float2 v = fbuf[((r + a.off) << a.lpw) + col + a.off];
+        dst[e] = v.x * scale;
+        if (two) dst[e + next] = v.y * scale;
+      }
+      __syncthreads();   // the image is read out before the next one overwrites it
+    }
 }
 
 int log2_ceil(int v) {
@@ -233,7 +263,11 @@ hipError_t launch_conv_full_fft(const ConvFftArgs &g, hipStream_t stream) {
   FftInvArgs v;
   v.xf = g.xf; v.wf = g.wf; v.N = g.N; v.K = g.K; v.C = g.C; v.lph = lph; v.lpw = lpw;
   v.H = g.H; v.W = g.W; v.off = g.pad; v.out = g.dx;
-  hipLaunchKernelGGL(fft2_product_inverse_kernel, dim3(g.C, pairs), dim3(kFftThreads), lds, stream, v);
+  // 2 x 2 tiles once there is enough work to fill the chip with them
+  if ((long)pairs * g.C >= 4 * 256)
+    hipLaunchKernelGGL((fft2_product_inverse_kernel<2, 2>), dim3((g.C + 1) / 2, (pairs + 1) / 2), dim3(kFftThreads), lds, stream, v);
+  else
+    hipLaunchKernelGGL((fft2_product_inverse_kernel<1, 1>), dim3(g.C, pairs), dim3(kFftThreads), lds, stream, v);
   return hipGetLastError();
 }
 

@@ -121,6 +121,7 @@ FFT_CASES = [
     ConvSpec(1, 2, 64, 64, 3, 17, 17, 0, "relu", 1),          # the largest supported full size, 48x48 maps
     ConvSpec(2, 2, 3, 5, 3, 2, 4, 0, "identity", 1),          # tiny: padded sides 4 x 8, fewer butterflies than threads
     ConvSpec(1, 1, 1, 1, 1, 1, 1, 0, "identity", 1),          # degenerate: a single product
+    ConvSpec(63, 33, 10, 12, 2, 3, 3, 0, "relu", 1),          # enough (pair, channel) work for the 2 x 2 tiles, both edges ragged
 ]
 
 
