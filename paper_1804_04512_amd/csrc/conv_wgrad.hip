@@ -716,7 +716,10 @@ bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, int po
   if (resident < 1) resident = 1;
   long G = 256 * resident / ((long)plan->nchunks * kgroups);
   if (G < 1) G = 1;
-  if (G > (items + 1) / 2) G = (items + 1) / 2;
+  // fewer tiles than CUs: one tile per workgroup (what counts there is the length of the longest
+  // workgroup, not the number of partial blocks)
+  const long cap = items <= 256 ? items : (items + 1) / 2;
+  if (G > cap) G = cap;
   if (G < 1) G = 1;
   plan->G = (int)G;
   plan->n_partials = plan->G;
