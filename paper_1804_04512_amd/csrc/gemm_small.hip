@@ -93,9 +93,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_small_kernel(const SmallParam
 #pragma unroll
     for (int j = 0; j < 2; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-  float afA[2][8], bfA[2][8], afB[2][8], bfB[2][8];
+  float afA[2][8], bfA[2][8], afB[2][8], bfB[2][8], afC[2][8], bfC[2][8], afD[2][8], bfD[2][8];
   auto load_tile = [&](int kt, float (&af)[2][8], float (&bf)[2][8]) __attribute__((always_inline)) {
-    // a k-tile past the end is loaded (from clamped addresses) like any other and never multiplied
     load_frags<A_KC>(af, a.A, a.a_m, a.a_k, m0, a.M, kt * KT, a.Kdim, i16, kq, p.a_vec != 0, false);
     load_frags<B_KC>(bf, a.B, a.b_n, a.b_k, n0, a.N, kt * KT, a.Kdim, i16, kq, p.b_vec != 0, kt * KT + KT > a.Kdim);
   };
@@ -107,17 +106,30 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_small_kernel(const SmallParam
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf[j][s], af[i][s], acc[i][j], 0, 0, 0);
   };
-  // this wavefront's k-tiles: wave, wave + WAVES, ...; two register sets, the next tile's loads in flight
+  // this wavefront's k-tiles: wave, wave + WAVES, ...; four register sets, so that three k-tiles'
+  // loads are in flight while one is multiplied: with a handful of workgroups on the whole chip
+  // (a batch-by-64 product over a long k) the loop runs at memory latency divided by that depth
   if (wave < nkt) {
+    // (uniform conditions: a wavefront with one k-tile issues one k-tile's loads)
     load_tile(wave, afA, bfA);
-    for (int kt = wave; kt < nkt; kt += 2 * WAVES) {
-      load_tile(kt + WAVES, afB, bfB);
+    if (wave + WAVES < nkt) load_tile(wave + WAVES, afB, bfB);
+    if (wave + 2 * WAVES < nkt) load_tile(wave + 2 * WAVES, afC, bfC);
+    for (int kt = wave; kt < nkt; kt += 4 * WAVES) {
+      if (kt + 3 * WAVES < nkt) load_tile(kt + 3 * WAVES, afD, bfD);
       __builtin_amdgcn_sched_barrier(0);
       multiply(afA, bfA);
       __builtin_amdgcn_sched_barrier(0);
-      load_tile(kt + 2 * WAVES, afA, bfA);
+      if (kt + 4 * WAVES < nkt) load_tile(kt + 4 * WAVES, afA, bfA);
       __builtin_amdgcn_sched_barrier(0);
       if (kt + WAVES < nkt) multiply(afB, bfB);
+      __builtin_amdgcn_sched_barrier(0);
+      if (kt + 5 * WAVES < nkt) load_tile(kt + 5 * WAVES, afB, bfB);
+      __builtin_amdgcn_sched_barrier(0);
+      if (kt + 2 * WAVES < nkt) multiply(afC, bfC);
+      __builtin_amdgcn_sched_barrier(0);
+      if (kt + 6 * WAVES < nkt) load_tile(kt + 6 * WAVES, afC, bfC);
+      __builtin_amdgcn_sched_barrier(0);
+      if (kt + 3 * WAVES < nkt) multiply(afD, bfD);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
