@@ -25,7 +25,6 @@ namespace {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr int TS = 32;    // tile side
 constexpr int KT = 32;    // k-tile
 
 __device__ __forceinline__ float act_apply(int act, float z) {
@@ -50,12 +49,12 @@ struct SmallParams {
 // output rows/columns that are never stored.  A k past the end re-reads k = 0 (a finite value);
 // `zero_tail` (uniform; set for ONE operand of the k-tile that overhangs Kdim) then clears those
 // entries, so that their products vanish.
-template <bool KC>
-__device__ __forceinline__ void load_frags(float (&frag)[2][8], const float *src, long sx, long sk, int x0, int X, int k0,
+template <bool KC, int Q>
+__device__ __forceinline__ void load_frags(float (&frag)[Q][8], const float *src, long sx, long sk, int x0, int X, int k0,
                                            int Kdim, int i16, int kq, bool vec, bool zero_tail) {
   const int k = k0 + 8 * kq;
 #pragma unroll
-  for (int t = 0; t < 2; ++t) {
+  for (int t = 0; t < Q; ++t) {
     const long base = (long)min(x0 + 16 * t + i16, X - 1) * sx;
     if (KC && vec) {   // uniform: rows are whole aligned 16-byte groups, so a group is entirely in or out of range
 #pragma unroll
@@ -71,40 +70,43 @@ __device__ __forceinline__ void load_frags(float (&frag)[2][8], const float *src
   }
   if (zero_tail) {
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < Q; ++t)
 #pragma unroll
       for (int s = 0; s < 8; ++s)
         if (k + s >= Kdim) frag[t][s] = 0.0f;
   }
 }
 
-template <bool A_KC, bool B_KC, int WAVES>
+// Q = 2: 32 x 32 tile (four 16 x 16 quarters); Q = 1: 16 x 16 tile, for products whose 32 x 32 tiles
+// would occupy a small part of the chip with long k loops
+template <bool A_KC, bool B_KC, int WAVES, int Q>
 __global__ __launch_bounds__(WAVES * 64) void gemm_small_kernel(const SmallParams p) {
-  __shared__ __attribute__((aligned(16))) float red[WAVES][4][64][4];   // [wavefront][quarter][lane][4]
+  constexpr int TS = 16 * Q;
+  __shared__ __attribute__((aligned(16))) float red[WAVES][Q * Q][64][4];   // [wavefront][quarter][lane][4]
   const GemmArgs &a = p.a;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i16 = lane & 15, kq = lane >> 4;
   const int m0 = blockIdx.y * TS, n0 = blockIdx.x * TS;
   const int nkt = (a.Kdim + KT - 1) / KT;
 
-  floatx4 acc[2][2];   // [m quarter][n quarter]; lane holds C(m = i16, n = 4 kq + v)
+  floatx4 acc[Q][Q];   // [m quarter][n quarter]; lane holds C(m = i16, n = 4 kq + v)
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < Q; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < Q; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-  float afA[2][8], bfA[2][8], afB[2][8], bfB[2][8], afC[2][8], bfC[2][8], afD[2][8], bfD[2][8];
-  auto load_tile = [&](int kt, float (&af)[2][8], float (&bf)[2][8]) __attribute__((always_inline)) {
-    load_frags<A_KC>(af, a.A, a.a_m, a.a_k, m0, a.M, kt * KT, a.Kdim, i16, kq, p.a_vec != 0, false);
-    load_frags<B_KC>(bf, a.B, a.b_n, a.b_k, n0, a.N, kt * KT, a.Kdim, i16, kq, p.b_vec != 0, kt * KT + KT > a.Kdim);
+  float afA[Q][8], bfA[Q][8], afB[Q][8], bfB[Q][8], afC[Q][8], bfC[Q][8], afD[Q][8], bfD[Q][8];
+  auto load_tile = [&](int kt, float (&af)[Q][8], float (&bf)[Q][8]) __attribute__((always_inline)) {
+    load_frags<A_KC, Q>(af, a.A, a.a_m, a.a_k, m0, a.M, kt * KT, a.Kdim, i16, kq, p.a_vec != 0, false);
+    load_frags<B_KC, Q>(bf, a.B, a.b_n, a.b_k, n0, a.N, kt * KT, a.Kdim, i16, kq, p.b_vec != 0, kt * KT + KT > a.Kdim);
   };
-  auto multiply = [&](const float (&af)[2][8], const float (&bf)[2][8]) __attribute__((always_inline)) {
+  auto multiply = [&](const float (&af)[Q][8], const float (&bf)[Q][8]) __attribute__((always_inline)) {
 #pragma unroll
     for (int s = 0; s < 8; ++s)
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < Q; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf[j][s], af[i][s], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < Q; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf[j][s], af[i][s], acc[i][j], 0, 0, 0);
   };
   // this wavefront's k-tiles: wave, wave + WAVES, ...; four register sets, so that three k-tiles'
   // loads are in flight while one is multiplied: with a handful of workgroups on the whole chip
@@ -136,14 +138,14 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_small_kernel(const SmallParam
 
   // ---- the partial tiles meet in LDS
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < Q; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
-      *reinterpret_cast<float4 *>(&red[wave][2 * i + j][lane][0]) = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+    for (int j = 0; j < Q; ++j)
+      *reinterpret_cast<float4 *>(&red[wave][Q * i + j][lane][0]) = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
   __syncthreads();
-  if (wave >= 4) return;
-  // ---- wavefront w < 4 finishes quarter w: rows m0 + 16 (w >> 1) .., columns n0 + 16 (w & 1) ..
-  const int m = m0 + 16 * (wave >> 1) + i16, n = n0 + 16 * (wave & 1) + 4 * kq;
+  if (wave >= Q * Q) return;
+  // ---- wavefront w < Q * Q finishes quarter w: rows m0 + 16 (w / Q) .., columns n0 + 16 (w % Q) ..
+  const int m = m0 + 16 * (wave / Q) + i16, n = n0 + 16 * (wave % Q) + 4 * kq;
   float c[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
   for (int w = 0; w < WAVES; ++w) {   // wavefront order, whatever finished first
@@ -192,9 +194,17 @@ hipError_t launch_gemm_small(const GemmArgs &a, hipStream_t stream) {
   const bool a_kc = a.a_k == 1, b_kc = a.b_k == 1;
   p.a_vec = a_kc && al16(a.A) && a.a_m % 4 == 0 && a.Kdim % 4 == 0;
   p.b_vec = b_kc && al16(a.B) && a.b_n % 4 == 0 && a.Kdim % 4 == 0;
+  // 16 x 16 tiles where 32 x 32 ones would leave three quarters of the chip idle under long k loops
+  const long tiles32 = (long)((a.N + 31) / 32) * ((a.M + 31) / 32);
+  const bool fine = tiles32 <= 64 && a.Kdim >= 256;
+  const int TS = fine ? 16 : 32;
   const dim3 grid((a.N + TS - 1) / TS, (a.M + TS - 1) / TS);
   // (eight wavefronts per workgroup, sharing the k range in eighths, measured slower at every size tried)
-#define DLL_SMALL(AK, BK_) hipLaunchKernelGGL((gemm_small_kernel<AK, BK_, 4>), grid, dim3(256), 0, stream, p)
+#define DLL_SMALL(AK, BK_)                                                                                         \
+  do {                                                                                                             \
+    if (fine) hipLaunchKernelGGL((gemm_small_kernel<AK, BK_, 4, 1>), grid, dim3(256), 0, stream, p);               \
+    else hipLaunchKernelGGL((gemm_small_kernel<AK, BK_, 4, 2>), grid, dim3(256), 0, stream, p);                    \
+  } while (0)
   if (a_kc && b_kc) DLL_SMALL(true, true);
   else if (a_kc) DLL_SMALL(true, false);
   else if (b_kc) DLL_SMALL(false, true);
