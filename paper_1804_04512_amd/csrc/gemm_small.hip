@@ -4,16 +4,16 @@
 // Such a product cannot fill the chip; what it costs is a chain of latencies (launch, first
 // loads, one LDS round trip and one barrier per k-tile, a split-K reduction launch).  This kernel
 // shortens the chain instead of raising the rate:
-//   * 32 x 32 output tile per workgroup (many more workgroups than the 128 x 64 tiles of the big
-//     kernel, far fewer products with padding);
+//   * 32 x 32 or, for the smallest products, 16 x 16 output tile per workgroup (many more workgroups
+//     than the 128 x 64 tiles of the big kernel, far fewer products with padding);
 //   * the four wavefronts split the k range BETWEEN them and each multiplies the whole tile, so
 //     there is no LDS staging and no barrier inside the k loop at all: every lane loads its
-//     MFMA fragments straight from global memory, the next k-tile's loads in flight while the
-//     current one is multiplied.  Inside a k-tile of 32, the lane with k-quarter kq owns the 8
+//     MFMA fragments straight from global memory, the next three k-tiles' loads in flight while
+//     the current one is multiplied.  Inside a k-tile of 32, the lane with k-quarter kq owns the 8
 //     consecutive k values 8*kq .. 8*kq+7 of both operands (any assignment works as long as both
 //     operands use the same one), which makes a k-contiguous operand two 16-byte loads per row;
 //   * the partial tiles meet in LDS once, are added in wavefront order (results do not depend
-//     on timing), and four wavefronts finish one 16 x 16 quarter each: bias, activation,
+//     on timing), and one wavefront per 16 x 16 quarter of the tile finishes it: bias, activation,
 //     act' of a reference tensor, store and/or fused parameter update.  No split-K partials in
 //     global memory, no reduction launch.
 // Every global load is issued unconditionally from a clamped address; nothing is masked before
@@ -194,9 +194,11 @@ hipError_t launch_gemm_small(const GemmArgs &a, hipStream_t stream) {
   const bool a_kc = a.a_k == 1, b_kc = a.b_k == 1;
   p.a_vec = a_kc && al16(a.A) && a.a_m % 4 == 0 && a.Kdim % 4 == 0;
   p.b_vec = b_kc && al16(a.B) && a.b_n % 4 == 0 && a.Kdim % 4 == 0;
-  // 16 x 16 tiles where 32 x 32 ones would leave three quarters of the chip idle under long k loops
+  // 16 x 16 tiles while 32 x 32 ones would number at most two per CU: four times the workgroups, a
+  // quarter of the multiplications per wavefront (measured faster for every product of the small
+  // workloads, whatever its k)
   const long tiles32 = (long)((a.N + 31) / 32) * ((a.M + 31) / 32);
-  const bool fine = tiles32 <= 64 && a.Kdim >= 256;
+  const bool fine = tiles32 <= 512;
   const int TS = fine ? 16 : 32;
   const dim3 grid((a.N + TS - 1) / TS, (a.M + TS - 1) / TS);
   // (eight wavefronts per workgroup, sharing the k range in eighths, measured slower at every size tried)
