@@ -147,12 +147,17 @@ __device__ __forceinline__ void engine_epilogue_as(const ConvEngineArgs &a, floa
           // pooling unit's probability is the sum of its block
           const int Hp = a.Hout >> 1, Wp = a.Wout >> 1;
           const int ob = ((n * a.Kout + ko) * Hp + py) * Wp + px0;
+          float ub[4];   // the blocks' uniform numbers, loaded together from clamped addresses
+          if (a.sample) {
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) ub[mt] = a.uniform[ob - px0 + min(px0 + mt, Wp - 1)];   // stays inside the row
+          }
 #pragma unroll
           for (int mt = 0; mt < 4; ++mt) {
             if (px0 + mt >= Wp) continue;
             if (a.out_pool) a.out_pool[ob + mt] = (pr[mt][0] + pr[mt][1]) + (pr[mt][2] + pr[mt][3]);
             if (a.sample) {
-              const float u = a.uniform[ob + mt];
+              const float u = ub[mt];
               float lo = 0.0f;
               bool taken = false;
 #pragma unroll
@@ -195,11 +200,18 @@ __device__ __forceinline__ void engine_epilogue_as(const ConvEngineArgs &a, floa
               *reinterpret_cast<float4 *>(a.sample + o + 4) = make_float4(sv[4], sv[5], sv[6], sv[7]);
             }
           } else {
+            // ragged row end: the uniform numbers first, all of them and from clamped addresses (a
+            // load behind the per-lane range check would be waited for on its own, eight in a row)
+            float uv[8];
+            if (a.sample && ACT != ACT_PMP) {
+#pragma unroll
+              for (int e = 0; e < 8; ++e) uv[e] = a.uniform[o - ox + min(ox + e, a.Wout - 1)];   // stays inside the row
+            }
 #pragma unroll
             for (int e = 0; e < 8; ++e)
               if (ox + e < a.Wout) {
                 a.out[o + e] = yv[e];
-                if (a.sample) a.sample[o + e] = ACT == ACT_PMP ? sv[e] : (a.uniform[o + e] < yv[e] ? 1.f : 0.f);
+                if (a.sample) a.sample[o + e] = ACT == ACT_PMP ? sv[e] : (uv[e] < yv[e] ? 1.f : 0.f);
               }
           }
         }
