@@ -560,6 +560,7 @@ dll_status run_cnn_step(const dll_net_desc *net, float *const *params, float *co
   }
   if (logits) nb.act[L + D] = logits;
   int logits_split = 1;
+  bool loss_fused = false;
   for (int q = 0; q < D; ++q) {
     const dll_dense_desc *dd = &net->dense[q];
     GemmArgs g;
@@ -573,6 +574,11 @@ dll_status run_cnn_step(const dll_net_desc *net, float *const *params, float *co
     g.partial = nb.partial;
     // the logits' split-K partials are added by the loss kernel, which reads them anyway
     if (q == D - 1 && g.split_k > 1) { g.defer_reduce = true; logits_split = g.split_k; }
+    // few classes and a small product: the loss rides in the product's epilogue
+    if (q == D - 1 && gemm_fuses_softmax(g.M, g.N, g.Kdim)) {
+      g.sm_labels = labels; g.sm_dz = nb.dz[D - 1]; g.sm_rowloss = nb.rowloss; g.sm_scale = 1.0f / (float)B;
+      loss_fused = true;
+    }
     if ((st = dev(launch_gemm(g, s))) != DLL_OK) return st;
   }
   // ---- loss
@@ -586,9 +592,11 @@ dll_status run_cnn_step(const dll_net_desc *net, float *const *params, float *co
     return r;
   };
   tail.rowloss = nb.rowloss; tail.rows = B; tail.loss = loss;
-  st = dev(launch_softmax_ce(nb.act[L + D], labels, B, net->classes, nullptr, nb.dz[D - 1], nb.rowloss,
-                             logits_split > 1 ? nb.partial : nullptr, logits_split, params[2 * (L + D - 1) + 1], s));
-  if (st != DLL_OK) return st;
+  if (!loss_fused) {
+    st = dev(launch_softmax_ce(nb.act[L + D], labels, B, net->classes, nullptr, nb.dz[D - 1], nb.rowloss,
+                               logits_split > 1 ? nb.partial : nullptr, logits_split, params[2 * (L + D - 1) + 1], s));
+    if (st != DLL_OK) return st;
+  }
   // ---- dense backward: data gradient first (old weights), then weight gradient + update
   for (int q = D - 1; q >= 0; --q) {
     const dll_dense_desc *dd = &net->dense[q];

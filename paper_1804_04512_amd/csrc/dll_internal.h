@@ -152,6 +152,12 @@ struct GemmArgs {
   // split_k > 1 only: leave the partials as they are; the consumer adds them (in split order,
   // then the bias) itself.  Only for an identity epilogue without update.
   bool defer_reduce = false;
+  // Softmax + cross-entropy in the epilogue (only where gemm_fuses_softmax() says so: every row of
+  // logits lies inside one 16-column tile): Cout receives the logits, sm_dz (strides of Cout)
+  // (softmax - onehot(label)) * sm_scale, sm_rowloss[m] = -ln softmax[label].
+  const int *sm_labels = nullptr;
+  float *sm_dz = nullptr, *sm_rowloss = nullptr;
+  float sm_scale = 1.0f;
 };
 int gemm_pick_split_k(int M, int N, int Kdim);
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream);
@@ -159,6 +165,7 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream);
 // short latency chain instead: 32 x 32 tiles, the k range split between the wavefronts of a
 // workgroup, no split-K partials (gemm_pick_split_k returns 1 for them).  launch_gemm routes there.
 bool gemm_is_small(int M, int N, int Kdim);
+bool gemm_fuses_softmax(int M, int N, int Kdim);
 hipError_t launch_gemm_small(const GemmArgs &a, hipStream_t stream);
 
 // Column sums out[n] = sum_m A(m,n) of a row-major [M][N] array; optional update.

@@ -855,6 +855,7 @@ int gemm_pick_split_k(int M, int N, int Kdim) {
 
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream) {
   if (a.split_k <= 1 && gemm_is_small(a.M, a.N, a.Kdim)) return launch_gemm_small(a, stream);
+  if (a.sm_labels) return hipErrorInvalidValue;   // the fused loss exists in the small-product kernel only
   GemmParams p;
   p.a = a;
   if (p.a.split_k < 1) p.a.split_k = 1;

@@ -166,6 +166,37 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_small_kernel(const SmallParam
     uv[v] = a.update ? a.update[o[v]] : 0.0f;
     vv[v] = a.vel ? a.vel[o[v]] : 0.0f;
   }
+  if (Q == 1 && a.sm_labels) {
+    // Softmax + cross-entropy on the finished logits: a row's 16 columns sit in the four lanes
+    // i16, i16 + 16, i16 + 32, i16 + 48 (four columns each), so two exchanges complete a row.
+    // Columns past N count as -inf / 0; rows past M compute on clamped data and store nothing.
+    const int label = a.sm_labels[min(m, a.M - 1)];
+    float z[4], mx = -INFINITY;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      z[v] = c[v] + bv[v];
+      if (n + v < a.N) mx = fmaxf(mx, z[v]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    float e[4], sum = 0.0f;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      e[v] = n + v < a.N ? expf(z[v] - mx) : 0.0f;
+      sum += e[v];
+    }
+    sum += __shfl_xor(sum, 16, 64);
+    sum += __shfl_xor(sum, 32, 64);
+    const float inv = 1.0f / sum;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      if (!ok[v]) continue;
+      if (a.Cout) a.Cout[o[v]] = z[v];
+      a.sm_dz[o[v]] = (e[v] * inv - (n + v == label ? 1.0f : 0.0f)) * a.sm_scale;
+      if (n + v == label) a.sm_rowloss[m] = -(z[v] - mx - logf(sum));
+    }
+    return;
+  }
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
     c[v] = act_apply(a.act, c[v] + bv[v]);
@@ -186,7 +217,13 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_small_kernel(const SmallParam
 // persistent kernel's rate matters more than the latency chain.
 bool gemm_is_small(int M, int N, int Kdim) { return (long)M * N * Kdim <= (1L << 27); }
 
+// Tiles of 16 x 16 (the launcher's choice below for this size) hold whole rows of up to 16 logits.
+bool gemm_fuses_softmax(int M, int N, int Kdim) { return gemm_is_small(M, N, Kdim) && N <= 16 && (M + 31) / 32 <= 512; }
+
 hipError_t launch_gemm_small(const GemmArgs &a, hipStream_t stream) {
+  if (a.sm_labels && (!gemm_fuses_softmax(a.M, a.N, a.Kdim) || !a.sm_dz || !a.sm_rowloss || a.act != ACT_IDENTITY || a.update ||
+                      a.C_ref))
+    return hipErrorInvalidValue;
   SmallParams p;
   p.a = a;
   p.a.split_k = 1;
