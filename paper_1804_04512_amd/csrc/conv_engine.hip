@@ -17,6 +17,7 @@
 // channel roles swapped, which turns the paper's "full convolution" (Section II-A) into this
 // same valid-convolution engine run on an input padded by R-1-pad.
 #include "dll_internal.h"
+#include <cstdlib>
 
 #include <type_traits>
 
@@ -1000,6 +1001,7 @@ hipError_t launch_conv_engine(const ConvEngineArgs &a, hipStream_t stream) {
   // S of every 4*ceil((16+S-1)/4) window columns, clearly beats Kout of 16 channel columns
   if (a.Kout <= 3 && a.Kout * (4 * ((16 + a.S - 1 + 3) / 4)) * 3 < 16 * a.S * 2 && conv_fewout_applies(a))
     return launch_conv_fewout(a, stream);
+  { static const bool no_wino = getenv("DLL_NO_WINO") != nullptr; if (!no_wino && conv_wino_applies(a)) return launch_conv_wino(a, stream); }
   if (a.Hout > 8 && conv3x3c16_applies(a)) {
     // 16 output channels: 4 waves x 2 row pairs; 32: 8 waves x 1 row pair (more waves hide the
     // longer per-step operand traffic better than more accumulators do)

@@ -1,0 +1,214 @@
+// Forward 3x3 convolution of a 16 -> 16 channel layer with ReLU and 2x2 max pooling in the
+// minimal-filtering form F(2x2, 3x3): every 2x2 block of outputs comes from a 4x4 input patch,
+//   Y = At [ (G g Gt) .* (Bt d B) ] A,
+// so that the 36 multiplications per output pixel, input channel and filter of the direct sum
+// become 16 per 2x2 block = 4 per pixel.  The products over the input channels are the matrix
+// part: for each of the 16 transform points p, M_p[tile][k] = sum_c V_p[tile][c] U_p[c][k] runs on
+// fp32 MFMA (16 tiles x 16 filters x 4 channels per instruction); the transforms are additions
+// on the vector pipe.  A 2x2 output block is exactly one pooling window, so bias, ReLU, the
+// maximum and its position follow in registers and only the pooled map is stored.
+//
+// Tile: 16 x 32 outputs = 8 x 16 blocks per workgroup; wavefront w owns block rows 2w, 2w+1; lane
+// (i16, kq) transforms the patch of block column i16 for the channels kq, 4+kq, 8+kq, 12+kq (its
+// MFMA A fragments) and ends up with the 16 point sums of blocks 4kq..4kq+3 for filter i16.
+// Results differ from the direct sum by rounding only (a few 1e-7 of the output scale).
+#include "dll_internal.h"
+
+namespace dllk {
+namespace {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWT = 256;
+constexpr int kC = 16, kK = 16;          // channels in, filters
+constexpr int kRS = 36;                  // row stride of the halo tile in LDS (34 columns used)
+constexpr int kRows = 18;
+constexpr int kPS = kRows * kRS + 8;     // plane stride: 656 = 16 mod 32, the four channel groups of a wavefront land 16 banks apart
+
+struct WinoParams {
+  ConvEngineArgs a;
+  int tiles_x, tiles_y, items;
+};
+
+__global__ __launch_bounds__(kWT, 2) void conv3x3_wino_kernel(const WinoParams p) {
+  __shared__ __attribute__((aligned(16))) float xs[kC * kPS];       // [c][row][col], zero-padded halo tile
+  __shared__ __attribute__((aligned(16))) float us[16 * kC * kK];   // [point][c][k], transformed filters
+  const ConvEngineArgs &a = p.a;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i16 = lane & 15, kq = lane >> 4;
+
+  // ---- filters: U = G g Gt, one (channel, filter) pair per thread
+  {
+    const int c = tid >> 4, k = tid & 15;
+    const float *g = a.w + ((long)k * kC + c) * 9;
+    float gv[9];
+#pragma unroll
+    for (int e = 0; e < 9; ++e) gv[e] = g[e];
+    float t[4][3];   // G g
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+      t[0][j] = gv[j];
+      t[1][j] = 0.5f * (gv[j] + gv[3 + j] + gv[6 + j]);
+      t[2][j] = 0.5f * (gv[j] - gv[3 + j] + gv[6 + j]);
+      t[3][j] = gv[6 + j];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float u0 = t[i][0], u1 = 0.5f * (t[i][0] + t[i][1] + t[i][2]), u2 = 0.5f * (t[i][0] - t[i][1] + t[i][2]), u3 = t[i][2];
+      us[((4 * i + 0) * kC + c) * kK + k] = u0;
+      us[((4 * i + 1) * kC + c) * kK + k] = u1;
+      us[((4 * i + 2) * kC + c) * kK + k] = u2;
+      us[((4 * i + 3) * kC + c) * kK + k] = u3;
+    }
+  }
+  const float bias = a.bias ? a.bias[i16] : 0.0f;
+  const int Hp = a.Hout >> 1, Wp = a.Wout >> 1;
+
+  // Staging slots: 16 channels x 18 rows x 9 groups of four columns (36 >= 34; the last two are never
+  // read), eleven rounds of 256 threads.  What does not depend on the tile is worked out once: the
+  // byte offset from the halo tile's first element, the LDS offset, the row and the column group.
+  // The loads are range-checked buffer loads of 16 bytes at 4-byte alignment: an offset past the end
+  // of the tensor (or "negative", i.e. huge) reads zeros, which is what padding needs.
+  constexpr int kSlots = kC * kRows * 9, kRounds = (kSlots + kWT - 1) / kWT;
+  constexpr unsigned kOob = 0x80000000u;
+  const __amdgpu_buffer_rsrc_t rs_x =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.src), 0, (int)(4u * (unsigned)a.N * kC * a.Hin * a.Win), 0x00020000);
+  int goff[kRounds], loff[kRounds], srow[kRounds], sq[kRounds];
+#pragma unroll
+  for (int it = 0; it < kRounds; ++it) {
+    const int e = tid + it * kWT;
+    const int c = e / (kRows * 9), rem = e - c * (kRows * 9);
+    const int r = rem / 9, q = rem - r * 9;
+    const bool in = e < kSlots;
+    goff[it] = in ? 4 * ((c * a.Hin + r) * a.Win + 4 * q) : (int)kOob;
+    loff[it] = in ? c * kPS + r * kRS + 4 * q : -1;
+    srow[it] = r;
+    sq[it] = q;
+  }
+  for (int item = blockIdx.x; item < p.items; item += gridDim.x) {
+    const int tx = item % p.tiles_x, ty = (item / p.tiles_x) % p.tiles_y, n = item / (p.tiles_x * p.tiles_y);
+    const int oy0 = ty * 16, ox0 = tx * 32;
+    __syncthreads();   // the previous tile's readers are done (first tile: the filters are in place)
+    // ---- halo tile: all loads first, then the edge fixes and the LDS stores
+    {
+      const int base = 4 * (((n * kC) * a.Hin + oy0 - 1) * a.Win + ox0 - 1);   // bytes; negative at the very first tile
+      const bool left = ox0 == 0, right = ox0 + 32 >= a.Win;
+      const bool inner_rows = oy0 >= 1 && oy0 + 17 <= a.Hin;
+      floatx4 v[kRounds];
+#pragma unroll
+      for (int it = 0; it < kRounds; ++it) {
+        int off = goff[it] + base;
+        if (!inner_rows) {
+          const int gi = oy0 - 1 + srow[it];
+          if (gi < 0 || gi >= a.Hin) off = (int)kOob;
+        }
+        // the groups that overhang the image on the left / right are read one / three columns further
+        // in, so that no access starts before the tensor or runs past its end
+        if (left && sq[it] == 0) off += 4;
+        if (right && sq[it] == 8) off -= 12;
+        if (goff[it] == (int)kOob) off = (int)kOob;
+        v[it] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rs_x, off, 0, 0));
+      }
+#pragma unroll
+      for (int it = 0; it < kRounds; ++it) {
+        if (loff[it] < 0) continue;
+        floatx4 t = v[it];
+        if (left && sq[it] == 0) t = floatx4{0.0f, t[0], t[1], t[2]};    // column -1 of the image is padding
+        if (right && sq[it] == 8) t = floatx4{t[3], 0.0f, 0.0f, 0.0f};   // column Win is padding (the two after it are never read)
+        *reinterpret_cast<floatx4 *>(xs + loff[it]) = t;
+      }
+    }
+    __syncthreads();
+#pragma unroll 1
+    for (int grp = 0; grp < 2; ++grp) {
+      const int tr = 2 * wave + grp;   // block row inside the tile
+      floatx4 acc[16];
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[q] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        // input transform V = Bt d B of the lane's patch, channel 4s + kq
+        const float *d0 = xs + (4 * s + kq) * kPS + (2 * tr) * kRS + 2 * i16;
+        float d[4][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float2 lo = *reinterpret_cast<const float2 *>(d0 + i * kRS);
+          const float2 hi = *reinterpret_cast<const float2 *>(d0 + i * kRS + 2);
+          d[i][0] = lo.x; d[i][1] = lo.y; d[i][2] = hi.x; d[i][3] = hi.y;
+        }
+        float t[4][4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          t[0][j] = d[0][j] - d[2][j];
+          t[1][j] = d[1][j] + d[2][j];
+          t[2][j] = d[2][j] - d[1][j];
+          t[3][j] = d[1][j] - d[3][j];
+        }
+        float V[16];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          V[4 * i + 0] = t[i][0] - t[i][2];
+          V[4 * i + 1] = t[i][1] + t[i][2];
+          V[4 * i + 2] = t[i][2] - t[i][1];
+          V[4 * i + 3] = t[i][1] - t[i][3];
+        }
+        // the 16 point products of this channel quartet: A = V (block i16, channel kq), B = U (channel kq, filter i16)
+        const float *up = us + (4 * s + kq) * kK + i16;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(V[q], up[q * kC * kK], acc[q], 0, 0, 0);
+      }
+      // ---- output transform, bias, ReLU, pooling: lane holds blocks 4kq + v (v = 0..3) of filter i16
+      float yv[4];
+      unsigned char iv[4];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        float sr[2][4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          sr[0][j] = acc[j][v] + acc[4 + j][v] + acc[8 + j][v];
+          sr[1][j] = acc[4 + j][v] - acc[8 + j][v] - acc[12 + j][v];
+        }
+        const float y00 = sr[0][0] + sr[0][1] + sr[0][2], y01 = sr[0][1] - sr[0][2] - sr[0][3];
+        const float y10 = sr[1][0] + sr[1][1] + sr[1][2], y11 = sr[1][1] - sr[1][2] - sr[1][3];
+        float m = y00;
+        int arg = 0;
+        if (y01 > m) { m = y01; arg = 1; }
+        if (y10 > m) { m = y10; arg = 2; }
+        if (y11 > m) { m = y11; arg = 3; }
+        const float o = m + bias;
+        yv[v] = o > 0.0f ? o : 0.0f;
+        iv[v] = (unsigned char)(arg | (yv[v] > 0.0f ? 0 : kIdxInactive));
+      }
+      const long o = (((long)n * kK + i16) * Hp + (oy0 >> 1) + tr) * Wp + (ox0 >> 1) + 4 * kq;
+      *reinterpret_cast<float4 *>(a.out + o) = make_float4(yv[0], yv[1], yv[2], yv[3]);
+      if (a.out_idx) *reinterpret_cast<uchar4 *>(a.out_idx + o) = make_uchar4(iv[0], iv[1], iv[2], iv[3]);
+    }
+  }
+}
+
+inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
+
+}  // namespace
+
+// Plain source tensor, 16 channels in and out, padded 3x3, ReLU + 2x2 pooling, whole 16 x 32 tiles.
+bool conv_wino_applies(const ConvEngineArgs &a) {
+  return !a.src_dz && !a.w_flip && a.Cin == kC && a.Kout == kK && a.R == 3 && a.S == 3 && a.pad_h == 1 && a.pad_w == 1 &&
+         a.act == ACT_RELU && a.pool == 2 && !a.sample && !a.out_pool && a.Hout == a.Hin && a.Wout == a.Win &&
+         a.Hout % 16 == 0 && a.Wout % 32 == 0 && aligned16(a.out) && (!a.out_idx || (reinterpret_cast<uintptr_t>(a.out_idx) & 3u) == 0) &&
+         (long)a.N * kC * a.Hin * a.Win < (1L << 31);
+}
+
+hipError_t launch_conv_wino(const ConvEngineArgs &a, hipStream_t stream) {
+  if (!conv_wino_applies(a)) return hipErrorInvalidValue;
+  WinoParams p;
+  p.a = a;
+  p.tiles_x = a.Wout / 32;
+  p.tiles_y = a.Hout / 16;
+  p.items = a.N * p.tiles_x * p.tiles_y;
+  int blocks = 256 * 2;   // two resident workgroups per CU (LDS)
+  if (blocks > p.items) blocks = p.items;
+  hipLaunchKernelGGL(conv3x3_wino_kernel, dim3(blocks), dim3(kWT), 0, stream, p);
+  return hipGetLastError();
+}
+
+}  // namespace dllk
