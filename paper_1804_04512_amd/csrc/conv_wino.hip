@@ -8,7 +8,8 @@
 // on the vector pipe.  A 2x2 output block is exactly one pooling window, so bias, ReLU, the
 // maximum and its position follow in registers and only the pooled map is stored.
 //
-// Tile: 16 x 32 outputs = 8 x 16 blocks per workgroup; wavefront w owns block rows 2w, 2w+1; lane
+// Tile: 8 x 32 outputs = 4 x 16 blocks per workgroup (16 x 32 as a second instance); wavefront w owns
+// block row w; lane
 // (i16, kq) transforms the patch of block column i16 for the channels kq, 4+kq, 8+kq, 12+kq (its
 // MFMA A fragments) and ends up with the 16 point sums of blocks 4kq..4kq+3 for filter i16.
 // Results differ from the direct sum by rounding only (a few 1e-7 of the output scale).
@@ -22,15 +23,21 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int kWT = 256;
 constexpr int kC = 16, kK = 16;          // channels in, filters
 constexpr int kRS = 36;                  // row stride of the halo tile in LDS (34 columns used)
-constexpr int kRows = 18;
-constexpr int kPS = kRows * kRS + 8;     // plane stride: 656 = 16 mod 32, the four channel groups of a wavefront land 16 banks apart
+// GRP block rows per wavefront: 2 -> tiles of 16 x 32 outputs (18 halo rows), 1 -> 8 x 32 (10 halo rows, less
+// LDS: more workgroups per CU).  Plane stride = 16 mod 32: the four channel groups of a wavefront land 16 banks apart.
+template <int GRP> struct WinoGeom {
+  static constexpr int kRows = 8 * GRP + 2;
+  static constexpr int kPS = GRP == 2 ? kRows * kRS + 8 : kRows * kRS + 16;   // 656, 376
+};
 
 struct WinoParams {
   ConvEngineArgs a;
   int tiles_x, tiles_y, items;
 };
 
-__global__ __launch_bounds__(kWT, 2) void conv3x3_wino_kernel(const WinoParams p) {
+template <int GRP>
+__global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(const WinoParams p) {
+  constexpr int kRows = WinoGeom<GRP>::kRows, kPS = WinoGeom<GRP>::kPS, kTH = 8 * GRP;
   __shared__ __attribute__((aligned(16))) float xs[kC * kPS];       // [c][row][col], zero-padded halo tile
   __shared__ __attribute__((aligned(16))) float us[16 * kC * kK];   // [point][c][k], transformed filters
   const ConvEngineArgs &a = p.a;
@@ -91,10 +98,10 @@ __global__ __launch_bounds__(kWT, 2) void conv3x3_wino_kernel(const WinoParams p
   floatx4 v[kRounds];
   auto load_tile = [&](int item) __attribute__((always_inline)) {
     const int tx = item % p.tiles_x, ty = (item / p.tiles_x) % p.tiles_y, n = item / (p.tiles_x * p.tiles_y);
-    const int oy0 = ty * 16, ox0 = tx * 32;
+    const int oy0 = ty * kTH, ox0 = tx * 32;
     const int base = 4 * (((n * kC) * a.Hin + oy0 - 1) * a.Win + ox0 - 1);   // bytes; negative at the very first tile
     const bool left = ox0 == 0, right = ox0 + 32 >= a.Win;
-    const bool inner_rows = oy0 >= 1 && oy0 + 17 <= a.Hin;
+    const bool inner_rows = oy0 >= 1 && oy0 + kTH + 1 <= a.Hin;
 #pragma unroll
     for (int it = 0; it < kRounds; ++it) {
       int off = goff[it] + base;
@@ -125,27 +132,34 @@ __global__ __launch_bounds__(kWT, 2) void conv3x3_wino_kernel(const WinoParams p
   };
   for (int item = blockIdx.x; item < p.items; item += gridDim.x) {
     const int tx = item % p.tiles_x, ty = (item / p.tiles_x) % p.tiles_y, n = item / (p.tiles_x * p.tiles_y);
-    const int oy0 = ty * 16, ox0 = tx * 32;
+    const int oy0 = ty * kTH, ox0 = tx * 32;
     __syncthreads();   // the previous tile's readers are done (first tile: the filters are in place)
     load_tile(item);
     store_tile(item);
     __syncthreads();
 #pragma unroll 1
-    for (int grp = 0; grp < 2; ++grp) {
-      const int tr = 2 * wave + grp;   // block row inside the tile
+    for (int grp = 0; grp < GRP; ++grp) {
+      const int tr = GRP * wave + grp;   // block row inside the tile
       floatx4 acc[16];
       const floatx4 zero = floatx4{0.f, 0.f, 0.f, 0.f};   // the first channel quartet starts the sums from it
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        // input transform V = Bt d B of the lane's patch, channel 4s + kq
+      // Per channel quartet s: patch and filter fragments come from LDS in one batch, issued while the
+      // previous quartet's 16 products run (two register sets), so that no product waits for its own read.
+      float dA[4][4], dB[4][4], uA[16], uB[16];
+      auto read_s = [&](int s, float (&d)[4][4], float (&u)[16]) __attribute__((always_inline)) {
         const float *d0 = xs + (4 * s + kq) * kPS + (2 * tr) * kRS + 2 * i16;
-        float d[4][4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const float2 lo = *reinterpret_cast<const float2 *>(d0 + i * kRS);
           const float2 hi = *reinterpret_cast<const float2 *>(d0 + i * kRS + 2);
           d[i][0] = lo.x; d[i][1] = lo.y; d[i][2] = hi.x; d[i][3] = hi.y;
         }
+        const float *up = us + (4 * s + kq) * kK + i16;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) u[q] = up[q * kC * kK];
+      };
+      auto mul_s = [&](bool first, const float (&d)[4][4], const float (&u)[16]) __attribute__((always_inline)) {
+        // input transform V = Bt d B of the lane's patch; then the 16 point products:
+        // A = V (block i16, channel kq), B = U (channel kq, filter i16)
         float t[4][4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -162,11 +176,24 @@ __global__ __launch_bounds__(kWT, 2) void conv3x3_wino_kernel(const WinoParams p
           V[4 * i + 2] = t[i][2] - t[i][1];
           V[4 * i + 3] = t[i][1] - t[i][3];
         }
-        // the 16 point products of this channel quartet: A = V (block i16, channel kq), B = U (channel kq, filter i16)
-        const float *up = us + (4 * s + kq) * kK + i16;
 #pragma unroll
-        for (int q = 0; q < 16; ++q) acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(V[q], up[q * kC * kK], s == 0 ? zero : acc[q], 0, 0, 0);
-      }
+        for (int q = 0; q < 16; ++q) acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(V[q], u[q], first ? zero : acc[q], 0, 0, 0);
+      };
+      read_s(0, dA, uA);
+      read_s(1, dB, uB);
+      __builtin_amdgcn_sched_barrier(0);
+      mul_s(true, dA, uA);
+      __builtin_amdgcn_sched_barrier(0);
+      read_s(2, dA, uA);
+      __builtin_amdgcn_sched_barrier(0);
+      mul_s(false, dB, uB);
+      __builtin_amdgcn_sched_barrier(0);
+      read_s(3, dB, uB);
+      __builtin_amdgcn_sched_barrier(0);
+      mul_s(false, dA, uA);
+      __builtin_amdgcn_sched_barrier(0);
+      mul_s(false, dB, uB);
+      __builtin_amdgcn_sched_barrier(0);
       // ---- output transform, bias, ReLU, pooling: lane holds blocks 4kq + v (v = 0..3) of filter i16
       float yv[4];
       unsigned char iv[4];
@@ -204,7 +231,7 @@ inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 
 bool conv_wino_applies(const ConvEngineArgs &a) {
   return !a.src_dz && !a.w_flip && a.Cin == kC && a.Kout == kK && a.R == 3 && a.S == 3 && a.pad_h == 1 && a.pad_w == 1 &&
          a.act == ACT_RELU && a.pool == 2 && !a.sample && !a.out_pool && a.Hout == a.Hin && a.Wout == a.Win &&
-         a.Hout % 16 == 0 && a.Wout % 32 == 0 && aligned16(a.out) && (!a.out_idx || (reinterpret_cast<uintptr_t>(a.out_idx) & 3u) == 0) &&
+         a.Hout % 8 == 0 && a.Wout % 32 == 0 && aligned16(a.out) && (!a.out_idx || (reinterpret_cast<uintptr_t>(a.out_idx) & 3u) == 0) &&
          (long)a.N * kC * a.Hin * a.Win < (1L << 31);
 }
 
@@ -212,12 +239,15 @@ hipError_t launch_conv_wino(const ConvEngineArgs &a, hipStream_t stream) {
   if (!conv_wino_applies(a)) return hipErrorInvalidValue;
   WinoParams p;
   p.a = a;
+  // 8-row tiles: three workgroups per CU instead of two (measured 80 vs 85 us on the 128 x 128 layer)
+  const int grp = 1;
   p.tiles_x = a.Wout / 32;
-  p.tiles_y = a.Hout / 16;
+  p.tiles_y = a.Hout / (8 * grp);
   p.items = a.N * p.tiles_x * p.tiles_y;
-  int blocks = 256 * 2;   // two resident workgroups per CU (LDS)
+  int blocks = 256 * (grp == 2 ? 2 : 3);   // resident workgroups per CU (LDS, registers)
   if (blocks > p.items) blocks = p.items;
-  hipLaunchKernelGGL(conv3x3_wino_kernel, dim3(blocks), dim3(kWT), 0, stream, p);
+  if (grp == 2) hipLaunchKernelGGL(conv3x3_wino_kernel<2>, dim3(blocks), dim3(kWT), 0, stream, p);
+  else hipLaunchKernelGGL(conv3x3_wino_kernel<1>, dim3(blocks), dim3(kWT), 0, stream, p);
   return hipGetLastError();
 }
 
