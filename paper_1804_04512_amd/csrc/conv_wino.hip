@@ -35,7 +35,10 @@ struct WinoParams {
   int tiles_x, tiles_y, items;
 };
 
-template <int GRP>
+// BWD: the backward-data pass of such a layer instead (the same sum with the filters rotated and
+// transposed): the source is dz = unpool(dy) with the ReLU flags of the pooling bytes, formed while
+// staging from the pooled gradient; the 2x2 output blocks are stored as they are.
+template <int GRP, bool BWD>
 __global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(const WinoParams p) {
   constexpr int kRows = WinoGeom<GRP>::kRows, kPS = WinoGeom<GRP>::kPS, kTH = 8 * GRP;
   __shared__ __attribute__((aligned(16))) float xs[kC * kPS];       // [c][row][col], zero-padded halo tile
@@ -47,10 +50,12 @@ __global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(con
   // ---- filters: U = G g Gt, one (channel, filter) pair per thread
   {
     const int c = tid >> 4, k = tid & 15;
-    const float *g = a.w + ((long)k * kC + c) * 9;
+    // forward: w[k][c][r][s]; backward-data: source channel c is the layer's filter index and the
+    // taps are rotated, g[r][s] = w[c][k][2 - r][2 - s]
+    const float *g = BWD ? a.w + ((long)c * kK + k) * 9 : a.w + ((long)k * kC + c) * 9;
     float gv[9];
 #pragma unroll
-    for (int e = 0; e < 9; ++e) gv[e] = g[e];
+    for (int e = 0; e < 9; ++e) gv[e] = g[BWD ? 8 - e : e];
     float t[4][3];   // G g
 #pragma unroll
     for (int j = 0; j < 3; ++j) {
@@ -91,6 +96,38 @@ __global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(con
     loff[it] = in ? c * kPS + r * kRS + 4 * q : -1;
     srow[it] = r;
     sq[it] = q;
+  }
+  // Backward-data staging slots over the tile's pooled window (rows oy0/2 - 1 .. oy0/2 + kTH/2, columns
+  // ox0/2 - 1 .. ox0/2 + 16): per (channel, pooled row) four groups of four aligned columns, read as
+  // 16 bytes of gradient + 4 pooling bytes, and the two edge columns, read one by one.  Per slot: the
+  // source offset from the window's first element, the LDS offset of entry (0, 0) of its (first)
+  // window, which may lie outside the tile: bit a of `rows` says whether window row a is inside.
+  constexpr int kPR = kTH / 2 + 2;
+  constexpr int kVecSlots = kC * kPR * 4, kVecRounds = BWD ? (kVecSlots + kWT - 1) / kWT : 1;
+  constexpr int kEdgeSlots = kC * kPR * 2;
+  static_assert(kEdgeSlots <= kWT, "one round of edge slots");
+  int voffs[kVecRounds], vwin[kVecRounds], vinfo[kVecRounds];   // vinfo: rows mask (bits 0-1), pr (bits 4-7), exists (bit 8)
+  int eoffs = 0, ewin = 0, einfo = 0;                            // einfo: rows mask, pr, exists, bit 9: right edge
+  if constexpr (BWD) {
+    const int Hs = a.Hin >> 1, Ws = a.Win >> 1;
+    auto rows_of = [&](int pr) { return (2 * pr - 1 >= 0 ? 1 : 0) | (2 * pr < kRows ? 2 : 0); };
+#pragma unroll
+    for (int it = 0; it < kVecRounds; ++it) {
+      const int e = tid + it * kWT;
+      const int c = e / (kPR * 4), rem = e - c * (kPR * 4);
+      const int pr = rem >> 2, g = rem & 3;
+      voffs[it] = (c * Hs + pr) * Ws + 1 + 4 * g;
+      vwin[it] = c * kPS + (2 * pr - 1) * kRS + 2 * (1 + 4 * g) - 1;
+      vinfo[it] = rows_of(pr) | (pr << 4) | (e < kVecSlots ? 1 << 8 : 0);
+    }
+    {
+      const int e = tid;
+      const int c = e / (kPR * 2), rem = e - c * (kPR * 2);
+      const int pr = rem >> 1, right = rem & 1, pc = right ? 17 : 0;
+      eoffs = (c * Hs + pr) * Ws + pc;
+      ewin = c * kPS + (2 * pr - 1) * kRS + 2 * pc - 1;
+      einfo = rows_of(pr) | (pr << 4) | (e < kEdgeSlots ? 1 << 8 : 0) | (right << 9);
+    }
   }
   // global -> registers for one tile, registers -> LDS with the edge fixes.  (Issuing the loads one
   // tile ahead, across the transforms and products of the previous tile, measured slower: 92 vs 86 us
@@ -134,8 +171,57 @@ __global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(con
     const int tx = item % p.tiles_x, ty = (item / p.tiles_x) % p.tiles_y, n = item / (p.tiles_x * p.tiles_y);
     const int oy0 = ty * kTH, ox0 = tx * 32;
     __syncthreads();   // the previous tile's readers are done (first tile: the filters are in place)
-    load_tile(item);
-    store_tile(item);
+    if constexpr (!BWD) {
+      load_tile(item);
+      store_tile(item);
+    } else {
+      // dz halo tile from the pooled gradient.  The tile is cleared with 16-byte stores; then every
+      // pooled element drops its gradient at the recorded position of its window, if that entry lies
+      // inside the tile and the unit is not flagged inactive.  All loads first, stores after.
+      const int Hs = a.Hin >> 1, Ws = a.Win >> 1;   // pooled source size
+      const long pbase = (((long)n * kC) * Hs + (oy0 >> 1) - 1) * Ws + (ox0 >> 1) - 1;
+      float4 gv[kVecRounds];
+      uchar4 fv[kVecRounds];
+      bool vok[kVecRounds];
+#pragma unroll
+      for (int it = 0; it < kVecRounds; ++it) {
+        const int pi = (oy0 >> 1) - 1 + ((vinfo[it] >> 4) & 15);
+        vok[it] = ((vinfo[it] >> 8) & 1) && pi >= 0 && pi < Hs;
+        const long o = vok[it] ? pbase + voffs[it] : 0;   // element 0 stands in (16-byte aligned like every group)
+        gv[it] = *reinterpret_cast<const float4 *>(a.src + o);
+        fv[it] = *reinterpret_cast<const uchar4 *>(a.src_idx + o);
+      }
+      bool eok;
+      float ge;
+      unsigned char fe;
+      {
+        const int pi = (oy0 >> 1) - 1 + ((einfo >> 4) & 15);
+        const int pj = (ox0 >> 1) - 1 + (((einfo >> 9) & 1) ? 17 : 0);
+        eok = ((einfo >> 8) & 1) && pi >= 0 && pi < Hs && pj >= 0 && pj < Ws;
+        const long o = eok ? pbase + eoffs : 0;
+        ge = a.src[o];
+        fe = a.src_idx[o];
+      }
+      for (int e = tid; e < kC * kPS / 4; e += kWT) reinterpret_cast<floatx4 *>(xs)[e] = floatx4{0.f, 0.f, 0.f, 0.f};
+      __syncthreads();
+#pragma unroll
+      for (int it = 0; it < kVecRounds; ++it) {
+        if (!vok[it]) continue;
+        const float g4[4] = {gv[it].x, gv[it].y, gv[it].z, gv[it].w};
+        const unsigned char f4[4] = {fv[it].x, fv[it].y, fv[it].z, fv[it].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int pos = f4[j] & kIdxPosMask;
+          if (!(f4[j] & kIdxInactive) && ((vinfo[it] >> (pos >> 1)) & 1)) xs[vwin[it] + 2 * j + (pos >> 1) * kRS + (pos & 1)] = g4[j];
+        }
+      }
+      if (eok && !(fe & kIdxInactive)) {
+        const int pos = fe & kIdxPosMask;
+        // left edge: only window column 1 is inside the tile; right edge: only column 0
+        const bool col_in = ((einfo >> 9) & 1) ? (pos & 1) == 0 : (pos & 1) == 1;
+        if (col_in && ((einfo >> (pos >> 1)) & 1)) xs[ewin + (pos >> 1) * kRS + (pos & 1)] = ge;
+      }
+    }
     __syncthreads();
 #pragma unroll 1
     for (int grp = 0; grp < GRP; ++grp) {
@@ -194,31 +280,51 @@ __global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(con
       __builtin_amdgcn_sched_barrier(0);
       mul_s(false, dB, uB);
       __builtin_amdgcn_sched_barrier(0);
-      // ---- output transform, bias, ReLU, pooling: lane holds blocks 4kq + v (v = 0..3) of filter i16
+      // ---- output transform: lane holds blocks 4kq + v (v = 0..3) of filter (output channel) i16;
+      // two blocks at a time keep few values alive
       float yv[4];
       unsigned char iv[4];
 #pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        float sr[2][4];
+      for (int h = 0; h < 2; ++h) {
+        float y00[2], y01[2], y10[2], y11[2];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          sr[0][j] = acc[j][v] + acc[4 + j][v] + acc[8 + j][v];
-          sr[1][j] = acc[4 + j][v] - acc[8 + j][v] - acc[12 + j][v];
+        for (int w = 0; w < 2; ++w) {
+          const int v = 2 * h + w;
+          float sr[2][4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            sr[0][j] = acc[j][v] + acc[4 + j][v] + acc[8 + j][v];
+            sr[1][j] = acc[4 + j][v] - acc[8 + j][v] - acc[12 + j][v];
+          }
+          y00[w] = sr[0][0] + sr[0][1] + sr[0][2]; y01[w] = sr[0][1] - sr[0][2] - sr[0][3];
+          y10[w] = sr[1][0] + sr[1][1] + sr[1][2]; y11[w] = sr[1][1] - sr[1][2] - sr[1][3];
         }
-        const float y00 = sr[0][0] + sr[0][1] + sr[0][2], y01 = sr[0][1] - sr[0][2] - sr[0][3];
-        const float y10 = sr[1][0] + sr[1][1] + sr[1][2], y11 = sr[1][1] - sr[1][2] - sr[1][3];
-        float m = y00;
-        int arg = 0;
-        if (y01 > m) { m = y01; arg = 1; }
-        if (y10 > m) { m = y10; arg = 2; }
-        if (y11 > m) { m = y11; arg = 3; }
-        const float o = m + bias;
-        yv[v] = o > 0.0f ? o : 0.0f;
-        iv[v] = (unsigned char)(arg | (yv[v] > 0.0f ? 0 : kIdxInactive));
+        if constexpr (BWD) {
+          // the blocks as they are: two rows of four consecutive columns per pair of blocks
+          float *o0 = a.out + (((long)n * kK + i16) * a.Hout + oy0 + 2 * tr) * a.Wout + ox0 + 8 * kq + 4 * h;
+          *reinterpret_cast<float4 *>(o0) = make_float4(y00[0], y01[0], y00[1], y01[1]);
+          *reinterpret_cast<float4 *>(o0 + a.Wout) = make_float4(y10[0], y11[0], y10[1], y11[1]);
+        } else {
+          // bias, ReLU, pooling: a block is one pooling window
+#pragma unroll
+          for (int w = 0; w < 2; ++w) {
+            const int v = 2 * h + w;
+            float m = y00[w];
+            int arg = 0;
+            if (y01[w] > m) { m = y01[w]; arg = 1; }
+            if (y10[w] > m) { m = y10[w]; arg = 2; }
+            if (y11[w] > m) { m = y11[w]; arg = 3; }
+            const float o = m + bias;
+            yv[v] = o > 0.0f ? o : 0.0f;
+            iv[v] = (unsigned char)(arg | (yv[v] > 0.0f ? 0 : kIdxInactive));
+          }
+        }
       }
-      const long o = (((long)n * kK + i16) * Hp + (oy0 >> 1) + tr) * Wp + (ox0 >> 1) + 4 * kq;
-      *reinterpret_cast<float4 *>(a.out + o) = make_float4(yv[0], yv[1], yv[2], yv[3]);
-      if (a.out_idx) *reinterpret_cast<uchar4 *>(a.out_idx + o) = make_uchar4(iv[0], iv[1], iv[2], iv[3]);
+      if constexpr (!BWD) {
+        const long o = (((long)n * kK + i16) * Hp + (oy0 >> 1) + tr) * Wp + (ox0 >> 1) + 4 * kq;
+        *reinterpret_cast<float4 *>(a.out + o) = make_float4(yv[0], yv[1], yv[2], yv[3]);
+        if (a.out_idx) *reinterpret_cast<uchar4 *>(a.out_idx + o) = make_uchar4(iv[0], iv[1], iv[2], iv[3]);
+      }
     }
   }
 }
@@ -227,12 +333,24 @@ inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 
 
 }  // namespace
 
-// Plain source tensor, 16 channels in and out, padded 3x3, ReLU + 2x2 pooling, whole 16 x 32 tiles.
-bool conv_wino_applies(const ConvEngineArgs &a) {
-  return !a.src_dz && !a.w_flip && a.Cin == kC && a.Kout == kK && a.R == 3 && a.S == 3 && a.pad_h == 1 && a.pad_w == 1 &&
-         a.act == ACT_RELU && a.pool == 2 && !a.sample && !a.out_pool && a.Hout == a.Hin && a.Wout == a.Win &&
-         a.Hout % 8 == 0 && a.Wout % 32 == 0 && aligned16(a.out) && (!a.out_idx || (reinterpret_cast<uintptr_t>(a.out_idx) & 3u) == 0) &&
+// Forward: plain source tensor, 16 channels in and out, padded 3x3, ReLU + 2x2 pooling, whole 8 x 32
+// tiles.  Backward-data of such a layer: pooled gradient + pooling bytes with the ReLU flags in,
+// plain gradient out.
+namespace {
+bool wino_common(const ConvEngineArgs &a) {
+  return a.Cin == kC && a.Kout == kK && a.R == 3 && a.S == 3 && a.pad_h == 1 && a.pad_w == 1 && !a.sample && !a.out_pool &&
+         a.Hout == a.Hin && a.Wout == a.Win && a.Hout % 8 == 0 && a.Wout % 32 == 0 && aligned16(a.out) &&
          (long)a.N * kC * a.Hin * a.Win < (1L << 31);
+}
+bool wino_is_bwd(const ConvEngineArgs &a) {
+  return a.src_dz && a.w_flip && a.src_pool == 2 && a.src_act == ACT_RELU_FLAGGED && a.src_idx && a.act == ACT_IDENTITY &&
+         a.pool == 1 && !a.bias && aligned16(a.src) && (reinterpret_cast<uintptr_t>(a.src_idx) & 3u) == 0;
+}
+}  // namespace
+bool conv_wino_applies(const ConvEngineArgs &a) {
+  if (!wino_common(a)) return false;
+  if (wino_is_bwd(a)) return true;
+  return !a.src_dz && !a.w_flip && a.act == ACT_RELU && a.pool == 2 && (!a.out_idx || (reinterpret_cast<uintptr_t>(a.out_idx) & 3u) == 0);
 }
 
 hipError_t launch_conv_wino(const ConvEngineArgs &a, hipStream_t stream) {
@@ -246,8 +364,8 @@ hipError_t launch_conv_wino(const ConvEngineArgs &a, hipStream_t stream) {
   p.items = a.N * p.tiles_x * p.tiles_y;
   int blocks = 256 * (grp == 2 ? 2 : 3);   // resident workgroups per CU (LDS, registers)
   if (blocks > p.items) blocks = p.items;
-  if (grp == 2) hipLaunchKernelGGL(conv3x3_wino_kernel<2>, dim3(blocks), dim3(kWT), 0, stream, p);
-  else hipLaunchKernelGGL(conv3x3_wino_kernel<1>, dim3(blocks), dim3(kWT), 0, stream, p);
+  if (wino_is_bwd(a)) hipLaunchKernelGGL((conv3x3_wino_kernel<1, true>), dim3(blocks), dim3(kWT), 0, stream, p);
+  else hipLaunchKernelGGL((conv3x3_wino_kernel<1, false>), dim3(blocks), dim3(kWT), 0, stream, p);
   return hipGetLastError();
 }
 

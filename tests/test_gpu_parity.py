@@ -70,9 +70,12 @@ def check_trio(cs: ConvSpec, x, w, b, dy):
         check_pool_idx(idx_g, idx_o, pre, y_o)
         if cs.act == "relu":
             # without the layer output the backward passes take act' from the flags: the very
-            # same decisions as y > 0 on the GPU's own y, hence bit-identical results
+            # same decisions as y > 0 on the GPU's own y, hence bit-identical filter gradients; the
+            # data gradient may come from another kernel (the minimal-filtering form takes the
+            # flagged 16-channel layers) and then differs by rounding only
             _, _, dx_f, dw_f, db_f = gpu_trio(cs, x, w, b, dy, flagged=True)
-            assert np.array_equal(dx_f, dx_own) and np.array_equal(dw_f, dw_own) and np.array_equal(db_f, db_own)
+            assert np.array_equal(dw_f, dw_own) and np.array_equal(db_f, db_own)
+            assert max_rel_err(dx_f, dx_own) <= 2e-6
     # backward ops on identical inputs (the oracle's y and the GPU's own index decisions)
     use_idx = idx_g if cs.pool == 2 else None
     _, _, dx_g, dw_g, db_g = gpu_trio(cs, x, w, b, dy, y_in=y_o, idx_in=use_idx)
