@@ -38,8 +38,12 @@ struct WinoParams {
 // BWD: the backward-data pass of such a layer instead (the same sum with the filters rotated and
 // transposed): the source is dz = unpool(dy) with the ReLU flags of the pooling bytes, formed while
 // staging from the pooled gradient; the 2x2 output blocks are stored as they are.
-template <int GRP, bool BWD>
+// CCH: source channels in chunks of 16 (1 or 2): a chunk is staged, its filters transformed, its
+// products added to the same accumulators; LDS holds one chunk at a time.
+template <int GRP, bool BWD, int CCH>
 __global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(const WinoParams p) {
+  static_assert(GRP == 1, "one block row per wavefront: the accumulators live across the channel chunks");
+  constexpr int kCin = kC * CCH;
   constexpr int kRows = WinoGeom<GRP>::kRows, kPS = WinoGeom<GRP>::kPS, kTH = 8 * GRP;
   __shared__ __attribute__((aligned(16))) float xs[kC * kPS];       // [c][row][col], zero-padded halo tile
   __shared__ __attribute__((aligned(16))) float us[16 * kC * kK];   // [point][c][k], transformed filters
@@ -47,12 +51,12 @@ __global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(con
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i16 = lane & 15, kq = lane >> 4;
 
-  // ---- filters: U = G g Gt, one (channel, filter) pair per thread
-  {
+  // ---- filters of a channel chunk: U = G g Gt, one (channel, filter) pair per thread
+  auto load_filters = [&](int c0) __attribute__((always_inline)) {
     const int c = tid >> 4, k = tid & 15;
     // forward: w[k][c][r][s]; backward-data: source channel c is the layer's filter index and the
     // taps are rotated, g[r][s] = w[c][k][2 - r][2 - s]
-    const float *g = BWD ? a.w + ((long)c * kK + k) * 9 : a.w + ((long)k * kC + c) * 9;
+    const float *g = BWD ? a.w + ((long)(c0 + c) * kK + k) * 9 : a.w + ((long)k * kCin + c0 + c) * 9;
     float gv[9];
 #pragma unroll
     for (int e = 0; e < 9; ++e) gv[e] = g[BWD ? 8 - e : e];
@@ -72,7 +76,8 @@ __global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(con
       us[((4 * i + 2) * kC + c) * kK + k] = u2;
       us[((4 * i + 3) * kC + c) * kK + k] = u3;
     }
-  }
+  };
+  if (CCH == 1) load_filters(0);
   const float bias = a.bias ? a.bias[i16] : 0.0f;
   const int Hp = a.Hout >> 1, Wp = a.Wout >> 1;
 
@@ -84,7 +89,7 @@ __global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(con
   constexpr int kSlots = kC * kRows * 9, kRounds = (kSlots + kWT - 1) / kWT;
   constexpr unsigned kOob = 0x80000000u;
   const __amdgpu_buffer_rsrc_t rs_x =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.src), 0, (int)(4u * (unsigned)a.N * kC * a.Hin * a.Win), 0x00020000);
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.src), 0, (int)(4u * (unsigned)a.N * kCin * a.Hin * a.Win), 0x00020000);
   int goff[kRounds], loff[kRounds], srow[kRounds], sq[kRounds];
 #pragma unroll
   for (int it = 0; it < kRounds; ++it) {
@@ -133,10 +138,10 @@ __global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(con
   // tile ahead, across the transforms and products of the previous tile, measured slower: 92 vs 86 us
   // on the 128 x 128 layer; the two resident workgroups of a CU overlap each other's staging instead.)
   floatx4 v[kRounds];
-  auto load_tile = [&](int item) __attribute__((always_inline)) {
+  auto load_tile = [&](int item, int c0) __attribute__((always_inline)) {
     const int tx = item % p.tiles_x, ty = (item / p.tiles_x) % p.tiles_y, n = item / (p.tiles_x * p.tiles_y);
     const int oy0 = ty * kTH, ox0 = tx * 32;
-    const int base = 4 * (((n * kC) * a.Hin + oy0 - 1) * a.Win + ox0 - 1);   // bytes; negative at the very first tile
+    const int base = 4 * (((n * kCin + c0) * a.Hin + oy0 - 1) * a.Win + ox0 - 1);   // bytes; negative at the very first tile
     const bool left = ox0 == 0, right = ox0 + 32 >= a.Win;
     const bool inner_rows = oy0 >= 1 && oy0 + kTH + 1 <= a.Hin;
 #pragma unroll
@@ -170,16 +175,23 @@ __global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(con
   for (int item = blockIdx.x; item < p.items; item += gridDim.x) {
     const int tx = item % p.tiles_x, ty = (item / p.tiles_x) % p.tiles_y, n = item / (p.tiles_x * p.tiles_y);
     const int oy0 = ty * kTH, ox0 = tx * 32;
-    __syncthreads();   // the previous tile's readers are done (first tile: the filters are in place)
+    const int tr = wave;   // block row inside the tile
+    floatx4 acc[16];
+    const floatx4 zero = floatx4{0.f, 0.f, 0.f, 0.f};   // the first channel quartet starts the sums from it
+#pragma unroll 1
+    for (int chunk = 0; chunk < CCH; ++chunk) {
+    const int c0 = chunk * kC;
+    __syncthreads();   // the previous chunk's / tile's readers are done (first tile: the filters are in place)
+    if (CCH > 1) load_filters(c0);
     if constexpr (!BWD) {
-      load_tile(item);
+      load_tile(item, c0);
       store_tile(item);
     } else {
       // dz halo tile from the pooled gradient.  The tile is cleared with 16-byte stores; then every
       // pooled element drops its gradient at the recorded position of its window, if that entry lies
       // inside the tile and the unit is not flagged inactive.  All loads first, stores after.
       const int Hs = a.Hin >> 1, Ws = a.Win >> 1;   // pooled source size
-      const long pbase = (((long)n * kC) * Hs + (oy0 >> 1) - 1) * Ws + (ox0 >> 1) - 1;
+      const long pbase = (((long)n * kCin + c0) * Hs + (oy0 >> 1) - 1) * Ws + (ox0 >> 1) - 1;
       float4 gv[kVecRounds];
       uchar4 fv[kVecRounds];
       bool vok[kVecRounds];
@@ -223,11 +235,7 @@ __global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(con
       }
     }
     __syncthreads();
-#pragma unroll 1
-    for (int grp = 0; grp < GRP; ++grp) {
-      const int tr = GRP * wave + grp;   // block row inside the tile
-      floatx4 acc[16];
-      const floatx4 zero = floatx4{0.f, 0.f, 0.f, 0.f};   // the first channel quartet starts the sums from it
+    {
       // Per channel quartet s: patch and filter fragments come from LDS in one batch, issued while the
       // previous quartet's 16 products run (two register sets), so that no product waits for its own read.
       float dA[4][4], dB[4][4], uA[16], uB[16];
@@ -268,7 +276,7 @@ __global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(con
       read_s(0, dA, uA);
       read_s(1, dB, uB);
       __builtin_amdgcn_sched_barrier(0);
-      mul_s(true, dA, uA);
+      mul_s(chunk == 0, dA, uA);
       __builtin_amdgcn_sched_barrier(0);
       read_s(2, dA, uA);
       __builtin_amdgcn_sched_barrier(0);
@@ -280,6 +288,9 @@ __global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(con
       __builtin_amdgcn_sched_barrier(0);
       mul_s(false, dB, uB);
       __builtin_amdgcn_sched_barrier(0);
+    }
+    }   // channel chunks
+    {
       // ---- output transform: lane holds blocks 4kq + v (v = 0..3) of filter (output channel) i16;
       // two blocks at a time keep few values alive
       float yv[4];
@@ -334,13 +345,13 @@ inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 
 }  // namespace
 
 // Forward: plain source tensor, 16 channels in and out, padded 3x3, ReLU + 2x2 pooling, whole 8 x 32
-// tiles.  Backward-data of such a layer: pooled gradient + pooling bytes with the ReLU flags in,
-// plain gradient out.
+// tiles.  Backward-data of such a layer, or of one with 32 filters (two chunks of 16 source channels):
+// pooled gradient + pooling bytes with the ReLU flags in, plain gradient out.
 namespace {
 bool wino_common(const ConvEngineArgs &a) {
-  return a.Cin == kC && a.Kout == kK && a.R == 3 && a.S == 3 && a.pad_h == 1 && a.pad_w == 1 && !a.sample && !a.out_pool &&
+  return (a.Cin == kC || a.Cin == 2 * kC) && a.Kout == kK && a.R == 3 && a.S == 3 && a.pad_h == 1 && a.pad_w == 1 && !a.sample && !a.out_pool &&
          a.Hout == a.Hin && a.Wout == a.Win && a.Hout % 8 == 0 && a.Wout % 32 == 0 && aligned16(a.out) &&
-         (long)a.N * kC * a.Hin * a.Win < (1L << 31);
+         (long)a.N * a.Cin * a.Hin * a.Win < (1L << 31);
 }
 bool wino_is_bwd(const ConvEngineArgs &a) {
   return a.src_dz && a.w_flip && a.src_pool == 2 && a.src_act == ACT_RELU_FLAGGED && a.src_idx && a.act == ACT_IDENTITY &&
@@ -350,6 +361,7 @@ bool wino_is_bwd(const ConvEngineArgs &a) {
 bool conv_wino_applies(const ConvEngineArgs &a) {
   if (!wino_common(a)) return false;
   if (wino_is_bwd(a)) return true;
+  if (a.Cin != kC) return false;   // two channel chunks: backward-data only
   return !a.src_dz && !a.w_flip && a.act == ACT_RELU && a.pool == 2 && (!a.out_idx || (reinterpret_cast<uintptr_t>(a.out_idx) & 3u) == 0);
 }
 
@@ -364,8 +376,13 @@ hipError_t launch_conv_wino(const ConvEngineArgs &a, hipStream_t stream) {
   p.items = a.N * p.tiles_x * p.tiles_y;
   int blocks = 256 * (grp == 2 ? 2 : 3);   // resident workgroups per CU (LDS, registers)
   if (blocks > p.items) blocks = p.items;
-  if (wino_is_bwd(a)) hipLaunchKernelGGL((conv3x3_wino_kernel<1, true>), dim3(blocks), dim3(kWT), 0, stream, p);
-  else hipLaunchKernelGGL((conv3x3_wino_kernel<1, false>), dim3(blocks), dim3(kWT), 0, stream, p);
+  const bool two = a.Cin == 2 * kC;
+  if (wino_is_bwd(a)) {
+    if (two) hipLaunchKernelGGL((conv3x3_wino_kernel<1, true, 2>), dim3(blocks), dim3(kWT), 0, stream, p);
+    else hipLaunchKernelGGL((conv3x3_wino_kernel<1, true, 1>), dim3(blocks), dim3(kWT), 0, stream, p);
+  } else {
+    hipLaunchKernelGGL((conv3x3_wino_kernel<1, false, 1>), dim3(blocks), dim3(kWT), 0, stream, p);
+  }
   return hipGetLastError();
 }
 
