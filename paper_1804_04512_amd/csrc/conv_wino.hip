@@ -32,7 +32,7 @@ template <int GRP> struct WinoGeom {
 
 struct WinoParams {
   ConvEngineArgs a;
-  int tiles_x, tiles_y, items;
+  int tiles_x, tiles_y, items, xcd;
 };
 
 // BWD: the backward-data pass of such a layer instead (the same sum with the filters rotated and
@@ -172,7 +172,12 @@ __global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(con
       *reinterpret_cast<floatx4 *>(xs + loff[it]) = t;
     }
   };
-  for (int item = blockIdx.x; item < p.items; item += gridDim.x) {
+  const int vb = p.xcd ? (int)(blockIdx.x & 7) * (int)(gridDim.x >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+  for (int item0 = 0; item0 < p.items; item0 += gridDim.x) {
+    // whole rounds: neighbouring tiles on one XCD (one L2); the last, partial round in launch order,
+    // which spreads it evenly over the XCDs
+    const int item = item0 + (item0 + (int)gridDim.x <= p.items ? vb : (int)blockIdx.x);
+    if (item >= p.items) break;
     const int tx = item % p.tiles_x, ty = (item / p.tiles_x) % p.tiles_y, n = item / (p.tiles_x * p.tiles_y);
     const int oy0 = ty * kTH, ox0 = tx * 32;
     const int tr = wave;   // block row inside the tile
@@ -376,6 +381,7 @@ hipError_t launch_conv_wino(const ConvEngineArgs &a, hipStream_t stream) {
   p.items = a.N * p.tiles_x * p.tiles_y;
   int blocks = 256 * (grp == 2 ? 2 : 3);   // resident workgroups per CU (LDS, registers)
   if (blocks > p.items) blocks = p.items;
+  p.xcd = blocks % 8 == 0;   // workgroups go to the eight XCDs in turn: see the kernel's tile loop
   const bool two = a.Cin == 2 * kC;
   if (wino_is_bwd(a)) {
     if (two) hipLaunchKernelGGL((conv3x3_wino_kernel<1, true, 2>), dim3(blocks), dim3(kWT), 0, stream, p);
