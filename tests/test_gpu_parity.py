@@ -99,6 +99,7 @@ CASES = [
     ConvSpec(2, 16, 40, 40, 16, 3, 3, 1, "relu", 2),          # config-5 style block
     ConvSpec(3, 16, 48, 64, 16, 3, 3, 1, "relu", 2),          # whole 16 x 32 tiles: the forward pass takes the minimal-filtering kernel
     ConvSpec(2, 16, 40, 64, 32, 3, 3, 1, "relu", 2),          # 16 -> 32 on whole 8 x 32 tiles: backward-data in two 16-channel chunks
+    ConvSpec(25, 16, 64, 128, 16, 3, 3, 1, "relu", 2),        # 800 tiles of the minimal-filtering kernel: one whole round of 768 workgroups + a partial one
     ConvSpec(1, 32, 32, 32, 32, 3, 3, 1, "relu", 2),          # config-5 conv4 shape
     ConvSpec(2, 2, 9, 14, 3, 2, 4, 0, "identity", 1),         # non-square filter
     ConvSpec(2, 4, 11, 9, 6, 1, 1, 0, "relu", 1),             # 1x1 filter, odd map
