@@ -81,11 +81,13 @@ def engine_kernel_name(cs, backward: bool) -> str:
     same = cs.R == 3 and cs.S == 3 and cs.pad == 1
     # 16 -> 16 channel layers with ReLU + pooling on whole 8 x 32 tiles: the minimal-filtering kernel
     # (forward, and backward-data from the pooled gradient with the ReLU flags, as the step calls it)
+    if same and cs.C == 32 and cs.K == 32 and cs.act == "relu" and cs.pool == 2 and cs.Ho % 8 == 0 and cs.Wo % 32 == 0:
+        return f"conv3x3_wino_kernel<1,{'true' if backward else 'false'},2,2>"
     if same and cs.C == 16 and cs.act == "relu" and cs.pool == 2 and cs.Ho % 8 == 0 and cs.Wo % 32 == 0:
         if cs.K == 16:
-            return f"conv3x3_wino_kernel<1,{'true' if backward else 'false'},1>"
-        if cs.K == 32 and backward:   # two chunks of 16 gradient channels
-            return "conv3x3_wino_kernel<1,true,2>"
+            return f"conv3x3_wino_kernel<1,{'true' if backward else 'false'},1,1>"
+        if cs.K == 32:   # backward-data: two chunks of 16 gradient channels; forward: two groups of 16 filters
+            return "conv3x3_wino_kernel<1,true,2,1>" if backward else "conv3x3_wino_kernel<1,false,1,2>"
     chunked = cin % 16 == 0 or (cin % 8 == 0 and kout <= 16) or cin <= 12
     if same and chunked and hout > 8 and cs.W % (8 if backward and cs.pool == 2 else 4) == 0:
         src = 0 if not backward else (2 if cs.pool == 2 else 1)

@@ -40,23 +40,29 @@ struct WinoParams {
 // staging from the pooled gradient; the 2x2 output blocks are stored as they are.
 // CCH: source channels in chunks of 16 (1 or 2): a chunk is staged, its filters transformed, its
 // products added to the same accumulators; LDS holds one chunk at a time.
-template <int GRP, bool BWD, int CCH>
-__global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(const WinoParams p) {
+// KCH: filters in groups of 16 (1 or 2): with 2, every transformed patch is multiplied
+// with both groups' filters (two accumulator sets, two resident workgroups per CU instead of three).
+template <int GRP, bool BWD, int CCH, int KCH>
+__global__ __launch_bounds__(kWT, (GRP == 2 || KCH == 2) ? 2 : 3) void conv3x3_wino_kernel(const WinoParams p) {
+  constexpr int kKout = kK * KCH;
   static_assert(GRP == 1, "one block row per wavefront: the accumulators live across the channel chunks");
   constexpr int kCin = kC * CCH;
   constexpr int kRows = WinoGeom<GRP>::kRows, kPS = WinoGeom<GRP>::kPS, kTH = 8 * GRP;
   __shared__ __attribute__((aligned(16))) float xs[kC * kPS];       // [c][row][col], zero-padded halo tile
-  __shared__ __attribute__((aligned(16))) float us[16 * kC * kK];   // [point][c][k], transformed filters
+  __shared__ __attribute__((aligned(16))) float us[16 * kC * kKout];   // [point][c][k], transformed filters
   const ConvEngineArgs &a = p.a;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i16 = lane & 15, kq = lane >> 4;
 
   // ---- filters of a channel chunk: U = G g Gt, one (channel, filter) pair per thread
   auto load_filters = [&](int c0) __attribute__((always_inline)) {
-    const int c = tid >> 4, k = tid & 15;
+    const int c = tid >> 4;
+#pragma unroll
+    for (int kg = 0; kg < KCH; ++kg) {
+    const int k = kg * kK + (tid & 15);
     // forward: w[k][c][r][s]; backward-data: source channel c is the layer's filter index and the
     // taps are rotated, g[r][s] = w[c][k][2 - r][2 - s]
-    const float *g = BWD ? a.w + ((long)(c0 + c) * kK + k) * 9 : a.w + ((long)k * kCin + c0 + c) * 9;
+    const float *g = BWD ? a.w + ((long)(c0 + c) * kKout + k) * 9 : a.w + ((long)k * kCin + c0 + c) * 9;
     float gv[9];
 #pragma unroll
     for (int e = 0; e < 9; ++e) gv[e] = g[BWD ? 8 - e : e];
@@ -71,14 +77,17 @@ __global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(con
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const float u0 = t[i][0], u1 = 0.5f * (t[i][0] + t[i][1] + t[i][2]), u2 = 0.5f * (t[i][0] - t[i][1] + t[i][2]), u3 = t[i][2];
-      us[((4 * i + 0) * kC + c) * kK + k] = u0;
-      us[((4 * i + 1) * kC + c) * kK + k] = u1;
-      us[((4 * i + 2) * kC + c) * kK + k] = u2;
-      us[((4 * i + 3) * kC + c) * kK + k] = u3;
+      us[((4 * i + 0) * kC + c) * kKout + k] = u0;
+      us[((4 * i + 1) * kC + c) * kKout + k] = u1;
+      us[((4 * i + 2) * kC + c) * kKout + k] = u2;
+      us[((4 * i + 3) * kC + c) * kKout + k] = u3;
     }
+    }   // filter groups
   };
   if (CCH == 1) load_filters(0);
-  const float bias = a.bias ? a.bias[i16] : 0.0f;
+  float bias[KCH];
+#pragma unroll
+  for (int kg = 0; kg < KCH; ++kg) bias[kg] = a.bias ? a.bias[kg * kK + i16] : 0.0f;
   const int Hp = a.Hout >> 1, Wp = a.Wout >> 1;
 
   // Staging slots: 16 channels x 18 rows x 9 groups of four columns (36 >= 34; the last two are never
@@ -181,7 +190,7 @@ __global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(con
     const int tx = item % p.tiles_x, ty = (item / p.tiles_x) % p.tiles_y, n = item / (p.tiles_x * p.tiles_y);
     const int oy0 = ty * kTH, ox0 = tx * 32;
     const int tr = wave;   // block row inside the tile
-    floatx4 acc[16];
+    floatx4 acc[KCH][16];
     const floatx4 zero = floatx4{0.f, 0.f, 0.f, 0.f};   // the first channel quartet starts the sums from it
 #pragma unroll 1
     for (int chunk = 0; chunk < CCH; ++chunk) {
@@ -243,8 +252,8 @@ __global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(con
     {
       // Per channel quartet s: patch and filter fragments come from LDS in one batch, issued while the
       // previous quartet's 16 products run (two register sets), so that no product waits for its own read.
-      float dA[4][4], dB[4][4], uA[16], uB[16];
-      auto read_s = [&](int s, float (&d)[4][4], float (&u)[16]) __attribute__((always_inline)) {
+      float dA[4][4], dB[4][4], uA[KCH][16], uB[KCH][16];
+      auto read_s = [&](int s, float (&d)[4][4], float (&u)[KCH][16]) __attribute__((always_inline)) {
         const float *d0 = xs + (4 * s + kq) * kPS + (2 * tr) * kRS + 2 * i16;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -252,11 +261,13 @@ __global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(con
           const float2 hi = *reinterpret_cast<const float2 *>(d0 + i * kRS + 2);
           d[i][0] = lo.x; d[i][1] = lo.y; d[i][2] = hi.x; d[i][3] = hi.y;
         }
-        const float *up = us + (4 * s + kq) * kK + i16;
+        const float *up = us + (4 * s + kq) * kKout + i16;
 #pragma unroll
-        for (int q = 0; q < 16; ++q) u[q] = up[q * kC * kK];
+        for (int kg = 0; kg < KCH; ++kg)
+#pragma unroll
+          for (int q = 0; q < 16; ++q) u[kg][q] = up[q * kC * kKout + kg * kK];
       };
-      auto mul_s = [&](bool first, const float (&d)[4][4], const float (&u)[16]) __attribute__((always_inline)) {
+      auto mul_s = [&](bool first, const float (&d)[4][4], const float (&u)[KCH][16]) __attribute__((always_inline)) {
         // input transform V = Bt d B of the lane's patch; then the 16 point products:
         // A = V (block i16, channel kq), B = U (channel kq, filter i16)
         float t[4][4];
@@ -276,8 +287,72 @@ __global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(con
           V[4 * i + 3] = t[i][1] - t[i][3];
         }
 #pragma unroll
-        for (int q = 0; q < 16; ++q) acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(V[q], u[q], first ? zero : acc[q], 0, 0, 0);
+        for (int q = 0; q < 16; ++q)
+#pragma unroll
+          for (int kg = 0; kg < KCH; ++kg)
+            acc[kg][q] = __builtin_amdgcn_mfma_f32_16x16x4f32(V[q], u[kg][q], first ? zero : acc[kg][q], 0, 0, 0);
       };
+      if constexpr (KCH == 2) {
+        // Two filter groups: a quartet's transformed patch is used twice, 16 products per group.  The
+        // filter fragments of a group are read into the registers whose products have just been
+        // issued, one quartet ahead (u0: group 0, u1: group 1); the patch one quartet ahead as well.
+        float u0[16], u1[16], V[16];
+        auto read_d = [&](int s, float (&d)[4][4]) __attribute__((always_inline)) {
+          const float *d0 = xs + (4 * s + kq) * kPS + (2 * tr) * kRS + 2 * i16;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float2 lo = *reinterpret_cast<const float2 *>(d0 + i * kRS);
+            const float2 hi = *reinterpret_cast<const float2 *>(d0 + i * kRS + 2);
+            d[i][0] = lo.x; d[i][1] = lo.y; d[i][2] = hi.x; d[i][3] = hi.y;
+          }
+        };
+        auto read_u = [&](int s, int kg, float (&u)[16]) __attribute__((always_inline)) {
+          const float *up = us + (4 * s + kq) * kKout + kg * kK + i16;
+#pragma unroll
+          for (int q = 0; q < 16; ++q) u[q] = up[q * kC * kKout];
+        };
+        auto xform = [&](const float (&d)[4][4]) __attribute__((always_inline)) {
+          float t[4][4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            t[0][j] = d[0][j] - d[2][j];
+            t[1][j] = d[1][j] + d[2][j];
+            t[2][j] = d[2][j] - d[1][j];
+            t[3][j] = d[1][j] - d[3][j];
+          }
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            V[4 * i + 0] = t[i][0] - t[i][2];
+            V[4 * i + 1] = t[i][1] + t[i][2];
+            V[4 * i + 2] = t[i][2] - t[i][1];
+            V[4 * i + 3] = t[i][1] - t[i][3];
+          }
+        };
+        auto mul_g = [&](bool first, int kg, const float (&u)[16]) __attribute__((always_inline)) {
+#pragma unroll
+          for (int q = 0; q < 16; ++q) acc[kg][q] = __builtin_amdgcn_mfma_f32_16x16x4f32(V[q], u[q], first ? zero : acc[kg][q], 0, 0, 0);
+        };
+        read_d(0, dA);
+        read_u(0, 0, u0);
+        read_u(0, 1, u1);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const bool first = chunk == 0 && s == 0;
+          __builtin_amdgcn_sched_barrier(0);
+          xform(dA);
+          __builtin_amdgcn_sched_barrier(0);
+          if (s < 3) read_d(s + 1, dA);   // into the registers the transform has just consumed
+          __builtin_amdgcn_sched_barrier(0);
+          mul_g(first, 0, u0);
+          __builtin_amdgcn_sched_barrier(0);
+          if (s < 3) read_u(s + 1, 0, u0);
+          __builtin_amdgcn_sched_barrier(0);
+          mul_g(first, 1, u1);
+          __builtin_amdgcn_sched_barrier(0);
+          if (s < 3) read_u(s + 1, 1, u1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      } else {
       read_s(0, dA, uA);
       read_s(1, dB, uB);
       __builtin_amdgcn_sched_barrier(0);
@@ -293,9 +368,11 @@ __global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(con
       __builtin_amdgcn_sched_barrier(0);
       mul_s(false, dB, uB);
       __builtin_amdgcn_sched_barrier(0);
+      }
     }
     }   // channel chunks
-    {
+#pragma unroll
+    for (int kg = 0; kg < KCH; ++kg) {
       // ---- output transform: lane holds blocks 4kq + v (v = 0..3) of filter (output channel) i16;
       // two blocks at a time keep few values alive
       float yv[4];
@@ -309,15 +386,15 @@ __global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(con
           float sr[2][4];
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
-            sr[0][j] = acc[j][v] + acc[4 + j][v] + acc[8 + j][v];
-            sr[1][j] = acc[4 + j][v] - acc[8 + j][v] - acc[12 + j][v];
+            sr[0][j] = acc[kg][j][v] + acc[kg][4 + j][v] + acc[kg][8 + j][v];
+            sr[1][j] = acc[kg][4 + j][v] - acc[kg][8 + j][v] - acc[kg][12 + j][v];
           }
           y00[w] = sr[0][0] + sr[0][1] + sr[0][2]; y01[w] = sr[0][1] - sr[0][2] - sr[0][3];
           y10[w] = sr[1][0] + sr[1][1] + sr[1][2]; y11[w] = sr[1][1] - sr[1][2] - sr[1][3];
         }
         if constexpr (BWD) {
           // the blocks as they are: two rows of four consecutive columns per pair of blocks
-          float *o0 = a.out + (((long)n * kK + i16) * a.Hout + oy0 + 2 * tr) * a.Wout + ox0 + 8 * kq + 4 * h;
+          float *o0 = a.out + (((long)n * kKout + kg * kK + i16) * a.Hout + oy0 + 2 * tr) * a.Wout + ox0 + 8 * kq + 4 * h;
           *reinterpret_cast<float4 *>(o0) = make_float4(y00[0], y01[0], y00[1], y01[1]);
           *reinterpret_cast<float4 *>(o0 + a.Wout) = make_float4(y10[0], y11[0], y10[1], y11[1]);
         } else {
@@ -330,14 +407,14 @@ __global__ __launch_bounds__(kWT, GRP == 2 ? 2 : 3) void conv3x3_wino_kernel(con
             if (y01[w] > m) { m = y01[w]; arg = 1; }
             if (y10[w] > m) { m = y10[w]; arg = 2; }
             if (y11[w] > m) { m = y11[w]; arg = 3; }
-            const float o = m + bias;
+            const float o = m + bias[kg];
             yv[v] = o > 0.0f ? o : 0.0f;
             iv[v] = (unsigned char)(arg | (yv[v] > 0.0f ? 0 : kIdxInactive));
           }
         }
       }
       if constexpr (!BWD) {
-        const long o = (((long)n * kK + i16) * Hp + (oy0 >> 1) + tr) * Wp + (ox0 >> 1) + 4 * kq;
+        const long o = (((long)n * kKout + kg * kK + i16) * Hp + (oy0 >> 1) + tr) * Wp + (ox0 >> 1) + 4 * kq;
         *reinterpret_cast<float4 *>(a.out + o) = make_float4(yv[0], yv[1], yv[2], yv[3]);
         if (a.out_idx) *reinterpret_cast<uchar4 *>(a.out_idx + o) = make_uchar4(iv[0], iv[1], iv[2], iv[3]);
       }
@@ -354,7 +431,7 @@ inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 
 // pooled gradient + pooling bytes with the ReLU flags in, plain gradient out.
 namespace {
 bool wino_common(const ConvEngineArgs &a) {
-  return (a.Cin == kC || a.Cin == 2 * kC) && a.Kout == kK && a.R == 3 && a.S == 3 && a.pad_h == 1 && a.pad_w == 1 && !a.sample && !a.out_pool &&
+  return (a.Cin == kC || a.Cin == 2 * kC) && (a.Kout == kK || a.Kout == 2 * kK) && a.R == 3 && a.S == 3 && a.pad_h == 1 && a.pad_w == 1 && !a.sample && !a.out_pool &&
          a.Hout == a.Hin && a.Wout == a.Win && a.Hout % 8 == 0 && a.Wout % 32 == 0 && aligned16(a.out) &&
          (long)a.N * a.Cin * a.Hin * a.Win < (1L << 31);
 }
@@ -365,8 +442,8 @@ bool wino_is_bwd(const ConvEngineArgs &a) {
 }  // namespace
 bool conv_wino_applies(const ConvEngineArgs &a) {
   if (!wino_common(a)) return false;
-  if (wino_is_bwd(a)) return true;
-  if (a.Cin != kC) return false;   // two channel chunks: backward-data only
+  if (wino_is_bwd(a)) return a.Kout == kK || a.Cin == 2 * kC;   // two filter groups: with two channel chunks only
+  if (a.Cin != kC && a.Kout != 2 * kK) return false;   // forward, two channel chunks: with two filter groups only
   return !a.src_dz && !a.w_flip && a.act == ACT_RELU && a.pool == 2 && (!a.out_idx || (reinterpret_cast<uintptr_t>(a.out_idx) & 3u) == 0);
 }
 
@@ -379,15 +456,19 @@ hipError_t launch_conv_wino(const ConvEngineArgs &a, hipStream_t stream) {
   p.tiles_x = a.Wout / 32;
   p.tiles_y = a.Hout / (8 * grp);
   p.items = a.N * p.tiles_x * p.tiles_y;
-  int blocks = 256 * (grp == 2 ? 2 : 3);   // resident workgroups per CU (LDS, registers)
+  const bool kk = a.Kout == 2 * kK;
+  int blocks = 256 * ((grp == 2 || kk) ? 2 : 3);   // resident workgroups per CU (LDS, registers)
   if (blocks > p.items) blocks = p.items;
   p.xcd = blocks % 8 == 0;   // workgroups go to the eight XCDs in turn: see the kernel's tile loop
   const bool two = a.Cin == 2 * kC;
   if (wino_is_bwd(a)) {
-    if (two) hipLaunchKernelGGL((conv3x3_wino_kernel<1, true, 2>), dim3(blocks), dim3(kWT), 0, stream, p);
-    else hipLaunchKernelGGL((conv3x3_wino_kernel<1, true, 1>), dim3(blocks), dim3(kWT), 0, stream, p);
+    if (two && kk) hipLaunchKernelGGL((conv3x3_wino_kernel<1, true, 2, 2>), dim3(blocks), dim3(kWT), 0, stream, p);
+    else if (two) hipLaunchKernelGGL((conv3x3_wino_kernel<1, true, 2, 1>), dim3(blocks), dim3(kWT), 0, stream, p);
+    else hipLaunchKernelGGL((conv3x3_wino_kernel<1, true, 1, 1>), dim3(blocks), dim3(kWT), 0, stream, p);
   } else {
-    hipLaunchKernelGGL((conv3x3_wino_kernel<1, false, 1>), dim3(blocks), dim3(kWT), 0, stream, p);
+    if (kk && two) hipLaunchKernelGGL((conv3x3_wino_kernel<1, false, 2, 2>), dim3(blocks), dim3(kWT), 0, stream, p);
+    else if (kk) hipLaunchKernelGGL((conv3x3_wino_kernel<1, false, 1, 2>), dim3(blocks), dim3(kWT), 0, stream, p);
+    else hipLaunchKernelGGL((conv3x3_wino_kernel<1, false, 1, 1>), dim3(blocks), dim3(kWT), 0, stream, p);
   }
   return hipGetLastError();
 }
