@@ -433,7 +433,8 @@ namespace {
 bool wino_common(const ConvEngineArgs &a) {
   return (a.Cin == kC || a.Cin == 2 * kC) && (a.Kout == kK || a.Kout == 2 * kK) && a.R == 3 && a.S == 3 && a.pad_h == 1 && a.pad_w == 1 && !a.sample && !a.out_pool &&
          a.Hout == a.Hin && a.Wout == a.Win && a.Hout % 8 == 0 && a.Wout % 32 == 0 && aligned16(a.out) &&
-         (long)a.N * a.Cin * a.Hin * a.Win < (1L << 31);
+         // the forward staging addresses the source with signed 32-bit BYTE offsets (negative = out of range)
+         4L * a.N * a.Cin * a.Hin * a.Win < (1L << 31);
 }
 bool wino_is_bwd(const ConvEngineArgs &a) {
   return a.src_dz && a.w_flip && a.src_pool == 2 && a.src_act == ACT_RELU_FLAGGED && a.src_idx && a.act == ACT_IDENTITY &&
