@@ -1,4 +1,5 @@
-// Forward 3x3 convolution of a 16 -> 16 channel layer with ReLU and 2x2 max pooling in the
+// Forward 3x3 convolution of a layer with 16 or 32 channels in and out, ReLU and 2x2 max pooling
+// (and the backward-data pass of such a layer) in the
 // minimal-filtering form F(2x2, 3x3): every 2x2 block of outputs comes from a 4x4 input patch,
 //   Y = At [ (G g Gt) .* (Bt d B) ] A,
 // so that the 36 multiplications per output pixel, input channel and filter of the direct sum
@@ -8,8 +9,7 @@
 // on the vector pipe.  A 2x2 output block is exactly one pooling window, so bias, ReLU, the
 // maximum and its position follow in registers and only the pooled map is stored.
 //
-// Tile: 8 x 32 outputs = 4 x 16 blocks per workgroup (16 x 32 as a second instance); wavefront w owns
-// block row w; lane
+// Tile: 8 x 32 outputs = 4 x 16 blocks per workgroup; wavefront w owns block row w; lane
 // (i16, kq) transforms the patch of block column i16 for the channels kq, 4+kq, 8+kq, 12+kq (its
 // MFMA A fragments) and ends up with the 16 point sums of blocks 4kq..4kq+3 for filter i16.
 // Results differ from the direct sum by rounding only (a few 1e-7 of the output scale).
@@ -23,8 +23,8 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int kWT = 256;
 constexpr int kC = 16, kK = 16;          // channels in, filters
 constexpr int kRS = 36;                  // row stride of the halo tile in LDS (34 columns used)
-// GRP block rows per wavefront: 2 -> tiles of 16 x 32 outputs (18 halo rows), 1 -> 8 x 32 (10 halo rows, less
-// LDS: more workgroups per CU).  Plane stride = 16 mod 32: the four channel groups of a wavefront land 16 banks apart.
+// GRP block rows per wavefront: 1 -> tiles of 8 x 32 outputs (10 halo rows), the only form in use (tiles of
+// 16 x 32 with 18 halo rows, GRP 2, leave room for two workgroups per CU instead of three and measured slower).  Plane stride = 16 mod 32: the four channel groups of a wavefront land 16 banks apart.
 template <int GRP> struct WinoGeom {
   static constexpr int kRows = 8 * GRP + 2;
   static constexpr int kPS = GRP == 2 ? kRows * kRS + 8 : kRows * kRS + 16;   // 656, 376
@@ -452,7 +452,8 @@ hipError_t launch_conv_wino(const ConvEngineArgs &a, hipStream_t stream) {
   if (!conv_wino_applies(a)) return hipErrorInvalidValue;
   WinoParams p;
   p.a = a;
-  // 8-row tiles: three workgroups per CU instead of two (measured 80 vs 85 us on the 128 x 128 layer)
+  // 8-row tiles: three workgroups per CU instead of two (measured 80 vs 85 us on the 128 x 128 layer);
+  // with two filter groups the accumulators take 128 registers and two workgroups stay resident
   const int grp = 1;
   p.tiles_x = a.Wout / 32;
   p.tiles_y = a.Hout / (8 * grp);
