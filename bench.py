@@ -79,7 +79,7 @@ def engine_kernel_name(cs, backward: bool) -> str:
     (mirrors the dispatch in csrc/conv_engine.hip; used only to group launches for the report)."""
     cin, kout, hout = (cs.K, cs.C, cs.H) if backward else (cs.C, cs.K, cs.Ho)
     same = cs.R == 3 and cs.S == 3 and cs.pad == 1
-    # 16 -> 16 channel layers with ReLU + pooling on whole 8 x 32 tiles: the minimal-filtering kernel
+    # layers with 16 or 32 channels in and out, ReLU + pooling, on whole 8 x 32 tiles: the minimal-filtering kernel
     # (forward, and backward-data from the pooled gradient with the ReLU flags, as the step calls it)
     if same and cs.C == 32 and cs.K == 32 and cs.act == "relu" and cs.pool == 2 and cs.Ho % 8 == 0 and cs.Wo % 32 == 0:
         return f"conv3x3_wino_kernel<1,{'true' if backward else 'false'},2,2>"

@@ -70,7 +70,9 @@ hipError_t launch_conv_engine(const ConvEngineArgs &a, hipStream_t stream);
 // The same operation for at most three output channels (CRBM reconstruction, backward-data into a
 // grey-scale or RGB input): output columns instead of output channels ride on the MFMA N axis.
 // launch_conv_engine routes there by itself when it pays.
-// Forward 16 -> 16 channel 3x3 layers with ReLU + pooling in the minimal-filtering form F(2x2, 3x3).
+// Padded 3x3 layers with 16 or 32 channels in and out, ReLU + pooling, on whole 8 x 32 tiles, in the
+// minimal-filtering form F(2x2, 3x3): the forward pass, and the backward-data pass from the pooled
+// gradient with the ReLU flags in the pooling bytes.  launch_conv_engine routes there by itself.
 bool conv_wino_applies(const ConvEngineArgs &a);
 hipError_t launch_conv_wino(const ConvEngineArgs &a, hipStream_t stream);
 bool conv_fewout_applies(const ConvEngineArgs &a);
