@@ -634,22 +634,26 @@ dll_status run_cnn_step(const dll_net_desc *net, float *const *params, float *co
                                                       (upd && velocity) ? velocity[2 * (L + q) + 1] : nullptr, mu};
     }
   }
-  // ---- convolution backward: data gradient with the old filters, then the filter-gradient partial
-  // sums; their reduction and the filter update wait for the closing launch
+  // ---- convolution backward: filter-gradient partial sums, then the data gradient with the old filters;
+  // the reduction of the partial sums and the filter update wait for the closing launch
   float *gcur = nb.gbuf[0], *gnext = nb.gbuf[1];
   for (int l = L - 1; l >= 0; --l) {
     const dll_conv_desc *d = &net->conv[l];
     // pooled ReLU layers: the forward pass above flagged the inactive units in idx, so the
     // backward passes do not read the layer output
     const float *yl = (d->act == DLL_ACT_RELU && d->pool == 2) ? nullptr : nb.act[l + 1];
-    if (l > 0) {
-      st = dev(launch_conv_engine(bwd_args(d, gcur, yl, nb.idx[l], params[2 * l], gnext), s));
-      if (st != DLL_OK) return st;
-    }
+    // The filter-gradient partial sums first: the layer's output gradient has just been written by the
+    // layer above's data-gradient pass and is read back while the memory-side cache still holds it
+    // (measured 0.6 % of the large-image step against the other order).  The filters change only in
+    // the closing launch, so the data-gradient pass after it still sees the old ones.
     WgradPlan plan;
     if (!plan_for(d, &plan)) return DLL_ERR_UNSUPPORTED;
     st = dev(launch_wgrad(wgrad_args(d, nb.act[l], gcur, yl, nb.idx[l], nb.cpartial[l]), plan, s));
     if (st != DLL_OK) return st;
+    if (l > 0) {
+      st = dev(launch_conv_engine(bwd_args(d, gcur, yl, nb.idx[l], params[2 * l], gnext), s));
+      if (st != DLL_OK) return st;
+    }
     WgradReduceArgs r;
     r.pos = nb.cpartial[l]; r.scale = 1.0f;
     r.dw = grads ? grads[2 * l] : nullptr;
