@@ -3,7 +3,9 @@
 //   * fp32 MFMA: a register-only loop of v_mfma_f32_16x16x4_f32 with eight independent
 //     accumulators per wavefront, at 1, 2 and 4 wavefronts per SIMD;
 //   * HBM: a 16-byte-per-lane copy of 1 GiB (read + write), a read-only sum and a write-only fill.
-// Usage: chip_probe        (prints one line per measurement)
+// Usage: bench_chip_probe   (prints one line per measurement, then one JSON line that bench.py reads:
+//        the best MFMA rate, the three HBM rates, and what the runtime reports of the device)
+// Built by __graft_entry__.build(); bench.py runs it as a child process when it is there.
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
@@ -74,6 +76,11 @@ int main() {
   CHECK(hipGetDeviceProperties(&prop, 0));
   printf("device %s  CUs %d  clock %d MHz\n", prop.name, prop.multiProcessorCount, prop.clockRate / 1000);
   const int cus = prop.multiProcessorCount;
+  int lds_cu = 0, lds_block = 0;
+  CHECK(hipDeviceGetAttribute(&lds_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, 0));
+  CHECK(hipDeviceGetAttribute(&lds_block, hipDeviceAttributeMaxSharedMemoryPerBlock, 0));
+  printf("LDS per compute unit %d bytes, per workgroup %d bytes; L2 %d bytes\n", lds_cu, lds_block, prop.l2CacheSize);
+  double best_mfma = 0.0;
 
   float *out = nullptr;
   CHECK(hipMalloc(&out, (size_t)cus * 4 * 256 * sizeof(float)));
@@ -83,6 +90,7 @@ int main() {
     const float ms = time_ms([&] { hipLaunchKernelGGL(mfma_loop, dim3(blocks), dim3(256), 0, 0, out, iters, 1.0f, 0.5f); }, 3);
     const double flop = (double)blocks * 4 * iters * 8 * 2048.0;
     printf("fp32 MFMA 16x16x4, registers only, %d wavefront(s) per SIMD: %.3f ms  %.1f TFLOP/s\n", wps, ms, flop / ms / 1e9);
+    if (flop / ms / 1e9 > best_mfma) best_mfma = flop / ms / 1e9;
   }
   CHECK(hipFree(out));
 
@@ -97,10 +105,16 @@ int main() {
   CHECK(hipDeviceSynchronize());
   float ms = time_ms([&] { hipLaunchKernelGGL(copy16, dim3(blocks), dim3(256), 0, 0, (const float4 *)src, dst, n); }, 10);
   printf("HBM copy 1 GiB (read + write): %.3f ms  %.2f TB/s\n", ms, 2.0 * bytes / ms / 1e9);
+  const double copy_tbs = 2.0 * bytes / ms / 1e9;
   ms = time_ms([&] { hipLaunchKernelGGL(read16, dim3(blocks), dim3(256), 0, 0, (const float4 *)src, sink, n); }, 10);
   printf("HBM read 1 GiB: %.3f ms  %.2f TB/s\n", ms, 1.0 * bytes / ms / 1e9);
+  const double read_tbs = 1.0 * bytes / ms / 1e9;
   ms = time_ms([&] { hipLaunchKernelGGL(fill16, dim3(blocks), dim3(256), 0, 0, dst, n, 2.0f); }, 10);
   printf("HBM write 1 GiB: %.3f ms  %.2f TB/s\n", ms, 1.0 * bytes / ms / 1e9);
+  const double write_tbs = 1.0 * bytes / ms / 1e9;
+  printf("{\"mfma_f32_tflops\": %.2f, \"hbm_copy_gbps\": %.1f, \"hbm_read_gbps\": %.1f, \"hbm_write_gbps\": %.1f, "
+         "\"cus\": %d, \"clock_mhz\": %d, \"lds_per_cu\": %d, \"lds_per_workgroup\": %d}\n",
+         best_mfma, copy_tbs * 1e3, read_tbs * 1e3, write_tbs * 1e3, cus, prop.clockRate / 1000, lds_cu, lds_block);
   CHECK(hipFree(src));
   CHECK(hipFree(dst));
   CHECK(hipFree(sink));

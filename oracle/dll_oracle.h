@@ -88,7 +88,8 @@ void oracle_set_threads(int n);
                         REAL *v1, REAL *h1_prob, REAL *recon_mse);                               \
   int PFX##cnn_train_step(const oracle_net_desc *net, REAL *const *params, REAL *const *grads,   \
                           const REAL *x, const int *labels, REAL lr, REAL *loss, REAL *logits,   \
-                          const unsigned char *const *pool_idx_in, unsigned char *const *pool_idx_out); \
+                          const unsigned char *const *pool_idx_in, unsigned char *const *pool_idx_out, \
+                          const unsigned char *const *active_in);                                \
   int PFX##cnn_forward(const oracle_net_desc *net, const REAL *const *params, const REAL *x,     \
                        REAL *logits, REAL *prob);
 

@@ -321,8 +321,11 @@ class CnnResult:
     pool_idx: list
 
 
-def cnn_train_step(net: Net, params, x, labels, lr=0.0, pool_idx_in=None, f64=False) -> CnnResult:
-    """params: list of arrays (storage dtype, contiguous), updated IN PLACE when lr != 0."""
+def cnn_train_step(net: Net, params, x, labels, lr=0.0, pool_idx_in=None, f64=False, active_in=None) -> CnnResult:
+    """params: list of arrays (storage dtype, contiguous), updated IN PLACE when lr != 0.
+    pool_idx_in / active_in: per conv layer (entries may be None) the pooling positions and, for
+    ReLU layers, the activity record (non-zero = unit active) to use in the backward pass instead
+    of the oracle's own decisions."""
     dt = _dt(f64)
     shapes = net.param_shapes()
     assert len(params) == len(shapes)
@@ -349,11 +352,18 @@ def cnn_train_step(net: Net, params, x, labels, lr=0.0, pool_idx_in=None, f64=Fa
     if pool_idx_in is not None:
         keep = [None if i is None else np.ascontiguousarray(i, np.uint8) for i in pool_idx_in]
         ii = IP(*[None if i is None else i.ctypes.data for i in keep])
+    aa = None
+    keep_a = []
+    if active_in is not None:
+        keep_a = [None if a is None else np.ascontiguousarray(a, np.uint8) for a in active_in]
+        for a, d in zip(keep_a, net.conv):
+            assert a is None or a.shape == tuple(d.out_shape), (a.shape, d.out_shape)
+        aa = IP(*[None if a is None else a.ctypes.data for a in keep_a])
     fn = getattr(lib(), _pfx(f64) + "cnn_train_step")
     real = C.c_double if f64 else C.c_float
     fn.argtypes = [C.POINTER(NetDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, real,
-                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
-    _check(fn(C.byref(nd), pp, gg, _p(x), _p(labels), lr, _p(loss), _p(logits), ii, io), "cnn_train_step")
+                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    _check(fn(C.byref(nd), pp, gg, _p(x), _p(labels), lr, _p(loss), _p(logits), ii, io, aa), "cnn_train_step")
     return CnnResult(float(loss[0]), logits, grads, idx_out)
 
 

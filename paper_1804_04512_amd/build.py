@@ -13,16 +13,15 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdll_conv.so")
 SOURCES = ["conv_engine.hip", "conv_fewout.hip", "conv_fft.hip", "conv_wino.hip", "conv_wgrad.hip", "gemm.hip", "gemm_small.hip", "rbm.hip", "api.hip"]
-PROBE = os.path.join(HERE, "chip_probe")   # stand-alone program: measured MFMA and HBM rates of the GPU
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 VALU forms are switched off on purpose: the compiler then emits no v_pk_*_f32 instructions
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
-    cmd = [HIPCC] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+def _compile(src: str, folder: str = CSRC) -> str:
+    obj = os.path.join(folder, os.path.splitext(src)[0] + ".o")
+    cmd = [HIPCC] + FLAGS + ["-c", os.path.join(folder, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
@@ -38,9 +37,16 @@ def build() -> str:
         objs = list(ex.map(_compile, SOURCES))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     subprocess.run(cmd, check=True)
-    obj = _compile("chip_probe.hip")
-    subprocess.run([HIPCC, "--offload-arch=gfx950", "-o", PROBE, obj], check=True)
     return LIB
+
+
+def build_program(src_path: str, out_path: str) -> str:
+    """Compiles one stand-alone HIP program (same flags as the library)."""
+    folder, src = os.path.split(src_path)
+    obj = _compile(src, folder)
+    subprocess.run([HIPCC, "--offload-arch=gfx950", "-o", out_path, obj], check=True)
+    os.remove(obj)
+    return out_path
 
 
 if __name__ == "__main__":

@@ -6,7 +6,62 @@
 
 #include <stdint.h>
 
+#include <mutex>
+#include <utility>
+#include <vector>
+
 using namespace dllk;
+
+namespace dllk {
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_chip_mutex;
+ChipInfo g_chip[kMaxDevices];
+bool g_chip_known[kMaxDevices];
+std::vector<std::pair<int, const void *>> g_large_lds_done;
+}  // namespace
+
+// Asked once per device.  The library is built for gfx950 only; where no device answers (a
+// workspace query on a machine without a GPU) the MI355X's published figures stand in: 256 compute
+// units, 160 KB of LDS per compute unit.
+const ChipInfo &chip() {
+  static const ChipInfo mi355x{256, (size_t)160 * 1024};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();
+    return mi355x;
+  }
+  std::lock_guard<std::mutex> lock(g_chip_mutex);
+  if (!g_chip_known[dev]) {
+    int cus = 0, lds = 0;
+    ChipInfo info = mi355x;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0) info.cus = cus;
+    if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) == hipSuccess && lds >= 64 * 1024)
+      info.lds_bytes = (size_t)lds;
+    (void)hipGetLastError();
+    g_chip[dev] = info;
+    g_chip_known[dev] = true;
+  }
+  return g_chip[dev];
+}
+
+hipError_t allow_large_lds(const void *kernel, size_t lds_bytes) {
+  if (lds_bytes <= 64 * 1024) return hipSuccess;
+  const size_t limit = chip().lds_bytes;
+  if (lds_bytes > limit) return hipErrorInvalidValue;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  std::lock_guard<std::mutex> lock(g_chip_mutex);
+  for (const auto &d : g_large_lds_done)
+    if (d.first == dev && d.second == kernel) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)limit);
+  if (e == hipSuccess) g_large_lds_done.emplace_back(dev, kernel);
+  return e;
+}
+
+}  // namespace dllk
 
 namespace {
 

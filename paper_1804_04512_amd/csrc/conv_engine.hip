@@ -17,7 +17,6 @@
 // channel roles swapped, which turns the paper's "full convolution" (Section II-A) into this
 // same valid-convolution engine run on an input padded by R-1-pad.
 #include "dll_internal.h"
-#include <cstdlib>
 
 #include <type_traits>
 
@@ -911,30 +910,47 @@ __global__ __launch_bounds__(WAVES * 64, conv3x3_occupancy(NT, WAVES, CC)) void 
   }
 }
 
-template <int NT, int CC>
-size_t conv3x3c16_lds(int nchunks) {
+constexpr size_t conv3x3c16_lds_bytes(int NT, int CC, int nchunks) {
   return sizeof(float) * ((size_t)CC * round_up_mod_c(36 * 18, 8, 2) + (size_t)nchunks * NT * 9 * CC * 16);
 }
 
 inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
 
+// Which instance of the specialised kernel takes a layer: NT (16-filter groups per workgroup), wavefronts
+// and channels per chunk; NT == 0: none applies.
+struct Conv3x3Pick { int NT = 0, WAVES = 0, CC = 0; };
+
 // The specialised kernel applies to 3x3 filters with one row/column of padding, channel
-// counts that are multiples of 16, rows that are whole 16-byte groups and aligned tensors.
-bool conv3x3c16_applies(const ConvEngineArgs &a) {
-  if (a.R != 3 || a.S != 3 || a.pad_h != 1 || a.pad_w != 1) return false;
+// counts that are multiples of 16 (of 8 for layers of at most 16 filters) or at most 12, rows that are
+// whole 16-byte groups and aligned tensors, as long as the filter slices of ALL channel chunks,
+// which a workgroup keeps in LDS for its whole life, fit the CU's LDS next to the halo tile
+// (deeper layers take the generic kernel, which stages one chunk's slice at a time).
+Conv3x3Pick conv3x3c16_pick(const ConvEngineArgs &a) {
+  Conv3x3Pick none, pick;
+  if (a.R != 3 || a.S != 3 || a.pad_h != 1 || a.pad_w != 1) return none;
   // whole 16-channel chunks, whole 8-channel chunks for layers of at most 16 filters, or up to three 4-channel chunks
-  if (a.Cin % 16 != 0 && !(a.Cin % 8 == 0 && a.Kout <= 16) && a.Cin > 12) return false;
-  if (a.Hout != a.Hin || a.Wout != a.Win) return false;
-  if (!aligned16(a.src)) return false;
+  if (a.Cin % 16 != 0 && !(a.Cin % 8 == 0 && a.Kout <= 16) && a.Cin > 12) return none;
+  if (a.Hout != a.Hin || a.Wout != a.Win) return none;
+  if (!aligned16(a.src)) return none;
   // the kernel addresses the source through 32-bit byte offsets that must stay below 2 GiB
-  if ((long)a.N * a.Cin * a.Hin * a.Win * 4 >= (1L << 31)) return false;
+  if ((long)a.N * a.Cin * a.Hin * a.Win * 4 >= (1L << 31)) return none;
   if (a.src_dz) {
     // the dz instances store plainly: anything else on top of a backward-form pass takes the generic kernel
-    if (a.act != ACT_IDENTITY || a.pool != 1) return false;
-    if (reads_output(a.src_act) && !aligned16(a.src_y)) return false;
-    if (a.src_pool == 2) return (a.Win % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.src_idx) & 3u) == 0);
+    if (a.act != ACT_IDENTITY || a.pool != 1) return none;
+    if (reads_output(a.src_act) && !aligned16(a.src_y)) return none;
+    if (a.src_pool == 2) {
+      if (a.Win % 8 != 0 || (reinterpret_cast<uintptr_t>(a.src_idx) & 3u) != 0) return none;
+    }
   }
-  return a.Win % 4 == 0;
+  if (a.Win % 4 != 0) return none;
+  // 16 output channels: 4 waves x 2 row pairs; 32: 8 waves x 1 row pair (more waves hide the
+  // longer per-step operand traffic better than more accumulators do)
+  if (a.Cin % 8 == 0 && a.Kout <= 16) pick = Conv3x3Pick{1, 4, 8};   // 8-channel chunks: four workgroups fit a CU's LDS instead of three
+  else if (a.Cin % 16 != 0) pick = a.Kout <= 16 ? Conv3x3Pick{1, 4, 4} : Conv3x3Pick{2, 4, 4};
+  else pick = Conv3x3Pick{2, 8, 16};   // wider layers run as groups of 32 output channels
+  const int nchunks = (a.Cin + pick.CC - 1) / pick.CC;
+  if (conv3x3c16_lds_bytes(pick.NT, pick.CC, nchunks) > chip().lds_bytes) return none;
+  return pick;
 }
 
 template <int NT, int WAVES, int CC>
@@ -955,13 +971,13 @@ hipError_t launch_3x3(const ConvEngineArgs &a, hipStream_t stream) {
   }
   const long tiles = (long)a.N * p.g.tiles_x * p.g.tiles_y;
   if (tiles <= 0 || tiles * p.g.nchunks > 0x7fffffffL) return hipErrorInvalidValue;
-  const size_t lds = conv3x3c16_lds<NT, CC>(p.g.nchunks);
-  if (lds > 160 * 1024) return hipErrorInvalidValue;
+  const size_t lds = conv3x3c16_lds_bytes(NT, CC, p.g.nchunks);
+  if (lds > chip().lds_bytes) return hipErrorInvalidValue;   // conv3x3c16_pick lets no such layer through
   // persistent workgroups: as many as fit on the chip at once (LDS-limited), each walks tiles
-  long resident = (long)(160 * 1024 / lds);
+  long resident = (long)(chip().lds_bytes / lds);
   constexpr long by_regs = conv3x3_occupancy(NT, WAVES, CC) / (WAVES / 4);
   if (resident > by_regs) resident = by_regs;
-  long blocks = 256 * resident / p.g.kgroups;
+  long blocks = (long)chip().cus * resident / p.g.kgroups;
   if (blocks < 1) blocks = 1;
   // Every CU gets its full set of resident workgroups even when the tiles do not divide evenly:
   // the workgroups of one CU share its MFMA pipes, so what has to balance is the tile count per
@@ -970,10 +986,8 @@ hipError_t launch_3x3(const ConvEngineArgs &a, hipStream_t stream) {
   if (blocks >= 8) blocks = (blocks + 7) / 8 * 8;   // whole rows of XCDs (see the tile order in the kernel)
   dim3 grid((unsigned)blocks, (unsigned)p.g.kgroups, 1);
   auto launch = [&](auto kern) -> hipError_t {
-    if (lds > 64 * 1024) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      if (e != hipSuccess) return e;
-    }
+    const hipError_t e = allow_large_lds(reinterpret_cast<const void *>(kern), lds);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, grid, dim3(WAVES * 64), lds, stream, p);
     return hipGetLastError();
   };
@@ -1001,16 +1015,13 @@ hipError_t launch_conv_engine(const ConvEngineArgs &a, hipStream_t stream) {
   // S of every 4*ceil((16+S-1)/4) window columns, clearly beats Kout of 16 channel columns
   if (a.Kout <= 3 && a.Kout * (4 * ((16 + a.S - 1 + 3) / 4)) * 3 < 16 * a.S * 2 && conv_fewout_applies(a))
     return launch_conv_fewout(a, stream);
-  { static const bool no_wino = getenv("DLL_NO_WINO") != nullptr; if (!no_wino && conv_wino_applies(a)) return launch_conv_wino(a, stream); }
-  if (a.Hout > 8 && conv3x3c16_applies(a)) {
-    // 16 output channels: 4 waves x 2 row pairs; 32: 8 waves x 1 row pair (more waves hide the
-    // longer per-step operand traffic better than more accumulators do)
-    if (a.Cin % 8 == 0 && a.Kout <= 16) return launch_3x3<1, 4, 8>(a, stream);   // 8-channel chunks: four workgroups fit a CU's LDS instead of three
-    if (a.Cin % 16 != 0) {
-      if (a.Kout <= 16) return launch_3x3<1, 4, 4>(a, stream);
-      return launch_3x3<2, 4, 4>(a, stream);
-    }
-    return launch_3x3<2, 8, 16>(a, stream);   // wider layers run as groups of 32 output channels
+  if (conv_wino_applies(a)) return launch_conv_wino(a, stream);
+  if (a.Hout > 8) {
+    const Conv3x3Pick pick = conv3x3c16_pick(a);
+    if (pick.NT == 1 && pick.CC == 8) return launch_3x3<1, 4, 8>(a, stream);
+    if (pick.NT == 1 && pick.CC == 4) return launch_3x3<1, 4, 4>(a, stream);
+    if (pick.NT == 2 && pick.CC == 4) return launch_3x3<2, 4, 4>(a, stream);
+    if (pick.NT == 2 && pick.CC == 16) return launch_3x3<2, 8, 16>(a, stream);
   }
   if (small) {
     if (nt == 1) return launch_t<1, 1>(a, stream);

@@ -264,7 +264,7 @@ hipError_t launch_conv_full_fft(const ConvFftArgs &g, hipStream_t stream) {
   v.xf = g.xf; v.wf = g.wf; v.N = g.N; v.K = g.K; v.C = g.C; v.lph = lph; v.lpw = lpw;
   v.H = g.H; v.W = g.W; v.off = g.pad; v.out = g.dx;
   // 2 x 2 tiles once there is enough work to fill the chip with them
-  if ((long)pairs * g.C >= 4 * 256)
+  if ((long)pairs * g.C >= 4L * chip().cus)
     hipLaunchKernelGGL((fft2_product_inverse_kernel<2, 2>), dim3((g.C + 1) / 2, (pairs + 1) / 2), dim3(kFftThreads), lds, stream, v);
   else
     hipLaunchKernelGGL((fft2_product_inverse_kernel<1, 1>), dim3(g.C, pairs), dim3(kFftThreads), lds, stream, v);

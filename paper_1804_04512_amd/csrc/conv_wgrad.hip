@@ -698,7 +698,7 @@ bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, int po
   const int kgroups = (K + mtf * 16 - 1) / (mtf * 16);
   // persistent workgroups: as many as stay resident (LDS and register budget), at least two
   // tiles each where the problem is large enough
-  long resident = (long)(160 * 1024 / plan->lds_bytes);
+  long resident = (long)(chip().lds_bytes / plan->lds_bytes);
   // waves per SIMD that the kernel instance's registers (vector + accumulator, from the compiler's
   // resource report) leave room for; a grid beyond it would queue workgroups behind resident ones
   static const int kByRegs[2][3][4] = {
@@ -714,11 +714,12 @@ bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, int po
   if (best_ntt == 2 && lines * 8 <= kThreads && lines * (S - 1) <= kThreads) by_regs = kByRegsOneRound[pool == 2 ? 0 : 1][mtf - 1];
   if (resident > by_regs) resident = by_regs;
   if (resident < 1) resident = 1;
-  long G = 256 * resident / ((long)plan->nchunks * kgroups);
+  const long cus = chip().cus;
+  long G = cus * resident / ((long)plan->nchunks * kgroups);
   if (G < 1) G = 1;
   // fewer tiles than CUs: one tile per workgroup (what counts there is the length of the longest
   // workgroup, not the number of partial blocks)
-  const long cap = items <= 256 ? items : (items + 1) / 2;
+  const long cap = items <= cus ? items : (items + 1) / 2;
   if (G > cap) G = cap;
   if (G < 1) G = 1;
   plan->G = (int)G;

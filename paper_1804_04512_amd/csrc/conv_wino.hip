@@ -459,7 +459,7 @@ hipError_t launch_conv_wino(const ConvEngineArgs &a, hipStream_t stream) {
   p.tiles_y = a.Hout / (8 * grp);
   p.items = a.N * p.tiles_x * p.tiles_y;
   const bool kk = a.Kout == 2 * kK;
-  int blocks = 256 * ((grp == 2 || kk) ? 2 : 3);   // resident workgroups per CU (LDS, registers)
+  int blocks = chip().cus * ((grp == 2 || kk) ? 2 : 3);   // resident workgroups per CU (LDS, registers)
   if (blocks > p.items) blocks = p.items;
   p.xcd = blocks % 8 == 0;   // workgroups go to the eight XCDs in turn: see the kernel's tile loop
   const bool two = a.Cin == 2 * kC;

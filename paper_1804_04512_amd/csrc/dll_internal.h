@@ -20,6 +20,14 @@ enum { ACT_PMP = 4 };
 // forward pass of a ReLU layer also sets kIdxInactive where the pooled output is zero.
 constexpr unsigned char kIdxPosMask = 3, kIdxInactive = 4;
 
+// What the launchers need to know of the GPU they size their grids for: the number of compute
+// units and the LDS of one compute unit, asked of the runtime once per device.
+struct ChipInfo { int cus = 0; size_t lds_bytes = 0; };
+const ChipInfo &chip();
+// Kernels that use more than 64 KB of dynamic LDS need the limit raised once per kernel and device;
+// this remembers which it has done.  A no-op for smaller sizes.
+hipError_t allow_large_lds(const void *kernel, size_t lds_bytes);
+
 // In-place parameter update, shared by every kernel that produces a gradient g of a parameter theta:
 //   v == NULL:  theta += step * g                                    (plain descent, step = -lr)
 //   v != NULL:  v = mu * v + step * (g + decay * theta);  theta += v  (momentum and weight decay)

@@ -849,7 +849,7 @@ int gemm_pick_split_k(int M, int N, int Kdim) {
   const long tiles = (long)((M + BM - 1) / BM) * ((N + BN - 1) / BN);
   const int ksteps = (Kdim + BK - 1) / BK;
   int split = 1;
-  while (tiles * split < 512 && split * 2 <= ksteps / 4 && split < 64) split *= 2;
+  while (tiles * split < 2L * chip().cus && split * 2 <= ksteps / 4 && split < 64) split *= 2;   // two units per compute unit
   return split;
 }
 
@@ -881,7 +881,8 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream) {
     hipLaunchKernelGGL(gemm_kernel, grid, dim3(kThreads), 0, stream, p);
   } else {
     const long units = (long)grid.x * grid.y * grid.z;
-    const dim3 pgrid((unsigned)(units < 768 ? units : 768));   // three resident workgroups per CU
+    const long resident = 3L * chip().cus;   // three resident workgroups per CU
+    const dim3 pgrid((unsigned)(units < resident ? units : resident));
     const int mode = p.a.split_k > 1 ? 0 : ((a.update && p.c_vec && !a.bias && a.act == ACT_IDENTITY && !a.C_ref) ? 1 : 2);
 #define DLL_GEMM_LAUNCH(AK, BK_)                                                                                      \
   do {                                                                                                                 \

@@ -9,15 +9,36 @@ TOL_FWD = 1e-4    # forward outputs, loss, logits, probabilities
 TOL_GRAD = 5e-4   # gradients and parameter deltas
 
 
+# (worst per-tensor error, worst element-wise relative error, number of tensors) of the test that is
+# running; conftest.py prints the table at the end of the session
+REPORT = {}
+_current = [None]
+
+
+def begin_report(test_name):
+    _current[0] = test_name
+
+
 def max_rel_err(got, ref) -> float:
-    """Per-tensor error: max |got - ref| / max(max |ref|, 1e-30)."""
+    """Per-tensor error: max |got - ref| / max(max |ref|, 1e-30).  Also records, for the session's
+    report, the element-wise relative error max |got - ref| / |ref| over the elements with
+    |ref| > 1e-3 max |ref| (small elements excluded: ReLU zeros and cancelling sums make the
+    ratio meaningless there)."""
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     assert got.shape == ref.shape, (got.shape, ref.shape)
     if ref.size == 0:
         return 0.0
     assert np.all(np.isfinite(got)), "non-finite values in the GPU result"
-    return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30))
+    diff = np.abs(got - ref)
+    top = max(np.abs(ref).max(), 1e-30)
+    err = float(diff.max() / top)
+    big = np.abs(ref) > 1e-3 * top
+    elem = float((diff[big] / np.abs(ref[big])).max()) if big.any() else 0.0
+    if _current[0] is not None:
+        e0, l0, n0 = REPORT.get(_current[0], (0.0, 0.0, 0))
+        REPORT[_current[0]] = (max(e0, err), max(l0, elem), n0 + 1)
+    return err
 
 
 def odesc(cs: wl.ConvSpec, pool=None, act=None):
@@ -55,6 +76,19 @@ def check_idx_flags_against(raw, relu, y_ref, tol=2e-5):
     assert not (flags[y_ref > tol * scale] != 0).any(), "inactive flag on a clearly active unit"
     stray = int((flags[y_ref == 0] == 0).sum())
     assert stray <= max(4, int(1e-4 * raw.size)), f"{stray} units flagged active where the reference output is zero"
+
+
+def check_relu_activity(active_gpu, y_ref, tol=2e-5):
+    """Activity decisions (unit output > 0) of a ReLU layer taken from the GPU's fp32 output against
+    a reference output: they may differ only inside a rounding band around zero, and rarely."""
+    active_ref = y_ref > 0
+    differ = active_gpu != active_ref
+    n = int(differ.sum())
+    if n:
+        scale = max(float(np.abs(y_ref).max()), 1e-30)
+        assert not (differ & (np.abs(y_ref) > tol * scale)).any(), "activity differs on a unit that is clearly on"
+        assert n <= max(4, int(1e-4 * differ.size)), f"{n} activity decisions differ"
+    return n
 
 
 def check_pool_idx(gpu_idx, ora_idx, prepool_act, y, tol=2e-5):

@@ -168,6 +168,63 @@ def test_cnn_step_pool_idx_override_routes_gradient():
     np.testing.assert_array_equal(other.grads[6], base.grads[6])   # layers above are unaffected
 
 
+def test_cnn_step_activity_override_decides_relu_derivative():
+    """The handed-in activity record replaces "output > 0" of a ReLU layer: the layer's own record
+    changes nothing; switching one active unit off removes exactly that unit's share of the bias
+    gradient (its pooled gradient, read off a composition of the separately pinned layers);
+    switching an inactive one on adds it; layers above are unaffected; an all-zero record kills
+    every gradient below the layer; a sigmoid layer ignores the record."""
+    B = 2
+    conv = [orc.conv_desc(B, 2, 10, 10, 3, 3, 3, 1, orc.ACT_RELU, 2), orc.conv_desc(B, 3, 5, 5, 4, 2, 2, 0, orc.ACT_RELU, 1)]
+    net = orc.Net(conv, [(4 * 4 * 4, 6, orc.ACT_RELU), (6, 5, orc.ACT_IDENTITY)], 5)
+    params, x, labels = tiny_inputs(net, 204)
+    run = lambda **kw: orc.cnn_train_step(net, [p.copy() for p in params], x, labels, 0.0, f64=True, **kw)
+    base = run()
+    y1, _ = orc.conv_valid_fwd(conv[0], x, params[0], params[1], f64=True)
+    y2, _ = orc.conv_valid_fwd(conv[1], y1, params[2], params[3], f64=True)
+    own = [(y1 > 0).astype(np.uint8), (y2 > 0).astype(np.uint8)]
+    same = run(active_in=own)
+    for a, b in zip(base.grads, same.grads):
+        np.testing.assert_array_equal(a, b)
+    # the gradient that reaches layer 2's output, from the dense layers
+    flat = y2.reshape(B, -1)
+    h1 = orc.dense_fwd(flat, params[4], params[5], orc.ACT_RELU, f64=True)
+    logits = orc.dense_fwd(h1, params[6], params[7], orc.ACT_IDENTITY, f64=True)
+    _, _, dl = orc.softmax_ce(logits, labels, f64=True)
+    dh1, _, _ = orc.dense_bwd(h1, params[6], logits, dl, orc.ACT_IDENTITY, f64=True)
+    dflat, _, _ = orc.dense_bwd(flat, params[4], h1, dh1, orc.ACT_RELU, f64=True)
+    dy2 = dflat.reshape(y2.shape)
+    on = np.argwhere(own[1] == 1)[0]
+    off = np.argwhere(own[1] == 0)[0]
+    for pos, sign in ((on, -1.0), (off, +1.0)):
+        rec = [own[0], own[1].copy()]
+        rec[1][tuple(pos)] ^= 1
+        got = run(active_in=rec)
+        k = pos[1]
+        expect = base.grads[3].copy()
+        expect[k] += sign * dy2[tuple(pos)]
+        np.testing.assert_allclose(got.grads[3], expect, rtol=1e-12, atol=1e-15)
+        for p in (4, 5, 6, 7):
+            np.testing.assert_array_equal(got.grads[p], base.grads[p])
+    dead = run(active_in=[None, np.zeros_like(own[1])])
+    for p in (0, 1, 2, 3):
+        assert not dead.grads[p].any()
+    np.testing.assert_array_equal(dead.grads[4], base.grads[4])
+    # only layer 1 overridden (pooled layer): switching a unit with non-zero gradient off changes dw0
+    rec0 = own[0].copy()
+    rec0[tuple(np.argwhere(own[0] == 1)[0])] = 0
+    assert not np.array_equal(run(active_in=[rec0, None]).grads[0], base.grads[0])
+    np.testing.assert_array_equal(run(active_in=[rec0, None]).grads[2], base.grads[2])
+    # a sigmoid layer's derivative does not look at the record
+    snet = tiny_net()
+    sp, sx, sl = tiny_inputs(snet, 205)
+    a = orc.cnn_train_step(snet, [p.copy() for p in sp], sx, sl, 0.0, f64=True)
+    zeros = [np.zeros(d.out_shape, np.uint8) for d in snet.conv]
+    b = orc.cnn_train_step(snet, [p.copy() for p in sp], sx, sl, 0.0, f64=True, active_in=zeros)
+    for u, v in zip(a.grads, b.grads):
+        np.testing.assert_array_equal(u, v)
+
+
 # ---------------------------------------------------------------- CRBM CD-1
 
 def crbm_inputs(seed, N=3, C=2, H=9, W=8, K=4, R=3, S=3):
