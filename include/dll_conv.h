@@ -46,7 +46,8 @@ typedef enum {
   DLL_ERR_SHAPE = 2,
   DLL_ERR_UNSUPPORTED = 3,
   DLL_ERR_WORKSPACE = 4,
-  DLL_ERR_DEVICE = 5
+  DLL_ERR_DEVICE = 5,
+  DLL_ERR_SCRATCH_LIMIT = 6 /* dll_conv_valid_wgrad_noalloc only: the layer needs more than its built-in scratch */
 } dll_status;
 
 /* Activation functions the paper's networks use (Sections II-B, IV-B, V, VI). */
@@ -131,6 +132,23 @@ dll_status dll_conv_full_bwd_fft(const dll_conv_desc *d, const float *dy, const 
 dll_status dll_conv_valid_wgrad(const dll_conv_desc *d, const float *x, const float *dy,
                                 const float *y, const unsigned char *pool_idx, float *dw,
                                 float *dbias, void *ws, size_t ws_bytes, void *stream);
+
+/* The same filter-gradient layer for callers that cannot allocate device memory or carry a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments (minus the workspace), same kernels, bit-identical results; the partial sums
+ * live in an array built into the library, DLL_NOALLOC_SCRATCH_BYTES of device memory that every
+ * GPU the library runs on holds until the process ends.  The call allocates and frees nothing.
+ *   - A layer whose dll_conv_workspace_bytes(d) exceeds DLL_NOALLOC_SCRATCH_BYTES is rejected
+ *     with DLL_ERR_SCRATCH_LIMIT before anything is launched (config 5's largest layer needs 3.7 MB).
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ *     streams, two threads) race and give undefined results; calls on one stream are ordered.
+ *     Nothing in the array has to be cleared between calls.
+ *   - The first call on a device asks the runtime for the array's address on that device; make
+ *     that first call outside graph capture. */
+#define DLL_NOALLOC_SCRATCH_BYTES ((size_t)8 << 20)
+dll_status dll_conv_valid_wgrad_noalloc(const dll_conv_desc *d, const float *x, const float *dy,
+                                        const float *y, const unsigned char *pool_idx, float *dw,
+                                        float *dbias, void *stream);
 
 /* One CD-1 step of a convolutional RBM with binary visible and hidden units (Section II:
  * RBM/CRBM trained with Contrastive Divergence).  d->act and d->pool are ignored.

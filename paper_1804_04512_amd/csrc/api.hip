@@ -181,6 +181,7 @@ const char *dll_status_string(dll_status s) {
   case DLL_ERR_UNSUPPORTED: return "unsupported configuration";
   case DLL_ERR_WORKSPACE: return "workspace too small or misaligned";
   case DLL_ERR_DEVICE: return "device launch failed";
+  case DLL_ERR_SCRATCH_LIMIT: return "layer needs more scratch than the built-in array of the no-allocation entry point holds";
   }
   return "unknown status";
 }
@@ -268,6 +269,53 @@ dll_status dll_conv_valid_wgrad(const dll_conv_desc *d, const float *x, const fl
   r.pos = partial; r.scale = 1.0f; r.dw = dw; r.db = dbias;
   r.C = d->C; r.K = d->K; r.R = d->R; r.S = d->S;
   return dev(launch_wgrad_reduce(r, plan, s));
+}
+
+// ---- the filter gradient for callers that cannot allocate: same kernels, the partial sums live in
+// a file-scope device array instead of a caller workspace.  Every GPU the library runs on holds its
+// own copy of the array (at its own address) until the process ends.
+}  // extern "C"
+
+namespace {
+constexpr size_t kScratchBytes = DLL_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[64];   // per device: the array's device address, asked of the runtime once
+
+// The array's name is a host-side stand-in for the symbol, not a device address: host code only
+// ever uses the address the runtime returns for the current device.
+dll_status scratch_of_current_device(void **out) {
+  int device = 0;
+  if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= 64) return DLL_ERR_DEVICE;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return DLL_ERR_DEVICE;
+    }
+    g_scratch_ptr[device] = ptr;
+  }
+  *out = g_scratch_ptr[device];
+  return DLL_OK;
+}
+}  // namespace
+
+extern "C" {
+
+dll_status dll_conv_valid_wgrad_noalloc(const dll_conv_desc *d, const float *x, const float *dy, const float *y,
+                                        const unsigned char *pool_idx, float *dw, float *dbias, void *stream) {
+  dll_status st = check_desc(d);
+  if (st != DLL_OK) return st;
+  WgradPlan plan;
+  if (!plan_for(d, &plan)) return DLL_ERR_UNSUPPORTED;
+  if (align_up(plan.partial_floats * sizeof(float)) > kScratchBytes) return DLL_ERR_SCRATCH_LIMIT;
+  void *ptr = nullptr;
+  st = scratch_of_current_device(&ptr);
+  if (st != DLL_OK) return st;
+  // every partial sum the reduction reads is written by the first kernel of this call: nothing in
+  // the array has to start at zero, and what an earlier (larger) call left behind is never read
+  return dll_conv_valid_wgrad(d, x, dy, y, pool_idx, dw, dbias, ptr, kScratchBytes, stream);
 }
 
 size_t dll_crbm_workspace_bytes(const dll_conv_desc *d) {

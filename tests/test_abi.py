@@ -28,8 +28,8 @@ def test_header_symbols_are_exported():
 
 def test_status_strings():
     L = binding.lib()
-    seen = {L.dll_status_string(i).decode() for i in range(6)}
-    assert len(seen) == 6 and "ok" in seen
+    seen = {L.dll_status_string(i).decode() for i in range(7)}
+    assert len(seen) == 7 and "ok" in seen
 
 
 def test_workspace_queries_are_host_side():
