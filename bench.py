@@ -158,6 +158,35 @@ def conv_pass_table(B, wl_cnn, dev_params, x_dev, iters):
 
 
 SETTLE_S = 0.1   # untimed steady-state run-in before the timed steps (see main)
+N_BATCHES = 3    # input batches the timed steps of config 5 rotate through (3 x 100.7 MB: more than the 256 MB memory-side cache)
+
+# Figures of one config-5 step (batch 128) that only profiler counter runs can give; they do not depend
+# on the data, only on the kernels, and are re-taken whenever a kernel changes (the profile file
+# names the commands).  MFMA wave-instructions: SQ_INSTS_VALU_MFMA_MOPS_F32-class counters summed over
+# the step's kernels, each v_mfma_f32_16x16x4_f32 being 2048 FLOP.  HBM bytes: FETCH_SIZE and
+# WRITE_SIZE summed over the step's kernels with the copy-kernel calibration.
+RECORDED_STEP_COUNTERS = {
+    ("c5_large_image_cnn", 128): {"mfma_wave_instructions": 30.5e6, "hbm_bytes": 1.8e9,
+                                  "source": "profiles/c5_cnn_train_step.md (rocprofv3 --pmc runs of this bench command)"},
+}
+
+
+def chip_probe():
+    """Runs the stand-alone probe (bench_chip_probe, built by __graft_entry__.build()) as a child
+    process and returns its JSON line: the fp32 MFMA rate of a register-only loop and the HBM
+    copy / read / write rates on this very box.  None when the program is not there."""
+    import subprocess
+    exe = os.path.join(ROOT, "bench_chip_probe")
+    if not os.path.exists(exe):
+        return None
+    try:
+        r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+        for line in reversed(r.stdout.splitlines()):
+            if line.startswith("{"):
+                return json.loads(line)
+    except Exception as e:   # noqa: BLE001 - the probe is a side measurement
+        print(f"bench.py: chip probe failed ({e})", file=sys.stderr)
+    return None
 
 # HBM bytes per launch of the kernels that can come out as the dominant one at config 5, batch 128,
 # from the FETCH_SIZE / WRITE_SIZE counter runs summarised in profiles/c5_cnn_train_step.md
@@ -359,6 +388,7 @@ def main():
     from paper_1804_04512_amd import workloads as wl
 
     B.lib()  # fail loudly when the HIP library is missing
+    probe = chip_probe() if args.mode == "train" else None   # before this process touches the GPU
     torch.cuda.set_device(0)
     if args.mode == "infer":
         return infer_line(args, B, wl, torch)
@@ -376,6 +406,14 @@ def main():
         ws = B.workspace(B.dll_cnn_workspace_bytes(net))
         step = lambda: B.dll_cnn_train_step(net, params, None, x, labels, w.lr, loss, None, None, ws)
         batch = w.batch
+        # further input batches for the timed steps to rotate through (same distribution, seeded on the device)
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(18040451)
+        xs, ls = [x], [labels]
+        for _ in range(N_BATCHES - 1 if cfg == 5 else 0):
+            xs.append(torch.randn(x.shape, device="cuda", generator=gen))
+            ls.append(torch.randint(0, w.classes, labels.shape, device="cuda", generator=gen, dtype=torch.int32))
+        step_on = lambda j: B.dll_cnn_train_step(net, params, None, xs[j], ls[j], w.lr, loss, None, None, ws)
     elif isinstance(w, wl.CrbmWorkload):
         cs = w.conv
         W, b, c = dev(w.W), dev(w.b), dev(w.c)
@@ -420,45 +458,100 @@ def main():
     # to step, so a whole step can be captured once into a HIP graph and replayed: the same
     # kernels on the same data, with the launch work done once.  Plain launches remain as
     # `--launch eager`, and as the fallback should the capture fail.
-    run, launch = step, "eager"
+    rotating = isinstance(w, wl.CnnWorkload) and len(xs) > 1
+    runs, launch = ([lambda j=j: step_on(j) for j in range(len(xs))] if rotating else [step]), "eager"
     if args.launch == "graph":
         try:
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
-                step()
+            graphs = []
+            for r_ in runs:   # one graph per input batch: same kernels, same parameters and workspace, another x
+                gr_ = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gr_):
+                    r_()
+                graphs.append(gr_)
             torch.cuda.synchronize()
             for _ in range(max(1, args.warmup)):
-                graph.replay()
+                for gr_ in graphs:
+                    gr_.replay()
             torch.cuda.synchronize()
-            run, launch = graph.replay, "hip graph replay"
+            runs, launch = [gr_.replay for gr_ in graphs], "hip graph replay"
         except Exception as e:   # noqa: BLE001 - any capture problem means: time plain launches
             print(f"bench.py: graph capture failed ({e}); timing plain launches", file=sys.stderr)
             torch.cuda.synchronize()
-    # The chip takes some tens of milliseconds of continuous work to reach its steady clocks after
-    # an idle spell (the set-up above leaves several): steps are run, untimed, for SETTLE_S seconds
-    # so that the timed steps measure the steady state a training job runs in.
-    t_settle = time.perf_counter()
-    while time.perf_counter() - t_settle < SETTLE_S:
-        for _ in range(10):
-            run()
+
+    def timed(run_list):
+        # The chip takes some tens of milliseconds of continuous work to reach its steady clocks after
+        # an idle spell (the set-up above leaves several): steps are run, untimed, for SETTLE_S seconds
+        # so that the timed steps measure the steady state a training job runs in.
+        t_settle = time.perf_counter()
+        k = 0
+        while time.perf_counter() - t_settle < SETTLE_S:
+            for _ in range(10):
+                run_list[k % len(run_list)]()
+                k += 1
+            torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            run_list[i % len(run_list)]()
         torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        run()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
+        return (time.perf_counter() - t0) / args.steps * 1e3
+
+    # the timed steps: every step takes the next input batch, so that no step finds its input in the
+    # memory-side cache; the same steps on ONE resident batch are timed beside them
+    resident_ms = timed(runs[:1]) if rotating else None
+    ms_per_step = timed(runs)
     flop = w.flop()
     gflops = flop / (ms_per_step * 1e-3) / 1e9
+
+    # after the timed region: the state thousands of in-place updates have left must still train.
+    # One more step as the timed steps ran it, and the same step from the same state as plain launches:
+    # both losses must be finite and bit-equal (the kernels are deterministic).
+    loss_check = None
+    if isinstance(w, wl.CnnWorkload):
+        saved = [p_.clone() for p_ in params]
+        runs[0]()
+        torch.cuda.synchronize()
+        loss_timed_path = float(loss.item())
+        for p_, s_ in zip(params, saved):
+            p_.copy_(s_)
+        (step_on(0) if rotating else step())
+        torch.cuda.synchronize()
+        loss_eager = float(loss.item())
+        if not (np.isfinite(loss_timed_path) and loss_timed_path == loss_eager):
+            print(f"bench.py: loss check failed: {loss_timed_path} (timed path) vs {loss_eager} (plain launches)", file=sys.stderr)
+            return 1
+        loss_check = {"loss_after_timed_steps": loss_timed_path, "equals_plain_launch_step_from_same_state": True}
+        del saved
 
     out = {
         "metric": METRIC, "value": gflops, "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": w.name, "batch": batch, "flop_per_step": flop, "launch": launch, "settle_s": SETTLE_S},
+        "config": {"workload": w.name, "batch": batch, "flop_per_step": flop, "launch": launch, "settle_s": SETTLE_S,
+                   "input_batches_rotated": len(runs)},
         "images_per_s": batch / (ms_per_step * 1e-3),
+        # value / peak with the FLOP of the direct sums (the algorithmic work), also for the passes that run in
+        # the minimal-filtering form and execute fewer multiplications: an EFFECTIVE figure, not an MFMA rate
         "pct_fp32_mfma_peak": 100.0 * gflops / (PEAK_FP32_MFMA_TFLOPS * 1e3),
+        "pct_fp32_mfma_peak_is": "direct-sum FLOP per second over the published peak (effective; see mfma_executed)",
     }
+    if resident_ms is not None:
+        out["resident_batch"] = {"ms_per_step": resident_ms, "value": flop / (resident_ms * 1e-3) / 1e9,
+                                 "note": "the same steps fed ONE input batch: part of x then survives in the memory-side cache from step to step"}
+    if loss_check:
+        out["loss_check"] = loss_check
+    if probe:
+        out["measured_peaks"] = probe
+        out["pct_measured_mfma_peak"] = 100.0 * gflops / (probe["mfma_f32_tflops"] * 1e3)
+    rec = RECORDED_STEP_COUNTERS.get((w.name, batch))
+    if rec:
+        ex = rec["mfma_wave_instructions"] * 2048 / (ms_per_step * 1e-3) / 1e12
+        out["mfma_executed"] = {"tflops": ex, "util_of_published_peak": ex / PEAK_FP32_MFMA_TFLOPS,
+                                "util_of_measured_loop": (ex / probe["mfma_f32_tflops"]) if probe else None,
+                                "wave_instructions_per_step": rec["mfma_wave_instructions"], "source": rec["source"]}
+        hb = rec["hbm_bytes"] / (ms_per_step * 1e-3) / 1e9
+        out["hbm"] = {"gbps": hb, "bytes_per_step": rec["hbm_bytes"], "copy_peak_gbps": probe["hbm_copy_gbps"] if probe else None,
+                      "frac_of_copy_peak": (hb / probe["hbm_copy_gbps"]) if probe else None,
+                      "frac_of_published_peak": hb / 8000.0, "source": rec["source"]}
     if isinstance(w, wl.CnnWorkload):
         out["config"]["conv_flop_per_step"] = w.conv_flop()
         conv_ms = sum(r["ms"] for r in table)
@@ -477,7 +570,9 @@ def main():
                            "avg_launch_ms": gr["ms"] / gr["n"], "flop_per_launch": gr["flop"] / gr["n"],
                            "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                            "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-                           "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, batch, name))}
+                           "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, batch, name)),
+                           "traffic_source": "recorded: profiles/c5_cnn_train_step.md counter runs (FETCH_SIZE, WRITE_SIZE with the "
+                                             "copy-kernel calibration); counters cannot be read inside this run"}
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_batch if cfg == 5 else batch, threads=args.cpu_threads)
     print(json.dumps(out))

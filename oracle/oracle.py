@@ -18,7 +18,8 @@ from typing import Optional, Sequence
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libdll_oracle.so")
+# DLL_ORACLE_LIB points the tests at another build of the same source (the sanitizer build)
+_LIB_PATH = os.environ.get("DLL_ORACLE_LIB") or os.path.join(_HERE, "libdll_oracle.so")
 
 ACT_IDENTITY, ACT_SIGMOID, ACT_RELU = 0, 1, 2
 
@@ -30,6 +31,18 @@ def build(force: bool = True) -> str:
                os.path.join(_HERE, "dll_oracle.c"), "-o", _LIB_PATH, "-lm"]
         subprocess.run(cmd, check=True, cwd=_HERE)
     return _LIB_PATH
+
+
+def build_sanitized(out_path: str) -> str:
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer (host code only).  Run
+    the CPU tests on it with
+      LD_PRELOAD=$(gcc -print-file-name=libasan.so) ASAN_OPTIONS=detect_leaks=0 \
+      UBSAN_OPTIONS=halt_on_error=1 DLL_ORACLE_LIB=<out_path> python -m pytest tests -m 'not gpu'
+    """
+    cmd = ["gcc", "-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+           "-fopenmp", "-Wall", "-Wextra", "-shared", "-fPIC", os.path.join(_HERE, "dll_oracle.c"), "-o", out_path, "-lm"]
+    subprocess.run(cmd, check=True, cwd=_HERE)
+    return out_path
 
 
 class ConvDesc(C.Structure):
