@@ -104,6 +104,10 @@ def engine_kernel_name(cs, backward: bool) -> str:
 def wgrad_kernel_name(cs) -> str:
     """Name of the filter-gradient kernel instance of a layer (mirrors plan_wgrad / launch_wgrad in
     csrc/conv_wgrad.hip for aligned tensors; used only to label the pass in the report)."""
+    if (cs.R == 3 and cs.S == 3 and cs.pad == 1 and cs.pool == 2 and cs.act == "relu" and cs.C in (16, 32) and cs.K in (16, 32)
+            and cs.W % 8 == 0):
+        # the pooled ReLU layers with 16 or 32 channels in and out: minimal-filtering form (the step passes no layer output)
+        return f"wgrad_wino_kernel<{cs.K // 16},{cs.C // 16}>"
     taps = cs.R * cs.S
     best = None
     for cc in range(1, min(cs.C, 16) + 1):

@@ -721,6 +721,9 @@ bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, int po
   // workgroup, not the number of partial blocks)
   const long cap = items <= cus ? items : (items + 1) / 2;
   if (G > cap) G = cap;
+  // layers the minimal-filtering kernel can take: its registers leave two workgroups per compute unit,
+  // and every one of them should be resident from the start (the direct kernel copes with any G)
+  if (wgrad_wino_shape(C, H, W, K, R, S, pad, pool) && mtf * 16 == K && best_cc == 16) G = 2 * cus < items ? 2 * cus : items;
   if (G < 1) G = 1;
   plan->G = (int)G;
   plan->n_partials = plan->G;
@@ -767,6 +770,7 @@ inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 
 }  // namespace
 
 hipError_t launch_wgrad(const WgradArgs &a, const WgradPlan &plan, hipStream_t stream) {
+  if (wgrad_wino_applies(a, plan)) return launch_wgrad_wino(a, plan, stream);
   WgradParams p;
   p.a = a;
   p.Ho = a.H + 2 * a.pad - a.R + 1;

@@ -1,0 +1,373 @@
+// Filter gradient of the padded 3x3 layers with 16 or 32 channels in and out behind ReLU + 2x2 max
+// pooling, in the minimal-filtering form F(3x3, 2x2), on fp32 MFMA (v_mfma_f32_16x16x4_f32), gfx950.
+//
+//   dw[k,c,r,s] = sum_{n,i,j} dz[n,k,i,j] * xpad[n,c,i+r,j+s]      (Section II-A, gradient computations)
+//
+// Seen per 2x2 block of dz, the nine sums are a 3x3-output correlation of the block (the "filter")
+// with the 4x4 patch of x around it:  dw = sum_blocks A^T [ (G g G^T) .* (B^T d B) ] A  with
+//   B^T = [1 0 -1 0; 0 1 1 0; 0 -1 1 0; 0 1 0 -1],  G = [1 0; 1 1; 1 -1; 0 -1],  A^T = [1 .5 .5 0; 0 .5 -.5 0; 0 .5 .5 1]
+// (the transposed form of the F(2x2, 3x3) matrices the forward kernel uses).  The sums over blocks
+// and images of the 16 point-wise products are the matrix part: per transform point p,
+// M_p[k][c] = sum_blocks U_p[k][block] * V_p[c][block], 16 x 16 x 4 blocks per MFMA: four
+// instructions per block of four pixels where the direct sum takes nine; A^T . A is applied once,
+// at the very end.  The pooled layer makes the filter-side transform trivial: a 2x2 block of dz is
+// one pooling window and holds at most one non-zero, dy at the recorded position (a, b), so
+// U = dy * (G[:,a] outer G[:,b]) has entries 0 and +-dy only: selects, no arithmetic.
+//
+// Layout: filters on the MFMA M axis, channels on N, blocks on K.  Lane (i16, kq) builds U for
+// filter i16 and V for channel i16 of ITS block, register-local: the x patch comes from LDS as four
+// rows of two 8-byte reads, dy and the pooling byte straight from global memory (16 consecutive
+// blocks of a filter row are four lanes' 16-byte loads).  Every wavefront works alone: its own
+// (filter tile, channel tile) pair, its own strip of blocks, its own four-row ring of x rows in
+// LDS (two new rows per block row, fetched one block row ahead), no workgroup barrier until the
+// final, fixed-order sum of the wavefronts' results.  The partial blocks have the layout of the
+// direct kernel's, so the same reduction kernel finishes both.
+#include "dll_internal.h"
+
+#include <type_traits>
+
+namespace dllk {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kRS = 36;                 // LDS row: image columns x0-1 .. x0+32 at LDS columns 0 .. 33
+constexpr int kPS = 4 * kRS + 2;        // channel plane of four row slots; half of it odd: conflict-free 8-byte reads
+constexpr int kWaveFloats = 16 * kPS;   // one wavefront's ring: 16 channels
+constexpr int kXR = 4;                  // 16 channels x 2 rows x 8 aligned 16-byte groups = 4 per lane
+constexpr unsigned kOob = 0x80000000u;
+
+struct WinoWgradParams {
+  WgradArgs a;
+  int Hp, Wp;          // pooled map = blocks per column / row
+  int xsegs, xgroups;  // 32-pixel column segments; groups of as many neighbouring segments as a workgroup has streams
+  int rg, rgroups;     // block rows per work item, row groups per image
+  int items;           // work items of a workgroup: N * rgroups * xgroups
+  int G;               // workgroups = partial blocks per channel chunk
+  long db_offset;
+  unsigned x_bytes, dy_bytes;
+};
+
+// KT, CT: 16-filter and 16-channel tiles (1 or 2 each); the 4 / (KT * CT) remaining wavefronts of a
+// workgroup are independent streams over the work items.
+template <int KT, int CT>
+__global__ __launch_bounds__(kThreads, 2) void wgrad_wino_kernel(const WinoWgradParams p) {
+  constexpr int NC = KT * CT, S = 4 / NC;
+  extern __shared__ float lds[];
+  const WgradArgs &a = p.a;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i16 = lane & 15, kq = lane >> 4;
+  const int combo = wave % NC, stream = wave / NC;
+  const int ktile = combo % KT, ctile = combo / KT;
+  const int gidx = blockIdx.x;
+  const int c0 = ctile * 16, k0 = ktile * 16;
+  float *xs = lds + wave * kWaveFloats;
+
+  const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.x), 0, (int)p.x_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_dy = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.dy), 0, (int)p.dy_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_idx = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char *>(a.idx), 0, (int)(p.dy_bytes >> 2), 0x00020000);
+
+  // Staging slots of a pair of image rows.  Main slots: (channel, row of the pair, aligned 16-byte
+  // group j of the segment), four per lane; halo slots: (channel, row, left or right neighbour
+  // column), one per lane.  A slot's place in the tensor is fixed per work item (xv, hv: byte
+  // offsets of the slot in the item's FIRST pair, or an out-of-range offset where the slot lies
+  // outside the image: such loads return zero, the padding value).
+  int xlo[kXR], xcol[kXR], xpl[kXR];
+  bool xr1[kXR];
+#pragma unroll
+  for (int it = 0; it < kXR; ++it) {
+    const int s = lane + 64 * it;
+    const int ch = s >> 4, rr = (s >> 3) & 1, j = s & 7;
+    xr1[it] = rr == 1;
+    xpl[it] = (ch * a.H + rr) * a.W + 4 * j;      // elements from (n, c0, first row of the pair, x0)
+    xcol[it] = 4 * j;
+    xlo[it] = ch * kPS + rr * kRS + 4 * j + 1;
+  }
+  const int h_ch = lane >> 2, h_rr = (lane >> 1) & 1, h_side = lane & 1;
+  const int hpl = (h_ch * a.H + h_rr) * a.W + (h_side ? 32 : -1);
+  const int hlo = h_ch * kPS + h_rr * kRS + (h_side ? 33 : 0);
+
+  floatx4 acc[16];
+#pragma unroll
+  for (int q = 0; q < 16; ++q) acc[q] = floatx4{0.f, 0.f, 0.f, 0.f};
+  float dbsum = 0.0f;
+
+  float4 xa[kXR], xb[kXR];   // two pairs of rows on their way from memory to LDS
+  float ha = 0.0f, hb = 0.0f;
+  float4 dyc = make_float4(0.f, 0.f, 0.f, 0.f), dyn = dyc;
+  unsigned idc = 0, idn = 0;
+  unsigned xv[kXR], hv = kOob, dv = kOob, iv = kOob;   // per-item byte offsets of the lane's slots
+
+  // per item: where the lane's slots of the item's first pair (rows 2*by0-1, 2*by0) and first block row lie
+  auto item_setup = [&](int n, int x0, int bx0, int by0) {
+    const int base = ((n * a.C + c0) * a.H + (2 * by0 - 1)) * a.W + x0;
+#pragma unroll
+    for (int it = 0; it < kXR; ++it) xv[it] = x0 + xcol[it] < a.W ? 4u * (unsigned)(base + xpl[it]) : kOob;
+    const int hc = x0 + (h_side ? 32 : -1);
+    hv = (x0 < a.W && (unsigned)hc < (unsigned)a.W) ? 4u * (unsigned)(base + hpl) : kOob;
+    const bool ok = bx0 + 4 * kq < p.Wp;
+    const unsigned e = (unsigned)(((n * a.K + k0 + i16) * p.Hp + by0) * p.Wp + bx0 + 4 * kq);
+    dv = ok ? 4u * e : kOob;
+    iv = ok ? e : kOob;
+  };
+  // rows 2P-1 and 2P -> registers; dP = P - by0 of the item.  The pair's distance from the item's
+  // first pair is added to the lanes' offsets, not passed as the loads' scalar offset: row -1 of the
+  // tensor's very first plane has a negative offset, and the range check of a buffer load looks at
+  // the vector offset on its own, so a negative one made good by a scalar offset would read zero.
+  auto load_pair = [&](int P, int dP, float4 (&xr)[kXR], float &xh) {
+    const unsigned down = (unsigned)(8 * a.W) * (unsigned)dP;
+    const bool top = P == 0, bot = 2 * P >= a.H;        // the pair's first row is above / its second row below the image
+#pragma unroll
+    for (int it = 0; it < kXR; ++it) {
+      unsigned off = xv[it] + down;                     // an out-of-range marker stays one (down < 2^24)
+      if (top || bot) off = (xr1[it] ? bot : top) ? kOob : off;
+      const floatx4 v = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rs_x, (int)off, 0, 0));
+      xr[it] = make_float4(v[0], v[1], v[2], v[3]);
+    }
+    unsigned off = hv + down;
+    if (top || bot) off = (h_rr ? bot : top) ? kOob : off;
+    xh = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_x, (int)off, 0, 0));
+  };
+  // registers -> the pair's two row slots (image column x0 sits at LDS column 1)
+  auto store_pair = [&](int slotpair, const float4 (&xr)[kXR], float xh) {
+    float *dst = xs + slotpair * 2 * kRS;
+#pragma unroll
+    for (int it = 0; it < kXR; ++it) {
+      float *d = dst + xlo[it];
+      d[0] = xr[it].x;
+      *reinterpret_cast<float2 *>(d + 1) = make_float2(xr[it].y, xr[it].z);
+      d[3] = xr[it].w;
+    }
+    dst[hlo] = xh;
+  };
+  // pooled gradients and pooling bytes of block row by0 + dB: the lane's filter, blocks bx0 + 4kq .. + 3
+  auto load_dy = [&](int dB, float4 &g, unsigned &f) {
+    const floatx4 v = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rs_dy, (int)dv, (int)(4u * (unsigned)p.Wp * (unsigned)dB), 0));
+    g = make_float4(v[0], v[1], v[2], v[3]);
+    f = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(rs_idx, (int)iv, (int)((unsigned)p.Wp * (unsigned)dB), 0);
+  };
+
+  // one block row: four groups of four blocks; `spc` = parity of the block row = which row slots hold
+  // rows 2by-1, 2by (pair by) and 2by+1, 2by+2 (pair by+1)
+  const float *patch = xs + i16 * kPS + 8 * kq;
+  auto block_row = [&](auto spc) {
+    constexpr int SP = decltype(spc)::value;
+    const float gv[4] = {dyc.x, dyc.y, dyc.z, dyc.w};
+    // x patch of the lane's block of group g (rows 2by-1 .. 2by+2, columns 2bx-1 .. 2bx+2); the reads
+    // of group g+1 are issued before the products of group g
+    float2 pl[2][4], ph[2][4];
+    auto read_patch = [&](auto gc) {
+      constexpr int g = decltype(gc)::value;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int slot = i < 2 ? 2 * SP + i : 2 * (SP ^ 1) + (i - 2);
+        pl[g & 1][i] = *reinterpret_cast<const float2 *>(patch + slot * kRS + 2 * g);
+        ph[g & 1][i] = *reinterpret_cast<const float2 *>(patch + slot * kRS + 2 * g + 2);
+      }
+    };
+    auto group = [&](auto gc) {
+      constexpr int g = decltype(gc)::value;
+      if constexpr (g < 3) read_patch(std::integral_constant<int, g + 1>{});
+      __builtin_amdgcn_sched_barrier(0);
+      // ---- U = dy * (G[:,a] outer G[:,b]): G[:,0] = (1, 1, 1, 0), G[:,1] = (0, 1, -1, -1)
+      const unsigned f = (idc >> (8 * g)) & 0xffu;
+      const float v = (f & kIdxInactive) ? 0.0f : gv[g];
+      if (CT == 1 || ctile == 0) dbsum += v;
+      const bool pa = (f & 2u) != 0, pb = (f & 1u) != 0;
+      const float R[4] = {pa ? 0.0f : v, v, pa ? -v : v, pa ? -v : 0.0f};
+      // ---- V = B^T d B
+      float t[4][4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float d0 = j < 2 ? (j ? pl[g & 1][0].y : pl[g & 1][0].x) : (j == 2 ? ph[g & 1][0].x : ph[g & 1][0].y);
+        const float d1 = j < 2 ? (j ? pl[g & 1][1].y : pl[g & 1][1].x) : (j == 2 ? ph[g & 1][1].x : ph[g & 1][1].y);
+        const float d2 = j < 2 ? (j ? pl[g & 1][2].y : pl[g & 1][2].x) : (j == 2 ? ph[g & 1][2].x : ph[g & 1][2].y);
+        const float d3 = j < 2 ? (j ? pl[g & 1][3].y : pl[g & 1][3].x) : (j == 2 ? ph[g & 1][3].x : ph[g & 1][3].y);
+        t[0][j] = d0 - d2;
+        t[1][j] = d1 + d2;
+        t[2][j] = d2 - d1;
+        t[3][j] = d1 - d3;
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float V0 = t[i][0] - t[i][2], V1 = t[i][1] + t[i][2], V2 = t[i][2] - t[i][1], V3 = t[i][1] - t[i][3];
+        const float U0 = pb ? 0.0f : R[i], U1 = R[i], U2 = pb ? -R[i] : R[i], U3 = pb ? -R[i] : 0.0f;
+        acc[4 * i + 0] = __builtin_amdgcn_mfma_f32_16x16x4f32(U0, V0, acc[4 * i + 0], 0, 0, 0);
+        acc[4 * i + 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(U1, V1, acc[4 * i + 1], 0, 0, 0);
+        acc[4 * i + 2] = __builtin_amdgcn_mfma_f32_16x16x4f32(U2, V2, acc[4 * i + 2], 0, 0, 0);
+        acc[4 * i + 3] = __builtin_amdgcn_mfma_f32_16x16x4f32(U3, V3, acc[4 * i + 3], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    read_patch(std::integral_constant<int, 0>{});
+    group(std::integral_constant<int, 0>{});
+    group(std::integral_constant<int, 1>{});
+    group(std::integral_constant<int, 2>{});
+    group(std::integral_constant<int, 3>{});
+  };
+
+  // ---- work items: (image, group of block rows, group of S neighbouring column segments), one segment
+  // per stream, so that the wavefronts of a workgroup read neighbouring pieces of the same image
+  // rows at about the same time; each stream walks its segment downwards.  A stream whose segment
+  // lies beyond the row (the last group of a row that is not a multiple of S segments wide) sits the
+  // item out.  The two pairs of rows and the gradients that an item starts with are requested during
+  // the last block row of the item before it, so a stream waits for memory only once, at its start.
+  auto begin_item = [&](int item, int &by1) {
+    const int xg = item % p.xgroups;
+    const int rgrp = (item / p.xgroups) % p.rgroups;
+    const int n = item / (p.xgroups * p.rgroups);
+    const int xseg = xg * S + stream;
+    const int by0 = rgrp * p.rg;
+    item_setup(n, xseg * 32, xseg * 16, by0);      // a segment beyond the row gets out-of-range offsets only
+    by1 = xseg < p.xsegs ? min(by0 + p.rg, p.Hp) : by0;
+    return by0;
+  };
+  auto request_item = [&](int item) {
+    int by1;
+    const int by0 = begin_item(item, by1);
+    if (by1 > by0) {
+      load_pair(by0, 0, xa, ha);
+      load_pair(by0 + 1, 1, xb, hb);
+      load_dy(0, dyn, idn);
+    }
+  };
+  if (gidx < p.items) request_item(gidx);
+  for (int item = gidx; item < p.items; item += p.G) {
+    int by1;
+    const int by0 = begin_item(item, by1);
+    dyc = dyn;
+    idc = idn;
+    if (by1 > by0) store_pair(by0 & 1, xa, ha);
+    for (int by = by0; by < by1; ++by) {
+      // rows 2by+1, 2by+2, requested during the previous block row (or with the item's first pair)
+      if (by == by0) store_pair((by + 1) & 1, xb, hb);
+      else store_pair((by + 1) & 1, xa, ha);
+      if (by + 1 < by1) {
+        load_pair(by + 2, by + 2 - by0, xa, ha);    // in flight during this block row's products
+        load_dy(by + 1 - by0, dyn, idn);
+      } else if (item + p.G < p.items) {
+        request_item(item + p.G);
+      }
+      if (by & 1) block_row(std::integral_constant<int, 1>{});
+      else block_row(std::integral_constant<int, 0>{});
+      dyc = dyn;
+      idc = idn;
+    }
+    if (by1 == by0 && item + p.G < p.items) request_item(item + p.G);   // sat this one out: still ask for the next
+  }
+
+  // ---- output transform, register-local: the lane holds all 16 points of filters 4kq+v, channel i16
+  float out[4][9];
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    float t[3][4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float m0 = acc[j][v], m1 = acc[4 + j][v], m2 = acc[8 + j][v], m3 = acc[12 + j][v];
+      t[0][j] = m0 + 0.5f * (m1 + m2);
+      t[1][j] = 0.5f * (m1 - m2);
+      t[2][j] = 0.5f * (m1 + m2) + m3;
+    }
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+      out[v][3 * r + 0] = t[r][0] + 0.5f * (t[r][1] + t[r][2]);
+      out[v][3 * r + 1] = 0.5f * (t[r][1] - t[r][2]);
+      out[v][3 * r + 2] = 0.5f * (t[r][1] + t[r][2]) + t[r][3];
+    }
+  }
+
+  // ---- every wavefront drops its 16 x 16 x 9 results into LDS at their place in the partial block's
+  // layout [tap tile][v][lane] (element (filter 4kq'+v, tap = channel * 9 + rs) sits at lane
+  // 16kq' + tap % 16 of tap tile tap / 16); then the whole workgroup adds the streams of each
+  // (filter tile, channel tile) pair in stream order and writes the block with 16-byte stores
+  constexpr int SUB = 9 * 256;                     // floats of one pair's part of a partial block
+  float *blk = lds;                                // [wavefront][SUB], over the wavefronts' rings
+  float *dbs = lds + 4 * kWaveFloats;              // [S][KT][16]
+  __syncthreads();                                 // every wavefront is done with its ring
+#pragma unroll
+  for (int v = 0; v < 4; ++v)
+#pragma unroll
+    for (int q = 0; q < 9; ++q) {
+      const int tap = i16 * 9 + q;
+      blk[wave * SUB + ((tap >> 4) * 4 + v) * 64 + kq * 16 + (tap & 15)] = out[v][q];
+    }
+  {
+    float s = dbsum;
+    s += __shfl_xor(s, 16, 64);
+    s += __shfl_xor(s, 32, 64);
+    if (kq == 0 && ctile == 0) dbs[(stream * KT + ktile) * 16 + i16] = s;
+  }
+  __syncthreads();
+  constexpr int BLK = KT * SUB;                    // the partial block of one channel chunk: [filter tile][tap tile][v][lane]
+  for (int f = tid; f < NC * (SUB / 4); f += kThreads) {
+    const int cb = f / (SUB / 4), within = f - cb * (SUB / 4);
+    float4 sum = *reinterpret_cast<const float4 *>(blk + cb * SUB + 4 * within);
+#pragma unroll
+    for (int s2 = 1; s2 < S; ++s2) {
+      const float4 o = *reinterpret_cast<const float4 *>(blk + (s2 * NC + cb) * SUB + 4 * within);
+      sum.x += o.x; sum.y += o.y; sum.z += o.z; sum.w += o.w;
+    }
+    const int kt = cb % KT, ct = cb / KT;
+    *reinterpret_cast<float4 *>(a.partial + (long)(ct * p.G + gidx) * BLK + kt * SUB + 4 * within) = sum;
+  }
+  if (tid < KT * 16) {
+    float s = dbs[tid];
+#pragma unroll
+    for (int s2 = 1; s2 < S; ++s2) s += dbs[s2 * KT * 16 + tid];
+    a.partial[p.db_offset + (long)gidx * a.K + tid] = s;
+  }
+}
+
+inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
+
+}  // namespace
+
+bool wgrad_wino_shape(int C, int H, int W, int K, int R, int S, int pad, int pool) {
+  return R == 3 && S == 3 && pad == 1 && pool == 2 && (C == 16 || C == 32) && (K == 16 || K == 32) && W % 8 == 0 && H % 2 == 0;
+}
+
+bool wgrad_wino_applies(const WgradArgs &a, const WgradPlan &plan) {
+  if (!wgrad_wino_shape(a.C, a.H, a.W, a.K, a.R, a.S, a.pad, a.pool)) return false;
+  if (a.act != ACT_RELU_FLAGGED || !a.idx || a.W >= (1 << 17)) return false;
+  if (plan.MTF * 16 != a.K || plan.NTT != 9 || plan.CC != 16 || plan.nchunks * 16 != a.C) return false;
+  if (!aligned16(a.x) || !aligned16(a.dy) || (reinterpret_cast<uintptr_t>(a.idx) & 3u)) return false;
+  const long limit = (1L << 31) - (1L << 24);
+  return 4L * a.N * a.C * a.H * a.W < limit && 4L * a.N * a.K * (a.H / 2) * (a.W / 2) < limit;
+}
+
+hipError_t launch_wgrad_wino(const WgradArgs &a, const WgradPlan &plan, hipStream_t stream) {
+  if (!wgrad_wino_applies(a, plan)) return hipErrorInvalidValue;
+  WinoWgradParams p;
+  p.a = a;
+  p.Hp = a.H / 2;
+  p.Wp = a.W / 2;
+  p.xsegs = (a.W + 31) / 32;
+  p.G = plan.G;
+  p.db_offset = (long)plan.db_offset;
+  p.x_bytes = (unsigned)(4L * a.N * a.C * a.H * a.W);
+  p.dy_bytes = (unsigned)(4L * a.N * a.K * p.Hp * p.Wp);
+  const int KT = a.K / 16, CT = a.C / 16, streams = 4 / (KT * CT);
+  p.xgroups = (p.xsegs + streams - 1) / streams;
+  // block rows per work item: long strips re-read fewer halo rows, short ones balance the workgroups;
+  // the first length that leaves every workgroup an item, else the shortest
+  p.rg = 2;
+  for (int rg = 8; rg >= 2; rg /= 2) {
+    const long items = (long)a.N * p.xgroups * ((p.Hp + rg - 1) / rg);
+    if (items >= p.G || rg == 2) { p.rg = rg; break; }
+  }
+  p.rgroups = (p.Hp + p.rg - 1) / p.rg;
+  const long items = (long)a.N * p.xgroups * p.rgroups;
+  if (items > 0x7fffffffL) return hipErrorInvalidValue;
+  p.items = (int)items;
+  const size_t lds = sizeof(float) * (4 * kWaveFloats + 4 * 2 * 16);
+  const dim3 grid((unsigned)p.G), block(kThreads);
+  if (KT == 1 && CT == 1) hipLaunchKernelGGL((wgrad_wino_kernel<1, 1>), grid, block, lds, stream, p);
+  else if (KT == 2 && CT == 1) hipLaunchKernelGGL((wgrad_wino_kernel<2, 1>), grid, block, lds, stream, p);
+  else if (KT == 1 && CT == 2) hipLaunchKernelGGL((wgrad_wino_kernel<1, 2>), grid, block, lds, stream, p);
+  else hipLaunchKernelGGL((wgrad_wino_kernel<2, 2>), grid, block, lds, stream, p);
+  return hipGetLastError();
+}
+
+}  // namespace dllk

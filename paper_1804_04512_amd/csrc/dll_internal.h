@@ -127,6 +127,12 @@ struct WgradPlan {
 };
 
 bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, int pool, WgradPlan *plan);
+// Padded 3x3 layers with 16 or 32 channels in and out behind ReLU + pooling, gradient and pooling bytes
+// alone (no layer output): the minimal-filtering form F(3x3, 2x2), same partial blocks as the direct
+// kernel.  launch_wgrad routes there by itself.
+bool wgrad_wino_shape(int C, int H, int W, int K, int R, int S, int pad, int pool);
+bool wgrad_wino_applies(const WgradArgs &a, const WgradPlan &plan);
+hipError_t launch_wgrad_wino(const WgradArgs &a, const WgradPlan &plan, hipStream_t stream);
 hipError_t launch_wgrad(const WgradArgs &a, const WgradPlan &plan, hipStream_t stream);
 
 // dw = scale * (sum(pos partials) - sum(neg partials)); optional in-place theta += step * dw.

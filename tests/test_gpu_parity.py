@@ -70,13 +70,18 @@ def check_trio(cs: ConvSpec, x, w, b, dy):
         idx_g = check_idx_bytes(raw_g, cs.act == "relu", y_g)
         check_pool_idx(idx_g, idx_o, pre, y_o)
         if cs.act == "relu":
-            # without the layer output the backward passes take act' from the flags: the very
-            # same decisions as y > 0 on the GPU's own y, hence bit-identical filter gradients; the
-            # data gradient may come from another kernel (the minimal-filtering form takes the
-            # flagged 16-channel layers) and then differs by rounding only
+            # without the layer output the backward passes take act' from the flags: the very same
+            # decisions as y > 0 on the GPU's own y.  Other kernels may take the flagged layers (the
+            # minimal-filtering forms of the data and filter gradients), so the results agree with the
+            # unflagged route's up to rounding, and they are checked against the oracle on their own:
+            # the oracle gets the GPU's decisions (positions, and a 0/1 output standing for the flags)
             _, _, dx_f, dw_f, db_f = gpu_trio(cs, x, w, b, dy, flagged=True)
-            assert np.array_equal(dw_f, dw_own) and np.array_equal(db_f, db_own)
+            assert max_rel_err(dw_f, dw_own) <= 5e-6 and max_rel_err(db_f, db_own) <= 5e-6
             assert max_rel_err(dx_f, dx_own) <= 2e-6
+            on = ((raw_g & 4) == 0).astype(np.float32)
+            assert max_rel_err(dx_f, orc.conv_full_bwd(d, dy, on, idx_g, w)) <= TOL_GRAD
+            dw_o2, db_o2 = orc.conv_valid_wgrad(d, x, dy, on, idx_g)
+            assert max_rel_err(dw_f, dw_o2) <= TOL_GRAD and max_rel_err(db_f, db_o2) <= TOL_GRAD
     # backward ops on identical inputs (the oracle's y and the GPU's own index decisions)
     use_idx = idx_g if cs.pool == 2 else None
     _, _, dx_g, dw_g, db_g = gpu_trio(cs, x, w, b, dy, y_in=y_o, idx_in=use_idx)
@@ -102,6 +107,9 @@ CASES = [
     ConvSpec(2, 16, 40, 64, 32, 3, 3, 1, "relu", 2),          # 16 -> 32 on whole 8 x 32 tiles: backward-data in two 16-channel chunks
     ConvSpec(25, 16, 64, 128, 16, 3, 3, 1, "relu", 2),        # 800 tiles of the minimal-filtering kernel: one whole round of 768 workgroups + a partial one
     ConvSpec(1, 32, 32, 32, 32, 3, 3, 1, "relu", 2),          # config-5 conv4 shape
+    ConvSpec(3, 32, 24, 40, 16, 3, 3, 1, "relu", 2),          # 32 -> 16: two channel tiles, one filter tile; a ragged second column segment
+    ConvSpec(5, 16, 36, 72, 32, 3, 3, 1, "relu", 2),          # 16 -> 32 on 18 block rows: row groups with a short last one, three column segments (the last 8 wide)
+    ConvSpec(2, 32, 20, 8, 32, 3, 3, 1, "relu", 2),           # 32 -> 32 on a map narrower than one column segment
     ConvSpec(2, 2, 9, 14, 3, 2, 4, 0, "identity", 1),         # non-square filter
     ConvSpec(2, 4, 11, 9, 6, 1, 1, 0, "relu", 1),             # 1x1 filter, odd map
     ConvSpec(1, 40, 20, 20, 1, 9, 9, 0, "identity", 1),       # single filter, deep contraction
@@ -205,10 +213,11 @@ def test_fwd_without_bias_and_shift_identity():
 def test_wgrad_is_bit_reproducible():
     cs = ConvSpec(4, 16, 40, 40, 16, 3, 3, 1, "relu", 2)
     x, w, b, dy = rand_layer(cs, 77)
-    a = gpu_trio(cs, x, w, b, dy)
-    c = gpu_trio(cs, x, w, b, dy)
-    np.testing.assert_array_equal(a[3], c[3])
-    np.testing.assert_array_equal(a[4], c[4])
+    for flagged in (False, True):   # the direct kernel, and the minimal-filtering one that takes the flagged layer
+        a = gpu_trio(cs, x, w, b, dy, flagged=flagged)
+        c = gpu_trio(cs, x, w, b, dy, flagged=flagged)
+        np.testing.assert_array_equal(a[3], c[3])
+        np.testing.assert_array_equal(a[4], c[4])
 
 
 # ---------------------------------------------------------------- CRBM CD-1
