@@ -701,6 +701,8 @@ dll_status run_cnn_step(const dll_net_desc *net, float *const *params, float *co
     if (st != DLL_OK) return st;
   }
   // ---- dense backward: data gradient first (old weights), then weight gradient + update
+  GemmArgs pending;
+  bool have_pending = false;
   for (int q = D - 1; q >= 0; --q) {
     const dll_dense_desc *dd = &net->dense[q];
     // dz[q] is dz of layer q: the loss kernel wrote it for the top layer, and each data-gradient
@@ -728,8 +730,19 @@ dll_status run_cnn_step(const dll_net_desc *net, float *const *params, float *co
       if (velocity) { h.vel = velocity[2 * (L + q)]; h.mu = mu; h.decay = decay; }
     }
     h.split_k = 1;
-    if (h.Cout || h.update)
-      if ((st = dev(launch_gemm(h, s))) != DLL_OK) return st;
+    // The weight-gradient product only has to be done before the step ends (nothing below reads the
+    // updated weights: every data gradient is taken with the old ones, just above).  It waits for
+    // the next layer's, and the two share a launch: the upper layers' products are too small to
+    // fill the chip on their own.
+    if (h.Cout || h.update) {
+      if (have_pending) {
+        if ((st = dev(launch_gemm_pair(h, pending, s))) != DLL_OK) return st;
+        have_pending = false;
+      } else {
+        pending = h;
+        have_pending = true;
+      }
+    }
     float *gb = grads ? grads[2 * (L + q) + 1] : nullptr;
     if (gb || upd) {
       if (tail.n_colsum == StepTail::kMaxColsum && (st = flush_tail()) != DLL_OK) return st;
@@ -737,6 +750,7 @@ dll_status run_cnn_step(const dll_net_desc *net, float *const *params, float *co
                                                       (upd && velocity) ? velocity[2 * (L + q) + 1] : nullptr, mu};
     }
   }
+  if (have_pending && (st = dev(launch_gemm(pending, s))) != DLL_OK) return st;
   // ---- convolution backward: filter-gradient partial sums, then the data gradient with the old filters;
   // the reduction of the partial sums and the filter update wait for the closing launch
   float *gcur = nb.gbuf[0], *gnext = nb.gbuf[1];

@@ -180,6 +180,8 @@ struct GemmArgs {
 };
 int gemm_pick_split_k(int M, int N, int Kdim);
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream);
+// Two products that do not depend on each other, in one launch where their forms allow it.
+hipError_t launch_gemm_pair(const GemmArgs &a, const GemmArgs &b, hipStream_t stream);
 // Small products (the dense layers of the MNIST/CIFAR-sized networks) take a kernel built for a
 // short latency chain instead: 32 x 32 tiles, the k range split between the wavefronts of a
 // workgroup, no split-K partials (gemm_pick_split_k returns 1 for them).  launch_gemm routes there.

@@ -385,6 +385,7 @@ struct UnitPos {
   int unit;        // index of the (m-tile, n-tile, split) unit, or >= units when the stream has ended
   int kt, nkt;     // k-tile inside the unit, number of k-tiles of the unit
   int m0, n0, kbeg, kend, z;
+  int second;      // pair launches: the unit belongs to the second product
 };
 
 // MODE fixes the epilogue at compile time (the launcher knows it), which keeps the code and the
@@ -393,26 +394,41 @@ struct UnitPos {
 //   1  fused parameter update, nothing else on the way (no bias, identity, no reference tensor);
 //      the parameter tile is prefetched during the unit's last k-tile
 //   2  everything else
-template <bool A_KC, bool B_KC, int MODE>
-__global__ __launch_bounds__(kThreads, 3) void gemm_fast_kernel(const GemmParams p) {
+// PAIR: one launch walks the units of TWO products of the same operand forms (p, then p2; both
+// without split-K): a product too small to fill the chip rides along with a large one instead of
+// paying for a launch of its own.
+template <bool A_KC, bool B_KC, int MODE, bool PAIR>
+__device__ __forceinline__ void gemm_fast_body(const GemmParams &p, const GemmParams &p2) {
   __shared__ __attribute__((aligned(16))) float As[2][FA_TILE];
   __shared__ __attribute__((aligned(16))) float Bs[2][FB_TILE];
-  const GemmArgs &a = p.a;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i16 = lane & 15, kq = lane >> 4;
   const int wm = (wave >> 1) * 64, wn = (wave & 1) * 32;
-  const int tiles_n = (a.N + BN - 1) / BN, tiles_m = (a.M + BM - 1) / BM;
-  const int units = tiles_m * tiles_n * a.split_k;
-  const unsigned a_sx = (unsigned)a.a_m, a_sk = (unsigned)a.a_k, b_sx = (unsigned)a.b_n, b_sk = (unsigned)a.b_k;
+  const int tiles_n = (p.a.N + BN - 1) / BN, tiles_m = (p.a.M + BM - 1) / BM;
+  const int units1 = tiles_m * tiles_n * p.a.split_k;
+  const int tiles_n2 = PAIR ? (p2.a.N + BN - 1) / BN : 1;
+  const int units = PAIR ? units1 + ((p2.a.M + BM - 1) / BM) * tiles_n2 : units1;
+  auto args_of = [&](const UnitPos &u) __attribute__((always_inline)) -> const GemmArgs & { return (PAIR && u.second) ? p2.a : p.a; };
 
   auto locate = [&](UnitPos &u) __attribute__((always_inline)) {   // fills the fields that follow from u.unit
     if (u.unit >= units) return;
-    const int tile = u.unit / a.split_k;
-    u.z = u.unit - tile * a.split_k;
-    u.m0 = (tile / tiles_n) * BM;
-    u.n0 = (tile % tiles_n) * BN;
-    u.kbeg = u.z * p.k_per_split;
-    u.kend = min(a.Kdim, u.kbeg + p.k_per_split);
+    if (PAIR && u.unit >= units1) {
+      const int tile = u.unit - units1;
+      u.second = 1;
+      u.z = 0;
+      u.m0 = (tile / tiles_n2) * BM;
+      u.n0 = (tile % tiles_n2) * BN;
+      u.kbeg = 0;
+      u.kend = p2.a.Kdim;
+    } else {
+      const int tile = u.unit / p.a.split_k;
+      u.second = 0;
+      u.z = u.unit - tile * p.a.split_k;
+      u.m0 = (tile / tiles_n) * BM;
+      u.n0 = (tile % tiles_n) * BN;
+      u.kbeg = u.z * p.k_per_split;
+      u.kend = min(p.a.Kdim, u.kbeg + p.k_per_split);
+    }
     u.nkt = max(1, (u.kend - u.kbeg + BK - 1) / BK);   // an empty split still writes its zero partial
     u.kt = 0;
   };
@@ -422,14 +438,21 @@ __global__ __launch_bounds__(kThreads, 3) void gemm_fast_kernel(const GemmParams
     locate(u);
   };
 
-  // per-slot byte offsets inside a tile (constant for the whole kernel)
+  // per-slot byte offsets inside a tile (constant for a product; a pair launch works them out again
+  // when its loading position crosses into the second product, once per workgroup)
   unsigned sa[SlotGeom<BM, A_KC>::NV], sb[SlotGeom<BN, B_KC>::NV];
+  unsigned a_sx, a_sk, b_sx, b_sk;
+  int slots_of = 0;
+  auto slot_offsets = [&](const GemmArgs &a) __attribute__((always_inline)) {
+    a_sx = (unsigned)a.a_m; a_sk = (unsigned)a.a_k; b_sx = (unsigned)a.b_n; b_sk = (unsigned)a.b_k;
 #pragma unroll
-  for (int it = 0; it < SlotGeom<BM, A_KC>::NV; ++it)
-    sa[it] = 4u * ((unsigned)SlotGeom<BM, A_KC>::xl(tid, it) * a_sx + (unsigned)SlotGeom<BM, A_KC>::kl(tid, it) * a_sk);
+    for (int it = 0; it < SlotGeom<BM, A_KC>::NV; ++it)
+      sa[it] = 4u * ((unsigned)SlotGeom<BM, A_KC>::xl(tid, it) * a_sx + (unsigned)SlotGeom<BM, A_KC>::kl(tid, it) * a_sk);
 #pragma unroll
-  for (int it = 0; it < SlotGeom<BN, B_KC>::NV; ++it)
-    sb[it] = 4u * ((unsigned)SlotGeom<BN, B_KC>::xl(tid, it) * b_sx + (unsigned)SlotGeom<BN, B_KC>::kl(tid, it) * b_sk);
+    for (int it = 0; it < SlotGeom<BN, B_KC>::NV; ++it)
+      sb[it] = 4u * ((unsigned)SlotGeom<BN, B_KC>::xl(tid, it) * b_sx + (unsigned)SlotGeom<BN, B_KC>::kl(tid, it) * b_sk);
+  };
+  slot_offsets(p.a);
 
   int la[SlotGeom<BM, A_KC>::NV], lb[SlotGeom<BN, B_KC>::NV];   // LDS offsets of the thread's slots
 #pragma unroll
@@ -441,6 +464,8 @@ __global__ __launch_bounds__(kThreads, 3) void gemm_fast_kernel(const GemmParams
   TileRegs<BN> tb[2];
   auto load_tiles = [&](auto setc, const UnitPos &u) __attribute__((always_inline)) {
     constexpr int S_ = decltype(setc)::value;
+    const GemmArgs &a = args_of(u);
+    if (PAIR && u.second != slots_of) { slot_offsets(a); slots_of = u.second; }
     const int k0 = u.kbeg + u.kt * BK;
     fast_tile_load<BM, A_KC>(ta[S_], a.A, sa, a_sx, a_sk, u.m0, k0, a.M, u.kend);
     fast_tile_load<BN, B_KC>(tb[S_], a.B, sb, b_sx, b_sk, u.n0, k0, a.N, u.kend);
@@ -506,6 +531,7 @@ __global__ __launch_bounds__(kThreads, 3) void gemm_fast_kernel(const GemmParams
   constexpr bool upd_mode = MODE == 1;
   float4 upd[4][2];
   auto prefetch_update = [&](const UnitPos &u) __attribute__((always_inline)) {
+    const GemmArgs &a = args_of(u);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -518,6 +544,7 @@ __global__ __launch_bounds__(kThreads, 3) void gemm_fast_kernel(const GemmParams
 
   // lane holds C(m = i16, n = 4*kq + v) of each 16x16 tile
   auto epilogue = [&](const UnitPos &u) __attribute__((always_inline)) {
+    const GemmArgs &a = args_of(u);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int m = u.m0 + wm + i * 16 + i16;
@@ -654,6 +681,15 @@ __global__ __launch_bounds__(kThreads, 3) void gemm_fast_kernel(const GemmParams
     if (!step(S0{})) break;
     if (!step(S1{})) break;
   }
+}
+
+template <bool A_KC, bool B_KC, int MODE>
+__global__ __launch_bounds__(kThreads, 3) void gemm_fast_kernel(const GemmParams p) {
+  gemm_fast_body<A_KC, B_KC, MODE, false>(p, p);
+}
+template <bool A_KC, bool B_KC>
+__global__ __launch_bounds__(kThreads, 3) void gemm_fast_pair_kernel(const GemmParams p, const GemmParams p2) {
+  gemm_fast_body<A_KC, B_KC, 1, true>(p, p2);
 }
 
 __global__ __launch_bounds__(kThreads) void gemm_splitk_reduce_kernel(const GemmArgs a) {
@@ -853,10 +889,20 @@ int gemm_pick_split_k(int M, int N, int Kdim) {
   return split;
 }
 
-hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream) {
-  if (a.split_k <= 1 && gemm_is_small(a.M, a.N, a.Kdim)) return launch_gemm_small(a, stream);
-  if (a.sm_labels) return hipErrorInvalidValue;   // the fused loss exists in the small-product kernel only
+namespace {
+
+// What launch_gemm works out of a product before it picks a kernel.
+struct GemmPlan {
   GemmParams p;
+  dim3 grid;          // tiles along n, tiles along m, k splits
+  bool a_kc, b_kc;    // operand is contiguous along k
+  bool fast;          // the persistent vector kernel applies
+  int mode;           // its epilogue form (see gemm_fast_body)
+};
+
+GemmPlan plan_gemm(const GemmArgs &a) {
+  GemmPlan g;
+  GemmParams &p = g.p;
   p.a = a;
   if (p.a.split_k < 1) p.a.split_k = 1;
   const int ksteps = (a.Kdim + BK - 1) / BK;
@@ -866,39 +912,51 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream) {
   p.a_vec = al16(a.A) && ((a.a_k == 1 ? a.a_m : a.a_k) % 4 == 0) && (a.a_k == 1 || a.a_m == 1);
   p.b_vec = al16(a.B) && ((a.b_k == 1 ? a.b_n : a.b_k) % 4 == 0) && (a.b_k == 1 || a.b_n == 1);
   p.c_vec = a.c_n == 1 && a.c_m % 4 == 0 && (!a.Cout || al16(a.Cout)) && (!a.update || al16(a.update)) && (!a.vel || al16(a.vel));
-  dim3 grid((a.N + BN - 1) / BN, (a.M + BM - 1) / BM, p.a.split_k);
+  g.grid = dim3((a.N + BN - 1) / BN, (a.M + BM - 1) / BM, p.a.split_k);
   // whole 16-byte groups along each operand's contiguous axis, the k ranges of the splits start
   // on multiples of 32, and every operand element lies within 4 GiB of its base (32-bit byte
   // offsets): then the persistent vector kernel runs, else the generic one
-  const bool a_kc = a.a_k == 1, b_kc = a.b_k == 1;
+  g.a_kc = a.a_k == 1;
+  g.b_kc = a.b_k == 1;
   const auto extent = [](long n0, long s0, long n1, long s1) { return 4 * ((n0 - 1) * s0 + (n1 - 1) * s1 + 4); };
   const bool small = extent(a.M, a.a_m, a.Kdim, a.a_k) < (1L << 32) && extent(a.N, a.b_n, a.Kdim, a.b_k) < (1L << 32) &&
                      extent(a.M, a.c_m, a.N, a.c_n) < (1L << 32) && a.a_m >= 0 && a.a_k >= 0 && a.b_n >= 0 && a.b_k >= 0 &&
                      a.c_m >= 0 && a.c_n >= 0;
-  const bool fast = small && p.a_vec && p.b_vec && (a_kc ? a.Kdim % 4 == 0 : a.M % 4 == 0) &&
-                    (b_kc ? a.Kdim % 4 == 0 : a.N % 4 == 0);
-  if (!fast) {
-    hipLaunchKernelGGL(gemm_kernel, grid, dim3(kThreads), 0, stream, p);
+  g.fast = small && p.a_vec && p.b_vec && (g.a_kc ? a.Kdim % 4 == 0 : a.M % 4 == 0) && (g.b_kc ? a.Kdim % 4 == 0 : a.N % 4 == 0);
+  g.mode = p.a.split_k > 1 ? 0 : ((a.update && p.c_vec && !a.bias && a.act == ACT_IDENTITY && !a.C_ref) ? 1 : 2);
+  return g;
+}
+
+}  // namespace
+
+hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream) {
+  if (a.split_k <= 1 && gemm_is_small(a.M, a.N, a.Kdim)) return launch_gemm_small(a, stream);
+  if (a.sm_labels) return hipErrorInvalidValue;   // the fused loss exists in the small-product kernel only
+  const GemmPlan g = plan_gemm(a);
+  const GemmParams &p = g.p;
+  if (!g.fast) {
+    hipLaunchKernelGGL(gemm_kernel, g.grid, dim3(kThreads), 0, stream, p);
   } else {
-    const long units = (long)grid.x * grid.y * grid.z;
+    const long units = (long)g.grid.x * g.grid.y * g.grid.z;
     const long resident = 3L * chip().cus;   // three resident workgroups per CU
     const dim3 pgrid((unsigned)(units < resident ? units : resident));
-    const int mode = p.a.split_k > 1 ? 0 : ((a.update && p.c_vec && !a.bias && a.act == ACT_IDENTITY && !a.C_ref) ? 1 : 2);
+    const int mode = g.mode;
 #define DLL_GEMM_LAUNCH(AK, BK_)                                                                                      \
   do {                                                                                                                 \
     if (mode == 0) hipLaunchKernelGGL((gemm_fast_kernel<AK, BK_, 0>), pgrid, dim3(kThreads), 0, stream, p);           \
     else if (mode == 1) hipLaunchKernelGGL((gemm_fast_kernel<AK, BK_, 1>), pgrid, dim3(kThreads), 0, stream, p);      \
     else hipLaunchKernelGGL((gemm_fast_kernel<AK, BK_, 2>), pgrid, dim3(kThreads), 0, stream, p);                     \
   } while (0)
-    if (a_kc && b_kc) DLL_GEMM_LAUNCH(true, true);
-    else if (a_kc && !b_kc) DLL_GEMM_LAUNCH(true, false);
-    else if (!a_kc && b_kc) DLL_GEMM_LAUNCH(false, true);
+    if (g.a_kc && g.b_kc) DLL_GEMM_LAUNCH(true, true);
+    else if (g.a_kc && !g.b_kc) DLL_GEMM_LAUNCH(true, false);
+    else if (!g.a_kc && g.b_kc) DLL_GEMM_LAUNCH(false, true);
     else DLL_GEMM_LAUNCH(false, false);
 #undef DLL_GEMM_LAUNCH
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (p.a.split_k > 1 && !a.defer_reduce) {
+    auto al16 = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
     const long total = (long)a.M * a.N;
     const bool vec = a.N % 4 == 0 && a.c_n == 1 && a.c_m % 4 == 0 && al16(a.partial) && (!a.Cout || al16(a.Cout));
     long blocks = ((vec ? total / 4 : total) + kThreads - 1) / kThreads;
@@ -908,6 +966,29 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream) {
     e = hipGetLastError();
   }
   return e;
+}
+
+// Two independent products in one launch (the weight-gradient products of two dense layers: both
+// update their parameters in place, neither reads what the other writes).  Where both take the
+// persistent kernel's fused-update form with the same operand forms, the units of the second are
+// appended to the first's; else they are launched one after the other.
+hipError_t launch_gemm_pair(const GemmArgs &a, const GemmArgs &b, hipStream_t stream) {
+  const bool a_small = a.split_k <= 1 && gemm_is_small(a.M, a.N, a.Kdim), b_small = b.split_k <= 1 && gemm_is_small(b.M, b.N, b.Kdim);
+  if (!a_small && !b_small && !a.sm_labels && !b.sm_labels && a.split_k <= 1 && b.split_k <= 1) {
+    const GemmPlan ga = plan_gemm(a), gb = plan_gemm(b);
+    if (ga.fast && gb.fast && ga.mode == 1 && gb.mode == 1 && ga.a_kc == gb.a_kc && ga.b_kc == gb.b_kc) {
+      const long units = (long)ga.grid.x * ga.grid.y + (long)gb.grid.x * gb.grid.y;
+      const long resident = 3L * chip().cus;
+      const dim3 pgrid((unsigned)(units < resident ? units : resident));
+      if (ga.a_kc && ga.b_kc) hipLaunchKernelGGL((gemm_fast_pair_kernel<true, true>), pgrid, dim3(kThreads), 0, stream, ga.p, gb.p);
+      else if (ga.a_kc) hipLaunchKernelGGL((gemm_fast_pair_kernel<true, false>), pgrid, dim3(kThreads), 0, stream, ga.p, gb.p);
+      else if (ga.b_kc) hipLaunchKernelGGL((gemm_fast_pair_kernel<false, true>), pgrid, dim3(kThreads), 0, stream, ga.p, gb.p);
+      else hipLaunchKernelGGL((gemm_fast_pair_kernel<false, false>), pgrid, dim3(kThreads), 0, stream, ga.p, gb.p);
+      return hipGetLastError();
+    }
+  }
+  const hipError_t e = launch_gemm(a, stream);
+  return e != hipSuccess ? e : launch_gemm(b, stream);
 }
 
 hipError_t launch_colsum(const float *A, int M, int N, float *out, float *update, float step, float *vel, float mu,
