@@ -724,6 +724,8 @@ bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, int po
   // layers the minimal-filtering kernel can take: its registers leave two workgroups per compute unit,
   // and every one of them should be resident from the start (the direct kernel copes with any G)
   if (wgrad_wino_shape(C, H, W, K, R, S, pad, pool) && mtf * 16 == K && best_cc == 16) G = 2 * cus < items ? 2 * cus : items;
+  // the first-layer kernel keeps four workgroups per compute unit resident
+  if (wgrad_fewch_shape(C, H, W, K, R, S, pad, pool) && mtf == 1 && best_ntt == 2 && best_cc == C) G = 4 * cus < items ? 4 * cus : items;
   if (G < 1) G = 1;
   plan->G = (int)G;
   plan->n_partials = plan->G;
@@ -771,6 +773,7 @@ inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 
 
 hipError_t launch_wgrad(const WgradArgs &a, const WgradPlan &plan, hipStream_t stream) {
   if (wgrad_wino_applies(a, plan)) return launch_wgrad_wino(a, plan, stream);
+  if (wgrad_fewch_applies(a, plan)) return launch_wgrad_fewch(a, plan, stream);
   WgradParams p;
   p.a = a;
   p.Ho = a.H + 2 * a.pad - a.R + 1;

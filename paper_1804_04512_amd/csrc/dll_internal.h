@@ -133,6 +133,12 @@ bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, int po
 bool wgrad_wino_shape(int C, int H, int W, int K, int R, int S, int pad, int pool);
 bool wgrad_wino_applies(const WgradArgs &a, const WgradPlan &plan);
 hipError_t launch_wgrad_wino(const WgradArgs &a, const WgradPlan &plan, hipStream_t stream);
+// Padded 3x3 layers with one to three input channels and at most 16 filters behind ReLU + pooling
+// (the first layer of the image networks), gradient and pooling bytes alone: the filter-side operand
+// is formed in registers from the pooled tensors.  Same partial blocks; launch_wgrad routes there.
+bool wgrad_fewch_shape(int C, int H, int W, int K, int R, int S, int pad, int pool);
+bool wgrad_fewch_applies(const WgradArgs &a, const WgradPlan &plan);
+hipError_t launch_wgrad_fewch(const WgradArgs &a, const WgradPlan &plan, hipStream_t stream);
 hipError_t launch_wgrad(const WgradArgs &a, const WgradPlan &plan, hipStream_t stream);
 
 // dw = scale * (sum(pos partials) - sum(neg partials)); optional in-place theta += step * dw.

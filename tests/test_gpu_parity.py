@@ -110,6 +110,11 @@ CASES = [
     ConvSpec(3, 32, 24, 40, 16, 3, 3, 1, "relu", 2),          # 32 -> 16: two channel tiles, one filter tile; a ragged second column segment
     ConvSpec(5, 16, 36, 72, 32, 3, 3, 1, "relu", 2),          # 16 -> 32 on 18 block rows: row groups with a short last one, three column segments (the last 8 wide)
     ConvSpec(2, 32, 20, 8, 32, 3, 3, 1, "relu", 2),           # 32 -> 32 on a map narrower than one column segment
+    # first layers of image networks (one to three channels in, at most 16 filters): the filter gradient forms dz in registers
+    ConvSpec(3, 3, 24, 72, 16, 3, 3, 1, "relu", 2),           # RGB, a whole 64-pixel strip and a ragged one of 8 pixels
+    ConvSpec(2, 3, 36, 328, 16, 3, 3, 1, "relu", 2),          # six strips: two groups of four, the second with two strips sitting out; 18 window rows
+    ConvSpec(2, 1, 20, 64, 8, 3, 3, 1, "relu", 2),            # grey-scale, eight filters: tap columns 9.. and filters 8.. are padding
+    ConvSpec(1, 2, 10, 8, 5, 3, 3, 1, "relu", 2),             # far below one strip
     ConvSpec(2, 2, 9, 14, 3, 2, 4, 0, "identity", 1),         # non-square filter
     ConvSpec(2, 4, 11, 9, 6, 1, 1, 0, "relu", 1),             # 1x1 filter, odd map
     ConvSpec(1, 40, 20, 20, 1, 9, 9, 0, "identity", 1),       # single filter, deep contraction
