@@ -79,6 +79,8 @@ def engine_kernel_name(cs, backward: bool) -> str:
     (mirrors the dispatch in csrc/conv_engine.hip; used only to group launches for the report)."""
     cin, kout, hout = (cs.K, cs.C, cs.H) if backward else (cs.C, cs.K, cs.Ho)
     same = cs.R == 3 and cs.S == 3 and cs.pad == 1
+    if same and not backward and cs.C <= 3 and cs.K <= 16 and cs.act == "relu" and cs.pool == 2 and cs.W % 8 == 0:
+        return "conv_fwd_fewch_kernel"   # first layer of the image networks
     # layers with 16 or 32 channels in and out, ReLU + pooling, on whole 8 x 32 tiles: the minimal-filtering kernel
     # (forward, and backward-data from the pooled gradient with the ReLU flags, as the step calls it)
     if same and cs.C == 32 and cs.K == 32 and cs.act == "relu" and cs.pool == 2 and cs.Ho % 8 == 0 and cs.Wo % 32 == 0:
@@ -202,7 +204,7 @@ def chip_probe():
 MEASURED_TRAFFIC_BYTES = {
     # conv1's filter gradient: x (100.7 MB) + pooled gradient (134.2 MB) + pooling bytes (33.6 MB) in, partial sums out
     ("c5_large_image_cnn", 128, "wgrad_fewch_kernel + wgrad_reduce_kernel"): (266605.6 + 3696.0) * 1024,
-    ("c5_large_image_cnn", 128, "conv3x3c16_kernel<1,4,0,4,true,1>"): (99047.4 + 169396.2) * 1024,
+    ("c5_large_image_cnn", 128, "conv_fwd_fewch_kernel"): (99047.4 + 169396.2) * 1024,
 }
 
 

@@ -83,6 +83,10 @@ hipError_t launch_conv_engine(const ConvEngineArgs &a, hipStream_t stream);
 // gradient with the ReLU flags in the pooling bytes.  launch_conv_engine routes there by itself.
 bool conv_wino_applies(const ConvEngineArgs &a);
 hipError_t launch_conv_wino(const ConvEngineArgs &a, hipStream_t stream);
+// Forward pass of a padded 3x3 layer with one to three input channels and at most 16 filters, ReLU +
+// pooling (the first layer of the image networks); launch_conv_engine routes there by itself.
+bool conv_fwd_fewch_applies(const ConvEngineArgs &a);
+hipError_t launch_conv_fwd_fewch(const ConvEngineArgs &a, hipStream_t stream);
 bool conv_fewout_applies(const ConvEngineArgs &a);
 hipError_t launch_conv_fewout(const ConvEngineArgs &a, hipStream_t stream);
 
