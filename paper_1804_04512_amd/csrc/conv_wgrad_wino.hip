@@ -57,7 +57,8 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_wino_kernel(const WinoWgrad
   constexpr int NC = KT * CT, S = 4 / NC;
   extern __shared__ float lds[];
   const WgradArgs &a = p.a;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // the same in every lane: said so, it lives in scalar registers
   const int i16 = lane & 15, kq = lane >> 4;
   const int combo = wave % NC, stream = wave / NC;
   const int ktile = combo % KT, ctile = combo / KT;
@@ -96,8 +97,8 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_wino_kernel(const WinoWgrad
 
   float4 xa[kXR], xb[kXR];   // two pairs of rows on their way from memory to LDS
   float ha = 0.0f, hb = 0.0f;
-  float4 dyc = make_float4(0.f, 0.f, 0.f, 0.f), dyn = dyc;
-  unsigned idc = 0, idn = 0;
+  float4 dyc = make_float4(0.f, 0.f, 0.f, 0.f), dya = dyc, dyb = dyc;   // gradients: in use / on their way with xa / xb
+  unsigned idc = 0, ida = 0, idb = 0;
   unsigned xv[kXR], hv = kOob, dv = kOob, iv = kOob;   // per-item byte offsets of the lane's slots
 
   // per item: where the lane's slots of the item's first pair (rows 2*by0-1, 2*by0) and first block row lie
@@ -143,17 +144,19 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_wino_kernel(const WinoWgrad
     dst[hlo] = xh;
   };
   // pooled gradients and pooling bytes of block row by0 + dB: the lane's filter, blocks bx0 + 4kq .. + 3
-  auto load_dy = [&](int dB, float4 &g, unsigned &f) {
-    const floatx4 v = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rs_dy, (int)dv, (int)(4u * (unsigned)p.Wp * (unsigned)dB), 0));
+  // (`none`: no such block row - the loads are issued all the same, out of range, and return zeros)
+  auto load_dy = [&](int dB, bool none, float4 &g, unsigned &f) {
+    const unsigned od = none ? kOob : dv, oi = none ? kOob : iv;
+    const floatx4 v = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rs_dy, (int)od, (int)(4u * (unsigned)p.Wp * (unsigned)dB), 0));
     g = make_float4(v[0], v[1], v[2], v[3]);
-    f = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(rs_idx, (int)iv, (int)((unsigned)p.Wp * (unsigned)dB), 0);
+    f = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(rs_idx, (int)oi, (int)((unsigned)p.Wp * (unsigned)dB), 0);
   };
 
-  // one block row: four groups of four blocks; `spc` = parity of the block row = which row slots hold
-  // rows 2by-1, 2by (pair by) and 2by+1, 2by+2 (pair by+1)
+  // one block row: four groups of four blocks; `sp` = parity of the block row inside its item = which
+  // row slots hold its upper pair of rows (the lower pair sits in the other two)
   const float *patch = xs + i16 * kPS + 8 * kq;
-  auto block_row = [&](auto spc) {
-    constexpr int SP = decltype(spc)::value;
+  auto block_row = [&](int sp) {
+    const float *pup = patch + sp * 2 * kRS, *pdn = patch + (sp ^ 1) * 2 * kRS;
     const float gv[4] = {dyc.x, dyc.y, dyc.z, dyc.w};
     // x patch of the lane's block of group g (rows 2by-1 .. 2by+2, columns 2bx-1 .. 2bx+2); the reads
     // of group g+1 are issued before the products of group g
@@ -162,9 +165,9 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_wino_kernel(const WinoWgrad
       constexpr int g = decltype(gc)::value;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const int slot = i < 2 ? 2 * SP + i : 2 * (SP ^ 1) + (i - 2);
-        pl[g & 1][i] = *reinterpret_cast<const float2 *>(patch + slot * kRS + 2 * g);
-        ph[g & 1][i] = *reinterpret_cast<const float2 *>(patch + slot * kRS + 2 * g + 2);
+        const float *row = i < 2 ? pup + i * kRS : pdn + (i - 2) * kRS;
+        pl[g & 1][i] = *reinterpret_cast<const float2 *>(row + 2 * g);
+        ph[g & 1][i] = *reinterpret_cast<const float2 *>(row + 2 * g + 2);
       }
     };
     auto group = [&](auto gc) {
@@ -211,51 +214,81 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_wino_kernel(const WinoWgrad
   // ---- work items: (image, group of block rows, group of S neighbouring column segments), one segment
   // per stream, so that the wavefronts of a workgroup read neighbouring pieces of the same image
   // rows at about the same time; each stream walks its segment downwards.  A stream whose segment
-  // lies beyond the row (the last group of a row that is not a multiple of S segments wide) sits the
-  // item out.  The two pairs of rows and the gradients that an item starts with are requested during
-  // the last block row of the item before it, so a stream waits for memory only once, at its start.
-  auto begin_item = [&](int item, int &by1) {
+  // lies beyond the row (the last group of a row that is not a multiple of S segments wide) skips
+  // the item.
+  //
+  // The stream's work is one sequence of PACKETS: packet q of an item of n block rows (q = 0 .. n)
+  // is the pair of image rows 2(by0+q)-1, 2(by0+q) together with the gradients of block row q-1
+  // (none for q = 0).  Packets travel through two register sets in turn (xa/ha/dya/ida, xb/hb/dyb/idb)
+  // and are requested TWO packets ahead of their use, straight across item boundaries: handling a
+  // packet means moving its rows into the ring (pair q into row slots 2(q&1), 2(q&1)+1), taking its
+  // gradients, asking for the packet after next into the set just emptied, and (q >= 1) multiplying
+  // block row q-1, whose other pair of rows the packet before brought.  Every packet issues the same
+  // seven loads on every path (when the items have run out, or for the gradients of q = 0, from
+  // out-of-range offsets), so the number of loads issued after any given one is known at compile time
+  // and the wait before a set is used leaves the other set's loads in flight.
+  auto take = [](auto &d, auto v) { asm volatile("v_mov_b32 %0, %1" : "=v"(d) : "v"(v)); };
+  auto rows_of = [&](int item, int &n_img, int &xseg, int &by0) -> int {
     const int xg = item % p.xgroups;
     const int rgrp = (item / p.xgroups) % p.rgroups;
-    const int n = item / (p.xgroups * p.rgroups);
-    const int xseg = xg * S + stream;
-    const int by0 = rgrp * p.rg;
-    item_setup(n, xseg * 32, xseg * 16, by0);      // a segment beyond the row gets out-of-range offsets only
-    by1 = xseg < p.xsegs ? min(by0 + p.rg, p.Hp) : by0;
-    return by0;
+    n_img = item / (p.xgroups * p.rgroups);
+    xseg = xg * S + stream;
+    by0 = rgrp * p.rg;
+    return xseg < p.xsegs ? min(by0 + p.rg, p.Hp) - by0 : 0;
   };
-  auto request_item = [&](int item) {
-    int by1;
-    const int by0 = begin_item(item, by1);
-    if (by1 > by0) {
-      load_pair(by0, 0, xa, ha);
-      load_pair(by0 + 1, 1, xb, hb);
-      load_dy(0, dyn, idn);
+  // request cursor: packet (r_item, r_q) is the next to ask for; consume cursor: (c_item, c_q) the next to handle
+  int r_item = gidx - p.G, r_q = 0, r_n = -1, r_by0 = 0;
+  auto next_request_item = [&]() {
+    int n_img = 0, xseg = 0;
+    r_n = 0;
+    for (r_item += p.G; r_item < p.items; r_item += p.G)
+      if ((r_n = rows_of(r_item, n_img, xseg, r_by0)) > 0) break;
+    r_q = 0;
+    if (r_item < p.items) {
+      item_setup(n_img, xseg * 32, xseg * 16, r_by0);
+    } else {                                      // nothing left: every further request reads zeros
+#pragma unroll
+      for (int it = 0; it < kXR; ++it) xv[it] = kOob;
+      hv = dv = iv = kOob;
+      r_by0 = 0;
     }
   };
-  if (gidx < p.items) request_item(gidx);
-  for (int item = gidx; item < p.items; item += p.G) {
-    int by1;
-    const int by0 = begin_item(item, by1);
-    dyc = dyn;
-    idc = idn;
-    if (by1 > by0) store_pair(by0 & 1, xa, ha);
-    for (int by = by0; by < by1; ++by) {
-      // rows 2by+1, 2by+2, requested during the previous block row (or with the item's first pair)
-      if (by == by0) store_pair((by + 1) & 1, xb, hb);
-      else store_pair((by + 1) & 1, xa, ha);
-      if (by + 1 < by1) {
-        load_pair(by + 2, by + 2 - by0, xa, ha);    // in flight during this block row's products
-        load_dy(by + 1 - by0, dyn, idn);
-      } else if (item + p.G < p.items) {
-        request_item(item + p.G);
-      }
-      if (by & 1) block_row(std::integral_constant<int, 1>{});
-      else block_row(std::integral_constant<int, 0>{});
-      dyc = dyn;
-      idc = idn;
-    }
-    if (by1 == by0 && item + p.G < p.items) request_item(item + p.G);   // sat this one out: still ask for the next
+  auto request = [&](float4 (&xr)[kXR], float &xh, float4 &g, unsigned &f) {
+    load_pair(r_by0 + r_q, r_q, xr, xh);
+    load_dy(r_q > 0 ? r_q - 1 : 0, r_q == 0, g, f);
+    if (++r_q > r_n) next_request_item();
+  };
+  int c_item = gidx - p.G, c_q = 0, c_n = -1;
+  auto next_consume_item = [&]() {
+    int n_img, xseg, by0;
+    c_n = 0;
+    for (c_item += p.G; c_item < p.items; c_item += p.G)
+      if ((c_n = rows_of(c_item, n_img, xseg, by0)) > 0) break;
+    c_q = 0;
+  };
+  // (a packet handled after the stream's last item is an empty one: the loop below leaves only after
+  // whole rounds of both register sets, so that no path leads from one set's packet straight to the
+  // same set's next - the compiler would have to assume the loads just issued are the ones awaited)
+  auto handle = [&](float4 (&xr)[kXR], float &xh, float4 &g, unsigned &f) {
+    const bool live = c_item < p.items;
+    store_pair(c_q & 1, xr, xh);
+    // real moves, here, where the packet has arrived: left to itself the compiler keeps the gradients
+    // where they were loaded and moves the NEXT packet's into place at the end of the loop body
+    // instead, which waits for loads that were only just issued
+    take(dyc.x, g.x); take(dyc.y, g.y); take(dyc.z, g.z); take(dyc.w, g.w);
+    take(idc, f);
+    request(xr, xh, g, f);
+    if (live && c_q > 0) block_row((c_q - 1) & 1);
+    if (live && ++c_q > c_n) next_consume_item();
+  };
+
+  next_request_item();
+  next_consume_item();
+  request(xa, ha, dya, ida);
+  request(xb, hb, dyb, idb);
+  while (c_item < p.items) {
+    handle(xa, ha, dya, ida);
+    handle(xb, hb, dyb, idb);
   }
 
   // ---- output transform, register-local: the lane holds all 16 points of filters 4kq+v, channel i16
