@@ -193,15 +193,25 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_wino_kernel(const WinoWgrad
         t[2][j] = d2 - d1;
         t[3][j] = d1 - d3;
       }
+      // all 32 operands first, then the 16 products back to back: a switch between the vector and the
+      // matrix instruction streams costs about eight cycles each time (a loop of MFMAs with V vector
+      // instructions between every two takes 33 + 8 + 4V cycles per MFMA, the same work in blocks of
+      // 16 takes 33 + 4V), and left to itself the compiler alternates them
+      float U[16], V[16];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float V0 = t[i][0] - t[i][2], V1 = t[i][1] + t[i][2], V2 = t[i][2] - t[i][1], V3 = t[i][1] - t[i][3];
-        const float U0 = pb ? 0.0f : R[i], U1 = R[i], U2 = pb ? -R[i] : R[i], U3 = pb ? -R[i] : 0.0f;
-        acc[4 * i + 0] = __builtin_amdgcn_mfma_f32_16x16x4f32(U0, V0, acc[4 * i + 0], 0, 0, 0);
-        acc[4 * i + 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(U1, V1, acc[4 * i + 1], 0, 0, 0);
-        acc[4 * i + 2] = __builtin_amdgcn_mfma_f32_16x16x4f32(U2, V2, acc[4 * i + 2], 0, 0, 0);
-        acc[4 * i + 3] = __builtin_amdgcn_mfma_f32_16x16x4f32(U3, V3, acc[4 * i + 3], 0, 0, 0);
+        V[4 * i + 0] = t[i][0] - t[i][2];
+        V[4 * i + 1] = t[i][1] + t[i][2];
+        V[4 * i + 2] = t[i][2] - t[i][1];
+        V[4 * i + 3] = t[i][1] - t[i][3];
+        U[4 * i + 0] = pb ? 0.0f : R[i];
+        U[4 * i + 1] = R[i];
+        U[4 * i + 2] = pb ? -R[i] : R[i];
+        U[4 * i + 3] = pb ? -R[i] : 0.0f;
       }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(U[q], V[q], acc[q], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     };
     read_patch(std::integral_constant<int, 0>{});
