@@ -12,7 +12,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdll_conv.so")
-SOURCES = ["conv_engine.hip", "conv_fewout.hip", "conv_fwd_fewch.hip", "conv_fft.hip", "conv_wino.hip", "conv_wgrad.hip", "conv_wgrad_wino.hip", "conv_wgrad_fewch.hip", "gemm.hip", "gemm_small.hip", "rbm.hip", "api.hip"]
+SOURCES = ["conv_engine.hip", "conv_fewout.hip", "conv_fwd_fewch.hip", "conv_fft.hip", "conv_wino.hip", "conv_wino_stream.hip", "conv_wgrad.hip", "conv_wgrad_wino.hip", "conv_wgrad_fewch.hip", "gemm.hip", "gemm_small.hip", "rbm.hip", "api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 VALU forms are switched off on purpose: the compiler then emits no v_pk_*_f32 instructions
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
