@@ -1016,7 +1016,7 @@ hipError_t launch_conv_engine(const ConvEngineArgs &a, hipStream_t stream) {
   if (a.Kout <= 3 && a.Kout * (4 * ((16 + a.S - 1 + 3) / 4)) * 3 < 16 * a.S * 2 && conv_fewout_applies(a))
     return launch_conv_fewout(a, stream);
   if (conv_fwd_fewch_applies(a)) return launch_conv_fwd_fewch(a, stream);
-  if (conv_wino_stream_applies(a)) return launch_conv_wino_stream(a, stream);
+  if (conv_wino_stream_applies(a) || conv_wino_stream_bwd_applies(a)) return launch_conv_wino_stream(a, stream);
   if (conv_wino_applies(a)) return launch_conv_wino(a, stream);
   if (a.Hout > 8) {
     const Conv3x3Pick pick = conv3x3c16_pick(a);

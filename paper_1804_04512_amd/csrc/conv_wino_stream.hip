@@ -321,6 +321,286 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_kernel(const 
   }
 }
 
+// ---- Backward-data pass of such a layer (the full convolution of Section II-A as a valid one with
+// rotated, transposed filters): the source is dz = unpool(dy) with the ReLU flags of the pooling
+// bytes, formed in the ring from the pooled gradient; the 2x2 output blocks are stored as they are.
+//
+// A packet is one POOLED row of the segment: 16 channels x (16 + 2 neighbour) gradients and pooling
+// bytes; handling it writes the two dz rows of its windows into one of three slot pairs of a six-row
+// ring (pooled row R of an item starting at block row by0 sits in slot pair (R - by0 + 1) mod 3).
+// Block row by needs dz rows 2by-1 .. 2by+2: the lower row of pooled row by-1, both rows of pooled
+// row by, the upper row of pooled row by+1; an item of n block rows therefore has n + 2 packets.
+constexpr int kPSB = 6 * kRS + 2;        // channel plane of six row slots; half of it odd
+constexpr int kWaveFloatsB = 16 * kPSB;
+
+__global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_bwd_kernel(const WinoStreamParams p) {
+  extern __shared__ float lds[];
+  const ConvEngineArgs &a = p.a;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int i16 = lane & 15, kq = lane >> 4;
+  const int gidx = blockIdx.x;
+  float *xs = lds + wave * kWaveFloatsB;
+
+  // ---- transformed filters: source channel c of this pass is the layer's filter index, output k its
+  // input channel, the taps rotated: g[r][s] = w[c][k][2 - r][2 - s]
+  {
+    const int c = tid >> 4, k = tid & 15;
+    const float *g = a.w + ((long)c * 16 + k) * 9;
+    float gv[9];
+#pragma unroll
+    for (int e = 0; e < 9; ++e) gv[e] = g[8 - e];
+    float t[4][3];
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+      t[0][j] = gv[j];
+      t[1][j] = 0.5f * (gv[j] + gv[3 + j] + gv[6 + j]);
+      t[2][j] = 0.5f * (gv[j] - gv[3 + j] + gv[6 + j]);
+      t[3][j] = gv[6 + j];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      lds[((4 * i + 0) * 16 + c) * 16 + k] = t[i][0];
+      lds[((4 * i + 1) * 16 + c) * 16 + k] = 0.5f * (t[i][0] + t[i][1] + t[i][2]);
+      lds[((4 * i + 2) * 16 + c) * 16 + k] = 0.5f * (t[i][0] - t[i][1] + t[i][2]);
+      lds[((4 * i + 3) * 16 + c) * 16 + k] = t[i][2];
+    }
+  }
+  __syncthreads();
+  float U[4][16];
+#pragma unroll
+  for (int s = 0; s < 4; ++s)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) U[s][q] = lds[(q * 16 + 4 * s + kq) * 16 + i16];
+  __syncthreads();
+
+  const __amdgpu_buffer_rsrc_t rs_g = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.src), 0, (int)p.x_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_f = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char *>(a.src_idx), 0, (int)(p.x_bytes >> 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(a.out, 0, (int)p.y_bytes, 0x00020000);
+
+  // Packet slots.  Main: (channel lane >> 2, windows 4j .. 4j+3 of the segment, j = lane & 3): 16 bytes of
+  // gradient and 4 pooling bytes.  Neighbours (lanes 0 .. 31): (channel lane >> 1, the window left of the
+  // segment or right of it): one gradient, one byte.
+  const int m_ch = lane >> 2, m_j = lane & 3;
+  const int m_lo = m_ch * kPSB + 8 * m_j + 1;             // LDS: image column x0 sits at column 1
+  const int n_ch = (lane & 31) >> 1, n_side = lane & 1;
+  const int n_lo = n_ch * kPSB + (n_side ? 33 : 0);
+  const int plane = p.Hp * p.Wp;
+  int me = 0, ne = 0;              // element offsets of the lane's slots in the first packet of the item being requested
+  bool mok = false, nok = false;
+  auto item_setup = [&](int n, int bx0, int by0) {
+    const int base = ((n * 16) * p.Hp + (by0 - 1)) * p.Wp + bx0;
+    me = base + m_ch * plane + 4 * m_j;
+    mok = bx0 + 4 * m_j < p.Wp;
+    const int nc = bx0 + (n_side ? 16 : -1);
+    ne = base + n_ch * plane + (n_side ? 16 : -1);
+    nok = lane < 32 && bx0 < p.Wp && (unsigned)nc < (unsigned)p.Wp;
+  };
+  struct Packet {
+    float4 g;
+    unsigned f;
+    float ng;
+    unsigned nf;
+  };
+  Packet pa, pb;
+  pa.g = pb.g = make_float4(0.f, 0.f, 0.f, 0.f);
+  pa.f = pb.f = pa.nf = pb.nf = 0;
+  pa.ng = pb.ng = 0.0f;
+  // pooled row R -> registers; dP = R - (by0 - 1).  A row above or below the map is asked for out of range
+  auto load_packet = [&](int R, int dP, Packet &k) {
+    const bool none = R < 0 || R >= p.Hp;
+    const unsigned e = (unsigned)(me + p.Wp * dP), en = (unsigned)(ne + p.Wp * dP);
+    const bool ok = mok && !none, okn = nok && !none;
+    const floatx4 v = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rs_g, (int)(ok ? 4u * e : kOob), 0, 0));
+    k.g = make_float4(v[0], v[1], v[2], v[3]);
+    k.f = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(rs_f, (int)(ok ? e : kOob), 0, 0);
+    k.ng = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_g, (int)(okn ? 4u * en : kOob), 0, 0));
+    k.nf = (unsigned)__builtin_amdgcn_raw_buffer_load_b8(rs_f, (int)(okn ? en : kOob), 0, 0);
+  };
+  // registers -> the two dz rows of the packet's windows in slot pair `slot` (out-of-range loads gave
+  // zeros: zero gradient, zeros written)
+  auto scatter = [&](int slot, const Packet &k) {
+    float *r0 = xs + slot * 2 * kRS + m_lo, *r1 = r0 + kRS;
+    const float gq[4] = {k.g.x, k.g.y, k.g.z, k.g.w};
+    float z0[8], z1[8];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const unsigned f = (k.f >> (8 * w)) & 0xffu;
+      const float v = (f & kIdxInactive) ? 0.0f : gq[w];
+      const unsigned pos = f & kIdxPosMask;
+      z0[2 * w] = pos == 0 ? v : 0.0f;
+      z0[2 * w + 1] = pos == 1 ? v : 0.0f;
+      z1[2 * w] = pos == 2 ? v : 0.0f;
+      z1[2 * w + 1] = pos == 3 ? v : 0.0f;
+    }
+    r0[0] = z0[0];
+    *reinterpret_cast<float2 *>(r0 + 1) = make_float2(z0[1], z0[2]);
+    *reinterpret_cast<float2 *>(r0 + 3) = make_float2(z0[3], z0[4]);
+    *reinterpret_cast<float2 *>(r0 + 5) = make_float2(z0[5], z0[6]);
+    r0[7] = z0[7];
+    r1[0] = z1[0];
+    *reinterpret_cast<float2 *>(r1 + 1) = make_float2(z1[1], z1[2]);
+    *reinterpret_cast<float2 *>(r1 + 3) = make_float2(z1[3], z1[4]);
+    *reinterpret_cast<float2 *>(r1 + 5) = make_float2(z1[5], z1[6]);
+    r1[7] = z1[7];
+    if (lane < 32) {
+      // the left neighbour window shows its right column (positions 1, 3), the right one its left column (0, 2)
+      const float v = (k.nf & kIdxInactive) ? 0.0f : k.ng;
+      const unsigned pos = k.nf & kIdxPosMask, col = n_side ? 0u : 1u;
+      float *d = xs + slot * 2 * kRS + n_lo;
+      d[0] = pos == col ? v : 0.0f;
+      d[kRS] = pos == col + 2u ? v : 0.0f;
+    }
+  };
+
+  // ---- one block row: 16 blocks x 16 output channels; s0, s1, s2: slot pairs of the pooled rows by-1, by, by+1
+  const float *patch = xs + kq * kPSB + 2 * i16;
+  const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
+  auto block_row = [&](int s0, int s1, int s2, floatx4 (&y)[4]) {
+    const float *rw[4] = {patch + (2 * s0 + 1) * kRS, patch + 2 * s1 * kRS, patch + (2 * s1 + 1) * kRS, patch + 2 * s2 * kRS};
+    floatx4 acc[16];
+    float2 pl[2][4], ph[2][4];
+    auto read_patch = [&](auto sc) {
+      constexpr int s = decltype(sc)::value;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float *row = rw[i] + 4 * s * kPSB;
+        pl[s & 1][i] = *reinterpret_cast<const float2 *>(row);
+        ph[s & 1][i] = *reinterpret_cast<const float2 *>(row + 2);
+      }
+    };
+    auto quartet = [&](auto sc) {
+      constexpr int s = decltype(sc)::value;
+      if constexpr (s < 3) read_patch(std::integral_constant<int, s + 1>{});
+      __builtin_amdgcn_sched_barrier(0);
+      float t[4][4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float d0 = j < 2 ? (j ? pl[s & 1][0].y : pl[s & 1][0].x) : (j == 2 ? ph[s & 1][0].x : ph[s & 1][0].y);
+        const float d1 = j < 2 ? (j ? pl[s & 1][1].y : pl[s & 1][1].x) : (j == 2 ? ph[s & 1][1].x : ph[s & 1][1].y);
+        const float d2 = j < 2 ? (j ? pl[s & 1][2].y : pl[s & 1][2].x) : (j == 2 ? ph[s & 1][2].x : ph[s & 1][2].y);
+        const float d3 = j < 2 ? (j ? pl[s & 1][3].y : pl[s & 1][3].x) : (j == 2 ? ph[s & 1][3].x : ph[s & 1][3].y);
+        t[0][j] = d0 - d2;
+        t[1][j] = d1 + d2;
+        t[2][j] = d2 - d1;
+        t[3][j] = d1 - d3;
+      }
+      float V[16];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        V[4 * i + 0] = t[i][0] - t[i][2];
+        V[4 * i + 1] = t[i][1] + t[i][2];
+        V[4 * i + 2] = t[i][2] - t[i][1];
+        V[4 * i + 3] = t[i][1] - t[i][3];
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(V[q], U[s][q], s == 0 ? zero : acc[q], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    read_patch(std::integral_constant<int, 0>{});
+    quartet(std::integral_constant<int, 0>{});
+    quartet(std::integral_constant<int, 1>{});
+    quartet(std::integral_constant<int, 2>{});
+    quartet(std::integral_constant<int, 3>{});
+    // ---- output transform; the lane's blocks 4kq .. 4kq+3 are eight neighbouring columns of two rows
+    float r0[8], r1[8];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      float sr[2][4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        sr[0][j] = acc[j][v] + acc[4 + j][v] + acc[8 + j][v];
+        sr[1][j] = acc[4 + j][v] - acc[8 + j][v] - acc[12 + j][v];
+      }
+      r0[2 * v] = sr[0][0] + sr[0][1] + sr[0][2];
+      r0[2 * v + 1] = sr[0][1] - sr[0][2] - sr[0][3];
+      r1[2 * v] = sr[1][0] + sr[1][1] + sr[1][2];
+      r1[2 * v + 1] = sr[1][1] - sr[1][2] - sr[1][3];
+    }
+    y[0] = floatx4{r0[0], r0[1], r0[2], r0[3]};
+    y[1] = floatx4{r0[4], r0[5], r0[6], r0[7]};
+    y[2] = floatx4{r1[0], r1[1], r1[2], r1[3]};
+    y[3] = floatx4{r1[4], r1[5], r1[6], r1[7]};
+  };
+
+  auto rows_of = [&](int item, int &n_img, int &xseg, int &by0) -> int {
+    const int xg = item % p.xgroups;
+    const int rgrp = (item / p.xgroups) % p.rgroups;
+    n_img = item / (p.xgroups * p.rgroups);
+    xseg = xg * 4 + wave;
+    by0 = rgrp * p.rg;
+    return xseg < p.xsegs ? min(by0 + p.rg, p.Hp) - by0 : 0;
+  };
+  int r_item = gidx - p.G, r_q = 0, r_n = -1, r_by0 = 0;
+  auto next_request_item = [&]() {
+    int n_img = 0, xseg = 0;
+    r_n = 0;
+    for (r_item += p.G; r_item < p.items; r_item += p.G)
+      if ((r_n = rows_of(r_item, n_img, xseg, r_by0)) > 0) break;
+    r_q = 0;
+    if (r_item < p.items) {
+      item_setup(n_img, xseg * 16, r_by0);
+    } else {
+      mok = nok = false;
+      r_by0 = 0;
+    }
+  };
+  auto request = [&](Packet &k) {
+    load_packet(r_by0 - 1 + r_q, r_q, k);
+    if (++r_q > r_n + 1) next_request_item();
+  };
+  int c_item = gidx - p.G, c_q = 0, c_n = -1, c_slot = 0;
+  unsigned c_yo = kOob;   // element offset of the lane's outputs in the item's first block row
+  auto next_consume_item = [&]() {
+    int n_img = 0, xseg = 0, by0 = 0;
+    c_n = 0;
+    for (c_item += p.G; c_item < p.items; c_item += p.G)
+      if ((c_n = rows_of(c_item, n_img, xseg, by0)) > 0) break;
+    c_q = 0;
+    c_slot = 0;
+    const int x = xseg * 32 + 8 * kq;
+    c_yo = (c_item < p.items && x < a.Wout) ? (unsigned)(((n_img * 16 + i16) * a.Hout + 2 * by0) * a.Wout + x) : kOob;
+  };
+  auto handle = [&](Packet &k) {
+    const bool live = c_item < p.items;
+    scatter(c_slot, k);
+    request(k);
+    floatx4 y[4] = {zero, zero, zero, zero};
+    unsigned yo = kOob;
+    if (live && c_q > 1) {
+      const int s2 = c_slot, s1 = s2 == 0 ? 2 : s2 - 1, s0 = s1 == 0 ? 2 : s1 - 1;
+      block_row(s0, s1, s2, y);
+      if (c_yo != kOob) yo = 4u * (c_yo + (unsigned)(2 * (c_q - 2) * a.Wout));
+    }
+    const unsigned rowb = 4u * (unsigned)a.Wout;
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4, y[0]), rs_y, (int)yo, 0, 0);
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4, y[1]), rs_y, (int)(yo == kOob ? kOob : yo + 16u), 0, 0);
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4, y[2]), rs_y, (int)(yo == kOob ? kOob : yo + rowb), 0, 0);
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4, y[3]), rs_y, (int)(yo == kOob ? kOob : yo + rowb + 16u), 0, 0);
+    if (live) {
+      c_slot = c_slot == 2 ? 0 : c_slot + 1;
+      if (++c_q > c_n + 1) next_consume_item();
+    }
+  };
+
+  next_request_item();
+  next_consume_item();
+  auto empty_stores = [&]() {
+#pragma unroll
+    for (int q = 0; q < 4; ++q)   // four different (out-of-range) places: identical stores would be merged into one
+      __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4, zero), rs_y, (int)(kOob + 16u * (unsigned)q), 0, 0);
+  };
+  request(pa);
+  empty_stores();
+  request(pb);
+  empty_stores();
+  while (c_item < p.items) {
+    handle(pa);
+    handle(pb);
+  }
+}
+
 inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
 
 }  // namespace
@@ -335,7 +615,39 @@ bool conv_wino_stream_applies(const ConvEngineArgs &a) {
   return 4L * a.N * a.Cin * a.Hin * a.Win < limit && 4L * a.N * a.Kout * (a.Hin / 2) * (a.Win / 2) < limit;
 }
 
+bool conv_wino_stream_bwd_applies(const ConvEngineArgs &a) {
+  if (!a.src_dz || !a.w_flip || a.src_pool != 2 || a.src_act != ACT_RELU_FLAGGED || !a.src_idx) return false;
+  if (a.R != 3 || a.S != 3 || a.pad_h != 1 || a.pad_w != 1 || a.Cin != 16 || a.Kout != 16) return false;
+  if (a.act != ACT_IDENTITY || a.pool != 1 || a.bias || a.uniform || a.sample || a.out_pool) return false;
+  if (a.Hout != a.Hin || a.Wout != a.Win || a.Win % 8 != 0 || a.Hin % 2 != 0 || a.Win >= (1 << 17)) return false;
+  if (!aligned16(a.src) || !aligned16(a.out) || (reinterpret_cast<uintptr_t>(a.src_idx) & 3u)) return false;
+  const long limit = (1L << 31) - (1L << 24);
+  return 4L * a.N * a.Kout * a.Hin * a.Win < limit;
+}
+
 hipError_t launch_conv_wino_stream(const ConvEngineArgs &a, hipStream_t stream) {
+  if (conv_wino_stream_bwd_applies(a)) {
+    WinoStreamParams p;
+    p.a = a;
+    p.Hp = a.Hin / 2;
+    p.Wp = a.Win / 2;
+    p.xsegs = (a.Win + 31) / 32;
+    p.xgroups = (p.xsegs + 3) / 4;
+    p.x_bytes = (unsigned)(4L * a.N * a.Cin * p.Hp * p.Wp);
+    p.y_bytes = (unsigned)(4L * a.N * a.Kout * a.Hin * a.Win);
+    const long resident = 2L * chip().cus;
+    p.rg = 2;
+    for (int rg = 16; rg >= 2; rg /= 2) {
+      const long items = (long)a.N * p.xgroups * ((p.Hp + rg - 1) / rg);
+      if (items >= resident || rg == 2) { p.rg = rg; break; }
+    }
+    p.rgroups = (p.Hp + p.rg - 1) / p.rg;
+    p.items = a.N * p.rgroups * p.xgroups;
+    p.G = (int)(p.items < resident ? p.items : resident);
+    static_assert(4 * kWaveFloatsB >= 16 * 16 * 16, "the transformed filters pass through the rings' memory");
+    hipLaunchKernelGGL(conv3x3_wino_stream_bwd_kernel, dim3(p.G), dim3(kThreads), sizeof(float) * 4 * kWaveFloatsB, stream, p);
+    return hipGetLastError();
+  }
   if (!conv_wino_stream_applies(a)) return hipErrorInvalidValue;
   WinoStreamParams p;
   p.a = a;

@@ -90,6 +90,7 @@ hipError_t launch_conv_fwd_fewch(const ConvEngineArgs &a, hipStream_t stream);
 // Forward pass of a padded 3x3 layer with 16 channels in and 16 filters, ReLU + pooling, in the
 // minimal-filtering form as a wavefront-private streaming kernel; launch_conv_engine routes there by itself.
 bool conv_wino_stream_applies(const ConvEngineArgs &a);
+bool conv_wino_stream_bwd_applies(const ConvEngineArgs &a);   // the backward-data pass of such a layer (same launcher)
 hipError_t launch_conv_wino_stream(const ConvEngineArgs &a, hipStream_t stream);
 bool conv_fewout_applies(const ConvEngineArgs &a);
 hipError_t launch_conv_fewout(const ConvEngineArgs &a, hipStream_t stream);
