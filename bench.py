@@ -88,6 +88,8 @@ def engine_kernel_name(cs, backward: bool) -> str:
     if same and cs.C == 16 and cs.K == 16 and cs.act == "relu" and cs.pool == 2 and cs.W % 8 == 0 and cs.H % 2 == 0:
         # the minimal-filtering form as a streaming kernel (backward-data from the pooled gradient with the ReLU flags)
         return "conv3x3_wino_stream_bwd_kernel" if backward else "conv3x3_wino_stream_kernel"
+    if same and not backward and cs.C == 16 and cs.K == 32 and cs.act == "relu" and cs.pool == 2 and cs.W % 8 == 0 and cs.H % 2 == 0:
+        return "conv3x3_wino_stream_kernel"
     if same and cs.C == 16 and cs.act == "relu" and cs.pool == 2 and cs.Ho % 8 == 0 and cs.Wo % 32 == 0:
         if cs.K == 16:
             return f"conv3x3_wino_kernel<1,{'true' if backward else 'false'},1,1>"

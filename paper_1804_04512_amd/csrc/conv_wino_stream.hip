@@ -39,14 +39,17 @@ constexpr unsigned kOob = 0x80000000u;
 struct WinoStreamParams {
   ConvEngineArgs a;
   int Hp, Wp;          // pooled map = blocks per column / row
-  int xsegs, xgroups;  // 32-pixel column segments; groups of four neighbouring segments (one per wavefront)
+  int xsegs, xgroups;  // 32-pixel column segments; groups of as many neighbouring segments as a workgroup has streams
   int rg, rgroups;     // block rows per work item, row groups per image
   int items;           // work items of a workgroup: N * rgroups * xgroups
   int G;               // workgroups
   unsigned x_bytes, y_bytes;
 };
 
-template <bool IDX>
+// KT: groups of 16 filters (1 or 2); a wavefront works ONE group, the 4 / KT wavefronts of a group are
+// independent streams over neighbouring segments (with two groups, two wavefronts stage the same rows,
+// each into its own ring).
+template <bool IDX, int KT>
 __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_kernel(const WinoStreamParams p) {
   extern __shared__ float lds[];
   const ConvEngineArgs &a = p.a;
@@ -54,13 +57,16 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_kernel(const 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // the same in every lane: it lives in scalar registers
   const int i16 = lane & 15, kq = lane >> 4;
   const int gidx = blockIdx.x;
+  constexpr int S = 4 / KT, kKout = 16 * KT;
+  const int ktile = wave % KT, stream = wave / KT, k0 = 16 * ktile;
   float *xs = lds + wave * kWaveFloats;
 
   // ---- transformed filters U = G g Gt, G = [1 0 0; .5 .5 .5; .5 -.5 .5; 0 0 1]: one (channel, filter)
   // pair per thread into LDS [point][channel][filter] (over the rings, which are not in use yet), then
   // each lane takes its B fragments: channel 4s+kq, filter i16, every point
-  {
-    const int c = tid >> 4, k = tid & 15;
+#pragma unroll
+  for (int kt = 0; kt < KT; ++kt) {
+    const int c = tid >> 4, k = 16 * kt + (tid & 15);
     const float *g = a.w + ((long)k * 16 + c) * 9;
     float gv[9];
 #pragma unroll
@@ -75,10 +81,10 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_kernel(const 
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      lds[((4 * i + 0) * 16 + c) * 16 + k] = t[i][0];
-      lds[((4 * i + 1) * 16 + c) * 16 + k] = 0.5f * (t[i][0] + t[i][1] + t[i][2]);
-      lds[((4 * i + 2) * 16 + c) * 16 + k] = 0.5f * (t[i][0] - t[i][1] + t[i][2]);
-      lds[((4 * i + 3) * 16 + c) * 16 + k] = t[i][2];
+      lds[((4 * i + 0) * 16 + c) * kKout + k] = t[i][0];
+      lds[((4 * i + 1) * 16 + c) * kKout + k] = 0.5f * (t[i][0] + t[i][1] + t[i][2]);
+      lds[((4 * i + 2) * 16 + c) * kKout + k] = 0.5f * (t[i][0] - t[i][1] + t[i][2]);
+      lds[((4 * i + 3) * 16 + c) * kKout + k] = t[i][2];
     }
   }
   __syncthreads();
@@ -86,9 +92,9 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_kernel(const 
 #pragma unroll
   for (int s = 0; s < 4; ++s)
 #pragma unroll
-    for (int q = 0; q < 16; ++q) U[s][q] = lds[(q * 16 + 4 * s + kq) * 16 + i16];
+    for (int q = 0; q < 16; ++q) U[s][q] = lds[(q * 16 + 4 * s + kq) * kKout + k0 + i16];
   __syncthreads();   // everybody has its fragments: the rings may be written
-  const float bias = a.bias ? a.bias[i16] : 0.0f;
+  const float bias = a.bias ? a.bias[k0 + i16] : 0.0f;
 
   const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.src), 0, (int)p.x_bytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(a.out, 0, (int)p.y_bytes, 0x00020000);
@@ -248,7 +254,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_kernel(const 
     const int xg = item % p.xgroups;
     const int rgrp = (item / p.xgroups) % p.rgroups;
     n_img = item / (p.xgroups * p.rgroups);
-    xseg = xg * 4 + wave;
+    xseg = xg * S + stream;
     by0 = rgrp * p.rg;
     return xseg < p.xsegs ? min(by0 + p.rg, p.Hp) - by0 : 0;
   };
@@ -282,7 +288,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_kernel(const 
       if ((c_n = rows_of(c_item, n_img, xseg, by0)) > 0) break;
     c_q = 0;
     const int bx = xseg * 16 + 4 * kq;
-    c_yo = (c_item < p.items && bx < p.Wp) ? (unsigned)(((n_img * 16 + i16) * p.Hp + by0) * p.Wp + bx) : kOob;
+    c_yo = (c_item < p.items && bx < p.Wp) ? (unsigned)(((n_img * kKout + k0 + i16) * p.Hp + by0) * p.Wp + bx) : kOob;
   };
   // (a packet handled after the wavefront's last item is an empty one: the loop below leaves only after
   // whole rounds of both register sets, so that no path leads from one set's packet straight to the
@@ -607,7 +613,7 @@ inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 
 
 bool conv_wino_stream_applies(const ConvEngineArgs &a) {
   if (a.src_dz || a.w_flip || a.R != 3 || a.S != 3 || a.pad_h != 1 || a.pad_w != 1) return false;
-  if (a.Cin != 16 || a.Kout != 16 || a.act != ACT_RELU || a.pool != 2) return false;
+  if (a.Cin != 16 || (a.Kout != 16 && a.Kout != 32) || a.act != ACT_RELU || a.pool != 2) return false;
   if (a.Hout != a.Hin || a.Wout != a.Win || a.Win % 8 != 0 || a.Hin % 2 != 0 || a.Win >= (1 << 17)) return false;
   if (a.uniform || a.sample || a.out_pool) return false;
   if (!aligned16(a.src) || !aligned16(a.out) || (a.out_idx && (reinterpret_cast<uintptr_t>(a.out_idx) & 3u))) return false;
@@ -653,8 +659,9 @@ hipError_t launch_conv_wino_stream(const ConvEngineArgs &a, hipStream_t stream) 
   p.a = a;
   p.Hp = a.Hin / 2;
   p.Wp = a.Win / 2;
+  const int KT = a.Kout / 16, streams = 4 / KT;
   p.xsegs = (a.Win + 31) / 32;
-  p.xgroups = (p.xsegs + 3) / 4;
+  p.xgroups = (p.xsegs + streams - 1) / streams;
   p.x_bytes = (unsigned)(4L * a.N * a.Cin * a.Hin * a.Win);
   p.y_bytes = (unsigned)(4L * a.N * a.Kout * p.Hp * p.Wp);
   const long resident = 2L * chip().cus;   // two workgroups per compute unit (registers)
@@ -669,9 +676,14 @@ hipError_t launch_conv_wino_stream(const ConvEngineArgs &a, hipStream_t stream) 
   p.items = a.N * p.rgroups * p.xgroups;
   p.G = (int)(p.items < resident ? p.items : resident);
   const size_t smem = sizeof(float) * 4 * kWaveFloats;
-  static_assert(4 * kWaveFloats >= 16 * 16 * 16, "the transformed filters pass through the rings' memory");
-  if (a.out_idx) hipLaunchKernelGGL(conv3x3_wino_stream_kernel<true>, dim3(p.G), dim3(kThreads), smem, stream, p);
-  else hipLaunchKernelGGL(conv3x3_wino_stream_kernel<false>, dim3(p.G), dim3(kThreads), smem, stream, p);
+  static_assert(4 * kWaveFloats >= 16 * 16 * 32, "the transformed filters pass through the rings' memory");
+  if (KT == 1) {
+    if (a.out_idx) hipLaunchKernelGGL((conv3x3_wino_stream_kernel<true, 1>), dim3(p.G), dim3(kThreads), smem, stream, p);
+    else hipLaunchKernelGGL((conv3x3_wino_stream_kernel<false, 1>), dim3(p.G), dim3(kThreads), smem, stream, p);
+  } else {
+    if (a.out_idx) hipLaunchKernelGGL((conv3x3_wino_stream_kernel<true, 2>), dim3(p.G), dim3(kThreads), smem, stream, p);
+    else hipLaunchKernelGGL((conv3x3_wino_stream_kernel<false, 2>), dim3(p.G), dim3(kThreads), smem, stream, p);
+  }
   return hipGetLastError();
 }
 
