@@ -110,6 +110,10 @@ CASES = [
     ConvSpec(3, 32, 24, 40, 16, 3, 3, 1, "relu", 2),          # 32 -> 16: two channel tiles, one filter tile; a ragged second column segment
     ConvSpec(5, 16, 36, 72, 32, 3, 3, 1, "relu", 2),          # 16 -> 32 on 18 block rows: row groups with a short last one, three column segments (the last 8 wide)
     ConvSpec(2, 32, 20, 8, 32, 3, 3, 1, "relu", 2),           # 32 -> 32 on a map narrower than one column segment
+    # streaming minimal-filtering kernels (16 channels in; forward 16 or 32 filters, backward-data 16 -> 16)
+    ConvSpec(12, 16, 256, 256, 16, 3, 3, 1, "relu", 2),       # 768 work items on 512 workgroups: wavefronts pass from one item to the next with rows in flight
+    ConvSpec(6, 16, 256, 264, 32, 3, 3, 1, "relu", 2),        # two filter groups, nine column segments: the last group of two has one, a wavefront pair skips items
+    ConvSpec(3, 16, 18, 40, 16, 3, 3, 1, "relu", 2),          # nine block rows (a short last row group), a second segment of 8 columns
     # first layers of image networks (one to three channels in, at most 16 filters): the filter gradient forms dz in registers
     ConvSpec(3, 3, 24, 72, 16, 3, 3, 1, "relu", 2),           # RGB, a whole 64-pixel strip and a ragged one of 8 pixels
     ConvSpec(2, 3, 36, 328, 16, 3, 3, 1, "relu", 2),          # six strips: two groups of four, the second with two strips sitting out; 18 window rows
