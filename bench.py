@@ -81,15 +81,15 @@ def engine_kernel_name(cs, backward: bool) -> str:
     same = cs.R == 3 and cs.S == 3 and cs.pad == 1
     if same and not backward and cs.C <= 3 and cs.K <= 16 and cs.act == "relu" and cs.pool == 2 and cs.W % 8 == 0:
         return "conv_fwd_fewch_kernel"   # first layer of the image networks
-    # layers with 16 or 32 channels in and out, ReLU + pooling, on whole 8 x 32 tiles: the minimal-filtering kernel
-    # (forward, and backward-data from the pooled gradient with the ReLU flags, as the step calls it)
+    # layers with 16 or 32 channels in and out, ReLU + pooling: the minimal-filtering form as a streaming kernel
+    # (forward, and backward-data from the pooled gradient with the ReLU flags, as the step calls it); a 32-channel
+    # source needs column segments that fill the workgroup's streams, else the tile kernel below takes the layer
+    if same and cs.C in (16, 32) and cs.K in (16, 32) and cs.C + cs.K < 64 and cs.act == "relu" and cs.pool == 2 and cs.W % 8 == 0 and cs.H % 2 == 0:
+        streams = 4 // ((cin // 16) * (kout // 16))
+        if cin == 16 or ((cs.W + 31) // 32) % streams == 0:
+            return "conv3x3_wino_stream_bwd_kernel" if backward else "conv3x3_wino_stream_kernel"
     if same and cs.C == 32 and cs.K == 32 and cs.act == "relu" and cs.pool == 2 and cs.Ho % 8 == 0 and cs.Wo % 32 == 0:
         return f"conv3x3_wino_kernel<1,{'true' if backward else 'false'},2,2>"
-    if same and cs.C == 16 and cs.K == 16 and cs.act == "relu" and cs.pool == 2 and cs.W % 8 == 0 and cs.H % 2 == 0:
-        # the minimal-filtering form as a streaming kernel (backward-data from the pooled gradient with the ReLU flags)
-        return "conv3x3_wino_stream_bwd_kernel" if backward else "conv3x3_wino_stream_kernel"
-    if same and not backward and cs.C == 16 and cs.K == 32 and cs.act == "relu" and cs.pool == 2 and cs.W % 8 == 0 and cs.H % 2 == 0:
-        return "conv3x3_wino_stream_kernel"
     if same and cs.C == 16 and cs.act == "relu" and cs.pool == 2 and cs.Ho % 8 == 0 and cs.Wo % 32 == 0:
         if cs.K == 16:
             return f"conv3x3_wino_kernel<1,{'true' if backward else 'false'},1,1>"

@@ -46,10 +46,15 @@ struct WinoStreamParams {
   unsigned x_bytes, y_bytes;
 };
 
-// KT: groups of 16 filters (1 or 2); a wavefront works ONE group, the 4 / KT wavefronts of a group are
-// independent streams over neighbouring segments (with two groups, two wavefronts stage the same rows,
-// each into its own ring).
-template <bool IDX, int KT>
+// KT: groups of 16 filters (1 or 2); a wavefront works ONE group (with two groups, two wavefronts stage
+// the same rows, each into its own ring).
+// CH: halves of a 32-channel source (1: 16 channels).  With CH = 2 two wavefronts work the two halves of
+// the same segment and filter group; after the output transform (it is linear) the wavefront of the
+// upper half hands its 16 values per lane over through LDS and the other adds them and finishes.  That
+// costs one workgroup barrier per packet, so with CH = 2 all four wavefronts run the same packets in
+// step: no wavefront skips an item (the launcher takes only shapes whose segments fill the streams).
+// The 4 / (KT * CH) remaining wavefronts are independent streams over neighbouring segments.
+template <bool IDX, int KT, int CH>
 __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_kernel(const WinoStreamParams p) {
   extern __shared__ float lds[];
   const ConvEngineArgs &a = p.a;
@@ -57,43 +62,51 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_kernel(const 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // the same in every lane: it lives in scalar registers
   const int i16 = lane & 15, kq = lane >> 4;
   const int gidx = blockIdx.x;
-  constexpr int S = 4 / KT, kKout = 16 * KT;
-  const int ktile = wave % KT, stream = wave / KT, k0 = 16 * ktile;
+  constexpr int S = 4 / (KT * CH), kKout = 16 * KT, kCin = 16 * CH;
+  const int chalf = wave % CH, ktile = (wave / CH) % KT, stream = wave / (CH * KT);
+  const int c0 = 16 * chalf, k0 = 16 * ktile;
   float *xs = lds + wave * kWaveFloats;
+  floatx4 *exch = reinterpret_cast<floatx4 *>(lds + 4 * kWaveFloats);   // CH = 2: [packet parity][pair][4][lane]
 
-  // ---- transformed filters U = G g Gt, G = [1 0 0; .5 .5 .5; .5 -.5 .5; 0 0 1]: one (channel, filter)
-  // pair per thread into LDS [point][channel][filter] (over the rings, which are not in use yet), then
-  // each lane takes its B fragments: channel 4s+kq, filter i16, every point
-#pragma unroll
-  for (int kt = 0; kt < KT; ++kt) {
-    const int c = tid >> 4, k = 16 * kt + (tid & 15);
-    const float *g = a.w + ((long)k * 16 + c) * 9;
-    float gv[9];
-#pragma unroll
-    for (int e = 0; e < 9; ++e) gv[e] = g[e];
-    float t[4][3];
-#pragma unroll
-    for (int j = 0; j < 3; ++j) {
-      t[0][j] = gv[j];
-      t[1][j] = 0.5f * (gv[j] + gv[3 + j] + gv[6 + j]);
-      t[2][j] = 0.5f * (gv[j] - gv[3 + j] + gv[6 + j]);
-      t[3][j] = gv[6 + j];
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      lds[((4 * i + 0) * 16 + c) * kKout + k] = t[i][0];
-      lds[((4 * i + 1) * 16 + c) * kKout + k] = 0.5f * (t[i][0] + t[i][1] + t[i][2]);
-      lds[((4 * i + 2) * 16 + c) * kKout + k] = 0.5f * (t[i][0] - t[i][1] + t[i][2]);
-      lds[((4 * i + 3) * 16 + c) * kKout + k] = t[i][2];
-    }
-  }
-  __syncthreads();
+  // ---- transformed filters U = G g Gt, G = [1 0 0; .5 .5 .5; .5 -.5 .5; 0 0 1]: per (channel half, filter
+  // group), one (channel, filter) pair per thread into LDS [point][channel][filter] (over the rings, which
+  // are not in use yet); the wavefronts of that half and group then take their B fragments: channel
+  // 4s+kq, filter i16, every point
   float U[4][16];
 #pragma unroll
-  for (int s = 0; s < 4; ++s)
+  for (int cb = 0; cb < CH * KT; ++cb) {
+    const int ch = cb % CH, kt = cb / CH;
+    {
+      const int c = tid >> 4, k = tid & 15;
+      const float *g = a.w + ((long)(16 * kt + k) * kCin + 16 * ch + c) * 9;
+      float gv[9];
 #pragma unroll
-    for (int q = 0; q < 16; ++q) U[s][q] = lds[(q * 16 + 4 * s + kq) * kKout + k0 + i16];
-  __syncthreads();   // everybody has its fragments: the rings may be written
+      for (int e = 0; e < 9; ++e) gv[e] = g[e];
+      float t[4][3];
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        t[0][j] = gv[j];
+        t[1][j] = 0.5f * (gv[j] + gv[3 + j] + gv[6 + j]);
+        t[2][j] = 0.5f * (gv[j] - gv[3 + j] + gv[6 + j]);
+        t[3][j] = gv[6 + j];
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        lds[((4 * i + 0) * 16 + c) * 16 + k] = t[i][0];
+        lds[((4 * i + 1) * 16 + c) * 16 + k] = 0.5f * (t[i][0] + t[i][1] + t[i][2]);
+        lds[((4 * i + 2) * 16 + c) * 16 + k] = 0.5f * (t[i][0] - t[i][1] + t[i][2]);
+        lds[((4 * i + 3) * 16 + c) * 16 + k] = t[i][2];
+      }
+    }
+    __syncthreads();
+    if (ch == chalf && kt == ktile) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) U[s][q] = lds[(q * 16 + 4 * s + kq) * 16 + i16];
+    }
+    __syncthreads();   // everybody has its fragments: the next group, or the rings, may be written
+  }
   const float bias = a.bias ? a.bias[k0 + i16] : 0.0f;
 
   const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.src), 0, (int)p.x_bytes, 0x00020000);
@@ -125,7 +138,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_kernel(const 
   unsigned xv[kXR], hv = kOob;   // byte offsets of the lane's slots in the first pair of the item being requested
 
   auto item_setup = [&](int n, int x0, int by0) {
-    const int base = ((n * 16) * a.Hin + (2 * by0 - 1)) * a.Win + x0;
+    const int base = ((n * kCin + c0) * a.Hin + (2 * by0 - 1)) * a.Win + x0;
 #pragma unroll
     for (int it = 0; it < kXR; ++it) xv[it] = x0 + xcol[it] < a.Win ? 4u * (unsigned)(base + xpl[it]) : kOob;
     const int hc = x0 + (h_side ? 32 : -1);
@@ -167,7 +180,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_kernel(const 
   // `yo`: element offset of the lane's four pooled outputs (filter i16, blocks 4kq .. 4kq+3), or out of range.
   const float *patch = xs + kq * kPS + 2 * i16;
   const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
-  auto block_row = [&](int sp, floatx4 &y, unsigned &ib) {
+  auto block_row = [&](int sp, floatx4 (&z)[4]) {
     const float *pup = patch + sp * 2 * kRS, *pdn = patch + (sp ^ 1) * 2 * kRS;
     floatx4 acc[16];
     float2 pl[2][4], ph[2][4];
@@ -217,9 +230,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_kernel(const 
     quartet(std::integral_constant<int, 1>{});
     quartet(std::integral_constant<int, 2>{});
     quartet(std::integral_constant<int, 3>{});
-    // ---- output transform At M A, At = [1 1 1 0; 0 1 -1 -1], then bias, ReLU, pooling: a block is one window
-    float yv[4];
-    ib = 0;
+    // ---- output transform At M A, At = [1 1 1 0; 0 1 -1 -1]: z[v] = the 2x2 block 4kq+v (y00, y01, y10, y11)
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       float sr[2][4];
@@ -228,13 +239,21 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_kernel(const 
         sr[0][j] = acc[j][v] + acc[4 + j][v] + acc[8 + j][v];
         sr[1][j] = acc[4 + j][v] - acc[8 + j][v] - acc[12 + j][v];
       }
-      const float y00 = sr[0][0] + sr[0][1] + sr[0][2], y01 = sr[0][1] - sr[0][2] - sr[0][3];
-      const float y10 = sr[1][0] + sr[1][1] + sr[1][2], y11 = sr[1][1] - sr[1][2] - sr[1][3];
-      float m = y00;
+      z[v] = floatx4{sr[0][0] + sr[0][1] + sr[0][2], sr[0][1] - sr[0][2] - sr[0][3],
+                     sr[1][0] + sr[1][1] + sr[1][2], sr[1][1] - sr[1][2] - sr[1][3]};
+    }
+  };
+  // bias, ReLU, pooling: a block is one window; first maximum in the order (0,0), (0,1), (1,0), (1,1)
+  auto finish = [&](const floatx4 (&z)[4], floatx4 &y, unsigned &ib) {
+    float yv[4];
+    ib = 0;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      float m = z[v][0];
       unsigned arg = 0;
-      if (y01 > m) { m = y01; arg = 1; }
-      if (y10 > m) { m = y10; arg = 2; }
-      if (y11 > m) { m = y11; arg = 3; }
+      if (z[v][1] > m) { m = z[v][1]; arg = 1; }
+      if (z[v][2] > m) { m = z[v][2]; arg = 2; }
+      if (z[v][3] > m) { m = z[v][3]; arg = 3; }
       const float o = m + bias;
       yv[v] = o > 0.0f ? o : 0.0f;
       ib |= (arg | (yv[v] > 0.0f ? 0u : (unsigned)kIdxInactive)) << (8 * v);
@@ -256,7 +275,8 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_kernel(const 
     n_img = item / (p.xgroups * p.rgroups);
     xseg = xg * S + stream;
     by0 = rgrp * p.rg;
-    return xseg < p.xsegs ? min(by0 + p.rg, p.Hp) - by0 : 0;
+    // (CH = 2: never skipped, the four wavefronts stay in step; a segment beyond the row would be worked on zeros)
+    return (CH == 2 || xseg < p.xsegs) ? min(by0 + p.rg, p.Hp) - by0 : 0;
   };
   // request cursor: packet (r_item, r_q) is the next to ask for; consume cursor: (c_item, c_q) the next to handle
   int r_item = gidx - p.G, r_q = 0, r_n = -1, r_by0 = 0;
@@ -279,7 +299,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_kernel(const 
     load_pair(r_by0 + r_q, r_q, xr, xh);
     if (++r_q > r_n) next_request_item();
   };
-  int c_item = gidx - p.G, c_q = 0, c_n = -1;
+  int c_item = gidx - p.G, c_q = 0, c_n = -1, c_par = 0;
   unsigned c_yo = kOob;   // element offset of the lane's outputs in the item's first block row
   auto next_consume_item = [&]() {
     int n_img = 0, xseg = 0, by0 = 0;
@@ -298,10 +318,31 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_kernel(const 
     store_pair(c_q & 1, xr, xh);
     request(xr, xh);
     // the stores are issued for every packet (out of range where no block row was worked), like the loads
+    floatx4 z[4] = {zero, zero, zero, zero};
     floatx4 y = zero;
     unsigned ib = 0, yo = kOob;
-    if (live && c_q > 0) {
-      block_row((c_q - 1) & 1, y, ib);
+    const bool work = live && c_q > 0;
+    if (work) block_row((c_q - 1) & 1, z);
+    if constexpr (CH == 2) {
+      // the upper half's partial blocks go to the lower half's wavefront; every wavefront of the
+      // workgroup passes this barrier once per packet
+      floatx4 *ex = exch + ((c_par * 2 + wave / 2) * 4) * 64 + lane;
+      if (chalf == 1) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) ex[64 * v] = z[v];
+      }
+      __syncthreads();
+      if (chalf == 0) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const floatx4 o = ex[64 * v];
+          z[v] += o;
+        }
+      }
+      c_par ^= 1;
+    }
+    if (work && chalf == 0) {
+      finish(z, y, ib);
       if (c_yo != kOob) yo = c_yo + (unsigned)((c_q - 1) * p.Wp);
     }
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4, y), rs_y, (int)(yo == kOob ? kOob : 4u * yo), 0, 0);
@@ -339,6 +380,8 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_kernel(const 
 constexpr int kPSB = 6 * kRS + 2;        // channel plane of six row slots; half of it odd
 constexpr int kWaveFloatsB = 16 * kPSB;
 
+// KT: groups of 16 output channels, CH: halves of a 32-channel gradient, as in the forward kernel.
+template <int KT, int CH>
 __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_bwd_kernel(const WinoStreamParams p) {
   extern __shared__ float lds[];
   const ConvEngineArgs &a = p.a;
@@ -346,39 +389,49 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_bwd_kernel(co
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int i16 = lane & 15, kq = lane >> 4;
   const int gidx = blockIdx.x;
+  constexpr int S = 4 / (KT * CH), kKout = 16 * KT, kCin = 16 * CH;
+  const int chalf = wave % CH, ktile = (wave / CH) % KT, stream = wave / (CH * KT);
+  const int c0 = 16 * chalf, k0 = 16 * ktile;
   float *xs = lds + wave * kWaveFloatsB;
+  floatx4 *exch = reinterpret_cast<floatx4 *>(lds + 4 * kWaveFloatsB);   // CH = 2: [packet parity][pair][4][lane]
 
   // ---- transformed filters: source channel c of this pass is the layer's filter index, output k its
-  // input channel, the taps rotated: g[r][s] = w[c][k][2 - r][2 - s]
-  {
-    const int c = tid >> 4, k = tid & 15;
-    const float *g = a.w + ((long)c * 16 + k) * 9;
-    float gv[9];
-#pragma unroll
-    for (int e = 0; e < 9; ++e) gv[e] = g[8 - e];
-    float t[4][3];
-#pragma unroll
-    for (int j = 0; j < 3; ++j) {
-      t[0][j] = gv[j];
-      t[1][j] = 0.5f * (gv[j] + gv[3 + j] + gv[6 + j]);
-      t[2][j] = 0.5f * (gv[j] - gv[3 + j] + gv[6 + j]);
-      t[3][j] = gv[6 + j];
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      lds[((4 * i + 0) * 16 + c) * 16 + k] = t[i][0];
-      lds[((4 * i + 1) * 16 + c) * 16 + k] = 0.5f * (t[i][0] + t[i][1] + t[i][2]);
-      lds[((4 * i + 2) * 16 + c) * 16 + k] = 0.5f * (t[i][0] - t[i][1] + t[i][2]);
-      lds[((4 * i + 3) * 16 + c) * 16 + k] = t[i][2];
-    }
-  }
-  __syncthreads();
+  // input channel, the taps rotated: g[r][s] = w[c][k][2 - r][2 - s]; per (channel half, output group)
   float U[4][16];
 #pragma unroll
-  for (int s = 0; s < 4; ++s)
+  for (int cb = 0; cb < CH * KT; ++cb) {
+    const int ch = cb % CH, kt = cb / CH;
+    {
+      const int c = tid >> 4, k = tid & 15;
+      const float *g = a.w + ((long)(16 * ch + c) * kKout + 16 * kt + k) * 9;
+      float gv[9];
 #pragma unroll
-    for (int q = 0; q < 16; ++q) U[s][q] = lds[(q * 16 + 4 * s + kq) * 16 + i16];
-  __syncthreads();
+      for (int e = 0; e < 9; ++e) gv[e] = g[8 - e];
+      float t[4][3];
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        t[0][j] = gv[j];
+        t[1][j] = 0.5f * (gv[j] + gv[3 + j] + gv[6 + j]);
+        t[2][j] = 0.5f * (gv[j] - gv[3 + j] + gv[6 + j]);
+        t[3][j] = gv[6 + j];
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        lds[((4 * i + 0) * 16 + c) * 16 + k] = t[i][0];
+        lds[((4 * i + 1) * 16 + c) * 16 + k] = 0.5f * (t[i][0] + t[i][1] + t[i][2]);
+        lds[((4 * i + 2) * 16 + c) * 16 + k] = 0.5f * (t[i][0] - t[i][1] + t[i][2]);
+        lds[((4 * i + 3) * 16 + c) * 16 + k] = t[i][2];
+      }
+    }
+    __syncthreads();
+    if (ch == chalf && kt == ktile) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) U[s][q] = lds[(q * 16 + 4 * s + kq) * 16 + i16];
+    }
+    __syncthreads();
+  }
 
   const __amdgpu_buffer_rsrc_t rs_g = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.src), 0, (int)p.x_bytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t rs_f = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char *>(a.src_idx), 0, (int)(p.x_bytes >> 2), 0x00020000);
@@ -395,7 +448,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_bwd_kernel(co
   int me = 0, ne = 0;              // element offsets of the lane's slots in the first packet of the item being requested
   bool mok = false, nok = false;
   auto item_setup = [&](int n, int bx0, int by0) {
-    const int base = ((n * 16) * p.Hp + (by0 - 1)) * p.Wp + bx0;
+    const int base = ((n * kCin + c0) * p.Hp + (by0 - 1)) * p.Wp + bx0;
     me = base + m_ch * plane + 4 * m_j;
     mok = bx0 + 4 * m_j < p.Wp;
     const int nc = bx0 + (n_side ? 16 : -1);
@@ -462,7 +515,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_bwd_kernel(co
   // ---- one block row: 16 blocks x 16 output channels; s0, s1, s2: slot pairs of the pooled rows by-1, by, by+1
   const float *patch = xs + kq * kPSB + 2 * i16;
   const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
-  auto block_row = [&](int s0, int s1, int s2, floatx4 (&y)[4]) {
+  auto block_row = [&](int s0, int s1, int s2, floatx4 (&z)[4]) {
     const float *rw[4] = {patch + (2 * s0 + 1) * kRS, patch + 2 * s1 * kRS, patch + (2 * s1 + 1) * kRS, patch + 2 * s2 * kRS};
     floatx4 acc[16];
     float2 pl[2][4], ph[2][4];
@@ -509,8 +562,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_bwd_kernel(co
     quartet(std::integral_constant<int, 1>{});
     quartet(std::integral_constant<int, 2>{});
     quartet(std::integral_constant<int, 3>{});
-    // ---- output transform; the lane's blocks 4kq .. 4kq+3 are eight neighbouring columns of two rows
-    float r0[8], r1[8];
+    // ---- output transform: z[v] = the 2x2 block 4kq+v (y00, y01, y10, y11)
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       float sr[2][4];
@@ -519,24 +571,18 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_bwd_kernel(co
         sr[0][j] = acc[j][v] + acc[4 + j][v] + acc[8 + j][v];
         sr[1][j] = acc[4 + j][v] - acc[8 + j][v] - acc[12 + j][v];
       }
-      r0[2 * v] = sr[0][0] + sr[0][1] + sr[0][2];
-      r0[2 * v + 1] = sr[0][1] - sr[0][2] - sr[0][3];
-      r1[2 * v] = sr[1][0] + sr[1][1] + sr[1][2];
-      r1[2 * v + 1] = sr[1][1] - sr[1][2] - sr[1][3];
+      z[v] = floatx4{sr[0][0] + sr[0][1] + sr[0][2], sr[0][1] - sr[0][2] - sr[0][3],
+                     sr[1][0] + sr[1][1] + sr[1][2], sr[1][1] - sr[1][2] - sr[1][3]};
     }
-    y[0] = floatx4{r0[0], r0[1], r0[2], r0[3]};
-    y[1] = floatx4{r0[4], r0[5], r0[6], r0[7]};
-    y[2] = floatx4{r1[0], r1[1], r1[2], r1[3]};
-    y[3] = floatx4{r1[4], r1[5], r1[6], r1[7]};
   };
 
   auto rows_of = [&](int item, int &n_img, int &xseg, int &by0) -> int {
     const int xg = item % p.xgroups;
     const int rgrp = (item / p.xgroups) % p.rgroups;
     n_img = item / (p.xgroups * p.rgroups);
-    xseg = xg * 4 + wave;
+    xseg = xg * S + stream;
     by0 = rgrp * p.rg;
-    return xseg < p.xsegs ? min(by0 + p.rg, p.Hp) - by0 : 0;
+    return (CH == 2 || xseg < p.xsegs) ? min(by0 + p.rg, p.Hp) - by0 : 0;
   };
   int r_item = gidx - p.G, r_q = 0, r_n = -1, r_by0 = 0;
   auto next_request_item = [&]() {
@@ -556,7 +602,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_bwd_kernel(co
     load_packet(r_by0 - 1 + r_q, r_q, k);
     if (++r_q > r_n + 1) next_request_item();
   };
-  int c_item = gidx - p.G, c_q = 0, c_n = -1, c_slot = 0;
+  int c_item = gidx - p.G, c_q = 0, c_n = -1, c_slot = 0, c_par = 0;
   unsigned c_yo = kOob;   // element offset of the lane's outputs in the item's first block row
   auto next_consume_item = [&]() {
     int n_img = 0, xseg = 0, by0 = 0;
@@ -566,19 +612,39 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_bwd_kernel(co
     c_q = 0;
     c_slot = 0;
     const int x = xseg * 32 + 8 * kq;
-    c_yo = (c_item < p.items && x < a.Wout) ? (unsigned)(((n_img * 16 + i16) * a.Hout + 2 * by0) * a.Wout + x) : kOob;
+    c_yo = (c_item < p.items && x < a.Wout) ? (unsigned)(((n_img * kKout + k0 + i16) * a.Hout + 2 * by0) * a.Wout + x) : kOob;
   };
   auto handle = [&](Packet &k) {
     const bool live = c_item < p.items;
     scatter(c_slot, k);
     request(k);
-    floatx4 y[4] = {zero, zero, zero, zero};
+    floatx4 z[4] = {zero, zero, zero, zero};
     unsigned yo = kOob;
-    if (live && c_q > 1) {
+    const bool work = live && c_q > 1;
+    if (work) {
       const int s2 = c_slot, s1 = s2 == 0 ? 2 : s2 - 1, s0 = s1 == 0 ? 2 : s1 - 1;
-      block_row(s0, s1, s2, y);
-      if (c_yo != kOob) yo = 4u * (c_yo + (unsigned)(2 * (c_q - 2) * a.Wout));
+      block_row(s0, s1, s2, z);
     }
+    if constexpr (CH == 2) {
+      floatx4 *ex = exch + ((c_par * 2 + wave / 2) * 4) * 64 + lane;
+      if (chalf == 1) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) ex[64 * v] = z[v];
+      }
+      __syncthreads();
+      if (chalf == 0) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const floatx4 o = ex[64 * v];
+          z[v] += o;
+        }
+      }
+      c_par ^= 1;
+    }
+    if (work && chalf == 0 && c_yo != kOob) yo = 4u * (c_yo + (unsigned)(2 * (c_q - 2) * a.Wout));
+    // the lane's blocks 4kq .. 4kq+3 are eight neighbouring columns of two rows
+    const floatx4 y[4] = {floatx4{z[0][0], z[0][1], z[1][0], z[1][1]}, floatx4{z[2][0], z[2][1], z[3][0], z[3][1]},
+                          floatx4{z[0][2], z[0][3], z[1][2], z[1][3]}, floatx4{z[2][2], z[2][3], z[3][2], z[3][3]}};
     const unsigned rowb = 4u * (unsigned)a.Wout;
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4, y[0]), rs_y, (int)yo, 0, 0);
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4, y[1]), rs_y, (int)(yo == kOob ? kOob : yo + 16u), 0, 0);
@@ -611,59 +677,28 @@ inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 
 
 }  // namespace
 
-bool conv_wino_stream_applies(const ConvEngineArgs &a) {
-  if (a.src_dz || a.w_flip || a.R != 3 || a.S != 3 || a.pad_h != 1 || a.pad_w != 1) return false;
-  if (a.Cin != 16 || (a.Kout != 16 && a.Kout != 32) || a.act != ACT_RELU || a.pool != 2) return false;
-  if (a.Hout != a.Hin || a.Wout != a.Win || a.Win % 8 != 0 || a.Hin % 2 != 0 || a.Win >= (1 << 17)) return false;
-  if (a.uniform || a.sample || a.out_pool) return false;
-  if (!aligned16(a.src) || !aligned16(a.out) || (a.out_idx && (reinterpret_cast<uintptr_t>(a.out_idx) & 3u))) return false;
-  const long limit = (1L << 31) - (1L << 24);
-  return 4L * a.N * a.Cin * a.Hin * a.Win < limit && 4L * a.N * a.Kout * (a.Hin / 2) * (a.Win / 2) < limit;
+namespace {
+// streams of a workgroup for a layer with `cin` source channels and `kout` outputs, or 0 when the kernels do not take it
+// (32 -> 32 channels stay with the tile kernel: on config 5's 32 x 32 maps the single stream of such a
+// workgroup has one short item, and the pass measured 20.9 against 18.0 us)
+int stream_count(int cin, int kout) {
+  if ((cin != 16 && cin != 32) || (kout != 16 && kout != 32) || (cin == 32 && kout == 32)) return 0;
+  return 4 / ((cin / 16) * (kout / 16));
+}
+// a 32-channel source is worked by wavefront pairs that meet at a barrier per packet: every stream of
+// a workgroup must then have a segment in every item
+bool streams_filled(const ConvEngineArgs &a) {
+  const int S = stream_count(a.Cin, a.Kout);
+  return S > 0 && (a.Cin == 16 || ((a.Win + 31) / 32) % S == 0);
 }
 
-bool conv_wino_stream_bwd_applies(const ConvEngineArgs &a) {
-  if (!a.src_dz || !a.w_flip || a.src_pool != 2 || a.src_act != ACT_RELU_FLAGGED || !a.src_idx) return false;
-  if (a.R != 3 || a.S != 3 || a.pad_h != 1 || a.pad_w != 1 || a.Cin != 16 || a.Kout != 16) return false;
-  if (a.act != ACT_IDENTITY || a.pool != 1 || a.bias || a.uniform || a.sample || a.out_pool) return false;
-  if (a.Hout != a.Hin || a.Wout != a.Win || a.Win % 8 != 0 || a.Hin % 2 != 0 || a.Win >= (1 << 17)) return false;
-  if (!aligned16(a.src) || !aligned16(a.out) || (reinterpret_cast<uintptr_t>(a.src_idx) & 3u)) return false;
-  const long limit = (1L << 31) - (1L << 24);
-  return 4L * a.N * a.Kout * a.Hin * a.Win < limit;
-}
-
-hipError_t launch_conv_wino_stream(const ConvEngineArgs &a, hipStream_t stream) {
-  if (conv_wino_stream_bwd_applies(a)) {
-    WinoStreamParams p;
-    p.a = a;
-    p.Hp = a.Hin / 2;
-    p.Wp = a.Win / 2;
-    p.xsegs = (a.Win + 31) / 32;
-    p.xgroups = (p.xsegs + 3) / 4;
-    p.x_bytes = (unsigned)(4L * a.N * a.Cin * p.Hp * p.Wp);
-    p.y_bytes = (unsigned)(4L * a.N * a.Kout * a.Hin * a.Win);
-    const long resident = 2L * chip().cus;
-    p.rg = 2;
-    for (int rg = 16; rg >= 2; rg /= 2) {
-      const long items = (long)a.N * p.xgroups * ((p.Hp + rg - 1) / rg);
-      if (items >= resident || rg == 2) { p.rg = rg; break; }
-    }
-    p.rgroups = (p.Hp + p.rg - 1) / p.rg;
-    p.items = a.N * p.rgroups * p.xgroups;
-    p.G = (int)(p.items < resident ? p.items : resident);
-    static_assert(4 * kWaveFloatsB >= 16 * 16 * 16, "the transformed filters pass through the rings' memory");
-    hipLaunchKernelGGL(conv3x3_wino_stream_bwd_kernel, dim3(p.G), dim3(kThreads), sizeof(float) * 4 * kWaveFloatsB, stream, p);
-    return hipGetLastError();
-  }
-  if (!conv_wino_stream_applies(a)) return hipErrorInvalidValue;
-  WinoStreamParams p;
+void fill_params(const ConvEngineArgs &a, WinoStreamParams &p) {
+  const int streams = stream_count(a.Cin, a.Kout);
   p.a = a;
   p.Hp = a.Hin / 2;
   p.Wp = a.Win / 2;
-  const int KT = a.Kout / 16, streams = 4 / KT;
   p.xsegs = (a.Win + 31) / 32;
   p.xgroups = (p.xsegs + streams - 1) / streams;
-  p.x_bytes = (unsigned)(4L * a.N * a.Cin * a.Hin * a.Win);
-  p.y_bytes = (unsigned)(4L * a.N * a.Kout * p.Hp * p.Wp);
   const long resident = 2L * chip().cus;   // two workgroups per compute unit (registers)
   // block rows per work item: long strips re-read fewer halo rows, short ones balance the workgroups;
   // the first length that leaves every resident workgroup an item, else the shortest
@@ -675,16 +710,64 @@ hipError_t launch_conv_wino_stream(const ConvEngineArgs &a, hipStream_t stream) 
   p.rgroups = (p.Hp + p.rg - 1) / p.rg;
   p.items = a.N * p.rgroups * p.xgroups;
   p.G = (int)(p.items < resident ? p.items : resident);
-  const size_t smem = sizeof(float) * 4 * kWaveFloats;
-  static_assert(4 * kWaveFloats >= 16 * 16 * 32, "the transformed filters pass through the rings' memory");
-  if (KT == 1) {
-    if (a.out_idx) hipLaunchKernelGGL((conv3x3_wino_stream_kernel<true, 1>), dim3(p.G), dim3(kThreads), smem, stream, p);
-    else hipLaunchKernelGGL((conv3x3_wino_stream_kernel<false, 1>), dim3(p.G), dim3(kThreads), smem, stream, p);
-  } else {
-    if (a.out_idx) hipLaunchKernelGGL((conv3x3_wino_stream_kernel<true, 2>), dim3(p.G), dim3(kThreads), smem, stream, p);
-    else hipLaunchKernelGGL((conv3x3_wino_stream_kernel<false, 2>), dim3(p.G), dim3(kThreads), smem, stream, p);
-  }
+}
+
+template <typename Kern>
+hipError_t launch_stream(Kern kern, const WinoStreamParams &p, size_t lds_bytes, hipStream_t stream) {
+  const hipError_t e = allow_large_lds(reinterpret_cast<const void *>(kern), lds_bytes);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(kern, dim3(p.G), dim3(kThreads), lds_bytes, stream, p);
   return hipGetLastError();
+}
+constexpr size_t kExchBytes = sizeof(floatx4) * 2 * 2 * 4 * 64;   // two packet parities x two wavefront pairs x 4 x 64 lanes
+}  // namespace
+
+bool conv_wino_stream_applies(const ConvEngineArgs &a) {
+  if (a.src_dz || a.w_flip || a.R != 3 || a.S != 3 || a.pad_h != 1 || a.pad_w != 1) return false;
+  if (!streams_filled(a) || a.act != ACT_RELU || a.pool != 2) return false;
+  if (a.Hout != a.Hin || a.Wout != a.Win || a.Win % 8 != 0 || a.Hin % 2 != 0 || a.Win >= (1 << 17)) return false;
+  if (a.uniform || a.sample || a.out_pool) return false;
+  if (!aligned16(a.src) || !aligned16(a.out) || (a.out_idx && (reinterpret_cast<uintptr_t>(a.out_idx) & 3u))) return false;
+  const long limit = (1L << 31) - (1L << 24);
+  return 4L * a.N * a.Cin * a.Hin * a.Win < limit && 4L * a.N * a.Kout * (a.Hin / 2) * (a.Win / 2) < limit;
+}
+
+bool conv_wino_stream_bwd_applies(const ConvEngineArgs &a) {
+  if (!a.src_dz || !a.w_flip || a.src_pool != 2 || a.src_act != ACT_RELU_FLAGGED || !a.src_idx) return false;
+  if (a.R != 3 || a.S != 3 || a.pad_h != 1 || a.pad_w != 1 || !streams_filled(a)) return false;
+  if (a.act != ACT_IDENTITY || a.pool != 1 || a.bias || a.uniform || a.sample || a.out_pool) return false;
+  if (a.Hout != a.Hin || a.Wout != a.Win || a.Win % 8 != 0 || a.Hin % 2 != 0 || a.Win >= (1 << 17)) return false;
+  if (!aligned16(a.src) || !aligned16(a.out) || (reinterpret_cast<uintptr_t>(a.src_idx) & 3u)) return false;
+  const long limit = (1L << 31) - (1L << 24);
+  return 4L * a.N * a.Kout * a.Hin * a.Win < limit && 4L * a.N * a.Cin * (a.Hin / 2) * (a.Win / 2) < limit;
+}
+
+hipError_t launch_conv_wino_stream(const ConvEngineArgs &a, hipStream_t stream) {
+  static_assert(4 * kWaveFloats >= 16 * 16 * 16 && 4 * kWaveFloatsB >= 16 * 16 * 16, "the transformed filters pass through the rings' memory");
+  WinoStreamParams p;
+  const int KT = a.Kout / 16, CH = a.Cin / 16;
+  if (conv_wino_stream_bwd_applies(a)) {
+    fill_params(a, p);
+    p.x_bytes = (unsigned)(4L * a.N * a.Cin * p.Hp * p.Wp);
+    p.y_bytes = (unsigned)(4L * a.N * a.Kout * a.Hin * a.Win);
+    const size_t lds = sizeof(float) * 4 * kWaveFloatsB + (CH == 2 ? kExchBytes : 0);
+    if (KT == 1 && CH == 1) return launch_stream(conv3x3_wino_stream_bwd_kernel<1, 1>, p, lds, stream);
+    if (KT == 2 && CH == 1) return launch_stream(conv3x3_wino_stream_bwd_kernel<2, 1>, p, lds, stream);
+    return launch_stream(conv3x3_wino_stream_bwd_kernel<1, 2>, p, lds, stream);
+  }
+  if (!conv_wino_stream_applies(a)) return hipErrorInvalidValue;
+  fill_params(a, p);
+  p.x_bytes = (unsigned)(4L * a.N * a.Cin * a.Hin * a.Win);
+  p.y_bytes = (unsigned)(4L * a.N * a.Kout * p.Hp * p.Wp);
+  const size_t lds = sizeof(float) * 4 * kWaveFloats + (CH == 2 ? kExchBytes : 0);
+  if (a.out_idx) {
+    if (KT == 1 && CH == 1) return launch_stream(conv3x3_wino_stream_kernel<true, 1, 1>, p, lds, stream);
+    if (KT == 2 && CH == 1) return launch_stream(conv3x3_wino_stream_kernel<true, 2, 1>, p, lds, stream);
+    return launch_stream(conv3x3_wino_stream_kernel<true, 1, 2>, p, lds, stream);
+  }
+  if (KT == 1 && CH == 1) return launch_stream(conv3x3_wino_stream_kernel<false, 1, 1>, p, lds, stream);
+  if (KT == 2 && CH == 1) return launch_stream(conv3x3_wino_stream_kernel<false, 2, 1>, p, lds, stream);
+  return launch_stream(conv3x3_wino_stream_kernel<false, 1, 2>, p, lds, stream);
 }
 
 }  // namespace dllk
