@@ -723,7 +723,10 @@ bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, int po
   if (G > cap) G = cap;
   // layers the minimal-filtering kernel can take: its registers leave two workgroups per compute unit,
   // and every one of them should be resident from the start (the direct kernel copes with any G)
-  if (wgrad_wino_shape(C, H, W, K, R, S, pad, pool) && mtf * 16 == K && best_cc == 16) G = 2 * cus < items ? 2 * cus : items;
+  if (wgrad_wino_shape(C, H, W, K, R, S, pad, pool) && mtf * 16 == K && best_cc == 16) {
+    const long want = (C == 32 && K == 32) ? cus : 2 * cus;   // 32 x 32 filters: 36 KB per partial block; halving their number took 2 us off the step
+    G = want < items ? want : items;
+  }
   // the first-layer kernel keeps four workgroups per compute unit resident
   if (wgrad_fewch_shape(C, H, W, K, R, S, pad, pool) && mtf == 1 && best_ntt == 2 && best_cc == C) G = 4 * cus < items ? 4 * cus : items;
   if (G < 1) G = 1;
