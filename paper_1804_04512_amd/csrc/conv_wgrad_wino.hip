@@ -19,7 +19,7 @@
 // rows of two 8-byte reads, dy and the pooling byte straight from global memory (16 consecutive
 // blocks of a filter row are four lanes' 16-byte loads).  Every wavefront works alone: its own
 // (filter tile, channel tile) pair, its own strip of blocks, its own four-row ring of x rows in
-// LDS (two new rows per block row, fetched one block row ahead), no workgroup barrier until the
+// LDS (two new rows per block row, requested two block rows ahead), no workgroup barrier until the
 // final, fixed-order sum of the wavefronts' results.  The partial blocks have the layout of the
 // direct kernel's, so the same reduction kernel finishes both.
 #include "dll_internal.h"
