@@ -27,9 +27,13 @@ __global__ __launch_bounds__(256) void mfma_loop(float *out, int iters, float a0
 #pragma unroll
   for (int i = 0; i < 8; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
   const float a = a0 + (float)threadIdx.x, b = b0;
-  for (int it = 0; it < iters; ++it) {
+  // 64 products per trip: with only eight, the loop's own branch shows (41 instead of 33 cycles per
+  // product at one wavefront per SIMD)
+  for (int it = 0; it < iters; it += 8) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[i], 0, 0, 0);
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[i], 0, 0, 0);
   }
   float s = 0.f;
 #pragma unroll
