@@ -765,11 +765,29 @@ dll_status run_cnn_step(const dll_net_desc *net, float *const *params, float *co
     // the closing launch, so the data-gradient pass after it still sees the old ones.
     WgradPlan plan;
     if (!plan_for(d, &plan)) return DLL_ERR_UNSUPPORTED;
-    st = dev(launch_wgrad(wgrad_args(d, nb.act[l], gcur, yl, nb.idx[l], nb.cpartial[l]), plan, s));
-    if (st != DLL_OK) return st;
+    const WgradArgs wa = wgrad_args(d, nb.act[l], gcur, yl, nb.idx[l], nb.cpartial[l]);
+    bool shared = false;
     if (l > 0) {
-      st = dev(launch_conv_engine(bwd_args(d, gcur, yl, nb.idx[l], params[2 * l], gnext), s));
+      // the two passes do not depend on each other; where both are streaming kernels they share a launch
+      // (the filter gradient then with half as many workgroups, hence a plan of its own - never more
+      // partial blocks than the plan the workspace was sized with)
+      const ConvEngineArgs ba = bwd_args(d, gcur, yl, nb.idx[l], params[2 * l], gnext);
+      WgradPlan half;
+      if (plan_wgrad(d->N, d->C, d->H, d->W, d->K, d->R, d->S, d->pad, d->pool, &half, true) &&
+          half.partial_floats <= plan.partial_floats && wgrad_bwd_pair_applies(wa, half, ba)) {
+        st = dev(launch_wgrad_bwd_pair(wa, half, ba, s));
+        if (st != DLL_OK) return st;
+        plan = half;
+        shared = true;
+      }
+    }
+    if (!shared) {
+      st = dev(launch_wgrad(wa, plan, s));
       if (st != DLL_OK) return st;
+      if (l > 0) {
+        st = dev(launch_conv_engine(bwd_args(d, gcur, yl, nb.idx[l], params[2 * l], gnext), s));
+        if (st != DLL_OK) return st;
+      }
     }
     WgradReduceArgs r;
     r.pos = nb.cpartial[l]; r.scale = 1.0f;

@@ -665,7 +665,7 @@ inline Geom x_geom(int R, int S, int pad) {
 
 }  // namespace
 
-bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, int pool, WgradPlan *plan) {
+bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, int pool, WgradPlan *plan, bool shared_launch) {
   const int Ho = H + 2 * pad - R + 1, Wo = W + 2 * pad - S + 1;
   const int RSf = R * S;
   // channels per chunk: minimise (chunks x tap tiles) with at most 9 tap tiles
@@ -724,7 +724,7 @@ bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, int po
   // layers the minimal-filtering kernel can take: its registers leave two workgroups per compute unit,
   // and every one of them should be resident from the start (the direct kernel copes with any G)
   if (wgrad_wino_shape(C, H, W, K, R, S, pad, pool) && mtf * 16 == K && best_cc == 16) {
-    const long want = (C == 32 && K == 32) ? cus : 2 * cus;   // 32 x 32 filters: 36 KB per partial block; halving their number took 2 us off the step
+    const long want = ((C == 32 && K == 32) || shared_launch) ? cus : 2 * cus;   // 32 x 32 filters: 36 KB per partial block; halving their number took 2 us off the step
     G = want < items ? want : items;
   }
   // the first-layer kernel keeps four workgroups per compute unit resident

@@ -18,6 +18,7 @@
 // straight across work-item boundaries; every block row issues the same loads and stores on every
 // path (out-of-range offsets where there is nothing to move), so the number of memory instructions
 // issued after any given one is known at compile time and a wait leaves the later ones in flight.
+#include "conv_wgrad_wino_body.h"
 #include "dll_internal.h"
 
 #include <type_traits>
@@ -381,14 +382,14 @@ constexpr int kPSB = 6 * kRS + 2;        // channel plane of six row slots; half
 constexpr int kWaveFloatsB = 16 * kPSB;
 
 // KT: groups of 16 output channels, CH: halves of a 32-channel gradient, as in the forward kernel.
+// (the body as a function of the workgroup's index `gidx` among p.G workgroups and its dynamic LDS: it
+// also runs as one role of the launch it shares with the layer's filter gradient, below)
 template <int KT, int CH>
-__global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_bwd_kernel(const WinoStreamParams p) {
-  extern __shared__ float lds[];
+__device__ __forceinline__ void stream_bwd_body(const WinoStreamParams &p, float *lds, const int gidx) {
   const ConvEngineArgs &a = p.a;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int i16 = lane & 15, kq = lane >> 4;
-  const int gidx = blockIdx.x;
   constexpr int S = 4 / (KT * CH), kKout = 16 * KT, kCin = 16 * CH;
   const int chalf = wave % CH, ktile = (wave / CH) % KT, stream = wave / (CH * KT);
   const int c0 = 16 * chalf, k0 = 16 * ktile;
@@ -673,6 +674,27 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_bwd_kernel(co
   }
 }
 
+template <int KT, int CH>
+__global__ __launch_bounds__(kThreads, 2) void conv3x3_wino_stream_bwd_kernel(const WinoStreamParams p) {
+  extern __shared__ float lds[];
+  stream_bwd_body<KT, CH>(p, lds, blockIdx.x);
+}
+
+// A layer's filter gradient and its backward-data pass read the same gradient and do not depend on
+// each other: one launch runs both, half of the workgroups each (roles alternate in groups of eight
+// workgroup indices, so that each of the eight XCDs - indices go to them in turn - gets both), and the
+// ramp and drain of a launch are paid once instead of twice.  Both bodies walk their work items
+// with the stride of their own workgroup count, so neither knows of the other.
+template <int KT, int CT>
+__global__ __launch_bounds__(kThreads, 2) void wgrad_bwd_pair_kernel(const wgw::WinoWgradParams pw, const WinoStreamParams pb) {
+  extern __shared__ float lds[];
+  const int role = (blockIdx.x >> 3) & 1, idx = (int)(((blockIdx.x >> 4) << 3) | (blockIdx.x & 7));
+  // filter gradient: K filters (KT tiles) x C channels (CT tiles); backward-data of the same layer: K source
+  // channels (halves: KT) -> C outputs (groups: CT)
+  if (role) wgw::wgrad_wino_body<KT, CT>(pw, lds, idx);
+  else stream_bwd_body<CT, KT>(pb, lds, idx);
+}
+
 inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
 
 }  // namespace
@@ -692,14 +714,15 @@ bool streams_filled(const ConvEngineArgs &a) {
   return S > 0 && (a.Cin == 16 || ((a.Win + 31) / 32) % S == 0);
 }
 
-void fill_params(const ConvEngineArgs &a, WinoStreamParams &p) {
+void fill_params(const ConvEngineArgs &a, WinoStreamParams &p, long workgroups = 0) {
   const int streams = stream_count(a.Cin, a.Kout);
   p.a = a;
   p.Hp = a.Hin / 2;
   p.Wp = a.Win / 2;
   p.xsegs = (a.Win + 31) / 32;
   p.xgroups = (p.xsegs + streams - 1) / streams;
-  const long resident = 2L * chip().cus;   // two workgroups per compute unit (registers)
+  // two workgroups per compute unit (registers), unless the launch is shared and the caller says how many are this pass's
+  const long resident = workgroups > 0 ? workgroups : 2L * chip().cus;
   // block rows per work item: long strips re-read fewer halo rows, short ones balance the workgroups;
   // the first length that leaves every resident workgroup an item, else the shortest
   p.rg = 2;
@@ -768,6 +791,39 @@ hipError_t launch_conv_wino_stream(const ConvEngineArgs &a, hipStream_t stream) 
   if (KT == 1 && CH == 1) return launch_stream(conv3x3_wino_stream_kernel<false, 1, 1>, p, lds, stream);
   if (KT == 2 && CH == 1) return launch_stream(conv3x3_wino_stream_kernel<false, 2, 1>, p, lds, stream);
   return launch_stream(conv3x3_wino_stream_kernel<false, 1, 2>, p, lds, stream);
+}
+
+// The filter gradient (plan with `cus` workgroups) and the backward-data pass of one layer in one launch.
+bool wgrad_bwd_pair_applies(const WgradArgs &w, const WgradPlan &plan, const ConvEngineArgs &b) {
+  if (!wgrad_wino_applies(w, plan) || !conv_wino_stream_bwd_applies(b)) return false;
+  if (w.C == 32) return false;                       // the backward-data pass of a 32-channel layer is not a streaming one
+  if (b.Cin != w.K || b.Kout != w.C || b.N != w.N || b.Hin != w.H || b.Win != w.W) return false;
+  WinoStreamParams pb;
+  fill_params(b, pb, plan.G);
+  return pb.G == plan.G && plan.G % 8 == 0;          // equal halves, whole groups of eight
+}
+
+hipError_t launch_wgrad_bwd_pair(const WgradArgs &w, const WgradPlan &plan, const ConvEngineArgs &b, hipStream_t stream) {
+  if (!wgrad_bwd_pair_applies(w, plan, b)) return hipErrorInvalidValue;
+  wgw::WinoWgradParams pw;
+  if (!wgw::fill_wino_wgrad_params(w, plan, pw)) return hipErrorInvalidValue;
+  WinoStreamParams pb;
+  fill_params(b, pb, plan.G);
+  pb.x_bytes = (unsigned)(4L * b.N * b.Cin * pb.Hp * pb.Wp);
+  pb.y_bytes = (unsigned)(4L * b.N * b.Kout * b.Hin * b.Win);
+  const int KT = w.K / 16;
+  size_t lds = sizeof(float) * 4 * kWaveFloatsB + (KT == 2 ? kExchBytes : 0);
+  if (lds < wgw::kWinoWgradLdsBytes) lds = wgw::kWinoWgradLdsBytes;
+  const dim3 grid((unsigned)(2 * plan.G)), block(kThreads);
+  hipError_t e;
+  if (KT == 1) {
+    if ((e = allow_large_lds(reinterpret_cast<const void *>(wgrad_bwd_pair_kernel<1, 1>), lds)) != hipSuccess) return e;
+    hipLaunchKernelGGL((wgrad_bwd_pair_kernel<1, 1>), grid, block, lds, stream, pw, pb);
+  } else {
+    if ((e = allow_large_lds(reinterpret_cast<const void *>(wgrad_bwd_pair_kernel<2, 1>), lds)) != hipSuccess) return e;
+    hipLaunchKernelGGL((wgrad_bwd_pair_kernel<2, 1>), grid, block, lds, stream, pw, pb);
+  }
+  return hipGetLastError();
 }
 
 }  // namespace dllk

@@ -92,6 +92,7 @@ hipError_t launch_conv_fwd_fewch(const ConvEngineArgs &a, hipStream_t stream);
 bool conv_wino_stream_applies(const ConvEngineArgs &a);
 bool conv_wino_stream_bwd_applies(const ConvEngineArgs &a);   // the backward-data pass of such a layer (same launcher)
 hipError_t launch_conv_wino_stream(const ConvEngineArgs &a, hipStream_t stream);
+
 bool conv_fewout_applies(const ConvEngineArgs &a);
 hipError_t launch_conv_fewout(const ConvEngineArgs &a, hipStream_t stream);
 
@@ -135,13 +136,19 @@ struct WgradPlan {
   int n_partials;        // per chunk: one block per workgroup (G)
 };
 
-bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, int pool, WgradPlan *plan);
+// `shared_launch`: the plan of a filter gradient that shares its launch with the layer's backward-data
+// pass (half as many workgroups; only the minimal-filtering shapes have such a form, others plan as ever)
+bool plan_wgrad(int N, int C, int H, int W, int K, int R, int S, int pad, int pool, WgradPlan *plan, bool shared_launch = false);
 // Padded 3x3 layers with 16 or 32 channels in and out behind ReLU + pooling, gradient and pooling bytes
 // alone (no layer output): the minimal-filtering form F(3x3, 2x2), same partial blocks as the direct
 // kernel.  launch_wgrad routes there by itself.
 bool wgrad_wino_shape(int C, int H, int W, int K, int R, int S, int pad, int pool);
 bool wgrad_wino_applies(const WgradArgs &a, const WgradPlan &plan);
 hipError_t launch_wgrad_wino(const WgradArgs &a, const WgradPlan &plan, hipStream_t stream);
+// That filter gradient and the layer's backward-data pass (streaming form) in ONE launch, half of the
+// workgroups each; `plan` must be one made for a shared launch (plan_wgrad's last argument).
+bool wgrad_bwd_pair_applies(const WgradArgs &w, const WgradPlan &plan, const ConvEngineArgs &b);
+hipError_t launch_wgrad_bwd_pair(const WgradArgs &w, const WgradPlan &plan, const ConvEngineArgs &b, hipStream_t stream);
 // Padded 3x3 layers with one to three input channels and at most 16 filters behind ReLU + pooling
 // (the first layer of the image networks), gradient and pooling bytes alone: the filter-side operand
 // is formed in registers from the pooled tensors.  Same partial blocks; launch_wgrad routes there.
