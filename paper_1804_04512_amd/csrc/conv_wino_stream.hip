@@ -703,19 +703,19 @@ namespace {
 // streams of a workgroup for a layer with `cin` source channels and `kout` outputs, or 0 when the kernels do not take it
 // (32 -> 32 channels stay with the tile kernel: on config 5's 32 x 32 maps the single stream of such a
 // workgroup has one short item, and the pass measured 20.9 against 18.0 us)
-int stream_count(int cin, int kout) {
-  if ((cin != 16 && cin != 32) || (kout != 16 && kout != 32) || (cin == 32 && kout == 32)) return 0;
+int stream_count(int cin, int kout, bool both32 = false) {
+  if ((cin != 16 && cin != 32) || (kout != 16 && kout != 32) || (cin == 32 && kout == 32 && !both32)) return 0;
   return 4 / ((cin / 16) * (kout / 16));
 }
 // a 32-channel source is worked by wavefront pairs that meet at a barrier per packet: every stream of
 // a workgroup must then have a segment in every item
-bool streams_filled(const ConvEngineArgs &a) {
-  const int S = stream_count(a.Cin, a.Kout);
+bool streams_filled(const ConvEngineArgs &a, bool both32 = false) {
+  const int S = stream_count(a.Cin, a.Kout, both32);
   return S > 0 && (a.Cin == 16 || ((a.Win + 31) / 32) % S == 0);
 }
 
 void fill_params(const ConvEngineArgs &a, WinoStreamParams &p, long workgroups = 0) {
-  const int streams = stream_count(a.Cin, a.Kout);
+  const int streams = stream_count(a.Cin, a.Kout, true);
   p.a = a;
   p.Hp = a.Hin / 2;
   p.Wp = a.Win / 2;
@@ -755,15 +755,21 @@ bool conv_wino_stream_applies(const ConvEngineArgs &a) {
   return 4L * a.N * a.Cin * a.Hin * a.Win < limit && 4L * a.N * a.Kout * (a.Hin / 2) * (a.Win / 2) < limit;
 }
 
-bool conv_wino_stream_bwd_applies(const ConvEngineArgs &a) {
+namespace {
+bool stream_bwd_ok(const ConvEngineArgs &a, bool both32);
+}
+bool conv_wino_stream_bwd_applies(const ConvEngineArgs &a) { return stream_bwd_ok(a, false); }
+namespace {
+bool stream_bwd_ok(const ConvEngineArgs &a, bool both32) {
   if (!a.src_dz || !a.w_flip || a.src_pool != 2 || a.src_act != ACT_RELU_FLAGGED || !a.src_idx) return false;
-  if (a.R != 3 || a.S != 3 || a.pad_h != 1 || a.pad_w != 1 || !streams_filled(a)) return false;
+  if (a.R != 3 || a.S != 3 || a.pad_h != 1 || a.pad_w != 1 || !streams_filled(a, both32)) return false;
   if (a.act != ACT_IDENTITY || a.pool != 1 || a.bias || a.uniform || a.sample || a.out_pool) return false;
   if (a.Hout != a.Hin || a.Wout != a.Win || a.Win % 8 != 0 || a.Hin % 2 != 0 || a.Win >= (1 << 17)) return false;
   if (!aligned16(a.src) || !aligned16(a.out) || (reinterpret_cast<uintptr_t>(a.src_idx) & 3u)) return false;
   const long limit = (1L << 31) - (1L << 24);
   return 4L * a.N * a.Kout * a.Hin * a.Win < limit && 4L * a.N * a.Cin * (a.Hin / 2) * (a.Win / 2) < limit;
 }
+}  // namespace
 
 hipError_t launch_conv_wino_stream(const ConvEngineArgs &a, hipStream_t stream) {
   static_assert(4 * kWaveFloats >= 16 * 16 * 16 && 4 * kWaveFloatsB >= 16 * 16 * 16, "the transformed filters pass through the rings' memory");
@@ -795,8 +801,10 @@ hipError_t launch_conv_wino_stream(const ConvEngineArgs &a, hipStream_t stream) 
 
 // The filter gradient (plan with `cus` workgroups) and the backward-data pass of one layer in one launch.
 bool wgrad_bwd_pair_applies(const WgradArgs &w, const WgradPlan &plan, const ConvEngineArgs &b) {
-  if (!wgrad_wino_applies(w, plan) || !conv_wino_stream_bwd_applies(b)) return false;
-  if (w.C == 32) return false;                       // the backward-data pass of a 32-channel layer is not a streaming one
+  // (in a shared launch the streaming backward-data form also takes 32 -> 32 channels: on its own it is
+  // slower than the tile kernel there, but less so than a launch costs)
+  if (!wgrad_wino_applies(w, plan) || !stream_bwd_ok(b, true)) return false;
+  if (w.C == 32 && w.K != 32) return false;          // 32 -> 16 channels: its backward-data pass (16 -> 32) has a form, its pair is not built
   if (b.Cin != w.K || b.Kout != w.C || b.N != w.N || b.Hin != w.H || b.Win != w.W) return false;
   WinoStreamParams pb;
   fill_params(b, pb, plan.G);
@@ -811,7 +819,7 @@ hipError_t launch_wgrad_bwd_pair(const WgradArgs &w, const WgradPlan &plan, cons
   fill_params(b, pb, plan.G);
   pb.x_bytes = (unsigned)(4L * b.N * b.Cin * pb.Hp * pb.Wp);
   pb.y_bytes = (unsigned)(4L * b.N * b.Kout * b.Hin * b.Win);
-  const int KT = w.K / 16;
+  const int KT = w.K / 16, CT = w.C / 16;
   size_t lds = sizeof(float) * 4 * kWaveFloatsB + (KT == 2 ? kExchBytes : 0);
   if (lds < wgw::kWinoWgradLdsBytes) lds = wgw::kWinoWgradLdsBytes;
   const dim3 grid((unsigned)(2 * plan.G)), block(kThreads);
@@ -819,6 +827,9 @@ hipError_t launch_wgrad_bwd_pair(const WgradArgs &w, const WgradPlan &plan, cons
   if (KT == 1) {
     if ((e = allow_large_lds(reinterpret_cast<const void *>(wgrad_bwd_pair_kernel<1, 1>), lds)) != hipSuccess) return e;
     hipLaunchKernelGGL((wgrad_bwd_pair_kernel<1, 1>), grid, block, lds, stream, pw, pb);
+  } else if (CT == 2) {
+    if ((e = allow_large_lds(reinterpret_cast<const void *>(wgrad_bwd_pair_kernel<2, 2>), lds)) != hipSuccess) return e;
+    hipLaunchKernelGGL((wgrad_bwd_pair_kernel<2, 2>), grid, block, lds, stream, pw, pb);
   } else {
     if ((e = allow_large_lds(reinterpret_cast<const void *>(wgrad_bwd_pair_kernel<2, 1>), lds)) != hipSuccess) return e;
     hipLaunchKernelGGL((wgrad_bwd_pair_kernel<2, 1>), grid, block, lds, stream, pw, pb);
