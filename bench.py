@@ -179,7 +179,7 @@ N_BATCHES = 3    # input batches the timed steps of config 5 rotate through (3 x
 # the step's kernels, each v_mfma_f32_16x16x4_f32 being 2048 FLOP.  HBM bytes: FETCH_SIZE and
 # WRITE_SIZE summed over the step's kernels with the copy-kernel calibration.
 RECORDED_STEP_COUNTERS = {
-    ("c5_large_image_cnn", 128): {"mfma_wave_instructions": 25.95e6, "hbm_bytes": 1.875e9,
+    ("c5_large_image_cnn", 128): {"mfma_wave_instructions": 25.95e6, "hbm_bytes": 1.842e9,
                                   "source": "profiles/c5_cnn_train_step.md (rocprofv3 --pmc runs of this bench command)"},
 }
 
