@@ -379,6 +379,18 @@ def test_config5_full_size_step():
     check_cnn(wl.config5())
 
 
+def test_cnn_step_layers_that_share_launches():
+    """Three padded 3x3 ReLU + pooling layers with 16 -> 16, 16 -> 32 and 32 -> 32 channels: in the
+    training step each layer's filter gradient and backward-data pass run as ONE launch (half of
+    the workgroups each, the filter gradient with half as many partial blocks as on its own).
+    Batch and map sizes give each role a multiple of eight workgroups and several work items per
+    workgroup in the first layer."""
+    conv = [ConvSpec(24, 16, 64, 128, 16, 3, 3, 1, "relu", 2), ConvSpec(24, 16, 32, 64, 32, 3, 3, 1, "relu", 2),
+            ConvSpec(24, 32, 16, 32, 32, 3, 3, 1, "relu", 2)]
+    dense = [wl.DenseSpec(32 * 8 * 16, 96, "relu"), wl.DenseSpec(96, 10, "identity")]
+    check_cnn(wl._cnn(77, "shared_launch_layers", conv, dense, 10, 0.01, "normal", None))
+
+
 def test_cnn_step_with_unpooled_and_mixed_layers():
     """Layers without pooling inside a network (sigmoid and identity activations, a 1x1 and a 2x2
     filter, three dense layers): the step's backward passes then read the layer outputs instead
