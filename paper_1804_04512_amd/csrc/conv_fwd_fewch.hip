@@ -156,7 +156,8 @@ __global__ __launch_bounds__(kThreads, 3) void conv_fwd_fewch_kernel(const FwdFe
       if constexpr (t < 6) read_step(std::integral_constant<int, t + 1>{});
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int mt = 0; mt < 8; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(fr[t & 1][mt], wB[t], acc[mt], 0, 0, 0);
+      for (int mt = 0; mt < 8; ++mt)   // the first step starts from zero: no clearing of the accumulators between window rows
+        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(fr[t & 1][mt], wB[t], t == 0 ? floatx4{0.f, 0.f, 0.f, 0.f} : acc[mt], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     };
     read_step(std::integral_constant<int, 0>{});
@@ -179,7 +180,6 @@ __global__ __launch_bounds__(kThreads, 3) void conv_fwd_fewch_kernel(const FwdFe
       const float y = fmaxf(m + bias, 0.0f);
       yv[mt] = y;
       ib[mt >> 2] |= (arg | (y > 0.0f ? 0u : (unsigned)kIdxInactive)) << (8 * (mt & 3));
-      acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
     const unsigned o = out0 + (unsigned)dW * (unsigned)p.Wp;
     const floatx4 y0 = {yv[0], yv[1], yv[2], yv[3]}, y1 = {yv[4], yv[5], yv[6], yv[7]};
