@@ -133,6 +133,20 @@ dll_status dll_conv_valid_wgrad(const dll_conv_desc *d, const float *x, const fl
                                 const float *y, const unsigned char *pool_idx, float *dw,
                                 float *dbias, void *ws, size_t ws_bytes, void *stream);
 
+/* The two launches of dll_conv_valid_wgrad as calls of their own, for callers that gather the
+ * reductions of several layers behind their filter-gradient kernels (the training step below does
+ * that with its closing launch) or that time the kernel alone.  _partial runs the filter-gradient
+ * kernel: it leaves the per-workgroup partial sums of dw and dbias in ws (same size as above,
+ * layout private to the library) and writes nothing else.  _finish adds them up in the fixed
+ * order and writes dw (and dbias unless NULL); it reads ws as the _partial call of the SAME
+ * descriptor left it, on the same stream or after it.  The two in a row give bit for bit what
+ * dll_conv_valid_wgrad gives.  Errors as there; dw == ws -> DLL_ERR_SHAPE. */
+dll_status dll_conv_valid_wgrad_partial(const dll_conv_desc *d, const float *x, const float *dy,
+                                        const float *y, const unsigned char *pool_idx, void *ws,
+                                        size_t ws_bytes, void *stream);
+dll_status dll_conv_valid_wgrad_finish(const dll_conv_desc *d, float *dw, float *dbias,
+                                       const void *ws, size_t ws_bytes, void *stream);
+
 /* The same filter-gradient layer for callers that cannot allocate device memory or carry a
  * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
  * Same arguments (minus the workspace), same kernels, bit-identical results; the partial sums

@@ -23,7 +23,8 @@ SYMBOLS = ["dll_status_string", "dll_conv_workspace_bytes", "dll_conv_valid_fwd"
            "dll_conv_valid_wgrad", "dll_crbm_workspace_bytes", "dll_crbm_cd1_step",
            "dll_cnn_workspace_bytes", "dll_cnn_train_step", "dll_cnn_forward_workspace_bytes", "dll_cnn_forward",
            "dll_cnn_train_step_momentum", "dll_crbm_cd1_step_units", "dll_rbm_workspace_bytes", "dll_rbm_cd1_step",
-           "dll_conv_full_fft_workspace_bytes", "dll_conv_full_bwd_fft", "dll_conv_valid_wgrad_noalloc"]
+           "dll_conv_full_fft_workspace_bytes", "dll_conv_full_bwd_fft", "dll_conv_valid_wgrad_noalloc",
+           "dll_conv_valid_wgrad_partial", "dll_conv_valid_wgrad_finish"]
 NOALLOC_SCRATCH_BYTES = 8 << 20   # DLL_NOALLOC_SCRATCH_BYTES of include/dll_conv.h
 VISIBLE = {"binary": 0, "gaussian": 1}
 
@@ -68,6 +69,8 @@ def lib() -> C.CDLL:
         L.dll_conv_full_bwd.argtypes = [pd, vp, vp, vp, vp, vp, vp, sz, vp]
         L.dll_conv_valid_wgrad.argtypes = [pd, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.dll_conv_valid_wgrad_noalloc.argtypes = [pd, vp, vp, vp, vp, vp, vp, vp]
+        L.dll_conv_valid_wgrad_partial.argtypes = [pd, vp, vp, vp, vp, vp, sz, vp]
+        L.dll_conv_valid_wgrad_finish.argtypes = [pd, vp, vp, vp, sz, vp]
         L.dll_conv_full_fft_workspace_bytes.restype = sz
         L.dll_conv_full_fft_workspace_bytes.argtypes = [pd]
         L.dll_conv_full_bwd_fft.argtypes = [pd, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -147,6 +150,18 @@ def dll_conv_valid_wgrad(cs: ConvSpec, x, dy, y, pool_idx, dw, dbias, ws, stream
     d = conv_desc(cs)
     _ok(lib().dll_conv_valid_wgrad(C.byref(d), _ptr(x), _ptr(dy), _ptr(y), _ptr(pool_idx), _ptr(dw), _ptr(dbias),
                                    _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream)), "dll_conv_valid_wgrad")
+
+
+def dll_conv_valid_wgrad_partial(cs: ConvSpec, x, dy, y, pool_idx, ws, stream=None) -> None:
+    d = conv_desc(cs)
+    _ok(lib().dll_conv_valid_wgrad_partial(C.byref(d), _ptr(x), _ptr(dy), _ptr(y), _ptr(pool_idx), _ptr(ws),
+                                           0 if ws is None else ws.numel(), _stream(stream)), "dll_conv_valid_wgrad_partial")
+
+
+def dll_conv_valid_wgrad_finish(cs: ConvSpec, dw, dbias, ws, stream=None) -> None:
+    d = conv_desc(cs)
+    _ok(lib().dll_conv_valid_wgrad_finish(C.byref(d), _ptr(dw), _ptr(dbias), _ptr(ws), 0 if ws is None else ws.numel(),
+                                          _stream(stream)), "dll_conv_valid_wgrad_finish")
 
 
 def dll_conv_valid_wgrad_noalloc(cs: ConvSpec, x, dy, y, pool_idx, dw, dbias, stream=None) -> None:

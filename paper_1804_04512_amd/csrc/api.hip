@@ -249,6 +249,36 @@ dll_status dll_conv_full_bwd_fft(const dll_conv_desc *d, const float *dy, const 
   return dev(launch_conv_full_fft(a, static_cast<hipStream_t>(stream)));
 }
 
+dll_status dll_conv_valid_wgrad_partial(const dll_conv_desc *d, const float *x, const float *dy, const float *y,
+                                        const unsigned char *pool_idx, void *ws, size_t ws_bytes, void *stream) {
+  dll_status st = check_desc(d);
+  if (st != DLL_OK) return st;
+  if (!x || !dy || (output_required(d) && !y) || (d->pool == 2 && !pool_idx)) return DLL_ERR_NULL;
+  if (misaligned(x) || misaligned(dy) || misaligned(y)) return DLL_ERR_SHAPE;
+  WgradPlan plan;
+  if (!plan_for(d, &plan)) return DLL_ERR_UNSUPPORTED;
+  st = check_ws(ws, ws_bytes, align_up(plan.partial_floats * sizeof(float)));
+  if (st != DLL_OK) return st;
+  return dev(launch_wgrad(wgrad_args(d, x, dy, y, pool_idx, static_cast<float *>(ws)), plan, static_cast<hipStream_t>(stream)));
+}
+
+dll_status dll_conv_valid_wgrad_finish(const dll_conv_desc *d, float *dw, float *dbias, const void *ws, size_t ws_bytes,
+                                       void *stream) {
+  dll_status st = check_desc(d);
+  if (st != DLL_OK) return st;
+  if (!dw) return DLL_ERR_NULL;
+  if (misaligned(dw)) return DLL_ERR_SHAPE;
+  WgradPlan plan;
+  if (!plan_for(d, &plan)) return DLL_ERR_UNSUPPORTED;
+  st = check_ws(ws, ws_bytes, align_up(plan.partial_floats * sizeof(float)));
+  if (st != DLL_OK) return st;
+  if (static_cast<const void *>(dw) == ws) return DLL_ERR_SHAPE;
+  WgradReduceArgs r;
+  r.pos = static_cast<const float *>(ws); r.scale = 1.0f; r.dw = dw; r.db = dbias;
+  r.C = d->C; r.K = d->K; r.R = d->R; r.S = d->S;
+  return dev(launch_wgrad_reduce(r, plan, static_cast<hipStream_t>(stream)));
+}
+
 dll_status dll_conv_valid_wgrad(const dll_conv_desc *d, const float *x, const float *dy, const float *y,
                                 const unsigned char *pool_idx, float *dw, float *dbias, void *ws, size_t ws_bytes,
                                 void *stream) {
@@ -256,19 +286,10 @@ dll_status dll_conv_valid_wgrad(const dll_conv_desc *d, const float *x, const fl
   if (st != DLL_OK) return st;
   if (!x || !dy || !dw || (output_required(d) && !y) || (d->pool == 2 && !pool_idx)) return DLL_ERR_NULL;
   if ((const float *)dw == x || (const float *)dw == dy || (const float *)dw == y) return DLL_ERR_SHAPE;
-  if (misaligned(x) || misaligned(dy) || misaligned(y) || misaligned(dw)) return DLL_ERR_SHAPE;
-  WgradPlan plan;
-  if (!plan_for(d, &plan)) return DLL_ERR_UNSUPPORTED;
-  st = check_ws(ws, ws_bytes, align_up(plan.partial_floats * sizeof(float)));
+  if (misaligned(dw)) return DLL_ERR_SHAPE;
+  st = dll_conv_valid_wgrad_partial(d, x, dy, y, pool_idx, ws, ws_bytes, stream);
   if (st != DLL_OK) return st;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  float *partial = static_cast<float *>(ws);
-  st = dev(launch_wgrad(wgrad_args(d, x, dy, y, pool_idx, partial), plan, s));
-  if (st != DLL_OK) return st;
-  WgradReduceArgs r;
-  r.pos = partial; r.scale = 1.0f; r.dw = dw; r.db = dbias;
-  r.C = d->C; r.K = d->K; r.R = d->R; r.S = d->S;
-  return dev(launch_wgrad_reduce(r, plan, s));
+  return dll_conv_valid_wgrad_finish(d, dw, dbias, ws, ws_bytes, stream);
 }
 
 // ---- the filter gradient for callers that cannot allocate: same kernels, the partial sums live in

@@ -74,6 +74,11 @@ def test_argument_errors_are_reported_before_any_launch():
     a, b, c, e = (C.c_void_p(0x1000 * i) for i in (1, 2, 3, 4))
     assert L.dll_conv_valid_wgrad(C.byref(d), a, b, None, None, c, None, None, 0, None) == 4    # no workspace
     assert L.dll_conv_valid_wgrad(C.byref(d), a, b, None, None, c, None, e, 16, None) == 4      # too small
+    assert L.dll_conv_valid_wgrad_partial(C.byref(d), a, None, None, None, e, 1 << 30, None) == 1   # NULL dy
+    assert L.dll_conv_valid_wgrad_partial(C.byref(d), a, b, None, None, e, 16, None) == 4           # too small
+    assert L.dll_conv_valid_wgrad_finish(C.byref(d), None, None, e, 1 << 30, None) == 1             # NULL dw
+    assert L.dll_conv_valid_wgrad_finish(C.byref(d), c, None, e, 16, None) == 4                     # too small
+    assert L.dll_conv_valid_wgrad_finish(C.byref(d), e, None, e, 1 << 30, None) == 2                # dw is the workspace
     assert L.dll_conv_full_bwd(C.byref(d), a, None, None, None, c, None, 0, None) == 1          # NULL w
     pooled = binding.conv_desc(ConvSpec(2, 1, 8, 8, 4, 3, 3, 0, "relu", 2))
     assert L.dll_conv_full_bwd(C.byref(pooled), a, b, None, c, e, None, 0, None) == 1           # pool needs idx

@@ -56,6 +56,12 @@ def gpu_trio(cs: ConvSpec, x, w, b, dy, y_in=None, idx_in=None, flagged=False):
     dw = torch.full(cs.w_shape, float("nan"), device="cuda")
     db = torch.full((cs.K,), float("nan"), device="cuda")
     B.dll_conv_valid_wgrad(cs, xd, dyd, yb, ib, dw, db, ws)
+    # the same pass as its two launches, each a call of its own: bit for bit the same gradients
+    ws2 = B.workspace(B.dll_conv_workspace_bytes(cs))
+    dw2, db2 = torch.full_like(dw, float("nan")), torch.full_like(db, float("nan"))
+    B.dll_conv_valid_wgrad_partial(cs, xd, dyd, yb, ib, ws2)
+    B.dll_conv_valid_wgrad_finish(cs, dw2, db2, ws2)
+    assert torch.equal(dw2, dw) and torch.equal(db2, db), "partial + finish differ from the one call"
     return host(y), (host(idx) if idx is not None else None), host(dx), host(dw), host(db)
 
 
