@@ -9,6 +9,11 @@ ragged 8 x 32 / 16 x 32 tiles, one to three output channels (the banded-filter k
 with one to nine tap tiles in the filter-gradient kernel, pooled and unpooled layers of every
 activation.  The networks mix pooled and unpooled ReLU layers, so the decisions "unit on/off"
 that the GPU takes from its own fp32 values are checked against the oracle's and handed to it.
+A third family are stacks of padded 3x3 ReLU + pooling layers with 16 or 32 channels behind a first
+layer of one, three or sixteen channels (the shape of Section VI's network, on maps from 16 to 256
+columns wide, whole and ragged against the kernels' 32- and 64-column segments): these reach the
+streaming forms, the first-layer kernels and the launches that a layer's filter gradient and
+backward-data pass share inside the training step.
 """
 import random
 
@@ -24,7 +29,7 @@ import test_gpu_parity as T
 
 pytestmark = pytest.mark.gpu
 
-N_LAYERS, N_NETS = 40, 10
+N_LAYERS, N_NETS, N_STACKS = 40, 10, 8
 
 
 def layer_cases(count=N_LAYERS, seed=20241):
@@ -103,8 +108,33 @@ def net_cases(count=N_NETS, seed=20242):
     return cases
 
 
+def stack_cases(count=N_STACKS, seed=20243):
+    rnd = random.Random(seed)
+    cases = []
+    while len(cases) < count:
+        B = rnd.choice([1, 2, 3, 4, 6, 8, 12, 16, 24])
+        C = rnd.choice([1, 3, 3, 16])
+        H = rnd.choice([16, 32, 48, 64, 96, 128])
+        W = rnd.choice([16, 32, 40, 64, 72, 96, 128, 136, 192, 256])
+        if B * H * W > 1600000:   # keeps the oracle's step within a few seconds
+            continue
+        conv = []
+        for _ in range(rnd.randint(2, 4)):
+            if H % 2 or W % 2:
+                break
+            K = rnd.choice([16, 16, 32])
+            conv.append(ConvSpec(B, C, H, W, K, 3, 3, 1, "relu", 2))
+            C, H, W = K, H // 2, W // 2
+        if len(conv) < 2 or C * H * W > 40000:
+            continue
+        classes = rnd.choice([10, 37, 100])
+        cases.append((conv, [DenseSpec(C * H * W, 64, "relu"), DenseSpec(64, classes, "identity")], classes, "normal"))
+    return cases
+
+
 LAYERS = layer_cases()
 NETS = net_cases()
+STACKS = stack_cases()
 
 
 def layer_id(c):
@@ -132,3 +162,15 @@ def test_sweep_network_step(i):
     w = wl._cnn(100 + i, "sweep", conv, dense, classes, 0.05, kind, None)
     T.check_cnn(w)
     T.check_forward(w)
+
+
+def stack_id(case):
+    conv = case[0]
+    return f"B{conv[0].N}_{conv[0].H}x{conv[0].W}_" + "-".join([str(conv[0].C)] + [str(c.K) for c in conv])
+
+
+@pytest.mark.parametrize("i", range(N_STACKS), ids=[stack_id(c) for c in STACKS])
+def test_sweep_pooled_3x3_stack_step(i):
+    conv, dense, classes, kind = STACKS[i]
+    print(f"sweep stack {i}: {stack_id(STACKS[i])}", flush=True)
+    T.check_cnn(wl._cnn(300 + i, "sweep", conv, dense, classes, 0.02, kind, None))
