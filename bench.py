@@ -220,9 +220,9 @@ def chip_probe():
 # cannot be taken live; any other kernel or workload reports null.
 MEASURED_TRAFFIC_BYTES = {
     # conv1's filter gradient: x (100.7 MB) + pooled gradient (134.2 MB) + pooling bytes (33.6 MB) in, partial sums out
-    ("c5_large_image_cnn", 128, "wgrad_fewch_kernel"): (267961.8 + 2112.0) * 1024,
+    ("c5_large_image_cnn", 128, "wgrad_fewch_kernel"): (268162.6 + 2112.0) * 1024,
     # conv1's forward pass: x in; pooled output (134.2 MB) + pooling bytes (33.6 MB) out
-    ("c5_large_image_cnn", 128, "conv_fwd_fewch_kernel"): (104062.5 + 164901.1) * 1024,
+    ("c5_large_image_cnn", 128, "conv_fwd_fewch_kernel"): (104051.2 + 164810.6) * 1024,
 }
 
 
