@@ -55,16 +55,16 @@ def parse():
     return ap.parse_args()
 
 
-def event_time_ms(fn, iters, warm=2):
+def event_time_ms(fn, iters, warm=5, n_groups=5):
     """Average duration of fn() in ms: HIP events on torch's current stream (the launch stream)
     around `iters` back-to-back calls, so the figure is the kernels' own time plus the gap
-    between dependent launches, not the host's call overhead.  Returns (mean of groups, groups)."""
+    between dependent launches, not the host's call overhead.  Returns (median of the groups, groups)."""
     import torch
     for _ in range(warm):
         fn()
     torch.cuda.synchronize()
     groups = []
-    for _ in range(3):
+    for _ in range(n_groups):
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
         for _ in range(iters):
