@@ -160,6 +160,21 @@ FFT_CASES = [
 ]
 
 
+def test_trio_on_a_tensor_beyond_2_gib():
+    """A first-layer shape whose input holds 553 M elements (2.2 GB): the specialised kernels address
+    their tensors through 32-bit byte offsets and must all step aside (forward and filter gradient
+    run on the general kernels), while the backward-data pass, whose SOURCE is the 1.1 GB pooled
+    gradient, stays on the 3x3 engine and writes a destination beyond 2 GiB."""
+    cs = ConvSpec(33, 1, 4096, 4096, 2, 3, 3, 1, "relu", 2)
+    assert 4 * cs.N * cs.C * cs.H * cs.W > 2 ** 31 > cs.N * cs.C * cs.H * cs.W
+    r = np.random.default_rng(77031)
+    x = r.standard_normal(cs.x_shape, dtype=np.float32)
+    w = (r.standard_normal(cs.w_shape) * np.sqrt(2.0 / 9.0)).astype(np.float32)
+    b = (r.standard_normal((cs.K,)) * 0.1).astype(np.float32)
+    dy = r.standard_normal(cs.y_shape, dtype=np.float32)
+    check_trio(cs, x, w, b, dy)
+
+
 @pytest.mark.parametrize("cs", FFT_CASES, ids=lambda c: f"N{c.N}C{c.C}_{c.H}x{c.W}_K{c.K}_{c.R}x{c.S}p{c.pad}_{c.act}_pool{c.pool}")
 def test_full_convolution_through_fft_matches_oracle(cs):
     """Backward-data computed through the Fourier transform against the oracle's plain sum, and
