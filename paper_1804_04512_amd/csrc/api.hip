@@ -738,6 +738,7 @@ dll_status run_cnn_step(const dll_net_desc *net, float *const *params, float *co
     if (q > 0 && net->dense[q - 1].act != DLL_ACT_IDENTITY) { g.C_ref = nb.act[L + q]; g.c_ref_act = net->dense[q - 1].act; }
     g.split_k = gemm_pick_split_k(g.M, g.N, g.Kdim);
     g.partial = nb.partial;
+    if (g.split_k > 1 && gemm_prefers_small(g)) { g.split_k = 1; g.small_form = true; }
     // the gradient with respect to the network input has no consumer
     if (q > 0 || L > 0)
       if ((st = dev(launch_gemm(g, s))) != DLL_OK) return st;

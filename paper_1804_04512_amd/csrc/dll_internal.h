@@ -193,6 +193,9 @@ struct GemmArgs {
   // split_k > 1 only: leave the partials as they are; the consumer adds them (in split order,
   // then the bias) itself.  Only for an identity epilogue without update.
   bool defer_reduce = false;
+  // split_k <= 1 only: take the small-product kernel although the product is larger than
+  // gemm_is_small() allows (see gemm_prefers_small)
+  bool small_form = false;
   // Softmax + cross-entropy in the epilogue (only where gemm_fuses_softmax() says so: every row of
   // logits lies inside one 16-column tile): Cout receives the logits, sm_dz (strides of Cout)
   // (softmax - onehot(label)) * sm_scale, sm_rowloss[m] = -ln softmax[label].
@@ -208,6 +211,11 @@ hipError_t launch_gemm_pair(const GemmArgs &a, const GemmArgs &b, hipStream_t st
 // short latency chain instead: 32 x 32 tiles, the k range split between the wavefronts of a
 // workgroup, no split-K partials (gemm_pick_split_k returns 1 for them).  launch_gemm routes there.
 bool gemm_is_small(int M, int N, int Kdim);
+// Data-gradient products (A contiguous along k, B along n) of up to 2^28 multiply-adds are still
+// faster there than as a split-K product with its reduction launch behind it (measured on the
+// 128 x 2048 x 1000 product of the 1000-class layer: 18 against 21 us); the forward and
+// weight-gradient forms of that size are not.
+bool gemm_prefers_small(const GemmArgs &a);
 bool gemm_fuses_softmax(int M, int N, int Kdim);
 hipError_t launch_gemm_small(const GemmArgs &a, hipStream_t stream);
 

@@ -930,7 +930,7 @@ GemmPlan plan_gemm(const GemmArgs &a) {
 }  // namespace
 
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream) {
-  if (a.split_k <= 1 && gemm_is_small(a.M, a.N, a.Kdim)) return launch_gemm_small(a, stream);
+  if (a.split_k <= 1 && (gemm_is_small(a.M, a.N, a.Kdim) || a.small_form)) return launch_gemm_small(a, stream);
   if (a.sm_labels) return hipErrorInvalidValue;   // the fused loss exists in the small-product kernel only
   const GemmPlan g = plan_gemm(a);
   const GemmParams &p = g.p;

@@ -217,6 +217,11 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_small_kernel(const SmallParam
 // persistent kernel's rate matters more than the latency chain.
 bool gemm_is_small(int M, int N, int Kdim) { return (long)M * N * Kdim <= (1L << 27); }
 
+bool gemm_prefers_small(const GemmArgs &a) {
+  if (gemm_is_small(a.M, a.N, a.Kdim)) return true;
+  return a.a_k == 1 && a.b_n == 1 && !a.update && !a.sm_labels && (long)a.M * a.N * a.Kdim <= (1L << 28);
+}
+
 // Tiles of 16 x 16 (the launcher's choice below for this size) hold whole rows of up to 16 logits.
 bool gemm_fuses_softmax(int M, int N, int Kdim) { return gemm_is_small(M, N, Kdim) && N <= 16 && (M + 31) / 32 <= 512; }
 
