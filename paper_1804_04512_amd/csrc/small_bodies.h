@@ -39,15 +39,22 @@ __device__ __forceinline__ void colsum_block(const float *A, int M, int N, float
   }
 }
 
+// Sum or maximum over the workgroup's 256 threads, the same value in every thread: lane exchanges
+// inside a wavefront (a butterfly, so every lane adds the same pairs in the same order), then the
+// four wavefronts' results in wavefront order.  Two barriers instead of the nine of a tree in LDS,
+// which were most of what the small row kernels spent.  sh: at least 4 floats, free again on return.
 __device__ __forceinline__ float block_reduce(float v, float *sh, bool is_max) {
-  const int tid = threadIdx.x;
-  sh[tid] = v;
-  __syncthreads();
-  for (int s = kSmallThreads / 2; s > 0; s >>= 1) {
-    if (tid < s) sh[tid] = is_max ? fmaxf(sh[tid], sh[tid + s]) : sh[tid] + sh[tid + s];
-    __syncthreads();
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float w = __shfl_xor(v, o);
+    v = is_max ? fmaxf(v, w) : v + w;
   }
-  const float r = sh[0];
+  const int tid = threadIdx.x;
+  if ((tid & 63) == 0) sh[tid >> 6] = v;
+  __syncthreads();
+  float r = sh[0];
+#pragma unroll
+  for (int w = 1; w < kSmallThreads / 64; ++w) r = is_max ? fmaxf(r, sh[w]) : r + sh[w];
   __syncthreads();
   return r;
 }
