@@ -196,11 +196,13 @@ __global__ __launch_bounds__(kWT, (GRP == 2 || KCH == 2) ? 2 : 3) void conv3x3_w
     for (int chunk = 0; chunk < CCH; ++chunk) {
     const int c0 = chunk * kC;
     __syncthreads();   // the previous chunk's / tile's readers are done (first tile: the filters are in place)
-    if (CCH > 1) load_filters(c0);
     if constexpr (!BWD) {
+      // the tile's loads go out ahead of the chunk's filter loads: one memory round trip for both
       load_tile(item, c0);
+      if (CCH > 1) load_filters(c0);
       store_tile(item);
     } else {
+      if (CCH > 1) load_filters(c0);
       // dz halo tile from the pooled gradient.  The tile is cleared with 16-byte stores; then every
       // pooled element drops its gradient at the recorded position of its window, if that entry lies
       // inside the tile and the unit is not flagged inactive.  All loads first, stores after.
