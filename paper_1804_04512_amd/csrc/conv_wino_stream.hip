@@ -532,42 +532,58 @@ __device__ __forceinline__ void stream_bwd_body(const WinoStreamParams &p, float
   // ---- one block row: 16 blocks x 16 output channels; s0, s1, s2: slot pairs of the pooled rows by-1, by, by+1
   const float *patch = xs + kq * kPSB + 2 * i16;
   const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
-  auto block_row = [&](int s0, int s1, int s2, floatx4 (&z)[4]) {
-    const float *rw[4] = {patch + (2 * s0 + 1) * kRS, patch + 2 * s1 * kRS, patch + (2 * s1 + 1) * kRS, patch + 2 * s2 * kRS};
+  // The input transform is taken row-wise first, as in the forward kernel: H = d B of a dz row serves
+  // two block rows (the upper row of pooled row R as row 3 of block row R-1 and row 1 of block row R,
+  // the lower one as row 2 of block row R and row 0 of block row R+1), so the H of a packet's two dz rows
+  // is computed once, when the packet arrives, and kept: `X` holds the rows of the packet before last
+  // and receives the arriving packet's (its upper row at once - the old one is no longer needed -, its
+  // lower row after the old lower row has been used as row 0 of the block row worked now), `Y` those of
+  // the packet before.  The two sets swap roles from packet to packet.
+  struct HSet { float u[4][4], l[4][4]; };   // [channel quartet][value]: upper and lower dz row of a pooled row
+  auto h_row = [&](const float2 &l, const float2 &h, float (&o)[4]) {
+    o[0] = l.x - h.x;
+    o[1] = l.y + h.x;
+    o[2] = h.x - l.y;
+    o[3] = l.y - h.y;
+  };
+  // a packet with no block row to work (the first two of an item): only its H is taken
+  auto prime = [&](int slot, HSet &X) {
+    const float *pnew = patch + 2 * slot * kRS;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const float *row = pnew + 4 * s * kPSB;
+      h_row(*reinterpret_cast<const float2 *>(row), *reinterpret_cast<const float2 *>(row + 2), X.u[s]);
+      h_row(*reinterpret_cast<const float2 *>(row + kRS), *reinterpret_cast<const float2 *>(row + kRS + 2), X.l[s]);
+    }
+  };
+  auto block_row = [&](int slot, HSet &X, const HSet &Y, floatx4 (&z)[4]) {
+    const float *pnew = patch + 2 * slot * kRS;   // the two dz rows of the packet just scattered
     floatx4 acc[16];
-    float2 pl[2][4], ph[2][4];
+    float2 pl[2][2], ph[2][2];
     auto read_patch = [&](auto sc) {
       constexpr int s = decltype(sc)::value;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float *row = rw[i] + 4 * s * kPSB;
-        pl[s & 1][i] = *reinterpret_cast<const float2 *>(row);
-        ph[s & 1][i] = *reinterpret_cast<const float2 *>(row + 2);
+      for (int r = 0; r < 2; ++r) {
+        const float *row = pnew + r * kRS + 4 * s * kPSB;
+        pl[s & 1][r] = *reinterpret_cast<const float2 *>(row);
+        ph[s & 1][r] = *reinterpret_cast<const float2 *>(row + 2);
       }
     };
     auto quartet = [&](auto sc) {
       constexpr int s = decltype(sc)::value;
       if constexpr (s < 3) read_patch(std::integral_constant<int, s + 1>{});
       __builtin_amdgcn_sched_barrier(0);
-      float t[4][4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const float d0 = j < 2 ? (j ? pl[s & 1][0].y : pl[s & 1][0].x) : (j == 2 ? ph[s & 1][0].x : ph[s & 1][0].y);
-        const float d1 = j < 2 ? (j ? pl[s & 1][1].y : pl[s & 1][1].x) : (j == 2 ? ph[s & 1][1].x : ph[s & 1][1].y);
-        const float d2 = j < 2 ? (j ? pl[s & 1][2].y : pl[s & 1][2].x) : (j == 2 ? ph[s & 1][2].x : ph[s & 1][2].y);
-        const float d3 = j < 2 ? (j ? pl[s & 1][3].y : pl[s & 1][3].x) : (j == 2 ? ph[s & 1][3].x : ph[s & 1][3].y);
-        t[0][j] = d0 - d2;
-        t[1][j] = d1 + d2;
-        t[2][j] = d2 - d1;
-        t[3][j] = d1 - d3;
-      }
+      // V = Bt H over the rows X.l (old), Y.u, Y.l, X.u (new)
       float V[16];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        V[4 * i + 0] = t[i][0] - t[i][2];
-        V[4 * i + 1] = t[i][1] + t[i][2];
-        V[4 * i + 2] = t[i][2] - t[i][1];
-        V[4 * i + 3] = t[i][1] - t[i][3];
+      for (int j = 0; j < 4; ++j) V[j] = X.l[s][j] - Y.l[s][j];
+      h_row(pl[s & 1][0], ph[s & 1][0], X.u[s]);
+      h_row(pl[s & 1][1], ph[s & 1][1], X.l[s]);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        V[4 + j] = Y.u[s][j] + Y.l[s][j];
+        V[8 + j] = Y.l[s][j] - Y.u[s][j];
+        V[12 + j] = Y.u[s][j] - X.u[s][j];
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -631,17 +647,15 @@ __device__ __forceinline__ void stream_bwd_body(const WinoStreamParams &p, float
     const int x = xseg * 32 + 8 * kq;
     c_yo = (c_item < p.items && x < a.Wout) ? (unsigned)(((n_img * kKout + k0 + i16) * a.Hout + 2 * by0) * a.Wout + x) : kOob;
   };
-  auto handle = [&](Packet &k) {
+  auto handle = [&](Packet &k, HSet &X, const HSet &Y) {
     const bool live = c_item < p.items;
     scatter(c_slot, k);
     request(k);
     floatx4 z[4] = {zero, zero, zero, zero};
     unsigned yo = kOob;
     const bool work = live && c_q > 1;
-    if (work) {
-      const int s2 = c_slot, s1 = s2 == 0 ? 2 : s2 - 1, s0 = s1 == 0 ? 2 : s1 - 1;
-      block_row(s0, s1, s2, z);
-    }
+    if (work) block_row(c_slot, X, Y, z);
+    else prime(c_slot, X);
     if constexpr (CH == 2) {
       floatx4 *ex = exch + ((c_par * 2 + wave / 2) * 4) * 64 + lane;
       if (chalf == 1) {
@@ -684,9 +698,10 @@ __device__ __forceinline__ void stream_bwd_body(const WinoStreamParams &p, float
   empty_stores();
   request(pb);
   empty_stores();
+  HSet HA = {}, HB = {};
   while (c_item < p.items) {
-    handle(pa);
-    handle(pb);
+    handle(pa, HA, HB);
+    handle(pb, HB, HA);
   }
 }
 
