@@ -191,7 +191,7 @@ N_BATCHES = 3    # input batches the timed steps of config 5 rotate through (3 x
 # the step's kernels, each v_mfma_f32_16x16x4_f32 being 2048 FLOP.  HBM bytes: FETCH_SIZE and
 # WRITE_SIZE summed over the step's kernels with the copy-kernel calibration.
 RECORDED_STEP_COUNTERS = {
-    ("c5_large_image_cnn", 128): {"mfma_wave_instructions": 25.95e6, "hbm_bytes": 1.838e9,
+    ("c5_large_image_cnn", 128): {"mfma_wave_instructions": 25.95e6, "hbm_bytes": 1.837e9,
                                   "source": "profiles/c5_cnn_train_step.md (rocprofv3 --pmc runs of this bench command)"},
 }
 
@@ -220,9 +220,9 @@ def chip_probe():
 # cannot be taken live; any other kernel or workload reports null.
 MEASURED_TRAFFIC_BYTES = {
     # conv1's filter gradient: x (100.7 MB) + pooled gradient (134.2 MB) + pooling bytes (33.6 MB) in, partial sums out
-    ("c5_large_image_cnn", 128, "wgrad_fewch_kernel"): (268196.1 + 2112.0) * 1024,
+    ("c5_large_image_cnn", 128, "wgrad_fewch_kernel"): (267950.7 + 2112.0) * 1024,
     # conv1's forward pass: x in; pooled output (134.2 MB) + pooling bytes (33.6 MB) out
-    ("c5_large_image_cnn", 128, "conv_fwd_fewch_kernel"): (104050.0 + 164800.2) * 1024,
+    ("c5_large_image_cnn", 128, "conv_fwd_fewch_kernel"): (104060.4 + 164834.4) * 1024,
 }
 
 
